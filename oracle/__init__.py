@@ -1,0 +1,189 @@
+"""ctypes front end of the CPU oracle (oracle/csb_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg; never by the product package.  It marshals numpy arrays, nothing else:
+all arithmetic is in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "csb_oracle.c")
+_LIB = os.path.join(_HERE, "libcsb_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP over output rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.orc_num_threads.restype = C.c_int
+        _lib.orc_csb_encode.restype = C.c_int
+        _lib.orc_csb_decode.restype = C.c_int
+        _lib.orc_rnn_forward.restype = C.c_int
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().orc_set_threads(C.c_int(n))
+
+
+class CsbArrays:
+    """The five CSB arrays of Sec. 3.1.1 plus the derived exclusive prefix sums."""
+
+    def __init__(self, rows, cols, br, bc, nrows, ncols, rowidx, colidx, val):
+        self.rows, self.cols, self.br, self.bc = rows, cols, br, bc
+        self.nbr, self.nbc = -(-rows // br), -(-cols // bc)
+        self.nrows, self.ncols = nrows, ncols
+        self.rowidx, self.colidx, self.val = rowidx, colidx, val
+        self.nnz = int(val.shape[0])
+        self.val_off = np.concatenate(([0], np.cumsum(nrows.astype(np.int64) * ncols.astype(np.int64))))
+        self.row_off = np.concatenate(([0], np.cumsum(nrows.astype(np.int64))))
+        self.col_off = np.concatenate(([0], np.cumsum(ncols.astype(np.int64))))
+
+
+def csb_encode(A: np.ndarray, br: int, bc: int) -> CsbArrays:
+    lib = _load()
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    R, Cc = A.shape
+    nb = (-(-R // br)) * (-(-Cc // bc))
+    nrows = np.zeros(nb, np.int32)
+    ncols = np.zeros(nb, np.int32)
+    tot = (C.c_int64 * 3)()
+    rc = lib.orc_csb_encode(_p(A), C.c_int64(R), C.c_int64(Cc), C.c_int64(Cc), C.c_int32(br),
+                            C.c_int32(bc), _p(nrows), _p(ncols), None, C.c_int64(0), None,
+                            C.c_int64(0), None, C.c_int64(0), tot)
+    if rc != 0:
+        raise ValueError("orc_csb_encode(count) failed")
+    nv, nr, nc = int(tot[0]), int(tot[1]), int(tot[2])
+    rowidx = np.zeros(nr, np.uint16)
+    colidx = np.zeros(nc, np.uint16)
+    val = np.zeros(nv, np.float32)
+    rc = lib.orc_csb_encode(_p(A), C.c_int64(R), C.c_int64(Cc), C.c_int64(Cc), C.c_int32(br),
+                            C.c_int32(bc), _p(nrows), _p(ncols), _p(rowidx), C.c_int64(nr),
+                            _p(colidx), C.c_int64(nc), _p(val), C.c_int64(nv), tot)
+    if rc != 0:
+        raise ValueError("orc_csb_encode(fill) failed")
+    return CsbArrays(R, Cc, br, bc, nrows, ncols, rowidx, colidx, val)
+
+
+def csb_decode(m: CsbArrays) -> np.ndarray:
+    lib = _load()
+    A = np.empty((m.rows, m.cols), np.float32)
+    rc = lib.orc_csb_decode(C.c_int64(m.rows), C.c_int64(m.cols), C.c_int32(m.br), C.c_int32(m.bc),
+                            _p(m.nrows), _p(m.ncols), _p(m.rowidx), _p(m.colidx), _p(m.val),
+                            _p(A), C.c_int64(m.cols))
+    if rc != 0:
+        raise ValueError("orc_csb_decode failed")
+    return A
+
+
+def matvec(A: np.ndarray, x: np.ndarray) -> np.ndarray:
+    lib = _load()
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    R, Cc = A.shape
+    assert x.shape == (Cc,)
+    y = np.empty(R, np.float64)
+    lib.orc_matvec(_p(A), C.c_int64(R), C.c_int64(Cc), C.c_int64(Cc), _p(x), _p(y))
+    return y
+
+
+def matvec_abs(A: np.ndarray, x: np.ndarray) -> np.ndarray:
+    lib = _load()
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    R, Cc = A.shape
+    y = np.empty(R, np.float64)
+    lib.orc_matvec_abs(_p(A), C.c_int64(R), C.c_int64(Cc), C.c_int64(Cc), _p(x), _p(y))
+    return y
+
+
+def matmat(A: np.ndarray, X: np.ndarray) -> np.ndarray:
+    """Y = A X with X of shape [C, B]."""
+    lib = _load()
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    R, Cc = A.shape
+    assert X.shape[0] == Cc
+    nb = X.shape[1]
+    Y = np.empty((R, nb), np.float64)
+    lib.orc_matmat(_p(A), C.c_int64(R), C.c_int64(Cc), C.c_int64(Cc), _p(X), C.c_int64(nb),
+                   _p(Y), C.c_int64(nb), C.c_int64(nb))
+    return Y
+
+
+def matmat_rows(A: np.ndarray, rows: Sequence[int], X: np.ndarray) -> np.ndarray:
+    lib = _load()
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    Cc = A.shape[1]
+    nb = X.shape[1]
+    Y = np.empty((rows.shape[0], nb), np.float64)
+    lib.orc_matmat_rows(_p(A), C.c_int64(Cc), C.c_int64(Cc), _p(rows), C.c_int64(rows.shape[0]),
+                        _p(X), C.c_int64(nb), _p(Y), C.c_int64(nb), C.c_int64(nb))
+    return Y
+
+
+def rnn_forward(cell: int, W: List[np.ndarray], bias: Optional[List[Optional[np.ndarray]]],
+                x: np.ndarray, input: int, hidden: int,
+                h0: Optional[np.ndarray] = None, c0: Optional[np.ndarray] = None,
+                want_hseq: bool = True) -> Tuple[Optional[np.ndarray], np.ndarray, np.ndarray]:
+    """Stacked LSTM (cell 0) / GRU (cell 1).  W[l]: dense (G*H) x (in_l + H) float32.
+    x: [T, B, I] float32.  Returns (hseq [T,B,H] or None, hT [L,B,H], cT [L,B,H]) float64."""
+    lib = _load()
+    L = len(W)
+    G = 4 if cell == 0 else 3
+    Ws = []
+    for l, w in enumerate(W):
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        n_in = input if l == 0 else hidden
+        assert w.shape == (G * hidden, n_in + hidden), (w.shape, l)
+        Ws.append(w)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    T, B, I = x.shape
+    assert I == input
+    Wp = (C.c_void_p * L)(*[w.ctypes.data for w in Ws])
+    bs = None
+    Bp = None
+    if bias is not None:
+        bs = [None if b is None else np.ascontiguousarray(b, dtype=np.float32) for b in bias]
+        Bp = (C.c_void_p * L)(*[None if b is None else b.ctypes.data for b in bs])
+    h0 = None if h0 is None else np.ascontiguousarray(h0, dtype=np.float64).reshape(L, B, hidden)
+    c0 = None if c0 is None else np.ascontiguousarray(c0, dtype=np.float64).reshape(L, B, hidden)
+    hseq = np.empty((T, B, hidden), np.float64) if want_hseq else None
+    hT = np.empty((L, B, hidden), np.float64)
+    cT = np.empty((L, B, hidden), np.float64)
+    rc = lib.orc_rnn_forward(C.c_int(cell), C.c_int32(L), C.c_int64(input), C.c_int64(hidden), Wp, Bp,
+                             _p(x), _p(h0), _p(c0), _p(hseq), _p(hT), _p(cT), C.c_int64(T), C.c_int64(B))
+    if rc != 0:
+        raise ValueError("orc_rnn_forward failed")
+    return hseq, hT, cT

@@ -1,0 +1,279 @@
+/*
+ * CPU oracle for CSB-RNN inference.  TEST INFRASTRUCTURE ONLY: nothing in the product
+ * path may call this file; only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg do.  It shares no code with the HIP library.
+ *
+ * What it computes, and where the paper defines it:
+ *   - the CSB encoding of a block-structured pruned matrix and its inverse
+ *     (Sec. 3.1.1: per block the kernel-matrix row and column counts, the indices of the
+ *     surviving rows and columns, and the kernel values of successive blocks, blocks in
+ *     row-major order, concatenated);
+ *   - y = A x and Y = A X on the DECOMPRESSED dense matrix, float64 accumulation
+ *     (CSB is a lossless encoding, so CSB-MVM of Sec. 4.3.1 equals the plain product);
+ *   - LSTM and GRU inference over a sequence (Sec. 2.1: mat-vec of the weight matrices
+ *     with input and hidden vectors, then sigmoid / tanh / element-wise products and
+ *     sums, with c_{t-1}, h_{t-1} carried to the next step), float64 throughout.
+ *
+ * Readings where the paper is silent (its cell equations sit in a figure):
+ *   - LSTM without peepholes, gate rows stacked i,f,g,o; W = [W_x | W_h], one bias;
+ *   - GRU in the "reset after the recurrent product" form, rows stacked r,z,n;
+ *   - inside a block the kernel is stored row-major; indices ascend;
+ *   - "non-zero" means v != 0.0f (so -0.0 is zero and NaN is kept);
+ *   - edge blocks of a ragged matrix are truncated.
+ *
+ * Parity pins (tests/test_oracle_*.py): a hand-worked two-block example, brute force on
+ * tiny matrices, numpy's float64 product, torch.nn.LSTM / torch.nn.GRU in float64 on the
+ * CPU, closed forms for zero weights, encode/decode invariants.  No function here is
+ * "parity unpinned".
+ *
+ * Plain loops on purpose: no blocking, no fusion, no reordering.  The only concession to
+ * run time is an OpenMP "parallel for" over output rows, which does not change any sum.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void orc_set_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+static int64_t imin64(int64_t a, int64_t b) { return a < b ? a : b; }
+
+/*
+ * CSB encoding (Sec. 3.1.1).  Blocks are visited in row-major order.  In block b the kept
+ * rows are those with any non-zero inside the block, likewise the kept columns; the
+ * kernel is the sub-matrix at their cross-points (zeros at cross-points stay, as values).
+ *
+ * Outputs may be NULL to only count.  nrows/ncols have one entry per block.  rowidx /
+ * colidx / val are filled up to the given capacities; the totals are returned in tot[3] =
+ * {sum of kernel sizes, sum of kept rows, sum of kept cols}.  Returns 0, or -1 if a
+ * capacity was too small or an argument invalid.
+ */
+int orc_csb_encode(const float *A, int64_t R, int64_t C, int64_t ld, int32_t BR, int32_t BC,
+                   int32_t *nrows, int32_t *ncols,
+                   uint16_t *rowidx, int64_t cap_row, uint16_t *colidx, int64_t cap_col,
+                   float *val, int64_t cap_val, int64_t tot[3]) {
+    if (!A || R <= 0 || C <= 0 || ld < C || BR <= 0 || BC <= 0 || !tot) return -1;
+    int64_t nbr = (R + BR - 1) / BR, nbc = (C + BC - 1) / BC;
+    int64_t nv = 0, nr = 0, nc = 0;
+    int *keep_r = (int *)malloc(sizeof(int) * (size_t)BR);
+    int *keep_c = (int *)malloc(sizeof(int) * (size_t)BC);
+    int status = 0;
+    for (int64_t bi = 0; bi < nbr; ++bi) {
+        for (int64_t bj = 0; bj < nbc; ++bj) {
+            int64_t r0 = bi * BR, c0 = bj * BC;
+            int64_t h = imin64(BR, R - r0), w = imin64(BC, C - c0);
+            for (int64_t i = 0; i < h; ++i) keep_r[i] = 0;
+            for (int64_t j = 0; j < w; ++j) keep_c[j] = 0;
+            for (int64_t i = 0; i < h; ++i)
+                for (int64_t j = 0; j < w; ++j)
+                    if (A[(r0 + i) * ld + (c0 + j)] != 0.0f) { keep_r[i] = 1; keep_c[j] = 1; }
+            int32_t rb = 0, cb = 0;
+            for (int64_t i = 0; i < h; ++i) rb += keep_r[i];
+            for (int64_t j = 0; j < w; ++j) cb += keep_c[j];
+            int64_t b = bi * nbc + bj;
+            if (nrows) nrows[b] = rb;
+            if (ncols) ncols[b] = cb;
+            for (int64_t i = 0; i < h; ++i) {
+                if (!keep_r[i]) continue;
+                if (rowidx) { if (nr < cap_row) rowidx[nr] = (uint16_t)i; else status = -1; }
+                ++nr;
+            }
+            for (int64_t j = 0; j < w; ++j) {
+                if (!keep_c[j]) continue;
+                if (colidx) { if (nc < cap_col) colidx[nc] = (uint16_t)j; else status = -1; }
+                ++nc;
+            }
+            for (int64_t i = 0; i < h; ++i) {
+                if (!keep_r[i]) continue;
+                for (int64_t j = 0; j < w; ++j) {
+                    if (!keep_c[j]) continue;
+                    if (val) { if (nv < cap_val) val[nv] = A[(r0 + i) * ld + (c0 + j)]; else status = -1; }
+                    ++nv;
+                }
+            }
+        }
+    }
+    free(keep_r);
+    free(keep_c);
+    tot[0] = nv; tot[1] = nr; tot[2] = nc;
+    return status;
+}
+
+/* Inverse of the encoding: writes the full R x C matrix (zeros elsewhere).  The arrays are
+ * consumed strictly sequentially, as the format intends (it stores no offsets). */
+int orc_csb_decode(int64_t R, int64_t C, int32_t BR, int32_t BC,
+                   const int32_t *nrows, const int32_t *ncols,
+                   const uint16_t *rowidx, const uint16_t *colidx, const float *val,
+                   float *A, int64_t ld) {
+    if (!A || R <= 0 || C <= 0 || ld < C || BR <= 0 || BC <= 0) return -1;
+    int64_t nbr = (R + BR - 1) / BR, nbc = (C + BC - 1) / BC;
+    for (int64_t i = 0; i < R; ++i)
+        for (int64_t j = 0; j < C; ++j) A[i * ld + j] = 0.0f;
+    int64_t pv = 0, pr = 0, pc = 0;
+    for (int64_t bi = 0; bi < nbr; ++bi) {
+        for (int64_t bj = 0; bj < nbc; ++bj) {
+            int64_t b = bi * nbc + bj;
+            int32_t rb = nrows[b], cb = ncols[b];
+            for (int32_t i = 0; i < rb; ++i) {
+                int64_t gi = bi * BR + rowidx[pr + i];
+                if (gi >= R) return -1;
+                for (int32_t j = 0; j < cb; ++j) {
+                    int64_t gj = bj * BC + colidx[pc + j];
+                    if (gj >= C) return -1;
+                    A[gi * ld + gj] = val[pv + (int64_t)i * cb + j];
+                }
+            }
+            pv += (int64_t)rb * cb; pr += rb; pc += cb;
+        }
+    }
+    return 0;
+}
+
+/* y = A x; A float32 widened, float64 accumulation in column order. */
+void orc_matvec(const float *A, int64_t R, int64_t C, int64_t ld, const float *x, double *y) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < R; ++i) {
+        double s = 0.0;
+        for (int64_t j = 0; j < C; ++j) s += (double)A[i * ld + j] * (double)x[j];
+        y[i] = s;
+    }
+}
+
+/* Per-row sum of |a_ij x_j| (the scale of the textbook dot-product rounding bound). */
+void orc_matvec_abs(const float *A, int64_t R, int64_t C, int64_t ld, const float *x, double *y) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < R; ++i) {
+        double s = 0.0;
+        for (int64_t j = 0; j < C; ++j) s += fabs((double)A[i * ld + j] * (double)x[j]);
+        y[i] = s;
+    }
+}
+
+/* Y = A X; X is [C][ldx] (column k = right-hand side k), Y is [R][ldy], nb columns. */
+void orc_matmat(const float *A, int64_t R, int64_t C, int64_t ld,
+                const float *X, int64_t ldx, double *Y, int64_t ldy, int64_t nb) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < R; ++i) {
+        for (int64_t k = 0; k < nb; ++k) {
+            double s = 0.0;
+            for (int64_t j = 0; j < C; ++j) s += (double)A[i * ld + j] * (double)X[j * ldx + k];
+            Y[i * ldy + k] = s;
+        }
+    }
+}
+
+/* Selected rows of Y = A X (for sampled checks at full size): rows[k], k < nsel. */
+void orc_matmat_rows(const float *A, int64_t C, int64_t ld, const int64_t *rows, int64_t nsel,
+                     const float *X, int64_t ldx, double *Y, int64_t ldy, int64_t nb) {
+#pragma omp parallel for schedule(static)
+    for (int64_t q = 0; q < nsel; ++q) {
+        int64_t i = rows[q];
+        for (int64_t k = 0; k < nb; ++k) {
+            double s = 0.0;
+            for (int64_t j = 0; j < C; ++j) s += (double)A[i * ld + j] * (double)X[j * ldx + k];
+            Y[q * ldy + k] = s;
+        }
+    }
+}
+
+static double sigmoid(double v) { return 1.0 / (1.0 + exp(-v)); }
+
+/*
+ * One layer, one time step, one sequence of the batch (Sec. 2.1; cell arithmetic after
+ * the works the paper cites for LSTM and GRU).
+ *   cell 0, LSTM: a = W [u; h] + b, rows i,f,g,o;
+ *                 c' = sig(a_f) c + sig(a_i) tanh(a_g);  h' = sig(a_o) tanh(c')
+ *   cell 1, GRU : ax = W[:, :n_in] u, ah = W[:, n_in:] h, rows r,z,n;
+ *                 r = sig(ax_r + ah_r + b_r), z = sig(ax_z + ah_z + b_z),
+ *                 n = tanh(ax_n + b_n + r ah_n);  h' = (1 - z) n + z h
+ * W is (G*H) x (n_in + H) dense float32 with leading dimension n_in + H.
+ */
+static void cell_step(int cell, int64_t n_in, int64_t H, const float *W, const float *bias,
+                      const double *u, double *h, double *c, double *ax, double *ah) {
+    int64_t G = cell == 0 ? 4 : 3, ld = n_in + H;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < G * H; ++i) {
+        double sx = 0.0, sh = 0.0;
+        for (int64_t j = 0; j < n_in; ++j) sx += (double)W[i * ld + j] * u[j];
+        for (int64_t j = 0; j < H; ++j) sh += (double)W[i * ld + n_in + j] * h[j];
+        ax[i] = sx; ah[i] = sh;
+    }
+    if (cell == 0) {
+        for (int64_t k = 0; k < H; ++k) {
+            double ai = ax[k] + ah[k] + (bias ? (double)bias[k] : 0.0);
+            double af = ax[H + k] + ah[H + k] + (bias ? (double)bias[H + k] : 0.0);
+            double ag = ax[2 * H + k] + ah[2 * H + k] + (bias ? (double)bias[2 * H + k] : 0.0);
+            double ao = ax[3 * H + k] + ah[3 * H + k] + (bias ? (double)bias[3 * H + k] : 0.0);
+            double cn = sigmoid(af) * c[k] + sigmoid(ai) * tanh(ag);
+            c[k] = cn;
+            h[k] = sigmoid(ao) * tanh(cn);
+        }
+    } else {
+        for (int64_t k = 0; k < H; ++k) {
+            double br = bias ? (double)bias[k] : 0.0;
+            double bz = bias ? (double)bias[H + k] : 0.0;
+            double bn = bias ? (double)bias[2 * H + k] : 0.0;
+            double r = sigmoid(ax[k] + ah[k] + br);
+            double z = sigmoid(ax[H + k] + ah[H + k] + bz);
+            double n = tanh(ax[2 * H + k] + bn + r * ah[2 * H + k]);
+            /* all ah were formed from the old h before any h[k] is replaced */
+            h[k] = (1.0 - z) * n + z * h[k];
+        }
+    }
+}
+
+/*
+ * Stacked RNN over a sequence.  Layer l at time t reads the layer below at the same t.
+ *   x    [T][B][I] float32        h0,c0 [L][B][H] float64 or NULL (zeros)
+ *   hseq [T][B][H] float64 of the last layer, or NULL
+ *   hT,cT [L][B][H] float64 (cT may be NULL; unused for GRU)
+ * W[l] dense (G*H) x (in_l + H), in_0 = I, in_l = H; bias[l] of G*H or NULL.
+ */
+int orc_rnn_forward(int cell, int32_t L, int64_t I, int64_t H,
+                    const float *const *W, const float *const *bias,
+                    const float *x, const double *h0, const double *c0,
+                    double *hseq, double *hT, double *cT, int64_t T, int64_t B) {
+    if ((cell != 0 && cell != 1) || L <= 0 || I <= 0 || H <= 0 || T < 0 || B <= 0 || !W || !hT) return -1;
+    int64_t G = cell == 0 ? 4 : 3;
+    int64_t maxin = I > H ? I : H;
+    double *h = (double *)calloc((size_t)(L * B * H), sizeof(double));
+    double *c = (double *)calloc((size_t)(L * B * H), sizeof(double));
+    double *u = (double *)malloc(sizeof(double) * (size_t)maxin);
+    double *ax = (double *)malloc(sizeof(double) * (size_t)(G * H));
+    double *ah = (double *)malloc(sizeof(double) * (size_t)(G * H));
+    if (h0) memcpy(h, h0, sizeof(double) * (size_t)(L * B * H));
+    if (c0) memcpy(c, c0, sizeof(double) * (size_t)(L * B * H));
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t s = 0; s < B; ++s) {
+            for (int32_t l = 0; l < L; ++l) {
+                int64_t n_in = l == 0 ? I : H;
+                if (l == 0) for (int64_t j = 0; j < I; ++j) u[j] = (double)x[(t * B + s) * I + j];
+                else        for (int64_t j = 0; j < H; ++j) u[j] = h[((l - 1) * B + s) * H + j];
+                cell_step(cell, n_in, H, W[l], bias ? bias[l] : NULL, u,
+                          h + (l * B + s) * H, c + (l * B + s) * H, ax, ah);
+            }
+            if (hseq) for (int64_t k = 0; k < H; ++k) hseq[(t * B + s) * H + k] = h[((L - 1) * B + s) * H + k];
+        }
+    }
+    memcpy(hT, h, sizeof(double) * (size_t)(L * B * H));
+    if (cT) memcpy(cT, c, sizeof(double) * (size_t)(L * B * H));
+    free(h); free(c); free(u); free(ax); free(ah);
+    return 0;
+}
