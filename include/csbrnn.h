@@ -1,0 +1,190 @@
+/*
+ * csbrnn.h -- C ABI of the MI355X (gfx950) CSB-RNN inference library.
+ *
+ * The library applies a CSB-pruned weight matrix (compressed structured blocks, paper
+ * Sec. 3.1.1) to vectors and runs LSTM / GRU inference with it (Sec. 2.1, Sec. 4.3.1).
+ *
+ * Conventions
+ *   - Every function returns an int status (CSB_OK = 0, negative on error) unless it
+ *     returns a size or a string.  csb_last_error() gives a thread-local message for the
+ *     last failing call on this thread.  Bad arguments never crash: they return
+ *     CSB_EINVAL.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers (prefix d_) are HIP
+ *     device memory owned by the caller.  The library never allocates device memory:
+ *     callers ask for sizes (csb_device_bytes, csb_workspace_bytes,
+ *     csb_rnn_workspace_bytes) and pass buffers in.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device
+ *     calls only enqueue work on that stream and do not synchronise with the host.
+ *   - Handles (csb_matrix, csb_rnn) are host objects owned by the library; release them
+ *     with csb_free / csb_rnn_free.  A csb_rnn borrows its csb_matrix handles and bias
+ *     pointers; they must outlive it.
+ *   - All matrices are float32.  A matrix is rows x cols, tiled in br x bc blocks (edge
+ *     blocks are truncated); blocks are numbered row-major, b = bi * nbc + bj.
+ *   - Calls that use the same csb_matrix (or csb_rnn) concurrently on different streams
+ *     race on its device-side merge counters: order them on one stream.
+ */
+#ifndef CSBRNN_H
+#define CSBRNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CSB_OK 0
+#define CSB_EINVAL (-1)       /* bad argument (NULL, non-positive size, out of range)   */
+#define CSB_ENOMEM (-2)       /* host allocation failed or a caller buffer is too small */
+#define CSB_EDEVICE (-3)      /* a HIP call failed                                      */
+#define CSB_EUNSUPPORTED (-4) /* valid request outside what the kernels cover           */
+#define CSB_ESTATE (-5)       /* call order wrong (e.g. spmv before plan/upload)        */
+
+#define CSB_CELL_LSTM 0
+#define CSB_CELL_GRU 1
+
+#define CSB_MAX_BLOCK 256     /* br, bc in [1, 256]: device indices are one byte */
+
+typedef struct csb_matrix csb_matrix;
+typedef struct csb_rnn csb_rnn;
+
+/*
+ * Canonical view of the five CSB arrays of Sec. 3.1.1 (row/column counts of the kernel
+ * matrix per block; indices of the surviving rows and columns; kernel values of
+ * successive blocks concatenated) plus exclusive prefix sums, which the paper omits
+ * because its engine reads the arrays sequentially.  Indices are block-local and
+ * ascending; a kernel is stored row-major; blocks follow in row-major order.
+ * All pointers are host memory owned by the csb_matrix and valid until csb_free.
+ */
+typedef struct {
+    int64_t rows, cols;
+    int32_t br, bc, nbr, nbc;
+    int64_t nnz, n_rowidx, n_colidx;
+    const int32_t *nrows, *ncols;               /* [nbr*nbc]            */
+    const uint16_t *rowidx, *colidx;            /* [n_rowidx],[n_colidx] */
+    const float *val;                           /* [nnz]                */
+    const int64_t *val_off, *row_off, *col_off; /* [nbr*nbc + 1]        */
+} csb_view;
+
+/*
+ * Result of the equal-work partition (the role Sec. 5.2 gives to the micro-instruction
+ * compiler: split the uneven kernel-matrix work so that every parallel unit gets the same
+ * amount).  Work is counted in wavefront steps: one step is one 64-lane multiply-add
+ * issue plus a fixed per-group overhead, which is what a wavefront's run time follows.
+ */
+typedef struct {
+    int32_t n_chunks;        /* workgroups the kernels will launch                      */
+    int32_t waves_per_chunk; /* wavefronts per workgroup                                */
+    int32_t n_groups;        /* wavefront-sized groups of kernel-matrix rows            */
+    int32_t n_shared_tiles;  /* output row tiles whose sum is merged across workgroups   */
+    double work_max;         /* largest work assigned to one wavefront (steps)          */
+    double work_mean;        /* mean work per wavefront (steps)                         */
+    double lane_fill;        /* nnz / (64 * multiply-add steps): useful lanes per issue */
+    double nosplit_max_over_mean; /* the same ratio when whole blocks are dealt out
+                                round-robin with no splitting (the "no sharing" baseline
+                                of Sec. 6.3.2), for context                             */
+} csb_plan_stats;
+
+const char *csb_last_error(void);
+
+/*
+ * CSB encoding, Sec. 3.1.1.  HOST ONLY.
+ * dense: host, row-major, leading dimension ld >= cols.  An entry survives iff
+ * v != 0.0f (so -0.0 is pruned, NaN is kept).  In each block the surviving rows
+ * (columns) are those with at least one surviving entry in the block; the kernel is the
+ * sub-matrix at their cross-points, explicit zeros included.
+ * *out receives a new handle.  Errors: NULL pointers, rows/cols <= 0, br/bc outside
+ * [1, CSB_MAX_BLOCK], ld < cols -> CSB_EINVAL; allocation failure -> CSB_ENOMEM.
+ */
+int csb_pack(const float *dense, int64_t rows, int64_t cols, int64_t ld,
+             int32_t br, int32_t bc, csb_matrix **out);
+
+/* Borrow the canonical arrays (host pointers, valid until csb_free). */
+int csb_view_get(const csb_matrix *m, csb_view *out);
+
+/* Inverse of csb_pack: writes all rows x cols entries of `dense` (host, ld >= cols). */
+int csb_unpack(const csb_matrix *m, float *dense, int64_t ld);
+
+/*
+ * Equal-work partition and device layout (host only; replaces the SMT-based schedule of
+ * Sec. 5.2.2 by a prefix sum).  Kernel-matrix rows of one block-row are packed into
+ * 64-lane groups, the groups' multiply-add steps are prefix-summed, and the sum is cut
+ * into n_chunks * waves_per_chunk equal ranges, one per wavefront; a cut may fall inside
+ * a group (between two of its column steps).  n_chunks = 0 picks a default for one
+ * MI355X.  May be called again to re-plan; the matrix must then be uploaded again.
+ * stats may be NULL.
+ */
+int csb_plan(csb_matrix *m, int32_t n_chunks, csb_plan_stats *stats);
+
+/* Integer self-check of the planned device image: every offset in bounds, every kernel
+ * value referenced exactly once, image decodes to the packed matrix.  Host only. */
+int csb_plan_validate(const csb_matrix *m);
+
+/* Bytes of device memory the planned matrix needs (0 if not planned). */
+size_t csb_device_bytes(const csb_matrix *m);
+
+/*
+ * Copy the planned image into d_buf (device, caller-owned, >= csb_device_bytes bytes,
+ * 256-byte aligned, must stay valid and otherwise untouched while the matrix is in use).
+ * Asynchronous on `stream` from a staging copy kept inside the handle.
+ */
+int csb_upload(csb_matrix *m, void *d_buf, size_t bytes, void *stream);
+
+/* Bytes of scratch csb_spmv / csb_spmm need for `batch` right-hand sides (partial sums of
+ * row tiles that several workgroups share).  Contents need no initialisation. */
+size_t csb_workspace_bytes(const csb_matrix *m, int32_t batch);
+
+/*
+ * CSB-MVM, Sec. 4.3.1: y = A x.  d_x [cols], d_y [rows] device float32; d_ws device
+ * scratch of csb_workspace_bytes(m, 1) (may be NULL if that is 0).  Every y entry is
+ * written (rows without survivors get 0).  Results are bitwise reproducible run to run.
+ * Errors: NULL -> CSB_EINVAL; not planned/uploaded -> CSB_ESTATE; launch failure ->
+ * CSB_EDEVICE.
+ */
+int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws, void *stream);
+
+/*
+ * Batched CSB-MVM: Y = A X for `batch` right-hand sides.  d_X is [cols][ldx] (entry
+ * (j,k) at d_X[j*ldx + k], ldx >= batch), d_Y is [rows][ldy] (ldy >= batch).
+ * d_ws: csb_workspace_bytes(m, batch).
+ */
+int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int64_t ldy,
+             int32_t batch, void *d_ws, void *stream);
+
+/*
+ * RNN handle (Sec. 2.1).  cell: CSB_CELL_LSTM (gate rows stacked i,f,g,o; no peepholes)
+ * or CSB_CELL_GRU (rows r,z,n; the reset gate multiplies the recurrent product of the n
+ * rows).  Layer l has W[l] of shape (G*hidden) x (in_l + hidden), in_0 = input,
+ * in_l = hidden, applied to [layer input ; h_{l,t-1}], and an optional device bias
+ * d_bias[l] of G*hidden floats (d_bias NULL or d_bias[l] NULL = zero bias).
+ * Each W[l] must be packed; it is planned by this call if it is not yet, in the layout
+ * the step kernels need (the GRU keeps the input-side and recurrent-side sums of its n
+ * rows apart).  Upload each W[l] afterwards with csb_upload.
+ */
+int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int32_t hidden,
+                   csb_matrix *const *W, const float *const *d_bias, csb_rnn **out);
+
+size_t csb_rnn_workspace_bytes(const csb_rnn *r, int32_t batch, int32_t T);
+
+/*
+ * Inference over a sequence.  All data device float32.
+ *   d_x    [T][batch][input]
+ *   d_h0   [n_layers][batch][hidden] or NULL (zeros);  d_c0 likewise (LSTM only)
+ *   d_hseq [T][batch][hidden], outputs of the last layer, or NULL
+ *   d_hT   [n_layers][batch][hidden];  d_cT likewise (LSTM; may be NULL)
+ *   d_ws   csb_rnn_workspace_bytes(r, batch, T) bytes
+ * T = 0 copies h0/c0 to hT/cT.  The time loop runs on the device side of `stream`
+ * without host synchronisation.  Errors: NULL / batch <= 0 / T < 0 -> CSB_EINVAL;
+ * a W[l] not uploaded -> CSB_ESTATE.
+ */
+int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0,
+                    float *d_hseq, float *d_hT, float *d_cT, int32_t T, int32_t batch,
+                    void *d_ws, void *stream);
+
+void csb_free(csb_matrix *m);
+void csb_rnn_free(csb_rnn *r);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSBRNN_H */

@@ -1,0 +1,255 @@
+"""ctypes binding with the same names as include/csbrnn.h (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+CELL_LSTM = 0
+CELL_GRU = 1
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libcsbrnn.so")
+_lib = None
+
+# every symbol include/csbrnn.h declares
+SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_plan", "csb_plan_validate",
+           "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm",
+           "csb_rnn_create", "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
+
+
+class CsbError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"csb error {code}: {msg}")
+        self.code = code
+
+
+class csb_view(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64),
+                ("br", C.c_int32), ("bc", C.c_int32), ("nbr", C.c_int32), ("nbc", C.c_int32),
+                ("nnz", C.c_int64), ("n_rowidx", C.c_int64), ("n_colidx", C.c_int64),
+                ("nrows", C.POINTER(C.c_int32)), ("ncols", C.POINTER(C.c_int32)),
+                ("rowidx", C.POINTER(C.c_uint16)), ("colidx", C.POINTER(C.c_uint16)),
+                ("val", C.POINTER(C.c_float)),
+                ("val_off", C.POINTER(C.c_int64)), ("row_off", C.POINTER(C.c_int64)),
+                ("col_off", C.POINTER(C.c_int64))]
+
+
+class csb_plan_stats(C.Structure):
+    _fields_ = [("n_chunks", C.c_int32), ("waves_per_chunk", C.c_int32), ("n_groups", C.c_int32),
+                ("n_shared_tiles", C.c_int32), ("work_max", C.c_double), ("work_mean", C.c_double),
+                ("lane_fill", C.c_double), ("nosplit_max_over_mean", C.c_double)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libcsbrnn.so; fails loudly if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2005_05758_amd.build` "
+                          "(there is no CPU fallback)")
+    L = C.CDLL(_LIB_PATH)
+    L.csb_last_error.restype = C.c_char_p
+    L.csb_pack.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+    L.csb_view_get.argtypes = [C.c_void_p, C.POINTER(csb_view)]
+    L.csb_unpack.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+    L.csb_plan.argtypes = [C.c_void_p, C.c_int32, C.POINTER(csb_plan_stats)]
+    L.csb_plan_validate.argtypes = [C.c_void_p]
+    L.csb_device_bytes.argtypes = [C.c_void_p]
+    L.csb_device_bytes.restype = C.c_size_t
+    L.csb_upload.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.csb_workspace_bytes.argtypes = [C.c_void_p, C.c_int32]
+    L.csb_workspace_bytes.restype = C.c_size_t
+    L.csb_spmv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.csb_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    L.csb_rnn_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
+                                 C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
+    L.csb_rnn_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    L.csb_rnn_workspace_bytes.restype = C.c_size_t
+    L.csb_rnn_forward.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    L.csb_free.argtypes = [C.c_void_p]
+    L.csb_free.restype = None
+    L.csb_rnn_free.argtypes = [C.c_void_p]
+    L.csb_rnn_free.restype = None
+    for name in SYMBOLS:
+        fn = getattr(L, name)
+        if fn.restype is C.c_int and name not in ("csb_free", "csb_rnn_free"):
+            fn.restype = C.c_int
+    _lib = L
+    return L
+
+
+def lib():
+    return load_library()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise CsbError(rc, lib().csb_last_error().decode())
+
+
+def _dptr(t) -> Optional[int]:
+    """Device pointer of a torch tensor (or None)."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    return t.data_ptr()
+
+
+def _stream_ptr(stream=None) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+class CsbMatrix:
+    """Owns one csb_matrix handle and (optionally) the torch buffer holding its device image."""
+
+    def __init__(self, dense: np.ndarray, br: int, bc: int, ld: Optional[int] = None):
+        dense = np.ascontiguousarray(dense, dtype=np.float32)
+        rows, cols = dense.shape
+        self._h = C.c_void_p()
+        _check(lib().csb_pack(dense.ctypes.data, rows, cols, cols if ld is None else ld, br, bc, C.byref(self._h)))
+        self.rows, self.cols, self.br, self.bc = rows, cols, br, bc
+        self.d_buf = None
+        self.d_ws = None
+        self.stats = None
+
+    @property
+    def handle(self):
+        return self._h
+
+    def view(self):
+        v = csb_view()
+        _check(lib().csb_view_get(self._h, C.byref(v)))
+        nb = v.nbr * v.nbc
+
+        def arr(p, n, dt):
+            return np.ctypeslib.as_array(p, shape=(n,)).astype(dt, copy=True) if n else np.zeros(0, dt)
+        return dict(rows=v.rows, cols=v.cols, br=v.br, bc=v.bc, nbr=v.nbr, nbc=v.nbc, nnz=v.nnz,
+                    nrows=arr(v.nrows, nb, np.int32), ncols=arr(v.ncols, nb, np.int32),
+                    rowidx=arr(v.rowidx, v.n_rowidx, np.uint16), colidx=arr(v.colidx, v.n_colidx, np.uint16),
+                    val=arr(v.val, v.nnz, np.float32),
+                    val_off=arr(v.val_off, nb + 1, np.int64), row_off=arr(v.row_off, nb + 1, np.int64),
+                    col_off=arr(v.col_off, nb + 1, np.int64))
+
+    def unpack(self) -> np.ndarray:
+        out = np.empty((self.rows, self.cols), np.float32)
+        _check(lib().csb_unpack(self._h, out.ctypes.data, self.cols))
+        return out
+
+    def plan(self, n_chunks: int = 0):
+        st = csb_plan_stats()
+        _check(lib().csb_plan(self._h, n_chunks, C.byref(st)))
+        self.stats = {k: getattr(st, k) for k, _ in csb_plan_stats._fields_}
+        return self.stats
+
+    def validate(self):
+        _check(lib().csb_plan_validate(self._h))
+
+    def device_bytes(self) -> int:
+        return int(lib().csb_device_bytes(self._h))
+
+    def workspace_bytes(self, batch: int = 1) -> int:
+        return int(lib().csb_workspace_bytes(self._h, batch))
+
+    def upload(self, device="cuda", stream=None):
+        """Allocate the image buffer with torch and copy the planned image into it."""
+        import torch
+        n = self.device_bytes()
+        self.d_buf = torch.empty(n + 256, dtype=torch.uint8, device=device)
+        base = self.d_buf.data_ptr()
+        self._d_ptr = (base + 255) // 256 * 256
+        _check(lib().csb_upload(self._h, self._d_ptr, n, _stream_ptr(stream)))
+        return self
+
+    def spmv(self, x, y=None, stream=None):
+        import torch
+        if y is None:
+            y = torch.empty(self.rows, dtype=torch.float32, device=x.device)
+        ws = self._workspace(1, x.device)
+        _check(lib().csb_spmv(self._h, _dptr(x), _dptr(y), _dptr(ws), _stream_ptr(stream)))
+        return y
+
+    def spmm(self, X, Y=None, stream=None):
+        import torch
+        cols, batch = X.shape
+        if Y is None:
+            Y = torch.empty((self.rows, batch), dtype=torch.float32, device=X.device)
+        ws = self._workspace(batch, X.device)
+        _check(lib().csb_spmm(self._h, _dptr(X), X.stride(0), _dptr(Y), Y.stride(0), batch, _dptr(ws),
+                              _stream_ptr(stream)))
+        return Y
+
+    def _workspace(self, batch, device):
+        import torch
+        need = self.workspace_bytes(batch)
+        if need == 0:
+            return None
+        if self.d_ws is None or self.d_ws.numel() * 4 < need:
+            self.d_ws = torch.empty((need + 3) // 4, dtype=torch.float32, device=device)
+        return self.d_ws
+
+    def close(self):
+        if self._h:
+            lib().csb_free(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class CsbRnn:
+    """csb_rnn handle; keeps its matrices and bias tensors alive."""
+
+    def __init__(self, cell: int, input: int, hidden: int, W: Sequence[CsbMatrix], bias=None):
+        self.cell, self.input, self.hidden, self.W = cell, input, hidden, list(W)
+        self.bias = list(bias) if bias is not None else None
+        L = len(self.W)
+        Wp = (C.c_void_p * L)(*[w.handle for w in self.W])
+        Bp = None
+        if self.bias is not None:
+            Bp = (C.c_void_p * L)(*[_dptr(b) for b in self.bias])
+        self._h = C.c_void_p()
+        _check(lib().csb_rnn_create(cell, L, input, hidden, Wp, Bp, C.byref(self._h)))
+        self.n_layers = L
+        self._ws = None
+
+    def workspace_bytes(self, batch: int, T: int) -> int:
+        return int(lib().csb_rnn_workspace_bytes(self._h, batch, T))
+
+    def forward(self, x, h0=None, c0=None, want_hseq=True, stream=None):
+        """x: [T, B, I] float32 cuda.  Returns (hseq or None, hT, cT or None)."""
+        import torch
+        T, B, I = x.shape
+        dev = x.device
+        need = self.workspace_bytes(B, T)
+        if self._ws is None or self._ws.numel() * 4 < need:
+            self._ws = torch.empty((need + 3) // 4 + 64, dtype=torch.float32, device=dev)
+        hseq = torch.empty((T, B, self.hidden), dtype=torch.float32, device=dev) if want_hseq else None
+        hT = torch.empty((self.n_layers, B, self.hidden), dtype=torch.float32, device=dev)
+        cT = torch.empty_like(hT) if self.cell == CELL_LSTM else None
+        _check(lib().csb_rnn_forward(self._h, _dptr(x), _dptr(h0), _dptr(c0), _dptr(hseq), _dptr(hT), _dptr(cT),
+                                     T, B, _dptr(self._ws), _stream_ptr(stream)))
+        return hseq, hT, cT
+
+    def close(self):
+        if self._h:
+            lib().csb_rnn_free(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

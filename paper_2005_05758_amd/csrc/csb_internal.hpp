@@ -1,0 +1,144 @@
+// Internal definitions shared by the host packer/planner and the gfx950 kernels.
+// Not part of the public ABI (that is include/csbrnn.h).
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "csbrnn.h"
+
+namespace csb {
+
+constexpr int kWave = 64;             // gfx950 wavefront width
+constexpr int kMaxVbPerGroup = 16;    // virtual blocks packed into one 64-lane group
+constexpr int kGroupOverhead = 8;     // per-group fixed cost in the work model (steps)
+constexpr int kAccRowsMax = 512;      // output-row slots one workgroup accumulates in LDS
+constexpr int kMaxStageCols = 24576;  // input vector floats staged in LDS (96 KB)
+
+// ---- device image records (plain structs, identical on host and device) ----------
+
+// A group: up to 64 kernel-matrix rows of up to 16 virtual blocks of ONE output row
+// tile, lanes ordered so that the virtual blocks' column counts descend.  Its values are
+// stored step-major: for column step j, the lanes whose block still has a column j
+// (always a prefix of the lanes) contribute one float each, contiguous.
+struct GroupRec {
+    uint32_t val_off;   // float index of (step 0, lane 0) in the value stream
+    uint32_t idx_off;   // byte offset in the index stream: lane descriptors, column lists
+    uint32_t vb_off;    // first VbRec of the group
+    uint32_t nzrank;    // rank of the group's output tile among tiles that have work
+    uint16_t cmax;      // column steps of the group (largest column count)
+    uint8_t nvb;        // virtual blocks
+    uint8_t nlanes;     // kernel-matrix rows (lanes in use)
+    uint32_t nvals;     // floats of the group in the value stream
+};
+static_assert(sizeof(GroupRec) == 24, "GroupRec layout");
+
+// A virtual block: the kernel-matrix rows of one CSB block that fall into one output tile
+// and one column part, at most 64 of them.
+struct VbRec {
+    uint8_t r;          // rows (lanes)
+    uint8_t lane0;      // first lane
+    uint16_t c;         // columns
+    uint16_t bj;        // block column: input base index = bj * bc
+    uint16_t coloff4;   // column list offset inside the group's index bytes, 4-byte units
+};
+static_assert(sizeof(VbRec) == 8, "VbRec layout");
+
+// Work of one wavefront: steps from (g_begin, j_begin) up to but excluding
+// (g_end, j_end), groups in order; (g, cmax_g) is the same position as (g + 1, 0).
+struct WaveRec {
+    uint32_t g_begin, g_end;
+    uint16_t j_begin, j_end;
+    uint32_t val_begin;  // float offset inside group g_begin of step j_begin
+};
+static_assert(sizeof(WaveRec) == 16, "WaveRec layout");
+
+struct ChunkRec {
+    uint32_t nzrank0;    // first non-empty tile rank the workgroup accumulates
+    uint32_t ntiles;     // how many (LDS slots of br rows each)
+    int32_t sid_first, part_first;  // shared-tile record / part of the first tile, or -1
+    int32_t sid_last, part_last;    // same for the last tile (only if ntiles > 1), or -1
+    uint32_t pad[2];
+};
+static_assert(sizeof(ChunkRec) == 32, "ChunkRec layout");
+
+struct SharedRec {
+    uint32_t tile;         // output tile
+    uint32_t nparts;       // workgroups that hold a partial sum of it
+    uint32_t partial_off;  // first partial slot (each slot br floats per right-hand side)
+    uint32_t pad;
+};
+static_assert(sizeof(SharedRec) == 16, "SharedRec layout");
+
+struct DevHeader {
+    uint64_t magic;
+    uint32_t n_chunks, waves_per_chunk, n_groups, n_vbs;
+    uint32_t n_shared, n_zero_tiles, n_nz_tiles, n_partial_slots;
+    uint32_t br, bc;
+    uint32_t max_chunk_tiles, reserved0;
+    uint64_t rows_out, cols;
+    uint64_t off_chunks, off_waves, off_groups, off_vbs, off_idx, off_vals;
+    uint64_t off_nz_tiles, off_zero_tiles, off_shared, off_counters;
+    uint64_t idx_bytes, n_vals, total_bytes;
+};
+
+// Device-side pointers resolved from the image base (kernel argument, by value).
+struct DevMat {
+    const ChunkRec *chunks;
+    const WaveRec *waves;
+    const GroupRec *groups;
+    const VbRec *vbs;
+    const uint8_t *idx;
+    const float *vals;
+    const uint32_t *nz_tiles;
+    const uint32_t *zero_tiles;
+    const SharedRec *shared;
+    uint32_t *counters;
+    uint32_t n_chunks, waves_per_chunk, n_zero_tiles, n_shared;
+    uint32_t br, bc;
+    uint32_t rows_out, cols;
+    uint32_t n_groups, reserved;
+};
+
+// How rows are relabelled when the image is built for a GRU: entries in rows >= split_row
+// and columns >= split_col are summed into output row (row + shift) instead of row.
+struct SplitSpec {
+    int64_t split_row = -1, split_col = -1, shift = 0;
+    bool active() const { return split_row >= 0; }
+    bool operator==(const SplitSpec &o) const {
+        return split_row == o.split_row && split_col == o.split_col && shift == o.shift;
+    }
+};
+
+struct Plan {
+    bool valid = false;
+    SplitSpec split;
+    std::vector<uint8_t> image;   // host staging copy of the device image
+    DevHeader hdr{};
+    csb_plan_stats stats{};
+};
+
+void set_error(const std::string &msg);
+
+}  // namespace csb
+
+struct csb_matrix {
+    int64_t rows = 0, cols = 0;
+    int32_t br = 0, bc = 0, nbr = 0, nbc = 0;
+    std::vector<int32_t> nrows, ncols;
+    std::vector<uint16_t> rowidx, colidx;
+    std::vector<float> val;
+    std::vector<int64_t> val_off, row_off, col_off;
+    csb::Plan plan;
+    void *d_buf = nullptr;        // caller-owned device image, set by csb_upload
+    bool uploaded = false;
+};
+
+namespace csb {
+int plan_matrix(csb_matrix *m, int32_t n_chunks, int32_t waves_per_chunk, const SplitSpec &split,
+                csb_plan_stats *stats);
+int validate_plan(const csb_matrix *m);
+DevMat dev_mat(const csb_matrix *m);
+}  // namespace csb

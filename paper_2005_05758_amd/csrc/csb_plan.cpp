@@ -1,0 +1,535 @@
+// Equal-work partition and device image builder (host only).
+//
+// Role in the method: the paper balances uneven kernel-matrix work across its PE groups
+// with a compiler pass (Sec. 5.2: every unit should end up with the average work of the
+// iteration).  Here the parallel unit is a 64-lane wavefront and the balance comes from a
+// prefix sum over wavefront steps that is cut into equal ranges.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "csb_internal.hpp"
+
+namespace csb {
+namespace {
+
+struct Vb {
+    uint32_t tile;             // output tile (out_row / br)
+    uint32_t b;                // source CSB block
+    uint16_t bj;
+    uint16_t q0, q1;           // column positions [q0, q1) of the block's column list
+    std::vector<uint16_t> a;   // kernel-matrix row positions inside the block
+    std::vector<uint8_t> slot; // out_row - tile * br for each of them
+    int c() const { return q1 - q0; }
+    int r() const { return (int)a.size(); }
+};
+
+struct Group {
+    uint32_t tile;
+    std::vector<uint32_t> vbs;  // indices into the Vb array, column counts descending
+    int cmax = 0, nlanes = 0;
+};
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Values a group holds before column step j (lanes are ordered by descending c).
+uint32_t vals_before_step(const std::vector<Vb> &vb, const Group &g, int j) {
+    uint32_t n = 0;
+    for (uint32_t k : g.vbs) n += (uint32_t)vb[k].r() * (uint32_t)std::min(j, vb[k].c());
+    return n;
+}
+
+}  // namespace
+
+int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, const SplitSpec &split,
+                csb_plan_stats *stats_out) {
+    if (!m) { set_error("csb_plan: NULL matrix"); return CSB_EINVAL; }
+    if (n_chunks_req < 0) { set_error("csb_plan: n_chunks < 0"); return CSB_EINVAL; }
+    if (waves_per_chunk != 4 && waves_per_chunk != 8 && waves_per_chunk != 16) {
+        set_error("csb_plan: waves_per_chunk must be 4, 8 or 16");
+        return CSB_EINVAL;
+    }
+    if (m->val.size() >= (1ull << 32) || m->cols > (int64_t)65535 * m->bc) {
+        set_error("csb_plan: matrix too large for 32-bit device offsets");
+        return CSB_EUNSUPPORTED;
+    }
+    try {
+        const int br = m->br, bc = m->bc;
+        const int64_t rows_out = split.active() ? m->rows + split.shift : m->rows;
+        const uint32_t n_tiles = (uint32_t)((rows_out + br - 1) / br);
+
+        // ---- 1. virtual blocks, bucketed by output tile --------------------------------
+        std::vector<Vb> vbs;
+        std::vector<std::vector<uint32_t>> by_tile(n_tiles);
+        for (int32_t bi = 0; bi < m->nbr; ++bi)
+            for (int32_t bj = 0; bj < m->nbc; ++bj) {
+                const size_t b = (size_t)bi * m->nbc + bj;
+                const int nr = m->nrows[b], nc = m->ncols[b];
+                if (nr == 0 || nc == 0) continue;
+                const uint16_t *ri = m->rowidx.data() + m->row_off[b];
+                const uint16_t *ci = m->colidx.data() + m->col_off[b];
+                int qs = nc;  // first column position at or past the split column
+                if (split.active()) {
+                    qs = 0;
+                    while (qs < nc && (int64_t)bj * bc + ci[qs] < split.split_col) ++qs;
+                }
+                // parts: (q0, q1, shifted?) ; rows below split_row always take the full range
+                struct Part { int q0, q1; bool lower, shifted; };
+                Part parts[3] = {{0, nc, true, false}, {0, qs, false, false}, {qs, nc, false, true}};
+                for (const Part &p : parts) {
+                    if (p.q0 >= p.q1) continue;
+                    Vb cur;
+                    bool open = false;
+                    auto flush = [&]() {
+                        if (open && !cur.a.empty()) {
+                            by_tile[cur.tile].push_back((uint32_t)vbs.size());
+                            vbs.push_back(cur);
+                        }
+                        open = false;
+                    };
+                    for (int a = 0; a < nr; ++a) {
+                        const int64_t gr = (int64_t)bi * br + ri[a];
+                        const bool is_lower = !split.active() || gr < split.split_row;
+                        if (is_lower != p.lower) continue;
+                        const int64_t orow = gr + (p.shifted ? split.shift : 0);
+                        const uint32_t tile = (uint32_t)(orow / br);
+                        if (!open || cur.tile != tile || cur.r() == kWave) {
+                            flush();
+                            cur = Vb{};
+                            cur.tile = tile; cur.b = (uint32_t)b; cur.bj = (uint16_t)bj;
+                            cur.q0 = (uint16_t)p.q0; cur.q1 = (uint16_t)p.q1;
+                            open = true;
+                        }
+                        cur.a.push_back((uint16_t)a);
+                        cur.slot.push_back((uint8_t)(orow - (int64_t)tile * br));
+                    }
+                    flush();
+                }
+            }
+
+        // ---- 2. 64-lane groups per tile -------------------------------------------------
+        std::vector<Group> groups;
+        std::vector<uint32_t> nz_tiles, zero_tiles, tile_rank(n_tiles, 0);
+        for (uint32_t t = 0; t < n_tiles; ++t) {
+            auto &lst = by_tile[t];
+            if (lst.empty()) { zero_tiles.push_back(t); continue; }
+            tile_rank[t] = (uint32_t)nz_tiles.size();
+            nz_tiles.push_back(t);
+            std::stable_sort(lst.begin(), lst.end(),
+                             [&](uint32_t x, uint32_t y) { return vbs[x].c() > vbs[y].c(); });
+            std::vector<char> used(lst.size(), 0);
+            size_t head = 0;
+            while (head < lst.size()) {
+                if (used[head]) { ++head; continue; }
+                Group g;
+                g.tile = t;
+                // fill with the next unused blocks that still fit (look a little ahead)
+                for (size_t p = head; p < lst.size() && p < head + 256; ++p) {
+                    if (used[p]) continue;
+                    const Vb &v = vbs[lst[p]];
+                    if (g.nlanes + v.r() > kWave) continue;
+                    used[p] = 1;
+                    g.vbs.push_back(lst[p]);
+                    g.nlanes += v.r();
+                    g.cmax = std::max(g.cmax, v.c());
+                    if ((int)g.vbs.size() == kMaxVbPerGroup || g.nlanes == kWave) break;
+                }
+                groups.push_back(std::move(g));
+            }
+        }
+        const uint32_t n_groups = (uint32_t)groups.size();
+
+        // ---- 3. cost axis, chunk and wave cuts -----------------------------------------
+        // Group g occupies [P[g], P[g+1]) with P[g+1]-P[g] = overhead + cmax; a cut inside
+        // the overhead part snaps to the group start.
+        std::vector<uint64_t> P(n_groups + 1, 0);
+        for (uint32_t g = 0; g < n_groups; ++g) P[g + 1] = P[g] + kGroupOverhead + groups[g].cmax;
+        const uint64_t total = P[n_groups];
+        int n_chunks = n_chunks_req;
+        if (n_chunks == 0) {
+            // default for one MI355X (256 CUs): two workgroups per CU once there is enough
+            // work for every wavefront to have a few groups, fewer for small matrices
+            const uint64_t per_wave_min = 4 * (kGroupOverhead + 8);
+            uint64_t want = total / (per_wave_min * (uint64_t)waves_per_chunk);
+            n_chunks = (int)std::min<uint64_t>(std::max<uint64_t>(want, 1), 512);
+        }
+        struct Pos { uint32_t g; uint32_t j; };
+        auto locate = [&](uint64_t X) -> Pos {
+            if (X >= total) return Pos{n_groups, 0};
+            uint32_t g = (uint32_t)(std::upper_bound(P.begin(), P.end(), X) - P.begin() - 1);
+            const uint64_t in = X - P[g];
+            if (in <= (uint64_t)kGroupOverhead) return Pos{g, 0};
+            return Pos{g, (uint32_t)(in - kGroupOverhead)};
+        };
+        const uint32_t max_tiles_per_chunk = (uint32_t)std::max(1, kAccRowsMax / br);
+        std::vector<uint64_t> chunk_cut;  // cost coordinates, chunk c = [cut[c], cut[c+1])
+        chunk_cut.push_back(0);
+        {
+            uint64_t X = 0;
+            int remaining = n_chunks;
+            while (X < total) {
+                if (remaining < 1) remaining = 1;
+                uint64_t target = (total - X + remaining - 1) / remaining;
+                uint64_t end = std::min(total, X + std::max<uint64_t>(target, 1));
+                // tile limit: walk groups from the first one touched
+                Pos a = locate(X);
+                uint32_t g = a.g;
+                uint32_t first_rank = g < n_groups ? tile_rank[groups[g].tile] : 0;
+                while (g < n_groups && P[g] < end) {
+                    if (tile_rank[groups[g].tile] - first_rank >= max_tiles_per_chunk) { end = P[g]; break; }
+                    ++g;
+                }
+                if (end <= X) end = std::min(total, P[a.g + 1]);  // always advance
+                chunk_cut.push_back(end);
+                X = end;
+                --remaining;
+            }
+            while ((int)chunk_cut.size() - 1 < n_chunks_req) chunk_cut.push_back(total);  // empty chunks
+        }
+        n_chunks = (int)chunk_cut.size() - 1;
+        if (n_chunks == 0) { chunk_cut.push_back(total); n_chunks = 1; }
+        const int NW = waves_per_chunk;
+        std::vector<WaveRec> waves((size_t)n_chunks * NW);
+        std::vector<ChunkRec> chunks(n_chunks);
+        std::vector<Pos> cpos_a(n_chunks), cpos_b(n_chunks);
+        std::vector<double> wave_cost(waves.size(), 0.0);
+        for (int c = 0; c < n_chunks; ++c) {
+            const uint64_t Xa = chunk_cut[c], Xb = chunk_cut[c + 1];
+            cpos_a[c] = locate(Xa);
+            cpos_b[c] = locate(Xb);
+            for (int w = 0; w < NW; ++w) {
+                const uint64_t xa = Xa + (Xb - Xa) * (uint64_t)w / NW;
+                const uint64_t xb = Xa + (Xb - Xa) * (uint64_t)(w + 1) / NW;
+                Pos a = locate(xa), b = locate(xb);
+                if (w == 0) a = cpos_a[c];
+                if (w == NW - 1) b = cpos_b[c];
+                WaveRec &wr = waves[(size_t)c * NW + w];
+                wr.g_begin = a.g; wr.j_begin = (uint16_t)a.j;
+                wr.g_end = b.g; wr.j_end = (uint16_t)b.j;
+                wr.val_begin = a.g < n_groups ? vals_before_step(vbs, groups[a.g], (int)a.j) : 0;
+                double cost = 0;
+                for (uint32_t g = a.g; g <= b.g && g < n_groups; ++g) {
+                    const int jlo = g == a.g ? (int)a.j : 0;
+                    const int jhi = g == b.g ? (int)b.j : groups[g].cmax;
+                    if (jhi > jlo) cost += kGroupOverhead + (jhi - jlo);
+                }
+                wave_cost[(size_t)c * NW + w] = cost;
+            }
+        }
+
+        // ---- 4. tiles per chunk, shared tiles -------------------------------------------
+        // touched groups of chunk c: [ga, gb] with gb included only if its j > 0
+        std::vector<int> tile_first_chunk(nz_tiles.size(), -1), tile_last_chunk(nz_tiles.size(), -1);
+        std::vector<int> c_rank0(n_chunks, 0), c_ntiles(n_chunks, 0);
+        for (int c = 0; c < n_chunks; ++c) {
+            uint32_t ga = cpos_a[c].g, gb = cpos_b[c].g;
+            if (cpos_b[c].j == 0) { if (gb == 0 || gb <= ga) { c_ntiles[c] = 0; continue; } --gb; }
+            if (ga >= n_groups) { c_ntiles[c] = 0; continue; }
+            // a chunk that starts at (ga, j) with j == cmax cannot happen: locate() keeps j < cmax
+            const uint32_t r0 = tile_rank[groups[ga].tile], r1 = tile_rank[groups[gb].tile];
+            c_rank0[c] = (int)r0;
+            c_ntiles[c] = (int)(r1 - r0 + 1);
+            for (uint32_t r = r0; r <= r1; ++r) {
+                if (tile_first_chunk[r] < 0) tile_first_chunk[r] = c;
+                tile_last_chunk[r] = c;
+            }
+        }
+        std::vector<SharedRec> shared;
+        std::vector<int> tile_sid(nz_tiles.size(), -1);
+        uint32_t n_partial_slots = 0;
+        for (size_t r = 0; r < nz_tiles.size(); ++r) {
+            if (tile_first_chunk[r] < 0) { set_error("csb_plan: internal: tile without a chunk"); return CSB_EINVAL; }
+            if (tile_last_chunk[r] > tile_first_chunk[r]) {
+                // chunks between first and last that touch no group at all do not exist on a
+                // contiguous axis, except empty trailing chunks; count only the touching ones
+                SharedRec s{};
+                s.tile = nz_tiles[r];
+                s.nparts = 0;
+                s.partial_off = n_partial_slots;
+                tile_sid[r] = (int)shared.size();
+                shared.push_back(s);
+            }
+        }
+        for (int c = 0; c < n_chunks; ++c) {
+            ChunkRec &cr = chunks[c];
+            cr = ChunkRec{};
+            cr.nzrank0 = (uint32_t)c_rank0[c];
+            cr.ntiles = (uint32_t)c_ntiles[c];
+            cr.sid_first = cr.part_first = cr.sid_last = cr.part_last = -1;
+            if (c_ntiles[c] == 0) continue;
+            const int rf = c_rank0[c], rl = c_rank0[c] + c_ntiles[c] - 1;
+            if (tile_sid[rf] >= 0) {
+                cr.sid_first = tile_sid[rf];
+                cr.part_first = (int32_t)shared[tile_sid[rf]].nparts++;
+            }
+            if (rl != rf && tile_sid[rl] >= 0) {
+                cr.sid_last = tile_sid[rl];
+                cr.part_last = (int32_t)shared[tile_sid[rl]].nparts++;
+            }
+        }
+        for (auto &s : shared) { s.partial_off = n_partial_slots; n_partial_slots += s.nparts; }
+
+        // ---- 5. streams -----------------------------------------------------------------
+        std::vector<GroupRec> grecs(n_groups);
+        std::vector<VbRec> vrecs;
+        std::vector<uint8_t> idx;
+        std::vector<float> vals;
+        vals.reserve(m->val.size());
+        uint64_t fma_steps = 0;
+        for (uint32_t gi = 0; gi < n_groups; ++gi) {
+            const Group &g = groups[gi];
+            GroupRec &gr = grecs[gi];
+            gr.val_off = (uint32_t)vals.size();
+            gr.idx_off = (uint32_t)idx.size();
+            gr.vb_off = (uint32_t)vrecs.size();
+            gr.nzrank = tile_rank[g.tile];
+            gr.cmax = (uint16_t)g.cmax;
+            gr.nvb = (uint8_t)g.vbs.size();
+            gr.nlanes = (uint8_t)g.nlanes;
+            // lane descriptors: row slot | (vb number << 8)
+            for (size_t k = 0; k < g.vbs.size(); ++k)
+                for (uint8_t s : vbs[g.vbs[k]].slot) { idx.push_back(s); idx.push_back((uint8_t)k); }
+            while (idx.size() % 4) idx.push_back(0);
+            const size_t col_base = idx.size();
+            int lane0 = 0;
+            for (size_t k = 0; k < g.vbs.size(); ++k) {
+                const Vb &v = vbs[g.vbs[k]];
+                VbRec vr{};
+                vr.r = (uint8_t)v.r(); vr.lane0 = (uint8_t)lane0; vr.c = (uint16_t)v.c(); vr.bj = v.bj;
+                vr.coloff4 = (uint16_t)((idx.size() - col_base) / 4);
+                const uint16_t *ci = m->colidx.data() + m->col_off[v.b];
+                for (int q = v.q0; q < v.q1; ++q) idx.push_back((uint8_t)ci[q]);
+                while (idx.size() % 4) idx.push_back(0);
+                vrecs.push_back(vr);
+                lane0 += v.r();
+            }
+            // values, step-major
+            for (int j = 0; j < g.cmax; ++j)
+                for (uint32_t k : g.vbs) {
+                    const Vb &v = vbs[k];
+                    if (j >= v.c()) continue;
+                    const int nc = m->ncols[v.b];
+                    const float *src = m->val.data() + m->val_off[v.b];
+                    for (uint16_t a : v.a) vals.push_back(src[(size_t)a * nc + v.q0 + j]);
+                }
+            gr.nvals = (uint32_t)vals.size() - gr.val_off;
+            fma_steps += (uint64_t)g.cmax;
+        }
+        if (vals.size() != m->val.size()) { set_error("csb_plan: internal: value count mismatch"); return CSB_EINVAL; }
+
+        // ---- 6. image -------------------------------------------------------------------
+        DevHeader h{};
+        h.magic = 0x4353424d49333535ull;  // "CSBMI355"
+        h.n_chunks = (uint32_t)n_chunks; h.waves_per_chunk = (uint32_t)NW;
+        h.n_groups = n_groups; h.n_vbs = (uint32_t)vrecs.size();
+        h.n_shared = (uint32_t)shared.size(); h.n_zero_tiles = (uint32_t)zero_tiles.size();
+        h.n_nz_tiles = (uint32_t)nz_tiles.size(); h.n_partial_slots = n_partial_slots;
+        h.max_chunk_tiles = 1;
+        for (const ChunkRec &cr : chunks) h.max_chunk_tiles = std::max(h.max_chunk_tiles, cr.ntiles);
+        h.br = (uint32_t)br; h.bc = (uint32_t)bc; h.rows_out = (uint64_t)rows_out; h.cols = (uint64_t)m->cols;
+        size_t off = align_up(sizeof(DevHeader), 256);
+        auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes + 64, 256); return o; };
+        h.off_chunks = place(chunks.size() * sizeof(ChunkRec));
+        h.off_waves = place(waves.size() * sizeof(WaveRec));
+        h.off_groups = place(grecs.size() * sizeof(GroupRec));
+        h.off_vbs = place(vrecs.size() * sizeof(VbRec));
+        h.off_idx = place(idx.size());
+        h.off_vals = place(vals.size() * sizeof(float));
+        h.off_nz_tiles = place(nz_tiles.size() * 4);
+        h.off_zero_tiles = place(zero_tiles.size() * 4);
+        h.off_shared = place(shared.size() * sizeof(SharedRec));
+        h.off_counters = place(shared.size() * 4);
+        h.idx_bytes = idx.size(); h.n_vals = vals.size(); h.total_bytes = off;
+        Plan &pl = m->plan;
+        pl.image.assign(off, 0);
+        uint8_t *im = pl.image.data();
+        std::memcpy(im, &h, sizeof(h));
+        auto put = [&](size_t o, const void *p, size_t n) { if (n) std::memcpy(im + o, p, n); };
+        put(h.off_chunks, chunks.data(), chunks.size() * sizeof(ChunkRec));
+        put(h.off_waves, waves.data(), waves.size() * sizeof(WaveRec));
+        put(h.off_groups, grecs.data(), grecs.size() * sizeof(GroupRec));
+        put(h.off_vbs, vrecs.data(), vrecs.size() * sizeof(VbRec));
+        put(h.off_idx, idx.data(), idx.size());
+        put(h.off_vals, vals.data(), vals.size() * sizeof(float));
+        put(h.off_nz_tiles, nz_tiles.data(), nz_tiles.size() * 4);
+        put(h.off_zero_tiles, zero_tiles.data(), zero_tiles.size() * 4);
+        put(h.off_shared, shared.data(), shared.size() * sizeof(SharedRec));
+        pl.hdr = h;
+        pl.split = split;
+        pl.valid = true;
+        m->uploaded = false;
+        m->d_buf = nullptr;
+
+        // ---- 7. statistics --------------------------------------------------------------
+        csb_plan_stats st{};
+        st.n_chunks = n_chunks; st.waves_per_chunk = NW; st.n_groups = (int32_t)n_groups;
+        st.n_shared_tiles = (int32_t)shared.size();
+        double wmax = 0, wsum = 0;
+        for (double c : wave_cost) { wmax = std::max(wmax, c); wsum += c; }
+        st.work_max = wmax;
+        st.work_mean = wave_cost.empty() ? 0 : wsum / (double)wave_cost.size();
+        st.lane_fill = fma_steps ? (double)m->val.size() / (64.0 * (double)fma_steps) : 0.0;
+        {
+            const size_t nwt = wave_cost.size();
+            std::vector<double> rr(nwt, 0.0);
+            size_t k = 0;
+            for (size_t b = 0; b < m->nrows.size(); ++b) {
+                if (m->nrows[b] == 0 || m->ncols[b] == 0) continue;
+                rr[k % nwt] += (double)m->nrows[b] * m->ncols[b];
+                ++k;
+            }
+            double mx = 0, sm = 0;
+            for (double v : rr) { mx = std::max(mx, v); sm += v; }
+            st.nosplit_max_over_mean = sm > 0 ? mx / (sm / (double)nwt) : 0.0;
+        }
+        pl.stats = st;
+        if (stats_out) *stats_out = st;
+        return CSB_OK;
+    } catch (const std::bad_alloc &) {
+        set_error("csb_plan: out of host memory");
+        return CSB_ENOMEM;
+    }
+}
+
+// Walk the image the way the kernels do, with bounds checks on every access, rebuild the
+// (output row, column) -> value map and compare it with the packed matrix.
+int validate_plan(const csb_matrix *m) {
+    if (!m) { set_error("csb_plan_validate: NULL matrix"); return CSB_EINVAL; }
+    if (!m->plan.valid) { set_error("csb_plan_validate: matrix not planned"); return CSB_ESTATE; }
+    const Plan &pl = m->plan;
+    const DevHeader &h = pl.hdr;
+    const uint8_t *im = pl.image.data();
+    auto fail = [&](const char *what) { set_error(std::string("csb_plan_validate: ") + what); return CSB_EINVAL; };
+    if (h.total_bytes != pl.image.size()) return fail("image size");
+    const auto *chunks = (const ChunkRec *)(im + h.off_chunks);
+    const auto *waves = (const WaveRec *)(im + h.off_waves);
+    const auto *groups = (const GroupRec *)(im + h.off_groups);
+    const auto *vbs = (const VbRec *)(im + h.off_vbs);
+    const uint8_t *idx = im + h.off_idx;
+    const float *vals = (const float *)(im + h.off_vals);
+    const auto *nz_tiles = (const uint32_t *)(im + h.off_nz_tiles);
+    const auto *zero_tiles = (const uint32_t *)(im + h.off_zero_tiles);
+    const auto *shared = (const SharedRec *)(im + h.off_shared);
+    const int64_t rows_out = (int64_t)h.rows_out, cols = (int64_t)h.cols;
+    const uint32_t br = h.br, bc = h.bc, NW = h.waves_per_chunk;
+    const uint32_t n_tiles = (uint32_t)((rows_out + br - 1) / br);
+
+    // expected map: dense rows_out x cols with the split relabelling applied
+    std::vector<float> expect((size_t)rows_out * cols, 0.0f), got((size_t)rows_out * cols, 0.0f);
+    std::vector<uint8_t> seen((size_t)rows_out * cols, 0);
+    for (int32_t bi = 0; bi < m->nbr; ++bi)
+        for (int32_t bj = 0; bj < m->nbc; ++bj) {
+            const size_t b = (size_t)bi * m->nbc + bj;
+            const int nr = m->nrows[b], nc = m->ncols[b];
+            for (int a = 0; a < nr; ++a)
+                for (int q = 0; q < nc; ++q) {
+                    int64_t gr = (int64_t)bi * br + m->rowidx[m->row_off[b] + a];
+                    const int64_t gc = (int64_t)bj * bc + m->colidx[m->col_off[b] + q];
+                    if (pl.split.active() && gr >= pl.split.split_row && gc >= pl.split.split_col) gr += pl.split.shift;
+                    expect[(size_t)gr * cols + gc] = m->val[m->val_off[b] + (size_t)a * nc + q];
+                }
+        }
+    std::vector<uint8_t> tile_written(n_tiles, 0);
+    std::vector<uint32_t> parts_seen(h.n_shared, 0);
+    uint64_t vals_used = 0;
+    for (uint32_t c = 0; c < h.n_chunks; ++c) {
+        const ChunkRec &cr = chunks[c];
+        if (cr.ntiles * br > (uint32_t)kAccRowsMax && cr.ntiles > 1) return fail("chunk tile span");
+        if (cr.nzrank0 + cr.ntiles > h.n_nz_tiles) return fail("chunk tile rank");
+        for (uint32_t w = 0; w < NW; ++w) {
+            const WaveRec &wr = waves[(size_t)c * NW + w];
+            if (wr.g_begin > h.n_groups || wr.g_end > h.n_groups || wr.g_begin > wr.g_end) return fail("wave range");
+            for (uint32_t g = wr.g_begin; g <= wr.g_end && g < h.n_groups; ++g) {
+                const GroupRec &gr = groups[g];
+                const int jlo = g == wr.g_begin ? wr.j_begin : 0;
+                const int jhi = g == wr.g_end ? wr.j_end : gr.cmax;
+                if (jhi <= jlo) continue;
+                if (jhi > gr.cmax) return fail("wave step range");
+                if (gr.nzrank < cr.nzrank0 || gr.nzrank >= cr.nzrank0 + cr.ntiles) return fail("group tile outside chunk");
+                if (gr.nlanes > kWave || gr.nvb > kMaxVbPerGroup) return fail("group size");
+                if ((uint64_t)gr.vb_off + gr.nvb > h.n_vbs) return fail("vb range");
+                const uint32_t tile = nz_tiles[gr.nzrank];
+                const uint32_t tile_h = (uint32_t)std::min<int64_t>(br, rows_out - (int64_t)tile * br);
+                const size_t col_base = (size_t)gr.idx_off + align_up(2 * (size_t)gr.nlanes, 4);
+                // offset of step jlo
+                uint32_t off = 0;
+                for (int j = 0; j < jlo; ++j)
+                    for (int k = 0; k < gr.nvb; ++k) if (j < vbs[gr.vb_off + k].c) off += vbs[gr.vb_off + k].r;
+                if (g == wr.g_begin && off != wr.val_begin) return fail("wave val_begin");
+                for (int j = jlo; j < jhi; ++j) {
+                    uint32_t n_active = 0;
+                    for (int lane = 0; lane < gr.nlanes; ++lane) {
+                        if ((size_t)gr.idx_off + 2 * lane + 1 >= h.idx_bytes) return fail("lane descriptor offset");
+                        const uint8_t slot = idx[gr.idx_off + 2 * lane], k = idx[gr.idx_off + 2 * lane + 1];
+                        if (k >= gr.nvb) return fail("lane vb number");
+                        const VbRec &v = vbs[gr.vb_off + k];
+                        if (lane < v.lane0 || lane >= v.lane0 + v.r) return fail("lane outside its vb");
+                        if (slot >= tile_h) return fail("row slot");
+                        if (j >= v.c) continue;
+                        if ((uint32_t)lane != n_active) return fail("active lanes are not a prefix");
+                        const size_t ia = col_base + 4 * (size_t)v.coloff4 + j;
+                        if (ia >= h.idx_bytes) return fail("column index offset");
+                        const uint32_t col = idx[ia];
+                        const int64_t gc = (int64_t)v.bj * bc + col;
+                        if (col >= bc || gc >= cols) return fail("column index");
+                        const uint64_t va = (uint64_t)gr.val_off + off + n_active;
+                        if (va >= h.n_vals || off + n_active >= gr.nvals) return fail("value offset");
+                        const size_t cell = (size_t)((int64_t)tile * br + slot) * cols + gc;
+                        if (seen[cell]) return fail("entry referenced twice");
+                        seen[cell] = 1;
+                        got[cell] = vals[va];
+                        ++vals_used;
+                        ++n_active;
+                    }
+                    off += n_active;
+                }
+            }
+        }
+        for (uint32_t s = 0; s < cr.ntiles; ++s) {
+            const uint32_t tile = nz_tiles[cr.nzrank0 + s];
+            int sid = -1, part = -1;
+            if (s == 0 && cr.sid_first >= 0) { sid = cr.sid_first; part = cr.part_first; }
+            else if (s == cr.ntiles - 1 && cr.sid_last >= 0) { sid = cr.sid_last; part = cr.part_last; }
+            if (sid >= 0) {
+                if ((uint32_t)sid >= h.n_shared || shared[sid].tile != tile) return fail("shared tile record");
+                if ((uint32_t)part >= shared[sid].nparts) return fail("shared part number");
+                if (parts_seen[sid] >> part & 1 && shared[sid].nparts <= 32) return fail("shared part twice");
+                if (shared[sid].nparts <= 32) parts_seen[sid] |= 1u << part;
+                if (shared[sid].partial_off + shared[sid].nparts > h.n_partial_slots) return fail("partial slot");
+                tile_written[tile] = 1;   // by the last part to arrive
+            } else {
+                if (tile_written[tile]) return fail("tile written twice");
+                tile_written[tile] = 1;
+            }
+        }
+    }
+    for (uint32_t s = 0; s < h.n_shared; ++s)
+        if (shared[s].nparts <= 32 && parts_seen[s] != (shared[s].nparts == 32 ? 0xffffffffu : (1u << shared[s].nparts) - 1))
+            return fail("shared tile with a missing part");
+    for (uint32_t z = 0; z < h.n_zero_tiles; ++z) {
+        if (zero_tiles[z] >= n_tiles || tile_written[zero_tiles[z]]) return fail("zero tile");
+        tile_written[zero_tiles[z]] = 1;
+    }
+    for (uint32_t t = 0; t < n_tiles; ++t) if (!tile_written[t]) return fail("tile never written");
+    if (vals_used != m->val.size()) return fail("not every value referenced exactly once");
+    if (std::memcmp(expect.data(), got.data(), expect.size() * sizeof(float)) != 0) return fail("image does not decode to the matrix");
+    return CSB_OK;
+}
+
+}  // namespace csb
+
+extern "C" int csb_plan(csb_matrix *m, int32_t n_chunks, csb_plan_stats *stats) {
+    return csb::plan_matrix(m, n_chunks, 16, csb::SplitSpec{}, stats);
+}
+
+extern "C" int csb_plan_validate(const csb_matrix *m) { return csb::validate_plan(m); }
+
+extern "C" size_t csb_device_bytes(const csb_matrix *m) {
+    return (m && m->plan.valid) ? m->plan.image.size() : 0;
+}
+
+extern "C" size_t csb_workspace_bytes(const csb_matrix *m, int32_t batch) {
+    if (!m || !m->plan.valid || batch <= 0) return 0;
+    return (size_t)m->plan.hdr.n_partial_slots * m->plan.hdr.br * sizeof(float) * (size_t)batch;
+}

@@ -1,0 +1,122 @@
+"""Parity of csb_spmv (HIP, through the C ABI) against the oracle's float64 product on the
+decompressed matrix.  Tolerances (float32 path):
+  - norm-wise: max|y - y_ref| / max|y_ref| <= 1e-5
+  - element-wise: |y_i - y_ref_i| <= 2 k_i 2^-24 sum_j |a_ij x_j|, k_i = kept entries of row
+    i (the textbook bound for a float32 dot product in any summation order)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import csb_inputs
+import oracle
+from paper_2005_05758_amd import CsbMatrix
+from helpers import rel_max_err
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def check_spmv(A, br, bc, x, n_chunks=0, tag=""):
+    say(f"[spmv] {tag} shape={A.shape} block={br}x{bc} n_chunks={n_chunks}")
+    enc = oracle.csb_encode(A, br, bc)
+    D = oracle.csb_decode(enc)                      # oracle works on the decompressed matrix
+    ref = oracle.matvec(D, x)
+    scale = oracle.matvec_abs(D, x)
+    M = CsbMatrix(A, br, bc)
+    M.plan(n_chunks)
+    M.validate()
+    M.upload()
+    xd = torch.from_numpy(x).cuda()
+    y = M.spmv(xd)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    assert got.shape == ref.shape
+    assert np.all(np.isfinite(got))
+    assert rel_max_err(got, ref) <= 1e-5, rel_max_err(got, ref)
+    k = np.count_nonzero(D, axis=1)
+    bound = 2.0 * np.maximum(k, 1) * 2.0 ** -24 * scale + 1e-30
+    assert np.all(np.abs(got - ref) <= bound)
+    # run-to-run bitwise reproducibility
+    y2 = M.spmv(xd)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    return M, got
+
+
+@pytest.mark.parametrize("R,C,br,bc,rate", [
+    (4, 8, 4, 4, 2.0), (1, 1, 1, 1, 1.0), (37, 53, 8, 8, 3.0), (200, 150, 16, 16, 6.0),
+    (130, 257, 32, 32, 5.0), (96, 96, 32, 16, 4.0), (70, 300, 16, 64, 4.0), (300, 40, 128, 8, 3.0),
+    (513, 100, 256, 256, 2.0), (64, 64, 64, 64, 1.0)])
+def test_spmv_small_shapes(R, C, br, bc, rate):
+    m = csb_inputs.small_matrix(R * 3 + C, R, C, br, bc, rate=rate)
+    x = csb_inputs.make_vectors(R + C, C, 1)
+    for n_chunks in (0, 1, 3, 7):
+        check_spmv(m.A, br, bc, x, n_chunks, tag="small")
+
+
+def test_spmv_degenerate_matrices():
+    x = csb_inputs.make_vectors(1, 48, 1)
+    Z = np.zeros((40, 48), np.float32)
+    check_spmv(Z, 16, 16, x, tag="all-zero")                       # every tile empty
+    E = Z.copy()
+    E[17, 5] = 2.0                                                 # a single survivor
+    _, got = check_spmv(E, 16, 16, x, tag="single")
+    assert got[17] == 2.0 * float(x[5]) and np.count_nonzero(got) == 1
+    Dn = csb_inputs.small_matrix(2, 40, 48, 16, 16, rate=1.0).A    # fully dense blocks
+    check_spmv(Dn, 16, 16, x, tag="dense")
+    I = np.eye(48, dtype=np.float32)
+    _, got = check_spmv(I, 16, 16, x, tag="identity")
+    assert np.array_equal(got, x.astype(np.float64))
+    P = np.zeros((48, 48), np.float32)
+    perm = np.random.default_rng(0).permutation(48)
+    P[np.arange(48), perm] = 1.0
+    _, got = check_spmv(P, 16, 16, x, n_chunks=5, tag="permutation")
+    assert np.array_equal(got, x[perm].astype(np.float64))
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3"])
+def test_spmv_rnn_matrices(name):
+    cfg = csb_inputs.CONFIGS[name]
+    m = csb_inputs.make_rnn(cfg, T=1).W[0]
+    x = csb_inputs.make_vectors(3, m.cols, 1)
+    for n_chunks in (0, 16, 100):
+        check_spmv(m.A, m.br, m.bc, x, n_chunks, tag=name)
+
+
+def test_spmv_result_independent_of_partition():
+    m = csb_inputs.small_matrix(9, 512, 640, 32, 32, rate=8.0, law="beta")
+    x = csb_inputs.make_vectors(9, 640, 1)
+    outs = [check_spmv(m.A, 32, 32, x, n, tag="partition")[1] for n in (1, 2, 13, 64)]
+    for o in outs[1:]:
+        assert rel_max_err(o, outs[0]) <= 1e-5
+
+
+@pytest.mark.parametrize("name", ["cfg5", "cfg5_diag"])
+def test_spmv_full_size_stress(name):
+    """8192 x 8192, heavy-tailed block sizes, in the launch configuration the benchmark uses
+    (default plan).  The oracle handles the full product in a few seconds."""
+    m = csb_inputs.make_mat(csb_inputs.CONFIGS[name])
+    x = csb_inputs.make_vectors(5, m.cols, 1)
+    say(f"[spmv] {name} nnz={m.nnz}")
+    ref = oracle.matvec(m.A, x)                    # m.A == decode(encode(m.A)) (pinned on the CPU)
+    scale = oracle.matvec_abs(m.A, x)
+    M = CsbMatrix(m.A, m.br, m.bc)
+    st = M.plan(0)
+    say(f"[spmv] plan {st}")
+    assert st["work_max"] / st["work_mean"] <= 1.10
+    M.upload()
+    xd = torch.from_numpy(x).cuda()
+    y = M.spmv(xd)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    assert rel_max_err(got, ref) <= 1e-5
+    k = np.count_nonzero(m.A, axis=1)
+    assert np.all(np.abs(got - ref) <= 2.0 * k * 2.0 ** -24 * scale + 1e-30)
+    for _ in range(3):
+        assert torch.equal(M.spmv(xd), y)

@@ -1,0 +1,157 @@
+"""Host logic of the library against the oracle: csb_pack bit-exact, plan self-check,
+error returns, exported symbols.  No GPU needed (no compute entry point is called)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import csb_inputs
+import oracle
+from paper_2005_05758_amd import CsbMatrix, CsbError, binding
+from helpers import read_golden
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _same_encoding(M, enc):
+    v = M.view()
+    for k in ("nrows", "ncols", "rowidx", "colidx", "val_off", "row_off", "col_off"):
+        assert np.array_equal(v[k], getattr(enc, k)), k
+    assert np.array_equal(v["val"].view(np.uint32), enc.val.view(np.uint32))
+    assert v["nnz"] == enc.nnz
+    return v
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "csbrnn.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(csb_[a-z_]+)\s*\(", hdr)))
+    assert declared, "no declarations found"
+    L = binding.load_library()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(binding.SYMBOLS) == declared
+
+
+def test_pack_hand_worked_example():
+    g = read_golden("two_block_example.txt")
+    A = np.array(g["A"], np.float32)
+    v = CsbMatrix(A, 4, 4).view()
+    assert v["nrows"].tolist() == g["nrows_a"] and v["ncols"].tolist() == g["ncols_a"]
+    assert v["rowidx"].tolist() == g["rowidx_a"] and v["colidx"].tolist() == g["colidx_a"]
+    assert v["val"].tolist() == g["val_a"]
+    assert v["val_off"].tolist() == g["val_off"] and v["row_off"].tolist() == g["row_off"]
+    assert v["col_off"].tolist() == g["col_off"]
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3"])
+def test_pack_bit_exact_on_workloads(name):
+    cfg = csb_inputs.CONFIGS[name]
+    for m in csb_inputs.make_rnn(cfg, T=1).W:
+        M = CsbMatrix(m.A, m.br, m.bc)
+        _same_encoding(M, oracle.csb_encode(m.A, m.br, m.bc))
+        assert np.array_equal(M.unpack().view(np.uint32), m.A.view(np.uint32))
+
+
+@pytest.mark.parametrize("R,C,br,bc", [(7, 5, 3, 2), (12, 12, 5, 5), (1, 1, 1, 1), (33, 70, 32, 32),
+                                      (300, 17, 256, 16), (64, 64, 64, 64), (5, 300, 2, 256)])
+def test_pack_ragged_and_degenerate(R, C, br, bc):
+    for seed in range(3):
+        rng = np.random.default_rng(seed * 7 + R + C)
+        A = rng.normal(size=(R, C)).astype(np.float32)
+        A[rng.random((R, C)) < (0.0, 0.7, 1.0)[seed]] = 0.0        # dense, sparse, all zero
+        M = CsbMatrix(A, br, bc)
+        _same_encoding(M, oracle.csb_encode(A, br, bc))
+        assert np.array_equal(M.unpack(), A)
+        M.plan()
+        M.validate()
+
+
+def test_pack_special_values_and_leading_dimension():
+    A = np.zeros((4, 6), np.float32)
+    A[0, 0] = -0.0
+    A[1, 2] = np.nan
+    A[3, 5] = np.inf
+    M = CsbMatrix(A, 2, 2)
+    enc = oracle.csb_encode(A, 2, 2)
+    v = M.view()
+    assert np.array_equal(v["nrows"], enc.nrows) and np.array_equal(v["colidx"], enc.colidx)
+    assert np.array_equal(v["val"].view(np.uint32), enc.val.view(np.uint32))
+    # ld > cols: pack a window of a wider array
+    wide = np.arange(40, dtype=np.float32).reshape(4, 10)
+    Mw = CsbMatrix(wide[:, :6].copy(), 2, 4)
+    h = C.c_void_p()
+    L = binding.lib()
+    assert L.csb_pack(wide.ctypes.data, 4, 6, 10, 2, 4, C.byref(h)) == 0
+    out = np.empty((4, 6), np.float32)
+    assert L.csb_unpack(h, out.ctypes.data, 6) == 0
+    assert np.array_equal(out, wide[:, :6]) and np.array_equal(Mw.unpack(), out)
+    L.csb_free(h)
+
+
+def test_error_returns():
+    L = binding.lib()
+    A = np.ones((4, 4), np.float32)
+    h = C.c_void_p()
+    assert L.csb_pack(None, 4, 4, 4, 2, 2, C.byref(h)) == -1
+    assert L.csb_pack(A.ctypes.data, 4, 4, 4, 2, 2, None) == -1
+    assert L.csb_pack(A.ctypes.data, 0, 4, 4, 2, 2, C.byref(h)) == -1
+    assert L.csb_pack(A.ctypes.data, 4, -1, 4, 2, 2, C.byref(h)) == -1
+    assert L.csb_pack(A.ctypes.data, 4, 4, 3, 2, 2, C.byref(h)) == -1
+    assert L.csb_pack(A.ctypes.data, 4, 4, 4, 0, 2, C.byref(h)) == -1
+    assert L.csb_pack(A.ctypes.data, 4, 4, 4, 2, 257, C.byref(h)) == -1
+    assert b"block size" in L.csb_last_error()
+    assert L.csb_pack(A.ctypes.data, 4, 4, 4, 2, 2, C.byref(h)) == 0
+    # order of calls: nothing device-side before plan + upload
+    assert L.csb_device_bytes(h) == 0
+    assert L.csb_plan_validate(h) == -5
+    assert L.csb_upload(h, 256, 1 << 20, None) == -5
+    assert L.csb_spmv(h, 256, 256, None, None) == -5
+    assert L.csb_plan(h, -1, None) == -1
+    assert L.csb_plan(h, 0, None) == 0
+    assert L.csb_device_bytes(h) > 0
+    assert L.csb_upload(h, None, 1 << 20, None) == -1
+    assert L.csb_upload(h, 256, 16, None) == -2          # undersized device buffer
+    assert L.csb_upload(h, 257, 1 << 20, None) == -1      # misaligned
+    assert L.csb_spmv(h, None, 256, None, None) == -1
+    assert L.csb_spmv(h, 256, 256, None, None) == -5      # planned but not uploaded
+    assert L.csb_view_get(None, None) == -1 and L.csb_unpack(h, None, 4) == -1
+    r = C.c_void_p()
+    Wp = (C.c_void_p * 1)(h)
+    assert L.csb_rnn_create(0, 1, 2, 2, Wp, None, C.byref(r)) == -1      # 4x4 is not (4*2) x (2+2)
+    assert L.csb_rnn_create(7, 1, 2, 1, Wp, None, C.byref(r)) == -1      # unknown cell
+    assert L.csb_rnn_create(0, 0, 2, 1, Wp, None, C.byref(r)) == -1
+    assert L.csb_rnn_create(0, 1, 3, 1, Wp, None, C.byref(r)) == 0       # (4*1) x (3+1)
+    assert L.csb_rnn_forward(r, None, None, None, None, None, None, 1, 1, None, None) == -1
+    assert L.csb_rnn_forward(r, 256, None, None, None, 256, None, -1, 1, 256, None) == -1
+    assert L.csb_rnn_forward(r, 256, None, None, None, 256, None, 1, 0, 256, None) == -1
+    assert L.csb_rnn_forward(r, 256, None, None, None, 256, None, 1, 1, 256, None) == -5   # not uploaded
+    L.csb_rnn_free(r)
+    L.csb_free(h)
+    L.csb_free(None)
+    L.csb_rnn_free(None)
+
+
+@pytest.mark.parametrize("name,n_chunks", [("cfg1", 0), ("cfg2", 0), ("cfg2", 37), ("cfg3", 0), ("cfg3", 64)])
+def test_plan_partition_invariants(name, n_chunks):
+    cfg = csb_inputs.CONFIGS[name]
+    m = csb_inputs.make_rnn(cfg, T=1).W[0]
+    M = CsbMatrix(m.A, m.br, m.bc)
+    st = M.plan(n_chunks)
+    M.validate()         # every value referenced exactly once, all offsets in bounds, decodes back
+    assert st["n_chunks"] >= max(n_chunks, 1)
+    assert st["work_max"] >= st["work_mean"] > 0
+    assert 0 < st["lane_fill"] <= 1.0
+
+
+def test_plan_balance_on_skewed_matrix():
+    """The load-balance workload (kept fraction per block Beta-distributed): the largest
+    wavefront share stays within 10 % of the mean, where dealing whole blocks out without
+    splitting is far off (the analogue of the no-sharing case of Sec. 6.3.2)."""
+    m = csb_inputs.make_rnn(csb_inputs.CONFIGS["cfg3"], T=1).W[0]
+    M = CsbMatrix(m.A, m.br, m.bc)
+    st = M.plan(0)
+    assert st["work_max"] / st["work_mean"] <= 1.10
+    assert st["nosplit_max_over_mean"] > 1.2
