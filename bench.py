@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the CSB-RNN hot path on one MI355X.
+
+Headline workload (BASELINE "configs[1]"): single-layer LSTM, input 153, hidden 512
+(W 2048 x 665), CSB block 32 x 32, 10x pruning, batch 1, T = 100, synthetic, seed 0.
+One "step" is one csb_rnn_forward over the whole T-frame sequence (pack / plan / upload
+are done once, before the timed region, as the paper loads weights and instructions once
+before streaming frames, Sec. 6.1).  The metric is microseconds per timestep (lower is
+better) with the algorithmic GB/s beside it.
+
+Also reported on the same JSON line:
+  roofline      -- the dominant kernel of the headline workload
+  spmv_stress   -- csb_spmv on the 8192 x 8192 heavy-tailed matrix (the HBM-bound case),
+                   warm (matrix resident in the Infinity Cache) and cold (rotating over
+                   distinct device copies of the matrix, > 512 MB in total)
+  cpu_baseline  -- the CPU oracle timed on this machine's host cores on the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def spmv_alg_bytes(view, batch=1):
+    """Algorithmic bytes of one CSB mat-vec: values (f32), one byte per row/column index,
+    two count bytes per block, x read once, y written once."""
+    nb = int(view["nbr"]) * int(view["nbc"])
+    return (4 * int(view["nnz"]) + len(view["rowidx"]) + len(view["colidx"]) + 2 * nb
+            + 4 * int(view["cols"]) * batch + 4 * int(view["rows"]) * batch)
+
+
+def rnn_step_alg_bytes(views, cell, hidden, batch=1):
+    G = 4 if cell == 0 else 3
+    total = 0
+    for v in views:
+        total += spmv_alg_bytes(v, batch) + 4 * G * hidden + 8 * hidden * batch + 4 * hidden * batch
+    return total
+
+
+def time_region(fn, reps, torch):
+    """Milliseconds for `reps` calls of fn on the current stream, HIP events on that stream."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(reps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-stress", action="store_true", help="skip the 8192^2 SpMV stress leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+              "(no collectives, no sharding in this path)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import csb_inputs
+    from paper_2005_05758_amd import CsbMatrix, CsbRnn
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    cfg = csb_inputs.CONFIGS[args.workload]
+    wl = csb_inputs.make_rnn(cfg)
+    Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+    bias = [torch.from_numpy(b).cuda() for b in wl.bias]
+    rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, bias)
+    for w in Ws:
+        w.upload()
+    views = [w.view() for w in Ws]
+    xd = torch.from_numpy(wl.x).cuda()
+    T, B = cfg.T, cfg.batch
+
+    def step():
+        rnn.forward(xd, want_hseq=True)
+
+    for _ in range(args.warmup):
+        step()
+    ms = time_region(step, args.steps, torch)
+    ms_per_step = ms / args.steps
+    us_per_t = ms_per_step * 1000.0 / T
+    bytes_step = rnn_step_alg_bytes(views, cfg.cell, cfg.hidden, B)
+    gbps = bytes_step / (us_per_t * 1e-6) / 1e9
+
+    # dominant kernel of the headline workload: one mat-vec launch per layer and timestep
+    # (the element-wise gate kernel is far smaller); time it alone, back to back
+    m0 = wl.W[0]
+    M = CsbMatrix(m0.A, m0.br, m0.bc)
+    M.plan(0)
+    M.upload()
+    z = torch.from_numpy(csb_inputs.make_vectors(1, M.cols, 1)).cuda()
+    y = torch.empty(M.rows, dtype=torch.float32, device="cuda")
+    for _ in range(20):
+        M.spmv(z, y)
+    n = 2000
+    us_launch = time_region(lambda: M.spmv(z, y), n, torch) * 1000.0 / n
+    ab = spmv_alg_bytes(views[0])
+    ach = ab / (us_launch * 1e-6) / 1e9
+    roofline = {"kernel": "csb::spmv_kernel<16>", "bound": "hbm", "achieved": round(ach, 2),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 5),
+                "traffic": None, "us_per_launch": round(us_launch, 3), "alg_bytes_per_launch": ab,
+                "note": "weights re-read from cache every launch; launch/latency-bound at this size"}
+
+    out = {
+        "metric": "us_per_timestep_csb_lstm_batch1",
+        "value": round(us_per_t, 4),
+        "unit": "us/timestep",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {'LSTM' if cfg.cell == 0 else 'GRU'} {cfg.input}->{cfg.hidden} x{cfg.n_layers}, "
+                               f"W {wl.W[0].rows}x{wl.W[0].cols}, CSB block {cfg.block}, {cfg.rate:g}x pruning, "
+                               f"batch {B}, T={T}, seed {cfg.seed}",
+                   "timesteps_per_step": T, "alg_bytes_per_timestep": bytes_step},
+        "gbps_algorithmic": round(gbps, 3),
+        "pct_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBS, 4),
+        "roofline": roofline,
+    }
+
+    if not args.no_stress:
+        out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix)
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_leg(cfg, wl)
+    print(json.dumps(out))
+
+
+def stress_leg(torch, np, csb_inputs, CsbMatrix):
+    """csb_spmv on the 8192^2 heavy-tailed matrix: warm and cold, with the static balance."""
+    res = {}
+    for name in ("cfg5", "cfg5_diag"):
+        m = csb_inputs.make_mat(csb_inputs.CONFIGS[name])
+        M = CsbMatrix(m.A, m.br, m.bc)
+        st = M.plan(0)
+        M.upload()
+        v = M.view()
+        ab = spmv_alg_bytes(v)
+        x = torch.from_numpy(csb_inputs.make_vectors(5, m.cols, 1)).cuda()
+        y = torch.empty(m.rows, dtype=torch.float32, device="cuda")
+        for _ in range(10):
+            M.spmv(x, y)
+        n = 200
+        us_warm = time_region(lambda: M.spmv(x, y), n, torch) * 1000.0 / n
+        entry = {"nnz": int(v["nnz"]), "alg_bytes": ab, "us_warm": round(us_warm, 3),
+                 "gbps_warm": round(ab / us_warm / 1e3, 1),
+                 "static_max_over_mean": round(st["work_max"] / st["work_mean"], 4),
+                 "nosplit_max_over_mean": round(st["nosplit_max_over_mean"], 4),
+                 "lane_fill": round(st["lane_fill"], 4), "n_chunks": st["n_chunks"]}
+        if name == "cfg5":
+            # cold: rotate over distinct device copies so that every launch streams from HBM
+            copies = [M]
+            n_copies = 24
+            for _ in range(n_copies - 1):
+                c = CsbMatrix(m.A, m.br, m.bc)
+                c.plan(0)
+                c.upload()
+                copies.append(c)
+            for c in copies:
+                c.spmv(x, y)
+            state = {"i": 0}
+
+            def cold():
+                copies[state["i"] % n_copies].spmv(x, y)
+                state["i"] += 1
+            n = 5 * n_copies
+            us_cold = time_region(cold, n, torch) * 1000.0 / n
+            entry.update({"us_cold": round(us_cold, 3), "gbps_cold": round(ab / us_cold / 1e3, 1),
+                          "frac_hbm_cold": round(ab / us_cold / 1e3 / HBM_PEAK_GBS, 4),
+                          "cold_copies": n_copies, "cold_bytes_total": n_copies * M.device_bytes()})
+            del copies
+        res[name] = entry
+        del M
+    return res
+
+
+def cpu_leg(cfg, wl):
+    """The CPU oracle as it stands, on the host cores of this machine: float64 LSTM/GRU on the
+    decompressed dense matrix, whole T-frame sequences until about 10 s have passed."""
+    import oracle
+    W = [m.A for m in wl.W]
+    oracle.rnn_forward(cfg.cell, W, wl.bias, wl.x[:2], cfg.input, cfg.hidden)   # warm-up
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        oracle.rnn_forward(cfg.cell, W, wl.bias, wl.x, cfg.input, cfg.hidden)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt > 10.0 or reps >= 200:
+            break
+    us = dt / (reps * cfg.T) * 1e6
+    return {"value": round(us, 3), "unit": "us/timestep", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{reps} full sequences of T={cfg.T} (float64 dense masked mat-vec + gates, OpenMP over rows)"}
+
+
+if __name__ == "__main__":
+    main()

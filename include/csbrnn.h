@@ -83,6 +83,9 @@ typedef struct {
     double nosplit_max_over_mean; /* the same ratio when whole blocks are dealt out
                                 round-robin with no splitting (the "no sharing" baseline
                                 of Sec. 6.3.2), for context                             */
+    double chunk_max_over_mean;   /* largest / mean work per workgroup                   */
+    int32_t whole_tiles;     /* 1: every workgroup owns whole output row tiles (no merge) */
+    int32_t reserved;
 } csb_plan_stats;
 
 const char *csb_last_error(void);
@@ -116,6 +119,17 @@ int csb_unpack(const csb_matrix *m, float *dense, int64_t ld);
  */
 int csb_plan(csb_matrix *m, int32_t n_chunks, csb_plan_stats *stats);
 
+/*
+ * csb_plan with the partition mode spelled out.  mode 0: as csb_plan (whole tiles when
+ * there are at least as many row tiles with work as workgroups wanted, else equal split);
+ * mode 1: workgroups own whole output row tiles (contiguous tile ranges of nearly equal
+ * work; no cross-workgroup merge; CSB_EUNSUPPORTED if one tile exceeds a workgroup's LDS);
+ * mode 2: equal-work split at step granularity, tiles that straddle a cut are merged by
+ * the last workgroup to arrive.  Inside a workgroup both modes split the steps equally
+ * over the 16 wavefronts.
+ */
+int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *stats);
+
 /* Integer self-check of the planned device image: every offset in bounds, every kernel
  * value referenced exactly once, image decodes to the packed matrix.  Host only. */
 int csb_plan_validate(const csb_matrix *m);
@@ -142,6 +156,17 @@ size_t csb_workspace_bytes(const csb_matrix *m, int32_t batch);
  * CSB_EDEVICE.
  */
 int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws, void *stream);
+
+/*
+ * Instrumented csb_spmv for load-balance evidence (the role cycle-level simulation plays in
+ * Sec. 6.1): same result, and every workgroup also writes shader-clock stamps to d_stamps
+ * (device, csb_debug_stamp_count(m) values of 64 bits).  Per workgroup: 8 phase stamps
+ * (start, loads issued, staged in LDS, mat-vec done, tile sums written, end, 2 unused), then
+ * a begin/end pair for each of its 16 wavefronts around the wavefront's mat-vec share.
+ */
+size_t csb_debug_stamp_count(const csb_matrix *m);
+int csb_debug_spmv_stamps(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws,
+                          unsigned long long *d_stamps, void *stream);
 
 /*
  * Batched CSB-MVM: Y = A X for `batch` right-hand sides.  d_X is [cols][ldx] (entry

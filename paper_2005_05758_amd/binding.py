@@ -15,8 +15,9 @@ _LIB_PATH = os.path.join(_PKG, "libcsbrnn.so")
 _lib = None
 
 # every symbol include/csbrnn.h declares
-SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_plan", "csb_plan_validate",
+SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_plan", "csb_plan_ex", "csb_plan_validate",
            "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm",
+           "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_rnn_create", "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
 
 
@@ -40,7 +41,8 @@ class csb_view(C.Structure):
 class csb_plan_stats(C.Structure):
     _fields_ = [("n_chunks", C.c_int32), ("waves_per_chunk", C.c_int32), ("n_groups", C.c_int32),
                 ("n_shared_tiles", C.c_int32), ("work_max", C.c_double), ("work_mean", C.c_double),
-                ("lane_fill", C.c_double), ("nosplit_max_over_mean", C.c_double)]
+                ("lane_fill", C.c_double), ("nosplit_max_over_mean", C.c_double),
+                ("chunk_max_over_mean", C.c_double), ("whole_tiles", C.c_int32), ("reserved", C.c_int32)]
 
 
 def lib_path() -> str:
@@ -61,6 +63,7 @@ def load_library():
     L.csb_view_get.argtypes = [C.c_void_p, C.POINTER(csb_view)]
     L.csb_unpack.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
     L.csb_plan.argtypes = [C.c_void_p, C.c_int32, C.POINTER(csb_plan_stats)]
+    L.csb_plan_ex.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(csb_plan_stats)]
     L.csb_plan_validate.argtypes = [C.c_void_p]
     L.csb_device_bytes.argtypes = [C.c_void_p]
     L.csb_device_bytes.restype = C.c_size_t
@@ -68,6 +71,9 @@ def load_library():
     L.csb_workspace_bytes.argtypes = [C.c_void_p, C.c_int32]
     L.csb_workspace_bytes.restype = C.c_size_t
     L.csb_spmv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.csb_debug_stamp_count.argtypes = [C.c_void_p]
+    L.csb_debug_stamp_count.restype = C.c_size_t
+    L.csb_debug_spmv_stamps.argtypes = [C.c_void_p] * 6
     L.csb_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     L.csb_rnn_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
@@ -145,9 +151,9 @@ class CsbMatrix:
         _check(lib().csb_unpack(self._h, out.ctypes.data, self.cols))
         return out
 
-    def plan(self, n_chunks: int = 0):
+    def plan(self, n_chunks: int = 0, mode: int = 0):
         st = csb_plan_stats()
-        _check(lib().csb_plan(self._h, n_chunks, C.byref(st)))
+        _check(lib().csb_plan_ex(self._h, n_chunks, mode, C.byref(st)))
         self.stats = {k: getattr(st, k) for k, _ in csb_plan_stats._fields_}
         return self.stats
 
@@ -177,6 +183,17 @@ class CsbMatrix:
         ws = self._workspace(1, x.device)
         _check(lib().csb_spmv(self._h, _dptr(x), _dptr(y), _dptr(ws), _stream_ptr(stream)))
         return y
+
+    def spmv_stamps(self, x, y=None, stream=None):
+        """csb_debug_spmv_stamps: returns (y, stamps [n_chunks, 8 + 2*16] int64 tensor)."""
+        import torch
+        if y is None:
+            y = torch.empty(self.rows, dtype=torch.float32, device=x.device)
+        n = int(lib().csb_debug_stamp_count(self._h))
+        st = torch.zeros(n, dtype=torch.int64, device=x.device)
+        ws = self._workspace(1, x.device)
+        _check(lib().csb_debug_spmv_stamps(self._h, _dptr(x), _dptr(y), _dptr(ws), _dptr(st), _stream_ptr(stream)))
+        return y, st.view(-1, 8 + 2 * 16)
 
     def spmm(self, X, Y=None, stream=None):
         import torch

@@ -14,8 +14,11 @@ namespace csb {
 constexpr int kWave = 64;             // gfx950 wavefront width
 constexpr int kMaxVbPerGroup = 16;    // virtual blocks packed into one 64-lane group
 constexpr int kGroupOverhead = 8;     // per-group fixed cost in the work model (steps)
-constexpr int kAccRowsMax = 512;      // output-row slots one workgroup accumulates in LDS
-constexpr int kMaxStageCols = 24576;  // input vector floats staged in LDS (96 KB)
+constexpr int kAccRowsMax = 256;      // output-row slots one workgroup accumulates in LDS
+constexpr int kMaxStageCols = 20480;  // input vector floats staged in LDS (80 KB)
+constexpr int kChunkValsMax = 28672;  // floats of the value stream one workgroup keeps in LDS
+constexpr int kChunkMetaMax = 20480;  // bytes of group/block/index records per workgroup
+constexpr int kLdsBudget = 160 * 1024 - 2048;  // gfx950 LDS per workgroup, minus slack
 
 // ---- device image records (plain structs, identical on host and device) ----------
 
@@ -52,17 +55,26 @@ struct WaveRec {
     uint32_t g_begin, g_end;
     uint16_t j_begin, j_end;
     uint32_t val_begin;  // float offset inside group g_begin of step j_begin
+    uint32_t v_begin;    // absolute float index of the wavefront's first value
+    uint32_t v_end;      // one past its last value
+    uint32_t pad[2];
 };
-static_assert(sizeof(WaveRec) == 16, "WaveRec layout");
+static_assert(sizeof(WaveRec) == 32, "WaveRec layout");
 
 struct ChunkRec {
     uint32_t nzrank0;    // first non-empty tile rank the workgroup accumulates
     uint32_t ntiles;     // how many (LDS slots of br rows each)
     int32_t sid_first, part_first;  // shared-tile record / part of the first tile, or -1
     int32_t sid_last, part_last;    // same for the last tile (only if ntiles > 1), or -1
+    uint32_t g0, ng;     // groups the workgroup touches: [g0, g0 + ng)
+    uint32_t vb0, nvbs;  // their virtual-block records
+    uint32_t idx0;       // their index bytes: start, rounded down to 16
+    uint32_t idx_bytes;  // length from idx0, rounded up to 16
+    uint32_t v0;         // first value of the workgroup's window (float index, multiple of 4)
+    uint32_t nv4;        // window length in float4
     uint32_t pad[2];
 };
-static_assert(sizeof(ChunkRec) == 32, "ChunkRec layout");
+static_assert(sizeof(ChunkRec) == 64, "ChunkRec layout");
 
 struct SharedRec {
     uint32_t tile;         // output tile
@@ -77,7 +89,8 @@ struct DevHeader {
     uint32_t n_chunks, waves_per_chunk, n_groups, n_vbs;
     uint32_t n_shared, n_zero_tiles, n_nz_tiles, n_partial_slots;
     uint32_t br, bc;
-    uint32_t max_chunk_tiles, reserved0;
+    uint32_t max_chunk_tiles, chunk_vals_cap;  // LDS sizing: tiles per chunk, floats per chunk
+    uint32_t meta_cap, reserved0;              // bytes of records per chunk
     uint64_t rows_out, cols;
     uint64_t off_chunks, off_waves, off_groups, off_vbs, off_idx, off_vals;
     uint64_t off_nz_tiles, off_zero_tiles, off_shared, off_counters;
@@ -134,11 +147,14 @@ struct csb_matrix {
     csb::Plan plan;
     void *d_buf = nullptr;        // caller-owned device image, set by csb_upload
     bool uploaded = false;
+    // launch bookkeeping for the cross-workgroup merge (mutable: csb_spmv takes a const handle)
+    mutable uint32_t epoch = 0;          // tag generation in which ws_seen was cleared
+    mutable const void *ws_seen = nullptr;  // workspace already cleared for this matrix
 };
 
 namespace csb {
 int plan_matrix(csb_matrix *m, int32_t n_chunks, int32_t waves_per_chunk, const SplitSpec &split,
-                csb_plan_stats *stats);
+                csb_plan_stats *stats, int32_t mode);
 int validate_plan(const csb_matrix *m);
 DevMat dev_mat(const csb_matrix *m);
 }  // namespace csb

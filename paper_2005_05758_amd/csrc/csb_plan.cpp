@@ -43,11 +43,12 @@ uint32_t vals_before_step(const std::vector<Vb> &vb, const Group &g, int j) {
 }  // namespace
 
 int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, const SplitSpec &split,
-                csb_plan_stats *stats_out) {
+                csb_plan_stats *stats_out, int32_t mode) {
     if (!m) { set_error("csb_plan: NULL matrix"); return CSB_EINVAL; }
     if (n_chunks_req < 0) { set_error("csb_plan: n_chunks < 0"); return CSB_EINVAL; }
-    if (waves_per_chunk != 4 && waves_per_chunk != 8 && waves_per_chunk != 16) {
-        set_error("csb_plan: waves_per_chunk must be 4, 8 or 16");
+    if (mode < 0 || mode > 2) { set_error("csb_plan: mode must be 0 (auto), 1 (whole tiles) or 2 (equal split)"); return CSB_EINVAL; }
+    if (waves_per_chunk != 16) {
+        set_error("csb_plan: waves_per_chunk must be 16");
         return CSB_EINVAL;
     }
     if (m->val.size() >= (1ull << 32) || m->cols > (int64_t)65535 * m->bc) {
@@ -140,141 +141,12 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         }
         const uint32_t n_groups = (uint32_t)groups.size();
 
-        // ---- 3. cost axis, chunk and wave cuts -----------------------------------------
-        // Group g occupies [P[g], P[g+1]) with P[g+1]-P[g] = overhead + cmax; a cut inside
-        // the overhead part snaps to the group start.
-        std::vector<uint64_t> P(n_groups + 1, 0);
-        for (uint32_t g = 0; g < n_groups; ++g) P[g + 1] = P[g] + kGroupOverhead + groups[g].cmax;
-        const uint64_t total = P[n_groups];
-        int n_chunks = n_chunks_req;
-        if (n_chunks == 0) {
-            // default for one MI355X (256 CUs): two workgroups per CU once there is enough
-            // work for every wavefront to have a few groups, fewer for small matrices
-            const uint64_t per_wave_min = 4 * (kGroupOverhead + 8);
-            uint64_t want = total / (per_wave_min * (uint64_t)waves_per_chunk);
-            n_chunks = (int)std::min<uint64_t>(std::max<uint64_t>(want, 1), 512);
-        }
-        struct Pos { uint32_t g; uint32_t j; };
-        auto locate = [&](uint64_t X) -> Pos {
-            if (X >= total) return Pos{n_groups, 0};
-            uint32_t g = (uint32_t)(std::upper_bound(P.begin(), P.end(), X) - P.begin() - 1);
-            const uint64_t in = X - P[g];
-            if (in <= (uint64_t)kGroupOverhead) return Pos{g, 0};
-            return Pos{g, (uint32_t)(in - kGroupOverhead)};
-        };
-        const uint32_t max_tiles_per_chunk = (uint32_t)std::max(1, kAccRowsMax / br);
-        std::vector<uint64_t> chunk_cut;  // cost coordinates, chunk c = [cut[c], cut[c+1])
-        chunk_cut.push_back(0);
-        {
-            uint64_t X = 0;
-            int remaining = n_chunks;
-            while (X < total) {
-                if (remaining < 1) remaining = 1;
-                uint64_t target = (total - X + remaining - 1) / remaining;
-                uint64_t end = std::min(total, X + std::max<uint64_t>(target, 1));
-                // tile limit: walk groups from the first one touched
-                Pos a = locate(X);
-                uint32_t g = a.g;
-                uint32_t first_rank = g < n_groups ? tile_rank[groups[g].tile] : 0;
-                while (g < n_groups && P[g] < end) {
-                    if (tile_rank[groups[g].tile] - first_rank >= max_tiles_per_chunk) { end = P[g]; break; }
-                    ++g;
-                }
-                if (end <= X) end = std::min(total, P[a.g + 1]);  // always advance
-                chunk_cut.push_back(end);
-                X = end;
-                --remaining;
-            }
-            while ((int)chunk_cut.size() - 1 < n_chunks_req) chunk_cut.push_back(total);  // empty chunks
-        }
-        n_chunks = (int)chunk_cut.size() - 1;
-        if (n_chunks == 0) { chunk_cut.push_back(total); n_chunks = 1; }
-        const int NW = waves_per_chunk;
-        std::vector<WaveRec> waves((size_t)n_chunks * NW);
-        std::vector<ChunkRec> chunks(n_chunks);
-        std::vector<Pos> cpos_a(n_chunks), cpos_b(n_chunks);
-        std::vector<double> wave_cost(waves.size(), 0.0);
-        for (int c = 0; c < n_chunks; ++c) {
-            const uint64_t Xa = chunk_cut[c], Xb = chunk_cut[c + 1];
-            cpos_a[c] = locate(Xa);
-            cpos_b[c] = locate(Xb);
-            for (int w = 0; w < NW; ++w) {
-                const uint64_t xa = Xa + (Xb - Xa) * (uint64_t)w / NW;
-                const uint64_t xb = Xa + (Xb - Xa) * (uint64_t)(w + 1) / NW;
-                Pos a = locate(xa), b = locate(xb);
-                if (w == 0) a = cpos_a[c];
-                if (w == NW - 1) b = cpos_b[c];
-                WaveRec &wr = waves[(size_t)c * NW + w];
-                wr.g_begin = a.g; wr.j_begin = (uint16_t)a.j;
-                wr.g_end = b.g; wr.j_end = (uint16_t)b.j;
-                wr.val_begin = a.g < n_groups ? vals_before_step(vbs, groups[a.g], (int)a.j) : 0;
-                double cost = 0;
-                for (uint32_t g = a.g; g <= b.g && g < n_groups; ++g) {
-                    const int jlo = g == a.g ? (int)a.j : 0;
-                    const int jhi = g == b.g ? (int)b.j : groups[g].cmax;
-                    if (jhi > jlo) cost += kGroupOverhead + (jhi - jlo);
-                }
-                wave_cost[(size_t)c * NW + w] = cost;
-            }
-        }
-
-        // ---- 4. tiles per chunk, shared tiles -------------------------------------------
-        // touched groups of chunk c: [ga, gb] with gb included only if its j > 0
-        std::vector<int> tile_first_chunk(nz_tiles.size(), -1), tile_last_chunk(nz_tiles.size(), -1);
-        std::vector<int> c_rank0(n_chunks, 0), c_ntiles(n_chunks, 0);
-        for (int c = 0; c < n_chunks; ++c) {
-            uint32_t ga = cpos_a[c].g, gb = cpos_b[c].g;
-            if (cpos_b[c].j == 0) { if (gb == 0 || gb <= ga) { c_ntiles[c] = 0; continue; } --gb; }
-            if (ga >= n_groups) { c_ntiles[c] = 0; continue; }
-            // a chunk that starts at (ga, j) with j == cmax cannot happen: locate() keeps j < cmax
-            const uint32_t r0 = tile_rank[groups[ga].tile], r1 = tile_rank[groups[gb].tile];
-            c_rank0[c] = (int)r0;
-            c_ntiles[c] = (int)(r1 - r0 + 1);
-            for (uint32_t r = r0; r <= r1; ++r) {
-                if (tile_first_chunk[r] < 0) tile_first_chunk[r] = c;
-                tile_last_chunk[r] = c;
-            }
-        }
-        std::vector<SharedRec> shared;
-        std::vector<int> tile_sid(nz_tiles.size(), -1);
-        uint32_t n_partial_slots = 0;
-        for (size_t r = 0; r < nz_tiles.size(); ++r) {
-            if (tile_first_chunk[r] < 0) { set_error("csb_plan: internal: tile without a chunk"); return CSB_EINVAL; }
-            if (tile_last_chunk[r] > tile_first_chunk[r]) {
-                // chunks between first and last that touch no group at all do not exist on a
-                // contiguous axis, except empty trailing chunks; count only the touching ones
-                SharedRec s{};
-                s.tile = nz_tiles[r];
-                s.nparts = 0;
-                s.partial_off = n_partial_slots;
-                tile_sid[r] = (int)shared.size();
-                shared.push_back(s);
-            }
-        }
-        for (int c = 0; c < n_chunks; ++c) {
-            ChunkRec &cr = chunks[c];
-            cr = ChunkRec{};
-            cr.nzrank0 = (uint32_t)c_rank0[c];
-            cr.ntiles = (uint32_t)c_ntiles[c];
-            cr.sid_first = cr.part_first = cr.sid_last = cr.part_last = -1;
-            if (c_ntiles[c] == 0) continue;
-            const int rf = c_rank0[c], rl = c_rank0[c] + c_ntiles[c] - 1;
-            if (tile_sid[rf] >= 0) {
-                cr.sid_first = tile_sid[rf];
-                cr.part_first = (int32_t)shared[tile_sid[rf]].nparts++;
-            }
-            if (rl != rf && tile_sid[rl] >= 0) {
-                cr.sid_last = tile_sid[rl];
-                cr.part_last = (int32_t)shared[tile_sid[rl]].nparts++;
-            }
-        }
-        for (auto &s : shared) { s.partial_off = n_partial_slots; n_partial_slots += s.nparts; }
-
-        // ---- 5. streams -----------------------------------------------------------------
+        // ---- 3. streams (group order) ---------------------------------------------------
         std::vector<GroupRec> grecs(n_groups);
         std::vector<VbRec> vrecs;
         std::vector<uint8_t> idx;
         std::vector<float> vals;
+        std::vector<uint32_t> idx_end(n_groups);   // end of each group's index bytes
         vals.reserve(m->val.size());
         uint64_t fma_steps = 0;
         for (uint32_t gi = 0; gi < n_groups; ++gi) {
@@ -304,6 +176,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                 vrecs.push_back(vr);
                 lane0 += v.r();
             }
+            idx_end[gi] = (uint32_t)idx.size();
             // values, step-major
             for (int j = 0; j < g.cmax; ++j)
                 for (uint32_t k : g.vbs) {
@@ -318,6 +191,281 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         }
         if (vals.size() != m->val.size()) { set_error("csb_plan: internal: value count mismatch"); return CSB_EINVAL; }
 
+        // ---- 4. cost axis, chunk and wave cuts -----------------------------------------
+        // Group g occupies [P[g], P[g+1]) with P[g+1]-P[g] = overhead + cmax; a cut inside
+        // the overhead part snaps to the group start.
+        const int NW = waves_per_chunk;
+        std::vector<uint64_t> P(n_groups + 1, 0);
+        for (uint32_t g = 0; g < n_groups; ++g) P[g + 1] = P[g] + kGroupOverhead + groups[g].cmax;
+        const uint64_t total = P[n_groups];
+        // LDS sizing: input vector + per-wavefront value windows + records + accumulators
+        const uint32_t acc_rows_cap = (uint32_t)std::max(kAccRowsMax, br);
+        const size_t zbytes = align_up((size_t)m->cols, 64) * 4;
+        if (m->cols > kMaxStageCols) {
+            set_error("csb_plan: more columns than the LDS staging of the input vector covers");
+            return CSB_EUNSUPPORTED;
+        }
+        int n_chunks = n_chunks_req;
+        if (n_chunks == 0) {
+            // default: one workgroup per CU of an MI355X (256) once every wavefront has a few
+            // groups of work; more when the per-wavefront value window would overflow
+            const uint64_t per_wave_min = 5 * (kGroupOverhead + 8);
+            uint64_t want = total / (per_wave_min * (uint64_t)NW);
+            want = std::min<uint64_t>(std::max<uint64_t>(want, 1), 256);
+            n_chunks = (int)want;
+        }
+        struct Pos { uint32_t g; uint32_t j; };
+        auto locate = [&](uint64_t X) -> Pos {
+            if (X >= total) return Pos{n_groups, 0};
+            uint32_t g = (uint32_t)(std::upper_bound(P.begin(), P.end(), X) - P.begin() - 1);
+            const uint64_t in = X - P[g];
+            if (in <= (uint64_t)kGroupOverhead) return Pos{g, 0};
+            return Pos{g, (uint32_t)(in - kGroupOverhead)};
+        };
+        auto abs_val = [&](Pos p) -> uint32_t {
+            if (p.g >= n_groups) return (uint32_t)vals.size();
+            return grecs[p.g].val_off + vals_before_step(vbs, groups[p.g], (int)p.j);
+        };
+        const uint32_t max_tiles_per_chunk = (uint32_t)std::max<uint32_t>(1, acc_rows_cap / br);
+        std::vector<uint64_t> chunk_cut;
+        std::vector<WaveRec> waves;
+        std::vector<Pos> cpos_a, cpos_b;
+        std::vector<double> wave_cost;
+        // per non-empty tile: group range, cost, values, record bytes
+        const size_t n_nz = nz_tiles.size();
+        std::vector<uint32_t> tile_g0(n_nz + 1, n_groups);
+        for (uint32_t g = n_groups; g-- > 0;) tile_g0[tile_rank[groups[g].tile]] = g;
+        auto tile_vals = [&](size_t r) { return (r + 1 < n_nz ? grecs[tile_g0[r + 1]].val_off : (uint32_t)vals.size()) - grecs[tile_g0[r]].val_off; };
+        auto tile_meta = [&](size_t r) {
+            const uint32_t ga = tile_g0[r], gb = tile_g0[r + 1] - 1;
+            return (size_t)(gb - ga + 1) * sizeof(GroupRec) + (size_t)(grecs[gb].vb_off + grecs[gb].nvb - grecs[ga].vb_off) * sizeof(VbRec) +
+                   (idx_end[gb] - grecs[ga].idx_off) + 64;
+        };
+        auto lds_for = [&](size_t nvals, size_t meta, size_t ntile) {
+            return zbytes + (align_up(nvals + 8, 64) + 64) * 4 + align_up(meta, 256) + (size_t)NW * ntile * br * 4;
+        };
+        // Whole-tile chunks: contiguous tile ranges, smallest possible largest cost for at most
+        // n_target chunks.  No output tile is then shared between workgroups.
+        bool whole_tiles = false;
+        if (mode != 2 && n_nz > 0) {
+            const size_t n_target = (size_t)std::max(1, n_chunks);
+            auto fill_tiles = [&](uint64_t Tmax, std::vector<uint64_t> *cuts) -> long {
+                long used = 0;
+                size_t r = 0;
+                if (cuts) cuts->assign(1, 0);
+                while (r < n_nz) {
+                    ++used;
+                    uint64_t cost = 0;
+                    size_t nv = 0, mb = 0, nt = 0;
+                    while (r < n_nz) {
+                        const uint64_t tc = P[tile_g0[r + 1]] - P[tile_g0[r]];
+                        const size_t tv = tile_vals(r), tm = tile_meta(r);
+                        const bool fits = nt + 1 <= max_tiles_per_chunk && lds_for(nv + tv, mb + tm, nt + 1) <= (size_t)kLdsBudget &&
+                                          nv + tv + 8 <= (size_t)kChunkValsMax && mb + tm <= (size_t)kChunkMetaMax;
+                        if (nt == 0 && !fits) return -1;            // a single tile does not fit
+                        if (!fits || (nt > 0 && cost + tc > Tmax)) break;
+                        cost += tc; nv += tv; mb += tm; ++nt; ++r;
+                    }
+                    if (cuts) cuts->push_back(r < n_nz ? P[tile_g0[r]] : total);
+                }
+                return used;
+            };
+            if (fill_tiles(total, nullptr) > 0 && (mode == 1 || n_nz >= n_target)) {
+                uint64_t lo = 1, hi = total;
+                while (lo < hi) {
+                    const uint64_t mid = (lo + hi) / 2;
+                    if (fill_tiles(mid, nullptr) <= (long)n_target) hi = mid; else lo = mid + 1;
+                }
+                fill_tiles(lo, &chunk_cut);
+                whole_tiles = true;
+            } else if (mode == 1) {
+                set_error("csb_plan: a row tile does not fit one workgroup's LDS; whole-tile mode impossible");
+                return CSB_EUNSUPPORTED;
+            }
+        }
+        for (int attempt = 0;; ++attempt) {
+            if (attempt > 40) { set_error("csb_plan: internal: cannot fit the LDS windows"); return CSB_EINVAL; }
+            if (!whole_tiles) {
+            chunk_cut.assign(1, 0);
+            uint64_t X = 0;
+            int remaining = n_chunks;
+            while (X < total) {
+                if (remaining < 1) remaining = 1;
+                const uint64_t target = (total - X + remaining - 1) / remaining;
+                uint64_t end = std::min(total, X + std::max<uint64_t>(target, 1));
+                // limits: output tiles and record bytes; walk groups from the first one touched
+                const Pos a = locate(X);
+                uint32_t g = a.g;
+                const uint32_t first_rank = g < n_groups ? tile_rank[groups[g].tile] : 0;
+                size_t meta = 0;
+                while (g < n_groups && P[g] < end) {
+                    const size_t gmeta = sizeof(GroupRec) + (size_t)grecs[g].nvb * sizeof(VbRec) + (idx_end[g] - grecs[g].idx_off);
+                    if (tile_rank[groups[g].tile] - first_rank >= max_tiles_per_chunk ||
+                        (g > a.g && meta + gmeta + 64 > (size_t)kChunkMetaMax)) { end = P[g]; break; }
+                    meta += gmeta;
+                    ++g;
+                }
+                if (end <= X) end = std::min(total, P[a.g + 1]);  // always advance
+                chunk_cut.push_back(end);
+                X = end;
+                --remaining;
+            }
+            }
+            while ((int)chunk_cut.size() - 1 < std::max(n_chunks_req, 1)) chunk_cut.push_back(total);  // empty chunks
+            const int nc = (int)chunk_cut.size() - 1;
+            waves.assign((size_t)nc * NW, WaveRec{});
+            cpos_a.assign(nc, Pos{0, 0});
+            cpos_b.assign(nc, Pos{0, 0});
+            wave_cost.assign(waves.size(), 0.0);
+            uint32_t win_max = 0, tiles_max = 1;
+            size_t meta_max = 64;
+            for (int c = 0; c < nc; ++c) {
+                const uint64_t Xa = chunk_cut[c], Xb = chunk_cut[c + 1];
+                cpos_a[c] = locate(Xa);
+                cpos_b[c] = locate(Xb);
+                // Wavefront cuts inside the chunk: smallest share T such that a greedy fill
+                // (a wavefront that resumes inside a group pays the group overhead again)
+                // needs at most NW wavefronts.
+                const Pos ca = cpos_a[c], cb = cpos_b[c];
+                auto before = [&](Pos p, Pos q) { return p.g < q.g || (p.g == q.g && p.j < q.j); };
+                auto fill = [&](uint64_t T, std::vector<Pos> *cuts) -> bool {
+                    Pos p = ca;
+                    int used = 0;
+                    if (cuts) cuts->assign(1, ca);
+                    while (before(p, cb)) {
+                        if (++used > NW) return false;
+                        uint64_t budget = T;
+                        bool first = true;
+                        while (before(p, cb)) {
+                            const uint32_t lim = p.g == cb.g ? cb.j : (uint32_t)groups[p.g].cmax;
+                            if (budget <= (uint64_t)kGroupOverhead && !first) break;
+                            if (budget <= (uint64_t)kGroupOverhead) budget = kGroupOverhead + 1;   // always advance
+                            budget -= kGroupOverhead;
+                            const uint32_t rem = lim - p.j;
+                            if (rem <= budget) {
+                                budget -= rem;
+                                if (p.g == cb.g) p = cb; else p = Pos{p.g + 1, 0};
+                            } else {
+                                p.j += (uint32_t)budget;
+                                budget = 0;
+                            }
+                            first = false;
+                            if (budget == 0) break;
+                        }
+                        if (cuts) cuts->push_back(p);
+                    }
+                    return true;
+                };
+                uint64_t lo = 1, hi = std::max<uint64_t>(Xb - Xa, 1) + 2 * kGroupOverhead + 2;
+                while (lo < hi) {
+                    const uint64_t mid = (lo + hi) / 2;
+                    if (fill(mid, nullptr)) hi = mid; else lo = mid + 1;
+                }
+                std::vector<Pos> cuts;
+                fill(lo, &cuts);
+                while ((int)cuts.size() < NW + 1) cuts.push_back(cb);
+                for (int w = 0; w < NW; ++w) {
+                    const Pos a = cuts[w], b = cuts[w + 1];
+                    WaveRec &wr = waves[(size_t)c * NW + w];
+                    wr.g_begin = a.g; wr.j_begin = (uint16_t)a.j;
+                    wr.g_end = b.g; wr.j_end = (uint16_t)b.j;
+                    wr.val_begin = a.g < n_groups ? vals_before_step(vbs, groups[a.g], (int)a.j) : 0;
+                    wr.v_begin = abs_val(a);
+                    wr.v_end = abs_val(b);
+                    double cost = 0;
+                    for (uint32_t g = a.g; g <= b.g && g < n_groups; ++g) {
+                        const int jlo = g == a.g ? (int)a.j : 0;
+                        const int jhi = g == b.g ? (int)b.j : groups[g].cmax;
+                        if (jhi > jlo) cost += kGroupOverhead + (jhi - jlo);
+                    }
+                    wave_cost[(size_t)c * NW + w] = cost;
+                }
+                // record bytes and tiles of this chunk
+                {
+                    uint32_t ga = ca.g, gb = cb.g;
+                    bool any = true;
+                    if (cb.j == 0) { if (gb == 0 || gb <= ga) any = false; else --gb; }
+                    if (ga >= n_groups) any = false;
+                    if (any) {
+                        const uint32_t i0 = grecs[ga].idx_off & ~15u;
+                        const size_t mb = align_up((gb - ga + 1) * sizeof(GroupRec), 16) +
+                                          align_up((grecs[gb].vb_off + grecs[gb].nvb - grecs[ga].vb_off) * sizeof(VbRec), 16) +
+                                          align_up(idx_end[gb] - i0, 16);
+                        meta_max = std::max(meta_max, mb);
+                        win_max = std::max<uint32_t>(win_max, abs_val(cb) - (abs_val(ca) & ~3u));
+                        tiles_max = std::max<uint32_t>(tiles_max, tile_rank[groups[gb].tile] - tile_rank[groups[ga].tile] + 1);
+                    }
+                }
+            }
+            const size_t lds_need = lds_for(win_max, meta_max, tiles_max);
+            const bool fits = lds_need <= (size_t)kLdsBudget && win_max + 8 <= (uint32_t)kChunkValsMax;
+            if (fits) { n_chunks = nc; break; }
+            whole_tiles = false;
+            if (n_chunks_req == 0) n_chunks = nc < 256 ? std::min(256, nc * 2) : (nc / 256 + 1) * 256;   // whole rounds of 256 CUs
+            else n_chunks = std::max(nc, n_chunks) * 5 / 4 + 1;
+        }
+        std::vector<ChunkRec> chunks(n_chunks);
+
+        // ---- 5. tiles per chunk, shared tiles -------------------------------------------
+        // touched groups of chunk c: [ga, gb] with gb included only if its j > 0
+        std::vector<int> tile_first_chunk(nz_tiles.size(), -1), tile_last_chunk(nz_tiles.size(), -1);
+        std::vector<int> c_rank0(n_chunks, 0), c_ntiles(n_chunks, 0);
+        std::vector<uint32_t> c_ga(n_chunks, 0), c_gb(n_chunks, 0);
+        for (int c = 0; c < n_chunks; ++c) {
+            uint32_t ga = cpos_a[c].g, gb = cpos_b[c].g;
+            if (cpos_b[c].j == 0) { if (gb == 0 || gb <= ga) { c_ntiles[c] = 0; continue; } --gb; }
+            if (ga >= n_groups) { c_ntiles[c] = 0; continue; }
+            const uint32_t r0 = tile_rank[groups[ga].tile], r1 = tile_rank[groups[gb].tile];
+            c_rank0[c] = (int)r0;
+            c_ntiles[c] = (int)(r1 - r0 + 1);
+            c_ga[c] = ga; c_gb[c] = gb;
+            for (uint32_t r = r0; r <= r1; ++r) {
+                if (tile_first_chunk[r] < 0) tile_first_chunk[r] = c;
+                tile_last_chunk[r] = c;
+            }
+        }
+        std::vector<SharedRec> shared;
+        std::vector<int> tile_sid(nz_tiles.size(), -1);
+        uint32_t n_partial_slots = 0;
+        for (size_t r = 0; r < nz_tiles.size(); ++r) {
+            if (tile_first_chunk[r] < 0) { set_error("csb_plan: internal: tile without a chunk"); return CSB_EINVAL; }
+            if (tile_last_chunk[r] > tile_first_chunk[r]) {
+                SharedRec s{};
+                s.tile = nz_tiles[r];
+                tile_sid[r] = (int)shared.size();
+                shared.push_back(s);
+            }
+        }
+        uint32_t meta_cap = 64;
+        for (int c = 0; c < n_chunks; ++c) {
+            ChunkRec &cr = chunks[c];
+            cr = ChunkRec{};
+            cr.nzrank0 = (uint32_t)c_rank0[c];
+            cr.ntiles = (uint32_t)c_ntiles[c];
+            cr.sid_first = cr.part_first = cr.sid_last = cr.part_last = -1;
+            if (c_ntiles[c] == 0) continue;
+            const int rf = c_rank0[c], rl = c_rank0[c] + c_ntiles[c] - 1;
+            if (tile_sid[rf] >= 0) {
+                cr.sid_first = tile_sid[rf];
+                cr.part_first = (int32_t)shared[tile_sid[rf]].nparts++;
+            }
+            if (rl != rf && tile_sid[rl] >= 0) {
+                cr.sid_last = tile_sid[rl];
+                cr.part_last = (int32_t)shared[tile_sid[rl]].nparts++;
+            }
+            const uint32_t ga = c_ga[c], gb = c_gb[c];
+            cr.g0 = ga; cr.ng = gb - ga + 1;
+            cr.vb0 = grecs[ga].vb_off; cr.nvbs = grecs[gb].vb_off + grecs[gb].nvb - cr.vb0;
+            cr.idx0 = grecs[ga].idx_off & ~15u;
+            cr.idx_bytes = (uint32_t)align_up(idx_end[gb] - cr.idx0, 16);
+            cr.v0 = abs_val(cpos_a[c]) & ~3u;
+            cr.nv4 = (abs_val(cpos_b[c]) - cr.v0 + 3u) >> 2;
+            const uint32_t mb = (uint32_t)(align_up(cr.ng * sizeof(GroupRec), 16) + align_up(cr.nvbs * sizeof(VbRec), 16) + cr.idx_bytes);
+            meta_cap = std::max(meta_cap, mb);
+        }
+        if (meta_cap > (uint32_t)kChunkMetaMax + 4096) { set_error("csb_plan: internal: record window overflow"); return CSB_EINVAL; }
+        for (auto &s : shared) { s.partial_off = n_partial_slots; n_partial_slots += s.nparts; }
+
         // ---- 6. image -------------------------------------------------------------------
         DevHeader h{};
         h.magic = 0x4353424d49333535ull;  // "CSBMI355"
@@ -326,6 +474,12 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         h.n_shared = (uint32_t)shared.size(); h.n_zero_tiles = (uint32_t)zero_tiles.size();
         h.n_nz_tiles = (uint32_t)nz_tiles.size(); h.n_partial_slots = n_partial_slots;
         h.max_chunk_tiles = 1;
+        {
+            uint32_t wmax = 16;
+            for (const ChunkRec &cr : chunks) wmax = std::max(wmax, cr.nv4);
+            h.chunk_vals_cap = (uint32_t)align_up((size_t)wmax * 4, 64);   // floats the kernel reserves
+        }
+        h.meta_cap = (uint32_t)align_up(meta_cap, 256);
         for (const ChunkRec &cr : chunks) h.max_chunk_tiles = std::max(h.max_chunk_tiles, cr.ntiles);
         h.br = (uint32_t)br; h.bc = (uint32_t)bc; h.rows_out = (uint64_t)rows_out; h.cols = (uint64_t)m->cols;
         size_t off = align_up(sizeof(DevHeader), 256);
@@ -369,6 +523,16 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         for (double c : wave_cost) { wmax = std::max(wmax, c); wsum += c; }
         st.work_max = wmax;
         st.work_mean = wave_cost.empty() ? 0 : wsum / (double)wave_cost.size();
+        {
+            double cmax_ = 0, csum_ = 0;
+            for (int c = 0; c < n_chunks; ++c) {
+                double cc = 0;
+                for (int w = 0; w < NW; ++w) cc += wave_cost[(size_t)c * NW + w];
+                cmax_ = std::max(cmax_, cc); csum_ += cc;
+            }
+            st.chunk_max_over_mean = csum_ > 0 ? cmax_ / (csum_ / n_chunks) : 0.0;
+            st.whole_tiles = whole_tiles ? 1 : 0;
+        }
         st.lane_fill = fma_steps ? (double)m->val.size() / (64.0 * (double)fma_steps) : 0.0;
         {
             const size_t nwt = wave_cost.size();
@@ -435,11 +599,19 @@ int validate_plan(const csb_matrix *m) {
     uint64_t vals_used = 0;
     for (uint32_t c = 0; c < h.n_chunks; ++c) {
         const ChunkRec &cr = chunks[c];
-        if (cr.ntiles * br > (uint32_t)kAccRowsMax && cr.ntiles > 1) return fail("chunk tile span");
+        if (cr.ntiles * br > (uint32_t)std::max<int>(kAccRowsMax, (int)br)) return fail("chunk tile span");
+        if (4 * (uint64_t)cr.nv4 > h.chunk_vals_cap || (cr.v0 & 3u) || (uint64_t)cr.v0 + 4 * (uint64_t)cr.nv4 > h.n_vals + 16) return fail("chunk value window");
+        if ((uint64_t)cr.g0 + cr.ng > h.n_groups || (uint64_t)cr.vb0 + cr.nvbs > h.n_vbs ||
+            (uint64_t)cr.idx0 + cr.idx_bytes > h.idx_bytes + 64) return fail("chunk record window");
+        if (align_up(cr.ng * sizeof(GroupRec), 16) + align_up(cr.nvbs * sizeof(VbRec), 16) + cr.idx_bytes > h.meta_cap)
+            return fail("chunk record window larger than its LDS space");
         if (cr.nzrank0 + cr.ntiles > h.n_nz_tiles) return fail("chunk tile rank");
         for (uint32_t w = 0; w < NW; ++w) {
             const WaveRec &wr = waves[(size_t)c * NW + w];
             if (wr.g_begin > h.n_groups || wr.g_end > h.n_groups || wr.g_begin > wr.g_end) return fail("wave range");
+            if (wr.v_begin > wr.v_end || wr.v_end > h.n_vals) return fail("wave value range");
+            if (wr.v_begin < wr.v_end && (wr.v_begin < cr.v0 || wr.v_end > cr.v0 + 4 * cr.nv4)) return fail("wave values outside the chunk window");
+            if (wr.g_begin < h.n_groups && wr.v_begin != groups[wr.g_begin].val_off + wr.val_begin) return fail("wave v_begin");
             for (uint32_t g = wr.g_begin; g <= wr.g_end && g < h.n_groups; ++g) {
                 const GroupRec &gr = groups[g];
                 const int jlo = g == wr.g_begin ? wr.j_begin : 0;
@@ -448,6 +620,9 @@ int validate_plan(const csb_matrix *m) {
                 if (jhi > gr.cmax) return fail("wave step range");
                 if (gr.nzrank < cr.nzrank0 || gr.nzrank >= cr.nzrank0 + cr.ntiles) return fail("group tile outside chunk");
                 if (gr.nlanes > kWave || gr.nvb > kMaxVbPerGroup) return fail("group size");
+                if (g < cr.g0 || g >= cr.g0 + cr.ng) return fail("group outside the chunk's record window");
+                if (gr.vb_off < cr.vb0 || gr.vb_off + gr.nvb > cr.vb0 + cr.nvbs) return fail("vb outside the chunk's record window");
+                if (gr.idx_off < cr.idx0) return fail("index bytes before the chunk's window");
                 if ((uint64_t)gr.vb_off + gr.nvb > h.n_vbs) return fail("vb range");
                 const uint32_t tile = nz_tiles[gr.nzrank];
                 const uint32_t tile_h = (uint32_t)std::min<int64_t>(br, rows_out - (int64_t)tile * br);
@@ -469,12 +644,13 @@ int validate_plan(const csb_matrix *m) {
                         if (j >= v.c) continue;
                         if ((uint32_t)lane != n_active) return fail("active lanes are not a prefix");
                         const size_t ia = col_base + 4 * (size_t)v.coloff4 + j;
-                        if (ia >= h.idx_bytes) return fail("column index offset");
+                        if (ia >= h.idx_bytes || ia >= (size_t)cr.idx0 + cr.idx_bytes) return fail("column index offset");
                         const uint32_t col = idx[ia];
                         const int64_t gc = (int64_t)v.bj * bc + col;
                         if (col >= bc || gc >= cols) return fail("column index");
                         const uint64_t va = (uint64_t)gr.val_off + off + n_active;
                         if (va >= h.n_vals || off + n_active >= gr.nvals) return fail("value offset");
+                        if (va < wr.v_begin || va >= wr.v_end) return fail("value outside the wave's window");
                         const size_t cell = (size_t)((int64_t)tile * br + slot) * cols + gc;
                         if (seen[cell]) return fail("entry referenced twice");
                         seen[cell] = 1;
@@ -520,7 +696,11 @@ int validate_plan(const csb_matrix *m) {
 }  // namespace csb
 
 extern "C" int csb_plan(csb_matrix *m, int32_t n_chunks, csb_plan_stats *stats) {
-    return csb::plan_matrix(m, n_chunks, 16, csb::SplitSpec{}, stats);
+    return csb::plan_matrix(m, n_chunks, 16, csb::SplitSpec{}, stats, 0);
+}
+
+extern "C" int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *stats) {
+    return csb::plan_matrix(m, n_chunks, 16, csb::SplitSpec{}, stats, mode);
 }
 
 extern "C" int csb_plan_validate(const csb_matrix *m) { return csb::validate_plan(m); }
@@ -531,5 +711,6 @@ extern "C" size_t csb_device_bytes(const csb_matrix *m) {
 
 extern "C" size_t csb_workspace_bytes(const csb_matrix *m, int32_t batch) {
     if (!m || !m->plan.valid || batch <= 0) return 0;
-    return (size_t)m->plan.hdr.n_partial_slots * m->plan.hdr.br * sizeof(float) * (size_t)batch;
+    // one 64-bit word (value, launch tag) per row of every partial tile sum
+    return (size_t)m->plan.hdr.n_partial_slots * m->plan.hdr.br * 8 * (size_t)batch;
 }

@@ -108,7 +108,7 @@ extern "C" int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int
             SplitSpec sp{};
             if (cell == CSB_CELL_GRU) { sp.split_row = 2 * (int64_t)hidden; sp.split_col = l == 0 ? input : hidden; sp.shift = hidden; }
             if (!W[l]->plan.valid || !(W[l]->plan.split == sp)) {
-                int rc = plan_matrix(W[l], 0, 16, sp, nullptr);
+                int rc = plan_matrix(W[l], 0, 16, sp, nullptr, 0);
                 if (rc != CSB_OK) { delete r; return rc; }
             }
             r->W.push_back(W[l]);

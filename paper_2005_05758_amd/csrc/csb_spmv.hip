@@ -10,6 +10,8 @@
 // last workgroup to arrive, again in a fixed order, so results are bitwise reproducible.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "csb_internal.hpp"
 #include "csb_kernels.hpp"
 
@@ -39,149 +41,311 @@ DevMat dev_mat(const csb_matrix *m) {
 
 __device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// The wavefront's share of the mat-vec: accumulates into myacc[(tile slot) * br + row slot].
-__device__ __forceinline__ void wave_groups(const DevMat &m, const WaveRec wr, const uint32_t nzrank0,
+// LDS map of one workgroup (byte offsets from the start of dynamic LDS).
+struct LdsMap {
+    uint32_t zpad;        // floats of the staged input vector
+    uint32_t vw;          // floats of the workgroup's value window
+    uint32_t meta_off;    // bytes: group records | block records | index bytes
+    uint32_t acc_off;     // bytes: [NW][acc_rows] accumulators
+};
+
+// The wavefront's share of the mat-vec, everything read from LDS: accumulates into
+// myacc[(tile slot) * br + row slot].
+__device__ __forceinline__ void wave_groups(const DevMat &m, const ChunkRec &cr, const WaveRec &wr,
+                                            const uint8_t *meta, const float *wv,
                                             const float *z, float *myacc, const int lane) {
-    const uint32_t g_begin = uni(wr.g_begin), g_end = uni(wr.g_end);
+    const uint32_t goff = 0, voff = (cr.ng * (uint32_t)sizeof(GroupRec) + 15u) & ~15u;
+    const uint32_t ioff = voff + ((cr.nvbs * (uint32_t)sizeof(VbRec) + 15u) & ~15u);
+    const GroupRec *lg = (const GroupRec *)(meta + goff);
+    const VbRec *lv = (const VbRec *)(meta + voff);
+    const uint8_t *lidx = meta + ioff;
+    const uint32_t g_begin = wr.g_begin, g_end = wr.g_end;
     for (uint32_t g = g_begin; g <= g_end && g < m.n_groups; ++g) {
-        const GroupRec *gp = m.groups + g;
-        const uint32_t cmax = uni(gp->cmax), nvb = uni(gp->nvb), nlanes = uni(gp->nlanes);
-        const uint32_t jlo = g == g_begin ? uni(wr.j_begin) : 0u;
-        const uint32_t jhi = g == g_end ? uni(wr.j_end) : cmax;
+        const GroupRec *gp = lg + (g - cr.g0);
+        const uint32_t cmax = uni(gp->cmax);
+        const uint32_t jlo = g == g_begin ? (uint32_t)wr.j_begin : 0u;
+        const uint32_t jhi = g == g_end ? (uint32_t)wr.j_end : cmax;
         if (jhi <= jlo) continue;
-        const uint32_t idx_off = uni(gp->idx_off), vb_off = uni(gp->vb_off);
-        const float *gv = m.vals + uni(gp->val_off) + (g == g_begin ? uni(wr.val_begin) : 0u);
+        const uint32_t nvb = uni(gp->nvb), nlanes = uni(gp->nlanes);
+        const uint32_t ib = uni(gp->idx_off) - cr.idx0, vb = uni(gp->vb_off) - cr.vb0;
+        const float *gv = wv + (uni(gp->val_off) + (g == g_begin ? wr.val_begin : 0u) - cr.v0);
         const bool act = (uint32_t)lane < nlanes;
         uint32_t slot = 0, k = 0xffffffffu, c_lane = 0, zb = 0;
-        const uint8_t *colp = m.idx;
+        const uint32_t *colp = (const uint32_t *)lidx;
         if (act) {
-            const uint32_t d = *(const uint16_t *)(m.idx + idx_off + 2 * lane);
+            const uint32_t d = *(const uint16_t *)(lidx + ib + 2 * lane);
             slot = d & 0xffu;
             k = d >> 8;
-            const VbRec v = m.vbs[vb_off + k];
+            const VbRec v = lv[vb + k];
             c_lane = v.c;
             zb = (uint32_t)v.bj * m.bc;
-            colp = m.idx + idx_off + ((2 * nlanes + 3) & ~3u) + 4u * v.coloff4;
+            colp = (const uint32_t *)(lidx + ib + ((2 * nlanes + 3) & ~3u)) + v.coloff4;
         }
+        const uint32_t jend = min(jhi, c_lane);
         float a = 0.0f;
         uint32_t off = 0;
-        for (uint32_t j = jlo; j < jhi; ++j) {
-            const bool on = j < c_lane;
-            if (on) {
-                const float w = gv[off + lane];
-                const uint32_t col = colp[j];
-                a = fmaf(w, z[zb + col], a);
+        // 32 column steps per pass; per 4 steps all LDS reads are issued before the first
+        // multiply-add.  Reads of lanes that sit out a step stay in bounds (the value window
+        // has 64 floats of slack, a zero index byte points at the block's first input) and
+        // their products are dropped.
+        for (uint32_t seg = jlo & ~31u; seg < jhi; seg += 32) {
+            uint32_t cw[8];
+#pragma unroll
+            for (int d = 0; d < 8; ++d) cw[d] = seg + 4 * d < jend ? colp[(seg >> 2) + d] : 0u;
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                if (seg + 4 * d >= jhi) break;
+                bool on[4];
+                float w[4], zz[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t j = seg + 4 * d + u;
+                    on[u] = j >= jlo && j < jend;
+                    w[u] = gv[off + lane];
+                    zz[u] = z[zb + ((cw[d] >> (8 * u)) & 0xffu)];
+                    off += (uint32_t)__popcll(__ballot(on[u]));
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) a = on[u] ? fmaf(w[u], zz[u], a) : a;
             }
-            off += (uint32_t)__popcll(__ballot(on));
         }
         // Row results into the wavefront's accumulator.  Lanes of different virtual blocks
         // may target the same row, so the blocks go one after another; a wavefront's LDS
         // operations execute in program order, which fixes the order of the sum.
-        const uint32_t rs = (uni(gp->nzrank) - nzrank0) * m.br + slot;
+        const uint32_t rs = (uni(gp->nzrank) - cr.nzrank0) * m.br + slot;
         for (uint32_t kk = 0; kk < nvb; ++kk) {
             if (k == kk) __hip_atomic_fetch_add(&myacc[rs], a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
         }
     }
 }
 
-template <int NW>
-__global__ __launch_bounds__(NW * 64) void spmv_kernel(const DevMat m, const float *__restrict__ x0,
-                                                        const uint32_t n0, const float *__restrict__ x1,
-                                                        float *__restrict__ y, float *__restrict__ partials,
-                                                        const uint32_t zpad) {
-    extern __shared__ float smem[];
-    __shared__ uint32_t s_last;
-    float *z = smem;            // [zpad] input vector
-    float *acc = smem + zpad;   // [NW][ntiles * br]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t c = blockIdx.x;
-    constexpr int NT = NW * 64;
+// Uniform copies of the records (every field through a scalar register).
+__device__ __forceinline__ ChunkRec load_chunk(const ChunkRec *p) {
+    ChunkRec c;
+    c.nzrank0 = uni(p->nzrank0); c.ntiles = uni(p->ntiles);
+    c.sid_first = (int32_t)uni((uint32_t)p->sid_first); c.part_first = (int32_t)uni((uint32_t)p->part_first);
+    c.sid_last = (int32_t)uni((uint32_t)p->sid_last); c.part_last = (int32_t)uni((uint32_t)p->part_last);
+    c.g0 = uni(p->g0); c.ng = uni(p->ng); c.vb0 = uni(p->vb0); c.nvbs = uni(p->nvbs);
+    c.idx0 = uni(p->idx0); c.idx_bytes = uni(p->idx_bytes); c.v0 = uni(p->v0); c.nv4 = uni(p->nv4);
+    c.pad[0] = c.pad[1] = 0;
+    return c;
+}
 
-    for (uint32_t i = tid; i < m.cols; i += NT) z[i] = i < n0 ? x0[i] : x1[i - n0];
-    const ChunkRec cr = m.chunks[c];
+__device__ __forceinline__ WaveRec load_wave(const WaveRec *p) {
+    WaveRec w;
+    w.g_begin = uni(p->g_begin); w.g_end = uni(p->g_end);
+    w.j_begin = (uint16_t)uni(p->j_begin); w.j_end = (uint16_t)uni(p->j_end);
+    w.val_begin = uni(p->val_begin); w.v_begin = uni(p->v_begin); w.v_end = uni(p->v_end);
+    w.pad[0] = w.pad[1] = 0;
+    return w;
+}
+
+constexpr int kSpmvWaves = 16;
+constexpr int kSpmvThreads = kSpmvWaves * 64;
+constexpr int kStampsPerChunk = 8 + 2 * kSpmvWaves;
+
+// A guarded load into a named register (arrays of these end up in scratch memory).
+#define CSB_LD4(name, src, idx, n) \
+    float4 name = make_float4(0.f, 0.f, 0.f, 0.f); \
+    { const uint32_t i_ = (idx); if (i_ < (n)) name = (src)[i_]; }
+#define CSB_LD2(name, src, idx, n) \
+    uint2 name = make_uint2(0u, 0u); \
+    { const uint32_t i_ = (idx); if (i_ < (n)) name = (src)[i_]; }
+#define CSB_ST(dst, idx, n, name) \
+    { const uint32_t i_ = (idx); if (i_ < (n)) (dst)[i_] = name; }
+
+__global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, const float *__restrict__ x0,
+                                                             const uint32_t n0, const float *__restrict__ x1,
+                                                             float *__restrict__ y, unsigned long long *__restrict__ partials,
+                                                             const uint32_t epoch, const LdsMap L,
+                                                             unsigned long long *__restrict__ stamps) {
+    extern __shared__ float4 smem4[];
+    __shared__ uint32_t s_last;
+    uint8_t *smem = (uint8_t *)smem4;
+    float *z = (float *)smem;                          // [zpad] input vector
+    float *vals_lds = z + L.zpad;                      // [vw] the chunk's run of the value stream
+    uint8_t *meta = smem + L.meta_off;
+    float *acc = (float *)(smem + L.acc_off);          // [NW][ntiles * br]
+    constexpr int NW = kSpmvWaves, NT = kSpmvThreads;
+    const uint32_t tid = threadIdx.x;
+    const int lane = tid & 63, wave = (int)uni(tid >> 6);
+    const uint32_t c = blockIdx.x;
+    static_assert(kChunkValsMax / 4 <= 7 * NT, "value window loads");
+    static_assert(kMaxStageCols / 4 <= 5 * NT, "input vector loads");
+    static_assert((kChunkMetaMax + 4096) / 8 <= 3 * NT, "record loads");
+
+    // optional clock stamps (debug): per workgroup 8 phase stamps, then begin/end per wavefront
+    unsigned long long *st = stamps ? stamps + (size_t)c * kStampsPerChunk : nullptr;
+    if (st && tid == 0) st[0] = __builtin_readcyclecounter();
+
+    // ---- issue every global load of the workgroup before waiting for any ---------------
+    const ChunkRec cr = load_chunk(m.chunks + c);
+    const WaveRec wr = load_wave(m.waves + (size_t)c * NW + wave);
+    const uint32_t n4 = cr.nv4;
+    const float4 *gsrc = (const float4 *)(m.vals + cr.v0);
+    CSB_LD4(rv0, gsrc, tid, n4) CSB_LD4(rv1, gsrc, tid + NT, n4) CSB_LD4(rv2, gsrc, tid + 2 * NT, n4)
+    CSB_LD4(rv3, gsrc, tid + 3 * NT, n4) CSB_LD4(rv4, gsrc, tid + 4 * NT, n4) CSB_LD4(rv5, gsrc, tid + 5 * NT, n4)
+    CSB_LD4(rv6, gsrc, tid + 6 * NT, n4)
+    // records: groups and virtual blocks in 8-byte units, index bytes in 16-byte units
+    const uint32_t gu = cr.ng * 3u, vu = cr.nvbs, iu = cr.idx_bytes >> 4;
+    const uint32_t voff = (cr.ng * (uint32_t)sizeof(GroupRec) + 15u) & ~15u;
+    const uint32_t ioff = voff + ((cr.nvbs * (uint32_t)sizeof(VbRec) + 15u) & ~15u);
+    const uint2 *gsrc8 = (const uint2 *)(m.groups + cr.g0);
+    const uint2 *vsrc8 = (const uint2 *)(m.vbs + cr.vb0);
+    const float4 *isrc = (const float4 *)(m.idx + cr.idx0);
+    CSB_LD2(rg0, gsrc8, tid, gu) CSB_LD2(rg1, gsrc8, tid + NT, gu) CSB_LD2(rg2, gsrc8, tid + 2 * NT, gu)
+    CSB_LD2(rb0, vsrc8, tid, vu) CSB_LD2(rb1, vsrc8, tid + NT, vu) CSB_LD2(rb2, vsrc8, tid + 2 * NT, vu)
+    CSB_LD4(ri0, isrc, tid, iu) CSB_LD4(ri1, isrc, tid + NT, iu)
+    // input vector: aligned single-source fast path, else element-wise from two sources
+    const bool zfast = n0 >= m.cols && (m.cols & 3u) == 0 && ((uintptr_t)x0 & 15u) == 0;
+    const uint32_t z4 = zfast ? (m.cols >> 2) : 0u;
+    const float4 *zsrc = (const float4 *)x0;
+    CSB_LD4(rz0, zsrc, tid, z4) CSB_LD4(rz1, zsrc, tid + NT, z4) CSB_LD4(rz2, zsrc, tid + 2 * NT, z4)
+    CSB_LD4(rz3, zsrc, tid + 3 * NT, z4) CSB_LD4(rz4, zsrc, tid + 4 * NT, z4)
+    if (!zfast)
+        for (uint32_t i = tid; i < m.cols; i += NT) z[i] = i < n0 ? x0[i] : x1[i - n0];
+
+    if (st && tid == 0) st[1] = __builtin_readcyclecounter();
+    // ---- independent work while the loads fly -------------------------------------------
     const uint32_t arows = cr.ntiles * m.br;
     for (uint32_t i = tid; i < NW * arows; i += NT) acc[i] = 0.0f;
-    // output tiles nobody has work for
-    for (uint32_t q = c; q < m.n_zero_tiles; q += m.n_chunks) {
+    for (uint32_t q = c; q < m.n_zero_tiles; q += m.n_chunks) {   // output tiles nobody has work for
         const uint32_t r0 = m.zero_tiles[q] * m.br;
         for (uint32_t i = tid; i < m.br; i += NT)
             if (r0 + i < m.rows_out) y[r0 + i] = 0.0f;
     }
-    __syncthreads();
 
-    wave_groups(m, m.waves[(size_t)c * NW + wave], cr.nzrank0, z, acc + wave * arows, lane);
+    // ---- commit to LDS ------------------------------------------------------------------
+    {
+        float4 *vd = (float4 *)vals_lds;
+        CSB_ST(vd, tid, n4, rv0) CSB_ST(vd, tid + NT, n4, rv1) CSB_ST(vd, tid + 2 * NT, n4, rv2)
+        CSB_ST(vd, tid + 3 * NT, n4, rv3) CSB_ST(vd, tid + 4 * NT, n4, rv4) CSB_ST(vd, tid + 5 * NT, n4, rv5)
+        CSB_ST(vd, tid + 6 * NT, n4, rv6)
+        uint2 *gd = (uint2 *)meta, *bd = (uint2 *)(meta + voff);
+        CSB_ST(gd, tid, gu, rg0) CSB_ST(gd, tid + NT, gu, rg1) CSB_ST(gd, tid + 2 * NT, gu, rg2)
+        CSB_ST(bd, tid, vu, rb0) CSB_ST(bd, tid + NT, vu, rb1) CSB_ST(bd, tid + 2 * NT, vu, rb2)
+        float4 *id = (float4 *)(meta + ioff);
+        CSB_ST(id, tid, iu, ri0) CSB_ST(id, tid + NT, iu, ri1)
+        float4 *zd = (float4 *)z;
+        CSB_ST(zd, tid, z4, rz0) CSB_ST(zd, tid + NT, z4, rz1) CSB_ST(zd, tid + 2 * NT, z4, rz2)
+        CSB_ST(zd, tid + 3 * NT, z4, rz3) CSB_ST(zd, tid + 4 * NT, z4, rz4)
+    }
     __syncthreads();
+    if (st && tid == 0) st[2] = __builtin_readcyclecounter();
+    if (st && lane == 0) st[8 + 2 * wave] = __builtin_readcyclecounter();
+    wave_groups(m, cr, wr, meta, vals_lds, z, acc + wave * arows, lane);
+    if (st && lane == 0) st[9 + 2 * wave] = __builtin_readcyclecounter();
+    __syncthreads();
+    if (st && tid == 0) st[3] = __builtin_readcyclecounter();
 
     // sum over wavefronts in wavefront order; store or hand over as a partial
     for (uint32_t i = tid; i < arows; i += NT) {
         float s = 0.0f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) s += acc[w * arows + i];
-        const uint32_t ts = i / m.br, ri = i - ts * m.br;
-        const uint32_t row = m.nz_tiles[cr.nzrank0 + ts] * m.br + ri;
+        const uint32_t ts = i / m.br, ri_ = i - ts * m.br;
+        const uint32_t row = m.nz_tiles[cr.nzrank0 + ts] * m.br + ri_;
+        // a partial travels as one 64-bit word: launch tag in the high half, value in the low
+        const unsigned long long pk = ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(s);
         if (ts == 0 && cr.sid_first >= 0)
-            partials[(size_t)(m.shared[cr.sid_first].partial_off + cr.part_first) * m.br + ri] = s;
+            __hip_atomic_store(&partials[(size_t)(m.shared[cr.sid_first].partial_off + cr.part_first) * m.br + ri_], pk,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         else if (ts == cr.ntiles - 1 && cr.sid_last >= 0)
-            partials[(size_t)(m.shared[cr.sid_last].partial_off + cr.part_last) * m.br + ri] = s;
+            __hip_atomic_store(&partials[(size_t)(m.shared[cr.sid_last].partial_off + cr.part_last) * m.br + ri_], pk,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         else if (row < m.rows_out)
             y[row] = s;
     }
-    // shared tiles: the last workgroup to arrive adds the parts in part order
+    if (st && tid == 0) st[4] = __builtin_readcyclecounter();
+    // Shared tiles: every workgroup publishes its partial, then takes a ticket; the one that
+    // draws the last ticket adds the parts in part order.  Nothing here relies on the order
+    // in which stores to different addresses become visible: a partial is valid only once
+    // its word shows this launch's tag, and the reader polls for that (all writers have
+    // issued their stores before taking their tickets, so the poll ends; it is bounded
+    // anyway and poisons the row with NaN if the bound is ever hit).
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
         const int32_t sid = e == 0 ? cr.sid_first : cr.sid_last;
         if (sid < 0) continue;               // uniform over the workgroup
-        __threadfence();
         __syncthreads();
         const SharedRec sr = m.shared[sid];
         if (tid == 0) {
-            const uint32_t t = __hip_atomic_fetch_add(&m.counters[sid], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = t == sr.nparts - 1 ? 1u : 0u;
+            const uint32_t t = __hip_atomic_fetch_add(&m.counters[sid], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (t + 1u) % sr.nparts == 0u ? 1u : 0u;
         }
         __syncthreads();
         if (s_last) {
-            __threadfence();
             for (uint32_t i = tid; i < m.br; i += NT) {
                 const uint32_t row = sr.tile * m.br + i;
                 if (row >= m.rows_out) continue;
                 float s = 0.0f;
-                for (uint32_t p = 0; p < sr.nparts; ++p)
-                    s += __builtin_nontemporal_load(&partials[(size_t)(sr.partial_off + p) * m.br + i]);
+                for (uint32_t p = 0; p < sr.nparts; ++p) {
+                    const unsigned long long *src = &partials[(size_t)(sr.partial_off + p) * m.br + i];
+                    unsigned long long v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (uint32_t spin = 0; (uint32_t)(v >> 32) != epoch && spin < (1u << 22); ++spin) {
+                        __builtin_amdgcn_s_sleep(1);
+                        v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    s += (uint32_t)(v >> 32) == epoch ? __uint_as_float((uint32_t)v) : __builtin_nanf("");
+                }
                 y[row] = s;
             }
-            if (tid == 0) __hip_atomic_store(&m.counters[sid], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
     }
+    if (st && tid == 0) st[5] = __builtin_readcyclecounter();
+}
+
+static std::atomic<uint64_t> g_launch{0};
+
+__global__ void clear_words_kernel(unsigned long long *p, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
 }
 
 static hipError_t launch_spmv(const csb_matrix *mat, const float *x0, uint32_t n0, const float *x1, float *y,
-                              float *partials, hipStream_t stream) {
+                              unsigned long long *partials, hipStream_t stream, unsigned long long *stamps = nullptr) {
     const DevHeader &h = mat->plan.hdr;
     const DevMat dm = dev_mat(mat);
-    const uint32_t zpad = ((uint32_t)h.cols + 63u) & ~63u;
-    const size_t lds = ((size_t)zpad + (size_t)h.waves_per_chunk * h.max_chunk_tiles * h.br) * sizeof(float);
-    auto go = [&](auto kern, int nw) -> hipError_t {
-        if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
+    LdsMap L{};
+    L.zpad = ((uint32_t)h.cols + 63u) & ~63u;
+    L.vw = h.chunk_vals_cap;
+    L.meta_off = (L.zpad + L.vw + 64u) * 4u;   // 64 floats of slack behind the value window
+    L.acc_off = L.meta_off + h.meta_cap;
+    const size_t lds = (size_t)L.acc_off + (size_t)h.waves_per_chunk * h.max_chunk_tiles * h.br * sizeof(float);
+    // Launch tag of the merge words; a workspace seen for the first time (or a wrapped tag)
+    // is cleared so that no stale word can carry the tag.
+    // Tags are unique per launch across the process (workspaces may be shared between
+    // matrices); every 2^32 launches a new generation starts and workspaces are cleared again.
+    uint32_t epoch = 0;
+    if (h.n_partial_slots) {
+        uint64_t n = g_launch.fetch_add(1, std::memory_order_relaxed) + 1;
+        if ((uint32_t)n == 0) n = g_launch.fetch_add(1, std::memory_order_relaxed) + 1;   // tag 0 = "never written"
+        const uint32_t gen = (uint32_t)(n >> 32);
+        epoch = (uint32_t)n;
+        const size_t words = (size_t)h.n_partial_slots * h.br;
+        if (mat->ws_seen != (const void *)partials || mat->epoch != gen) {
+            hipLaunchKernelGGL(clear_words_kernel, dim3((unsigned)std::min<size_t>((words + 255) / 256, 1024)), dim3(256), 0,
+                               stream, partials, words);
+            mat->ws_seen = partials;
+            mat->epoch = gen;
         }
-        hipLaunchKernelGGL(kern, dim3(h.n_chunks), dim3(nw * 64), lds, stream, dm, x0, n0, x1, y, partials, zpad);
+    }
+    auto go = [&](auto kern, int nw) -> hipError_t {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3(h.n_chunks), dim3(nw * 64), lds, stream, dm, x0, n0, x1, y, partials, epoch, L, stamps);
         return hipGetLastError();
     };
-    switch (h.waves_per_chunk) {
-        case 4: return go(spmv_kernel<4>, 4);
-        case 8: return go(spmv_kernel<8>, 8);
-        default: return go(spmv_kernel<16>, 16);
-    }
+    if (h.waves_per_chunk != (uint32_t)kSpmvWaves) return hipErrorInvalidValue;
+    return go(spmv_kernel, kSpmvWaves);
 }
 
 int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const float *d_x1, float *d_y,
-                  void *d_ws, void *stream) {
+                  void *d_ws, void *stream, unsigned long long *d_stamps) {
     if (!m->plan.valid || !m->uploaded || !m->d_buf) { set_error("csb_spmv: matrix not planned and uploaded"); return CSB_ESTATE; }
     if (m->plan.hdr.cols > (uint64_t)kMaxStageCols) { set_error("csb_spmv: more columns than the LDS staging covers"); return CSB_EUNSUPPORTED; }
     if (m->plan.hdr.n_partial_slots && !d_ws) { set_error("csb_spmv: workspace is NULL"); return CSB_EINVAL; }
-    hipError_t e = launch_spmv(m, d_x0, n0, d_x1, d_y, (float *)d_ws, (hipStream_t)stream);
+    hipError_t e = launch_spmv(m, d_x0, n0, d_x1, d_y, (unsigned long long *)d_ws, (hipStream_t)stream, d_stamps);
     if (e != hipSuccess) { set_error(std::string("csb_spmv: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
 }
@@ -204,5 +368,16 @@ extern "C" int csb_upload(csb_matrix *m, void *d_buf, size_t bytes, void *stream
 extern "C" int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws, void *stream) {
     if (!m || !d_x || !d_y) { csb::set_error("csb_spmv: NULL pointer"); return CSB_EINVAL; }
     if (m->plan.valid && m->plan.split.active()) { csb::set_error("csb_spmv: matrix is planned for a GRU step"); return CSB_ESTATE; }
-    return csb::spmv_segments(m, d_x, (uint32_t)m->cols, d_x, d_y, d_ws, stream);
+    return csb::spmv_segments(m, d_x, (uint32_t)m->cols, d_x, d_y, d_ws, stream, nullptr);
+}
+
+extern "C" size_t csb_debug_stamp_count(const csb_matrix *m) {
+    return (m && m->plan.valid) ? (size_t)m->plan.hdr.n_chunks * csb::kStampsPerChunk : 0;
+}
+
+extern "C" int csb_debug_spmv_stamps(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws,
+                                     unsigned long long *d_stamps, void *stream) {
+    if (!m || !d_x || !d_y || !d_stamps) { csb::set_error("csb_debug_spmv_stamps: NULL pointer"); return CSB_EINVAL; }
+    if (m->plan.valid && m->plan.split.active()) { csb::set_error("csb_debug_spmv_stamps: matrix is planned for a GRU step"); return CSB_ESTATE; }
+    return csb::spmv_segments(m, d_x, (uint32_t)m->cols, d_x, d_y, d_ws, stream, d_stamps);
 }
