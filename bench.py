@@ -86,8 +86,7 @@ def main():
     Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
     bias = [torch.from_numpy(b).cuda() for b in wl.bias]
     rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, bias)
-    for w in Ws:
-        w.upload()
+    rnn.upload()                      # resident layout: one launch runs all T steps
     views = [w.view() for w in Ws]
     xd = torch.from_numpy(wl.x).cuda()
     T, B = cfg.T, cfg.batch

@@ -189,6 +189,29 @@ int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int
 int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int32_t hidden,
                    csb_matrix *const *W, const float *const *d_bias, csb_rnn **out);
 
+/*
+ * Resident layout of the whole model for batch-1 inference: every row's surviving weights
+ * cut into equal slices, one slice per lane, kept in registers for the whole sequence (the
+ * equal-work split of Sec. 5.2 applied to on-chip storage).  csb_rnn_device_bytes is 0 if
+ * the model does not fit on chip.  After csb_rnn_upload (d_buf device, caller-owned,
+ * 256-byte aligned, >= csb_rnn_device_bytes, valid while the handle is used) csb_rnn_forward
+ * with batch 1 runs all timesteps of all layers in ONE kernel launch; without it, or for
+ * batch > 1, it launches one CSB mat-vec per step and layer and needs every W[l] uploaded.
+ * The resident kernel's workgroups wait for each other's h_t: they must all be on the GPU at
+ * once, so nothing else should occupy the device while it runs.
+ */
+typedef struct {
+    int32_t resident;          /* 1 if a resident layout exists                            */
+    int32_t n_workgroups;      /* workgroups (all layers)                                  */
+    int32_t slots_per_lane;    /* multiply-adds every lane issues per step (largest layer) */
+    int32_t reserved;
+    double slot_fill;          /* non-zeros / issued multiply-adds (1 = no padding)        */
+    double lanes_max_over_mean;/* largest / mean number of busy lanes per workgroup        */
+} csb_rnn_plan_stats;
+size_t csb_rnn_device_bytes(const csb_rnn *r);
+int csb_rnn_upload(csb_rnn *r, void *d_buf, size_t bytes, void *stream);
+int csb_rnn_stats(const csb_rnn *r, csb_rnn_plan_stats *out);
+
 size_t csb_rnn_workspace_bytes(const csb_rnn *r, int32_t batch, int32_t T);
 
 /*

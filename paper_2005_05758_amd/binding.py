@@ -18,7 +18,8 @@ _lib = None
 SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_plan", "csb_plan_ex", "csb_plan_validate",
            "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
-           "csb_rnn_create", "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
+           "csb_rnn_create", "csb_rnn_device_bytes", "csb_rnn_upload", "csb_rnn_stats",
+           "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
 
 
 class CsbError(RuntimeError):
@@ -36,6 +37,11 @@ class csb_view(C.Structure):
                 ("val", C.POINTER(C.c_float)),
                 ("val_off", C.POINTER(C.c_int64)), ("row_off", C.POINTER(C.c_int64)),
                 ("col_off", C.POINTER(C.c_int64))]
+
+
+class csb_rnn_plan_stats(C.Structure):
+    _fields_ = [("resident", C.c_int32), ("n_workgroups", C.c_int32), ("slots_per_lane", C.c_int32),
+                ("reserved", C.c_int32), ("slot_fill", C.c_double), ("lanes_max_over_mean", C.c_double)]
 
 
 class csb_plan_stats(C.Structure):
@@ -77,6 +83,10 @@ def load_library():
     L.csb_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     L.csb_rnn_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
+    L.csb_rnn_device_bytes.argtypes = [C.c_void_p]
+    L.csb_rnn_device_bytes.restype = C.c_size_t
+    L.csb_rnn_upload.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.csb_rnn_stats.argtypes = [C.c_void_p, C.POINTER(csb_rnn_plan_stats)]
     L.csb_rnn_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     L.csb_rnn_workspace_bytes.restype = C.c_size_t
     L.csb_rnn_forward.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
@@ -244,6 +254,25 @@ class CsbRnn:
 
     def workspace_bytes(self, batch: int, T: int) -> int:
         return int(lib().csb_rnn_workspace_bytes(self._h, batch, T))
+
+    def stats(self):
+        st = csb_rnn_plan_stats()
+        _check(lib().csb_rnn_stats(self._h, C.byref(st)))
+        return {k: getattr(st, k) for k, _ in csb_rnn_plan_stats._fields_ if k != "reserved"}
+
+    def device_bytes(self) -> int:
+        return int(lib().csb_rnn_device_bytes(self._h))
+
+    def upload(self, device="cuda", stream=None):
+        """Upload the resident (batch-1) layout; without it forward() streams the matrices."""
+        import torch
+        n = self.device_bytes()
+        if n == 0:
+            raise CsbError(-4, "model has no resident layout")
+        self._d_img = torch.empty(n + 256, dtype=torch.uint8, device=device)
+        ptr = (self._d_img.data_ptr() + 255) // 256 * 256
+        _check(lib().csb_rnn_upload(self._h, ptr, n, _stream_ptr(stream)))
+        return self
 
     def forward(self, x, h0=None, c0=None, want_hseq=True, stream=None):
         """x: [T, B, I] float32 cuda.  Returns (hseq or None, hT, cT or None)."""

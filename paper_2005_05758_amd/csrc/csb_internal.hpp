@@ -134,6 +134,7 @@ struct Plan {
 };
 
 void set_error(const std::string &msg);
+uint32_t reserve_tags(uint32_t count, uint32_t *generation);
 
 }  // namespace csb
 

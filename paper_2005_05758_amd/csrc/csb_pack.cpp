@@ -1,6 +1,7 @@
 // Host-side CSB packer (Sec. 3.1.1) and the handle's housekeeping.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "csb_internal.hpp"
@@ -8,6 +9,22 @@
 namespace csb {
 static thread_local std::string g_err;
 void set_error(const std::string &msg) { g_err = msg; }
+}  // namespace csb
+
+namespace csb {
+// Tags of the 64-bit (tag, value) words that kernels exchange through global memory: unique
+// across the process, never 0, `count` consecutive ones inside one 2^32 generation.
+uint32_t reserve_tags(uint32_t count, uint32_t *generation) {
+    static std::mutex mu;
+    static uint64_t next = 1;
+    std::lock_guard<std::mutex> lock(mu);
+    uint64_t n0 = next;
+    if ((uint32_t)n0 == 0) ++n0;
+    if (((n0 + count) >> 32) != (n0 >> 32)) n0 = (((n0 >> 32) + 1) << 32) | 1u;
+    next = n0 + count;
+    *generation = (uint32_t)(n0 >> 32);
+    return (uint32_t)n0;
+}
 }  // namespace csb
 
 extern "C" const char *csb_last_error(void) { return csb::g_err.c_str(); }

@@ -1,21 +1,453 @@
-// LSTM / GRU inference over a sequence (Sec. 2.1) on top of the CSB mat-vec.
+// LSTM / GRU inference over a sequence (Sec. 2.1) with CSB-pruned weights.
+//
+// Two device paths behind csb_rnn_forward:
+//
+//  * resident (batch 1, after csb_rnn_upload): ONE kernel launch runs all T steps of all
+//    layers.  The pruned weights are read from HBM once and stay in registers (the paper
+//    likewise loads weights on chip once before frames stream, Sec. 6.1); every
+//    workgroup owns a range of hidden units with all their gate rows, so the gate
+//    arithmetic needs no second pass.  A row's non-zeros are cut into equal slices of S
+//    entries, one slice per lane (the equal-work split that Sec. 5.2 obtains from its
+//    compiler), slices of a row are summed through LDS in a fixed order, and h_t travels
+//    between workgroups as 64-bit (tag, value) words that readers poll, so no grid-wide
+//    barrier and no cache flush sits on the step's critical path.
+//
+//  * streaming (any batch): per step and layer one CSB mat-vec launch plus one gate
+//    kernel, all enqueued on the stream without host synchronisation.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <atomic>
+#include <cstdlib>
+#include <cstring>
 #include <new>
 #include <vector>
 
 #include "csb_internal.hpp"
 #include "csb_kernels.hpp"
 
+namespace csb {
+
+constexpr int kRnnThreads = 1024;      // lanes per workgroup of the resident kernel
+constexpr int kRnnSlotsMax = 48;       // weights one lane keeps in registers
+constexpr int kRnnMaxWgs = 240;        // all workgroups must be co-resident (256 CUs)
+constexpr uint32_t kPollLimit = 1u << 24;
+
+// One workgroup of the resident kernel.
+struct RnnWgRec {
+    uint32_t layer;
+    uint32_t u0, nu;          // hidden units [u0, u0 + nu) of the layer
+    uint32_t nlanes;          // lanes that hold a slice of a row
+    uint32_t S;               // slots per lane
+    uint32_t n_in, C;         // input width of the layer, C = n_in + H
+    uint32_t off_rows;        // byte offset of the lane table: 1024 words (segment position, flags, row slot)
+    uint32_t off_w;           // byte offset of weights  [S][1024] float
+    uint32_t off_z;           // byte offset of z indices [S][1024] u16
+    uint32_t pad[6];
+};
+static_assert(sizeof(RnnWgRec) == 64, "RnnWgRec layout");
+
+struct RnnPlan {
+    bool valid = false;
+    int n_wgs = 0, smax = 0;
+    std::vector<uint8_t> image;
+    size_t off_wgs = 0;
+    double slot_fill = 0;      // non-zeros / (1024 * S * workgroups): the useful share of issued multiply-adds
+    double lanes_max_over_mean = 0;
+};
+
+}  // namespace csb
+
 struct csb_rnn {
     int32_t cell = 0, n_layers = 0, input = 0, hidden = 0;
     std::vector<csb_matrix *> W;
     std::vector<const float *> d_bias;
+    csb::RnnPlan plan;
+    void *d_img = nullptr;
+    bool uploaded = false;
+    mutable const void *ws_seen = nullptr;
+    mutable uint32_t ws_gen = 0xffffffffu;
 };
 
 namespace csb {
 
+// Row r of layer l as (column, value) pairs in column order, after the GRU relabelling:
+// virtual row v in [0, 4H): LSTM v = row; GRU v < 2H = row, 2H..3H = n rows restricted to
+// input columns, 3H..4H = n rows restricted to recurrent columns.
+static void gather_rows(const csb_matrix *m, int cell, int H, int n_in,
+                        std::vector<std::vector<std::pair<uint32_t, float>>> &rows) {
+    rows.assign((size_t)4 * H, {});
+    for (int32_t bi = 0; bi < m->nbr; ++bi)
+        for (int32_t bj = 0; bj < m->nbc; ++bj) {
+            const size_t b = (size_t)bi * m->nbc + bj;
+            const int nr = m->nrows[b], nc = m->ncols[b];
+            for (int a = 0; a < nr; ++a) {
+                const int64_t gr = (int64_t)bi * m->br + m->rowidx[m->row_off[b] + a];
+                for (int q = 0; q < nc; ++q) {
+                    const int64_t gc = (int64_t)bj * m->bc + m->colidx[m->col_off[b] + q];
+                    int64_t v = gr;
+                    if (cell == CSB_CELL_GRU && gr >= 2 * (int64_t)H && gc >= n_in) v = gr + H;
+                    rows[(size_t)v].emplace_back((uint32_t)gc, m->val[m->val_off[b] + (size_t)a * nc + q]);
+                }
+            }
+        }
+    // blocks are visited in block-column order per block-row, so each row is already sorted
+}
+
+static int build_resident_plan(csb_rnn *r) {
+    RnnPlan &pl = r->plan;
+    pl = RnnPlan{};
+    const int L = r->n_layers, H = r->hidden;
+    struct LayerTmp {
+        std::vector<std::vector<std::pair<uint32_t, float>>> rows;
+        int n_in, C, S, P;
+        std::vector<int> u_cut;     // unit ranges per workgroup
+    };
+    std::vector<LayerTmp> lt(L);
+    size_t total_nnz = 0;
+    for (int l = 0; l < L; ++l) {
+        lt[l].n_in = l == 0 ? r->input : H;
+        lt[l].C = lt[l].n_in + H;
+        if (lt[l].C + 1 > 16000) return CSB_EUNSUPPORTED;        // z indices are 16 bit, LDS holds z
+        gather_rows(r->W[l], r->cell, H, lt[l].n_in, lt[l].rows);
+        for (auto &row : lt[l].rows) total_nnz += row.size();
+    }
+    // Slots per lane S and workgroups per layer.  A row's non-zeros are cut into k slices of
+    // S entries, one lane each; the k lanes sit inside one 16-lane DPP row so that the row
+    // sum is a shift-and-add inside the wavefront (k <= 16 fixes the smallest S).  Units are
+    // laid out one after another (their four rows in a row), workgroups take contiguous
+    // unit ranges, and the largest number of 16-lane rows per workgroup is minimised.
+    constexpr int kBins = kRnnThreads / 16;
+    int s_lo = 4, s_hi = kRnnSlotsMax;
+    if (const char *e = getenv("CSB_RNN_S")) s_lo = s_hi = std::max(4, std::min(kRnnSlotsMax, atoi(e) / 4 * 4));
+    int total_wgs = 0;
+    for (int l = 0; l < L; ++l) {
+        LayerTmp &t = lt[l];
+        size_t max_nnz = 0;
+        for (auto &row : t.rows) max_nnz = std::max(max_nnz, row.size());
+        double best_cost = 1e30;
+        for (int S = s_lo; S <= s_hi; S += 4) {
+            if ((max_nnz + S - 1) / S > 16) continue;
+            auto kof = [&](int g, int u) { return (int)((t.rows[(size_t)g * H + u].size() + S - 1) / S); };
+            // exact number of 16-lane rows of a unit range: first-fit decreasing over its segments
+            auto pack = [&](int u0, int u1, std::vector<int> *place) {
+                std::vector<std::pair<int, int>> segs;      // (k, g * nu + ui)
+                for (int u = u0; u < u1; ++u)
+                    for (int g = 0; g < 4; ++g) if (kof(g, u) > 0) segs.emplace_back(kof(g, u), g * (u1 - u0) + (u - u0));
+                std::stable_sort(segs.begin(), segs.end(), [](auto &x, auto &y) { return x.first > y.first; });
+                std::vector<int> fill;
+                if (place) place->assign((size_t)4 * (u1 - u0), -1);
+                for (auto &sg : segs) {
+                    size_t bsel = fill.size();
+                    for (size_t bq = 0; bq < fill.size(); ++bq) if (fill[bq] + sg.first <= 16) { bsel = bq; break; }
+                    if (bsel == fill.size()) fill.push_back(0);
+                    if (place) (*place)[sg.second] = (int)bsel * 16 + fill[bsel];
+                    fill[bsel] += sg.first;
+                }
+                return (int)fill.size();
+            };
+            std::vector<long> pre(H + 1, 0);
+            for (int u = 0; u < H; ++u) { pre[u + 1] = pre[u]; for (int g = 0; g < 4; ++g) pre[u + 1] += kof(g, u); }
+            auto fill_wgs = [&](int cap, std::vector<int> *cut) {
+                int used = 0, u = 0;
+                if (cut) cut->assign(1, 0);
+                while (u < H) {
+                    ++used;
+                    int u1 = u + 1;
+                    while (u1 < H && u1 - u < kRnnThreads / 4 && pre[u1 + 1] - pre[u] <= (long)cap * 16) ++u1;
+                    while (u1 > u + 1 && pack(u, u1, nullptr) > cap) --u1;
+                    if (pack(u, u1, nullptr) > kBins) return 1 << 20;           // one unit alone does not fit
+                    if (cut) cut->push_back(u1);
+                    u = u1;
+                }
+                return used;
+            };
+            const int P = fill_wgs(kBins, nullptr);
+            if (P > kRnnMaxWgs) continue;
+            // step-time model (shader clocks): S gathers per lane at ~100 clocks each for a full
+            // workgroup, plus the exchange of h_t when more than one workgroup takes part
+            const double cost = 100.0 * S + (P > 1 || L > 1 ? 1500.0 : 0.0) + 2.0 * P;
+            if (cost >= best_cost) continue;
+            int lo = 1, hi = kBins;
+            while (lo < hi) {
+                const int mid = (lo + hi) / 2;
+                if (fill_wgs(mid, nullptr) <= P) hi = mid; else lo = mid + 1;
+            }
+            fill_wgs(lo, &t.u_cut);
+            t.S = S; t.P = (int)t.u_cut.size() - 1;
+            best_cost = cost;
+        }
+        if (best_cost >= 1e30) return CSB_EUNSUPPORTED;
+        total_wgs += t.P;
+    }
+    if (total_wgs > kRnnMaxWgs) return CSB_EUNSUPPORTED;
+
+    // image: workgroup records, then per workgroup the lane table and the slot arrays
+    std::vector<RnnWgRec> wgs;
+    std::vector<uint8_t> body;
+    auto align = [&](size_t a) { while (body.size() % a) body.push_back(0); };
+    size_t slots_total = 0;
+    int smax = 0;
+    double lanes_max = 0, lanes_sum = 0;
+    for (int l = 0; l < L; ++l) {
+        const LayerTmp &t = lt[l];
+        smax = std::max(smax, t.S);
+        for (int p = 0; p < t.P; ++p) {
+            RnnWgRec w{};
+            w.layer = (uint32_t)l; w.u0 = (uint32_t)t.u_cut[p]; w.nu = (uint32_t)(t.u_cut[p + 1] - t.u_cut[p]);
+            w.S = (uint32_t)t.S; w.n_in = (uint32_t)t.n_in; w.C = (uint32_t)t.C;
+            // per lane: position in its row's segment (bits 0-3), last lane of the segment
+            // (bit 4), lane in use (bit 5), row slot g*nu + unit (bits 8-19)
+            std::vector<uint32_t> lanetab(kRnnThreads, 0);
+            std::vector<float> wv((size_t)t.S * kRnnThreads, 0.0f);
+            std::vector<uint16_t> zi((size_t)t.S * kRnnThreads, (uint16_t)t.C);   // index C = the zero slot
+            uint32_t lane = 0, busy = 0;
+            // first-fit decreasing placement of the rows' segments into 16-lane rows
+            {
+                std::vector<std::pair<int, int>> segs;
+                for (uint32_t ui = 0; ui < w.nu; ++ui)
+                    for (int g = 0; g < 4; ++g) {
+                        const int k = (int)((t.rows[(size_t)g * H + w.u0 + ui].size() + t.S - 1) / t.S);
+                        if (k > 0) segs.emplace_back(k, g * (int)w.nu + (int)ui);
+                    }
+                std::stable_sort(segs.begin(), segs.end(), [](auto &x, auto &y) { return x.first > y.first; });
+                std::vector<int> fill;
+                for (auto &sg : segs) {
+                    size_t bsel = fill.size();
+                    for (size_t bq = 0; bq < fill.size(); ++bq) if (fill[bq] + sg.first <= 16) { bsel = bq; break; }
+                    if (bsel == fill.size()) fill.push_back(0);
+                    const uint32_t l0 = (uint32_t)bsel * 16 + (uint32_t)fill[bsel], k = (uint32_t)sg.first;
+                    fill[bsel] += sg.first;
+                    const int g = sg.second / (int)w.nu, ui = sg.second % (int)w.nu;
+                    const auto &row = t.rows[(size_t)g * H + w.u0 + ui];
+                    for (uint32_t q = 0; q < k; ++q)
+                        if (l0 + q < (uint32_t)kRnnThreads)
+                            lanetab[l0 + q] = q | (q + 1 == k ? 16u : 0u) | 32u | ((uint32_t)sg.second << 8);
+                    for (size_t e = 0; e < row.size(); ++e) {
+                        const uint32_t ln = l0 + (uint32_t)(e / t.S), sl = (uint32_t)(e % t.S);
+                        if (ln >= (uint32_t)kRnnThreads) continue;
+                        wv[(size_t)sl * kRnnThreads + ln] = row[e].second;
+                        zi[(size_t)sl * kRnnThreads + ln] = (uint16_t)row[e].first;
+                    }
+                    lane = std::max<uint32_t>(lane, l0 + k);
+                    busy += k;
+                }
+            }
+            if (lane > (uint32_t)kRnnThreads) { set_error("csb_rnn_create: internal: lane overflow"); return CSB_EINVAL; }
+            w.nlanes = busy;
+            align(256);
+            w.off_rows = (uint32_t)body.size();
+            body.insert(body.end(), (uint8_t *)lanetab.data(), (uint8_t *)(lanetab.data() + lanetab.size()));
+            align(256);
+            w.off_w = (uint32_t)body.size();
+            body.insert(body.end(), (uint8_t *)wv.data(), (uint8_t *)(wv.data() + wv.size()));
+            align(256);
+            w.off_z = (uint32_t)body.size();
+            body.insert(body.end(), (uint8_t *)zi.data(), (uint8_t *)(zi.data() + zi.size()));
+            wgs.push_back(w);
+            slots_total += (size_t)kRnnThreads * t.S;
+            lanes_max = std::max<double>(lanes_max, busy);
+            lanes_sum += busy;
+        }
+    }
+    align(256);
+    const size_t hdr = (wgs.size() * sizeof(RnnWgRec) + 255) / 256 * 256;
+    pl.image.assign(hdr + body.size() + 256, 0);
+    for (auto &w : wgs) { w.off_rows += (uint32_t)hdr; w.off_w += (uint32_t)hdr; w.off_z += (uint32_t)hdr; }
+    std::memcpy(pl.image.data(), wgs.data(), wgs.size() * sizeof(RnnWgRec));
+    std::memcpy(pl.image.data() + hdr, body.data(), body.size());
+    pl.n_wgs = (int)wgs.size();
+    pl.smax = smax;
+    pl.slot_fill = slots_total ? (double)total_nnz / (double)slots_total : 0.0;
+    pl.lanes_max_over_mean = lanes_sum > 0 ? lanes_max / (lanes_sum / (double)wgs.size()) : 0.0;
+    pl.valid = true;
+    return CSB_OK;
+}
+
+// ------------------------------------------------------------------ device side
+
 __device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
+
+// Gate non-linearities of the resident kernel, built on the hardware exp2 and reciprocal
+// (each within 1 ulp): sigmoid(v) = 1 / (1 + 2^(-v log2 e)); tanh(v) = 2 sigmoid(2v) - 1 for
+// |v| >= 0.1 and its odd Taylor polynomial up to v^5 below (truncation 17 v^7 / 315 < 6e-9
+// there), which keeps the relative error near zero small.  Absolute error below 5e-7 for any v
+// (the argument scaling adds |v| 2^-24 relative error to the exponential, which only matters
+// while the exponential is not negligible against 1).
+__device__ __forceinline__ float fast_sigmoid(float v) {
+    const float e = __builtin_amdgcn_exp2f(-1.44269504088896341f * v);
+    return __builtin_amdgcn_rcpf(1.0f + e);
+}
+__device__ __forceinline__ float fast_tanh(float v) {
+    const float big = fmaf(2.0f, fast_sigmoid(2.0f * v), -1.0f);
+    const float v2 = v * v;
+    const float small = v * fmaf(v2, fmaf(v2, 2.0f / 15.0f, -1.0f / 3.0f), 1.0f);
+    return fabsf(v) < 0.1f ? small : big;
+}
+
+struct RnnArgs {
+    const uint8_t *img;                 // resident image
+    const float *x;                     // [T][I]
+    const float *h0, *c0;               // [L][H] or null
+    const float *bias[8];               // per layer, entries may be null
+    float *hseq;                        // [T][H] or null
+    float *hT, *cT;                     // [L][H]; cT may be null
+    unsigned long long *seq;            // [L][T][H] tagged words
+    uint32_t T, L, H, I, cell, tag_base;
+    uint32_t wg_stride;                 // workgroup w is block w * wg_stride; other blocks exit at once
+    unsigned long long *dbg;            // optional: per-phase shader clocks summed over the steps (workgroup 0)
+};
+
+// Workgroup barrier that orders LDS traffic only: global loads and stores in flight (the
+// prefetched next frame, the published h_t) are not waited for.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Value of the lane n places down in the same 16-lane row (0 if there is none).
+template <int N>
+__device__ __forceinline__ float dpp_shr(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x110 + N, 0xf, 0xf, true));
+}
+
+// Poll a tagged word until it carries `tag`; bounded, returns NaN if the bound is hit.
+__device__ __forceinline__ float poll_word(const unsigned long long *p, uint32_t tag) {
+    unsigned long long v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (uint32_t spin = 0; (uint32_t)(v >> 32) != tag && spin < kPollLimit; ++spin)
+        v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return (uint32_t)(v >> 32) == tag ? __uint_as_float((uint32_t)v) : __builtin_nanf("");
+}
+
+template <int SMAX>
+__global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs A) {
+    extern __shared__ float lds[];
+    const uint32_t tid = threadIdx.x;
+    if (blockIdx.x % A.wg_stride != 0) return;
+    const RnnWgRec wg = ((const RnnWgRec *)A.img)[blockIdx.x / A.wg_stride];
+    const uint32_t l = wg.layer, H = A.H, T = A.T, nu = wg.nu, n_in = wg.n_in, C = wg.C, S = wg.S;
+    float *z = lds;                       // [C + 1], z[C] = 0
+    float *arow = lds + ((C + 1 + 63) & ~63u);   // [4 * nu] row sums
+    // weights and LDS addresses of their inputs: registers for the whole sequence
+    float w[SMAX];
+    uint32_t za[SMAX];
+    {
+        const float *gw = (const float *)(A.img + wg.off_w);
+        const uint16_t *gz = (const uint16_t *)(A.img + wg.off_z);
+#pragma unroll
+        for (int s = 0; s < SMAX; ++s) {
+            const bool in = (uint32_t)s < S;
+            w[s] = in ? gw[(size_t)s * kRnnThreads + tid] : 0.0f;
+            za[s] = (in ? (uint32_t)gz[(size_t)s * kRnnThreads + tid] : C) * 4u;
+        }
+    }
+    // unit state of this thread (threads 0 .. nu-1 each own one hidden unit) and the lanes
+    // that hold the slices of its four rows
+    const bool owner = tid < nu;
+    // this lane's place in its row's segment of lanes
+    const uint32_t ltab = ((const uint32_t *)(A.img + wg.off_rows))[tid];
+    const uint32_t seg_pos = ltab & 15u, row_slot = ltab >> 8;
+    const bool seg_last = (ltab & 16u) != 0;
+    const uint32_t unit = wg.u0 + tid;
+    float c_state = 0.0f, h_state = 0.0f, b0 = 0.0f, b1 = 0.0f, b2 = 0.0f, b3 = 0.0f;
+    const bool lstm = A.cell == CSB_CELL_LSTM;
+    if (owner) {
+        if (A.c0 && lstm) c_state = A.c0[(size_t)l * H + unit];
+        if (A.h0) h_state = A.h0[(size_t)l * H + unit];
+        const float *b = A.bias[l];
+        if (b) { b0 = b[unit]; b1 = b[H + unit]; b2 = b[2 * H + unit]; if (lstm) b3 = b[3 * H + unit]; }
+    }
+    if (tid == 0) z[C] = 0.0f;
+    for (uint32_t i = tid; i < 4 * nu; i += kRnnThreads) arow[i] = 0.0f;   // rows without survivors stay 0
+    const unsigned long long *seq_in = l > 0 ? A.seq + (size_t)(l - 1) * T * H : nullptr;
+    unsigned long long *seq_me = A.seq + (size_t)l * T * H;
+    // z entries are staged from the top of the workgroup: thread tid handles entries
+    // zt and zt + 1024.  The unit owners (low tids) publish h_t with global stores, and a
+    // wavefront's loads return behind its own earlier stores; this way the wavefronts that
+    // fetch the next input frame are not the ones that store.
+    const uint32_t zt = kRnnThreads - 1 - tid;
+    // first frame of the input sequence (layer 0 reads x directly, one step ahead)
+    float xnext0 = 0.0f, xnext1 = 0.0f;
+    if (l == 0 && T > 0) {
+        if (zt < n_in) xnext0 = A.x[zt];
+        if (zt + kRnnThreads < n_in) xnext1 = A.x[zt + kRnnThreads];
+    }
+    unsigned long long ph0 = 0, ph1 = 0, ph2 = 0, ph3 = 0, c0_ = 0, c1_ = 0;
+    const bool dbg = A.dbg != nullptr && blockIdx.x == 0 && tid == 0;
+    for (uint32_t t = 0; t < T; ++t) {
+        const uint32_t tag_now = A.tag_base + t, tag_prev = A.tag_base + t - 1;
+        if (dbg) c0_ = __builtin_readcyclecounter();
+        // ---- z = [layer input ; h_{t-1}] into LDS -------------------------------------------
+#pragma unroll
+        for (int rep = 0; rep < 2; ++rep) {
+            const uint32_t e = zt + rep * kRnnThreads;
+            if (e < C) {
+                float v;
+                if (e < n_in) {
+                    if (l == 0) v = rep == 0 ? xnext0 : xnext1;
+                    else v = poll_word(seq_in + (size_t)t * H + e, tag_now);
+                } else {
+                    const uint32_t u = e - n_in;
+                    if (t == 0) v = A.h0 ? A.h0[(size_t)l * H + u] : 0.0f;
+                    else if (u - wg.u0 < nu) continue;      // own unit: its owner already wrote z
+                    else v = poll_word(seq_me + (size_t)(t - 1) * H + u, tag_prev);
+                }
+                z[e] = v;
+            }
+        }
+        if (l == 0 && t + 1 < T) {
+            if (zt < n_in) xnext0 = A.x[(size_t)(t + 1) * A.I + zt];
+            if (zt + kRnnThreads < n_in) xnext1 = A.x[(size_t)(t + 1) * A.I + zt + kRnnThreads];
+        }
+        lds_barrier();
+        if (dbg) { c1_ = __builtin_readcyclecounter(); ph0 += c1_ - c0_; c0_ = c1_; }
+        // ---- this lane's slice of its row ----------------------------------------------------
+        float acc = 0.0f;
+        const uint8_t *zb = (const uint8_t *)z;
+        float zv[SMAX];
+#pragma unroll
+        for (int s = 0; s < SMAX; ++s) zv[s] = *(const float *)(zb + za[s]);   // unused slots read the zero entry
+#pragma unroll
+        for (int s = 0; s < SMAX; ++s) acc = fmaf(w[s], zv[s], acc);
+        // ---- row sum: inclusive scan over the segment's lanes inside the 16-lane row ---------
+        // (every lane executes the shifts; only the add is conditional)
+        { const float t1 = dpp_shr<1>(acc); acc += seg_pos >= 1 ? t1 : 0.0f; }
+        { const float t2 = dpp_shr<2>(acc); acc += seg_pos >= 2 ? t2 : 0.0f; }
+        { const float t4 = dpp_shr<4>(acc); acc += seg_pos >= 4 ? t4 : 0.0f; }
+        { const float t8 = dpp_shr<8>(acc); acc += seg_pos >= 8 ? t8 : 0.0f; }
+        if (seg_last) arow[row_slot] = acc;
+        lds_barrier();
+        if (dbg) { c1_ = __builtin_readcyclecounter(); ph1 += c1_ - c0_; c0_ = c1_; }
+        // ---- gates and state of the units this workgroup owns --------------------------------
+        if (owner) {
+            const float a0 = arow[tid] + b0, a1 = arow[nu + tid] + b1, a2 = arow[2 * nu + tid], a3 = arow[3 * nu + tid];
+            float hn;
+            if (lstm) {                                  // rows i, f, g, o
+                const float cn = fast_sigmoid(a1) * c_state + fast_sigmoid(a0) * fast_tanh(a2 + b2);
+                hn = fast_sigmoid(a3 + b3) * fast_tanh(cn);
+                c_state = cn;
+            } else {                                     // rows r, z, n (input side), n (recurrent side)
+                const float rg = fast_sigmoid(a0), zg = fast_sigmoid(a1);
+                const float n = fast_tanh(a2 + b2 + rg * a3);
+                hn = (1.0f - zg) * n + zg * h_state;
+            }
+            h_state = hn;
+            z[n_in + unit] = hn;        // next step's input, read only after the next barrier
+            const unsigned long long pk = ((unsigned long long)tag_now << 32) | (unsigned long long)__float_as_uint(hn);
+            __hip_atomic_store(seq_me + (size_t)t * H + unit, pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (A.hseq && l == A.L - 1) A.hseq[(size_t)t * H + unit] = hn;
+        }
+        if (dbg) { c1_ = __builtin_readcyclecounter(); ph3 += c1_ - c0_; }
+    }
+    if (dbg) { A.dbg[0] = ph0; A.dbg[1] = ph1; A.dbg[2] = ph2; A.dbg[3] = ph3; }
+    if (owner) {
+        A.hT[(size_t)l * H + unit] = h_state;
+        if (A.cT && lstm) A.cT[(size_t)l * H + unit] = c_state;
+    }
+}
+
+// ------------------------------------------------------------------ streaming path
 
 // Element-wise part of the LSTM cell: a = W [u; h] (+ bias), rows i,f,g,o.
 __global__ void lstm_gates_kernel(const float *__restrict__ a, const float *__restrict__ bias,
@@ -56,6 +488,10 @@ __global__ void copy_kernel(float *__restrict__ d, const float *__restrict__ s, 
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) d[i] = s[i];
 }
 
+__global__ void clear_tags_kernel(unsigned long long *p, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
+}
+
 static void init_state(float *dst, const float *src, size_t n, hipStream_t st) {
     const int blocks = (int)std::min<size_t>((n + 255) / 256, 1024);
     if (src) hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, st, dst, src, n);
@@ -65,22 +501,74 @@ static void init_state(float *dst, const float *src, size_t n, hipStream_t st) {
 static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 struct RnnWs {
-    size_t off_a, off_c, off_part, total;
+    size_t off_a, off_c, off_part, off_biasptr, off_seq, total;
 };
 
-static RnnWs ws_layout(const csb_rnn *r, int32_t batch) {
+static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     RnnWs w{};
     size_t off = 0;
     size_t rows_out = 0, part = 0;
     for (auto *m : r->W) {
+        if (!m->plan.valid) continue;
         rows_out = std::max<size_t>(rows_out, (size_t)m->plan.hdr.rows_out);
-        part = std::max<size_t>(part, (size_t)m->plan.hdr.n_partial_slots * m->plan.hdr.br * sizeof(float));
+        part = std::max<size_t>(part, (size_t)m->plan.hdr.n_partial_slots * m->plan.hdr.br * 8);
     }
     w.off_a = off; off = align256(off + rows_out * sizeof(float));
     w.off_c = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     w.off_part = off; off = align256(off + part);
+    w.off_biasptr = off; off = align256(off + (size_t)r->n_layers * sizeof(void *));
+    w.off_seq = off; off = align256(off + (size_t)r->n_layers * (size_t)std::max(T, 1) * r->hidden * 8);
+    off += 512;   // last 512 bytes: debug clocks of the resident kernel
     w.total = off;
     return w;
+}
+
+static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0, float *d_hseq,
+                            float *d_hT, float *d_cT, int32_t T, void *d_ws, hipStream_t st) {
+    const RnnWs wl = ws_layout(r, 1, T);
+    const int L = r->n_layers, H = r->hidden;
+    unsigned long long *seq = (unsigned long long *)((uint8_t *)d_ws + wl.off_seq);
+    const size_t words = (size_t)L * T * H;
+    // unique tags for this call's T steps; a workspace seen for the first time (or a new tag
+    // generation) is cleared so that no stale word can carry a tag of this call
+    uint32_t gen = 0;
+    const uint32_t tag_base = reserve_tags((uint32_t)T, &gen);
+    if (r->ws_seen != (const void *)seq || r->ws_gen != gen) {
+        hipLaunchKernelGGL(clear_tags_kernel, dim3((unsigned)std::min<size_t>((words + 255) / 256, 2048)), dim3(256), 0, st,
+                           seq, words);
+        r->ws_seen = seq;
+        r->ws_gen = gen;
+    }
+    RnnArgs A{};
+    A.img = (const uint8_t *)r->d_img;
+    A.x = d_x; A.h0 = d_h0; A.c0 = d_c0;
+    for (int l = 0; l < L && l < 8; ++l) A.bias[l] = r->d_bias[l];
+    A.hseq = d_hseq; A.hT = d_hT; A.cT = d_cT; A.seq = seq;
+    A.T = (uint32_t)T; A.L = (uint32_t)L; A.H = (uint32_t)H; A.I = (uint32_t)r->input; A.cell = (uint32_t)r->cell;
+    A.tag_base = tag_base;
+    A.wg_stride = 1;
+    if (getenv("CSB_RNN_DEBUG")) A.dbg = (unsigned long long *)((uint8_t *)d_ws + wl.total - 512);
+    if (const char *e = getenv("CSB_RNN_WG_STRIDE")) A.wg_stride = (uint32_t)std::max(1, atoi(e));
+    size_t cmax = 0;
+    for (int l = 0; l < L; ++l) cmax = std::max<size_t>(cmax, (size_t)(l == 0 ? r->input : H) + H);
+    const size_t lds = (((cmax + 1 + 63) & ~(size_t)63) + kRnnThreads) * sizeof(float);
+    auto go = [&](auto kern) -> hipError_t {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3(r->plan.n_wgs * A.wg_stride), dim3(kRnnThreads), lds, st, A);
+        return hipGetLastError();
+    };
+    hipError_t e;
+    if (r->plan.smax <= 4) e = go(rnn_resident_kernel<4>);
+    else if (r->plan.smax <= 8) e = go(rnn_resident_kernel<8>);
+    else if (r->plan.smax <= 12) e = go(rnn_resident_kernel<12>);
+    else if (r->plan.smax <= 16) e = go(rnn_resident_kernel<16>);
+    else if (r->plan.smax <= 24) e = go(rnn_resident_kernel<24>);
+    else if (r->plan.smax <= 32) e = go(rnn_resident_kernel<32>);
+    else if (r->plan.smax <= 40) e = go(rnn_resident_kernel<40>);
+    else e = go(rnn_resident_kernel<kRnnSlotsMax>);
+    if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    return CSB_OK;
 }
 
 }  // namespace csb
@@ -114,6 +602,7 @@ extern "C" int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int
             r->W.push_back(W[l]);
             r->d_bias.push_back(d_bias ? d_bias[l] : nullptr);
         }
+        if (n_layers <= 8) build_resident_plan(r);     // stays invalid if the model does not fit on chip
         *out = r;
         return CSB_OK;
     } catch (const std::bad_alloc &) {
@@ -122,10 +611,36 @@ extern "C" int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int
     }
 }
 
+extern "C" size_t csb_rnn_device_bytes(const csb_rnn *r) {
+    return (r && r->plan.valid) ? r->plan.image.size() : 0;
+}
+
+extern "C" int csb_rnn_upload(csb_rnn *r, void *d_buf, size_t bytes, void *stream) {
+    using namespace csb;
+    if (!r || !d_buf) { set_error("csb_rnn_upload: NULL pointer"); return CSB_EINVAL; }
+    if (!r->plan.valid) { set_error("csb_rnn_upload: this model has no resident layout"); return CSB_EUNSUPPORTED; }
+    if (bytes < r->plan.image.size()) { set_error("csb_rnn_upload: device buffer too small"); return CSB_ENOMEM; }
+    if ((uintptr_t)d_buf % 256) { set_error("csb_rnn_upload: device buffer not 256-byte aligned"); return CSB_EINVAL; }
+    hipError_t e = hipMemcpyAsync(d_buf, r->plan.image.data(), r->plan.image.size(), hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) { set_error(std::string("csb_rnn_upload: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    r->d_img = d_buf;
+    r->uploaded = true;
+    return CSB_OK;
+}
+
+extern "C" int csb_rnn_stats(const csb_rnn *r, csb_rnn_plan_stats *out) {
+    if (!r || !out) { csb::set_error("csb_rnn_stats: NULL pointer"); return CSB_EINVAL; }
+    out->resident = r->plan.valid ? 1 : 0;
+    out->n_workgroups = r->plan.n_wgs;
+    out->slots_per_lane = r->plan.smax;
+    out->slot_fill = r->plan.slot_fill;
+    out->lanes_max_over_mean = r->plan.lanes_max_over_mean;
+    return CSB_OK;
+}
+
 extern "C" size_t csb_rnn_workspace_bytes(const csb_rnn *r, int32_t batch, int32_t T) {
-    (void)T;
-    if (!r || batch <= 0) return 0;
-    return csb::ws_layout(r, batch).total;
+    if (!r || batch <= 0 || T < 0) return 0;
+    return csb::ws_layout(r, batch, T).total;
 }
 
 extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0,
@@ -135,16 +650,28 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
     if (!r || !d_hT || !d_ws) { set_error("csb_rnn_forward: NULL pointer"); return CSB_EINVAL; }
     if (batch <= 0 || T < 0) { set_error("csb_rnn_forward: batch <= 0 or T < 0"); return CSB_EINVAL; }
     if (T > 0 && !d_x) { set_error("csb_rnn_forward: NULL input sequence"); return CSB_EINVAL; }
-    for (auto *m : r->W)
-        if (!m->plan.valid || !m->uploaded) { set_error("csb_rnn_forward: a weight matrix is not uploaded"); return CSB_ESTATE; }
     hipStream_t st = (hipStream_t)stream;
     const int L = r->n_layers, H = r->hidden, I = r->input;
     const bool lstm = r->cell == CSB_CELL_LSTM;
-    const RnnWs wl = ws_layout(r, batch);
+    const size_t nstate = (size_t)L * batch * H;
+    if (T == 0) {                                  // hand the state through
+        init_state(d_hT, d_h0, nstate, st);
+        if (lstm && d_cT) init_state(d_cT, d_c0, nstate, st);
+        return CSB_OK;
+    }
+    const bool resident = batch == 1 && r->plan.valid && r->uploaded;
+    if (!resident)
+        for (auto *m : r->W)
+            if (!m->plan.valid || !m->uploaded) {
+                set_error("csb_rnn_forward: neither the resident layout nor every weight matrix is uploaded");
+                return CSB_ESTATE;
+            }
+    if (resident) return forward_resident(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, d_ws, st);
+
+    const RnnWs wl = ws_layout(r, batch, T);
     float *a = (float *)((uint8_t *)d_ws + wl.off_a);
     float *c = (lstm && d_cT) ? d_cT : (float *)((uint8_t *)d_ws + wl.off_c);
     void *part = (uint8_t *)d_ws + wl.off_part;
-    const size_t nstate = (size_t)L * batch * H;
     // the outputs double as the running state
     init_state(d_hT, d_h0, nstate, st);
     if (lstm) init_state(c, d_c0, nstate, st);

@@ -296,8 +296,6 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
     if (st && tid == 0) st[5] = __builtin_readcyclecounter();
 }
 
-static std::atomic<uint64_t> g_launch{0};
-
 __global__ void clear_words_kernel(unsigned long long *p, size_t n) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
 }
@@ -318,10 +316,8 @@ static hipError_t launch_spmv(const csb_matrix *mat, const float *x0, uint32_t n
     // matrices); every 2^32 launches a new generation starts and workspaces are cleared again.
     uint32_t epoch = 0;
     if (h.n_partial_slots) {
-        uint64_t n = g_launch.fetch_add(1, std::memory_order_relaxed) + 1;
-        if ((uint32_t)n == 0) n = g_launch.fetch_add(1, std::memory_order_relaxed) + 1;   // tag 0 = "never written"
-        const uint32_t gen = (uint32_t)(n >> 32);
-        epoch = (uint32_t)n;
+        uint32_t gen = 0;
+        epoch = reserve_tags(1, &gen);
         const size_t words = (size_t)h.n_partial_slots * h.br;
         if (mat->ws_seen != (const void *)partials || mat->epoch != gen) {
             hipLaunchKernelGGL(clear_words_kernel, dim3((unsigned)std::min<size_t>((words + 255) / 256, 1024)), dim3(256), 0,

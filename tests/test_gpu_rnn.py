@@ -20,24 +20,35 @@ def say(msg):
     sys.stdout.flush()
 
 
-def build_rnn(wl):
+def build_rnn(wl, resident):
+    """resident=True: upload the on-chip layout (one launch for the whole sequence, batch 1);
+    resident=False: upload the matrices only (one mat-vec launch per step and layer)."""
     cfg = wl.cfg
     Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
     bias = [torch.from_numpy(b).cuda() for b in wl.bias]
     rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, bias)
-    for w in Ws:
-        w.validate()
-        w.upload()
+    if resident:
+        assert rnn.stats()["resident"] == 1
+        rnn.upload()
+    else:
+        for w in Ws:
+            w.validate()
+            w.upload()
     return rnn
 
 
-def run_case(wl, h0=None, c0=None, tag=""):
+def run_case(wl, h0=None, c0=None, tag="", resident=None):
     cfg = wl.cfg
     T, B, _ = wl.x.shape
-    say(f"[rnn] {tag} cell={cfg.cell} L={cfg.n_layers} I={cfg.input} H={cfg.hidden} T={T} B={B}")
+    if resident is None:                      # both device paths where both apply
+        out = run_case(wl, h0, c0, tag, resident=False)
+        if B == 1:
+            out = run_case(wl, h0, c0, tag, resident=True)
+        return out
+    say(f"[rnn] {tag} cell={cfg.cell} L={cfg.n_layers} I={cfg.input} H={cfg.hidden} T={T} B={B} resident={resident}")
     W = [oracle.csb_decode(oracle.csb_encode(m.A, m.br, m.bc)) for m in wl.W]
     rseq, rhT, rcT = oracle.rnn_forward(cfg.cell, W, wl.bias, wl.x, cfg.input, cfg.hidden, h0=h0, c0=c0)
-    rnn = build_rnn(wl)
+    rnn = build_rnn(wl, resident)
     xd = torch.from_numpy(wl.x).cuda()
     h0d = None if h0 is None else torch.from_numpy(h0.astype(np.float32)).cuda()
     c0d = None if c0 is None else torch.from_numpy(c0.astype(np.float32)).cuda()
@@ -54,7 +65,8 @@ def run_case(wl, h0=None, c0=None, tag=""):
 
 @pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
 @pytest.mark.parametrize("L,I,H,T,B,block", [(1, 5, 7, 6, 1, 4), (2, 12, 16, 9, 3, 8), (1, 40, 100, 12, 2, 32),
-                                            (3, 8, 8, 4, 2, 8), (1, 33, 50, 5, 1, 16)])
+                                            (3, 8, 8, 4, 2, 8), (1, 33, 50, 5, 1, 16), (2, 30, 300, 7, 1, 32),
+                                            (3, 16, 64, 20, 1, 16)])
 def test_rnn_small(cell, L, I, H, T, B, block):
     cfg = csb_inputs.RnnConfig("t", cell, L, I, H, block, 3.0, "binomial", 0.3, B, T, 20 + L + I)
     wl = csb_inputs.make_rnn(cfg)
@@ -72,11 +84,12 @@ def test_rnn_workloads_full_size(name):
     run_case(wl, tag=name)
 
 
+@pytest.mark.parametrize("batch,resident", [(2, False), (1, False), (1, True)])
 @pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
-def test_rnn_resume_and_T0(cell):
-    cfg = csb_inputs.RnnConfig("t", cell, 2, 24, 32, 16, 4.0, "binomial", 0.3, 2, 10, 5)
+def test_rnn_resume_and_T0(cell, batch, resident):
+    cfg = csb_inputs.RnnConfig("t", cell, 2, 24, 32, 16, 4.0, "binomial", 0.3, batch, 10, 5)
     wl = csb_inputs.make_rnn(cfg)
-    rnn, (hseq, hT, cT) = run_case(wl, tag="resume-full")
+    rnn, (hseq, hT, cT) = run_case(wl, tag="resume-full", resident=resident)
     xd = torch.from_numpy(wl.x).cuda()
     s1, h1, c1 = rnn.forward(xd[:4].contiguous())
     s2, h2, c2 = rnn.forward(xd[4:].contiguous(), h1, c1)
@@ -92,8 +105,10 @@ def test_rnn_resume_and_T0(cell):
         assert torch.equal(c0, c1)
 
 
-def test_rnn_zero_weights_closed_form():
-    I, H, T, B = 3, 5, 7, 2
+@pytest.mark.parametrize("B,resident", [(2, False), (1, False), (1, True)])
+def test_rnn_zero_weights_closed_form(B, resident):
+    """W = 0, b = 0: LSTM c_T = c_0 / 2^T, h_T = tanh(c_T) / 2; GRU h_T = h_0 / 2^T."""
+    I, H, T = 3, 5, 7
     rng = np.random.default_rng(2)
     x = rng.uniform(-1, 1, (T, B, I)).astype(np.float32)
     h0 = rng.uniform(-1, 1, (1, B, H)).astype(np.float32)
@@ -101,7 +116,10 @@ def test_rnn_zero_weights_closed_form():
     for cell, G in ((0, 4), (1, 3)):
         W = CsbMatrix(np.zeros((G * H, I + H), np.float32), 4, 4)
         rnn = CsbRnn(cell, I, H, [W], None)
-        W.upload()
+        if resident:
+            rnn.upload()
+        else:
+            W.upload()
         _, hT, cT = rnn.forward(torch.from_numpy(x).cuda(), torch.from_numpy(h0).cuda(),
                                 torch.from_numpy(c0).cuda() if cell == 0 else None)
         torch.cuda.synchronize()
