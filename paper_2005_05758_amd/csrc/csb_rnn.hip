@@ -43,7 +43,8 @@ struct RnnWgRec {
     uint32_t off_rows;        // byte offset of the lane table: 1024 words (segment position, flags, row slot)
     uint32_t off_w;           // byte offset of weights  [S][1024] float
     uint32_t off_z;           // byte offset of z indices [S][1024] u16
-    uint32_t pad[6];
+    uint32_t upre;            // hidden units owned by the workgroups before this one (all layers)
+    uint32_t pad[5];
 };
 static_assert(sizeof(RnnWgRec) == 64, "RnnWgRec layout");
 
@@ -51,7 +52,7 @@ struct RnnPlan {
     bool valid = false;
     int n_wgs = 0, smax = 0;
     std::vector<uint8_t> image;
-    size_t off_wgs = 0;
+    size_t off_unit_wg = 0;    // [L][H] u16: workgroup that owns each hidden unit
     double slot_fill = 0;      // non-zeros / (1024 * S * workgroups): the useful share of issued multiply-adds
     double lanes_max_over_mean = 0;
 };
@@ -94,6 +95,35 @@ static void gather_rows(const csb_matrix *m, int cell, int H, int n_in,
     // blocks are visited in block-column order per block-row, so each row is already sorted
 }
 
+// Places row segments (k lanes each, k <= 32) into 16-lane rows of a workgroup: a segment
+// of at most 16 lanes lies inside one row; a longer one starts on an even row, fills it and
+// continues on the odd row after it.  First-fit decreasing.  Returns the number of 16-lane
+// rows used; place[i] = first lane of segment i (-1 for k = 0).
+static int pack_segments(const std::vector<int> &k, std::vector<int> *place) {
+    std::vector<int> order(k.size());
+    for (size_t i = 0; i < k.size(); ++i) order[i] = (int)i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return k[a] > k[b]; });
+    std::vector<int> fill;                               // lanes used per 16-lane row
+    if (place) place->assign(k.size(), -1);
+    for (int i : order) {
+        const int ki = k[i];
+        if (ki <= 0) continue;
+        if (ki > 16) {
+            if (fill.size() & 1) fill.push_back(0);      // start on an even row
+            if (place) (*place)[i] = (int)fill.size() * 16;
+            fill.push_back(16);
+            fill.push_back(ki - 16);
+        } else {
+            size_t r = fill.size();
+            for (size_t q = 0; q < fill.size(); ++q) if (fill[q] + ki <= 16) { r = q; break; }
+            if (r == fill.size()) fill.push_back(0);
+            if (place) (*place)[i] = (int)r * 16 + fill[r];
+            fill[r] += ki;
+        }
+    }
+    return (int)fill.size();
+}
+
 static int build_resident_plan(csb_rnn *r) {
     RnnPlan &pl = r->plan;
     pl = RnnPlan{};
@@ -113,11 +143,12 @@ static int build_resident_plan(csb_rnn *r) {
         for (auto &row : lt[l].rows) total_nnz += row.size();
     }
     // Slots per lane S and workgroups per layer.  A row's non-zeros are cut into k slices of
-    // S entries, one lane each; the k lanes sit inside one 16-lane DPP row so that the row
-    // sum is a shift-and-add inside the wavefront (k <= 16 fixes the smallest S).  Units are
+    // S entries, one lane each; the k lanes sit inside one aligned 32-lane half of a wavefront
+    // so that the row sum is a shift-and-add inside the wavefront (k <= 32 fixes the smallest S).  Units are
     // laid out one after another (their four rows in a row), workgroups take contiguous
     // unit ranges, and the largest number of 16-lane rows per workgroup is minimised.
-    constexpr int kBins = kRnnThreads / 16;
+    constexpr int kSeg = 32;                       // lanes one row's slices may span
+    constexpr int kBins = kRnnThreads / 16;        // 16-lane rows per workgroup
     int s_lo = 4, s_hi = kRnnSlotsMax;
     if (const char *e = getenv("CSB_RNN_S")) s_lo = s_hi = std::max(4, std::min(kRnnSlotsMax, atoi(e) / 4 * 4));
     int total_wgs = 0;
@@ -127,24 +158,14 @@ static int build_resident_plan(csb_rnn *r) {
         for (auto &row : t.rows) max_nnz = std::max(max_nnz, row.size());
         double best_cost = 1e30;
         for (int S = s_lo; S <= s_hi; S += 4) {
-            if ((max_nnz + S - 1) / S > 16) continue;
+            if ((max_nnz + S - 1) / S > (size_t)kSeg) continue;
             auto kof = [&](int g, int u) { return (int)((t.rows[(size_t)g * H + u].size() + S - 1) / S); };
-            // exact number of 16-lane rows of a unit range: first-fit decreasing over its segments
+            // exact number of 16-lane rows of a unit range
             auto pack = [&](int u0, int u1, std::vector<int> *place) {
-                std::vector<std::pair<int, int>> segs;      // (k, g * nu + ui)
+                std::vector<int> ks((size_t)4 * (u1 - u0));
                 for (int u = u0; u < u1; ++u)
-                    for (int g = 0; g < 4; ++g) if (kof(g, u) > 0) segs.emplace_back(kof(g, u), g * (u1 - u0) + (u - u0));
-                std::stable_sort(segs.begin(), segs.end(), [](auto &x, auto &y) { return x.first > y.first; });
-                std::vector<int> fill;
-                if (place) place->assign((size_t)4 * (u1 - u0), -1);
-                for (auto &sg : segs) {
-                    size_t bsel = fill.size();
-                    for (size_t bq = 0; bq < fill.size(); ++bq) if (fill[bq] + sg.first <= 16) { bsel = bq; break; }
-                    if (bsel == fill.size()) fill.push_back(0);
-                    if (place) (*place)[sg.second] = (int)bsel * 16 + fill[bsel];
-                    fill[bsel] += sg.first;
-                }
-                return (int)fill.size();
+                    for (int g = 0; g < 4; ++g) ks[(size_t)g * (u1 - u0) + (u - u0)] = kof(g, u);
+                return pack_segments(ks, place);
             };
             std::vector<long> pre(H + 1, 0);
             for (int u = 0; u < H; ++u) { pre[u + 1] = pre[u]; for (int g = 0; g < 4; ++g) pre[u + 1] += kof(g, u); }
@@ -166,7 +187,7 @@ static int build_resident_plan(csb_rnn *r) {
             if (P > kRnnMaxWgs) continue;
             // step-time model (shader clocks): S gathers per lane at ~100 clocks each for a full
             // workgroup, plus the exchange of h_t when more than one workgroup takes part
-            const double cost = 100.0 * S + (P > 1 || L > 1 ? 1500.0 : 0.0) + 2.0 * P;
+            const double cost = 60.0 * S + (P > 1 || L > 1 ? 1700.0 : 0.0) + 6.0 * P;
             if (cost >= best_cost) continue;
             int lo = 1, hi = kBins;
             while (lo < hi) {
@@ -187,6 +208,8 @@ static int build_resident_plan(csb_rnn *r) {
     std::vector<uint8_t> body;
     auto align = [&](size_t a) { while (body.size() % a) body.push_back(0); };
     size_t slots_total = 0;
+    uint32_t upre_run = 0;
+    std::vector<uint16_t> unit_wg((size_t)L * H, 0);
     int smax = 0;
     double lanes_max = 0, lanes_sum = 0;
     for (int l = 0; l < L; ++l) {
@@ -196,41 +219,58 @@ static int build_resident_plan(csb_rnn *r) {
             RnnWgRec w{};
             w.layer = (uint32_t)l; w.u0 = (uint32_t)t.u_cut[p]; w.nu = (uint32_t)(t.u_cut[p + 1] - t.u_cut[p]);
             w.S = (uint32_t)t.S; w.n_in = (uint32_t)t.n_in; w.C = (uint32_t)t.C;
-            // per lane: position in its row's segment (bits 0-3), last lane of the segment
-            // (bit 4), lane in use (bit 5), row slot g*nu + unit (bits 8-19)
+            w.upre = upre_run; upre_run += w.nu;
+            for (uint32_t ui = 0; ui < w.nu; ++ui) unit_wg[(size_t)l * H + w.u0 + ui] = (uint16_t)wgs.size();
+            // per lane: position in its row's segment (bits 0-4), last lane of the segment
+            // (bit 5), lane in use (bit 6), row slot g*nu + unit (bits 8-19)
             std::vector<uint32_t> lanetab(kRnnThreads, 0);
             std::vector<float> wv((size_t)t.S * kRnnThreads, 0.0f);
             std::vector<uint16_t> zi((size_t)t.S * kRnnThreads, (uint16_t)t.C);   // index C = the zero slot
             uint32_t lane = 0, busy = 0;
-            // first-fit decreasing placement of the rows' segments into 16-lane rows
+            std::vector<std::vector<std::pair<uint32_t, float>>> lane_elems(kRnnThreads);
+            // placement of the rows' segments into 16-lane rows
             {
-                std::vector<std::pair<int, int>> segs;
+                std::vector<int> ks((size_t)4 * w.nu), place;
                 for (uint32_t ui = 0; ui < w.nu; ++ui)
-                    for (int g = 0; g < 4; ++g) {
-                        const int k = (int)((t.rows[(size_t)g * H + w.u0 + ui].size() + t.S - 1) / t.S);
-                        if (k > 0) segs.emplace_back(k, g * (int)w.nu + (int)ui);
-                    }
-                std::stable_sort(segs.begin(), segs.end(), [](auto &x, auto &y) { return x.first > y.first; });
-                std::vector<int> fill;
-                for (auto &sg : segs) {
-                    size_t bsel = fill.size();
-                    for (size_t bq = 0; bq < fill.size(); ++bq) if (fill[bq] + sg.first <= 16) { bsel = bq; break; }
-                    if (bsel == fill.size()) fill.push_back(0);
-                    const uint32_t l0 = (uint32_t)bsel * 16 + (uint32_t)fill[bsel], k = (uint32_t)sg.first;
-                    fill[bsel] += sg.first;
-                    const int g = sg.second / (int)w.nu, ui = sg.second % (int)w.nu;
+                    for (int g = 0; g < 4; ++g)
+                        ks[(size_t)g * w.nu + ui] = (int)((t.rows[(size_t)g * H + w.u0 + ui].size() + t.S - 1) / t.S);
+                if (pack_segments(ks, &place) > kBins) { set_error("csb_rnn_create: internal: lane overflow"); return CSB_EINVAL; }
+                for (size_t sl = 0; sl < ks.size(); ++sl) {
+                    if (ks[sl] <= 0) continue;
+                    const uint32_t l0 = (uint32_t)place[sl], k = (uint32_t)ks[sl];
+                    const int g = (int)(sl / w.nu), ui = (int)(sl % w.nu);
                     const auto &row = t.rows[(size_t)g * H + w.u0 + ui];
                     for (uint32_t q = 0; q < k; ++q)
-                        if (l0 + q < (uint32_t)kRnnThreads)
-                            lanetab[l0 + q] = q | (q + 1 == k ? 16u : 0u) | 32u | ((uint32_t)sg.second << 8);
-                    for (size_t e = 0; e < row.size(); ++e) {
-                        const uint32_t ln = l0 + (uint32_t)(e / t.S), sl = (uint32_t)(e % t.S);
-                        if (ln >= (uint32_t)kRnnThreads) continue;
-                        wv[(size_t)sl * kRnnThreads + ln] = row[e].second;
-                        zi[(size_t)sl * kRnnThreads + ln] = (uint16_t)row[e].first;
-                    }
+                        lanetab[l0 + q] = q | (q + 1 == k ? 32u : 0u) | 64u | ((uint32_t)sl << 8);
+                    for (size_t e = 0; e < row.size(); ++e) lane_elems[l0 + (uint32_t)(e / t.S)].push_back(row[e]);
                     lane = std::max<uint32_t>(lane, l0 + k);
                     busy += k;
+                }
+            }
+            // Which of a lane's S slots each of its entries takes is free (it only fixes the
+            // order of the lane's sum).  The LDS serves 32 lanes at a time from 32 banks of
+            // 4 bytes: place the entries so that, slot by slot, the 32 lanes of a half
+            // wavefront hit different banks, or the very same word, as far as possible.
+            for (uint32_t h0 = 0; h0 < (uint32_t)kRnnThreads; h0 += 32) {
+                std::vector<std::vector<uint32_t>> seen((size_t)t.S * 32);   // [slot][bank] -> distinct words
+                for (uint32_t ln = h0; ln < h0 + 32; ++ln) {
+                    std::vector<char> used(t.S, 0);
+                    for (auto &el : lane_elems[ln]) {
+                        const uint32_t bank = el.first & 31u;
+                        int best = -1, best_cost = 1 << 30;
+                        for (int sl = 0; sl < t.S; ++sl) {
+                            if (used[sl]) continue;
+                            auto &words = seen[(size_t)sl * 32 + bank];
+                            int cost = (int)words.size() * 2;
+                            for (uint32_t wd : words) if (wd == el.first) { cost = -1; break; }   // broadcast
+                            if (cost < best_cost) { best_cost = cost; best = sl; }
+                        }
+                        used[best] = 1;
+                        auto &words = seen[(size_t)best * 32 + bank];
+                        if (std::find(words.begin(), words.end(), el.first) == words.end()) words.push_back(el.first);
+                        wv[(size_t)best * kRnnThreads + ln] = el.second;
+                        zi[(size_t)best * kRnnThreads + ln] = (uint16_t)el.first;
+                    }
                 }
             }
             if (lane > (uint32_t)kRnnThreads) { set_error("csb_rnn_create: internal: lane overflow"); return CSB_EINVAL; }
@@ -251,7 +291,11 @@ static int build_resident_plan(csb_rnn *r) {
         }
     }
     align(256);
+    const size_t off_uw_body = body.size();
+    body.insert(body.end(), (uint8_t *)unit_wg.data(), (uint8_t *)(unit_wg.data() + unit_wg.size()));
+    align(256);
     const size_t hdr = (wgs.size() * sizeof(RnnWgRec) + 255) / 256 * 256;
+    pl.off_unit_wg = hdr + off_uw_body;
     pl.image.assign(hdr + body.size() + 256, 0);
     for (auto &w : wgs) { w.off_rows += (uint32_t)hdr; w.off_w += (uint32_t)hdr; w.off_z += (uint32_t)hdr; }
     std::memcpy(pl.image.data(), wgs.data(), wgs.size() * sizeof(RnnWgRec));
@@ -278,11 +322,13 @@ __device__ __forceinline__ float fast_sigmoid(float v) {
     const float e = __builtin_amdgcn_exp2f(-1.44269504088896341f * v);
     return __builtin_amdgcn_rcpf(1.0f + e);
 }
+__device__ __forceinline__ float tanh_small(float v) {
+    const float v2 = v * v;
+    return v * fmaf(v2, fmaf(v2, 2.0f / 15.0f, -1.0f / 3.0f), 1.0f);
+}
 __device__ __forceinline__ float fast_tanh(float v) {
     const float big = fmaf(2.0f, fast_sigmoid(2.0f * v), -1.0f);
-    const float v2 = v * v;
-    const float small = v * fmaf(v2, fmaf(v2, 2.0f / 15.0f, -1.0f / 3.0f), 1.0f);
-    return fabsf(v) < 0.1f ? small : big;
+    return fabsf(v) < 0.1f ? tanh_small(v) : big;
 }
 
 struct RnnArgs {
@@ -294,6 +340,8 @@ struct RnnArgs {
     float *hT, *cT;                     // [L][H]; cT may be null
     unsigned long long *seq;            // [L][T][H] tagged words
     uint32_t T, L, H, I, cell, tag_base;
+    uint32_t off_unit_wg;               // byte offset in img of the [L][H] owner table
+    uint32_t poll_delay;                // s_sleep units before the first poll of a step (0 = none)
     uint32_t wg_stride;                 // workgroup w is block w * wg_stride; other blocks exit at once
     unsigned long long *dbg;            // optional: per-phase shader clocks summed over the steps (workgroup 0)
 };
@@ -313,10 +361,15 @@ __device__ __forceinline__ float dpp_shr(float v) {
 }
 
 // Poll a tagged word until it carries `tag`; bounded, returns NaN if the bound is hit.
-__device__ __forceinline__ float poll_word(const unsigned long long *p, uint32_t tag) {
+// `retried` is set if the first load did not already carry the tag.
+__device__ __forceinline__ float poll_word(const unsigned long long *p, uint32_t tag, bool &retried, uint32_t &npolls) {
     unsigned long long v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (uint32_t spin = 0; (uint32_t)(v >> 32) != tag && spin < kPollLimit; ++spin)
+    ++npolls;
+    for (uint32_t spin = 0; (uint32_t)(v >> 32) != tag && spin < kPollLimit; ++spin) {
+        retried = true;
+        ++npolls;
         v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     return (uint32_t)(v >> 32) == tag ? __uint_as_float((uint32_t)v) : __builtin_nanf("");
 }
 
@@ -347,38 +400,85 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     const bool owner = tid < nu;
     // this lane's place in its row's segment of lanes
     const uint32_t ltab = ((const uint32_t *)(A.img + wg.off_rows))[tid];
-    const uint32_t seg_pos = ltab & 15u, row_slot = ltab >> 8;
-    const bool seg_last = (ltab & 16u) != 0;
+    const uint32_t seg_pos = ltab & 31u, row_slot = ltab >> 8;
+    const bool seg_last = (ltab & 32u) != 0;
     const uint32_t unit = wg.u0 + tid;
-    float c_state = 0.0f, h_state = 0.0f, b0 = 0.0f, b1 = 0.0f, b2 = 0.0f, b3 = 0.0f;
     const bool lstm = A.cell == CSB_CELL_LSTM;
+    // the last lane of a row's segment ends up with the row sum: it adds the bias and applies
+    // the gate's non-linearity at once (LSTM rows i,f,o: sigmoid, g: tanh; GRU rows r,z:
+    // sigmoid, the two halves of n: none yet)
+    float row_bias = 0.0f;
+    uint32_t act = 0;                       // 0 none, 1 sigmoid, 2 tanh
+    if (seg_last) {
+        const uint32_t g = row_slot / nu, ui = row_slot - g * nu;
+        const float *b = A.bias[l];
+        if (lstm) { act = g == 2 ? 2u : 1u; if (b) row_bias = b[g * H + wg.u0 + ui]; }
+        else { act = g < 2 ? 1u : 0u; if (b && g < 3) row_bias = b[g * H + wg.u0 + ui]; }
+    }
+    float c_state = 0.0f, h_state = 0.0f;
     if (owner) {
         if (A.c0 && lstm) c_state = A.c0[(size_t)l * H + unit];
         if (A.h0) h_state = A.h0[(size_t)l * H + unit];
-        const float *b = A.bias[l];
-        if (b) { b0 = b[unit]; b1 = b[H + unit]; b2 = b[2 * H + unit]; if (lstm) b3 = b[3 * H + unit]; }
     }
     if (tid == 0) z[C] = 0.0f;
-    for (uint32_t i = tid; i < 4 * nu; i += kRnnThreads) arow[i] = 0.0f;   // rows without survivors stay 0
-    const unsigned long long *seq_in = l > 0 ? A.seq + (size_t)(l - 1) * T * H : nullptr;
-    unsigned long long *seq_me = A.seq + (size_t)l * T * H;
+    // rows without survivors have no lane: their entry keeps the activation of the bare bias
+    for (uint32_t i = tid; i < 4 * nu; i += kRnnThreads) {
+        const uint32_t g = i / nu, ui = i - g * nu;
+        const float *b = A.bias[l];
+        float v = 0.0f;
+        if (lstm) { if (b) v = b[g * H + wg.u0 + ui]; v = g == 2 ? fast_tanh(v) : fast_sigmoid(v); }
+        else { if (b && g < 3) v = b[g * H + wg.u0 + ui]; if (g < 2) v = fast_sigmoid(v); }
+        arow[i] = v;
+    }
+    // Exchange words: every workgroup publishes the h_t of its units into a region of its own,
+    // [t][unit of the workgroup]; the regions of different workgroups lie T * nu words apart,
+    // which spreads the polling over the memory channels.
+    unsigned long long *pub = A.seq + (size_t)T * wg.upre + tid;     // + t * nu
+    const uint16_t *unit_wg = (const uint16_t *)(A.img + A.off_unit_wg);
     // z entries are staged from the top of the workgroup: thread tid handles entries
     // zt and zt + 1024.  The unit owners (low tids) publish h_t with global stores, and a
     // wavefront's loads return behind its own earlier stores; this way the wavefronts that
     // fetch the next input frame are not the ones that store.
     const uint32_t zt = kRnnThreads - 1 - tid;
+    // where this thread's (at most two) polled z entries come from: word address at t = 0 and
+    // words per step of the source workgroup
+    const unsigned long long *src[2] = {nullptr, nullptr};
+    uint32_t src_stride[2] = {0, 0};
+    bool src_local[2] = {false, false};
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+        const uint32_t e = zt + rep * kRnnThreads;
+        if (e < C && e >= n_in && e - n_in - wg.u0 < nu) src_local[rep] = true;   // own unit: no poll
+        if (e < C && (e >= n_in || l > 0)) {
+            const uint32_t ls = e < n_in ? l - 1 : l, us = e < n_in ? e : e - n_in;
+            const RnnWgRec *q = (const RnnWgRec *)A.img + unit_wg[(size_t)ls * H + us];
+            src[rep] = A.seq + (size_t)T * q->upre + (us - q->u0);
+            src_stride[rep] = q->nu;
+        }
+    }
     // first frame of the input sequence (layer 0 reads x directly, one step ahead)
     float xnext0 = 0.0f, xnext1 = 0.0f;
     if (l == 0 && T > 0) {
         if (zt < n_in) xnext0 = A.x[zt];
         if (zt + kRnnThreads < n_in) xnext1 = A.x[zt + kRnnThreads];
     }
+    // does this wavefront poll at all (any lane with a remote source)?
+    const bool polls = __ballot((src[0] != nullptr && !(src_local[0])) || (src[1] != nullptr && !(src_local[1]))) != 0ull;
+    uint32_t delay = A.poll_delay, streak = 0, npolls = 0;
+    unsigned long long wave_arrive = 0, after_b = 0;
     unsigned long long ph0 = 0, ph1 = 0, ph2 = 0, ph3 = 0, c0_ = 0, c1_ = 0;
     const bool dbg = A.dbg != nullptr && blockIdx.x == 0 && tid == 0;
     for (uint32_t t = 0; t < T; ++t) {
         const uint32_t tag_now = A.tag_base + t, tag_prev = A.tag_base + t - 1;
         if (dbg) c0_ = __builtin_readcyclecounter();
         // ---- z = [layer input ; h_{t-1}] into LDS -------------------------------------------
+        // A load that samples memory just before h arrives costs a whole extra round trip, one
+        // that samples it long after wastes the difference.  Steps repeat with the same timing,
+        // so each wavefront waits `delay` sleeps before its first poll and tunes it: three more
+        // after a step in which a first poll came back stale, one less after 16 clean steps.
+        if (polls && (t > 0 || l > 0))
+            for (uint32_t d = 0; d < delay; ++d) __builtin_amdgcn_s_sleep(1);
+        bool retried = false;
 #pragma unroll
         for (int rep = 0; rep < 2; ++rep) {
             const uint32_t e = zt + rep * kRnnThreads;
@@ -386,15 +486,20 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
                 float v;
                 if (e < n_in) {
                     if (l == 0) v = rep == 0 ? xnext0 : xnext1;
-                    else v = poll_word(seq_in + (size_t)t * H + e, tag_now);
+                    else v = poll_word(src[rep] + (size_t)t * src_stride[rep], tag_now, retried, npolls);
                 } else {
                     const uint32_t u = e - n_in;
                     if (t == 0) v = A.h0 ? A.h0[(size_t)l * H + u] : 0.0f;
                     else if (u - wg.u0 < nu) continue;      // own unit: its owner already wrote z
-                    else v = poll_word(seq_me + (size_t)(t - 1) * H + u, tag_prev);
+                    else v = poll_word(src[rep] + (size_t)(t - 1) * src_stride[rep], tag_prev, retried, npolls);
                 }
                 z[e] = v;
             }
+        }
+        if (A.dbg && blockIdx.x == 0 && (tid & 63u) == 0 && t > 0) wave_arrive += __builtin_readcyclecounter() - after_b;
+        if (polls) {
+            if (__ballot(retried) != 0ull) { delay += 3; streak = 0; }
+            else if (++streak >= 16) { delay -= delay > 0 ? 1u : 0u; streak = 0; }
         }
         if (l == 0 && t + 1 < T) {
             if (zt < n_in) xnext0 = A.x[(size_t)(t + 1) * A.I + zt];
@@ -410,37 +515,52 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         for (int s = 0; s < SMAX; ++s) zv[s] = *(const float *)(zb + za[s]);   // unused slots read the zero entry
 #pragma unroll
         for (int s = 0; s < SMAX; ++s) acc = fmaf(w[s], zv[s], acc);
-        // ---- row sum: inclusive scan over the segment's lanes inside the 16-lane row ---------
-        // (every lane executes the shifts; only the add is conditional)
-        { const float t1 = dpp_shr<1>(acc); acc += seg_pos >= 1 ? t1 : 0.0f; }
-        { const float t2 = dpp_shr<2>(acc); acc += seg_pos >= 2 ? t2 : 0.0f; }
-        { const float t4 = dpp_shr<4>(acc); acc += seg_pos >= 4 ? t4 : 0.0f; }
-        { const float t8 = dpp_shr<8>(acc); acc += seg_pos >= 8 ? t8 : 0.0f; }
-        if (seg_last) arow[row_slot] = acc;
+        // ---- row sum: inclusive scan over the segment's lanes (inside a 32-lane half) ---------
+        // (every lane executes the shifts; only the add is conditional).  A segment of up to
+        // 16 lanes lies inside one 16-lane row; a longer one fills an even row and continues at
+        // the start of the odd row after it, which then adds the even row's total.
+        {
+            const uint32_t rp = seg_pos & 15u;
+            { const float t1 = dpp_shr<1>(acc); acc += rp >= 1 ? t1 : 0.0f; }
+            { const float t2 = dpp_shr<2>(acc); acc += rp >= 2 ? t2 : 0.0f; }
+            { const float t4 = dpp_shr<4>(acc); acc += rp >= 4 ? t4 : 0.0f; }
+            { const float t8 = dpp_shr<8>(acc); acc += rp >= 8 ? t8 : 0.0f; }
+            // lane 15 of rows 0 and 2 to every lane of rows 1 and 3
+            const float tb = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(acc), 0x142, 0xa, 0xf, false));
+            acc += seg_pos >= 16 ? tb : 0.0f;
+        }
+        {
+            const float pre = acc + row_bias;
+            const float sg = fast_sigmoid(act == 2 ? 2.0f * pre : pre);      // one exponential serves both
+            const float th = fabsf(pre) < 0.1f ? tanh_small(pre) : fmaf(2.0f, sg, -1.0f);
+            if (seg_last) arow[row_slot] = act == 0 ? pre : (act == 1 ? sg : th);
+        }
         lds_barrier();
+        if (A.dbg && blockIdx.x == 0 && (tid & 63u) == 0) after_b = __builtin_readcyclecounter();
         if (dbg) { c1_ = __builtin_readcyclecounter(); ph1 += c1_ - c0_; c0_ = c1_; }
         // ---- gates and state of the units this workgroup owns --------------------------------
         if (owner) {
-            const float a0 = arow[tid] + b0, a1 = arow[nu + tid] + b1, a2 = arow[2 * nu + tid], a3 = arow[3 * nu + tid];
+            const float a0 = arow[tid], a1 = arow[nu + tid], a2 = arow[2 * nu + tid], a3 = arow[3 * nu + tid];
             float hn;
-            if (lstm) {                                  // rows i, f, g, o
-                const float cn = fast_sigmoid(a1) * c_state + fast_sigmoid(a0) * fast_tanh(a2 + b2);
-                hn = fast_sigmoid(a3 + b3) * fast_tanh(cn);
+            if (lstm) {                                  // activated rows i, f, g, o
+                const float cn = a1 * c_state + a0 * a2;
+                hn = a3 * fast_tanh(cn);
                 c_state = cn;
-            } else {                                     // rows r, z, n (input side), n (recurrent side)
-                const float rg = fast_sigmoid(a0), zg = fast_sigmoid(a1);
-                const float n = fast_tanh(a2 + b2 + rg * a3);
-                hn = (1.0f - zg) * n + zg * h_state;
+            } else {                                     // r, z activated; n: input side (+ bias), recurrent side
+                const float n = fast_tanh(a2 + a0 * a3);
+                hn = (1.0f - a1) * n + a1 * h_state;
             }
             h_state = hn;
             z[n_in + unit] = hn;        // next step's input, read only after the next barrier
             const unsigned long long pk = ((unsigned long long)tag_now << 32) | (unsigned long long)__float_as_uint(hn);
-            __hip_atomic_store(seq_me + (size_t)t * H + unit, pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(pub + (size_t)t * nu, pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (A.hseq && l == A.L - 1) A.hseq[(size_t)t * H + unit] = hn;
         }
         if (dbg) { c1_ = __builtin_readcyclecounter(); ph3 += c1_ - c0_; }
     }
     if (dbg) { A.dbg[0] = ph0; A.dbg[1] = ph1; A.dbg[2] = ph2; A.dbg[3] = ph3; }
+    if (A.dbg && blockIdx.x == 0 && (tid & 63u) == 0) A.dbg[8 + (tid >> 6)] = wave_arrive;
+    if (A.dbg && blockIdx.x == 0 && tid == 512) { A.dbg[5] = npolls; A.dbg[6] = delay; }
     if (owner) {
         A.hT[(size_t)l * H + unit] = h_state;
         if (A.cT && lstm) A.cT[(size_t)l * H + unit] = c_state;
@@ -546,7 +666,10 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     A.hseq = d_hseq; A.hT = d_hT; A.cT = d_cT; A.seq = seq;
     A.T = (uint32_t)T; A.L = (uint32_t)L; A.H = (uint32_t)H; A.I = (uint32_t)r->input; A.cell = (uint32_t)r->cell;
     A.tag_base = tag_base;
+    A.off_unit_wg = (uint32_t)r->plan.off_unit_wg;
     A.wg_stride = 1;
+    A.poll_delay = r->plan.n_wgs > 1 ? 8u : 0u;   // fewer polls in flight while h_t cannot have arrived yet
+    if (const char *e = getenv("CSB_RNN_POLL_DELAY")) A.poll_delay = (uint32_t)std::max(0, atoi(e));
     if (getenv("CSB_RNN_DEBUG")) A.dbg = (unsigned long long *)((uint8_t *)d_ws + wl.total - 512);
     if (const char *e = getenv("CSB_RNN_WG_STRIDE")) A.wg_stride = (uint32_t)std::max(1, atoi(e));
     size_t cmax = 0;
