@@ -211,7 +211,9 @@ class CsbMatrix:
         if Y is None:
             Y = torch.empty((self.rows, batch), dtype=torch.float32, device=X.device)
         ws = self._workspace(batch, X.device)
-        _check(lib().csb_spmm(self._h, _dptr(X), X.stride(0), _dptr(Y), Y.stride(0), batch, _dptr(ws),
+        # rows may be strided views ([cols][ldx], [rows][ldy]); the batch index must be contiguous
+        assert X.is_cuda and Y.is_cuda and X.stride(1) == 1 and Y.stride(1) == 1
+        _check(lib().csb_spmm(self._h, X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), batch, _dptr(ws),
                               _stream_ptr(stream)))
         return Y
 

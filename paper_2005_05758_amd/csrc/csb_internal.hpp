@@ -94,6 +94,7 @@ struct DevHeader {
     uint64_t rows_out, cols;
     uint64_t off_chunks, off_waves, off_groups, off_vbs, off_idx, off_vals;
     uint64_t off_nz_tiles, off_zero_tiles, off_shared, off_counters;
+    uint64_t off_tile_g0;      // [n_nz_tiles + 1] first group of every row tile that has work
     uint64_t idx_bytes, n_vals, total_bytes;
 };
 
@@ -107,12 +108,13 @@ struct DevMat {
     const float *vals;
     const uint32_t *nz_tiles;
     const uint32_t *zero_tiles;
+    const uint32_t *tile_g0;
     const SharedRec *shared;
     uint32_t *counters;
     uint32_t n_chunks, waves_per_chunk, n_zero_tiles, n_shared;
     uint32_t br, bc;
     uint32_t rows_out, cols;
-    uint32_t n_groups, reserved;
+    uint32_t n_groups, n_nz_tiles;
 };
 
 // How rows are relabelled when the image is built for a GRU: entries in rows >= split_row

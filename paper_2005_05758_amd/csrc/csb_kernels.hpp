@@ -9,4 +9,9 @@ namespace csb {
 int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const float *d_x1, float *d_y,
                   void *d_ws, void *stream, unsigned long long *d_stamps = nullptr);
 
+// Y = A Z for `batch` right-hand sides.  Element (column j, right-hand side n) of Z is
+// p0[j*sj0 + n*sn0] for j < n0 and p1[(j-n0)*sj1 + n*sn1] otherwise; Y is [rows_out][ldy].
+int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj0, int64_t sn0, const float *p1,
+                 int64_t sj1, int64_t sn1, float *d_Y, int64_t ldy, int32_t batch, void *stream);
+
 }  // namespace csb

@@ -494,6 +494,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         h.off_zero_tiles = place(zero_tiles.size() * 4);
         h.off_shared = place(shared.size() * sizeof(SharedRec));
         h.off_counters = place(shared.size() * 4);
+        h.off_tile_g0 = place(tile_g0.size() * 4);
         h.idx_bytes = idx.size(); h.n_vals = vals.size(); h.total_bytes = off;
         Plan &pl = m->plan;
         pl.image.assign(off, 0);
@@ -509,6 +510,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         put(h.off_nz_tiles, nz_tiles.data(), nz_tiles.size() * 4);
         put(h.off_zero_tiles, zero_tiles.data(), zero_tiles.size() * 4);
         put(h.off_shared, shared.data(), shared.size() * sizeof(SharedRec));
+        put(h.off_tile_g0, tile_g0.data(), tile_g0.size() * 4);
         pl.hdr = h;
         pl.split = split;
         pl.valid = true;

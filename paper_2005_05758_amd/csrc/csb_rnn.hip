@@ -600,6 +600,54 @@ __global__ void gru_gates_kernel(const float *__restrict__ a, const float *__res
     if (hseq) hseq[k] = hn;
 }
 
+// Batched element-wise parts: a is [rows][B], the state is kept as [H][B].
+__global__ void lstm_gates_batched_kernel(const float *__restrict__ a, const float *__restrict__ bias,
+                                          float *__restrict__ c, float *__restrict__ h, float *__restrict__ hseq,
+                                          const int H, const int B) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= H * B) return;
+    const int k = e / B, n = e - k * B;
+    float ai = a[(size_t)k * B + n], af = a[(size_t)(H + k) * B + n], ag = a[(size_t)(2 * H + k) * B + n],
+          ao = a[(size_t)(3 * H + k) * B + n];
+    if (bias) { ai += bias[k]; af += bias[H + k]; ag += bias[2 * H + k]; ao += bias[3 * H + k]; }
+    const float cn = sigmoidf_(af) * c[e] + sigmoidf_(ai) * tanhf(ag);
+    const float hn = sigmoidf_(ao) * tanhf(cn);
+    c[e] = cn;
+    h[e] = hn;
+    if (hseq) hseq[(size_t)n * H + k] = hn;
+}
+
+__global__ void gru_gates_batched_kernel(const float *__restrict__ a, const float *__restrict__ bias,
+                                         float *__restrict__ h, float *__restrict__ hseq, const int H, const int B) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= H * B) return;
+    const int k = e / B, n = e - k * B;
+    float ar = a[(size_t)k * B + n], az = a[(size_t)(H + k) * B + n], anx = a[(size_t)(2 * H + k) * B + n];
+    const float anh = a[(size_t)(3 * H + k) * B + n];
+    if (bias) { ar += bias[k]; az += bias[H + k]; anx += bias[2 * H + k]; }
+    const float r = sigmoidf_(ar), z = sigmoidf_(az);
+    const float nn = tanhf(anx + r * anh);
+    const float hn = (1.0f - z) * nn + z * h[e];
+    h[e] = hn;
+    if (hseq) hseq[(size_t)n * H + k] = hn;
+}
+
+// [L][B][H] (caller's layout) <-> [L][H][B] (internal); src may be null (zeros).
+__global__ void state_in_kernel(float *__restrict__ dst, const float *__restrict__ src, int L, int B, int H) {
+    const size_t n = (size_t)L * B * H;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t l = i / ((size_t)H * B), rem = i - l * H * B, k = rem / B, b = rem - k * B;
+        dst[i] = src ? src[(l * B + b) * H + k] : 0.0f;
+    }
+}
+__global__ void state_out_kernel(float *__restrict__ dst, const float *__restrict__ src, int L, int B, int H) {
+    const size_t n = (size_t)L * B * H;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t l = i / ((size_t)H * B), rem = i - l * H * B, b = rem / H, k = rem - b * H;
+        dst[i] = src[(l * H + k) * B + b];
+    }
+}
+
 __global__ void fill_kernel(float *p, size_t n, float v) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -621,7 +669,7 @@ static void init_state(float *dst, const float *src, size_t n, hipStream_t st) {
 static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 struct RnnWs {
-    size_t off_a, off_c, off_part, off_biasptr, off_seq, total;
+    size_t off_a, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, total;
 };
 
 static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
@@ -633,11 +681,15 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
         rows_out = std::max<size_t>(rows_out, (size_t)m->plan.hdr.rows_out);
         part = std::max<size_t>(part, (size_t)m->plan.hdr.n_partial_slots * m->plan.hdr.br * 8);
     }
-    w.off_a = off; off = align256(off + rows_out * sizeof(float));
+    w.off_a = off; off = align256(off + rows_out * sizeof(float) * (size_t)batch);
     w.off_c = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     w.off_part = off; off = align256(off + part);
     w.off_biasptr = off; off = align256(off + (size_t)r->n_layers * sizeof(void *));
     w.off_seq = off; off = align256(off + (size_t)r->n_layers * (size_t)std::max(T, 1) * r->hidden * 8);
+    if (batch > 1) {
+        w.off_hint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
+        w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
+    }
     off += 512;   // last 512 bytes: debug clocks of the resident kernel
     w.total = off;
     return w;
@@ -793,6 +845,36 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
 
     const RnnWs wl = ws_layout(r, batch, T);
     float *a = (float *)((uint8_t *)d_ws + wl.off_a);
+    if (batch > 1) {
+        // batched: one MFMA mat-mat launch and one gate launch per step and layer; the state
+        // lives as [H][B] so that the batch index is the contiguous one
+        float *hi = (float *)((uint8_t *)d_ws + wl.off_hint), *ci = (float *)((uint8_t *)d_ws + wl.off_cint);
+        const int sblocks = (int)std::min<size_t>((nstate + 255) / 256, 2048);
+        hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, hi, d_h0, L, batch, H);
+        if (lstm) hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, ci, d_c0, L, batch, H);
+        const int gb = (H * batch + 255) / 256;
+        for (int t = 0; t < T; ++t)
+            for (int l = 0; l < L; ++l) {
+                float *hl = hi + (size_t)l * H * batch;
+                int rc;
+                if (l == 0)
+                    rc = spmm_strided(r->W[l], d_x + (size_t)t * batch * I, (uint32_t)I, 1, I, hl, batch, 1, a, batch, batch, st);
+                else
+                    rc = spmm_strided(r->W[l], hi + (size_t)(l - 1) * H * batch, (uint32_t)H, batch, 1, hl, batch, 1, a, batch, batch, st);
+                if (rc != CSB_OK) return rc;
+                float *hs = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * batch * H : nullptr;
+                if (lstm)
+                    hipLaunchKernelGGL(lstm_gates_batched_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l],
+                                       ci + (size_t)l * H * batch, hl, hs, H, batch);
+                else
+                    hipLaunchKernelGGL(gru_gates_batched_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l], hl, hs, H, batch);
+            }
+        hipLaunchKernelGGL(state_out_kernel, dim3(sblocks), dim3(256), 0, st, d_hT, hi, L, batch, H);
+        if (lstm && d_cT) hipLaunchKernelGGL(state_out_kernel, dim3(sblocks), dim3(256), 0, st, d_cT, ci, L, batch, H);
+        hipError_t eb = hipGetLastError();
+        if (eb != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(eb)); return CSB_EDEVICE; }
+        return CSB_OK;
+    }
     float *c = (lstm && d_cT) ? d_cT : (float *)((uint8_t *)d_ws + wl.off_c);
     void *part = (uint8_t *)d_ws + wl.off_part;
     // the outputs double as the running state
@@ -820,10 +902,3 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
 }
 
 extern "C" void csb_rnn_free(csb_rnn *r) { delete r; }
-
-extern "C" int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int64_t ldy,
-                        int32_t batch, void *d_ws, void *stream) {
-    (void)m; (void)d_X; (void)ldx; (void)d_Y; (void)ldy; (void)batch; (void)d_ws; (void)stream;
-    csb::set_error("csb_spmm: not built yet");
-    return CSB_EUNSUPPORTED;
-}

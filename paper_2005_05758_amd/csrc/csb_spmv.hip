@@ -36,6 +36,8 @@ DevMat dev_mat(const csb_matrix *m) {
     d.br = h.br; d.bc = h.bc;
     d.rows_out = (uint32_t)h.rows_out; d.cols = (uint32_t)h.cols;
     d.n_groups = h.n_groups;
+    d.n_nz_tiles = h.n_nz_tiles;
+    d.tile_g0 = (const uint32_t *)(b + h.off_tile_g0);
     return d;
 }
 

@@ -84,6 +84,24 @@ def test_rnn_workloads_full_size(name):
     run_case(wl, tag=name)
 
 
+def test_rnn_batched_two_layer_shape():
+    """cfg4's shape (2 x LSTM 1024 -> 1024, block 64, 25x, batch 64) on the MFMA path; T is cut
+    to 4 so that the float64 oracle finishes in seconds."""
+    cfg = csb_inputs.CONFIGS["cfg4"]
+    wl = csb_inputs.make_rnn(cfg, T=4)
+    run_case(wl, tag="cfg4-T4", resident=False)
+
+
+@pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
+def test_rnn_batched_ragged(cell):
+    cfg = csb_inputs.RnnConfig("t", cell, 2, 37, 70, 16, 4.0, "binomial", 0.3, 19, 6, 3)
+    wl = csb_inputs.make_rnn(cfg)
+    rng = np.random.default_rng(4)
+    h0 = rng.uniform(-0.5, 0.5, (2, 19, 70)).astype(np.float32).astype(np.float64)
+    c0 = rng.uniform(-0.5, 0.5, (2, 19, 70)).astype(np.float32).astype(np.float64)
+    run_case(wl, h0, c0 if cell == csb_inputs.LSTM else None, tag="batched-ragged", resident=False)
+
+
 @pytest.mark.parametrize("batch,resident", [(2, False), (1, False), (1, True)])
 @pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
 def test_rnn_resume_and_T0(cell, batch, resident):
