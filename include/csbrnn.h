@@ -162,7 +162,8 @@ int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws, void
  * Sec. 6.1): same result, and every workgroup also writes shader-clock stamps to d_stamps
  * (device, csb_debug_stamp_count(m) values of 64 bits).  Per workgroup: 8 phase stamps
  * (start, loads issued, staged in LDS, mat-vec done, tile sums written, end, 2 unused), then
- * a begin/end pair for each of its 16 wavefronts around the wavefront's mat-vec share.
+ * three stamps for each of its 16 wavefronts: begin of its mat-vec share, its kernel values
+ * arrived, end of the share.
  */
 size_t csb_debug_stamp_count(const csb_matrix *m);
 int csb_debug_spmv_stamps(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws,

@@ -195,7 +195,7 @@ class CsbMatrix:
         return y
 
     def spmv_stamps(self, x, y=None, stream=None):
-        """csb_debug_spmv_stamps: returns (y, stamps [n_chunks, 8 + 2*16] int64 tensor)."""
+        """csb_debug_spmv_stamps: returns (y, stamps [n_chunks, 8 + 3*16] int64 tensor)."""
         import torch
         if y is None:
             y = torch.empty(self.rows, dtype=torch.float32, device=x.device)
@@ -203,7 +203,7 @@ class CsbMatrix:
         st = torch.zeros(n, dtype=torch.int64, device=x.device)
         ws = self._workspace(1, x.device)
         _check(lib().csb_debug_spmv_stamps(self._h, _dptr(x), _dptr(y), _dptr(ws), _dptr(st), _stream_ptr(stream)))
-        return y, st.view(-1, 8 + 2 * 16)
+        return y, st.view(-1, 8 + 3 * 16)
 
     def spmm(self, X, Y=None, stream=None):
         import torch

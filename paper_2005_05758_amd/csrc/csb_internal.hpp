@@ -14,27 +14,30 @@ namespace csb {
 constexpr int kWave = 64;             // gfx950 wavefront width
 constexpr int kMaxVbPerGroup = 16;    // virtual blocks packed into one 64-lane group
 constexpr int kGroupOverhead = 8;     // per-group fixed cost in the work model (steps)
+constexpr int kStepQuantum = 2;       // a group's column steps are padded to, and cut at, multiples of this
 constexpr int kAccRowsMax = 256;      // output-row slots one workgroup accumulates in LDS
-constexpr int kMaxStageCols = 20480;  // input vector floats staged in LDS (80 KB)
-constexpr int kChunkValsMax = 28672;  // floats of the value stream one workgroup keeps in LDS
-constexpr int kChunkMetaMax = 20480;  // bytes of group/block/index records per workgroup
+constexpr int kAccPlanes = 4;         // accumulator copies per wavefront: lanes that share a row use different copies
+constexpr int kMaxStageCols = 16383;  // input vector floats staged in LDS; byte offsets fit 16 bits
+constexpr int kChunkMetaMax = 24576;  // bytes of group/block/index records per workgroup
 constexpr int kLdsBudget = 160 * 1024 - 2048;  // gfx950 LDS per workgroup, minus slack
 
 // ---- device image records (plain structs, identical on host and device) ----------
 
 // A group: up to 64 kernel-matrix rows of up to 16 virtual blocks of ONE output row
-// tile, lanes ordered so that the virtual blocks' column counts descend.  Its values are
-// stored step-major: for column step j, the lanes whose block still has a column j
-// (always a prefix of the lanes) contribute one float each, contiguous.
+// tile, one row per lane.  Its values are stored step-major with a fixed stride: column
+// step j is a run of 64 floats, lane l's value at [j * 64 + l], zero where the lane has no
+// row or its block has no column j.  Every kernel value is stored once; the zeros are
+// what keeps the inner loop free of address arithmetic and predicates.
 struct GroupRec {
     uint32_t val_off;   // float index of (step 0, lane 0) in the value stream
-    uint32_t idx_off;   // byte offset in the index stream: lane descriptors, column lists
     uint32_t vb_off;    // first VbRec of the group
+    uint32_t idx_off;   // byte offset in the index stream: lane descriptors, input-offset lists
     uint32_t nzrank;    // rank of the group's output tile among tiles that have work
-    uint16_t cmax;      // column steps of the group (largest column count)
+    uint16_t cmax;      // column steps of the group: largest column count, rounded up to kStepQuantum
     uint8_t nvb;        // virtual blocks
     uint8_t nlanes;     // kernel-matrix rows (lanes in use)
-    uint32_t nvals;     // floats of the group in the value stream
+    uint16_t nrounds;   // the largest number of lanes that share one output row
+    uint16_t pad;
 };
 static_assert(sizeof(GroupRec) == 24, "GroupRec layout");
 
@@ -45,7 +48,7 @@ struct VbRec {
     uint8_t lane0;      // first lane
     uint16_t c;         // columns
     uint16_t bj;        // block column: input base index = bj * bc
-    uint16_t coloff4;   // column list offset inside the group's index bytes, 4-byte units
+    uint16_t coloff4;   // offset of the block's input-offset list behind the lane descriptors, 4-byte units
 };
 static_assert(sizeof(VbRec) == 8, "VbRec layout");
 
@@ -54,9 +57,9 @@ static_assert(sizeof(VbRec) == 8, "VbRec layout");
 struct WaveRec {
     uint32_t g_begin, g_end;
     uint16_t j_begin, j_end;
-    uint32_t val_begin;  // float offset inside group g_begin of step j_begin
-    uint32_t v_begin;    // absolute float index of the wavefront's first value
-    uint32_t v_end;      // one past its last value
+    uint32_t val_begin;  // float offset inside group g_begin of step j_begin (j_begin * 64)
+    uint32_t v_begin;    // absolute float index of the wavefront's first value; its steps are the
+    uint32_t v_end;      // consecutive runs of 64 floats up to v_end
     uint32_t pad[2];
 };
 static_assert(sizeof(WaveRec) == 32, "WaveRec layout");
@@ -70,8 +73,8 @@ struct ChunkRec {
     uint32_t vb0, nvbs;  // their virtual-block records
     uint32_t idx0;       // their index bytes: start, rounded down to 16
     uint32_t idx_bytes;  // length from idx0, rounded up to 16
-    uint32_t v0;         // first value of the workgroup's window (float index, multiple of 4)
-    uint32_t nv4;        // window length in float4
+    uint32_t v0;         // first value of the workgroup's run of the value stream (float index, multiple of 64)
+    uint32_t nv4;        // length of the run in float4
     uint32_t pad[2];
 };
 static_assert(sizeof(ChunkRec) == 64, "ChunkRec layout");
@@ -89,7 +92,7 @@ struct DevHeader {
     uint32_t n_chunks, waves_per_chunk, n_groups, n_vbs;
     uint32_t n_shared, n_zero_tiles, n_nz_tiles, n_partial_slots;
     uint32_t br, bc;
-    uint32_t max_chunk_tiles, chunk_vals_cap;  // LDS sizing: tiles per chunk, floats per chunk
+    uint32_t max_chunk_tiles, chunk_vals_cap;  // LDS sizing: tiles per chunk; (unused)
     uint32_t meta_cap, reserved0;              // bytes of records per chunk
     uint64_t rows_out, cols;
     uint64_t off_chunks, off_waves, off_groups, off_vbs, off_idx, off_vals;

@@ -33,12 +33,8 @@ struct Group {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Values a group holds before column step j (lanes are ordered by descending c).
-uint32_t vals_before_step(const std::vector<Vb> &vb, const Group &g, int j) {
-    uint32_t n = 0;
-    for (uint32_t k : g.vbs) n += (uint32_t)vb[k].r() * (uint32_t)std::min(j, vb[k].c());
-    return n;
-}
+// Floats a group holds before column step j (every step is a run of 64).
+uint32_t vals_before_step(const std::vector<Vb> &, const Group &, int j) { return (uint32_t)j * kWave; }
 
 }  // namespace
 
@@ -136,6 +132,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                     g.cmax = std::max(g.cmax, v.c());
                     if ((int)g.vbs.size() == kMaxVbPerGroup || g.nlanes == kWave) break;
                 }
+                g.cmax = (g.cmax + kStepQuantum - 1) / kStepQuantum * kStepQuantum;
                 groups.push_back(std::move(g));
             }
         }
@@ -147,49 +144,87 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         std::vector<uint8_t> idx;
         std::vector<float> vals;
         std::vector<uint32_t> idx_end(n_groups);   // end of each group's index bytes
-        vals.reserve(m->val.size());
+        vals.reserve(m->val.size() + m->val.size() / 4);
         uint64_t fma_steps = 0;
+        size_t nnz_placed = 0;
         for (uint32_t gi = 0; gi < n_groups; ++gi) {
             const Group &g = groups[gi];
             GroupRec &gr = grecs[gi];
             gr.val_off = (uint32_t)vals.size();
+            while (idx.size() % 8) idx.push_back(0);
             gr.idx_off = (uint32_t)idx.size();
             gr.vb_off = (uint32_t)vrecs.size();
             gr.nzrank = tile_rank[g.tile];
             gr.cmax = (uint16_t)g.cmax;
             gr.nvb = (uint8_t)g.vbs.size();
             gr.nlanes = (uint8_t)g.nlanes;
-            // lane descriptors: row slot | (vb number << 8)
-            for (size_t k = 0; k < g.vbs.size(); ++k)
-                for (uint8_t s : vbs[g.vbs[k]].slot) { idx.push_back(s); idx.push_back((uint8_t)k); }
-            while (idx.size() % 4) idx.push_back(0);
+            // lane descriptors, 4 bytes per lane: row slot; block number (low 4 bits) and scatter
+            // round (high 4 bits); 16-bit byte offset of the block's input-offset list from idx_off
+            // (filled in below).  Lanes of one round have distinct row slots, so a round adds its
+            // row results to the accumulator without conflicts.
+            const size_t desc_base = idx.size();
+            {
+                uint8_t seen_rows[CSB_MAX_BLOCK] = {0};
+                int rounds = 0;
+                for (size_t k = 0; k < g.vbs.size(); ++k)
+                    for (uint8_t s : vbs[g.vbs[k]].slot) {
+                        const int rank = seen_rows[s]++;
+                        rounds = std::max(rounds, rank + 1);
+                        idx.push_back(s); idx.push_back((uint8_t)(k | (size_t)rank << 4)); idx.push_back(0); idx.push_back(0);
+                    }
+                gr.nrounds = (uint16_t)rounds;
+            }
+            while (idx.size() % 8) idx.push_back(0);
             const size_t col_base = idx.size();
+            const int cpad = (g.cmax + 3) & ~3;            // list length: lists stay 8-byte aligned
+            const uint16_t zero_off = (uint16_t)(m->cols * 4);   // byte offset of the zero entry behind the input vector
             int lane0 = 0;
             for (size_t k = 0; k < g.vbs.size(); ++k) {
                 const Vb &v = vbs[g.vbs[k]];
                 VbRec vr{};
                 vr.r = (uint8_t)v.r(); vr.lane0 = (uint8_t)lane0; vr.c = (uint16_t)v.c(); vr.bj = v.bj;
                 vr.coloff4 = (uint16_t)((idx.size() - col_base) / 4);
+                const size_t list_off = idx.size() - gr.idx_off;
+                if (list_off > 0xffff) { set_error("csb_plan: internal: list offset"); return CSB_EINVAL; }
+                for (int q = 0; q < v.r(); ++q) {
+                    idx[desc_base + 4 * (size_t)(lane0 + q) + 2] = (uint8_t)(list_off & 0xff);
+                    idx[desc_base + 4 * (size_t)(lane0 + q) + 3] = (uint8_t)(list_off >> 8);
+                }
                 const uint16_t *ci = m->colidx.data() + m->col_off[v.b];
-                for (int q = v.q0; q < v.q1; ++q) idx.push_back((uint8_t)ci[q]);
-                while (idx.size() % 4) idx.push_back(0);
+                // byte offsets of the block's inputs in the staged vector, then the zero entry
+                for (int j = 0; j < cpad; ++j) {
+                    const uint16_t o = j < v.c() ? (uint16_t)(((uint32_t)v.bj * (uint32_t)bc + ci[v.q0 + j]) * 4u) : zero_off;
+                    idx.push_back((uint8_t)(o & 0xff));
+                    idx.push_back((uint8_t)(o >> 8));
+                }
                 vrecs.push_back(vr);
                 lane0 += v.r();
             }
+            while (idx.size() % 8) idx.push_back(0);
             idx_end[gi] = (uint32_t)idx.size();
-            // values, step-major
-            for (int j = 0; j < g.cmax; ++j)
+            // values: step j is a run of 64 floats, lane l at [j * 64 + l], zero where unused
+            {
+                const size_t base = vals.size();
+                vals.resize(base + (size_t)g.cmax * kWave, 0.0f);
+                int l0 = 0;
                 for (uint32_t k : g.vbs) {
                     const Vb &v = vbs[k];
-                    if (j >= v.c()) continue;
                     const int nc = m->ncols[v.b];
                     const float *src = m->val.data() + m->val_off[v.b];
-                    for (uint16_t a : v.a) vals.push_back(src[(size_t)a * nc + v.q0 + j]);
+                    if (v.c() > g.cmax) { set_error("csb_plan: internal: group step count"); return CSB_EINVAL; }
+                    for (int j = 0; j < v.c(); ++j)
+                        for (int q = 0; q < v.r(); ++q)
+                            vals[base + (size_t)j * kWave + l0 + q] = src[(size_t)v.a[q] * nc + v.q0 + j];
+                    l0 += v.r();
+                    nnz_placed += (size_t)v.r() * v.c();
                 }
-            gr.nvals = (uint32_t)vals.size() - gr.val_off;
+            }
             fma_steps += (uint64_t)g.cmax;
         }
-        if (vals.size() != m->val.size()) { set_error("csb_plan: internal: value count mismatch"); return CSB_EINVAL; }
+        if (nnz_placed != m->val.size()) { set_error("csb_plan: internal: value count mismatch"); return CSB_EINVAL; }
+        if (vals.size() + kWave >= (1ull << 32)) { set_error("csb_plan: matrix too large for 32-bit device offsets"); return CSB_EUNSUPPORTED; }
+        const size_t vals_end = vals.size();
+        vals.resize(vals_end + kWave, 0.0f);   // a wavefront without work still issues one (unused) load
 
         // ---- 4. cost axis, chunk and wave cuts -----------------------------------------
         // Group g occupies [P[g], P[g+1]) with P[g+1]-P[g] = overhead + cmax; a cut inside
@@ -200,16 +235,17 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         const uint64_t total = P[n_groups];
         // LDS sizing: input vector + per-wavefront value windows + records + accumulators
         const uint32_t acc_rows_cap = (uint32_t)std::max(kAccRowsMax, br);
-        const size_t zbytes = align_up((size_t)m->cols, 64) * 4;
+        const size_t zbytes = align_up((size_t)m->cols + 1, 64) * 4;   // input vector + the zero entry
         if (m->cols > kMaxStageCols) {
             set_error("csb_plan: more columns than the LDS staging of the input vector covers");
             return CSB_EUNSUPPORTED;
         }
         int n_chunks = n_chunks_req;
         if (n_chunks == 0) {
-            // default: one workgroup per CU of an MI355X (256) once every wavefront has a few
-            // groups of work; more when the per-wavefront value window would overflow
-            const uint64_t per_wave_min = 5 * (kGroupOverhead + 8);
+            // default: one workgroup per CU of an MI355X (256) once every wavefront has a group's
+            // worth of work: a launch costs several microseconds of dependent latencies whatever
+            // its size, so a small matrix is spread over many workgroups rather than few
+            const uint64_t per_wave_min = kGroupOverhead + 4;
             uint64_t want = total / (per_wave_min * (uint64_t)NW);
             want = std::min<uint64_t>(std::max<uint64_t>(want, 1), 256);
             n_chunks = (int)want;
@@ -220,10 +256,10 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
             uint32_t g = (uint32_t)(std::upper_bound(P.begin(), P.end(), X) - P.begin() - 1);
             const uint64_t in = X - P[g];
             if (in <= (uint64_t)kGroupOverhead) return Pos{g, 0};
-            return Pos{g, (uint32_t)(in - kGroupOverhead)};
+            return Pos{g, (uint32_t)(in - kGroupOverhead) / kStepQuantum * kStepQuantum};
         };
         auto abs_val = [&](Pos p) -> uint32_t {
-            if (p.g >= n_groups) return (uint32_t)vals.size();
+            if (p.g >= n_groups) return (uint32_t)vals_end;
             return grecs[p.g].val_off + vals_before_step(vbs, groups[p.g], (int)p.j);
         };
         const uint32_t max_tiles_per_chunk = (uint32_t)std::max<uint32_t>(1, acc_rows_cap / br);
@@ -235,14 +271,13 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         const size_t n_nz = nz_tiles.size();
         std::vector<uint32_t> tile_g0(n_nz + 1, n_groups);
         for (uint32_t g = n_groups; g-- > 0;) tile_g0[tile_rank[groups[g].tile]] = g;
-        auto tile_vals = [&](size_t r) { return (r + 1 < n_nz ? grecs[tile_g0[r + 1]].val_off : (uint32_t)vals.size()) - grecs[tile_g0[r]].val_off; };
         auto tile_meta = [&](size_t r) {
             const uint32_t ga = tile_g0[r], gb = tile_g0[r + 1] - 1;
             return (size_t)(gb - ga + 1) * sizeof(GroupRec) + (size_t)(grecs[gb].vb_off + grecs[gb].nvb - grecs[ga].vb_off) * sizeof(VbRec) +
                    (idx_end[gb] - grecs[ga].idx_off) + 64;
         };
-        auto lds_for = [&](size_t nvals, size_t meta, size_t ntile) {
-            return zbytes + (align_up(nvals + 8, 64) + 64) * 4 + align_up(meta, 256) + (size_t)NW * ntile * br * 4;
+        auto lds_for = [&](size_t meta, size_t ntile) {
+            return zbytes + align_up(meta, 256) + (size_t)NW * kAccPlanes * ntile * br * 4 + 4 * (size_t)kAccRowsMax * 4;
         };
         // Whole-tile chunks: contiguous tile ranges, smallest possible largest cost for at most
         // n_target chunks.  No output tile is then shared between workgroups.
@@ -256,21 +291,21 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                 while (r < n_nz) {
                     ++used;
                     uint64_t cost = 0;
-                    size_t nv = 0, mb = 0, nt = 0;
+                    size_t mb = 0, nt = 0;
                     while (r < n_nz) {
                         const uint64_t tc = P[tile_g0[r + 1]] - P[tile_g0[r]];
-                        const size_t tv = tile_vals(r), tm = tile_meta(r);
-                        const bool fits = nt + 1 <= max_tiles_per_chunk && lds_for(nv + tv, mb + tm, nt + 1) <= (size_t)kLdsBudget &&
-                                          nv + tv + 8 <= (size_t)kChunkValsMax && mb + tm <= (size_t)kChunkMetaMax;
+                        const size_t tm = tile_meta(r);
+                        const bool fits = nt + 1 <= max_tiles_per_chunk && lds_for(mb + tm, nt + 1) <= (size_t)kLdsBudget &&
+                                          mb + tm <= (size_t)kChunkMetaMax;
                         if (nt == 0 && !fits) return -1;            // a single tile does not fit
                         if (!fits || (nt > 0 && cost + tc > Tmax)) break;
-                        cost += tc; nv += tv; mb += tm; ++nt; ++r;
+                        cost += tc; mb += tm; ++nt; ++r;
                     }
                     if (cuts) cuts->push_back(r < n_nz ? P[tile_g0[r]] : total);
                 }
                 return used;
             };
-            if (fill_tiles(total, nullptr) > 0 && (mode == 1 || n_nz >= n_target)) {
+            if (fill_tiles(total, nullptr) > 0 && (mode == 1 || 2 * n_nz >= n_target)) {   // merging shared tiles costs more than a moderate imbalance
                 uint64_t lo = 1, hi = total;
                 while (lo < hi) {
                     const uint64_t mid = (lo + hi) / 2;
@@ -316,18 +351,14 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
             waves.assign((size_t)nc * NW, WaveRec{});
             cpos_a.assign(nc, Pos{0, 0});
             cpos_b.assign(nc, Pos{0, 0});
-            wave_cost.assign(waves.size(), 0.0);
-            uint32_t win_max = 0, tiles_max = 1;
+            wave_cost.assign((size_t)nc * NW, 0.0);
+            uint32_t tiles_max = 1;
             size_t meta_max = 64;
-            for (int c = 0; c < nc; ++c) {
-                const uint64_t Xa = chunk_cut[c], Xb = chunk_cut[c + 1];
-                cpos_a[c] = locate(Xa);
-                cpos_b[c] = locate(Xb);
-                // Wavefront cuts inside the chunk: smallest share T such that a greedy fill
-                // (a wavefront that resumes inside a group pays the group overhead again)
-                // needs at most NW wavefronts.
-                const Pos ca = cpos_a[c], cb = cpos_b[c];
-                auto before = [&](Pos p, Pos q) { return p.g < q.g || (p.g == q.g && p.j < q.j); };
+            auto before = [&](Pos p, Pos q) { return p.g < q.g || (p.g == q.g && p.j < q.j); };
+            // Wavefront cuts inside [ca, cb): smallest share T such that a greedy fill (a
+            // wavefront that resumes inside a group pays the group overhead again) needs at
+            // most NW wavefronts.
+            auto cut_waves = [&](Pos ca, Pos cb, WaveRec *out, double *cost_out) {
                 auto fill = [&](uint64_t T, std::vector<Pos> *cuts) -> bool {
                     Pos p = ca;
                     int used = 0;
@@ -345,8 +376,9 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                             if (rem <= budget) {
                                 budget -= rem;
                                 if (p.g == cb.g) p = cb; else p = Pos{p.g + 1, 0};
-                            } else {
-                                p.j += (uint32_t)budget;
+                            } else {                       // rem > budget; both positions stay multiples of the quantum
+                                p.j += std::max<uint32_t>((uint32_t)budget / kStepQuantum * kStepQuantum, kStepQuantum);
+                                if (p.j >= lim) { if (p.g == cb.g) p = cb; else p = Pos{p.g + 1, 0}; }
                                 budget = 0;
                             }
                             first = false;
@@ -356,7 +388,9 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                     }
                     return true;
                 };
-                uint64_t lo = 1, hi = std::max<uint64_t>(Xb - Xa, 1) + 2 * kGroupOverhead + 2;
+                uint64_t span = 2 * kGroupOverhead + 2;
+                for (uint32_t g = ca.g; g <= cb.g && g < n_groups; ++g) span += kGroupOverhead + groups[g].cmax;
+                uint64_t lo = 1, hi = span;
                 while (lo < hi) {
                     const uint64_t mid = (lo + hi) / 2;
                     if (fill(mid, nullptr)) hi = mid; else lo = mid + 1;
@@ -366,10 +400,10 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                 while ((int)cuts.size() < NW + 1) cuts.push_back(cb);
                 for (int w = 0; w < NW; ++w) {
                     const Pos a = cuts[w], b = cuts[w + 1];
-                    WaveRec &wr = waves[(size_t)c * NW + w];
+                    WaveRec &wr = out[w];
                     wr.g_begin = a.g; wr.j_begin = (uint16_t)a.j;
                     wr.g_end = b.g; wr.j_end = (uint16_t)b.j;
-                    wr.val_begin = a.g < n_groups ? vals_before_step(vbs, groups[a.g], (int)a.j) : 0;
+                    wr.val_begin = a.j * kWave;
                     wr.v_begin = abs_val(a);
                     wr.v_end = abs_val(b);
                     double cost = 0;
@@ -378,8 +412,15 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                         const int jhi = g == b.g ? (int)b.j : groups[g].cmax;
                         if (jhi > jlo) cost += kGroupOverhead + (jhi - jlo);
                     }
-                    wave_cost[(size_t)c * NW + w] = cost;
+                    cost_out[w] += cost;
                 }
+            };
+            for (int c = 0; c < nc; ++c) {
+                const uint64_t Xa = chunk_cut[c], Xb = chunk_cut[c + 1];
+                cpos_a[c] = locate(Xa);
+                cpos_b[c] = locate(Xb);
+                const Pos ca = cpos_a[c], cb = cpos_b[c];
+                cut_waves(ca, cb, &waves[(size_t)c * NW], &wave_cost[(size_t)c * NW]);
                 // record bytes and tiles of this chunk
                 {
                     uint32_t ga = ca.g, gb = cb.g;
@@ -392,13 +433,11 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                                           align_up((grecs[gb].vb_off + grecs[gb].nvb - grecs[ga].vb_off) * sizeof(VbRec), 16) +
                                           align_up(idx_end[gb] - i0, 16);
                         meta_max = std::max(meta_max, mb);
-                        win_max = std::max<uint32_t>(win_max, abs_val(cb) - (abs_val(ca) & ~3u));
                         tiles_max = std::max<uint32_t>(tiles_max, tile_rank[groups[gb].tile] - tile_rank[groups[ga].tile] + 1);
                     }
                 }
             }
-            const size_t lds_need = lds_for(win_max, meta_max, tiles_max);
-            const bool fits = lds_need <= (size_t)kLdsBudget && win_max + 8 <= (uint32_t)kChunkValsMax;
+            const bool fits = lds_for(meta_max, tiles_max) <= (size_t)kLdsBudget && meta_max <= (size_t)kChunkMetaMax + 64;
             if (fits) { n_chunks = nc; break; }
             whole_tiles = false;
             if (n_chunks_req == 0) n_chunks = nc < 256 ? std::min(256, nc * 2) : (nc / 256 + 1) * 256;   // whole rounds of 256 CUs
@@ -458,8 +497,8 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
             cr.vb0 = grecs[ga].vb_off; cr.nvbs = grecs[gb].vb_off + grecs[gb].nvb - cr.vb0;
             cr.idx0 = grecs[ga].idx_off & ~15u;
             cr.idx_bytes = (uint32_t)align_up(idx_end[gb] - cr.idx0, 16);
-            cr.v0 = abs_val(cpos_a[c]) & ~3u;
-            cr.nv4 = (abs_val(cpos_b[c]) - cr.v0 + 3u) >> 2;
+            cr.v0 = abs_val(cpos_a[c]);
+            cr.nv4 = (abs_val(cpos_b[c]) - cr.v0) >> 2;
             const uint32_t mb = (uint32_t)(align_up(cr.ng * sizeof(GroupRec), 16) + align_up(cr.nvbs * sizeof(VbRec), 16) + cr.idx_bytes);
             meta_cap = std::max(meta_cap, mb);
         }
@@ -474,11 +513,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         h.n_shared = (uint32_t)shared.size(); h.n_zero_tiles = (uint32_t)zero_tiles.size();
         h.n_nz_tiles = (uint32_t)nz_tiles.size(); h.n_partial_slots = n_partial_slots;
         h.max_chunk_tiles = 1;
-        {
-            uint32_t wmax = 16;
-            for (const ChunkRec &cr : chunks) wmax = std::max(wmax, cr.nv4);
-            h.chunk_vals_cap = (uint32_t)align_up((size_t)wmax * 4, 64);   // floats the kernel reserves
-        }
+        h.chunk_vals_cap = 0;
         h.meta_cap = (uint32_t)align_up(meta_cap, 256);
         for (const ChunkRec &cr : chunks) h.max_chunk_tiles = std::max(h.max_chunk_tiles, cr.ntiles);
         h.br = (uint32_t)br; h.bc = (uint32_t)bc; h.rows_out = (uint64_t)rows_out; h.cols = (uint64_t)m->cols;
@@ -495,7 +530,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         h.off_shared = place(shared.size() * sizeof(SharedRec));
         h.off_counters = place(shared.size() * 4);
         h.off_tile_g0 = place(tile_g0.size() * 4);
-        h.idx_bytes = idx.size(); h.n_vals = vals.size(); h.total_bytes = off;
+        h.idx_bytes = idx.size(); h.n_vals = vals_end; h.total_bytes = off;
         Plan &pl = m->plan;
         pl.image.assign(off, 0);
         uint8_t *im = pl.image.data();
@@ -602,18 +637,39 @@ int validate_plan(const csb_matrix *m) {
     for (uint32_t c = 0; c < h.n_chunks; ++c) {
         const ChunkRec &cr = chunks[c];
         if (cr.ntiles * br > (uint32_t)std::max<int>(kAccRowsMax, (int)br)) return fail("chunk tile span");
-        if (4 * (uint64_t)cr.nv4 > h.chunk_vals_cap || (cr.v0 & 3u) || (uint64_t)cr.v0 + 4 * (uint64_t)cr.nv4 > h.n_vals + 16) return fail("chunk value window");
+        if ((cr.v0 & 63u) || (cr.nv4 & 15u) || (uint64_t)cr.v0 + 4 * (uint64_t)cr.nv4 > h.n_vals) return fail("chunk value window");
         if ((uint64_t)cr.g0 + cr.ng > h.n_groups || (uint64_t)cr.vb0 + cr.nvbs > h.n_vbs ||
             (uint64_t)cr.idx0 + cr.idx_bytes > h.idx_bytes + 64) return fail("chunk record window");
         if (align_up(cr.ng * sizeof(GroupRec), 16) + align_up(cr.nvbs * sizeof(VbRec), 16) + cr.idx_bytes > h.meta_cap)
             return fail("chunk record window larger than its LDS space");
         if (cr.nzrank0 + cr.ntiles > h.n_nz_tiles) return fail("chunk tile rank");
-        for (uint32_t w = 0; w < NW; ++w) {
-            const WaveRec &wr = waves[(size_t)c * NW + w];
+        uint32_t v_expect = cr.v0;   // the wavefronts' value runs tile the chunk's run in order
+        for (uint32_t sw = 0; sw < NW; ++sw) {
+            const WaveRec &wr = waves[(size_t)c * NW + sw];
+            const uint32_t half_lo = cr.v0, half_hi = cr.v0 + 4 * cr.nv4;
+            if (wr.v_begin < wr.v_end) {
+                if (wr.v_begin != v_expect || ((wr.v_end - wr.v_begin) & 63u)) return fail("wave value run");
+                v_expect = wr.v_end;
+            }
             if (wr.g_begin > h.n_groups || wr.g_end > h.n_groups || wr.g_begin > wr.g_end) return fail("wave range");
             if (wr.v_begin > wr.v_end || wr.v_end > h.n_vals) return fail("wave value range");
-            if (wr.v_begin < wr.v_end && (wr.v_begin < cr.v0 || wr.v_end > cr.v0 + 4 * cr.nv4)) return fail("wave values outside the chunk window");
+            if (wr.v_begin < wr.v_end && (wr.v_begin < half_lo || wr.v_end > half_hi)) return fail("wave values outside the chunk's run");
             if (wr.g_begin < h.n_groups && wr.v_begin != groups[wr.g_begin].val_off + wr.val_begin) return fail("wave v_begin");
+            if (wr.val_begin != (uint32_t)wr.j_begin * kWave) return fail("wave val_begin");
+            // the kernel walks (v_end - v_begin) / 64 steps from (g_begin, j_begin), moving to the
+            // next group at each group's last step: that walk must end at (g_end, j_end)
+            {
+                uint64_t steps = 0;
+                for (uint32_t g = wr.g_begin; g <= wr.g_end && g < h.n_groups; ++g) {
+                    const int jlo = g == wr.g_begin ? wr.j_begin : 0;
+                    const int jhi = g == wr.g_end ? wr.j_end : groups[g].cmax;
+                    if (jhi < jlo) return fail("wave step range");
+                    if (g != wr.g_begin && g != wr.g_end && groups[g].cmax == 0) return fail("empty group");
+                    steps += (uint64_t)(jhi - jlo);
+                }
+                if (steps * kWave != (uint64_t)(wr.v_end - wr.v_begin)) return fail("wave step count");
+                if (wr.g_begin < h.n_groups && wr.j_begin >= groups[wr.g_begin].cmax && steps) return fail("wave starts past its group's end");
+            }
             for (uint32_t g = wr.g_begin; g <= wr.g_end && g < h.n_groups; ++g) {
                 const GroupRec &gr = groups[g];
                 const int jlo = g == wr.g_begin ? wr.j_begin : 0;
@@ -621,49 +677,66 @@ int validate_plan(const csb_matrix *m) {
                 if (jhi <= jlo) continue;
                 if (jhi > gr.cmax) return fail("wave step range");
                 if (gr.nzrank < cr.nzrank0 || gr.nzrank >= cr.nzrank0 + cr.ntiles) return fail("group tile outside chunk");
-                if (gr.nlanes > kWave || gr.nvb > kMaxVbPerGroup) return fail("group size");
+                if (gr.nlanes > kWave || gr.nvb > kMaxVbPerGroup || gr.nvb == 0) return fail("group size");
+                if ((gr.val_off & 63u) || (uint64_t)gr.val_off + (uint64_t)gr.cmax * kWave > h.n_vals) return fail("group value run");
+                {   // scatter rounds: (row slot, round) pairs are unique and rounds stay below nrounds
+                    uint8_t used[CSB_MAX_BLOCK][2] = {{0}};
+                    for (int lane = 0; lane < gr.nlanes; ++lane) {
+                        const uint8_t slot = idx[gr.idx_off + 4 * lane], rk = idx[gr.idx_off + 4 * lane + 1] >> 4;
+                        if (rk >= gr.nrounds) return fail("scatter round");
+                        if (used[slot][rk >> 3] >> (rk & 7) & 1) return fail("two lanes of one scatter round share a row");
+                        used[slot][rk >> 3] |= (uint8_t)(1u << (rk & 7));
+                    }
+                }
                 if (g < cr.g0 || g >= cr.g0 + cr.ng) return fail("group outside the chunk's record window");
                 if (gr.vb_off < cr.vb0 || gr.vb_off + gr.nvb > cr.vb0 + cr.nvbs) return fail("vb outside the chunk's record window");
                 if (gr.idx_off < cr.idx0) return fail("index bytes before the chunk's window");
                 if ((uint64_t)gr.vb_off + gr.nvb > h.n_vbs) return fail("vb range");
                 const uint32_t tile = nz_tiles[gr.nzrank];
                 const uint32_t tile_h = (uint32_t)std::min<int64_t>(br, rows_out - (int64_t)tile * br);
-                const size_t col_base = (size_t)gr.idx_off + align_up(2 * (size_t)gr.nlanes, 4);
-                // offset of step jlo
-                uint32_t off = 0;
-                for (int j = 0; j < jlo; ++j)
-                    for (int k = 0; k < gr.nvb; ++k) if (j < vbs[gr.vb_off + k].c) off += vbs[gr.vb_off + k].r;
-                if (g == wr.g_begin && off != wr.val_begin) return fail("wave val_begin");
+                const size_t col_base = (size_t)gr.idx_off + align_up(4 * (size_t)gr.nlanes, 8);
+                const int cpad = (gr.cmax + 3) & ~3;
+                if ((gr.idx_off & 7u) || gr.cmax % kStepQuantum || jlo % kStepQuantum || jhi % kStepQuantum) return fail("group alignment");
+                // input-offset lists: the block's columns, then the zero entry up to the padded length
+                for (int k = 0; k < gr.nvb; ++k) {
+                    const VbRec &v = vbs[gr.vb_off + k];
+                    if (v.c > gr.cmax || v.c == 0 || v.r == 0 || (uint32_t)v.lane0 + v.r > gr.nlanes) return fail("vb shape");
+                    if (v.coloff4 & 1u) return fail("input offset list alignment");
+                    for (int j = jlo & ~3; j < ((jhi + 3) & ~3) && j < cpad; ++j) {
+                        const size_t ia = col_base + 4 * (size_t)v.coloff4 + 2 * (size_t)j;
+                        if (ia + 1 >= h.idx_bytes || ia + 1 >= (size_t)cr.idx0 + cr.idx_bytes) return fail("input offset list position");
+                        const uint32_t o = (uint32_t)idx[ia] | (uint32_t)idx[ia + 1] << 8;
+                        if (j >= v.c) { if (o != (uint32_t)cols * 4u) return fail("input offset padding"); continue; }
+                        if ((o & 3u) || o / 4 >= (uint32_t)cols || o / 4 < (uint32_t)v.bj * bc || o / 4 >= ((uint32_t)v.bj + 1) * bc) return fail("input offset");
+                    }
+                }
                 for (int j = jlo; j < jhi; ++j) {
-                    uint32_t n_active = 0;
-                    for (int lane = 0; lane < gr.nlanes; ++lane) {
-                        if ((size_t)gr.idx_off + 2 * lane + 1 >= h.idx_bytes) return fail("lane descriptor offset");
-                        const uint8_t slot = idx[gr.idx_off + 2 * lane], k = idx[gr.idx_off + 2 * lane + 1];
+                    for (int lane = 0; lane < kWave; ++lane) {
+                        const uint64_t va = (uint64_t)gr.val_off + (uint64_t)j * kWave + lane;
+                        if (va >= h.n_vals) return fail("value offset");
+                        if (va < wr.v_begin || va >= wr.v_end) return fail("value outside the wave's window");
+                        if (lane >= gr.nlanes) { if (vals[va] != 0.0f) return fail("value padding (lane)"); continue; }
+                        if ((size_t)gr.idx_off + 4 * lane + 3 >= h.idx_bytes) return fail("lane descriptor offset");
+                        const uint8_t slot = idx[gr.idx_off + 4 * lane], k = idx[gr.idx_off + 4 * lane + 1] & 15;
                         if (k >= gr.nvb) return fail("lane vb number");
                         const VbRec &v = vbs[gr.vb_off + k];
+                        const size_t lo = (size_t)idx[gr.idx_off + 4 * lane + 2] | (size_t)idx[gr.idx_off + 4 * lane + 3] << 8;
+                        if ((size_t)gr.idx_off + lo != col_base + 4 * (size_t)v.coloff4) return fail("lane list offset");
                         if (lane < v.lane0 || lane >= v.lane0 + v.r) return fail("lane outside its vb");
                         if (slot >= tile_h) return fail("row slot");
-                        if (j >= v.c) continue;
-                        if ((uint32_t)lane != n_active) return fail("active lanes are not a prefix");
-                        const size_t ia = col_base + 4 * (size_t)v.coloff4 + j;
-                        if (ia >= h.idx_bytes || ia >= (size_t)cr.idx0 + cr.idx_bytes) return fail("column index offset");
-                        const uint32_t col = idx[ia];
-                        const int64_t gc = (int64_t)v.bj * bc + col;
-                        if (col >= bc || gc >= cols) return fail("column index");
-                        const uint64_t va = (uint64_t)gr.val_off + off + n_active;
-                        if (va >= h.n_vals || off + n_active >= gr.nvals) return fail("value offset");
-                        if (va < wr.v_begin || va >= wr.v_end) return fail("value outside the wave's window");
+                        if (j >= v.c) { if (vals[va] != 0.0f) return fail("value padding (step)"); continue; }
+                        const size_t ia = col_base + 4 * (size_t)v.coloff4 + 2 * (size_t)j;
+                        const int64_t gc = ((uint32_t)idx[ia] | (uint32_t)idx[ia + 1] << 8) / 4;
                         const size_t cell = (size_t)((int64_t)tile * br + slot) * cols + gc;
                         if (seen[cell]) return fail("entry referenced twice");
                         seen[cell] = 1;
                         got[cell] = vals[va];
                         ++vals_used;
-                        ++n_active;
                     }
-                    off += n_active;
                 }
             }
         }
+        if (v_expect != cr.v0 + 4 * cr.nv4 && cr.nv4) return fail("wave value runs do not cover the chunk's run");
         for (uint32_t s = 0; s < cr.ntiles; ++s) {
             const uint32_t tile = nz_tiles[cr.nzrank0 + s];
             int sid = -1, part = -1;

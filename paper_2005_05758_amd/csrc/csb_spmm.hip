@@ -49,7 +49,6 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(const DevMat m, cons
         return;
     }
     float *acc = smem_f;                                           // [waves][br][NB]
-    uint16_t *offtab = (uint16_t *)(smem_f + kSpmmWaves * br * NB) + wave * 320;   // [waves][320]
     float *myacc = acc + (size_t)wave * br * NB;
     for (uint32_t e = lane; e < br * NB; e += 64) myacc[e] = 0.0f;
     const uint32_t rank = blockIdx.x, tile = m.nz_tiles[rank];
@@ -58,7 +57,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(const DevMat m, cons
     uint32_t task = 0;
     for (uint32_t g = g0; g < g1; ++g) {
         const GroupRec *gp = m.groups + g;
-        const uint32_t nvb = uni_(gp->nvb), nlanes = uni_(gp->nlanes), cmax = uni_(gp->cmax);
+        const uint32_t nvb = uni_(gp->nvb), nlanes = uni_(gp->nlanes);
         const uint32_t idx_off = uni_(gp->idx_off), vb_off = uni_(gp->vb_off);
         const float *gv = m.vals + uni_(gp->val_off);
         // does this wavefront have a slice in the group?
@@ -66,43 +65,52 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(const DevMat m, cons
         for (uint32_t k = 0; k < nvb; ++k) ntask += ((uint32_t)m.vbs[vb_off + k].r + 15u) >> 4;
         const uint32_t first_mine = (wave + kSpmmWaves - task % kSpmmWaves) % kSpmmWaves;
         if (first_mine >= ntask) { task += ntask; continue; }
-        // values stored before column step j: sum over blocks of rows * min(j, columns)
-        for (uint32_t j = lane; j < cmax; j += 64) {
-            uint32_t o = 0;
-            for (uint32_t k = 0; k < nvb; ++k) {
-                const VbRec v = m.vbs[vb_off + k];
-                o += (uint32_t)v.r * min(j, (uint32_t)v.c);
-            }
-            offtab[j] = (uint16_t)o;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        const uint8_t *colbase = m.idx + idx_off + ((2 * nlanes + 3) & ~3u);
+        const uint8_t *colbase = m.idx + idx_off + ((4 * nlanes + 7) & ~7u);
         for (uint32_t k = 0; k < nvb; ++k) {
             const VbRec v = m.vbs[vb_off + k];
             const uint32_t r = uni_(v.r), c = uni_(v.c), lane0 = uni_(v.lane0);
-            const uint32_t zb = uni_((uint32_t)v.bj) * m.bc;
-            const uint8_t *colp = colbase + 4u * uni_(v.coloff4);
+            const uint16_t *colp = (const uint16_t *)(colbase + 4u * uni_(v.coloff4));   // byte offsets of the inputs
             for (uint32_t m0 = 0; m0 < r; m0 += 16, ++task) {
                 if (task % kSpmmWaves != wave) continue;
                 floatx4 D[NT];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) D[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
                 const bool row_ok = m0 + mrow < r;
-                for (uint32_t kk = 0; kk < c; kk += 4) {
-                    const uint32_t jj = kk + kq;
-                    const bool col_ok = jj < c;
-                    float a = 0.0f;
-                    if (col_ok && row_ok) a = gv[(uint32_t)offtab[jj] + lane0 + m0 + mrow];
-                    const uint32_t gcol = zb + (col_ok ? (uint32_t)colp[jj] : 0u);
+                const uint32_t arow = lane0 + m0 + (row_ok ? mrow : 0u);
+                // 32 columns (8 MFMA k-steps) per pass: all kernel values and column indices
+                // first, then all gathered inputs, then the MFMAs -- the loads of a pass
+                // are independent, so their latencies overlap.  Out-of-range lanes load
+                // from clamped addresses and their operands are zeroed.
+                for (uint32_t kc = 0; kc < c; kc += 32) {
+                    float av[8];
+                    uint32_t gc[8];
+                    bool ok[8];
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        const uint32_t n = bt0 + 16u * nt + mrow;
-                        float b = 0.0f;
-                        if (col_ok && n < batch)
-                            b = gcol < X.n0 ? X.p0[(int64_t)gcol * X.sj0 + (int64_t)n * X.sn0]
-                                            : X.p1[(int64_t)(gcol - X.n0) * X.sj1 + (int64_t)n * X.sn1];
-                        D[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, D[nt], 0, 0, 0);
+                    for (int s8 = 0; s8 < 8; ++s8) {
+                        const uint32_t jj = kc + 4u * s8 + kq;
+                        ok[s8] = jj < c;
+                        const uint32_t jc = ok[s8] ? jj : 0u;
+                        const float t = gv[jc * (uint32_t)kWave + arow];
+                        av[s8] = ok[s8] && row_ok ? t : 0.0f;
+                        gc[s8] = (uint32_t)colp[jc] >> 2;
+                    }
+                    float bv[8][NT];
+#pragma unroll
+                    for (int s8 = 0; s8 < 8; ++s8)
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            const uint32_t n = bt0 + 16u * nt + mrow;
+                            const uint32_t nc = n < batch ? n : 0u;
+                            const float t = gc[s8] < X.n0 ? X.p0[(int64_t)gc[s8] * X.sj0 + (int64_t)nc * X.sn0]
+                                                          : X.p1[(int64_t)(gc[s8] - X.n0) * X.sj1 + (int64_t)nc * X.sn1];
+                            bv[s8][nt] = ok[s8] && n < batch ? t : 0.0f;
+                        }
+#pragma unroll
+                    for (int s8 = 0; s8 < 8; ++s8) {
+                        if (kc + 4u * s8 >= c) break;          // uniform
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            D[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s8], bv[s8][nt], D[nt], 0, 0, 0);
                     }
                 }
                 // lane holds rows 4*(lane/16)+i, column lane%16 of each 16 x 16 result
@@ -110,16 +118,14 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(const DevMat m, cons
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t mr = m0 + 4u * kq + i;
                     if (mr < r) {
-                        const uint32_t slot = m.idx[idx_off + 2u * (lane0 + mr)];
+                        const uint32_t slot = m.idx[idx_off + 4u * (lane0 + mr)];
 #pragma unroll
                         for (int nt = 0; nt < NT; ++nt)
-                            __hip_atomic_fetch_add(&myacc[slot * NB + 16u * nt + mrow], D[nt][i], __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_WAVEFRONT);
+                            myacc[slot * NB + 16u * nt + mrow] += D[nt][i];   // rows of a slice are distinct: no two lanes meet
                     }
                 }
             }
         }
-        __builtin_amdgcn_wave_barrier();          // offtab is rewritten for the next group
     }
     __syncthreads();
     for (uint32_t e = tid; e < br * NB; e += kSpmmThreads) {
@@ -138,7 +144,7 @@ int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj
     const DevMat dm = dev_mat(mat);
     XSrc X{p0, n0, sj0, sn0, p1, sj1, sn1};
     const int nt = h.br <= 128 ? 2 : 1;
-    const size_t lds = (size_t)kSpmmWaves * h.br * 16 * nt * sizeof(float) + (size_t)kSpmmWaves * 320 * sizeof(uint16_t);
+    const size_t lds = (size_t)kSpmmWaves * h.br * 16 * nt * sizeof(float);
     const dim3 grid(h.n_nz_tiles + h.n_zero_tiles, (unsigned)((batch + 16 * nt - 1) / (16 * nt)));
     hipError_t e;
     if (nt == 2) {

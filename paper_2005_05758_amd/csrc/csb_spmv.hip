@@ -45,81 +45,11 @@ __device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_re
 
 // LDS map of one workgroup (byte offsets from the start of dynamic LDS).
 struct LdsMap {
-    uint32_t zpad;        // floats of the staged input vector
-    uint32_t vw;          // floats of the workgroup's value window
+    uint32_t zpad;        // floats of the staged input vector (with the zero entry behind it)
     uint32_t meta_off;    // bytes: group records | block records | index bytes
-    uint32_t acc_off;     // bytes: [NW][acc_rows] accumulators
+    uint32_t acc_off;     // bytes: [NW][kAccPlanes][acc_rows] accumulators
+    uint32_t red_off;     // bytes: [4][256] partial sums of the final reduction
 };
-
-// The wavefront's share of the mat-vec, everything read from LDS: accumulates into
-// myacc[(tile slot) * br + row slot].
-__device__ __forceinline__ void wave_groups(const DevMat &m, const ChunkRec &cr, const WaveRec &wr,
-                                            const uint8_t *meta, const float *wv,
-                                            const float *z, float *myacc, const int lane) {
-    const uint32_t goff = 0, voff = (cr.ng * (uint32_t)sizeof(GroupRec) + 15u) & ~15u;
-    const uint32_t ioff = voff + ((cr.nvbs * (uint32_t)sizeof(VbRec) + 15u) & ~15u);
-    const GroupRec *lg = (const GroupRec *)(meta + goff);
-    const VbRec *lv = (const VbRec *)(meta + voff);
-    const uint8_t *lidx = meta + ioff;
-    const uint32_t g_begin = wr.g_begin, g_end = wr.g_end;
-    for (uint32_t g = g_begin; g <= g_end && g < m.n_groups; ++g) {
-        const GroupRec *gp = lg + (g - cr.g0);
-        const uint32_t cmax = uni(gp->cmax);
-        const uint32_t jlo = g == g_begin ? (uint32_t)wr.j_begin : 0u;
-        const uint32_t jhi = g == g_end ? (uint32_t)wr.j_end : cmax;
-        if (jhi <= jlo) continue;
-        const uint32_t nvb = uni(gp->nvb), nlanes = uni(gp->nlanes);
-        const uint32_t ib = uni(gp->idx_off) - cr.idx0, vb = uni(gp->vb_off) - cr.vb0;
-        const float *gv = wv + (uni(gp->val_off) + (g == g_begin ? wr.val_begin : 0u) - cr.v0);
-        const bool act = (uint32_t)lane < nlanes;
-        uint32_t slot = 0, k = 0xffffffffu, c_lane = 0, zb = 0;
-        const uint32_t *colp = (const uint32_t *)lidx;
-        if (act) {
-            const uint32_t d = *(const uint16_t *)(lidx + ib + 2 * lane);
-            slot = d & 0xffu;
-            k = d >> 8;
-            const VbRec v = lv[vb + k];
-            c_lane = v.c;
-            zb = (uint32_t)v.bj * m.bc;
-            colp = (const uint32_t *)(lidx + ib + ((2 * nlanes + 3) & ~3u)) + v.coloff4;
-        }
-        const uint32_t jend = min(jhi, c_lane);
-        float a = 0.0f;
-        uint32_t off = 0;
-        // 32 column steps per pass; per 4 steps all LDS reads are issued before the first
-        // multiply-add.  Reads of lanes that sit out a step stay in bounds (the value window
-        // has 64 floats of slack, a zero index byte points at the block's first input) and
-        // their products are dropped.
-        for (uint32_t seg = jlo & ~31u; seg < jhi; seg += 32) {
-            uint32_t cw[8];
-#pragma unroll
-            for (int d = 0; d < 8; ++d) cw[d] = seg + 4 * d < jend ? colp[(seg >> 2) + d] : 0u;
-#pragma unroll
-            for (int d = 0; d < 8; ++d) {
-                if (seg + 4 * d >= jhi) break;
-                bool on[4];
-                float w[4], zz[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const uint32_t j = seg + 4 * d + u;
-                    on[u] = j >= jlo && j < jend;
-                    w[u] = gv[off + lane];
-                    zz[u] = z[zb + ((cw[d] >> (8 * u)) & 0xffu)];
-                    off += (uint32_t)__popcll(__ballot(on[u]));
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) a = on[u] ? fmaf(w[u], zz[u], a) : a;
-            }
-        }
-        // Row results into the wavefront's accumulator.  Lanes of different virtual blocks
-        // may target the same row, so the blocks go one after another; a wavefront's LDS
-        // operations execute in program order, which fixes the order of the sum.
-        const uint32_t rs = (uni(gp->nzrank) - cr.nzrank0) * m.br + slot;
-        for (uint32_t kk = 0; kk < nvb; ++kk) {
-            if (k == kk) __hip_atomic_fetch_add(&myacc[rs], a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-        }
-    }
-}
 
 // Uniform copies of the records (every field through a scalar register).
 __device__ __forceinline__ ChunkRec load_chunk(const ChunkRec *p) {
@@ -142,9 +72,17 @@ __device__ __forceinline__ WaveRec load_wave(const WaveRec *p) {
     return w;
 }
 
+// Barrier that orders LDS traffic only: global loads still in flight stay in flight.
+__device__ __forceinline__ void lds_only_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 constexpr int kSpmvWaves = 16;
 constexpr int kSpmvThreads = kSpmvWaves * 64;
-constexpr int kStampsPerChunk = 8 + 2 * kSpmvWaves;
+constexpr int kStampsPerChunk = 8 + 3 * kSpmvWaves;
+constexpr int kStepsInFlight = 32;   // column steps of a wavefront whose values are loaded at once
 
 // A guarded load into a named register (arrays of these end up in scratch memory).
 #define CSB_LD4(name, src, idx, n) \
@@ -156,6 +94,10 @@ constexpr int kStampsPerChunk = 8 + 2 * kSpmvWaves;
 #define CSB_ST(dst, idx, n, name) \
     { const uint32_t i_ = (idx); if (i_ < (n)) (dst)[i_] = name; }
 
+// One workgroup per chunk.  Records and the input vector go to LDS; the kernel values never
+// do: a wavefront's steps are consecutive 64-float runs of the value stream, so lane l loads
+// word l of every run straight into a register (one coalesced 256-byte read per step) and
+// multiplies it there.
 __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, const float *__restrict__ x0,
                                                              const uint32_t n0, const float *__restrict__ x1,
                                                              float *__restrict__ y, unsigned long long *__restrict__ partials,
@@ -164,30 +106,30 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
     extern __shared__ float4 smem4[];
     __shared__ uint32_t s_last;
     uint8_t *smem = (uint8_t *)smem4;
-    float *z = (float *)smem;                          // [zpad] input vector
-    float *vals_lds = z + L.zpad;                      // [vw] the chunk's run of the value stream
+    float *z = (float *)smem;                          // [zpad] input vector, z[cols] = 0
     uint8_t *meta = smem + L.meta_off;
-    float *acc = (float *)(smem + L.acc_off);          // [NW][ntiles * br]
-    constexpr int NW = kSpmvWaves, NT = kSpmvThreads;
+    float *acc = (float *)(smem + L.acc_off);          // [NW][kAccPlanes][ntiles * br]
+    float *red = (float *)(smem + L.red_off);          // [4][256]
+    constexpr int NW = kSpmvWaves, NT = kSpmvThreads, CAP = kStepsInFlight, Q = kStepQuantum;
     const uint32_t tid = threadIdx.x;
     const int lane = tid & 63, wave = (int)uni(tid >> 6);
     const uint32_t c = blockIdx.x;
-    static_assert(kChunkValsMax / 4 <= 7 * NT, "value window loads");
-    static_assert(kMaxStageCols / 4 <= 5 * NT, "input vector loads");
-    static_assert((kChunkMetaMax + 4096) / 8 <= 3 * NT, "record loads");
+    static_assert(kMaxStageCols / 4 <= 4 * NT, "input vector loads");
+    static_assert(kChunkMetaMax <= 3 * NT * 8, "record loads");
+    static_assert(kChunkMetaMax + 16 <= 2 * NT * 16, "index byte loads");
+    static_assert(kAccRowsMax <= 256 && NT == 1024 && (kAccPlanes & (kAccPlanes - 1)) == 0, "final reduction layout");
+    static_assert(CAP % Q == 0 && Q % 2 == 0 && (CAP & (CAP - 1)) == 0, "step quantum / batch size");
 
-    // optional clock stamps (debug): per workgroup 8 phase stamps, then begin/end per wavefront
+    // optional clock stamps (debug): per workgroup 8 phase stamps, then per wavefront: begin,
+    // values arrived, end
     unsigned long long *st = stamps ? stamps + (size_t)c * kStampsPerChunk : nullptr;
     if (st && tid == 0) st[0] = __builtin_readcyclecounter();
 
-    // ---- issue every global load of the workgroup before waiting for any ---------------
+    // ---- issue every global load before waiting for any ---------------------------------
+    // Loads return in issue order: first what the whole workgroup needs (records, input
+    // vector), then this wavefront's values.
     const ChunkRec cr = load_chunk(m.chunks + c);
     const WaveRec wr = load_wave(m.waves + (size_t)c * NW + wave);
-    const uint32_t n4 = cr.nv4;
-    const float4 *gsrc = (const float4 *)(m.vals + cr.v0);
-    CSB_LD4(rv0, gsrc, tid, n4) CSB_LD4(rv1, gsrc, tid + NT, n4) CSB_LD4(rv2, gsrc, tid + 2 * NT, n4)
-    CSB_LD4(rv3, gsrc, tid + 3 * NT, n4) CSB_LD4(rv4, gsrc, tid + 4 * NT, n4) CSB_LD4(rv5, gsrc, tid + 5 * NT, n4)
-    CSB_LD4(rv6, gsrc, tid + 6 * NT, n4)
     // records: groups and virtual blocks in 8-byte units, index bytes in 16-byte units
     const uint32_t gu = cr.ng * 3u, vu = cr.nvbs, iu = cr.idx_bytes >> 4;
     const uint32_t voff = (cr.ng * (uint32_t)sizeof(GroupRec) + 15u) & ~15u;
@@ -203,26 +145,29 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
     const uint32_t z4 = zfast ? (m.cols >> 2) : 0u;
     const float4 *zsrc = (const float4 *)x0;
     CSB_LD4(rz0, zsrc, tid, z4) CSB_LD4(rz1, zsrc, tid + NT, z4) CSB_LD4(rz2, zsrc, tid + 2 * NT, z4)
-    CSB_LD4(rz3, zsrc, tid + 3 * NT, z4) CSB_LD4(rz4, zsrc, tid + 4 * NT, z4)
+    CSB_LD4(rz3, zsrc, tid + 3 * NT, z4)
     if (!zfast)
         for (uint32_t i = tid; i < m.cols; i += NT) z[i] = i < n0 ? x0[i] : x1[i - n0];
+    // values of the wavefront's first CAP steps (steps past its last one repeat the last)
+    const uint32_t nsteps = (wr.v_end - wr.v_begin) >> 6;
+    const uint32_t last_step = nsteps ? nsteps - 1u : 0u;
+    const float *wv = m.vals + wr.v_begin + lane;
+    float R[CAP];
+#pragma unroll
+    for (int s = 0; s < CAP; ++s) R[s] = wv[(size_t)min((uint32_t)s, last_step) * kWave];
 
     if (st && tid == 0) st[1] = __builtin_readcyclecounter();
     // ---- independent work while the loads fly -------------------------------------------
     const uint32_t arows = cr.ntiles * m.br;
-    for (uint32_t i = tid; i < NW * arows; i += NT) acc[i] = 0.0f;
+    for (uint32_t i = tid; i < NW * kAccPlanes * arows; i += NT) acc[i] = 0.0f;
     for (uint32_t q = c; q < m.n_zero_tiles; q += m.n_chunks) {   // output tiles nobody has work for
         const uint32_t r0 = m.zero_tiles[q] * m.br;
         for (uint32_t i = tid; i < m.br; i += NT)
             if (r0 + i < m.rows_out) y[r0 + i] = 0.0f;
     }
 
-    // ---- commit to LDS ------------------------------------------------------------------
+    // ---- records and input vector into LDS ----------------------------------------------
     {
-        float4 *vd = (float4 *)vals_lds;
-        CSB_ST(vd, tid, n4, rv0) CSB_ST(vd, tid + NT, n4, rv1) CSB_ST(vd, tid + 2 * NT, n4, rv2)
-        CSB_ST(vd, tid + 3 * NT, n4, rv3) CSB_ST(vd, tid + 4 * NT, n4, rv4) CSB_ST(vd, tid + 5 * NT, n4, rv5)
-        CSB_ST(vd, tid + 6 * NT, n4, rv6)
         uint2 *gd = (uint2 *)meta, *bd = (uint2 *)(meta + voff);
         CSB_ST(gd, tid, gu, rg0) CSB_ST(gd, tid + NT, gu, rg1) CSB_ST(gd, tid + 2 * NT, gu, rg2)
         CSB_ST(bd, tid, vu, rb0) CSB_ST(bd, tid + NT, vu, rb1) CSB_ST(bd, tid + 2 * NT, vu, rb2)
@@ -230,21 +175,124 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
         CSB_ST(id, tid, iu, ri0) CSB_ST(id, tid + NT, iu, ri1)
         float4 *zd = (float4 *)z;
         CSB_ST(zd, tid, z4, rz0) CSB_ST(zd, tid + NT, z4, rz1) CSB_ST(zd, tid + 2 * NT, z4, rz2)
-        CSB_ST(zd, tid + 3 * NT, z4, rz3) CSB_ST(zd, tid + 4 * NT, z4, rz4)
+        CSB_ST(zd, tid + 3 * NT, z4, rz3)
+        if (tid == 0) z[m.cols] = 0.0f;          // what padded steps multiply their zero values with
     }
-    __syncthreads();
+    lds_only_barrier();
     if (st && tid == 0) st[2] = __builtin_readcyclecounter();
-    if (st && lane == 0) st[8 + 2 * wave] = __builtin_readcyclecounter();
-    wave_groups(m, cr, wr, meta, vals_lds, z, acc + wave * arows, lane);
-    if (st && lane == 0) st[9 + 2 * wave] = __builtin_readcyclecounter();
+    if (st && lane == 0) st[8 + 3 * wave] = __builtin_readcyclecounter();
+    if (st) {                                    // debug only: separate the wait for the values from the arithmetic
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (lane == 0) st[9 + 3 * wave] = __builtin_readcyclecounter();
+    }
+
+    // ---- the wavefront's steps ------------------------------------------------------------
+    // Lane l owns one kernel-matrix row of one virtual block of the current group (inner-
+    // block parallelism over rows, inter-block parallelism over the lanes' different blocks)
+    // and walks the block's list of input offsets.  Eight steps at a time: the gathers of all
+    // eight, then the multiply-adds, with the next eight list entries already on their way.
+    // The records of the next group are fetched while the current one is being worked on.
+    {
+        const uint8_t *lidx = meta + ioff;
+        const uint8_t *zb = (const uint8_t *)z;
+        float *myacc = acc + wave * (kAccPlanes * arows);
+        const uint32_t g_last = cr.g0 + cr.ng - 1u;       // last group with records in LDS
+        // a group's record words: {idx_off, nzrank} and {cmax | nvb << 16 | nlanes << 24, nrounds}
+        auto rec_lo = [&](uint32_t g) { return *(const uint2 *)(meta + (min(g, g_last) - cr.g0) * (uint32_t)sizeof(GroupRec) + 8u); };
+        auto rec_hi = [&](uint32_t g) { return *(const uint2 *)(meta + (min(g, g_last) - cr.g0) * (uint32_t)sizeof(GroupRec) + 16u); };
+        // a lane's descriptor; lanes without a row use lane 0's list (their values are all zero)
+        auto lane_word = [&](uint32_t idx_off, uint32_t nlanes) {
+            return *(const uint32_t *)(lidx + (idx_off - cr.idx0) + 4u * ((uint32_t)lane < nlanes ? (uint32_t)lane : 0u));
+        };
+        uint32_t g = wr.g_begin, j = wr.j_begin;
+        uint2 clo = make_uint2(cr.idx0, 0u), chi = make_uint2(0u, 0u);
+        uint32_t cd = 0;
+        if (nsteps) {
+            clo = rec_lo(g); chi = rec_hi(g);
+            cd = lane_word(uni(clo.x), uni(chi.x) >> 24);
+        }
+        for (uint32_t base = 0; base < nsteps; base += CAP) {
+            if (base) {                          // a wavefront with more than CAP steps: next batch
+#pragma unroll
+                for (int s = 0; s < CAP; ++s) R[s] = wv[(size_t)min(base + (uint32_t)s, last_step) * kWave];
+            }
+            const uint32_t bsteps = min((uint32_t)CAP, nsteps - base);
+            uint32_t s = 0;
+            while (s < bsteps) {                                     // one run: steps of one group
+                const uint32_t ib = uni(clo.x) - cr.idx0, nzrank = uni(clo.y), w2 = uni(chi.x);
+                const uint32_t cmax = w2 & 0xffffu, nlanes = w2 >> 24;
+                const uint32_t jhi = g == wr.g_end ? (uint32_t)wr.j_end : cmax;
+                const uint32_t run = min(jhi - j, bsteps - s);
+                const uint2 nlo = rec_lo(g + 1u), nhi = rec_hi(g + 1u);   // next group's records
+                const bool act = (uint32_t)lane < nlanes;
+                const uint32_t d = cd;
+                const uint32_t *zw = (const uint32_t *)(lidx + ib + (d >> 16) + 2u * j);   // this lane's position in its block's list
+                uint32_t w0 = zw[0], w1 = zw[1], w2_ = zw[2], w3 = zw[3];
+                float a0 = 0.0f, a1 = 0.0f;
+                for (uint32_t t = 0; t < run; t += 8) {
+                    const uint32_t left = run - t, s0 = s + t;
+                    const uint32_t c0 = w0, c1 = w1, c2 = w2_, c3 = w3;
+                    zw += 4;
+                    if (left > 8) { w0 = zw[0]; w1 = zw[1]; w2_ = zw[2]; w3 = zw[3]; }   // uniform
+                    // pairs of steps past the end of the run are skipped (uniform branches)
+                    float z0, z1, z2 = 0.0f, z3 = 0.0f, z4 = 0.0f, z5 = 0.0f, z6 = 0.0f, z7 = 0.0f;
+                    float r0, r1, r2 = 0.0f, r3 = 0.0f, r4 = 0.0f, r5 = 0.0f, r6 = 0.0f, r7 = 0.0f;
+                    z0 = *(const float *)(zb + (c0 & 0xffffu)); z1 = *(const float *)(zb + (c0 >> 16));
+                    if (left > 2) { z2 = *(const float *)(zb + (c1 & 0xffffu)); z3 = *(const float *)(zb + (c1 >> 16)); }
+                    if (left > 4) { z4 = *(const float *)(zb + (c2 & 0xffffu)); z5 = *(const float *)(zb + (c2 >> 16)); }
+                    if (left > 6) { z6 = *(const float *)(zb + (c3 & 0xffffu)); z7 = *(const float *)(zb + (c3 >> 16)); }
+                    // register of step s0 + i (uniform index)
+                    r0 = R[s0 & (CAP - 1)]; r1 = R[(s0 + 1) & (CAP - 1)];
+                    if (left > 2) { r2 = R[(s0 + 2) & (CAP - 1)]; r3 = R[(s0 + 3) & (CAP - 1)]; }
+                    if (left > 4) { r4 = R[(s0 + 4) & (CAP - 1)]; r5 = R[(s0 + 5) & (CAP - 1)]; }
+                    if (left > 6) { r6 = R[(s0 + 6) & (CAP - 1)]; r7 = R[(s0 + 7) & (CAP - 1)]; }
+                    a0 = fmaf(r0, z0, a0); a1 = fmaf(r1, z1, a1);
+                    a0 = fmaf(r2, z2, a0); a1 = fmaf(r3, z3, a1);
+                    a0 = fmaf(r4, z4, a0); a1 = fmaf(r5, z5, a1);
+                    a0 = fmaf(r6, z6, a0); a1 = fmaf(r7, z7, a1);
+                }
+                // the next group's lane descriptors (its records have arrived by now)
+                const uint32_t nd = lane_word(uni(nlo.x), uni(nhi.x) >> 24);
+                // Row results into the wavefront's accumulator.  Lanes of different virtual blocks
+                // may target the same row: the planner numbered the lanes of each row, and lane
+                // number q of a row adds into accumulator copy q % kAccPlanes, so all lanes of a
+                // round (q / kAccPlanes, nearly always the only one) hit different words and a
+                // plain read-add-write does (LDS float atomics take a few clocks per lane).  A
+                // wavefront's LDS operations execute in program order, which fixes the sum.
+                {
+                    const float asum = a0 + a1;
+                    const uint32_t q = (d >> 12) & 15u;
+                    float *dst = myacc + (q & (kAccPlanes - 1)) * arows + (nzrank - cr.nzrank0) * m.br + (d & 0xffu);
+                    const uint32_t round = act ? q / kAccPlanes : 0xffffffffu;
+                    const uint32_t nr = (uni(chi.y) & 0xffffu) + kAccPlanes - 1;
+                    for (uint32_t rq = 0; rq < nr / kAccPlanes; ++rq)
+                        if (round == rq) *dst += asum;
+                }
+                s += run;
+                j += run;
+                if (j == jhi) { ++g; j = 0; clo = nlo; chi = nhi; cd = nd; }
+            }
+        }
+    }
+    if (st && lane == 0) st[10 + 3 * wave] = __builtin_readcyclecounter();
     __syncthreads();
     if (st && tid == 0) st[3] = __builtin_readcyclecounter();
 
-    // sum over wavefronts in wavefront order; store or hand over as a partial
-    for (uint32_t i = tid; i < arows; i += NT) {
-        float s = 0.0f;
+    // Sum of the NW * kAccPlanes accumulator copies, in a fixed order: four partial sums of a
+    // quarter of the copies each, then their sum; store or hand over as a partial.
+    {
+        constexpr uint32_t C = NW * kAccPlanes;
+        const uint32_t part = tid >> 8, i = tid & 255u;
+        if (i < arows) {
+            float p = 0.0f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) s += acc[w * arows + i];
+            for (uint32_t cpy = 0; cpy < C / 4; ++cpy) p += acc[(part * (C / 4) + cpy) * arows + i];
+            red[part * 256u + i] = p;
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < arows; i += NT) {
+        const float s = (red[i] + red[256u + i]) + (red[512u + i] + red[768u + i]);
         const uint32_t ts = i / m.br, ri_ = i - ts * m.br;
         const uint32_t row = m.nz_tiles[cr.nzrank0 + ts] * m.br + ri_;
         // a partial travels as one 64-bit word: launch tag in the high half, value in the low
@@ -307,11 +355,11 @@ static hipError_t launch_spmv(const csb_matrix *mat, const float *x0, uint32_t n
     const DevHeader &h = mat->plan.hdr;
     const DevMat dm = dev_mat(mat);
     LdsMap L{};
-    L.zpad = ((uint32_t)h.cols + 63u) & ~63u;
-    L.vw = h.chunk_vals_cap;
-    L.meta_off = (L.zpad + L.vw + 64u) * 4u;   // 64 floats of slack behind the value window
+    L.zpad = ((uint32_t)h.cols + 1u + 63u) & ~63u;
+    L.meta_off = L.zpad * 4u;
     L.acc_off = L.meta_off + h.meta_cap;
-    const size_t lds = (size_t)L.acc_off + (size_t)h.waves_per_chunk * h.max_chunk_tiles * h.br * sizeof(float);
+    L.red_off = L.acc_off + h.waves_per_chunk * kAccPlanes * h.max_chunk_tiles * h.br * (uint32_t)sizeof(float);
+    const size_t lds = (size_t)L.red_off + 4 * 256 * sizeof(float);
     // Launch tag of the merge words; a workspace seen for the first time (or a wrapped tag)
     // is cleared so that no stale word can carry the tag.
     // Tags are unique per launch across the process (workspaces may be shared between
