@@ -42,15 +42,17 @@ struct GroupRec {
 static_assert(sizeof(GroupRec) == 24, "GroupRec layout");
 
 // A virtual block: the kernel-matrix rows of one CSB block that fall into one output tile
-// and one column part, at most 64 of them.
+// and one column part, at most 64 of them.  Only the batched kernel reads these records (the
+// mat-vec kernel finds everything it needs in the lane descriptors).
 struct VbRec {
     uint8_t r;          // rows (lanes)
     uint8_t lane0;      // first lane
     uint16_t c;         // columns
-    uint16_t bj;        // block column: input base index = bj * bc
-    uint16_t coloff4;   // offset of the block's input-offset list behind the lane descriptors, 4-byte units
+    uint32_t val_off;   // the group's val_off
+    uint32_t desc_pos;  // the group's idx_off (lane descriptors)
+    uint32_t list_pos;  // byte position of the block's input-offset list in the index stream
 };
-static_assert(sizeof(VbRec) == 8, "VbRec layout");
+static_assert(sizeof(VbRec) == 16, "VbRec layout");
 
 // Work of one wavefront: steps from (g_begin, j_begin) up to but excluding
 // (g_end, j_end), groups in order; (g, cmax_g) is the same position as (g + 1, 0).
@@ -98,6 +100,9 @@ struct DevHeader {
     uint64_t off_chunks, off_waves, off_groups, off_vbs, off_idx, off_vals;
     uint64_t off_nz_tiles, off_zero_tiles, off_shared, off_counters;
     uint64_t off_tile_g0;      // [n_nz_tiles + 1] first group of every row tile that has work
+    uint64_t off_tile_seg0;    // [n_nz_tiles + 1] first record segment of every such tile
+    uint64_t off_seg_g0;       // [n_segs + 1] first group of every record segment (never crossing tiles)
+    uint64_t n_segs;
     uint64_t idx_bytes, n_vals, total_bytes;
 };
 
@@ -112,12 +117,15 @@ struct DevMat {
     const uint32_t *nz_tiles;
     const uint32_t *zero_tiles;
     const uint32_t *tile_g0;
+    const uint32_t *tile_seg0;
+    const uint32_t *seg_g0;
     const SharedRec *shared;
     uint32_t *counters;
     uint32_t n_chunks, waves_per_chunk, n_zero_tiles, n_shared;
     uint32_t br, bc;
     uint32_t rows_out, cols;
     uint32_t n_groups, n_nz_tiles;
+    uint32_t idx_bytes, pad;
 };
 
 // How rows are relabelled when the image is built for a GRU: entries in rows >= split_row

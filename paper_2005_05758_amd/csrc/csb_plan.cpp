@@ -175,15 +175,14 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                 gr.nrounds = (uint16_t)rounds;
             }
             while (idx.size() % 8) idx.push_back(0);
-            const size_t col_base = idx.size();
             const int cpad = (g.cmax + 3) & ~3;            // list length: lists stay 8-byte aligned
             const uint16_t zero_off = (uint16_t)(m->cols * 4);   // byte offset of the zero entry behind the input vector
             int lane0 = 0;
             for (size_t k = 0; k < g.vbs.size(); ++k) {
                 const Vb &v = vbs[g.vbs[k]];
                 VbRec vr{};
-                vr.r = (uint8_t)v.r(); vr.lane0 = (uint8_t)lane0; vr.c = (uint16_t)v.c(); vr.bj = v.bj;
-                vr.coloff4 = (uint16_t)((idx.size() - col_base) / 4);
+                vr.r = (uint8_t)v.r(); vr.lane0 = (uint8_t)lane0; vr.c = (uint16_t)v.c();
+                vr.val_off = gr.val_off; vr.desc_pos = gr.idx_off; vr.list_pos = (uint32_t)idx.size();
                 const size_t list_off = idx.size() - gr.idx_off;
                 if (list_off > 0xffff) { set_error("csb_plan: internal: list offset"); return CSB_EINVAL; }
                 for (int q = 0; q < v.r(); ++q) {
@@ -271,10 +270,26 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         const size_t n_nz = nz_tiles.size();
         std::vector<uint32_t> tile_g0(n_nz + 1, n_groups);
         for (uint32_t g = n_groups; g-- > 0;) tile_g0[tile_rank[groups[g].tile]] = g;
+        // record segments for the batched kernel: group ranges inside one tile whose records fit
+        // the LDS window one workgroup stages at a time
+        std::vector<uint32_t> seg_g0, tile_seg0(n_nz + 1, 0);
+        for (size_t r = 0; r < n_nz; ++r) {
+            tile_seg0[r] = (uint32_t)seg_g0.size();
+            size_t bytes = 0, nv = 0;
+            for (uint32_t g = tile_g0[r]; g < tile_g0[r + 1]; ++g) {
+                const size_t gb = sizeof(GroupRec) + (size_t)grecs[g].nvb * sizeof(VbRec) + (idx_end[g] - grecs[g].idx_off);
+                if (g == tile_g0[r] || bytes + gb + 64 > (size_t)kChunkMetaMax || nv + grecs[g].nvb > 2048) {
+                    seg_g0.push_back(g);
+                    bytes = 0; nv = 0;
+                }
+                bytes += gb; nv += grecs[g].nvb;
+            }
+        }
+        tile_seg0[n_nz] = (uint32_t)seg_g0.size();
+        seg_g0.push_back(n_groups);
         auto tile_meta = [&](size_t r) {
             const uint32_t ga = tile_g0[r], gb = tile_g0[r + 1] - 1;
-            return (size_t)(gb - ga + 1) * sizeof(GroupRec) + (size_t)(grecs[gb].vb_off + grecs[gb].nvb - grecs[ga].vb_off) * sizeof(VbRec) +
-                   (idx_end[gb] - grecs[ga].idx_off) + 64;
+            return (size_t)(gb - ga + 1) * sizeof(GroupRec) + (idx_end[gb] - grecs[ga].idx_off) + 64;
         };
         auto lds_for = [&](size_t meta, size_t ntile) {
             return zbytes + align_up(meta, 256) + (size_t)NW * kAccPlanes * ntile * br * 4 + 4 * (size_t)kAccRowsMax * 4;
@@ -334,7 +349,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                 const uint32_t first_rank = g < n_groups ? tile_rank[groups[g].tile] : 0;
                 size_t meta = 0;
                 while (g < n_groups && P[g] < end) {
-                    const size_t gmeta = sizeof(GroupRec) + (size_t)grecs[g].nvb * sizeof(VbRec) + (idx_end[g] - grecs[g].idx_off);
+                    const size_t gmeta = sizeof(GroupRec) + (idx_end[g] - grecs[g].idx_off);
                     if (tile_rank[groups[g].tile] - first_rank >= max_tiles_per_chunk ||
                         (g > a.g && meta + gmeta + 64 > (size_t)kChunkMetaMax)) { end = P[g]; break; }
                     meta += gmeta;
@@ -429,9 +444,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                     if (ga >= n_groups) any = false;
                     if (any) {
                         const uint32_t i0 = grecs[ga].idx_off & ~15u;
-                        const size_t mb = align_up((gb - ga + 1) * sizeof(GroupRec), 16) +
-                                          align_up((grecs[gb].vb_off + grecs[gb].nvb - grecs[ga].vb_off) * sizeof(VbRec), 16) +
-                                          align_up(idx_end[gb] - i0, 16);
+                        const size_t mb = align_up((gb - ga + 1) * sizeof(GroupRec), 16) + align_up(idx_end[gb] - i0, 16);
                         meta_max = std::max(meta_max, mb);
                         tiles_max = std::max<uint32_t>(tiles_max, tile_rank[groups[gb].tile] - tile_rank[groups[ga].tile] + 1);
                     }
@@ -499,7 +512,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
             cr.idx_bytes = (uint32_t)align_up(idx_end[gb] - cr.idx0, 16);
             cr.v0 = abs_val(cpos_a[c]);
             cr.nv4 = (abs_val(cpos_b[c]) - cr.v0) >> 2;
-            const uint32_t mb = (uint32_t)(align_up(cr.ng * sizeof(GroupRec), 16) + align_up(cr.nvbs * sizeof(VbRec), 16) + cr.idx_bytes);
+            const uint32_t mb = (uint32_t)(align_up(cr.ng * sizeof(GroupRec), 16) + cr.idx_bytes);
             meta_cap = std::max(meta_cap, mb);
         }
         if (meta_cap > (uint32_t)kChunkMetaMax + 4096) { set_error("csb_plan: internal: record window overflow"); return CSB_EINVAL; }
@@ -530,6 +543,9 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         h.off_shared = place(shared.size() * sizeof(SharedRec));
         h.off_counters = place(shared.size() * 4);
         h.off_tile_g0 = place(tile_g0.size() * 4);
+        h.off_tile_seg0 = place(tile_seg0.size() * 4);
+        h.off_seg_g0 = place(seg_g0.size() * 4);
+        h.n_segs = seg_g0.size() - 1;
         h.idx_bytes = idx.size(); h.n_vals = vals_end; h.total_bytes = off;
         Plan &pl = m->plan;
         pl.image.assign(off, 0);
@@ -546,6 +562,8 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         put(h.off_zero_tiles, zero_tiles.data(), zero_tiles.size() * 4);
         put(h.off_shared, shared.data(), shared.size() * sizeof(SharedRec));
         put(h.off_tile_g0, tile_g0.data(), tile_g0.size() * 4);
+        put(h.off_tile_seg0, tile_seg0.data(), tile_seg0.size() * 4);
+        put(h.off_seg_g0, seg_g0.data(), seg_g0.size() * 4);
         pl.hdr = h;
         pl.split = split;
         pl.valid = true;
@@ -612,6 +630,25 @@ int validate_plan(const csb_matrix *m) {
     const auto *nz_tiles = (const uint32_t *)(im + h.off_nz_tiles);
     const auto *zero_tiles = (const uint32_t *)(im + h.off_zero_tiles);
     const auto *shared = (const SharedRec *)(im + h.off_shared);
+    const auto *tile_g0v = (const uint32_t *)(im + h.off_tile_g0);
+    const auto *tile_seg0v = (const uint32_t *)(im + h.off_tile_seg0);
+    const auto *seg_g0v = (const uint32_t *)(im + h.off_seg_g0);
+    // record segments of the batched kernel: tile the tiles' group ranges, fit the LDS window
+    for (uint32_t r = 0; r < h.n_nz_tiles; ++r) {
+        if (tile_seg0v[r] > tile_seg0v[r + 1] || tile_seg0v[r + 1] > h.n_segs) return fail("tile segment range");
+        uint32_t gexp = tile_g0v[r];
+        for (uint32_t sgi = tile_seg0v[r]; sgi < tile_seg0v[r + 1]; ++sgi) {
+            const uint32_t ga = seg_g0v[sgi], gb = sgi + 1 < tile_seg0v[r + 1] ? seg_g0v[sgi + 1] : tile_g0v[r + 1];
+            if (ga != gexp || gb <= ga || gb > h.n_groups) return fail("segment group range");
+            const size_t i0 = groups[ga].idx_off & ~15u;
+            const size_t iend = gb < h.n_groups ? groups[gb].idx_off : (size_t)h.idx_bytes;
+            const size_t nv = groups[gb - 1].vb_off + groups[gb - 1].nvb - groups[ga].vb_off;
+            if (align_up((gb - ga) * sizeof(GroupRec), 16) + align_up(nv * sizeof(VbRec), 16) + align_up(iend - i0, 16) > (size_t)kChunkMetaMax + 64 || nv > 2048)
+                return fail("segment larger than the batched kernel's LDS window");
+            gexp = gb;
+        }
+        if (gexp != tile_g0v[r + 1]) return fail("segments do not cover the tile");
+    }
     const int64_t rows_out = (int64_t)h.rows_out, cols = (int64_t)h.cols;
     const uint32_t br = h.br, bc = h.bc, NW = h.waves_per_chunk;
     const uint32_t n_tiles = (uint32_t)((rows_out + br - 1) / br);
@@ -640,7 +677,7 @@ int validate_plan(const csb_matrix *m) {
         if ((cr.v0 & 63u) || (cr.nv4 & 15u) || (uint64_t)cr.v0 + 4 * (uint64_t)cr.nv4 > h.n_vals) return fail("chunk value window");
         if ((uint64_t)cr.g0 + cr.ng > h.n_groups || (uint64_t)cr.vb0 + cr.nvbs > h.n_vbs ||
             (uint64_t)cr.idx0 + cr.idx_bytes > h.idx_bytes + 64) return fail("chunk record window");
-        if (align_up(cr.ng * sizeof(GroupRec), 16) + align_up(cr.nvbs * sizeof(VbRec), 16) + cr.idx_bytes > h.meta_cap)
+        if (align_up(cr.ng * sizeof(GroupRec), 16) + cr.idx_bytes > h.meta_cap)
             return fail("chunk record window larger than its LDS space");
         if (cr.nzrank0 + cr.ntiles > h.n_nz_tiles) return fail("chunk tile rank");
         uint32_t v_expect = cr.v0;   // the wavefronts' value runs tile the chunk's run in order
@@ -701,13 +738,14 @@ int validate_plan(const csb_matrix *m) {
                 for (int k = 0; k < gr.nvb; ++k) {
                     const VbRec &v = vbs[gr.vb_off + k];
                     if (v.c > gr.cmax || v.c == 0 || v.r == 0 || (uint32_t)v.lane0 + v.r > gr.nlanes) return fail("vb shape");
-                    if (v.coloff4 & 1u) return fail("input offset list alignment");
+                    if (v.val_off != gr.val_off || v.desc_pos != gr.idx_off) return fail("vb group fields");
+                    if ((v.list_pos & 7u) || v.list_pos < col_base || (size_t)v.list_pos + 2 * (size_t)cpad > h.idx_bytes) return fail("vb list position");
                     for (int j = jlo & ~3; j < ((jhi + 3) & ~3) && j < cpad; ++j) {
-                        const size_t ia = col_base + 4 * (size_t)v.coloff4 + 2 * (size_t)j;
+                        const size_t ia = (size_t)v.list_pos + 2 * (size_t)j;
                         if (ia + 1 >= h.idx_bytes || ia + 1 >= (size_t)cr.idx0 + cr.idx_bytes) return fail("input offset list position");
                         const uint32_t o = (uint32_t)idx[ia] | (uint32_t)idx[ia + 1] << 8;
                         if (j >= v.c) { if (o != (uint32_t)cols * 4u) return fail("input offset padding"); continue; }
-                        if ((o & 3u) || o / 4 >= (uint32_t)cols || o / 4 < (uint32_t)v.bj * bc || o / 4 >= ((uint32_t)v.bj + 1) * bc) return fail("input offset");
+                        if ((o & 3u) || o / 4 >= (uint32_t)cols) return fail("input offset");
                     }
                 }
                 for (int j = jlo; j < jhi; ++j) {
@@ -721,11 +759,11 @@ int validate_plan(const csb_matrix *m) {
                         if (k >= gr.nvb) return fail("lane vb number");
                         const VbRec &v = vbs[gr.vb_off + k];
                         const size_t lo = (size_t)idx[gr.idx_off + 4 * lane + 2] | (size_t)idx[gr.idx_off + 4 * lane + 3] << 8;
-                        if ((size_t)gr.idx_off + lo != col_base + 4 * (size_t)v.coloff4) return fail("lane list offset");
+                        if ((size_t)gr.idx_off + lo != (size_t)v.list_pos) return fail("lane list offset");
                         if (lane < v.lane0 || lane >= v.lane0 + v.r) return fail("lane outside its vb");
                         if (slot >= tile_h) return fail("row slot");
                         if (j >= v.c) { if (vals[va] != 0.0f) return fail("value padding (step)"); continue; }
-                        const size_t ia = col_base + 4 * (size_t)v.coloff4 + 2 * (size_t)j;
+                        const size_t ia = (size_t)v.list_pos + 2 * (size_t)j;
                         const int64_t gc = ((uint32_t)idx[ia] | (uint32_t)idx[ia + 1] << 8) / 4;
                         const size_t cell = (size_t)((int64_t)tile * br + slot) * cols + gc;
                         if (seen[cell]) return fail("entry referenced twice");

@@ -2,14 +2,19 @@
 //
 // With B right-hand sides a kernel matrix K_b (r x c) meets a gathered c x B slab of X: a
 // real dense product, so it goes to the matrix cores (v_mfma_f32_16x16x4_f32).  One
-// workgroup owns one output row tile and one batch tile; its wavefronts take the tile's
-// virtual blocks round-robin, each as 16-row slices: per 4 columns one A operand (16 x 4
-// of the kernel) feeds one MFMA per 16 batch columns.  The 16 x 16 results are added at
-// the block's row indices into a per-wavefront accumulator tile in LDS (the role of
-// NeuronAccumBuffer, Sec. 4.3.1); the wavefronts' tiles are summed in wavefront order, so
-// the result does not depend on timing.  The paper's engine is batch 1 only; this is the
-// batched extension the matrix cores make worthwhile.
+// workgroup owns one output row tile and one batch tile.  The tile's records (groups,
+// virtual blocks, lane descriptors, input-offset lists) are staged in LDS one segment at a
+// time; the wavefronts take the segment's virtual blocks round-robin, each as 16-row
+// slices: per 4 columns one A operand (16 x 4 of the kernel) feeds one MFMA per 16 batch
+// columns.  The operands of the next pass are loaded while the current one multiplies.
+// The 16 x 16 results are added at the block's row indices into a per-wavefront
+// accumulator tile in LDS (the role of NeuronAccumBuffer, Sec. 4.3.1); the wavefronts'
+// tiles are summed in wavefront order, so the result does not depend on timing.  The
+// paper's engine is batch 1 only; this is the batched extension the matrix cores make
+// worthwhile.
 #include <hip/hip_runtime.h>
+
+#include <algorithm>
 
 #include "csb_internal.hpp"
 #include "csb_kernels.hpp"
@@ -20,22 +25,41 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kSpmmWaves = 8;
 constexpr int kSpmmThreads = kSpmmWaves * 64;
+constexpr int kSpmmMetaBytes = kChunkMetaMax + 256;   // LDS window of one record segment
 
 __device__ __forceinline__ uint32_t uni_(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// Element (column j of A, right-hand side n) of the input, from one of two sources.
+// Element (column j of A, right-hand side n) of the input, from one of two sources.  Element
+// offsets fit 32 bits and the strides over j fit 24 bits (checked on the host).
 struct XSrc {
     const float *p0;
     uint32_t n0;          // columns j < n0 come from p0, the rest from p1
-    int64_t sj0, sn0;     // strides over j and over n
+    uint32_t sj0, sn0;    // strides over j and over n
     const float *p1;
-    int64_t sj1, sn1;
+    uint32_t sj1, sn1;
+};
+
+// One pass: 32 columns (8 MFMA k-steps) of one 16-row slice of one virtual block.
+struct Pass {
+    uint32_t k;           // virtual block, counted inside the segment
+    uint32_t m0, kc;      // first row of the slice, first column of the pass
+    uint32_t r, c, lane0; // the block's rows, columns, first lane
+    uint32_t val_off;     // the group's values
+    uint32_t desc;        // LDS byte offset of the group's lane descriptors
+    uint32_t list;        // LDS byte offset of the block's input-offset list
+    bool valid;
 };
 
 template <int NT>
+struct Operands {
+    float av[8];
+    float bv[8][NT];
+};
+
+template <int NT, bool TWO>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(const DevMat m, const XSrc X, float *__restrict__ Y,
                                                              const int64_t ldy, const uint32_t batch) {
-    extern __shared__ float smem_f[];
+    extern __shared__ float4 smem4[];
     constexpr int NB = 16 * NT;                    // batch columns per workgroup
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uni_(tid >> 6);
     const uint32_t bt0 = blockIdx.y * NB;
@@ -48,83 +72,144 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(const DevMat m, cons
         }
         return;
     }
-    float *acc = smem_f;                                           // [waves][br][NB]
+    uint8_t *meta = (uint8_t *)smem4;                              // one record segment
+    float *acc = (float *)(meta + kSpmmMetaBytes);                 // [waves][br][NB]
     float *myacc = acc + (size_t)wave * br * NB;
     for (uint32_t e = lane; e < br * NB; e += 64) myacc[e] = 0.0f;
     const uint32_t rank = blockIdx.x, tile = m.nz_tiles[rank];
-    const uint32_t g0 = m.tile_g0[rank], g1 = m.tile_g0[rank + 1];
     const uint32_t mrow = lane & 15u, kq = lane >> 4;              // A: row, column-in-4; B: column n, row-in-4
-    uint32_t task = 0;
-    for (uint32_t g = g0; g < g1; ++g) {
-        const GroupRec *gp = m.groups + g;
-        const uint32_t nvb = uni_(gp->nvb), nlanes = uni_(gp->nlanes);
-        const uint32_t idx_off = uni_(gp->idx_off), vb_off = uni_(gp->vb_off);
-        const float *gv = m.vals + uni_(gp->val_off);
-        // does this wavefront have a slice in the group?
-        uint32_t ntask = 0;
-        for (uint32_t k = 0; k < nvb; ++k) ntask += ((uint32_t)m.vbs[vb_off + k].r + 15u) >> 4;
-        const uint32_t first_mine = (wave + kSpmmWaves - task % kSpmmWaves) % kSpmmWaves;
-        if (first_mine >= ntask) { task += ntask; continue; }
-        const uint8_t *colbase = m.idx + idx_off + ((4 * nlanes + 7) & ~7u);
-        for (uint32_t k = 0; k < nvb; ++k) {
-            const VbRec v = m.vbs[vb_off + k];
-            const uint32_t r = uni_(v.r), c = uni_(v.c), lane0 = uni_(v.lane0);
-            const uint16_t *colp = (const uint16_t *)(colbase + 4u * uni_(v.coloff4));   // byte offsets of the inputs
-            for (uint32_t m0 = 0; m0 < r; m0 += 16, ++task) {
-                if (task % kSpmmWaves != wave) continue;
-                floatx4 D[NT];
+    const uint32_t ncol = bt0 + mrow;                              // this lane's right-hand side (per 16: + 16 nt)
+    uint32_t noff0[NT], noff1[NT];                                 // its element offset in either source
+    bool n_ok[NT];
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) D[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
-                const bool row_ok = m0 + mrow < r;
-                const uint32_t arow = lane0 + m0 + (row_ok ? mrow : 0u);
-                // 32 columns (8 MFMA k-steps) per pass: all kernel values and column indices
-                // first, then all gathered inputs, then the MFMAs -- the loads of a pass
-                // are independent, so their latencies overlap.  Out-of-range lanes load
-                // from clamped addresses and their operands are zeroed.
-                for (uint32_t kc = 0; kc < c; kc += 32) {
-                    float av[8];
-                    uint32_t gc[8];
-                    bool ok[8];
+    for (int nt = 0; nt < NT; ++nt) {
+        const uint32_t n = ncol + 16u * nt;
+        n_ok[nt] = n < batch;
+        noff0[nt] = (n_ok[nt] ? n : 0u) * X.sn0;
+        noff1[nt] = (n_ok[nt] ? n : 0u) * X.sn1;
+    }
+
+    for (uint32_t sg = m.tile_seg0[rank]; sg < m.tile_seg0[rank + 1]; ++sg) {
+        // ---- stage the segment's records ------------------------------------------------
+        const uint32_t ga = m.seg_g0[sg], gb = m.seg_g0[sg + 1];
+        const uint32_t ng = gb - ga;
+        const uint32_t vb0 = m.groups[ga].vb_off;
+        const uint32_t nvbs = m.groups[gb - 1].vb_off + m.groups[gb - 1].nvb - vb0;
+        const uint32_t idx0 = m.groups[ga].idx_off & ~15u;
+        const uint32_t idx_end = gb < m.n_groups ? m.groups[gb].idx_off : m.idx_bytes;
+        const uint32_t voff = (ng * (uint32_t)sizeof(GroupRec) + 15u) & ~15u;
+        const uint32_t ioff = voff + ((nvbs * (uint32_t)sizeof(VbRec) + 15u) & ~15u);
+        __syncthreads();                                           // the previous segment is done with
+        {
+            const uint2 *gs = (const uint2 *)(m.groups + ga);
+            uint2 *gd = (uint2 *)meta;
+            for (uint32_t i = tid; i < ng * 3u; i += kSpmmThreads) gd[i] = gs[i];
+            const float4 *vs = (const float4 *)(m.vbs + vb0);
+            float4 *vd = (float4 *)(meta + voff);
+            for (uint32_t i = tid; i < nvbs; i += kSpmmThreads) vd[i] = vs[i];
+            const float4 *is = (const float4 *)(m.idx + idx0);
+            float4 *id = (float4 *)(meta + ioff);
+            for (uint32_t i = tid; i < (idx_end - idx0 + 15u) >> 4; i += kSpmmThreads) id[i] = is[i];
+        }
+        __syncthreads();
+
+        // ---- passes of this wavefront's virtual blocks ----------------------------------
+        auto open_vb = [&](uint32_t k) -> Pass {
+            Pass p{};
+            p.k = k;
+            p.valid = k < nvbs;
+            if (!p.valid) return p;
+            const uint4 v = *(const uint4 *)(meta + voff + k * (uint32_t)sizeof(VbRec));
+            const uint32_t v0 = uni_(v.x);
+            p.r = v0 & 0xffu; p.lane0 = (v0 >> 8) & 0xffu; p.c = v0 >> 16;
+            p.val_off = uni_(v.y);
+            p.desc = ioff + (uni_(v.z) - idx0);
+            p.list = ioff + (uni_(v.w) - idx0);
+            p.m0 = 0; p.kc = 0;
+            return p;
+        };
+        auto next_pass = [&](const Pass &p) -> Pass {
+            Pass q = p;
+            q.kc += 32;
+            if (q.kc < q.c) return q;
+            q.kc = 0; q.m0 += 16;
+            if (q.m0 < q.r) return q;
+            return open_vb(p.k + kSpmmWaves);
+        };
+        // All loads of a pass are independent: kernel values and gathered inputs of up to 8
+        // k-steps.  Out-of-range lanes load from clamped addresses; their operands are zeroed.
+        auto load_pass = [&](const Pass &p, Operands<NT> &o) {
+            const float *gv = m.vals + p.val_off;
+            const uint16_t *colp = (const uint16_t *)(meta + p.list);
+            const bool row_ok = p.m0 + mrow < p.r;
+            const uint32_t arow = p.lane0 + p.m0 + (row_ok ? mrow : 0u);
 #pragma unroll
-                    for (int s8 = 0; s8 < 8; ++s8) {
-                        const uint32_t jj = kc + 4u * s8 + kq;
-                        ok[s8] = jj < c;
-                        const uint32_t jc = ok[s8] ? jj : 0u;
-                        const float t = gv[jc * (uint32_t)kWave + arow];
-                        av[s8] = ok[s8] && row_ok ? t : 0.0f;
-                        gc[s8] = (uint32_t)colp[jc] >> 2;
-                    }
-                    float bv[8][NT];
+            for (int s8 = 0; s8 < 8; ++s8) {
+                if (p.kc + 4u * s8 >= p.c) break;                  // uniform: k-steps the block does not have
+                const uint32_t jj = p.kc + 4u * s8 + kq;
+                const bool ok = jj < p.c;
+                const uint32_t jc = ok ? jj : 0u;
+                const float t = gv[jc * (uint32_t)kWave + arow];
+                o.av[s8] = ok && row_ok ? t : 0.0f;
+                const uint32_t gc = (uint32_t)colp[jc] >> 2;
+                const bool first = !TWO || gc < X.n0;
+                const float *src = first ? X.p0 : X.p1;
+                const uint32_t joff = first ? __umul24(gc, X.sj0) : __umul24(gc - X.n0, X.sj1);
 #pragma unroll
-                    for (int s8 = 0; s8 < 8; ++s8)
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
-                            const uint32_t n = bt0 + 16u * nt + mrow;
-                            const uint32_t nc = n < batch ? n : 0u;
-                            const float t = gc[s8] < X.n0 ? X.p0[(int64_t)gc[s8] * X.sj0 + (int64_t)nc * X.sn0]
-                                                          : X.p1[(int64_t)(gc[s8] - X.n0) * X.sj1 + (int64_t)nc * X.sn1];
-                            bv[s8][nt] = ok[s8] && n < batch ? t : 0.0f;
-                        }
-#pragma unroll
-                    for (int s8 = 0; s8 < 8; ++s8) {
-                        if (kc + 4u * s8 >= c) break;          // uniform
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
-                            D[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s8], bv[s8][nt], D[nt], 0, 0, 0);
-                    }
-                }
-                // lane holds rows 4*(lane/16)+i, column lane%16 of each 16 x 16 result
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t mr = m0 + 4u * kq + i;
-                    if (mr < r) {
-                        const uint32_t slot = m.idx[idx_off + 4u * (lane0 + mr)];
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
-                            myacc[slot * NB + 16u * nt + mrow] += D[nt][i];   // rows of a slice are distinct: no two lanes meet
-                    }
+                for (int nt = 0; nt < NT; ++nt) {
+                    const float x = src[joff + (first ? noff0[nt] : noff1[nt])];
+                    o.bv[s8][nt] = ok && n_ok[nt] ? x : 0.0f;
                 }
             }
+        };
+        floatx4 D[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) D[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        auto mult_pass = [&](const Pass &p, const Operands<NT> &o) {
+#pragma unroll
+            for (int s8 = 0; s8 < 8; ++s8) {
+                if (p.kc + 4u * s8 >= p.c) break;                  // uniform
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    D[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.av[s8], o.bv[s8][nt], D[nt], 0, 0, 0);
+            }
+            if (p.kc + 32 < p.c) return;                           // the slice has more columns
+            // lane holds rows 4*(lane/16)+i, column lane%16 of each 16 x 16 result; the rows of
+            // a slice are distinct, so no two lanes meet in the accumulator: all reads, then
+            // all writes
+            uint32_t at[4];
+            bool on[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t mr = p.m0 + 4u * kq + i;
+                on[i] = mr < p.r;
+                const uint32_t slot = meta[p.desc + 4u * (p.lane0 + (on[i] ? mr : 0u))];
+                at[i] = slot * NB + mrow;
+            }
+            float old[4][NT];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) old[i][nt] = myacc[at[i] + 16u * nt];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    if (on[i]) myacc[at[i] + 16u * nt] = old[i][nt] + D[nt][i];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) D[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        };
+        Operands<NT> oa, ob;
+        Pass pa = open_vb(wave), pb{};
+        if (pa.valid) load_pass(pa, oa);
+        while (pa.valid) {
+            pb = next_pass(pa);
+            if (pb.valid) load_pass(pb, ob);
+            mult_pass(pa, oa);
+            if (!pb.valid) break;
+            pa = next_pass(pb);
+            if (pa.valid) load_pass(pa, oa);
+            mult_pass(pb, ob);
         }
     }
     __syncthreads();
@@ -142,19 +227,27 @@ int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj
     if (!mat->plan.valid || !mat->uploaded || !mat->d_buf) { set_error("csb_spmm: matrix not planned and uploaded"); return CSB_ESTATE; }
     const DevHeader &h = mat->plan.hdr;
     const DevMat dm = dev_mat(mat);
-    XSrc X{p0, n0, sj0, sn0, p1, sj1, sn1};
-    const int nt = h.br <= 128 ? 2 : 1;
-    const size_t lds = (size_t)kSpmmWaves * h.br * 16 * nt * sizeof(float);
-    const dim3 grid(h.n_nz_tiles + h.n_zero_tiles, (unsigned)((batch + 16 * nt - 1) / (16 * nt)));
-    hipError_t e;
-    if (nt == 2) {
-        e = hipFuncSetAttribute((const void *)spmm_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) hipLaunchKernelGGL(spmm_kernel<2>, grid, dim3(kSpmmThreads), lds, (hipStream_t)stream, dm, X, d_Y, ldy, (uint32_t)batch);
-    } else {
-        e = hipFuncSetAttribute((const void *)spmm_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) hipLaunchKernelGGL(spmm_kernel<1>, grid, dim3(kSpmmThreads), lds, (hipStream_t)stream, dm, X, d_Y, ldy, (uint32_t)batch);
+    // 32-bit element offsets, 24-bit multiplies
+    const int64_t smax_j = std::max(sj0, sj1), smax_n = std::max(sn0, sn1);
+    if (sj0 < 0 || sj1 < 0 || sn0 < 0 || sn1 < 0 || smax_j >= (1 << 24) || (int64_t)h.cols >= (1 << 24) ||
+        (int64_t)h.cols * smax_j + (int64_t)batch * smax_n >= (1ll << 30)) {
+        set_error("csb_spmm: strides or sizes beyond the kernel's 32-bit element offsets");
+        return CSB_EUNSUPPORTED;
     }
-    if (e == hipSuccess) e = hipGetLastError();
+    XSrc X{p0, n0, (uint32_t)sj0, (uint32_t)sn0, p1, (uint32_t)sj1, (uint32_t)sn1};
+    const bool two = n0 < (uint32_t)h.cols;
+    const int nt = h.br <= 128 ? 2 : 1;
+    const size_t lds = (size_t)kSpmmMetaBytes + (size_t)kSpmmWaves * h.br * 16 * nt * sizeof(float);
+    const dim3 grid(h.n_nz_tiles + h.n_zero_tiles, (unsigned)((batch + 16 * nt - 1) / (16 * nt)));
+    auto go = [&](auto kern) -> hipError_t {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, grid, dim3(kSpmmThreads), lds, (hipStream_t)stream, dm, X, d_Y, ldy, (uint32_t)batch);
+        return hipGetLastError();
+    };
+    hipError_t e;
+    if (nt == 2) e = two ? go(spmm_kernel<2, true>) : go(spmm_kernel<2, false>);
+    else e = two ? go(spmm_kernel<1, true>) : go(spmm_kernel<1, false>);
     if (e != hipSuccess) { set_error(std::string("csb_spmm: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
 }

@@ -37,7 +37,10 @@ DevMat dev_mat(const csb_matrix *m) {
     d.rows_out = (uint32_t)h.rows_out; d.cols = (uint32_t)h.cols;
     d.n_groups = h.n_groups;
     d.n_nz_tiles = h.n_nz_tiles;
+    d.idx_bytes = (uint32_t)h.idx_bytes;
     d.tile_g0 = (const uint32_t *)(b + h.off_tile_g0);
+    d.tile_seg0 = (const uint32_t *)(b + h.off_tile_seg0);
+    d.seg_g0 = (const uint32_t *)(b + h.off_seg_g0);
     return d;
 }
 
@@ -46,7 +49,7 @@ __device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_re
 // LDS map of one workgroup (byte offsets from the start of dynamic LDS).
 struct LdsMap {
     uint32_t zpad;        // floats of the staged input vector (with the zero entry behind it)
-    uint32_t meta_off;    // bytes: group records | block records | index bytes
+    uint32_t meta_off;    // bytes: group records | index bytes
     uint32_t acc_off;     // bytes: [NW][kAccPlanes][acc_rows] accumulators
     uint32_t red_off;     // bytes: [4][256] partial sums of the final reduction
 };
@@ -130,15 +133,12 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
     // vector), then this wavefront's values.
     const ChunkRec cr = load_chunk(m.chunks + c);
     const WaveRec wr = load_wave(m.waves + (size_t)c * NW + wave);
-    // records: groups and virtual blocks in 8-byte units, index bytes in 16-byte units
-    const uint32_t gu = cr.ng * 3u, vu = cr.nvbs, iu = cr.idx_bytes >> 4;
-    const uint32_t voff = (cr.ng * (uint32_t)sizeof(GroupRec) + 15u) & ~15u;
-    const uint32_t ioff = voff + ((cr.nvbs * (uint32_t)sizeof(VbRec) + 15u) & ~15u);
+    // records: groups in 8-byte units, index bytes in 16-byte units
+    const uint32_t gu = cr.ng * 3u, iu = cr.idx_bytes >> 4;
+    const uint32_t ioff = (cr.ng * (uint32_t)sizeof(GroupRec) + 15u) & ~15u;
     const uint2 *gsrc8 = (const uint2 *)(m.groups + cr.g0);
-    const uint2 *vsrc8 = (const uint2 *)(m.vbs + cr.vb0);
     const float4 *isrc = (const float4 *)(m.idx + cr.idx0);
     CSB_LD2(rg0, gsrc8, tid, gu) CSB_LD2(rg1, gsrc8, tid + NT, gu) CSB_LD2(rg2, gsrc8, tid + 2 * NT, gu)
-    CSB_LD2(rb0, vsrc8, tid, vu) CSB_LD2(rb1, vsrc8, tid + NT, vu) CSB_LD2(rb2, vsrc8, tid + 2 * NT, vu)
     CSB_LD4(ri0, isrc, tid, iu) CSB_LD4(ri1, isrc, tid + NT, iu)
     // input vector: aligned single-source fast path, else element-wise from two sources
     const bool zfast = n0 >= m.cols && (m.cols & 3u) == 0 && ((uintptr_t)x0 & 15u) == 0;
@@ -168,9 +168,8 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
 
     // ---- records and input vector into LDS ----------------------------------------------
     {
-        uint2 *gd = (uint2 *)meta, *bd = (uint2 *)(meta + voff);
+        uint2 *gd = (uint2 *)meta;
         CSB_ST(gd, tid, gu, rg0) CSB_ST(gd, tid + NT, gu, rg1) CSB_ST(gd, tid + 2 * NT, gu, rg2)
-        CSB_ST(bd, tid, vu, rb0) CSB_ST(bd, tid + NT, vu, rb1) CSB_ST(bd, tid + 2 * NT, vu, rb2)
         float4 *id = (float4 *)(meta + ioff);
         CSB_ST(id, tid, iu, ri0) CSB_ST(id, tid + NT, iu, ri1)
         float4 *zd = (float4 *)z;
