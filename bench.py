@@ -27,6 +27,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+MFMA_F32_PEAK_TFLOPS = 157.3
+# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very command, scaled by
+# the readings of a plain 256 MiB copy (profiles/bench_hbm_traffic_pmc.txt has the commands and raw readings)
+TRAFFIC_BYTES = {
+    "rnn_resident_cfg2": {"read": 6841958, "written": 704410},
+    "spmv_cfg5": {"read": 29220659, "written": 32768},
+    "spmm_cfg5_b128": {"read": 92339200, "written": 4194304},
+}
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 
@@ -66,6 +74,9 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-stress", action="store_true", help="skip the 8192^2 SpMV stress leg")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run plain 256 MiB device copies: the known-size kernel that scales rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -108,7 +119,8 @@ def main():
     ach = bytes_step * T / (ms_per_step * 1e-3) / 1e9
     roofline = {"kernel": f"csb::rnn_resident_kernel<{st['slots_per_lane']}>", "bound": "hbm",
                 "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": None,
+                "frac": round(ach / HBM_PEAK_GBS, 5),
+                "traffic": sum(TRAFFIC_BYTES["rnn_resident_cfg2"].values()) if args.workload == "cfg2" else None,
                 "us_per_launch": round(ms_per_step * 1e3, 3), "alg_bytes_per_launch": bytes_step * T,
                 "units_per_launch": T,
                 "note": "weights stay in registers for all T steps (read from HBM once per launch); a step is "
@@ -151,8 +163,17 @@ def main():
         "streaming_path": streaming,
     }
 
+    if args.calib_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calib_copy"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "launches": 5}
+        del src, dst
     if not args.no_stress:
         out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix)
+        out["batched"] = batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_leg(cfg, wl)
     print(json.dumps(out))
@@ -210,9 +231,58 @@ def stress_leg(torch, np, csb_inputs, CsbMatrix):
             del M
     best = min((e for k, e in res.items() if k.startswith("cfg5_") and "us_cold" in e), key=lambda e: e["us_cold"])
     res["roofline"] = {"kernel": "csb::spmv_kernel", "bound": "hbm", "achieved": best["gbps_cold"], "peak": HBM_PEAK_GBS,
-                       "unit": "GB/s", "frac": best["frac_hbm_cold"], "traffic": None,
+                       "unit": "GB/s", "frac": best["frac_hbm_cold"], "traffic": sum(TRAFFIC_BYTES["spmv_cfg5"].values()),
                        "us_per_launch": best["us_cold"], "alg_bytes_per_launch": best["alg_bytes"],
                        "note": "cold: every launch reads a different device copy of the matrix"}
+    return res
+
+
+def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
+    """The batched (matrix-core) path: csb_spmm on the 8192^2 matrix with 128 right-hand sides
+    and on a cfg4 layer matrix with 64, then the whole cfg4 workload (2-layer LSTM, batch 64,
+    T = 256) through csb_rnn_forward.  Flops are the algorithmic 2 * nnz * batch."""
+    res = {}
+    for name, batch in (("cfg5", 128), ("cfg4", 64)):
+        if name == "cfg5":
+            m = csb_inputs.make_mat(csb_inputs.CONFIGS[name])
+        else:
+            m = csb_inputs.make_rnn(csb_inputs.CONFIGS[name], T=1, batch=1).W[0]
+        M = CsbMatrix(m.A, m.br, m.bc)
+        M.plan()
+        M.upload()
+        X = torch.from_numpy(csb_inputs.make_vectors(5, m.cols, batch)).cuda()
+        Y = torch.empty((m.rows, batch), dtype=torch.float32, device="cuda")
+        for _ in range(3):
+            M.spmm(X, Y)
+        n = 20
+        us = time_region(lambda: M.spmm(X, Y), n, torch) * 1000.0 / n
+        fl = 2.0 * int(M.view()["nnz"]) * batch
+        res[f"spmm_{name}_b{batch}"] = {"shape": [int(m.rows), int(m.cols)], "nnz": int(M.view()["nnz"]), "batch": batch,
+                                        "us": round(us, 2), "tflops_algorithmic": round(fl / us / 1e6, 3),
+                                        "frac_fp32_mfma_peak": round(fl / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4)}
+        del M
+    best = res["spmm_cfg5_b128"]
+    res["roofline"] = {"kernel": "csb::spmm_kernel<2,false>", "bound": "mfma", "achieved": best["tflops_algorithmic"],
+                       "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": best["frac_fp32_mfma_peak"],
+                       "traffic": sum(TRAFFIC_BYTES["spmm_cfg5_b128"].values()),
+                       "us_per_launch": best["us"], "flops_per_launch": 2.0 * best["nnz"] * best["batch"]}
+    cfg = csb_inputs.CONFIGS["cfg4"]
+    wl = csb_inputs.make_rnn(cfg)
+    Ws = [CsbMatrix(w.A, w.br, w.bc) for w in wl.W]
+    bias = [torch.from_numpy(b).cuda() for b in wl.bias]
+    rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, bias)
+    for w in Ws:
+        w.upload()
+    xd = torch.from_numpy(wl.x).cuda()
+    rnn.forward(xd, want_hseq=False)
+    n = 3
+    ms = time_region(lambda: rnn.forward(xd, want_hseq=False), n, torch) / n
+    fl_step = sum(2.0 * int(w.view()["nnz"]) * cfg.batch for w in Ws)
+    res["rnn_cfg4"] = {"workload": f"{cfg.name}: {cfg.n_layers} x LSTM {cfg.input}->{cfg.hidden}, block {cfg.block}, "
+                                   f"{cfg.rate:g}x, batch {cfg.batch}, T={cfg.T}",
+                       "us_per_timestep": round(ms * 1000.0 / cfg.T, 2),
+                       "tflops_algorithmic": round(fl_step / (ms * 1e-3 / cfg.T) / 1e12, 3),
+                       "sequences_per_s": round(cfg.batch / (ms * 1e-3), 1)}
     return res
 
 
