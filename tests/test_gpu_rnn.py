@@ -92,6 +92,29 @@ def test_rnn_batched_two_layer_shape():
     run_case(wl, tag="cfg4-T4", resident=False)
 
 
+def test_rnn_batched_full_size_sampled():
+    """cfg4 as bench.py runs it (2 x LSTM 1024 -> 1024, batch 64, T = 256, the MFMA path).  The
+    sequences of a batch are independent, so the float64 oracle runs three sampled ones on
+    their own and the device results of those batch entries must match to the same bar."""
+    cfg = csb_inputs.CONFIGS["cfg4"]
+    wl = csb_inputs.make_rnn(cfg)
+    T, B, _ = wl.x.shape
+    assert (T, B) == (256, 64)
+    say(f"[rnn] cfg4 full size T={T} B={B}")
+    rnn = build_rnn(wl, resident=False)
+    hseq, hT, cT = rnn.forward(torch.from_numpy(wl.x).cuda())
+    torch.cuda.synchronize()
+    hseq, hT, cT = hseq.cpu().numpy(), hT.cpu().numpy(), cT.cpu().numpy()
+    W = [oracle.csb_decode(oracle.csb_encode(m.A, m.br, m.bc)) for m in wl.W]
+    for b in (0, 37, 63):
+        rseq, rhT, rcT = oracle.rnn_forward(cfg.cell, W, wl.bias, np.ascontiguousarray(wl.x[:, b:b + 1]), cfg.input, cfg.hidden)
+        e_seq = float(np.max(np.abs(hseq[:, b] - rseq[:, 0])))
+        e_h = float(np.max(np.abs(hT[:, b] - rhT[:, 0])))
+        e_c = float(np.max(np.abs(cT[:, b] - rcT[:, 0])))
+        say(f"[rnn] cfg4 sequence {b}: err hseq={e_seq:.3g} hT={e_h:.3g} cT={e_c:.3g}")
+        assert e_seq <= TOL and e_h <= TOL and e_c <= TOL
+
+
 @pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
 def test_rnn_batched_ragged(cell):
     cfg = csb_inputs.RnnConfig("t", cell, 2, 37, 70, 16, 4.0, "binomial", 0.3, 19, 6, 3)
