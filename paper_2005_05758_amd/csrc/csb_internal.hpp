@@ -81,6 +81,17 @@ struct ChunkRec {
 };
 static_assert(sizeof(ChunkRec) == 64, "ChunkRec layout");
 
+// A record segment of the batched kernel: a run of groups inside one row tile whose records
+// fit the kernel's LDS window.
+struct SegRec {
+    uint32_t g0, ng;       // groups
+    uint32_t vb0, nvbs;    // their virtual-block records
+    uint32_t idx0;         // their index bytes: start, rounded down to 16
+    uint32_t idx_bytes;    // length from idx0, rounded up to 16
+    uint32_t pad[2];
+};
+static_assert(sizeof(SegRec) == 32, "SegRec layout");
+
 struct SharedRec {
     uint32_t tile;         // output tile
     uint32_t nparts;       // workgroups that hold a partial sum of it
@@ -101,7 +112,7 @@ struct DevHeader {
     uint64_t off_nz_tiles, off_zero_tiles, off_shared, off_counters;
     uint64_t off_tile_g0;      // [n_nz_tiles + 1] first group of every row tile that has work
     uint64_t off_tile_seg0;    // [n_nz_tiles + 1] first record segment of every such tile
-    uint64_t off_seg_g0;       // [n_segs + 1] first group of every record segment (never crossing tiles)
+    uint64_t off_segs;         // [n_segs] record segments (never crossing tiles)
     uint64_t n_segs;
     uint64_t idx_bytes, n_vals, total_bytes;
 };
@@ -118,7 +129,7 @@ struct DevMat {
     const uint32_t *zero_tiles;
     const uint32_t *tile_g0;
     const uint32_t *tile_seg0;
-    const uint32_t *seg_g0;
+    const SegRec *segs;
     const SharedRec *shared;
     uint32_t *counters;
     uint32_t n_chunks, waves_per_chunk, n_zero_tiles, n_shared;

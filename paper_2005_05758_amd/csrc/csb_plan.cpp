@@ -544,8 +544,19 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         h.off_counters = place(shared.size() * 4);
         h.off_tile_g0 = place(tile_g0.size() * 4);
         h.off_tile_seg0 = place(tile_seg0.size() * 4);
-        h.off_seg_g0 = place(seg_g0.size() * 4);
-        h.n_segs = seg_g0.size() - 1;
+        std::vector<SegRec> segs(seg_g0.size() - 1);
+        for (size_t i = 0; i + 1 < seg_g0.size(); ++i) {
+            const uint32_t ga = seg_g0[i], gb = seg_g0[i + 1];
+            SegRec &sr = segs[i];
+            sr = SegRec{};
+            sr.g0 = ga; sr.ng = gb - ga;
+            sr.vb0 = grecs[ga].vb_off;
+            sr.nvbs = grecs[gb - 1].vb_off + grecs[gb - 1].nvb - sr.vb0;
+            sr.idx0 = grecs[ga].idx_off & ~15u;
+            sr.idx_bytes = (uint32_t)align_up(idx_end[gb - 1] - sr.idx0, 16);
+        }
+        h.off_segs = place(segs.size() * sizeof(SegRec));
+        h.n_segs = segs.size();
         h.idx_bytes = idx.size(); h.n_vals = vals_end; h.total_bytes = off;
         Plan &pl = m->plan;
         pl.image.assign(off, 0);
@@ -563,7 +574,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         put(h.off_shared, shared.data(), shared.size() * sizeof(SharedRec));
         put(h.off_tile_g0, tile_g0.data(), tile_g0.size() * 4);
         put(h.off_tile_seg0, tile_seg0.data(), tile_seg0.size() * 4);
-        put(h.off_seg_g0, seg_g0.data(), seg_g0.size() * 4);
+        put(h.off_segs, segs.data(), segs.size() * sizeof(SegRec));
         pl.hdr = h;
         pl.split = split;
         pl.valid = true;
@@ -632,18 +643,21 @@ int validate_plan(const csb_matrix *m) {
     const auto *shared = (const SharedRec *)(im + h.off_shared);
     const auto *tile_g0v = (const uint32_t *)(im + h.off_tile_g0);
     const auto *tile_seg0v = (const uint32_t *)(im + h.off_tile_seg0);
-    const auto *seg_g0v = (const uint32_t *)(im + h.off_seg_g0);
+    const auto *segsv = (const SegRec *)(im + h.off_segs);
     // record segments of the batched kernel: tile the tiles' group ranges, fit the LDS window
     for (uint32_t r = 0; r < h.n_nz_tiles; ++r) {
         if (tile_seg0v[r] > tile_seg0v[r + 1] || tile_seg0v[r + 1] > h.n_segs) return fail("tile segment range");
         uint32_t gexp = tile_g0v[r];
         for (uint32_t sgi = tile_seg0v[r]; sgi < tile_seg0v[r + 1]; ++sgi) {
-            const uint32_t ga = seg_g0v[sgi], gb = sgi + 1 < tile_seg0v[r + 1] ? seg_g0v[sgi + 1] : tile_g0v[r + 1];
-            if (ga != gexp || gb <= ga || gb > h.n_groups) return fail("segment group range");
-            const size_t i0 = groups[ga].idx_off & ~15u;
+            const SegRec &sr = segsv[sgi];
+            const uint32_t ga = sr.g0, gb = sr.g0 + sr.ng;
+            if (ga != gexp || sr.ng == 0 || gb > h.n_groups) return fail("segment group range");
+            if (sr.vb0 != groups[ga].vb_off || sr.nvbs != groups[gb - 1].vb_off + groups[gb - 1].nvb - sr.vb0 ||
+                (uint64_t)sr.vb0 + sr.nvbs > h.n_vbs) return fail("segment block records");
             const size_t iend = gb < h.n_groups ? groups[gb].idx_off : (size_t)h.idx_bytes;
-            const size_t nv = groups[gb - 1].vb_off + groups[gb - 1].nvb - groups[ga].vb_off;
-            if (align_up((gb - ga) * sizeof(GroupRec), 16) + align_up(nv * sizeof(VbRec), 16) + align_up(iend - i0, 16) > (size_t)kChunkMetaMax + 64 || nv > 2048)
+            if (sr.idx0 != (groups[ga].idx_off & ~15u) || (sr.idx_bytes & 15u) || (size_t)sr.idx0 + sr.idx_bytes < iend ||
+                (size_t)sr.idx0 + sr.idx_bytes > h.idx_bytes + 64) return fail("segment index bytes");
+            if (align_up(sr.ng * sizeof(GroupRec), 16) + align_up(sr.nvbs * sizeof(VbRec), 16) + sr.idx_bytes > (size_t)kChunkMetaMax + 64 || sr.nvbs > 2048)
                 return fail("segment larger than the batched kernel's LDS window");
             gexp = gb;
         }

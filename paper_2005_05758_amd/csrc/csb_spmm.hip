@@ -23,8 +23,6 @@ namespace csb {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kSpmmWaves = 8;
-constexpr int kSpmmThreads = kSpmmWaves * 64;
 constexpr int kSpmmMetaBytes = kChunkMetaMax + 256;   // LDS window of one record segment
 
 __device__ __forceinline__ uint32_t uni_(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -56,17 +54,18 @@ struct Operands {
     float bv[8][NT];
 };
 
-template <int NT, bool TWO>
-__global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(const DevMat m, const XSrc X, float *__restrict__ Y,
+template <int NT, bool TWO, int NW>
+__global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSrc X, float *__restrict__ Y,
                                                              const int64_t ldy, const uint32_t batch) {
     extern __shared__ float4 smem4[];
     constexpr int NB = 16 * NT;                    // batch columns per workgroup
+    constexpr uint32_t NTHR = NW * 64;             // NW wavefronts
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uni_(tid >> 6);
     const uint32_t bt0 = blockIdx.y * NB;
     const uint32_t br = m.br;
     if (blockIdx.x >= m.n_nz_tiles) {              // a row tile without work: zeros
         const uint32_t tile = m.zero_tiles[blockIdx.x - m.n_nz_tiles];
-        for (uint32_t e = tid; e < br * NB; e += kSpmmThreads) {
+        for (uint32_t e = tid; e < br * NB; e += NTHR) {
             const uint32_t row = tile * br + e / NB, n = bt0 + e % NB;
             if (row < m.rows_out && n < batch) Y[(size_t)row * ldy + n] = 0.0f;
         }
@@ -91,25 +90,21 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(const DevMat m, cons
 
     for (uint32_t sg = m.tile_seg0[rank]; sg < m.tile_seg0[rank + 1]; ++sg) {
         // ---- stage the segment's records ------------------------------------------------
-        const uint32_t ga = m.seg_g0[sg], gb = m.seg_g0[sg + 1];
-        const uint32_t ng = gb - ga;
-        const uint32_t vb0 = m.groups[ga].vb_off;
-        const uint32_t nvbs = m.groups[gb - 1].vb_off + m.groups[gb - 1].nvb - vb0;
-        const uint32_t idx0 = m.groups[ga].idx_off & ~15u;
-        const uint32_t idx_end = gb < m.n_groups ? m.groups[gb].idx_off : m.idx_bytes;
+        const SegRec *sp = m.segs + sg;
+        const uint32_t ga = sp->g0, ng = sp->ng, vb0 = sp->vb0, nvbs = sp->nvbs, idx0 = sp->idx0, idx_bytes = sp->idx_bytes;
         const uint32_t voff = (ng * (uint32_t)sizeof(GroupRec) + 15u) & ~15u;
         const uint32_t ioff = voff + ((nvbs * (uint32_t)sizeof(VbRec) + 15u) & ~15u);
         __syncthreads();                                           // the previous segment is done with
         {
             const uint2 *gs = (const uint2 *)(m.groups + ga);
             uint2 *gd = (uint2 *)meta;
-            for (uint32_t i = tid; i < ng * 3u; i += kSpmmThreads) gd[i] = gs[i];
+            for (uint32_t i = tid; i < ng * 3u; i += NTHR) gd[i] = gs[i];
             const float4 *vs = (const float4 *)(m.vbs + vb0);
             float4 *vd = (float4 *)(meta + voff);
-            for (uint32_t i = tid; i < nvbs; i += kSpmmThreads) vd[i] = vs[i];
+            for (uint32_t i = tid; i < nvbs; i += NTHR) vd[i] = vs[i];
             const float4 *is = (const float4 *)(m.idx + idx0);
             float4 *id = (float4 *)(meta + ioff);
-            for (uint32_t i = tid; i < (idx_end - idx0 + 15u) >> 4; i += kSpmmThreads) id[i] = is[i];
+            for (uint32_t i = tid; i < idx_bytes >> 4; i += NTHR) id[i] = is[i];
         }
         __syncthreads();
 
@@ -134,7 +129,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(const DevMat m, cons
             if (q.kc < q.c) return q;
             q.kc = 0; q.m0 += 16;
             if (q.m0 < q.r) return q;
-            return open_vb(p.k + kSpmmWaves);
+            return open_vb(p.k + NW);
         };
         // All loads of a pass are independent: kernel values and gathered inputs of up to 8
         // k-steps.  Out-of-range lanes load from clamped addresses; their operands are zeroed.
@@ -213,10 +208,10 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(const DevMat m, cons
         }
     }
     __syncthreads();
-    for (uint32_t e = tid; e < br * NB; e += kSpmmThreads) {
+    for (uint32_t e = tid; e < br * NB; e += NTHR) {
         float s = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kSpmmWaves; ++w) s += acc[(size_t)w * br * NB + e];
+        for (int w = 0; w < NW; ++w) s += acc[(size_t)w * br * NB + e];
         const uint32_t row = tile * br + e / NB, n = bt0 + e % NB;
         if (row < m.rows_out && n < batch) Y[(size_t)row * ldy + n] = s;
     }
@@ -237,17 +232,27 @@ int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj
     XSrc X{p0, n0, (uint32_t)sj0, (uint32_t)sn0, p1, (uint32_t)sj1, (uint32_t)sn1};
     const bool two = n0 < (uint32_t)h.cols;
     const int nt = h.br <= 128 ? 2 : 1;
-    const size_t lds = (size_t)kSpmmMetaBytes + (size_t)kSpmmWaves * h.br * 16 * nt * sizeof(float);
     const dim3 grid(h.n_nz_tiles + h.n_zero_tiles, (unsigned)((batch + 16 * nt - 1) / (16 * nt)));
+    // 16 wavefronts share a tile's blocks when their accumulator tiles fit LDS and the grid
+    // alone would not give every CU of an MI355X (256) two workgroups; else 8
+    const size_t acc_per_wave = (size_t)h.br * 16 * nt * sizeof(float);
+    const bool fits16 = (size_t)kSpmmMetaBytes + 16 * acc_per_wave <= (size_t)kLdsBudget;
+    const int nw = fits16 && (size_t)grid.x * grid.y < 2 * 256 ? 16 : 8;
+    const size_t lds = (size_t)kSpmmMetaBytes + (size_t)nw * acc_per_wave;
     auto go = [&](auto kern) -> hipError_t {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, dim3(kSpmmThreads), lds, (hipStream_t)stream, dm, X, d_Y, ldy, (uint32_t)batch);
+        hipLaunchKernelGGL(kern, grid, dim3(nw * 64), lds, (hipStream_t)stream, dm, X, d_Y, ldy, (uint32_t)batch);
         return hipGetLastError();
     };
     hipError_t e;
-    if (nt == 2) e = two ? go(spmm_kernel<2, true>) : go(spmm_kernel<2, false>);
-    else e = two ? go(spmm_kernel<1, true>) : go(spmm_kernel<1, false>);
+    if (nw == 16) {
+        if (nt == 2) e = two ? go(spmm_kernel<2, true, 16>) : go(spmm_kernel<2, false, 16>);
+        else e = two ? go(spmm_kernel<1, true, 16>) : go(spmm_kernel<1, false, 16>);
+    } else {
+        if (nt == 2) e = two ? go(spmm_kernel<2, true, 8>) : go(spmm_kernel<2, false, 8>);
+        else e = two ? go(spmm_kernel<1, true, 8>) : go(spmm_kernel<1, false, 8>);
+    }
     if (e != hipSuccess) { set_error(std::string("csb_spmm: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
 }

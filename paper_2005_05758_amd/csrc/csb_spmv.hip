@@ -40,7 +40,7 @@ DevMat dev_mat(const csb_matrix *m) {
     d.idx_bytes = (uint32_t)h.idx_bytes;
     d.tile_g0 = (const uint32_t *)(b + h.off_tile_g0);
     d.tile_seg0 = (const uint32_t *)(b + h.off_tile_seg0);
-    d.seg_g0 = (const uint32_t *)(b + h.off_seg_g0);
+    d.segs = (const SegRec *)(b + h.off_segs);
     return d;
 }
 
