@@ -84,6 +84,17 @@ def test_spmm_degenerate_and_column_consistency():
     assert rel_max_err(Yw[:, :20].cpu().numpy(), ref) <= 1e-5 and float(Yw[:, 20:].abs().max()) == 0.0
 
 
+def test_spmm_wide_rows_several_record_segments():
+    """Two row tiles of 750 blocks each: a tile's records exceed the kernel's LDS window, so it
+    is staged in several segments; and the widest input the 16-bit offsets allow."""
+    m = csb_inputs.small_matrix(21, 40, 12000, 32, 16, rate=2.0)
+    X = csb_inputs.make_vectors(4, 12000, 24)
+    M, _ = check_spmm(m.A, 32, 16, X, tag="wide")
+    m = csb_inputs.small_matrix(22, 70, 16383, 32, 64, rate=6.0)
+    X = csb_inputs.make_vectors(5, 16383, 8)
+    check_spmm(m.A, 32, 64, X, tag="max-cols")
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg4"])
 def test_spmm_rnn_matrices(name):
     cfg = csb_inputs.CONFIGS[name]

@@ -81,6 +81,31 @@ def test_spmv_degenerate_matrices():
     assert np.array_equal(got, x[perm].astype(np.float64))
 
 
+def test_spmv_widest_input_and_long_wavefront_runs():
+    """16383 columns: the widest input vector the 16-bit byte offsets address (odd width, so the
+    element-wise staging path runs); one chunk for a matrix with far more than 32 steps per
+    wavefront (the value registers are refilled batch by batch); non-finite inputs stay in the
+    rows that use them (padded steps multiply zeros with a zero word, not with the input)."""
+    m = csb_inputs.small_matrix(22, 70, 16383, 32, 64, rate=6.0)
+    x = csb_inputs.make_vectors(5, 16383, 1)
+    check_spmv(m.A, 32, 64, x, tag="max-cols")
+    check_spmv(m.A, 32, 64, x, n_chunks=3, tag="max-cols", mode=2)
+    m = csb_inputs.small_matrix(23, 256, 2048, 64, 64, rate=2.0)
+    x = csb_inputs.make_vectors(6, 2048, 1)
+    check_spmv(m.A, 64, 64, x, n_chunks=1, tag="one-chunk")
+    # a column nobody uses carries Inf: no row may see it
+    A = csb_inputs.small_matrix(24, 96, 130, 16, 16, rate=3.0).A.copy()
+    A[:, 77] = 0.0
+    x = csb_inputs.make_vectors(7, 130, 1).copy()
+    x[77] = np.inf
+    M = CsbMatrix(A, 16, 16)
+    M.plan()
+    M.upload()
+    y = M.spmv(torch.from_numpy(x.reshape(-1)).cuda())
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(y.cpu().numpy()))
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3"])
 def test_spmv_rnn_matrices(name):
     cfg = csb_inputs.CONFIGS[name]

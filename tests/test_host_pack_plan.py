@@ -176,3 +176,18 @@ def test_plan_validate_sweep_small_shapes():
     M = CsbMatrix(np.eye(48, dtype=np.float32), 16, 16)
     M.plan(0)
     M.validate()
+
+
+def test_plan_rejects_inputs_wider_than_the_offset_lists():
+    """Input offsets are 16-bit byte offsets into the staged vector (plus a zero word behind
+    it): 16383 columns plan, 16384 do not."""
+    A = np.zeros((8, 16384), np.float32)
+    A[3, 100] = 1.0
+    A[5, 16383] = 2.0
+    M = CsbMatrix(A, 8, 64)
+    with pytest.raises(CsbError) as e:
+        M.plan(0)
+    assert e.value.code == -4 and "columns" in str(e.value)
+    M = CsbMatrix(np.ascontiguousarray(A[:, :16383]), 8, 64)
+    M.plan(0)
+    M.validate()
