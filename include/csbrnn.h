@@ -116,6 +116,9 @@ int csb_unpack(const csb_matrix *m, float *dense, int64_t ld);
  * a group (between two of its column steps).  n_chunks = 0 picks a default for one
  * MI355X.  May be called again to re-plan; the matrix must then be uploaded again.
  * stats may be NULL.
+ * Errors: NULL / negative n_chunks -> CSB_EINVAL; more than 16383 columns (the device
+ * layout addresses the staged input vector with 16-bit byte offsets) or 2^32 stored
+ * values -> CSB_EUNSUPPORTED; allocation failure -> CSB_ENOMEM.
  */
 int csb_plan(csb_matrix *m, int32_t n_chunks, csb_plan_stats *stats);
 
@@ -172,7 +175,12 @@ int csb_debug_spmv_stamps(const csb_matrix *m, const float *d_x, float *d_y, voi
 /*
  * Batched CSB-MVM: Y = A X for `batch` right-hand sides.  d_X is [cols][ldx] (entry
  * (j,k) at d_X[j*ldx + k], ldx >= batch), d_Y is [rows][ldy] (ldy >= batch).
- * d_ws: csb_workspace_bytes(m, batch).
+ * d_ws: csb_workspace_bytes(m, batch) (may be NULL when that is 0).  Runs on the matrix
+ * cores (fp32 MFMA); the result does not depend on timing (fixed summation order).
+ * Errors: NULL / batch <= 0 / a leading dimension below batch -> CSB_EINVAL; not planned
+ * or uploaded, or planned for a GRU step -> CSB_ESTATE; cols * ldx beyond 2^30 elements
+ * or ldx >= 2^24 (the kernel uses 32-bit element offsets) -> CSB_EUNSUPPORTED; launch
+ * failure -> CSB_EDEVICE.
  */
 int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int64_t ldy,
              int32_t batch, void *d_ws, void *stream);

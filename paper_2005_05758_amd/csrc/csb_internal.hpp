@@ -105,7 +105,7 @@ struct DevHeader {
     uint32_t n_chunks, waves_per_chunk, n_groups, n_vbs;
     uint32_t n_shared, n_zero_tiles, n_nz_tiles, n_partial_slots;
     uint32_t br, bc;
-    uint32_t max_chunk_tiles, chunk_vals_cap;  // LDS sizing: tiles per chunk; (unused)
+    uint32_t max_chunk_tiles, reserved1;       // LDS sizing: tiles per chunk
     uint32_t meta_cap, reserved0;              // bytes of records per chunk
     uint64_t rows_out, cols;
     uint64_t off_chunks, off_waves, off_groups, off_vbs, off_idx, off_vals;

@@ -526,7 +526,6 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         h.n_shared = (uint32_t)shared.size(); h.n_zero_tiles = (uint32_t)zero_tiles.size();
         h.n_nz_tiles = (uint32_t)nz_tiles.size(); h.n_partial_slots = n_partial_slots;
         h.max_chunk_tiles = 1;
-        h.chunk_vals_cap = 0;
         h.meta_cap = (uint32_t)align_up(meta_cap, 256);
         for (const ChunkRec &cr : chunks) h.max_chunk_tiles = std::max(h.max_chunk_tiles, cr.ntiles);
         h.br = (uint32_t)br; h.bc = (uint32_t)bc; h.rows_out = (uint64_t)rows_out; h.cols = (uint64_t)m->cols;

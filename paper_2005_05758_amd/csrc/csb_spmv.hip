@@ -60,8 +60,9 @@ __device__ __forceinline__ ChunkRec load_chunk(const ChunkRec *p) {
     c.nzrank0 = uni(p->nzrank0); c.ntiles = uni(p->ntiles);
     c.sid_first = (int32_t)uni((uint32_t)p->sid_first); c.part_first = (int32_t)uni((uint32_t)p->part_first);
     c.sid_last = (int32_t)uni((uint32_t)p->sid_last); c.part_last = (int32_t)uni((uint32_t)p->part_last);
-    c.g0 = uni(p->g0); c.ng = uni(p->ng); c.vb0 = uni(p->vb0); c.nvbs = uni(p->nvbs);
-    c.idx0 = uni(p->idx0); c.idx_bytes = uni(p->idx_bytes); c.v0 = uni(p->v0); c.nv4 = uni(p->nv4);
+    c.g0 = uni(p->g0); c.ng = uni(p->ng);
+    c.idx0 = uni(p->idx0); c.idx_bytes = uni(p->idx_bytes);
+    c.vb0 = c.nvbs = c.v0 = c.nv4 = 0;          // host-side bookkeeping, not needed here
     c.pad[0] = c.pad[1] = 0;
     return c;
 }
@@ -70,7 +71,7 @@ __device__ __forceinline__ WaveRec load_wave(const WaveRec *p) {
     WaveRec w;
     w.g_begin = uni(p->g_begin); w.g_end = uni(p->g_end);
     w.j_begin = (uint16_t)uni(p->j_begin); w.j_end = (uint16_t)uni(p->j_end);
-    w.val_begin = uni(p->val_begin); w.v_begin = uni(p->v_begin); w.v_end = uni(p->v_end);
+    w.val_begin = 0; w.v_begin = uni(p->v_begin); w.v_end = uni(p->v_end);
     w.pad[0] = w.pad[1] = 0;
     return w;
 }
