@@ -66,6 +66,34 @@ def time_region(fn, reps, torch):
     return start.elapsed_time(stop)
 
 
+def time_each(fn, reps, torch):
+    """One event pair per repetition: (median, min) in ms."""
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    torch.cuda.synchronize()
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return ts[len(ts) // 2], ts[0]
+
+
+def stream_read_leg(torch, stream_read):
+    """Measured HBM read bandwidth of this GPU: a plain streaming read of 2 GiB (8 x the
+    Infinity Cache), the practical roofline the mat-vec figures are also quoted against."""
+    buf = torch.ones(512 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    out = stream_read(buf)
+    for _ in range(2):
+        stream_read(buf, out)
+    n = 10
+    ms = time_region(lambda: stream_read(buf, out), n, torch) / n
+    gbps = buf.numel() * 4 / (ms * 1e-3) / 1e9
+    del buf
+    return {"bytes": 512 * 1024 * 1024 * 4, "ms": round(ms, 4), "gbps": round(gbps, 1),
+            "frac_of_nominal_peak": round(gbps / HBM_PEAK_GBS, 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -86,7 +114,7 @@ def main():
     import numpy as np
     import torch
     import csb_inputs
-    from paper_2005_05758_amd import CsbMatrix, CsbRnn
+    from paper_2005_05758_amd import CsbMatrix, CsbRnn, stream_read
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -109,6 +137,7 @@ def main():
         step()
     ms = time_region(step, args.steps, torch)
     ms_per_step = ms / args.steps
+    ms_median, ms_min = time_each(step, args.steps, torch)
     us_per_t = ms_per_step * 1000.0 / T
     bytes_step = rnn_step_alg_bytes(views, cfg.cell, cfg.hidden, B)
     gbps = bytes_step / (us_per_t * 1e-6) / 1e9
@@ -157,6 +186,8 @@ def main():
                                f"W {wl.W[0].rows}x{wl.W[0].cols}, CSB block {cfg.block}, {cfg.rate:g}x pruning, "
                                f"batch {B}, T={T}, seed {cfg.seed}",
                    "timesteps_per_step": T, "alg_bytes_per_timestep": bytes_step},
+        "us_per_timestep_median": round(ms_median * 1000.0 / T, 4),
+        "us_per_timestep_min": round(ms_min * 1000.0 / T, 4),
         "gbps_algorithmic": round(gbps, 3),
         "pct_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBS, 4),
         "roofline": roofline,
@@ -172,14 +203,17 @@ def main():
         out["calib_copy"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "launches": 5}
         del src, dst
     if not args.no_stress:
-        out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix)
+        sr = stream_read_leg(torch, stream_read)
+        out["hbm_stream_read"] = sr
+        out["pct_of_measured_stream_read"] = round(100.0 * gbps / sr["gbps"], 4)
+        out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix, sr["gbps"])
         out["batched"] = batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_leg(cfg, wl)
     print(json.dumps(out))
 
 
-def stress_leg(torch, np, csb_inputs, CsbMatrix):
+def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
     """csb_spmv on the 8192^2 heavy-tailed matrices (the HBM-bound case): warm (matrix in the
     Infinity Cache) and cold (rotating over distinct device copies, > 512 MB in all), for
     the default plan (whole row tiles per workgroup) and the equal-split plan (mode 2)."""
@@ -198,7 +232,15 @@ def stress_leg(torch, np, csb_inputs, CsbMatrix):
                 M.spmv(x, y)
             n = 200
             us_warm = time_region(lambda: M.spmv(x, y), n, torch) * 1000.0 / n
+            # dynamic balance: clocks each wavefront spends on its share (stamps of one launch)
+            _, stamps = M.spmv_stamps(x)
+            torch.cuda.synchronize()
+            sp = stamps.cpu().numpy().astype(np.float64)
+            wv = sp[:, 10::3] - sp[:, 8::3]
+            wg = wv.max(axis=1)
             entry = {"nnz": int(v["nnz"]), "alg_bytes": ab, "us_warm": round(us_warm, 3),
+                     "dyn_wave_max_over_mean": round(float(wv.max() / wv.mean()), 4),
+                     "dyn_workgroup_max_over_mean": round(float(wg.max() / wg.mean()), 4),
                      "gbps_warm": round(ab / us_warm / 1e3, 1),
                      "wave_max_over_mean": round(st["work_max"] / st["work_mean"], 4),
                      "workgroup_max_over_mean": round(st["chunk_max_over_mean"], 4),
@@ -225,6 +267,7 @@ def stress_leg(torch, np, csb_inputs, CsbMatrix):
                 us_cold = time_region(cold, n, torch) * 1000.0 / n
                 entry.update({"us_cold": round(us_cold, 3), "gbps_cold": round(ab / us_cold / 1e3, 1),
                               "frac_hbm_cold": round(ab / us_cold / 1e3 / HBM_PEAK_GBS, 4),
+                              "frac_of_measured_stream_read_cold": round(ab / us_cold / 1e3 / stream_gbps, 4),
                               "cold_copies": n_copies, "cold_bytes_total": n_copies * M.device_bytes()})
                 del copies
             res[f"{name}_{tag}"] = entry
@@ -301,8 +344,21 @@ def cpu_leg(cfg, wl):
         if dt > 10.0 or reps >= 20000:
             break
     us = dt / (reps * cfg.T) * 1e6
-    return {"value": round(us, 3), "unit": "us/timestep", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{reps} full sequences of T={cfg.T} (float64 dense masked mat-vec + gates, OpenMP over rows)"}
+    res = {"value": round(us, 3), "unit": "us/timestep", "cores": oracle.num_threads(), "kind": "oracle",
+           "sample": f"{reps} full sequences of T={cfg.T} (float64 dense masked mat-vec + gates, OpenMP over rows)"}
+    # the same on one core (a few sequences), for the per-core figure
+    all_threads = oracle.num_threads()
+    try:
+        oracle.set_threads(1)
+        t0 = time.perf_counter()
+        r1 = 0
+        while time.perf_counter() - t0 < 3.0:
+            oracle.rnn_forward(cfg.cell, W, wl.bias, wl.x, cfg.input, cfg.hidden)
+            r1 += 1
+        res["one_core_us_per_timestep"] = round((time.perf_counter() - t0) / (r1 * cfg.T) * 1e6, 3)
+    finally:
+        oracle.set_threads(all_threads)
+    return res
 
 
 if __name__ == "__main__":

@@ -169,6 +169,15 @@ int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws, void
  * arrived, end of the share.
  */
 size_t csb_debug_stamp_count(const csb_matrix *m);
+
+/*
+ * Measurement aid (Sec. 6.1 reports throughput against the platform's capability): a plain
+ * streaming read of d_buf (device, 16-byte aligned, `bytes` a multiple of 16) whose timing
+ * gives the HBM read bandwidth this GPU reaches in practice.  Every thread writes its partial
+ * sum to d_out (device, csb_debug_stream_read_out_floats() floats).  Asynchronous on `stream`.
+ */
+size_t csb_debug_stream_read_out_floats(void);
+int csb_debug_stream_read(const void *d_buf, size_t bytes, float *d_out, void *stream);
 int csb_debug_spmv_stamps(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws,
                           unsigned long long *d_stamps, void *stream);
 

@@ -18,6 +18,7 @@ _lib = None
 SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_plan", "csb_plan_ex", "csb_plan_validate",
            "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
+           "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
            "csb_rnn_create", "csb_rnn_device_bytes", "csb_rnn_upload", "csb_rnn_stats",
            "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
 
@@ -80,6 +81,9 @@ def load_library():
     L.csb_debug_stamp_count.argtypes = [C.c_void_p]
     L.csb_debug_stamp_count.restype = C.c_size_t
     L.csb_debug_spmv_stamps.argtypes = [C.c_void_p] * 6
+    L.csb_debug_stream_read_out_floats.argtypes = []
+    L.csb_debug_stream_read_out_floats.restype = C.c_size_t
+    L.csb_debug_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     L.csb_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     L.csb_rnn_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
@@ -123,6 +127,17 @@ def _stream_ptr(stream=None) -> Optional[int]:
     import torch
     s = torch.cuda.current_stream() if stream is None else stream
     return s.cuda_stream or None
+
+
+def stream_read(buf, out=None, stream=None):
+    """csb_debug_stream_read on a device tensor (any dtype, size a multiple of 16 bytes)."""
+    import torch
+    n = int(lib().csb_debug_stream_read_out_floats())
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=buf.device)
+    assert out.numel() >= n and buf.is_contiguous()
+    _check(lib().csb_debug_stream_read(_dptr(buf), buf.numel() * buf.element_size(), _dptr(out), _stream_ptr(stream)))
+    return out
 
 
 class CsbMatrix:

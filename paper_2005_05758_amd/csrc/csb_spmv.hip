@@ -417,6 +417,35 @@ extern "C" int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void 
     return csb::spmv_segments(m, d_x, (uint32_t)m->cols, d_x, d_y, d_ws, stream, nullptr);
 }
 
+namespace csb {
+// Plain streaming read: the measured bandwidth the mat-vec figures are put next to.
+__global__ __launch_bounds__(256) void stream_read_kernel(const float4 *__restrict__ p, size_t n4, float *__restrict__ out) {
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n4; i += 4 * stride) {       // four independent loads in flight per thread
+        const float4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        s0 += a.x + a.y + a.z + a.w; s1 += b.x + b.y + b.z + b.w;
+        s2 += c.x + c.y + c.z + c.w; s3 += d.x + d.y + d.z + d.w;
+    }
+    for (; i < n4; i += stride) { const float4 a = p[i]; s0 += a.x + a.y + a.z + a.w; }
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = (s0 + s1) + (s2 + s3);
+}
+constexpr int kStreamReadBlocks = 256 * 8;               // 8 workgroups of 256 threads per CU
+}  // namespace csb
+
+extern "C" size_t csb_debug_stream_read_out_floats(void) { return (size_t)csb::kStreamReadBlocks * 256; }
+
+extern "C" int csb_debug_stream_read(const void *d_buf, size_t bytes, float *d_out, void *stream) {
+    if (!d_buf || !d_out) { csb::set_error("csb_debug_stream_read: NULL pointer"); return CSB_EINVAL; }
+    if (bytes % 16 || (uintptr_t)d_buf % 16) { csb::set_error("csb_debug_stream_read: buffer not a multiple of 16 bytes"); return CSB_EINVAL; }
+    hipLaunchKernelGGL(csb::stream_read_kernel, dim3(csb::kStreamReadBlocks), dim3(256), 0, (hipStream_t)stream,
+                       (const float4 *)d_buf, bytes / 16, d_out);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { csb::set_error(std::string("csb_debug_stream_read: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    return CSB_OK;
+}
+
 extern "C" size_t csb_debug_stamp_count(const csb_matrix *m) {
     return (m && m->plan.valid) ? (size_t)m->plan.hdr.n_chunks * csb::kStampsPerChunk : 0;
 }
