@@ -40,6 +40,7 @@ def _load():
         _lib.orc_csb_encode.restype = C.c_int
         _lib.orc_csb_decode.restype = C.c_int
         _lib.orc_rnn_forward.restype = C.c_int
+        _lib.orc_csb_project.restype = C.c_int
     return _lib
 
 
@@ -187,3 +188,17 @@ def rnn_forward(cell: int, W: List[np.ndarray], bias: Optional[List[Optional[np.
     if rc != 0:
         raise ValueError("orc_rnn_forward failed")
     return hseq, hT, cT
+
+
+def csb_project(W: np.ndarray, br: int, bc: int, rate: float) -> np.ndarray:
+    """Projection of dense float32 W onto the CSB pattern (blocks br x bc) at pruning rate
+    `rate` x: the RowPrune / ColumnPrune step of Algorithm 1.  Returns the pruned matrix."""
+    lib = _load()
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    R, Cc = W.shape
+    Z = np.empty_like(W)
+    rc = lib.orc_csb_project(_p(W), C.c_int64(R), C.c_int64(Cc), C.c_int64(Cc), C.c_int32(br), C.c_int32(bc),
+                             C.c_double(rate), _p(Z), C.c_int64(Cc))
+    if rc != 0:
+        raise ValueError("orc_csb_project: bad argument")
+    return Z

@@ -21,10 +21,29 @@
  *   - "non-zero" means v != 0.0f (so -0.0 is zero and NaN is kept);
  *   - edge blocks of a ragged matrix are truncated.
  *
+ *   - the projection of a dense matrix onto the CSB pattern at a given pruning rate (the
+ *     pruning step inside Algorithm 1, described in Sec. 3.2.2: partition into blocks; in
+ *     every block-column rank the in-block row segments by the sum of their squares and zero
+ *     the weakest share 1 - sqrt(1 - PruneRate); then the same for the in-block column
+ *     segments of every block-row, on the row-pruned matrix).
+ *
+ * Readings for the projection (the paper gives the procedure in words only):
+ *   - "PruneRate" is the pruned fraction 1 - 1/rate for a rate given as "rate x";
+ *   - the ranking runs over ALL row segments of a block-column (all column segments of a
+ *     block-row), so the kept count varies from block to block, as Sec. 3.1.2 says it does;
+ *   - the number zeroed among n segments is floor(n * (1 - rate^-1/2) + 1/2);
+ *   - ties and the decision itself: the sum of squares is accumulated in float32, left to
+ *     right (top to bottom), one fused multiply-add per element -- the arithmetic of the
+ *     device kernel, because the decision must be taken in one precision on both sides;
+ *     equal sums are ranked by position (the earlier segment is the weaker); a NaN sum
+ *     ranks above everything (its segment is kept);
+ *   - surviving entries keep their bits, pruned entries become +0.0.
+ *
  * Parity pins (tests/test_oracle_*.py): a hand-worked two-block example, brute force on
  * tiny matrices, numpy's float64 product, torch.nn.LSTM / torch.nn.GRU in float64 on the
- * CPU, closed forms for zero weights, encode/decode invariants.  No function here is
- * "parity unpinned".
+ * CPU, closed forms for zero weights, encode/decode invariants; for the projection a
+ * hand-worked example, exact integer brute force on tiny matrices, kept-count and
+ * pattern invariants.  No function here is "parity unpinned".
  *
  * Plain loops on purpose: no blocking, no fusion, no reordering.  The only concession to
  * run time is an OpenMP "parallel for" over output rows, which does not change any sum.
@@ -275,5 +294,77 @@ int orc_rnn_forward(int cell, int32_t L, int64_t I, int64_t H,
     memcpy(hT, h, sizeof(double) * (size_t)(L * B * H));
     if (cT) memcpy(cT, c, sizeof(double) * (size_t)(L * B * H));
     free(h); free(c); free(u); free(ax); free(ah);
+    return 0;
+}
+
+
+/* ------------------------------------------------------------------ CSB projection */
+
+typedef struct { uint32_t key; int64_t idx; } orc_rank;
+
+static int orc_rank_cmp(const void *a, const void *b) {
+    const orc_rank *x = (const orc_rank *)a, *y = (const orc_rank *)b;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    return x->idx < y->idx ? -1 : (x->idx > y->idx ? 1 : 0);
+}
+
+/* Ranking key of a float32 sum of squares: its bit pattern (sums are >= 0 or NaN, so the
+ * unsigned order of the bits is the numeric order, with NaN on top). */
+static uint32_t orc_key(float s) {
+    uint32_t u;
+    memcpy(&u, &s, 4);
+    if (s != s) u = 0xffffffffu;          /* every NaN alike */
+    return u & 0x7fffffffu ? u : 0u;      /* -0.0 cannot occur, but +0.0 == 0 */
+}
+
+static int64_t orc_prune_count(int64_t n, double rate) {
+    const double q = 1.0 - 1.0 / sqrt(rate);
+    int64_t k = (int64_t)floor((double)n * q + 0.5);
+    if (k < 0) k = 0;
+    if (k > n) k = n;
+    return k;
+}
+
+/*
+ * Z = projection of W (R x C, leading dimension ld) onto the CSB pattern with blocks
+ * BR x BC at pruning rate `rate` (>= 1; "rate x").  Z has leading dimension ldz and may not
+ * alias W.  Returns 0, or -1 on a bad argument.
+ */
+int orc_csb_project(const float *W, int64_t R, int64_t C, int64_t ld, int32_t BR, int32_t BC,
+                    double rate, float *Z, int64_t ldz) {
+    if (!W || !Z || R <= 0 || C <= 0 || ld < C || ldz < C || BR < 1 || BC < 1 || !(rate >= 1.0)) return -1;
+    const int64_t nbr = (R + BR - 1) / BR, nbc = (C + BC - 1) / BC;
+    for (int64_t i = 0; i < R; ++i) memcpy(Z + i * ldz, W + i * ld, sizeof(float) * (size_t)C);
+    orc_rank *rk = (orc_rank *)malloc(sizeof(orc_rank) * (size_t)(R > C ? R : C));
+    if (!rk) return -1;
+    /* RowPrune, block-column by block-column */
+    for (int64_t bj = 0; bj < nbc; ++bj) {
+        const int64_t c0 = bj * BC, c1 = imin64(C, c0 + BC);
+        for (int64_t i = 0; i < R; ++i) {
+            float s = 0.0f;
+            for (int64_t c = c0; c < c1; ++c) s = fmaf(Z[i * ldz + c], Z[i * ldz + c], s);
+            rk[i].key = orc_key(s);
+            rk[i].idx = i;
+        }
+        qsort(rk, (size_t)R, sizeof(orc_rank), orc_rank_cmp);
+        const int64_t k = orc_prune_count(R, rate);
+        for (int64_t t = 0; t < k; ++t)
+            for (int64_t c = c0; c < c1; ++c) Z[rk[t].idx * ldz + c] = 0.0f;
+    }
+    /* ColumnPrune, block-row by block-row, on the row-pruned matrix */
+    for (int64_t bi = 0; bi < nbr; ++bi) {
+        const int64_t r0 = bi * BR, r1 = imin64(R, r0 + BR);
+        for (int64_t c = 0; c < C; ++c) {
+            float s = 0.0f;
+            for (int64_t i = r0; i < r1; ++i) s = fmaf(Z[i * ldz + c], Z[i * ldz + c], s);
+            rk[c].key = orc_key(s);
+            rk[c].idx = c;
+        }
+        qsort(rk, (size_t)C, sizeof(orc_rank), orc_rank_cmp);
+        const int64_t k = orc_prune_count(C, rate);
+        for (int64_t t = 0; t < k; ++t)
+            for (int64_t i = r0; i < r1; ++i) Z[i * ldz + rk[t].idx] = 0.0f;
+    }
+    free(rk);
     return 0;
 }
