@@ -247,6 +247,29 @@ int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *d_h0, const
                     float *d_hseq, float *d_hT, float *d_cT, int32_t T, int32_t batch,
                     void *d_ws, void *stream);
 
+/*
+ * Projection of a dense matrix onto the CSB pattern: the pruning step inside Algorithm 1 as
+ * Sec. 3.2.2 describes it.  The matrix is partitioned into br x bc blocks (edge blocks
+ * truncated); RowPrune: in every block-column the in-block row segments are ranked by their
+ * sum of squares and the weakest share 1 - sqrt(1 - PruneRate) is zeroed; ColumnPrune: the
+ * same for the in-block column segments of every block-row, on the row-pruned matrix.
+ * `rate` is the pruning rate as a factor ("10x" = 10, PruneRate = 1 - 1/rate), so
+ * floor(n (1 - rate^-1/2) + 1/2) of n segments go in each pass.  Sums are float32, left to
+ * right / top to bottom with one fused multiply-add per element; equal sums rank by
+ * position (the earlier segment is the weaker); a NaN sum ranks on top.  Survivors keep
+ * their bits, pruned entries become +0.0: the result is ready for csb_pack.
+ * d_W: device, [rows][ld], ld >= cols.  d_Z: device, [rows][ldz], ldz >= cols; may be d_W
+ * itself (with ldz == ld).  d_ws: device, csb_project_workspace_bytes(...) bytes, 256-byte
+ * aligned, contents need no initialisation.  Five kernels, asynchronous on `stream`.
+ * Errors: NULL, non-positive sizes, a leading dimension below cols, block size outside
+ * [1, CSB_MAX_BLOCK], rate not a finite number >= 1 -> CSB_EINVAL; more than 16384 rows or
+ * columns (one workgroup ranks a whole block-column in LDS) -> CSB_EUNSUPPORTED; launch
+ * failure -> CSB_EDEVICE.
+ */
+size_t csb_project_workspace_bytes(int64_t rows, int64_t cols, int32_t br, int32_t bc);
+int csb_project(const float *d_W, int64_t rows, int64_t cols, int64_t ld, int32_t br, int32_t bc,
+                double rate, float *d_Z, int64_t ldz, void *d_ws, void *stream);
+
 void csb_free(csb_matrix *m);
 void csb_rnn_free(csb_rnn *r);
 

@@ -5,7 +5,7 @@ gfx950 kernels (device calls) or its host packer/planner.  There is no CPU fallb
 the library is missing, importing the binding's functions raises.
 """
 from .binding import (CsbMatrix, CsbRnn, CsbError, CELL_LSTM, CELL_GRU, lib, lib_path,
-                      load_library, stream_read)
+                      load_library, stream_read, project)
 
 __all__ = ["CsbMatrix", "CsbRnn", "CsbError", "CELL_LSTM", "CELL_GRU", "lib", "lib_path",
-           "load_library", "stream_read"]
+           "load_library", "stream_read", "project"]

@@ -19,6 +19,7 @@ SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_plan
            "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
+           "csb_project_workspace_bytes", "csb_project",
            "csb_rnn_create", "csb_rnn_device_bytes", "csb_rnn_upload", "csb_rnn_stats",
            "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
 
@@ -84,6 +85,10 @@ def load_library():
     L.csb_debug_stream_read_out_floats.argtypes = []
     L.csb_debug_stream_read_out_floats.restype = C.c_size_t
     L.csb_debug_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    L.csb_project_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32]
+    L.csb_project_workspace_bytes.restype = C.c_size_t
+    L.csb_project.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_double,
+                              C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     L.csb_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     L.csb_rnn_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
@@ -137,6 +142,22 @@ def stream_read(buf, out=None, stream=None):
         out = torch.empty(n, dtype=torch.float32, device=buf.device)
     assert out.numel() >= n and buf.is_contiguous()
     _check(lib().csb_debug_stream_read(_dptr(buf), buf.numel() * buf.element_size(), _dptr(out), _stream_ptr(stream)))
+    return out
+
+
+def project(W, br: int, bc: int, rate: float, out=None, stream=None):
+    """csb_project on a device tensor W [rows][cols] (float32, rows may be strided): returns the
+    pruned matrix (a new tensor, or `out`, which may be W itself)."""
+    import torch
+    assert W.dim() == 2 and W.dtype == torch.float32 and W.stride(1) == 1
+    rows, cols = W.shape
+    if out is None:
+        out = torch.empty((rows, cols), dtype=torch.float32, device=W.device)
+    assert out.shape == W.shape and out.dtype == torch.float32 and out.stride(1) == 1
+    nb = int(lib().csb_project_workspace_bytes(rows, cols, br, bc))
+    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device=W.device)
+    _check(lib().csb_project(W.data_ptr(), rows, cols, W.stride(0), br, bc, float(rate), out.data_ptr(), out.stride(0),
+                             _dptr(ws), _stream_ptr(stream)))
     return out
 
 
