@@ -208,6 +208,7 @@ def main():
         out["pct_of_measured_stream_read"] = round(100.0 * gbps / sr["gbps"], 4)
         out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix, sr["gbps"])
         out["batched"] = batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
+        out["projection"] = projection_leg(torch, np, sr["gbps"], not args.no_cpu)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_leg(cfg, wl)
     print(json.dumps(out))
@@ -326,6 +327,37 @@ def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
                        "us_per_timestep": round(ms * 1000.0 / cfg.T, 2),
                        "tflops_algorithmic": round(fl_step / (ms * 1e-3 / cfg.T) / 1e12, 3),
                        "sequences_per_s": round(cfg.batch / (ms * 1e-3), 1)}
+    return res
+
+
+def projection_leg(torch, np, stream_gbps, with_cpu):
+    """csb_project (RowPrune / ColumnPrune of Algorithm 1) on a dense 8192 x 8192 Gaussian matrix,
+    block 32, 12x: the matrix the stress leg's shape comes from.  Algorithmic bytes: one read
+    of W and one write of Z."""
+    from paper_2005_05758_amd import project
+    rows = cols = 8192
+    rng = np.random.default_rng(0)
+    Wh = rng.normal(0, 0.05, (rows, cols)).astype(np.float32)
+    W = torch.from_numpy(Wh).cuda()
+    Z = torch.empty_like(W)
+    for _ in range(2):
+        project(W, 32, 32, 12.0, out=Z)
+    n = 10
+    ms = time_region(lambda: project(W, 32, 32, 12.0, out=Z), n, torch) / n
+    ab = 2 * rows * cols * 4
+    res = {"shape": [rows, cols], "block": 32, "rate": 12.0, "ms": round(ms, 4), "alg_bytes": ab,
+           "gbps_algorithmic": round(ab / (ms * 1e-3) / 1e9, 1),
+           "roofline": {"kernel": "csb_project (5 kernels: row sums, select, column sums, select, masked copy)",
+                        "bound": "hbm", "achieved": round(ab / (ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": round(ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                        "frac_of_measured_stream_read": round(ab / (ms * 1e-3) / 1e9 / stream_gbps, 4)},
+           "density_out": round(float((Z != 0).float().mean()), 5)}
+    if with_cpu:
+        import oracle
+        t0 = time.perf_counter()
+        oracle.csb_project(Wh, 32, 32, 12.0)
+        res["cpu_baseline"] = {"value": round((time.perf_counter() - t0) * 1e3, 1), "unit": "ms", "cores": 1, "kind": "oracle",
+                               "sample": "one projection of the same matrix (single-threaded C: float32 sums, qsort per block-column / block-row)"}
     return res
 
 

@@ -27,18 +27,46 @@ __device__ __forceinline__ uint32_t rank_key(float s) {
     return s != s ? 0xffffffffu : u;
 }
 
-// keys[bj * R + i] for row segment (i, bj): thread per segment, bj fastest.
+// keys[bj * R + i] for row segment (i, bj).  A workgroup takes TR rows x TS segments: it
+// reads their columns coalesced into LDS (segment stride BC | 1 words, so that the lanes of
+// the next phase hit different banks), then thread (r, sj) adds up its own segment from left
+// to right.  DIV_SHIFT >= 0: BC is 1 << DIV_SHIFT.
+template <int DIV_SHIFT>
 __global__ __launch_bounds__(256) void row_segment_keys_kernel(const float *__restrict__ W, const int64_t ld,
                                                                  const uint32_t R, const uint32_t C, const uint32_t BC,
-                                                                 const uint32_t NBC, uint32_t *__restrict__ keys) {
-    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= (size_t)R * NBC) return;
-    const uint32_t i = (uint32_t)(e / NBC), bj = (uint32_t)(e - (size_t)i * NBC);
-    const uint32_t c0 = bj * BC, c1 = min(C, c0 + BC);
-    const float *p = W + (size_t)i * ld;
-    float s = 0.0f;
-    for (uint32_t c = c0; c < c1; ++c) s = fmaf(p[c], p[c], s);
-    keys[(size_t)bj * R + i] = rank_key(s);
+                                                                 const uint32_t NBC, const uint32_t TR, const uint32_t TS,
+                                                                 uint32_t *__restrict__ keys) {
+    extern __shared__ float tile[];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t bj0 = blockIdx.x * TS, i0 = blockIdx.y * TR;
+    const uint32_t c0 = bj0 * BC, c1 = min(C, (bj0 + TS) * BC), ncols = c1 - c0;
+    const uint32_t BCp = BC | 1u;
+    for (uint32_t r = 0; r < TR && i0 + r < R; ++r) {
+        const float *p = W + (size_t)(i0 + r) * ld + c0;
+        float *row = tile + (size_t)r * TS * BCp;
+        for (uint32_t cb = tid; cb < ncols; cb += 1024) {           // four independent loads per pass
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = cb + 256u * u < ncols ? p[cb + 256u * u] : 0.0f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t cc = cb + 256u * u;
+                if (cc < ncols) {
+                    const uint32_t seg = DIV_SHIFT >= 0 ? cc >> (DIV_SHIFT >= 0 ? DIV_SHIFT : 0) : cc / BC;
+                    row[seg * BCp + (cc - seg * BC)] = v[u];
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t r = tid / TS, sj = tid - r * TS;
+    if (r < TR && i0 + r < R && bj0 + sj < NBC) {
+        const uint32_t w = min(BC, C - (bj0 + sj) * BC);
+        const float *q = tile + ((size_t)r * TS + sj) * BCp;
+        float s = 0.0f;
+        for (uint32_t c = 0; c < w; ++c) s = fmaf(q[c], q[c], s);
+        keys[(size_t)(bj0 + sj) * R + i0 + r] = rank_key(s);
+    }
 }
 
 // keys[bi * C + c] for column segment (bi, c) of the row-pruned matrix: thread per segment,
@@ -82,15 +110,33 @@ __global__ __launch_bounds__(1024) void select_kernel(const uint32_t *__restrict
     for (uint32_t i = tid; i < n; i += 1024) keep[base + (uint32_t)sk[i]] = i >= k ? 1 : 0;
 }
 
-// Z = W where both its row segment and its column segment survive, else +0.
+// Z = W where both its row segment and its column segment survive, else +0.  A thread takes
+// four consecutive columns of one row (kMaskedCopyRows rows per workgroup).
+constexpr int kMaskedCopyRows = 4;
 __global__ __launch_bounds__(256) void masked_copy_kernel(const float *W, const int64_t ld, float *Z,
                                                             const int64_t ldz, const uint32_t R, const uint32_t C,
                                                             const uint32_t BR, const uint32_t BC,
-                                                            const uint8_t *__restrict__ keep_r, const uint8_t *__restrict__ keep_c) {
-    const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x, i = blockIdx.y;
-    if (c >= C) return;
-    const bool on = keep_r[(size_t)(c / BC) * R + i] && keep_c[(size_t)(i / BR) * C + c];
-    Z[(size_t)i * ldz + c] = on ? W[(size_t)i * ld + c] : 0.0f;
+                                                            const uint8_t *__restrict__ keep_r, const uint8_t *__restrict__ keep_c,
+                                                            const bool vec4) {
+    const uint32_t c = (blockIdx.x * 64u + (threadIdx.x & 63u)) * 4u;
+    const uint32_t i = blockIdx.y * kMaskedCopyRows + (threadIdx.x >> 6);
+    if (c >= C || i >= R) return;
+    const uint8_t *kc = keep_c + (size_t)(i / BR) * C;
+    if (vec4 && c + 3 < C) {
+        const float4 w = *(const float4 *)(W + (size_t)i * ld + c);
+        const uint32_t kc4 = *(const uint32_t *)(kc + c);           // four keep flags (C is a multiple of 4 here)
+        float4 z;
+        z.x = keep_r[(size_t)(c / BC) * R + i] && (kc4 & 0xffu) ? w.x : 0.0f;
+        z.y = keep_r[(size_t)((c + 1) / BC) * R + i] && (kc4 & 0xff00u) ? w.y : 0.0f;
+        z.z = keep_r[(size_t)((c + 2) / BC) * R + i] && (kc4 & 0xff0000u) ? w.z : 0.0f;
+        z.w = keep_r[(size_t)((c + 3) / BC) * R + i] && (kc4 & 0xff000000u) ? w.w : 0.0f;
+        *(float4 *)(Z + (size_t)i * ldz + c) = z;
+    } else {
+        for (uint32_t cc = c; cc < min(C, c + 4u); ++cc) {
+            const bool on = keep_r[(size_t)(cc / BC) * R + i] && kc[cc];
+            Z[(size_t)i * ldz + cc] = on ? W[(size_t)i * ld + cc] : 0.0f;
+        }
+    }
 }
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -155,14 +201,29 @@ extern "C" int csb_project(const float *d_W, int64_t rows, int64_t cols, int64_t
     hipError_t e = hipFuncSetAttribute((const void *)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)(std::max(Pr, Pc) * sizeof(unsigned long long)));
     if (e == hipSuccess) {
-        const size_t nseg = (size_t)R * NBC;
-        hipLaunchKernelGGL(row_segment_keys_kernel, dim3((unsigned)((nseg + 255) / 256)), dim3(256), 0, st, d_W, ld, R, C, BC, NBC, keys_r);
+        // tile of the row-sum kernel: TS segments x TR rows, at most 256 threads and 48 KB of LDS
+        const uint32_t BCp = BC | 1u;
+        const uint32_t TS = std::max(1u, std::min({NBC, 256u, 12288u / BCp}));
+        const uint32_t TR = std::max(1u, std::min({256u / TS, 12288u / (TS * BCp), R}));
+        const size_t lds_rows = (size_t)TR * TS * BCp * sizeof(float);
+        const dim3 grid_r((NBC + TS - 1) / TS, (R + TR - 1) / TR);
+        int shift = -1;
+        for (int b = 0; b < 9; ++b) if (BC == (1u << b)) shift = b;
+        switch (shift) {
+            case 4: hipLaunchKernelGGL(row_segment_keys_kernel<4>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
+            case 5: hipLaunchKernelGGL(row_segment_keys_kernel<5>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
+            case 6: hipLaunchKernelGGL(row_segment_keys_kernel<6>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
+            default: hipLaunchKernelGGL(row_segment_keys_kernel<-1>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
+        }
         hipLaunchKernelGGL(select_kernel, dim3(NBC), dim3(1024), Pr * sizeof(unsigned long long), st, keys_r, keep_r, R, Pr,
                            prune_count(rows, rate));
         hipLaunchKernelGGL(col_segment_keys_kernel, dim3((C + 255) / 256, NBR), dim3(256), 0, st, d_W, ld, R, C, BR, BC, keep_r, keys_c);
         hipLaunchKernelGGL(select_kernel, dim3(NBR), dim3(1024), Pc * sizeof(unsigned long long), st, keys_c, keep_c, C, Pc,
                            prune_count(cols, rate));
-        hipLaunchKernelGGL(masked_copy_kernel, dim3((C + 255) / 256, R), dim3(256), 0, st, d_W, ld, d_Z, ldz, R, C, BR, BC, keep_r, keep_c);
+        // float4 accesses need 16-byte aligned rows on both sides (and flag words at multiples of 4)
+        const bool vec4 = C % 4 == 0 && ld % 4 == 0 && ldz % 4 == 0 && (uintptr_t)d_W % 16 == 0 && (uintptr_t)d_Z % 16 == 0;
+        hipLaunchKernelGGL(masked_copy_kernel, dim3((C + 255) / 256, (R + kMaskedCopyRows - 1) / kMaskedCopyRows), dim3(256), 0, st,
+                           d_W, ld, d_Z, ldz, R, C, BR, BC, keep_r, keep_c, vec4);
         e = hipGetLastError();
     }
     if (e != hipSuccess) { set_error(std::string("csb_project: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
