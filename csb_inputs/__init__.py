@@ -223,6 +223,33 @@ def make_rnn(cfg: RnnConfig, T: Optional[int] = None, batch: Optional[int] = Non
     return RnnWorkload(cfg=cfg, W=Ws, bias=bias, x=x)
 
 
+@dataclass
+class LstmpWorkload:
+    input: int
+    hidden: int
+    proj: int
+    W: List[PrunedMatrix]       # (4H) x (in_l + P), in_0 = input, in_l = P
+    Wp: List[PrunedMatrix]      # P x H
+    bias: List[np.ndarray]      # 4H each
+    x: np.ndarray               # [T, B, input]
+
+
+def make_lstmp(seed: int, n_layers: int, input: int, hidden: int, proj: int, block: int, rate: float,
+               T: int, batch: int, law: str = "binomial", sigma: float = 0.05) -> LstmpWorkload:
+    """LSTM with a recurrent projection (the cell of the paper's SR1 rows of Table 1: 153 ->
+    1024 with a 512-wide projection).  Draw order: per layer the gate matrix then the projection
+    matrix, then all biases, then x."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    Ws, Ps = [], []
+    for l in range(n_layers):
+        in_l = input if l == 0 else proj
+        Ws.append(make_matrix(rng, 4 * hidden, in_l + proj, block, block, rate, law, sigma))
+        Ps.append(make_matrix(rng, proj, hidden, block, block, rate, law, sigma))
+    bias = [rng.normal(0.0, sigma, size=4 * hidden).astype(np.float32) for _ in range(n_layers)]
+    x = rng.uniform(-1.0, 1.0, size=(T, batch, input)).astype(np.float32)
+    return LstmpWorkload(input=input, hidden=hidden, proj=proj, W=Ws, Wp=Ps, bias=bias, x=x)
+
+
 def make_mat(cfg: MatConfig, seed: Optional[int] = None) -> PrunedMatrix:
     rng = np.random.Generator(np.random.PCG64(cfg.seed if seed is None else seed))
     return make_matrix(rng, cfg.rows, cols=cfg.cols, br=cfg.block, bc=cfg.block,

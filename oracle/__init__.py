@@ -41,6 +41,7 @@ def _load():
         _lib.orc_csb_decode.restype = C.c_int
         _lib.orc_rnn_forward.restype = C.c_int
         _lib.orc_csb_project.restype = C.c_int
+        _lib.orc_lstmp_forward.restype = C.c_int
     return _lib
 
 
@@ -202,3 +203,40 @@ def csb_project(W: np.ndarray, br: int, bc: int, rate: float) -> np.ndarray:
     if rc != 0:
         raise ValueError("orc_csb_project: bad argument")
     return Z
+
+
+def lstmp_forward(W: List[np.ndarray], Wp: List[np.ndarray], bias: Optional[List[Optional[np.ndarray]]],
+                  x: np.ndarray, input: int, hidden: int, proj: int,
+                  h0: Optional[np.ndarray] = None, c0: Optional[np.ndarray] = None,
+                  want_hseq: bool = True) -> Tuple[Optional[np.ndarray], np.ndarray, np.ndarray]:
+    """Stacked LSTM with recurrent projection.  W[l]: (4H) x (in_l + P), Wp[l]: P x H, dense
+    float32.  x: [T, B, I].  Returns (hseq [T,B,P] or None, hT [L,B,P], cT [L,B,H]) float64."""
+    lib = _load()
+    L = len(W)
+    Ws, Ps = [], []
+    for l in range(L):
+        n_in = input if l == 0 else proj
+        w = np.ascontiguousarray(W[l], dtype=np.float32)
+        p = np.ascontiguousarray(Wp[l], dtype=np.float32)
+        assert w.shape == (4 * hidden, n_in + proj) and p.shape == (proj, hidden), (w.shape, p.shape, l)
+        Ws.append(w)
+        Ps.append(p)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    T, B, I = x.shape
+    assert I == input
+    Wv = (C.c_void_p * L)(*[w.ctypes.data for w in Ws])
+    Pv = (C.c_void_p * L)(*[p.ctypes.data for p in Ps])
+    bs, Bv = None, None
+    if bias is not None:
+        bs = [None if b is None else np.ascontiguousarray(b, dtype=np.float32) for b in bias]
+        Bv = (C.c_void_p * L)(*[None if b is None else b.ctypes.data for b in bs])
+    h0 = None if h0 is None else np.ascontiguousarray(h0, dtype=np.float64).reshape(L, B, proj)
+    c0 = None if c0 is None else np.ascontiguousarray(c0, dtype=np.float64).reshape(L, B, hidden)
+    hseq = np.empty((T, B, proj), np.float64) if want_hseq else None
+    hT = np.empty((L, B, proj), np.float64)
+    cT = np.empty((L, B, hidden), np.float64)
+    rc = lib.orc_lstmp_forward(C.c_int32(L), C.c_int64(input), C.c_int64(hidden), C.c_int64(proj), Wv, Pv, Bv,
+                               _p(x), _p(h0), _p(c0), _p(hseq), _p(hT), _p(cT), C.c_int64(T), C.c_int64(B))
+    if rc != 0:
+        raise ValueError("orc_lstmp_forward failed")
+    return hseq, hT, cT

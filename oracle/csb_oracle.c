@@ -12,7 +12,9 @@
  *     (CSB is a lossless encoding, so CSB-MVM of Sec. 4.3.1 equals the plain product);
  *   - LSTM and GRU inference over a sequence (Sec. 2.1: mat-vec of the weight matrices
  *     with input and hidden vectors, then sigmoid / tanh / element-wise products and
- *     sums, with c_{t-1}, h_{t-1} carried to the next step), float64 throughout.
+ *     sums, with c_{t-1}, h_{t-1} carried to the next step), float64 throughout; also the
+ *     LSTM with a recurrent projection layer (LSTMP) that the paper's speech model SR1 uses
+ *     (Table 1);
  *
  * Readings where the paper is silent (its cell equations sit in a figure):
  *   - LSTM without peepholes, gate rows stacked i,f,g,o; W = [W_x | W_h], one bias;
@@ -41,7 +43,8 @@
  *
  * Parity pins (tests/test_oracle_*.py): a hand-worked two-block example, brute force on
  * tiny matrices, numpy's float64 product, torch.nn.LSTM / torch.nn.GRU in float64 on the
- * CPU, closed forms for zero weights, encode/decode invariants; for the projection a
+ * CPU (LSTMP: torch.nn.LSTM with proj_size), closed forms for zero weights, encode/decode
+ * invariants; for the projection a
  * hand-worked example, exact integer brute force on tiny matrices, kept-count and
  * pattern invariants.  No function here is "parity unpinned".
  *
@@ -294,6 +297,71 @@ int orc_rnn_forward(int cell, int32_t L, int64_t I, int64_t H,
     memcpy(hT, h, sizeof(double) * (size_t)(L * B * H));
     if (cT) memcpy(cT, c, sizeof(double) * (size_t)(L * B * H));
     free(h); free(c); free(u); free(ax); free(ah);
+    return 0;
+}
+
+
+/* ------------------------------------------------------------------ LSTM with a recurrent projection */
+
+/*
+ * LSTMP (the cell of the paper's speech model SR1, Table 1; the paper cites it and gives no
+ * equations, so this is the cell as published by its authors): an LSTM whose output
+ * m_t = o * tanh(c_t) (H wide) is projected to r_t = Wp m_t (P wide, no bias, no
+ * non-linearity); r_t is what recurs and what the next layer reads.
+ *   W[l]  dense (4H) x (in_l + P), rows i,f,g,o, in_0 = I, in_l = P; bias[l] of 4H or NULL
+ *   Wp[l] dense P x H
+ *   x [T][B][I] float32;  h0 [L][B][P], c0 [L][B][H] float64 or NULL (zeros)
+ *   hseq [T][B][P] of the last layer or NULL;  hT [L][B][P];  cT [L][B][H] or NULL
+ */
+int orc_lstmp_forward(int32_t L, int64_t I, int64_t H, int64_t P,
+                      const float *const *W, const float *const *Wp, const float *const *bias,
+                      const float *x, const double *h0, const double *c0,
+                      double *hseq, double *hT, double *cT, int64_t T, int64_t B) {
+    if (L <= 0 || I <= 0 || H <= 0 || P <= 0 || T < 0 || B <= 0 || !W || !Wp || !hT) return -1;
+    int64_t maxin = I > P ? I : P;
+    double *r = (double *)calloc((size_t)(L * B * P), sizeof(double));
+    double *c = (double *)calloc((size_t)(L * B * H), sizeof(double));
+    double *u = (double *)malloc(sizeof(double) * (size_t)maxin);
+    double *a = (double *)malloc(sizeof(double) * (size_t)(4 * H));
+    double *m = (double *)malloc(sizeof(double) * (size_t)H);
+    double *rn = (double *)malloc(sizeof(double) * (size_t)P);
+    if (h0) memcpy(r, h0, sizeof(double) * (size_t)(L * B * P));
+    if (c0) memcpy(c, c0, sizeof(double) * (size_t)(L * B * H));
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t s = 0; s < B; ++s) {
+            for (int32_t l = 0; l < L; ++l) {
+                const int64_t n_in = l == 0 ? I : P, ld = n_in + P;
+                if (l == 0) for (int64_t j = 0; j < I; ++j) u[j] = (double)x[(t * B + s) * I + j];
+                else        for (int64_t j = 0; j < P; ++j) u[j] = r[((l - 1) * B + s) * P + j];
+                double *rl = r + (l * B + s) * P, *cl = c + (l * B + s) * H;
+                const float *Wl = W[l], *bl = bias ? bias[l] : NULL;
+#pragma omp parallel for schedule(static)
+                for (int64_t i = 0; i < 4 * H; ++i) {
+                    double sum = bl ? (double)bl[i] : 0.0;
+                    for (int64_t j = 0; j < n_in; ++j) sum += (double)Wl[i * ld + j] * u[j];
+                    for (int64_t j = 0; j < P; ++j) sum += (double)Wl[i * ld + n_in + j] * rl[j];
+                    a[i] = sum;
+                }
+                for (int64_t k = 0; k < H; ++k) {
+                    double cn = sigmoid(a[H + k]) * cl[k] + sigmoid(a[k]) * tanh(a[2 * H + k]);
+                    cl[k] = cn;
+                    m[k] = sigmoid(a[3 * H + k]) * tanh(cn);
+                }
+                const float *Pl = Wp[l];
+#pragma omp parallel for schedule(static)
+                for (int64_t i = 0; i < P; ++i) {
+                    double sum = 0.0;
+                    for (int64_t k = 0; k < H; ++k) sum += (double)Pl[i * H + k] * m[k];
+                    rn[i] = sum;
+                }
+                memcpy(rl, rn, sizeof(double) * (size_t)P);
+            }
+            if (hseq) for (int64_t k = 0; k < P; ++k) hseq[(t * B + s) * P + k] = r[((L - 1) * B + s) * P + k];
+        }
+    }
+    memcpy(hT, r, sizeof(double) * (size_t)(L * B * P));
+    if (cT) memcpy(cT, c, sizeof(double) * (size_t)(L * B * H));
+    free(r); free(c); free(u); free(a); free(m); free(rn);
     return 0;
 }
 

@@ -143,3 +143,62 @@ def test_resume_and_layer_composition(cell):
     q2, qh2, qc2 = oracle.rnn_forward(cell, W[1:], wl.bias[1:], q1.astype(np.float32), H, H)
     assert np.array_equal(qh1[0], hT[0])
     assert np.allclose(q2, hseq, rtol=0, atol=5e-6)
+
+
+# ---- LSTM with a recurrent projection (the paper's SR1 cell, Table 1) -----------------------
+
+def _torch_lstmp(W, Wp, bias, x, I, H, P, h0, c0):
+    """torch.nn.LSTM with proj_size, CPU, float64: weight_ih|weight_hh = W split at the input
+    width, weight_hr = the projection, bias_ih = b, bias_hh = 0."""
+    L = len(W)
+    mod = torch.nn.LSTM(I, H, num_layers=L, bias=True, proj_size=P).double()
+    with torch.no_grad():
+        for l in range(L):
+            n_in = I if l == 0 else P
+            getattr(mod, f"weight_ih_l{l}").copy_(torch.from_numpy(W[l][:, :n_in].astype(np.float64)))
+            getattr(mod, f"weight_hh_l{l}").copy_(torch.from_numpy(W[l][:, n_in:].astype(np.float64)))
+            getattr(mod, f"weight_hr_l{l}").copy_(torch.from_numpy(Wp[l].astype(np.float64)))
+            getattr(mod, f"bias_ih_l{l}").copy_(torch.from_numpy(bias[l].astype(np.float64)))
+            getattr(mod, f"bias_hh_l{l}").zero_()
+        out, (hT, cT) = mod(torch.from_numpy(x.astype(np.float64)), (torch.from_numpy(h0), torch.from_numpy(c0)))
+    return out.numpy(), hT.numpy(), cT.numpy()
+
+
+@pytest.mark.parametrize("L,I,H,P,T,B", [(1, 5, 8, 3, 6, 1), (2, 12, 16, 8, 9, 3), (3, 7, 12, 11, 4, 2), (2, 9, 16, 4, 5, 2)])
+def test_lstmp_against_torch_float64(L, I, H, P, T, B):
+    wl = csb_inputs.make_lstmp(31 + L, L, I, H, P, 4, 2.0, T, B, sigma=0.3)
+    W, Wp = [m.A for m in wl.W], [m.A for m in wl.Wp]
+    rng = np.random.default_rng(2)
+    h0 = rng.uniform(-0.5, 0.5, (L, B, P))
+    c0 = rng.uniform(-0.5, 0.5, (L, B, H))
+    hseq, hT, cT = oracle.lstmp_forward(W, Wp, wl.bias, wl.x, I, H, P, h0=h0, c0=c0)
+    rseq, rhT, rcT = _torch_lstmp(W, Wp, wl.bias, wl.x, I, H, P, h0, c0)
+    assert np.allclose(hseq, rseq, rtol=0, atol=1e-12)
+    assert np.allclose(hT, rhT, rtol=0, atol=1e-12)
+    assert np.allclose(cT, rcT, rtol=0, atol=1e-12)
+
+
+def test_lstmp_with_identity_projection_is_the_lstm():
+    """P = H and Wp = I: the projected cell is the plain LSTM the other tests pin."""
+    L, I, H, T, B = 2, 6, 8, 7, 2
+    wl = _small(csb_inputs.LSTM, L, I, H, T, B, seed=5)
+    W = [m.A for m in wl.W]
+    eye = [np.eye(H, dtype=np.float32)] * L
+    a = oracle.lstmp_forward(W, eye, wl.bias, wl.x, I, H, H)
+    b = oracle.rnn_forward(csb_inputs.LSTM, W, wl.bias, wl.x, I, H)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+
+
+def test_lstmp_zero_gate_weights_closed_form():
+    """W = 0, b = 0: every gate is 1/2, g = 0, so c_t = c_0 / 2^t and r_t = Wp (tanh(c_t) / 2)."""
+    I, H, P, T = 3, 5, 4, 6
+    rng = np.random.default_rng(3)
+    Wp = rng.normal(0, 1, (P, H)).astype(np.float32)
+    c0 = rng.uniform(-1, 1, (1, 1, H))
+    x = rng.uniform(-1, 1, (T, 1, I)).astype(np.float32)
+    hseq, hT, cT = oracle.lstmp_forward([np.zeros((4 * H, I + P), np.float32)], [Wp], None, x, I, H, P, c0=c0)
+    for t in range(T):
+        ct = c0[0, 0] / 2.0 ** (t + 1)
+        assert np.allclose(hseq[t, 0], Wp.astype(np.float64) @ (0.5 * np.tanh(ct)), rtol=0, atol=1e-14)
+    assert np.allclose(cT[0, 0], c0[0, 0] / 2.0 ** T, rtol=0, atol=1e-15)
