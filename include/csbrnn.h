@@ -42,6 +42,7 @@ extern "C" {
 
 #define CSB_CELL_LSTM 0
 #define CSB_CELL_GRU 1
+#define CSB_CELL_LSTMP 2     /* LSTM with a recurrent projection; created by csb_rnn_create_lstmp */
 
 #define CSB_MAX_BLOCK 256     /* br, bc in [1, 256]: device indices are one byte */
 
@@ -206,6 +207,23 @@ int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int
  */
 int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int32_t hidden,
                    csb_matrix *const *W, const float *const *d_bias, csb_rnn **out);
+
+/*
+ * LSTM with a recurrent projection (LSTMP: the cell of the paper's speech model SR1,
+ * Table 1; the paper names the cell and gives no equations, so this is the cell as its
+ * authors published it).  Per layer: a = W [u ; r_(t-1)] + b with rows i,f,g,o as for the
+ * LSTM, c_t = f c_(t-1) + i g, m_t = o tanh(c_t) (hidden wide), and r_t = Wp m_t (proj wide,
+ * no bias, no non-linearity); r_t is the recurrent state and the next layer's input.
+ * W[l]: (4*hidden) x (in_l + proj) with in_0 = input, in_l = proj; Wp[l]: proj x hidden; both
+ * packed, planned by this call if they are not yet.  Upload every W[l] and Wp[l] with
+ * csb_upload.  In csb_rnn_forward the state h (d_h0, d_hT, d_hseq) is proj wide and the cell
+ * state c (d_c0, d_cT) hidden wide.  Runs on the streaming paths (two CSB products and one
+ * gate kernel per step and layer; batch > 1 on the matrix cores); there is no resident
+ * layout for this cell.  Errors as csb_rnn_create.
+ */
+int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hidden, int32_t proj,
+                         csb_matrix *const *W, csb_matrix *const *Wp, const float *const *d_bias,
+                         csb_rnn **out);
 
 /*
  * Resident layout of the whole model for batch-1 inference: every row's surviving weights

@@ -9,6 +9,7 @@ import numpy as np
 
 CELL_LSTM = 0
 CELL_GRU = 1
+CELL_LSTMP = 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libcsbrnn.so")
@@ -19,7 +20,7 @@ SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_plan
            "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
-           "csb_project_workspace_bytes", "csb_project",
+           "csb_project_workspace_bytes", "csb_project", "csb_rnn_create_lstmp",
            "csb_rnn_create", "csb_rnn_device_bytes", "csb_rnn_upload", "csb_rnn_stats",
            "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
 
@@ -92,6 +93,8 @@ def load_library():
     L.csb_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     L.csb_rnn_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
+    L.csb_rnn_create_lstmp.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
+                                       C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
     L.csb_rnn_device_bytes.argtypes = [C.c_void_p]
     L.csb_rnn_device_bytes.restype = C.c_size_t
     L.csb_rnn_upload.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -277,16 +280,25 @@ class CsbMatrix:
 class CsbRnn:
     """csb_rnn handle; keeps its matrices and bias tensors alive."""
 
-    def __init__(self, cell: int, input: int, hidden: int, W: Sequence[CsbMatrix], bias=None):
+    def __init__(self, cell: int, input: int, hidden: int, W: Sequence[CsbMatrix], bias=None,
+                 proj: int = 0, Wp: Optional[Sequence[CsbMatrix]] = None):
+        """cell CELL_LSTM / CELL_GRU: csb_rnn_create.  cell CELL_LSTMP: csb_rnn_create_lstmp with the
+        projection width `proj` and the projection matrices `Wp`."""
         self.cell, self.input, self.hidden, self.W = cell, input, hidden, list(W)
+        self.proj, self.Wp = proj, (list(Wp) if Wp is not None else [])
         self.bias = list(bias) if bias is not None else None
         L = len(self.W)
-        Wp = (C.c_void_p * L)(*[w.handle for w in self.W])
+        Wv = (C.c_void_p * L)(*[w.handle for w in self.W])
         Bp = None
         if self.bias is not None:
             Bp = (C.c_void_p * L)(*[_dptr(b) for b in self.bias])
         self._h = C.c_void_p()
-        _check(lib().csb_rnn_create(cell, L, input, hidden, Wp, Bp, C.byref(self._h)))
+        if cell == CELL_LSTMP:
+            assert proj > 0 and len(self.Wp) == L
+            Pv = (C.c_void_p * L)(*[w.handle for w in self.Wp])
+            _check(lib().csb_rnn_create_lstmp(L, input, hidden, proj, Wv, Pv, Bp, C.byref(self._h)))
+        else:
+            _check(lib().csb_rnn_create(cell, L, input, hidden, Wv, Bp, C.byref(self._h)))
         self.n_layers = L
         self._ws = None
 
@@ -320,9 +332,11 @@ class CsbRnn:
         need = self.workspace_bytes(B, T)
         if self._ws is None or self._ws.numel() * 4 < need:
             self._ws = torch.empty((need + 3) // 4 + 64, dtype=torch.float32, device=dev)
-        hseq = torch.empty((T, B, self.hidden), dtype=torch.float32, device=dev) if want_hseq else None
-        hT = torch.empty((self.n_layers, B, self.hidden), dtype=torch.float32, device=dev)
-        cT = torch.empty_like(hT) if self.cell == CELL_LSTM else None
+        hs = self.proj if self.cell == CELL_LSTMP else self.hidden        # width of the state h
+        hseq = torch.empty((T, B, hs), dtype=torch.float32, device=dev) if want_hseq else None
+        hT = torch.empty((self.n_layers, B, hs), dtype=torch.float32, device=dev)
+        cT = (torch.empty((self.n_layers, B, self.hidden), dtype=torch.float32, device=dev)
+              if self.cell in (CELL_LSTM, CELL_LSTMP) else None)
         _check(lib().csb_rnn_forward(self._h, _dptr(x), _dptr(h0), _dptr(c0), _dptr(hseq), _dptr(hT), _dptr(cT),
                                      T, B, _dptr(self._ws), _stream_ptr(stream)))
         return hseq, hT, cT

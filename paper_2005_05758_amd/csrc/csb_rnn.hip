@@ -61,7 +61,10 @@ struct RnnPlan {
 
 struct csb_rnn {
     int32_t cell = 0, n_layers = 0, input = 0, hidden = 0;
+    int32_t proj = 0;                      // LSTMP: width of the recurrent projection (the state h is this wide)
     std::vector<csb_matrix *> W;
+    std::vector<csb_matrix *> Wp;          // LSTMP: projection matrices, proj x hidden
+    int32_t state_width() const { return proj > 0 ? proj : hidden; }
     std::vector<const float *> d_bias;
     csb::RnnPlan plan;
     void *d_img = nullptr;
@@ -632,6 +635,40 @@ __global__ void gru_gates_batched_kernel(const float *__restrict__ a, const floa
     if (hseq) hseq[(size_t)n * H + k] = hn;
 }
 
+// LSTMP: the cell output m_t = o tanh(c_t) goes to a buffer of its own; the projection
+// r_t = Wp m_t (a CSB mat-vec) follows.
+__global__ void lstmp_gates_kernel(const float *__restrict__ a, const float *__restrict__ bias,
+                                   float *__restrict__ c, float *__restrict__ m, const int H) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= H) return;
+    float ai = a[k], af = a[H + k], ag = a[2 * H + k], ao = a[3 * H + k];
+    if (bias) { ai += bias[k]; af += bias[H + k]; ag += bias[2 * H + k]; ao += bias[3 * H + k]; }
+    const float cn = sigmoidf_(af) * c[k] + sigmoidf_(ai) * tanhf(ag);
+    c[k] = cn;
+    m[k] = sigmoidf_(ao) * tanhf(cn);
+}
+
+__global__ void lstmp_gates_batched_kernel(const float *__restrict__ a, const float *__restrict__ bias,
+                                           float *__restrict__ c, float *__restrict__ m, const int H, const int B) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= H * B) return;
+    const int k = e / B, n = e - k * B;
+    float ai = a[(size_t)k * B + n], af = a[(size_t)(H + k) * B + n], ag = a[(size_t)(2 * H + k) * B + n],
+          ao = a[(size_t)(3 * H + k) * B + n];
+    if (bias) { ai += bias[k]; af += bias[H + k]; ag += bias[2 * H + k]; ao += bias[3 * H + k]; }
+    const float cn = sigmoidf_(af) * c[e] + sigmoidf_(ai) * tanhf(ag);
+    c[e] = cn;
+    m[e] = sigmoidf_(ao) * tanhf(cn);
+}
+
+// hseq[b][k] = h[k][b] for one step ([W][B] internal -> [B][W] caller's layout)
+__global__ void seq_out_kernel(float *__restrict__ dst, const float *__restrict__ src, int W, int B) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= W * B) return;
+    const int b = e / W, k = e - b * W;
+    dst[e] = src[(size_t)k * B + b];
+}
+
 // [L][B][H] (caller's layout) <-> [L][H][B] (internal); src may be null (zeros).
 __global__ void state_in_kernel(float *__restrict__ dst, const float *__restrict__ src, int L, int B, int H) {
     const size_t n = (size_t)L * B * H;
@@ -669,27 +706,31 @@ static void init_state(float *dst, const float *src, size_t n, hipStream_t st) {
 static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 struct RnnWs {
-    size_t off_a, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, total;
+    size_t off_a, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, off_m, total;
 };
 
 static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     RnnWs w{};
     size_t off = 0;
     size_t rows_out = 0, part = 0;
-    for (auto *m : r->W) {
-        if (!m->plan.valid) continue;
+    auto account = [&](const csb_matrix *m) {
+        if (!m->plan.valid) return;
         rows_out = std::max<size_t>(rows_out, (size_t)m->plan.hdr.rows_out);
         part = std::max<size_t>(part, (size_t)m->plan.hdr.n_partial_slots * m->plan.hdr.br * 8);
-    }
+    };
+    for (auto *m : r->W) account(m);
+    for (auto *m : r->Wp) account(m);
+    const size_t HS = (size_t)r->state_width();
     w.off_a = off; off = align256(off + rows_out * sizeof(float) * (size_t)batch);
     w.off_c = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     w.off_part = off; off = align256(off + part);
     w.off_biasptr = off; off = align256(off + (size_t)r->n_layers * sizeof(void *));
     w.off_seq = off; off = align256(off + (size_t)r->n_layers * (size_t)std::max(T, 1) * r->hidden * 8);
     if (batch > 1) {
-        w.off_hint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
+        w.off_hint = off; off = align256(off + (size_t)r->n_layers * batch * HS * sizeof(float));
         w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     }
+    w.off_m = off; off = align256(off + (r->proj > 0 ? (size_t)batch * r->hidden * sizeof(float) : 0));
     off += 512;   // last 512 bytes: debug clocks of the resident kernel
     w.total = off;
     return w;
@@ -786,6 +827,42 @@ extern "C" int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int
     }
 }
 
+extern "C" int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hidden, int32_t proj,
+                                    csb_matrix *const *W, csb_matrix *const *Wp, const float *const *d_bias,
+                                    csb_rnn **out) {
+    using namespace csb;
+    if (!W || !Wp || !out) { set_error("csb_rnn_create_lstmp: NULL pointer"); return CSB_EINVAL; }
+    *out = nullptr;
+    if (n_layers <= 0 || input <= 0 || hidden <= 0 || proj <= 0) { set_error("csb_rnn_create_lstmp: non-positive size"); return CSB_EINVAL; }
+    for (int l = 0; l < n_layers; ++l) {
+        if (!W[l] || !Wp[l]) { set_error("csb_rnn_create_lstmp: NULL weight matrix"); return CSB_EINVAL; }
+        const int64_t n_in = l == 0 ? input : proj;
+        if (W[l]->rows != (int64_t)4 * hidden || W[l]->cols != n_in + proj || Wp[l]->rows != proj || Wp[l]->cols != hidden) {
+            set_error("csb_rnn_create_lstmp: shapes must be (4*hidden) x (in + proj) and proj x hidden");
+            return CSB_EINVAL;
+        }
+    }
+    try {
+        auto *r = new csb_rnn();
+        r->cell = CSB_CELL_LSTMP; r->n_layers = n_layers; r->input = input; r->hidden = hidden; r->proj = proj;
+        for (int l = 0; l < n_layers; ++l) {
+            for (csb_matrix *m : {W[l], Wp[l]})
+                if (!m->plan.valid || m->plan.split.active()) {
+                    int rc = plan_matrix(m, 0, 16, SplitSpec{}, nullptr, 0);
+                    if (rc != CSB_OK) { delete r; return rc; }
+                }
+            r->W.push_back(W[l]);
+            r->Wp.push_back(Wp[l]);
+            r->d_bias.push_back(d_bias ? d_bias[l] : nullptr);
+        }
+        *out = r;                                  // no resident layout for this cell: plan stays invalid
+        return CSB_OK;
+    } catch (const std::bad_alloc &) {
+        set_error("csb_rnn_create_lstmp: out of host memory");
+        return CSB_ENOMEM;
+    }
+}
+
 extern "C" size_t csb_rnn_device_bytes(const csb_rnn *r) {
     return (r && r->plan.valid) ? r->plan.image.size() : 0;
 }
@@ -827,20 +904,28 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
     if (T > 0 && !d_x) { set_error("csb_rnn_forward: NULL input sequence"); return CSB_EINVAL; }
     hipStream_t st = (hipStream_t)stream;
     const int L = r->n_layers, H = r->hidden, I = r->input;
-    const bool lstm = r->cell == CSB_CELL_LSTM;
-    const size_t nstate = (size_t)L * batch * H;
+    const bool lstmp = r->cell == CSB_CELL_LSTMP;
+    const bool lstm = r->cell == CSB_CELL_LSTM || lstmp;        // has a cell state c
+    const int HS = r->state_width();                             // width of h (the projection's for LSTMP)
+    const size_t nstate = (size_t)L * batch * HS, ncstate = (size_t)L * batch * H;
     if (T == 0) {                                  // hand the state through
         init_state(d_hT, d_h0, nstate, st);
-        if (lstm && d_cT) init_state(d_cT, d_c0, nstate, st);
+        if (lstm && d_cT) init_state(d_cT, d_c0, ncstate, st);
         return CSB_OK;
     }
     const bool resident = batch == 1 && r->plan.valid && r->uploaded;
-    if (!resident)
+    if (!resident) {
         for (auto *m : r->W)
             if (!m->plan.valid || !m->uploaded) {
                 set_error("csb_rnn_forward: neither the resident layout nor every weight matrix is uploaded");
                 return CSB_ESTATE;
             }
+        for (auto *m : r->Wp)
+            if (!m->plan.valid || !m->uploaded) {
+                set_error("csb_rnn_forward: a projection matrix is not uploaded");
+                return CSB_ESTATE;
+            }
+    }
     if (resident) return forward_resident(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, d_ws, st);
 
     const RnnWs wl = ws_layout(r, batch, T);
@@ -849,48 +934,62 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         // batched: one MFMA mat-mat launch and one gate launch per step and layer; the state
         // lives as [H][B] so that the batch index is the contiguous one
         float *hi = (float *)((uint8_t *)d_ws + wl.off_hint), *ci = (float *)((uint8_t *)d_ws + wl.off_cint);
-        const int sblocks = (int)std::min<size_t>((nstate + 255) / 256, 2048);
-        hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, hi, d_h0, L, batch, H);
+        float *mb = (float *)((uint8_t *)d_ws + wl.off_m);
+        const int sblocks = (int)std::min<size_t>((std::max(nstate, ncstate) + 255) / 256, 2048);
+        hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, hi, d_h0, L, batch, HS);
         if (lstm) hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, ci, d_c0, L, batch, H);
         const int gb = (H * batch + 255) / 256;
         for (int t = 0; t < T; ++t)
             for (int l = 0; l < L; ++l) {
-                float *hl = hi + (size_t)l * H * batch;
+                float *hl = hi + (size_t)l * HS * batch;
                 int rc;
                 if (l == 0)
                     rc = spmm_strided(r->W[l], d_x + (size_t)t * batch * I, (uint32_t)I, 1, I, hl, batch, 1, a, batch, batch, st);
                 else
-                    rc = spmm_strided(r->W[l], hi + (size_t)(l - 1) * H * batch, (uint32_t)H, batch, 1, hl, batch, 1, a, batch, batch, st);
+                    rc = spmm_strided(r->W[l], hi + (size_t)(l - 1) * HS * batch, (uint32_t)HS, batch, 1, hl, batch, 1, a, batch, batch, st);
                 if (rc != CSB_OK) return rc;
-                float *hs = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * batch * H : nullptr;
-                if (lstm)
+                float *hs = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * batch * HS : nullptr;
+                if (lstmp) {
+                    hipLaunchKernelGGL(lstmp_gates_batched_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l],
+                                       ci + (size_t)l * H * batch, mb, H, batch);
+                    rc = spmm_strided(r->Wp[l], mb, (uint32_t)H, batch, 1, mb, batch, 1, hl, batch, batch, st);
+                    if (rc != CSB_OK) return rc;
+                    if (hs) hipLaunchKernelGGL(seq_out_kernel, dim3((HS * batch + 255) / 256), dim3(256), 0, st, hs, hl, HS, batch);
+                } else if (lstm)
                     hipLaunchKernelGGL(lstm_gates_batched_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l],
                                        ci + (size_t)l * H * batch, hl, hs, H, batch);
                 else
                     hipLaunchKernelGGL(gru_gates_batched_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l], hl, hs, H, batch);
             }
-        hipLaunchKernelGGL(state_out_kernel, dim3(sblocks), dim3(256), 0, st, d_hT, hi, L, batch, H);
+        hipLaunchKernelGGL(state_out_kernel, dim3(sblocks), dim3(256), 0, st, d_hT, hi, L, batch, HS);
         if (lstm && d_cT) hipLaunchKernelGGL(state_out_kernel, dim3(sblocks), dim3(256), 0, st, d_cT, ci, L, batch, H);
         hipError_t eb = hipGetLastError();
         if (eb != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(eb)); return CSB_EDEVICE; }
         return CSB_OK;
     }
     float *c = (lstm && d_cT) ? d_cT : (float *)((uint8_t *)d_ws + wl.off_c);
+    float *mb = (float *)((uint8_t *)d_ws + wl.off_m);
     void *part = (uint8_t *)d_ws + wl.off_part;
     // the outputs double as the running state
     init_state(d_hT, d_h0, nstate, st);
-    if (lstm) init_state(c, d_c0, nstate, st);
+    if (lstm) init_state(c, d_c0, ncstate, st);
     const int gblocks = (H + 255) / 256;
     for (int t = 0; t < T; ++t)
         for (int s = 0; s < batch; ++s)
             for (int l = 0; l < L; ++l) {
-                const float *u = l == 0 ? d_x + ((size_t)t * batch + s) * I : d_hT + ((size_t)(l - 1) * batch + s) * H;
-                const uint32_t n_in = l == 0 ? (uint32_t)I : (uint32_t)H;
-                float *h = d_hT + ((size_t)l * batch + s) * H;
+                const float *u = l == 0 ? d_x + ((size_t)t * batch + s) * I : d_hT + ((size_t)(l - 1) * batch + s) * HS;
+                const uint32_t n_in = l == 0 ? (uint32_t)I : (uint32_t)HS;
+                float *h = d_hT + ((size_t)l * batch + s) * HS;
                 int rc = spmv_segments(r->W[l], u, n_in, h, a, part, st);
                 if (rc != CSB_OK) return rc;
-                float *hs = (d_hseq && l == L - 1) ? d_hseq + ((size_t)t * batch + s) * H : nullptr;
-                if (lstm)
+                float *hs = (d_hseq && l == L - 1) ? d_hseq + ((size_t)t * batch + s) * HS : nullptr;
+                if (lstmp) {
+                    hipLaunchKernelGGL(lstmp_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l],
+                                       c + ((size_t)l * batch + s) * H, mb, H);
+                    rc = spmv_segments(r->Wp[l], mb, (uint32_t)H, mb, h, part, st);
+                    if (rc != CSB_OK) return rc;
+                    if (hs) hipLaunchKernelGGL(copy_kernel, dim3((HS + 255) / 256), dim3(256), 0, st, hs, (const float *)h, (size_t)HS);
+                } else if (lstm)
                     hipLaunchKernelGGL(lstm_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l],
                                        c + ((size_t)l * batch + s) * H, h, hs, H);
                 else
