@@ -209,6 +209,7 @@ def main():
         out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix, sr["gbps"])
         out["batched"] = batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
         out["projection"] = projection_leg(torch, np, sr["gbps"], not args.no_cpu)
+        out["lstmp_sr1"] = lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, not args.no_cpu)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_leg(cfg, wl)
     print(json.dumps(out))
@@ -358,6 +359,43 @@ def projection_leg(torch, np, stream_gbps, with_cpu):
         oracle.csb_project(Wh, 32, 32, 12.0)
         res["cpu_baseline"] = {"value": round((time.perf_counter() - t0) * 1e3, 1), "unit": "ms", "cores": 1, "kind": "oracle",
                                "sample": "one projection of the same matrix (single-threaded C: float32 sums, qsort per block-column / block-row)"}
+    return res
+
+
+def lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
+    """The shape of the paper's speech model SR1 (Table 1): two LSTMP layers, 153 -> 1024 and
+    512 -> 1024 with a 512-wide projection, 13x in 32 x 32 blocks, synthetic weights.  Batch 1
+    (one frame at a time: two CSB mat-vecs and a gate kernel per layer and frame) and batch 32
+    on the matrix cores.  The paper's FPGA figure for its trained SR1 is 6.58 us per frame
+    (another machine, 16-bit fixed point: context, not a baseline)."""
+    from paper_2005_05758_amd import CELL_LSTMP
+    res = {}
+    for batch, T in ((1, 100), (32, 100)):
+        wl = csb_inputs.make_lstmp(0, 2, 153, 1024, 512, 32, 13.0, T, batch)
+        Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+        Ps = [CsbMatrix(m.A, m.br, m.bc) for m in wl.Wp]
+        bias = [torch.from_numpy(b).cuda() for b in wl.bias]
+        rnn = CsbRnn(CELL_LSTMP, 153, 1024, Ws, bias, proj=512, Wp=Ps)
+        for m in Ws + Ps:
+            m.upload()
+        xd = torch.from_numpy(wl.x).cuda()
+        rnn.forward(xd, want_hseq=True)
+        n = 3
+        ms = time_region(lambda: rnn.forward(xd, want_hseq=True), n, torch) / n
+        nnz = sum(int(m.view()["nnz"]) for m in Ws + Ps)
+        res[f"batch{batch}"] = {"us_per_frame": round(ms * 1000.0 / T, 2), "frames_per_s": round(batch * T / (ms * 1e-3), 1),
+                                "nnz": nnz, "tflops_algorithmic": round(2.0 * nnz * batch / (ms * 1e-3 / T) / 1e12, 4)}
+        if with_cpu and batch == 1:
+            import oracle
+            W, Wp = [m.A for m in wl.W], [m.A for m in wl.Wp]
+            t0 = time.perf_counter()
+            reps = 0
+            while time.perf_counter() - t0 < 5.0:
+                oracle.lstmp_forward(W, Wp, wl.bias, wl.x, 153, 1024, 512)
+                reps += 1
+            res["cpu_baseline"] = {"value": round((time.perf_counter() - t0) / (reps * T) * 1e6, 2), "unit": "us/frame",
+                                   "cores": oracle.num_threads(), "kind": "oracle",
+                                   "sample": f"{reps} sequences of T={T}, batch 1 (float64 dense masked products + gates)"}
     return res
 
 

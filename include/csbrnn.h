@@ -217,9 +217,11 @@ int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int32_t hidden
  * W[l]: (4*hidden) x (in_l + proj) with in_0 = input, in_l = proj; Wp[l]: proj x hidden; both
  * packed, planned by this call if they are not yet.  Upload every W[l] and Wp[l] with
  * csb_upload.  In csb_rnn_forward the state h (d_h0, d_hT, d_hseq) is proj wide and the cell
- * state c (d_c0, d_cT) hidden wide.  Runs on the streaming paths (two CSB products and one
- * gate kernel per step and layer; batch > 1 on the matrix cores); there is no resident
- * layout for this cell.  Errors as csb_rnn_create.
+ * state c (d_c0, d_cT) hidden wide.  Batch 1 with the resident layout uploaded
+ * (csb_rnn_upload): one kernel launch for the whole sequence, the gate rows and the
+ * projection rows of a layer being two stages that hand m_t and r_t to each other; else the
+ * streaming paths (two CSB products and one gate kernel per step and layer; batch > 1 on the
+ * matrix cores).  Errors as csb_rnn_create.
  */
 int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hidden, int32_t proj,
                          csb_matrix *const *W, csb_matrix *const *Wp, const float *const *d_bias,

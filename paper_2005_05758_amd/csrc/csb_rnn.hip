@@ -33,18 +33,32 @@ constexpr int kRnnSlotsMax = 48;       // weights one lane keeps in registers
 constexpr int kRnnMaxWgs = 240;        // all workgroups must be co-resident (256 CUs)
 constexpr uint32_t kPollLimit = 1u << 24;
 
+// The resident kernel works on a stack of stages.  An LSTM / GRU layer is one stage (its
+// units' gate rows); an LSTMP layer is two: the gate stage, whose output m_t is not state, and
+// a linear stage (the projection r_t = Wp m_t), whose output is the layer's state h and the
+// gate stage's recurrent input.
+constexpr uint32_t kStageLstm = 0, kStageGru = 1, kStageLinear = 2;
+constexpr uint32_t kStageOwnRec = 1;     // flag: the recurrent input is this stage's own output
+constexpr uint32_t kStageIsState = 2;    // flag: the output is the layer's h state (h0 / hT)
+constexpr uint32_t kStageIsSeq = 4;      // flag: the output is the model's output sequence
+constexpr uint32_t kNoStage = 0xffffffffu;
+
 // One workgroup of the resident kernel.
 struct RnnWgRec {
-    uint32_t layer;
-    uint32_t u0, nu;          // hidden units [u0, u0 + nu) of the layer
+    uint32_t layer;           // stage
+    uint32_t u0, nu;          // units [u0, u0 + nu) of the stage
     uint32_t nlanes;          // lanes that hold a slice of a row
     uint32_t S;               // slots per lane
-    uint32_t n_in, C;         // input width of the layer, C = n_in + H
+    uint32_t n_in, C;         // width of the input from below, C = n_in + width of the recurrent input
     uint32_t off_rows;        // byte offset of the lane table: 1024 words (segment position, flags, row slot)
     uint32_t off_w;           // byte offset of weights  [S][1024] float
     uint32_t off_z;           // byte offset of z indices [S][1024] u16
-    uint32_t upre;            // hidden units owned by the workgroups before this one (all layers)
-    uint32_t pad[5];
+    uint32_t upre;            // units owned by the workgroups before this one (all stages)
+    uint32_t kind;            // stage kind | model layer << 8 | flags << 16
+    uint32_t below;           // owner-table offset of the stage below, kNoStage = the input sequence x
+    uint32_t rec;             // owner-table offset of the stage the recurrent input comes from, or kNoStage
+    uint32_t width;           // units of this stage
+    uint32_t rec_width;       // units of the recurrent source (row length of h0 for it)
 };
 static_assert(sizeof(RnnWgRec) == 64, "RnnWgRec layout");
 
@@ -52,7 +66,9 @@ struct RnnPlan {
     bool valid = false;
     int n_wgs = 0, smax = 0;
     std::vector<uint8_t> image;
-    size_t off_unit_wg = 0;    // [L][H] u16: workgroup that owns each hidden unit
+    size_t off_unit_wg = 0;    // u16 per unit of every stage: the workgroup that owns it
+    size_t total_units = 0;    // units of all stages (exchange words per time step)
+    size_t cmax = 0;           // largest C of any stage (LDS sizing)
     double slot_fill = 0;      // non-zeros / (1024 * S * workgroups): the useful share of issued multiply-adds
     double lanes_max_over_mean = 0;
 };
@@ -127,23 +143,65 @@ static int pack_segments(const std::vector<int> &k, std::vector<int> *place) {
     return (int)fill.size();
 }
 
+// Rows of a projection matrix (P x H) as a linear stage: unit u has the single row u.
+static void gather_linear_rows(const csb_matrix *m, int width,
+                               std::vector<std::vector<std::pair<uint32_t, float>>> &rows) {
+    rows.assign((size_t)4 * width, {});
+    for (int32_t bi = 0; bi < m->nbr; ++bi)
+        for (int32_t bj = 0; bj < m->nbc; ++bj) {
+            const size_t b = (size_t)bi * m->nbc + bj;
+            const int nr = m->nrows[b], nc = m->ncols[b];
+            for (int a = 0; a < nr; ++a) {
+                const int64_t gr = (int64_t)bi * m->br + m->rowidx[m->row_off[b] + a];
+                for (int q = 0; q < nc; ++q)
+                    rows[(size_t)gr].emplace_back((uint32_t)((int64_t)bj * m->bc + m->colidx[m->col_off[b] + q]),
+                                                  m->val[m->val_off[b] + (size_t)a * nc + q]);
+            }
+        }
+}
+
 static int build_resident_plan(csb_rnn *r) {
     RnnPlan &pl = r->plan;
     pl = RnnPlan{};
-    const int L = r->n_layers, H = r->hidden;
+    const bool lstmp = r->cell == CSB_CELL_LSTMP;
+    const int NL = r->n_layers, L = lstmp ? 2 * NL : NL;      // L stages
     struct LayerTmp {
         std::vector<std::vector<std::pair<uint32_t, float>>> rows;
         int n_in, C, S, P;
+        int width;                  // units of the stage
+        uint32_t kind, real, flags;
+        int below, rec;             // stage indices, -1 = x / none
         std::vector<int> u_cut;     // unit ranges per workgroup
     };
     std::vector<LayerTmp> lt(L);
     size_t total_nnz = 0;
     for (int l = 0; l < L; ++l) {
-        lt[l].n_in = l == 0 ? r->input : H;
-        lt[l].C = lt[l].n_in + H;
-        if (lt[l].C + 1 > 16000) return CSB_EUNSUPPORTED;        // z indices are 16 bit, LDS holds z
-        gather_rows(r->W[l], r->cell, H, lt[l].n_in, lt[l].rows);
-        for (auto &row : lt[l].rows) total_nnz += row.size();
+        LayerTmp &t = lt[l];
+        if (!lstmp) {
+            t.width = r->hidden; t.real = (uint32_t)l;
+            t.kind = r->cell == CSB_CELL_LSTM ? kStageLstm : kStageGru;
+            t.n_in = l == 0 ? r->input : r->hidden;
+            t.C = t.n_in + r->hidden;
+            t.below = l - 1; t.rec = l;
+            t.flags = kStageOwnRec | kStageIsState | (l == L - 1 ? kStageIsSeq : 0u);
+            gather_rows(r->W[l], r->cell, r->hidden, t.n_in, t.rows);
+        } else if ((l & 1) == 0) {                       // gate stage of model layer l / 2
+            t.width = r->hidden; t.real = (uint32_t)(l / 2); t.kind = kStageLstm;
+            t.n_in = l == 0 ? r->input : r->proj;
+            t.C = t.n_in + r->proj;
+            t.below = l - 1; t.rec = l + 1;
+            t.flags = 0;
+            gather_rows(r->W[l / 2], CSB_CELL_LSTM, r->hidden, t.n_in, t.rows);
+        } else {                                         // projection stage
+            t.width = r->proj; t.real = (uint32_t)(l / 2); t.kind = kStageLinear;
+            t.n_in = r->hidden; t.C = r->hidden;
+            t.below = l - 1; t.rec = -1;
+            t.flags = kStageIsState | (l == L - 1 ? kStageIsSeq : 0u);
+            gather_linear_rows(r->Wp[l / 2], r->proj, t.rows);
+        }
+        if (t.C + 1 > 16000) return CSB_EUNSUPPORTED;            // z indices are 16 bit, LDS holds z
+        pl.cmax = std::max<size_t>(pl.cmax, (size_t)t.C);
+        for (auto &row : t.rows) total_nnz += row.size();
     }
     // Slots per lane S and workgroups per layer.  A row's non-zeros are cut into k slices of
     // S entries, one lane each; the k lanes sit inside one aligned 32-lane half of a wavefront
@@ -157,6 +215,7 @@ static int build_resident_plan(csb_rnn *r) {
     int total_wgs = 0;
     for (int l = 0; l < L; ++l) {
         LayerTmp &t = lt[l];
+        const int H = t.width;                    // units of this stage
         size_t max_nnz = 0;
         for (auto &row : t.rows) max_nnz = std::max(max_nnz, row.size());
         double best_cost = 1e30;
@@ -212,18 +271,27 @@ static int build_resident_plan(csb_rnn *r) {
     auto align = [&](size_t a) { while (body.size() % a) body.push_back(0); };
     size_t slots_total = 0;
     uint32_t upre_run = 0;
-    std::vector<uint16_t> unit_wg((size_t)L * H, 0);
+    std::vector<size_t> uoff(L + 1, 0);                      // owner-table offset of every stage
+    for (int l = 0; l < L; ++l) uoff[l + 1] = uoff[l] + (size_t)lt[l].width;
+    std::vector<uint16_t> unit_wg(uoff[L], 0);
+    pl.total_units = uoff[L];
     int smax = 0;
     double lanes_max = 0, lanes_sum = 0;
     for (int l = 0; l < L; ++l) {
         const LayerTmp &t = lt[l];
+        const int H = t.width;
         smax = std::max(smax, t.S);
         for (int p = 0; p < t.P; ++p) {
             RnnWgRec w{};
             w.layer = (uint32_t)l; w.u0 = (uint32_t)t.u_cut[p]; w.nu = (uint32_t)(t.u_cut[p + 1] - t.u_cut[p]);
             w.S = (uint32_t)t.S; w.n_in = (uint32_t)t.n_in; w.C = (uint32_t)t.C;
             w.upre = upre_run; upre_run += w.nu;
-            for (uint32_t ui = 0; ui < w.nu; ++ui) unit_wg[(size_t)l * H + w.u0 + ui] = (uint16_t)wgs.size();
+            w.kind = t.kind | t.real << 8 | t.flags << 16;
+            w.below = t.below < 0 ? kNoStage : (uint32_t)uoff[t.below];
+            w.rec = t.rec < 0 ? kNoStage : (uint32_t)uoff[t.rec];
+            w.width = (uint32_t)t.width;
+            w.rec_width = t.rec < 0 ? 0u : (uint32_t)lt[t.rec].width;
+            for (uint32_t ui = 0; ui < w.nu; ++ui) unit_wg[uoff[l] + w.u0 + ui] = (uint16_t)wgs.size();
             // per lane: position in its row's segment (bits 0-4), last lane of the segment
             // (bit 5), lane in use (bit 6), row slot g*nu + unit (bits 8-19)
             std::vector<uint32_t> lanetab(kRnnThreads, 0);
@@ -337,13 +405,13 @@ __device__ __forceinline__ float fast_tanh(float v) {
 struct RnnArgs {
     const uint8_t *img;                 // resident image
     const float *x;                     // [T][I]
-    const float *h0, *c0;               // [L][H] or null
-    const float *bias[8];               // per layer, entries may be null
-    float *hseq;                        // [T][H] or null
-    float *hT, *cT;                     // [L][H]; cT may be null
-    unsigned long long *seq;            // [L][T][H] tagged words
-    uint32_t T, L, H, I, cell, tag_base;
-    uint32_t off_unit_wg;               // byte offset in img of the [L][H] owner table
+    const float *h0, *c0;               // [layers][state width], [layers][H] or null
+    const float *bias[8];               // per model layer, entries may be null
+    float *hseq;                        // [T][state width] or null
+    float *hT, *cT;                     // [layers][state width], [layers][H]; cT may be null
+    unsigned long long *seq;            // tagged words: per workgroup [T][its units]
+    uint32_t T, H, I, tag_base;         // H: hidden width (rows per gate, width of c)
+    uint32_t off_unit_wg;               // byte offset in img of the owner table
     uint32_t poll_delay;                // s_sleep units before the first poll of a step (0 = none)
     uint32_t wg_stride;                 // workgroup w is block w * wg_stride; other blocks exit at once
     unsigned long long *dbg;            // optional: per-phase shader clocks summed over the steps (workgroup 0)
@@ -382,7 +450,10 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     const uint32_t tid = threadIdx.x;
     if (blockIdx.x % A.wg_stride != 0) return;
     const RnnWgRec wg = ((const RnnWgRec *)A.img)[blockIdx.x / A.wg_stride];
-    const uint32_t l = wg.layer, H = A.H, T = A.T, nu = wg.nu, n_in = wg.n_in, C = wg.C, S = wg.S;
+    const uint32_t H = A.H, T = A.T, nu = wg.nu, n_in = wg.n_in, C = wg.C, S = wg.S;
+    const uint32_t kind = wg.kind & 0xffu, real = (wg.kind >> 8) & 0xffu, flags = wg.kind >> 16;
+    const bool lstm = kind == kStageLstm, linear = kind == kStageLinear;
+    const bool from_x = wg.below == kNoStage, own_rec = (flags & kStageOwnRec) != 0;
     float *z = lds;                       // [C + 1], z[C] = 0
     float *arow = lds + ((C + 1 + 63) & ~63u);   // [4 * nu] row sums
     // weights and LDS addresses of their inputs: registers for the whole sequence
@@ -398,70 +469,70 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
             za[s] = (in ? (uint32_t)gz[(size_t)s * kRnnThreads + tid] : C) * 4u;
         }
     }
-    // unit state of this thread (threads 0 .. nu-1 each own one hidden unit) and the lanes
-    // that hold the slices of its four rows
+    // unit state of this thread (threads 0 .. nu-1 each own one unit) and the lanes that hold
+    // the slices of its rows
     const bool owner = tid < nu;
     // this lane's place in its row's segment of lanes
     const uint32_t ltab = ((const uint32_t *)(A.img + wg.off_rows))[tid];
     const uint32_t seg_pos = ltab & 31u, row_slot = ltab >> 8;
     const bool seg_last = (ltab & 32u) != 0;
     const uint32_t unit = wg.u0 + tid;
-    const bool lstm = A.cell == CSB_CELL_LSTM;
     // the last lane of a row's segment ends up with the row sum: it adds the bias and applies
     // the gate's non-linearity at once (LSTM rows i,f,o: sigmoid, g: tanh; GRU rows r,z:
-    // sigmoid, the two halves of n: none yet)
+    // sigmoid, the two halves of n: none yet; a linear stage: the bare sum)
     float row_bias = 0.0f;
     uint32_t act = 0;                       // 0 none, 1 sigmoid, 2 tanh
-    if (seg_last) {
+    if (seg_last && !linear) {
         const uint32_t g = row_slot / nu, ui = row_slot - g * nu;
-        const float *b = A.bias[l];
+        const float *b = A.bias[real];
         if (lstm) { act = g == 2 ? 2u : 1u; if (b) row_bias = b[g * H + wg.u0 + ui]; }
         else { act = g < 2 ? 1u : 0u; if (b && g < 3) row_bias = b[g * H + wg.u0 + ui]; }
     }
     float c_state = 0.0f, h_state = 0.0f;
     if (owner) {
-        if (A.c0 && lstm) c_state = A.c0[(size_t)l * H + unit];
-        if (A.h0) h_state = A.h0[(size_t)l * H + unit];
+        if (A.c0 && lstm) c_state = A.c0[(size_t)real * H + unit];
+        if (A.h0 && (flags & kStageIsState)) h_state = A.h0[(size_t)real * wg.width + unit];
     }
     if (tid == 0) z[C] = 0.0f;
     // rows without survivors have no lane: their entry keeps the activation of the bare bias
     for (uint32_t i = tid; i < 4 * nu; i += kRnnThreads) {
         const uint32_t g = i / nu, ui = i - g * nu;
-        const float *b = A.bias[l];
+        const float *b = linear ? nullptr : A.bias[real];
         float v = 0.0f;
         if (lstm) { if (b) v = b[g * H + wg.u0 + ui]; v = g == 2 ? fast_tanh(v) : fast_sigmoid(v); }
-        else { if (b && g < 3) v = b[g * H + wg.u0 + ui]; if (g < 2) v = fast_sigmoid(v); }
+        else if (!linear) { if (b && g < 3) v = b[g * H + wg.u0 + ui]; if (g < 2) v = fast_sigmoid(v); }
         arow[i] = v;
     }
-    // Exchange words: every workgroup publishes the h_t of its units into a region of its own,
-    // [t][unit of the workgroup]; the regions of different workgroups lie T * nu words apart,
-    // which spreads the polling over the memory channels.
+    // Exchange words: every workgroup publishes the outputs of its units into a region of its
+    // own, [t][unit of the workgroup]; the regions of different workgroups lie T * nu words
+    // apart, which spreads the polling over the memory channels.
     unsigned long long *pub = A.seq + (size_t)T * wg.upre + tid;     // + t * nu
     const uint16_t *unit_wg = (const uint16_t *)(A.img + A.off_unit_wg);
     // z entries are staged from the top of the workgroup: thread tid handles entries
-    // zt and zt + 1024.  The unit owners (low tids) publish h_t with global stores, and a
+    // zt and zt + 1024.  The unit owners (low tids) publish with global stores, and a
     // wavefront's loads return behind its own earlier stores; this way the wavefronts that
     // fetch the next input frame are not the ones that store.
     const uint32_t zt = kRnnThreads - 1 - tid;
     // where this thread's (at most two) polled z entries come from: word address at t = 0 and
-    // words per step of the source workgroup
+    // words per step of the source workgroup.  Entries below n_in come from the stage below at
+    // the same step (or from x), the others from the recurrent source one step back.
     const unsigned long long *src[2] = {nullptr, nullptr};
     uint32_t src_stride[2] = {0, 0};
     bool src_local[2] = {false, false};
 #pragma unroll
     for (int rep = 0; rep < 2; ++rep) {
         const uint32_t e = zt + rep * kRnnThreads;
-        if (e < C && e >= n_in && e - n_in - wg.u0 < nu) src_local[rep] = true;   // own unit: no poll
-        if (e < C && (e >= n_in || l > 0)) {
-            const uint32_t ls = e < n_in ? l - 1 : l, us = e < n_in ? e : e - n_in;
-            const RnnWgRec *q = (const RnnWgRec *)A.img + unit_wg[(size_t)ls * H + us];
+        if (e < C && e >= n_in && own_rec && e - n_in - wg.u0 < nu) src_local[rep] = true;   // own unit: no poll
+        if (e < C && (e >= n_in || !from_x)) {
+            const uint32_t tab = e < n_in ? wg.below : wg.rec, us = e < n_in ? e : e - n_in;
+            const RnnWgRec *q = (const RnnWgRec *)A.img + unit_wg[(size_t)tab + us];
             src[rep] = A.seq + (size_t)T * q->upre + (us - q->u0);
             src_stride[rep] = q->nu;
         }
     }
     // first frame of the input sequence (layer 0 reads x directly, one step ahead)
     float xnext0 = 0.0f, xnext1 = 0.0f;
-    if (l == 0 && T > 0) {
+    if (from_x && T > 0) {
         if (zt < n_in) xnext0 = A.x[zt];
         if (zt + kRnnThreads < n_in) xnext1 = A.x[zt + kRnnThreads];
     }
@@ -479,7 +550,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         // that samples it long after wastes the difference.  Steps repeat with the same timing,
         // so each wavefront waits `delay` sleeps before its first poll and tunes it: three more
         // after a step in which a first poll came back stale, one less after 16 clean steps.
-        if (polls && (t > 0 || l > 0))
+        if (polls && (t > 0 || !from_x))
             for (uint32_t d = 0; d < delay; ++d) __builtin_amdgcn_s_sleep(1);
         bool retried = false;
 #pragma unroll
@@ -488,12 +559,12 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
             if (e < C) {
                 float v;
                 if (e < n_in) {
-                    if (l == 0) v = rep == 0 ? xnext0 : xnext1;
+                    if (from_x) v = rep == 0 ? xnext0 : xnext1;
                     else v = poll_word(src[rep] + (size_t)t * src_stride[rep], tag_now, retried, npolls);
                 } else {
                     const uint32_t u = e - n_in;
-                    if (t == 0) v = A.h0 ? A.h0[(size_t)l * H + u] : 0.0f;
-                    else if (u - wg.u0 < nu) continue;      // own unit: its owner already wrote z
+                    if (t == 0) v = A.h0 ? A.h0[(size_t)real * wg.rec_width + u] : 0.0f;
+                    else if (own_rec && u - wg.u0 < nu) continue;      // own unit: its owner already wrote z
                     else v = poll_word(src[rep] + (size_t)(t - 1) * src_stride[rep], tag_prev, retried, npolls);
                 }
                 z[e] = v;
@@ -504,7 +575,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
             if (__ballot(retried) != 0ull) { delay += 3; streak = 0; }
             else if (++streak >= 16) { delay -= delay > 0 ? 1u : 0u; streak = 0; }
         }
-        if (l == 0 && t + 1 < T) {
+        if (from_x && t + 1 < T) {
             if (zt < n_in) xnext0 = A.x[(size_t)(t + 1) * A.I + zt];
             if (zt + kRnnThreads < n_in) xnext1 = A.x[(size_t)(t + 1) * A.I + zt + kRnnThreads];
         }
@@ -545,7 +616,9 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         if (owner) {
             const float a0 = arow[tid], a1 = arow[nu + tid], a2 = arow[2 * nu + tid], a3 = arow[3 * nu + tid];
             float hn;
-            if (lstm) {                                  // activated rows i, f, g, o
+            if (linear) {                                // the row sum is the output
+                hn = a0;
+            } else if (lstm) {                           // activated rows i, f, g, o
                 const float cn = a1 * c_state + a0 * a2;
                 hn = a3 * fast_tanh(cn);
                 c_state = cn;
@@ -554,10 +627,10 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
                 hn = (1.0f - a1) * n + a1 * h_state;
             }
             h_state = hn;
-            z[n_in + unit] = hn;        // next step's input, read only after the next barrier
+            if (own_rec) z[n_in + unit] = hn;        // next step's input, read only after the next barrier
             const unsigned long long pk = ((unsigned long long)tag_now << 32) | (unsigned long long)__float_as_uint(hn);
             __hip_atomic_store(pub + (size_t)t * nu, pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (A.hseq && l == A.L - 1) A.hseq[(size_t)t * H + unit] = hn;
+            if (A.hseq && (flags & kStageIsSeq)) A.hseq[(size_t)t * wg.width + unit] = hn;
         }
         if (dbg) { c1_ = __builtin_readcyclecounter(); ph3 += c1_ - c0_; }
     }
@@ -565,8 +638,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     if (A.dbg && blockIdx.x == 0 && (tid & 63u) == 0) A.dbg[8 + (tid >> 6)] = wave_arrive;
     if (A.dbg && blockIdx.x == 0 && tid == 512) { A.dbg[5] = npolls; A.dbg[6] = delay; }
     if (owner) {
-        A.hT[(size_t)l * H + unit] = h_state;
-        if (A.cT && lstm) A.cT[(size_t)l * H + unit] = c_state;
+        if (flags & kStageIsState) A.hT[(size_t)real * wg.width + unit] = h_state;
+        if (A.cT && lstm) A.cT[(size_t)real * H + unit] = c_state;
     }
 }
 
@@ -725,7 +798,7 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     w.off_c = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     w.off_part = off; off = align256(off + part);
     w.off_biasptr = off; off = align256(off + (size_t)r->n_layers * sizeof(void *));
-    w.off_seq = off; off = align256(off + (size_t)r->n_layers * (size_t)std::max(T, 1) * r->hidden * 8);
+    w.off_seq = off; off = align256(off + (size_t)r->n_layers * (size_t)std::max(T, 1) * (size_t)(r->hidden + r->proj) * 8);
     if (batch > 1) {
         w.off_hint = off; off = align256(off + (size_t)r->n_layers * batch * HS * sizeof(float));
         w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
@@ -741,7 +814,7 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     const RnnWs wl = ws_layout(r, 1, T);
     const int L = r->n_layers, H = r->hidden;
     unsigned long long *seq = (unsigned long long *)((uint8_t *)d_ws + wl.off_seq);
-    const size_t words = (size_t)L * T * H;
+    const size_t words = r->plan.total_units * (size_t)T;
     // unique tags for this call's T steps; a workspace seen for the first time (or a new tag
     // generation) is cleared so that no stale word can carry a tag of this call
     uint32_t gen = 0;
@@ -757,7 +830,7 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     A.x = d_x; A.h0 = d_h0; A.c0 = d_c0;
     for (int l = 0; l < L && l < 8; ++l) A.bias[l] = r->d_bias[l];
     A.hseq = d_hseq; A.hT = d_hT; A.cT = d_cT; A.seq = seq;
-    A.T = (uint32_t)T; A.L = (uint32_t)L; A.H = (uint32_t)H; A.I = (uint32_t)r->input; A.cell = (uint32_t)r->cell;
+    A.T = (uint32_t)T; A.H = (uint32_t)H; A.I = (uint32_t)r->input;
     A.tag_base = tag_base;
     A.off_unit_wg = (uint32_t)r->plan.off_unit_wg;
     A.wg_stride = 1;
@@ -765,8 +838,7 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     if (const char *e = getenv("CSB_RNN_POLL_DELAY")) A.poll_delay = (uint32_t)std::max(0, atoi(e));
     if (getenv("CSB_RNN_DEBUG")) A.dbg = (unsigned long long *)((uint8_t *)d_ws + wl.total - 512);
     if (const char *e = getenv("CSB_RNN_WG_STRIDE")) A.wg_stride = (uint32_t)std::max(1, atoi(e));
-    size_t cmax = 0;
-    for (int l = 0; l < L; ++l) cmax = std::max<size_t>(cmax, (size_t)(l == 0 ? r->input : H) + H);
+    const size_t cmax = r->plan.cmax;
     const size_t lds = (((cmax + 1 + 63) & ~(size_t)63) + kRnnThreads) * sizeof(float);
     auto go = [&](auto kern) -> hipError_t {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -855,7 +927,8 @@ extern "C" int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hid
             r->Wp.push_back(Wp[l]);
             r->d_bias.push_back(d_bias ? d_bias[l] : nullptr);
         }
-        *out = r;                                  // no resident layout for this cell: plan stays invalid
+        if (n_layers <= 8) build_resident_plan(r);     // stays invalid if the model does not fit on chip
+        *out = r;
         return CSB_OK;
     } catch (const std::bad_alloc &) {
         set_error("csb_rnn_create_lstmp: out of host memory");

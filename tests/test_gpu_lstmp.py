@@ -20,25 +20,36 @@ def say(msg):
     sys.stdout.flush()
 
 
-def build(wl):
+def build(wl, resident=False):
+    """resident=True: upload the on-chip layout (one launch for the whole sequence, batch 1);
+    else upload the matrices (mat-vec / mat-mat launches per step)."""
     Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
     Ps = [CsbMatrix(m.A, m.br, m.bc) for m in wl.Wp]
     bias = [torch.from_numpy(b).cuda() for b in wl.bias]
     rnn = CsbRnn(CELL_LSTMP, wl.input, wl.hidden, Ws, bias, proj=wl.proj, Wp=Ps)
-    for m in Ws + Ps:
-        m.validate()
-        m.upload()
+    if resident:
+        assert rnn.stats()["resident"] == 1
+        rnn.upload()
+    else:
+        for m in Ws + Ps:
+            m.validate()
+            m.upload()
     return rnn
 
 
-def run_case(wl, h0=None, c0=None, tag=""):
+def run_case(wl, h0=None, c0=None, tag="", resident=None):
     T, B, _ = wl.x.shape
     L = len(wl.W)
-    say(f"[lstmp] {tag} L={L} I={wl.input} H={wl.hidden} P={wl.proj} T={T} B={B}")
+    if resident is None:                      # both device paths where both apply
+        out = run_case(wl, h0, c0, tag, resident=False)
+        if B == 1:
+            out = run_case(wl, h0, c0, tag, resident=True)
+        return out
+    say(f"[lstmp] {tag} L={L} I={wl.input} H={wl.hidden} P={wl.proj} T={T} B={B} resident={resident}")
     W = [m.A for m in wl.W]
     Wp = [m.A for m in wl.Wp]
     rseq, rhT, rcT = oracle.lstmp_forward(W, Wp, wl.bias, wl.x, wl.input, wl.hidden, wl.proj, h0=h0, c0=c0)
-    rnn = build(wl)
+    rnn = build(wl, resident)
     h0d = None if h0 is None else torch.from_numpy(h0.astype(np.float32)).cuda()
     c0d = None if c0 is None else torch.from_numpy(c0.astype(np.float32)).cuda()
     hseq, hT, cT = rnn.forward(torch.from_numpy(wl.x).cuda(), h0d, c0d)
@@ -53,7 +64,8 @@ def run_case(wl, h0=None, c0=None, tag=""):
 
 
 @pytest.mark.parametrize("L,I,H,P,T,B,block", [(1, 5, 8, 3, 6, 1, 4), (2, 12, 16, 8, 9, 3, 8), (3, 7, 12, 11, 4, 2, 4),
-                                              (1, 40, 100, 37, 12, 1, 32), (2, 30, 96, 48, 7, 19, 16), (2, 9, 8, 16, 5, 2, 8)])
+                                              (1, 40, 100, 37, 12, 1, 32), (2, 30, 96, 48, 7, 19, 16), (2, 9, 8, 16, 5, 2, 8),
+                                              (2, 33, 300, 130, 9, 1, 32), (3, 16, 64, 24, 20, 1, 16)])
 def test_lstmp_small(L, I, H, P, T, B, block):
     wl = csb_inputs.make_lstmp(40 + L + I, L, I, H, P, block, 3.0, T, B, sigma=0.3)
     rng = np.random.default_rng(1)
@@ -68,6 +80,8 @@ def test_lstmp_speech_model_shape_batch1():
     512-wide projection, pruned 13x in 32 x 32 blocks; batch 1, T = 20."""
     wl = csb_inputs.make_lstmp(0, 2, 153, 1024, 512, 32, 13.0, 20, 1)
     run_case(wl, tag="sr1-shape")
+    wl = csb_inputs.make_lstmp(0, 2, 153, 1024, 512, 32, 13.0, 100, 1)
+    run_case(wl, tag="sr1-shape-T100", resident=True)
 
 
 def test_lstmp_speech_model_shape_batched_sampled():
