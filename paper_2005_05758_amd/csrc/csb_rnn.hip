@@ -32,6 +32,13 @@ constexpr int kRnnThreads = 1024;      // lanes per workgroup of the resident ke
 constexpr int kRnnSlotsMax = 48;       // weights one lane keeps in registers
 constexpr int kRnnMaxWgs = 240;        // all workgroups must be co-resident (256 CUs)
 constexpr uint32_t kPollLimit = 1u << 24;
+// Per-phase shader clocks of the resident kernel (a development aid): compiled in only on
+// request, so that the time loop of the shipped kernel carries none of it.
+#ifdef CSB_RNN_PHASE_CLOCKS
+constexpr bool kPhaseClocks = true;
+#else
+constexpr bool kPhaseClocks = false;
+#endif
 
 // The resident kernel works on a stack of stages.  An LSTM / GRU layer is one stage (its
 // units' gate rows); an LSTMP layer is two: the gate stage, whose output m_t is not state, and
@@ -425,10 +432,12 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// Value of the lane n places down in the same 16-lane row (0 if there is none).
+// Value of the lane N places down in the same 16-lane row, kept where `mask` is all ones and
+// dropped (0) where it is zero or there is no such lane.
 template <int N>
-__device__ __forceinline__ float dpp_shr(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x110 + N, 0xf, 0xf, true));
+__device__ __forceinline__ float masked_shr(float v, uint32_t mask) {
+    const uint32_t t = (uint32_t)__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x110 + N, 0xf, 0xf, true);
+    return __uint_as_float(t & mask);
 }
 
 // Poll a tagged word until it carries `tag`; bounded, returns NaN if the bound is hit.
@@ -444,16 +453,21 @@ __device__ __forceinline__ float poll_word(const unsigned long long *p, uint32_t
     return (uint32_t)(v >> 32) == tag ? __uint_as_float((uint32_t)v) : __builtin_nanf("");
 }
 
-template <int SMAX>
+// PLAIN: every stage is an LSTM / GRU layer (its own recurrent source, its output the layer's
+// state), so the stage-kind tests of the time loop fold away at compile time.
+template <int SMAX, bool PLAIN>
 __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs A) {
     extern __shared__ float lds[];
     const uint32_t tid = threadIdx.x;
     if (blockIdx.x % A.wg_stride != 0) return;
     const RnnWgRec wg = ((const RnnWgRec *)A.img)[blockIdx.x / A.wg_stride];
     const uint32_t H = A.H, T = A.T, nu = wg.nu, n_in = wg.n_in, C = wg.C, S = wg.S;
-    const uint32_t kind = wg.kind & 0xffu, real = (wg.kind >> 8) & 0xffu, flags = wg.kind >> 16;
-    const bool lstm = kind == kStageLstm, linear = kind == kStageLinear;
-    const bool from_x = wg.below == kNoStage, own_rec = (flags & kStageOwnRec) != 0;
+    // (the record is the same for every lane: keep what steers branches in scalar registers)
+    const uint32_t kword = __builtin_amdgcn_readfirstlane(wg.kind);
+    const uint32_t kind = kword & 0xffu, real = (kword >> 8) & 0xffu, flags = kword >> 16;
+    const bool lstm = kind == kStageLstm, linear = !PLAIN && kind == kStageLinear;
+    const bool from_x = __builtin_amdgcn_readfirstlane(wg.below) == kNoStage;
+    const bool own_rec = PLAIN || (flags & kStageOwnRec) != 0, is_state = PLAIN || (flags & kStageIsState) != 0;
     float *z = lds;                       // [C + 1], z[C] = 0
     float *arow = lds + ((C + 1 + 63) & ~63u);   // [4 * nu] row sums
     // weights and LDS addresses of their inputs: registers for the whole sequence
@@ -488,10 +502,18 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         if (lstm) { act = g == 2 ? 2u : 1u; if (b) row_bias = b[g * H + wg.u0 + ui]; }
         else { act = g < 2 ? 1u : 0u; if (b && g < 3) row_bias = b[g * H + wg.u0 + ui]; }
     }
+    const float act_k = act == 2 ? -2.0f * 1.44269504088896341f : -1.44269504088896341f;
+    const float act_a = act == 2 ? 2.0f : 1.0f, act_b = act == 2 ? -1.0f : 0.0f;
+    // row-sum scan: which lanes add the value 1, 2, 4, 8 lanes down / the total of the row before
+    // (kept as bit masks in vector registers: one AND per level instead of a compare-select)
+    uint32_t scan_m1 = (seg_pos & 15u) >= 1 ? ~0u : 0u, scan_m2 = (seg_pos & 15u) >= 2 ? ~0u : 0u;
+    uint32_t scan_m4 = (seg_pos & 15u) >= 4 ? ~0u : 0u, scan_m8 = (seg_pos & 15u) >= 8 ? ~0u : 0u;
+    uint32_t scan_mb = seg_pos >= 16 ? ~0u : 0u;
+    asm volatile("" : "+v"(scan_m1), "+v"(scan_m2), "+v"(scan_m4), "+v"(scan_m8), "+v"(scan_mb));
     float c_state = 0.0f, h_state = 0.0f;
     if (owner) {
         if (A.c0 && lstm) c_state = A.c0[(size_t)real * H + unit];
-        if (A.h0 && (flags & kStageIsState)) h_state = A.h0[(size_t)real * wg.width + unit];
+        if (A.h0 && is_state) h_state = A.h0[(size_t)real * wg.width + unit];
     }
     if (tid == 0) z[C] = 0.0f;
     // rows without survivors have no lane: their entry keeps the activation of the bare bias
@@ -541,7 +563,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     uint32_t delay = A.poll_delay, streak = 0, npolls = 0;
     unsigned long long wave_arrive = 0, after_b = 0;
     unsigned long long ph0 = 0, ph1 = 0, ph2 = 0, ph3 = 0, c0_ = 0, c1_ = 0;
-    const bool dbg = A.dbg != nullptr && blockIdx.x == 0 && tid == 0;
+    const bool dbg = kPhaseClocks && A.dbg != nullptr && blockIdx.x == 0 && tid == 0;
     for (uint32_t t = 0; t < T; ++t) {
         const uint32_t tag_now = A.tag_base + t, tag_prev = A.tag_base + t - 1;
         if (dbg) c0_ = __builtin_readcyclecounter();
@@ -570,7 +592,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
                 z[e] = v;
             }
         }
-        if (A.dbg && blockIdx.x == 0 && (tid & 63u) == 0 && t > 0) wave_arrive += __builtin_readcyclecounter() - after_b;
+        if (kPhaseClocks && A.dbg && blockIdx.x == 0 && (tid & 63u) == 0 && t > 0) wave_arrive += __builtin_readcyclecounter() - after_b;
         if (polls) {
             if (__ballot(retried) != 0ull) { delay += 3; streak = 0; }
             else if (++streak >= 16) { delay -= delay > 0 ? 1u : 0u; streak = 0; }
@@ -594,27 +616,31 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         // 16 lanes lies inside one 16-lane row; a longer one fills an even row and continues at
         // the start of the odd row after it, which then adds the even row's total.
         {
-            const uint32_t rp = seg_pos & 15u;
-            { const float t1 = dpp_shr<1>(acc); acc += rp >= 1 ? t1 : 0.0f; }
-            { const float t2 = dpp_shr<2>(acc); acc += rp >= 2 ? t2 : 0.0f; }
-            { const float t4 = dpp_shr<4>(acc); acc += rp >= 4 ? t4 : 0.0f; }
-            { const float t8 = dpp_shr<8>(acc); acc += rp >= 8 ? t8 : 0.0f; }
+            acc += masked_shr<1>(acc, scan_m1);
+            acc += masked_shr<2>(acc, scan_m2);
+            acc += masked_shr<4>(acc, scan_m4);
+            acc += masked_shr<8>(acc, scan_m8);
             // lane 15 of rows 0 and 2 to every lane of rows 1 and 3
-            const float tb = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(acc), 0x142, 0xa, 0xf, false));
-            acc += seg_pos >= 16 ? tb : 0.0f;
+            const uint32_t tb = (uint32_t)__builtin_amdgcn_update_dpp(0, __float_as_int(acc), 0x142, 0xa, 0xf, false);
+            acc += __uint_as_float(tb & scan_mb);
         }
         {
+            // one exponential and one reciprocal per lane: sigmoid(v) = 1 / (1 + 2^(-v log2 e)),
+            // tanh(v) = 2 sigmoid(2v) - 1; the lane's constants select between them
             const float pre = acc + row_bias;
-            const float sg = fast_sigmoid(act == 2 ? 2.0f * pre : pre);      // one exponential serves both
-            const float th = fabsf(pre) < 0.1f ? tanh_small(pre) : fmaf(2.0f, sg, -1.0f);
-            if (seg_last) arow[row_slot] = act == 0 ? pre : (act == 1 ? sg : th);
+            const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(pre * act_k));
+            const float out = act == 0 ? pre : fmaf(act_a, sg, act_b);
+            if (seg_last) arow[row_slot] = out;
         }
         lds_barrier();
-        if (A.dbg && blockIdx.x == 0 && (tid & 63u) == 0) after_b = __builtin_readcyclecounter();
+        if (kPhaseClocks && A.dbg && blockIdx.x == 0 && (tid & 63u) == 0) after_b = __builtin_readcyclecounter();
         if (dbg) { c1_ = __builtin_readcyclecounter(); ph1 += c1_ - c0_; c0_ = c1_; }
         // ---- gates and state of the units this workgroup owns --------------------------------
         if (owner) {
             const float a0 = arow[tid], a1 = arow[nu + tid], a2 = arow[2 * nu + tid], a3 = arow[3 * nu + tid];
+            // all four reads are issued here, before the branch on the stage kind (left to
+            // itself the compiler sinks three of them into the branches, one latency later)
+            if constexpr (!PLAIN) asm volatile("" ::"v"(a0), "v"(a1), "v"(a2), "v"(a3));
             float hn;
             if (linear) {                                // the row sum is the output
                 hn = a0;
@@ -635,10 +661,10 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         if (dbg) { c1_ = __builtin_readcyclecounter(); ph3 += c1_ - c0_; }
     }
     if (dbg) { A.dbg[0] = ph0; A.dbg[1] = ph1; A.dbg[2] = ph2; A.dbg[3] = ph3; }
-    if (A.dbg && blockIdx.x == 0 && (tid & 63u) == 0) A.dbg[8 + (tid >> 6)] = wave_arrive;
-    if (A.dbg && blockIdx.x == 0 && tid == 512) { A.dbg[5] = npolls; A.dbg[6] = delay; }
+    if (kPhaseClocks && A.dbg && blockIdx.x == 0 && (tid & 63u) == 0) A.dbg[8 + (tid >> 6)] = wave_arrive;
+    if (kPhaseClocks && A.dbg && blockIdx.x == 0 && tid == 512) { A.dbg[5] = npolls; A.dbg[6] = delay; }
     if (owner) {
-        if (flags & kStageIsState) A.hT[(size_t)real * wg.width + unit] = h_state;
+        if (is_state) A.hT[(size_t)real * wg.width + unit] = h_state;
         if (A.cT && lstm) A.cT[(size_t)real * H + unit] = c_state;
     }
 }
@@ -836,7 +862,7 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     A.wg_stride = 1;
     A.poll_delay = r->plan.n_wgs > 1 ? 8u : 0u;   // fewer polls in flight while h_t cannot have arrived yet
     if (const char *e = getenv("CSB_RNN_POLL_DELAY")) A.poll_delay = (uint32_t)std::max(0, atoi(e));
-    if (getenv("CSB_RNN_DEBUG")) A.dbg = (unsigned long long *)((uint8_t *)d_ws + wl.total - 512);
+    if (kPhaseClocks && getenv("CSB_RNN_DEBUG")) A.dbg = (unsigned long long *)((uint8_t *)d_ws + wl.total - 512);
     if (const char *e = getenv("CSB_RNN_WG_STRIDE")) A.wg_stride = (uint32_t)std::max(1, atoi(e));
     const size_t cmax = r->plan.cmax;
     const size_t lds = (((cmax + 1 + 63) & ~(size_t)63) + kRnnThreads) * sizeof(float);
@@ -847,14 +873,26 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
         return hipGetLastError();
     };
     hipError_t e;
-    if (r->plan.smax <= 4) e = go(rnn_resident_kernel<4>);
-    else if (r->plan.smax <= 8) e = go(rnn_resident_kernel<8>);
-    else if (r->plan.smax <= 12) e = go(rnn_resident_kernel<12>);
-    else if (r->plan.smax <= 16) e = go(rnn_resident_kernel<16>);
-    else if (r->plan.smax <= 24) e = go(rnn_resident_kernel<24>);
-    else if (r->plan.smax <= 32) e = go(rnn_resident_kernel<32>);
-    else if (r->plan.smax <= 40) e = go(rnn_resident_kernel<40>);
-    else e = go(rnn_resident_kernel<kRnnSlotsMax>);
+    const int smax = r->plan.smax;
+    if (r->cell != CSB_CELL_LSTMP) {
+        if (smax <= 4) e = go(rnn_resident_kernel<4, true>);
+        else if (smax <= 8) e = go(rnn_resident_kernel<8, true>);
+        else if (smax <= 12) e = go(rnn_resident_kernel<12, true>);
+        else if (smax <= 16) e = go(rnn_resident_kernel<16, true>);
+        else if (smax <= 24) e = go(rnn_resident_kernel<24, true>);
+        else if (smax <= 32) e = go(rnn_resident_kernel<32, true>);
+        else if (smax <= 40) e = go(rnn_resident_kernel<40, true>);
+        else e = go(rnn_resident_kernel<kRnnSlotsMax, true>);
+    } else {
+        if (smax <= 4) e = go(rnn_resident_kernel<4, false>);
+        else if (smax <= 8) e = go(rnn_resident_kernel<8, false>);
+        else if (smax <= 12) e = go(rnn_resident_kernel<12, false>);
+        else if (smax <= 16) e = go(rnn_resident_kernel<16, false>);
+        else if (smax <= 24) e = go(rnn_resident_kernel<24, false>);
+        else if (smax <= 32) e = go(rnn_resident_kernel<32, false>);
+        else if (smax <= 40) e = go(rnn_resident_kernel<40, false>);
+        else e = go(rnn_resident_kernel<kRnnSlotsMax, false>);
+    }
     if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
 }
