@@ -442,12 +442,13 @@ __device__ __forceinline__ float masked_shr(float v, uint32_t mask) {
 
 // Poll a tagged word until it carries `tag`; bounded, returns NaN if the bound is hit.
 // `retried` is set if the first load did not already carry the tag.
-__device__ __forceinline__ float poll_word(const unsigned long long *p, uint32_t tag, bool &retried, uint32_t &npolls) {
+__device__ __forceinline__ float poll_word(const unsigned long long *word, uint32_t tag, bool &retried) {
+    // (the words live in device memory: say so, or the loads are issued as generic ones)
+    const __attribute__((address_space(1))) unsigned long long *p =
+        (const __attribute__((address_space(1))) unsigned long long *)word;
     unsigned long long v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    ++npolls;
     for (uint32_t spin = 0; (uint32_t)(v >> 32) != tag && spin < kPollLimit; ++spin) {
         retried = true;
-        ++npolls;
         v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     return (uint32_t)(v >> 32) == tag ? __uint_as_float((uint32_t)v) : __builtin_nanf("");
@@ -535,71 +536,68 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     // wavefront's loads return behind its own earlier stores; this way the wavefronts that
     // fetch the next input frame are not the ones that store.
     const uint32_t zt = kRnnThreads - 1 - tid;
-    // where this thread's (at most two) polled z entries come from: word address at t = 0 and
-    // words per step of the source workgroup.  Entries below n_in come from the stage below at
-    // the same step (or from x), the others from the recurrent source one step back.
-    const unsigned long long *src[2] = {nullptr, nullptr};
-    uint32_t src_stride[2] = {0, 0};
-    bool src_local[2] = {false, false};
+    // This thread's (at most two) z entries.  An entry below n_in comes from the stage below
+    // at the same step (or from x), the others from the recurrent source one step back: they
+    // start from h0, and a unit of this workgroup is written by its owner, not polled.  A
+    // polled entry has the address of its word at step 0 (one step's stride back for a
+    // recurrent one, whose first poll is at step 1), the words per step of the workgroup that
+    // publishes it, and the tag it carries at step 0.
+    const unsigned long long *pp[2] = {nullptr, nullptr};
+    uint32_t pstride[2] = {0, 0}, ptmin[2] = {~0u, ~0u}, ptag[2] = {0, 0};
 #pragma unroll
     for (int rep = 0; rep < 2; ++rep) {
         const uint32_t e = zt + rep * kRnnThreads;
-        if (e < C && e >= n_in && own_rec && e - n_in - wg.u0 < nu) src_local[rep] = true;   // own unit: no poll
-        if (e < C && (e >= n_in || !from_x)) {
-            const uint32_t tab = e < n_in ? wg.below : wg.rec, us = e < n_in ? e : e - n_in;
-            const RnnWgRec *q = (const RnnWgRec *)A.img + unit_wg[(size_t)tab + us];
-            src[rep] = A.seq + (size_t)T * q->upre + (us - q->u0);
-            src_stride[rep] = q->nu;
-        }
+        if (e >= C) continue;
+        const bool rec = e >= n_in;
+        const uint32_t us = rec ? e - n_in : e;
+        if (rec) z[e] = A.h0 ? A.h0[(size_t)real * wg.rec_width + us] : 0.0f;
+        if (rec ? (own_rec && us - wg.u0 < nu) : from_x) continue;
+        const RnnWgRec *q = (const RnnWgRec *)A.img + unit_wg[(size_t)(rec ? wg.rec : wg.below) + us];
+        const uint32_t back = rec ? 1u : 0u;
+        pp[rep] = A.seq + ((size_t)T * q->upre + (us - q->u0)) - (size_t)back * q->nu;
+        pstride[rep] = q->nu;
+        ptmin[rep] = back;
+        ptag[rep] = A.tag_base - back;
     }
-    // first frame of the input sequence (layer 0 reads x directly, one step ahead)
+    // first frame of the input sequence (the first stage reads x directly, one step ahead)
+    const bool xl0 = from_x && zt < n_in, xl1 = from_x && zt + kRnnThreads < n_in;
     float xnext0 = 0.0f, xnext1 = 0.0f;
-    if (from_x && T > 0) {
-        if (zt < n_in) xnext0 = A.x[zt];
-        if (zt + kRnnThreads < n_in) xnext1 = A.x[zt + kRnnThreads];
+    if (T > 0) {
+        if (xl0) xnext0 = A.x[zt];
+        if (xl1) xnext1 = A.x[zt + kRnnThreads];
     }
     // does this wavefront poll at all (any lane with a remote source)?
-    const bool polls = __ballot((src[0] != nullptr && !(src_local[0])) || (src[1] != nullptr && !(src_local[1]))) != 0ull;
-    uint32_t delay = A.poll_delay, streak = 0, npolls = 0;
+    const bool polls = __ballot(ptmin[0] != ~0u || ptmin[1] != ~0u) != 0ull;
+    const bool two = C > kRnnThreads;           // second entries exist
+    uint32_t delay = A.poll_delay, streak = 0;
     unsigned long long wave_arrive = 0, after_b = 0;
     unsigned long long ph0 = 0, ph1 = 0, ph2 = 0, ph3 = 0, c0_ = 0, c1_ = 0;
     const bool dbg = kPhaseClocks && A.dbg != nullptr && blockIdx.x == 0 && tid == 0;
     for (uint32_t t = 0; t < T; ++t) {
-        const uint32_t tag_now = A.tag_base + t, tag_prev = A.tag_base + t - 1;
+        const uint32_t tag_now = A.tag_base + t;
         if (dbg) c0_ = __builtin_readcyclecounter();
         // ---- z = [layer input ; h_{t-1}] into LDS -------------------------------------------
         // A load that samples memory just before h arrives costs a whole extra round trip, one
         // that samples it long after wastes the difference.  Steps repeat with the same timing,
         // so each wavefront waits `delay` sleeps before its first poll and tunes it: three more
         // after a step in which a first poll came back stale, one less after 16 clean steps.
-        if (polls && (t > 0 || !from_x))
+        if (polls)
             for (uint32_t d = 0; d < delay; ++d) __builtin_amdgcn_s_sleep(1);
         bool retried = false;
-#pragma unroll
-        for (int rep = 0; rep < 2; ++rep) {
-            const uint32_t e = zt + rep * kRnnThreads;
-            if (e < C) {
-                float v;
-                if (e < n_in) {
-                    if (from_x) v = rep == 0 ? xnext0 : xnext1;
-                    else v = poll_word(src[rep] + (size_t)t * src_stride[rep], tag_now, retried, npolls);
-                } else {
-                    const uint32_t u = e - n_in;
-                    if (t == 0) v = A.h0 ? A.h0[(size_t)real * wg.rec_width + u] : 0.0f;
-                    else if (own_rec && u - wg.u0 < nu) continue;      // own unit: its owner already wrote z
-                    else v = poll_word(src[rep] + (size_t)(t - 1) * src_stride[rep], tag_prev, retried, npolls);
-                }
-                z[e] = v;
-            }
-        }
+        if (t >= ptmin[0]) z[zt] = poll_word(pp[0] + (size_t)t * pstride[0], ptag[0] + t, retried);
+        if (two && t >= ptmin[1]) z[zt + kRnnThreads] = poll_word(pp[1] + (size_t)t * pstride[1], ptag[1] + t, retried);
         if (kPhaseClocks && A.dbg && blockIdx.x == 0 && (tid & 63u) == 0 && t > 0) wave_arrive += __builtin_readcyclecounter() - after_b;
         if (polls) {
             if (__ballot(retried) != 0ull) { delay += 3; streak = 0; }
             else if (++streak >= 16) { delay -= delay > 0 ? 1u : 0u; streak = 0; }
         }
-        if (from_x && t + 1 < T) {
-            if (zt < n_in) xnext0 = A.x[(size_t)(t + 1) * A.I + zt];
-            if (zt + kRnnThreads < n_in) xnext1 = A.x[(size_t)(t + 1) * A.I + zt + kRnnThreads];
+        if (from_x) {
+            if (xl0) z[zt] = xnext0;
+            if (xl1) z[zt + kRnnThreads] = xnext1;
+            if (t + 1 < T) {
+                if (xl0) xnext0 = A.x[(size_t)(t + 1) * A.I + zt];
+                if (xl1) xnext1 = A.x[(size_t)(t + 1) * A.I + zt + kRnnThreads];
+            }
         }
         lds_barrier();
         if (dbg) { c1_ = __builtin_readcyclecounter(); ph0 += c1_ - c0_; c0_ = c1_; }
@@ -662,7 +660,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     }
     if (dbg) { A.dbg[0] = ph0; A.dbg[1] = ph1; A.dbg[2] = ph2; A.dbg[3] = ph3; }
     if (kPhaseClocks && A.dbg && blockIdx.x == 0 && (tid & 63u) == 0) A.dbg[8 + (tid >> 6)] = wave_arrive;
-    if (kPhaseClocks && A.dbg && blockIdx.x == 0 && tid == 512) { A.dbg[5] = npolls; A.dbg[6] = delay; }
+    if (kPhaseClocks && A.dbg && blockIdx.x == 0 && tid == 512) A.dbg[6] = delay;
     if (owner) {
         if (is_state) A.hT[(size_t)real * wg.width + unit] = h_state;
         if (A.cT && lstm) A.cT[(size_t)real * H + unit] = c_state;
