@@ -28,13 +28,15 @@ import numpy as np
 
 LSTM = 0
 GRU = 1
-GATES = {LSTM: 4, GRU: 3}
+LIGRU = 3          # Li-GRU (SR3 rows of Table 1): update gate and ReLU candidate
+GRU_RB = 4         # GRU with the reset gate applied before the recurrent product
+GATES = {LSTM: 4, GRU: 3, LIGRU: 2, GRU_RB: 3}
 
 
 @dataclass(frozen=True)
 class RnnConfig:
     name: str
-    cell: int                 # LSTM / GRU
+    cell: int                 # LSTM / GRU / LIGRU / GRU_RB
     n_layers: int
     input: int
     hidden: int

@@ -159,11 +159,12 @@ def rnn_forward(cell: int, W: List[np.ndarray], bias: Optional[List[Optional[np.
                 x: np.ndarray, input: int, hidden: int,
                 h0: Optional[np.ndarray] = None, c0: Optional[np.ndarray] = None,
                 want_hseq: bool = True) -> Tuple[Optional[np.ndarray], np.ndarray, np.ndarray]:
-    """Stacked LSTM (cell 0) / GRU (cell 1).  W[l]: dense (G*H) x (in_l + H) float32.
+    """Stacked LSTM (cell 0) / GRU (cell 1) / Li-GRU (cell 3) / GRU with the reset gate applied
+    before the recurrent product (cell 4).  W[l]: dense (G*H) x (in_l + H) float32.
     x: [T, B, I] float32.  Returns (hseq [T,B,H] or None, hT [L,B,H], cT [L,B,H]) float64."""
     lib = _load()
     L = len(W)
-    G = 4 if cell == 0 else 3
+    G = {0: 4, 1: 3, 3: 2, 4: 3}[cell]
     Ws = []
     for l, w in enumerate(W):
         w = np.ascontiguousarray(w, dtype=np.float32)

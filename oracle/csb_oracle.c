@@ -225,11 +225,18 @@ static double sigmoid(double v) { return 1.0 / (1.0 + exp(-v)); }
  *   cell 1, GRU : ax = W[:, :n_in] u, ah = W[:, n_in:] h, rows r,z,n;
  *                 r = sig(ax_r + ah_r + b_r), z = sig(ax_z + ah_z + b_z),
  *                 n = tanh(ax_n + b_n + r ah_n);  h' = (1 - z) n + z h
+ *   cell 3, Li-GRU (the cell of the paper's SR3 model, Table 1; as published by its authors,
+ *                 with the batch normalisation of the input part folded into W and b, which
+ *                 is what it is at inference): rows z, c;
+ *                 z = sig(a_z), cand = max(a_c, 0);  h' = z h + (1 - z) cand
+ *   cell 4, GRU with the reset gate applied BEFORE the recurrent product (the form of the
+ *                 work the paper cites for GRU): r, z as in cell 1, then
+ *                 n = tanh(ax_n + b_n + W[n rows, n_in:] (r * h));  h' = (1 - z) n + z h
  * W is (G*H) x (n_in + H) dense float32 with leading dimension n_in + H.
  */
 static void cell_step(int cell, int64_t n_in, int64_t H, const float *W, const float *bias,
                       const double *u, double *h, double *c, double *ax, double *ah) {
-    int64_t G = cell == 0 ? 4 : 3, ld = n_in + H;
+    int64_t G = cell == 0 ? 4 : (cell == 3 ? 2 : 3), ld = n_in + H;
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < G * H; ++i) {
         double sx = 0.0, sh = 0.0;
@@ -247,7 +254,7 @@ static void cell_step(int cell, int64_t n_in, int64_t H, const float *W, const f
             c[k] = cn;
             h[k] = sigmoid(ao) * tanh(cn);
         }
-    } else {
+    } else if (cell == 1) {
         for (int64_t k = 0; k < H; ++k) {
             double br = bias ? (double)bias[k] : 0.0;
             double bz = bias ? (double)bias[H + k] : 0.0;
@@ -258,6 +265,36 @@ static void cell_step(int cell, int64_t n_in, int64_t H, const float *W, const f
             /* all ah were formed from the old h before any h[k] is replaced */
             h[k] = (1.0 - z) * n + z * h[k];
         }
+    } else if (cell == 3) {
+        for (int64_t k = 0; k < H; ++k) {
+            double bz = bias ? (double)bias[k] : 0.0;
+            double bc = bias ? (double)bias[H + k] : 0.0;
+            double z = sigmoid(ax[k] + ah[k] + bz);
+            double pre = ax[H + k] + ah[H + k] + bc;
+            double cand = pre > 0.0 ? pre : 0.0;
+            h[k] = z * h[k] + (1.0 - z) * cand;
+        }
+    } else {
+        /* reset-before: the candidate's recurrent product is taken of q = r * h, so it can
+           only be formed once every r is known (ah's n rows, formed from h, are not used) */
+        double *q = (double *)malloc(sizeof(double) * (size_t)H);
+        for (int64_t k = 0; k < H; ++k) {
+            double br = bias ? (double)bias[k] : 0.0;
+            q[k] = sigmoid(ax[k] + ah[k] + br) * h[k];
+        }
+        for (int64_t k = 0; k < H; ++k) {
+            double s = 0.0;
+            for (int64_t j = 0; j < H; ++j) s += (double)W[(2 * H + k) * ld + n_in + j] * q[j];
+            ah[2 * H + k] = s;
+        }
+        for (int64_t k = 0; k < H; ++k) {
+            double bz = bias ? (double)bias[H + k] : 0.0;
+            double bn = bias ? (double)bias[2 * H + k] : 0.0;
+            double z = sigmoid(ax[H + k] + ah[H + k] + bz);
+            double n = tanh(ax[2 * H + k] + bn + ah[2 * H + k]);
+            h[k] = (1.0 - z) * n + z * h[k];
+        }
+        free(q);
     }
 }
 
@@ -265,15 +302,16 @@ static void cell_step(int cell, int64_t n_in, int64_t H, const float *W, const f
  * Stacked RNN over a sequence.  Layer l at time t reads the layer below at the same t.
  *   x    [T][B][I] float32        h0,c0 [L][B][H] float64 or NULL (zeros)
  *   hseq [T][B][H] float64 of the last layer, or NULL
- *   hT,cT [L][B][H] float64 (cT may be NULL; unused for GRU)
- * W[l] dense (G*H) x (in_l + H), in_0 = I, in_l = H; bias[l] of G*H or NULL.
+ *   hT,cT [L][B][H] float64 (cT may be NULL; only the LSTM has a c)
+ * W[l] dense (G*H) x (in_l + H), in_0 = I, in_l = H; bias[l] of G*H or NULL;
+ * G = 4 (LSTM), 3 (both GRU forms), 2 (Li-GRU).
  */
 int orc_rnn_forward(int cell, int32_t L, int64_t I, int64_t H,
                     const float *const *W, const float *const *bias,
                     const float *x, const double *h0, const double *c0,
                     double *hseq, double *hT, double *cT, int64_t T, int64_t B) {
-    if ((cell != 0 && cell != 1) || L <= 0 || I <= 0 || H <= 0 || T < 0 || B <= 0 || !W || !hT) return -1;
-    int64_t G = cell == 0 ? 4 : 3;
+    if ((cell != 0 && cell != 1 && cell != 3 && cell != 4) || L <= 0 || I <= 0 || H <= 0 || T < 0 || B <= 0 || !W || !hT) return -1;
+    int64_t G = cell == 0 ? 4 : (cell == 3 ? 2 : 3);
     int64_t maxin = I > H ? I : H;
     double *h = (double *)calloc((size_t)(L * B * H), sizeof(double));
     double *c = (double *)calloc((size_t)(L * B * H), sizeof(double));

@@ -202,3 +202,151 @@ def test_lstmp_zero_gate_weights_closed_form():
         ct = c0[0, 0] / 2.0 ** (t + 1)
         assert np.allclose(hseq[t, 0], Wp.astype(np.float64) @ (0.5 * np.tanh(ct)), rtol=0, atol=1e-14)
     assert np.allclose(cT[0, 0], c0[0, 0] / 2.0 ** T, rtol=0, atol=1e-15)
+
+
+# ---------------------------------------------------------------- Li-GRU (cell 3, SR3 rows of Table 1)
+
+def _torch_relu_rnn(Wc, bc, x, I, H, h0):
+    """torch.nn.RNN(nonlinearity='relu'), CPU, float64: h' = relu(W_ih x + W_hh h + b)."""
+    mod = torch.nn.RNN(I, H, num_layers=1, nonlinearity="relu", bias=True).double()
+    with torch.no_grad():
+        mod.weight_ih_l0.copy_(torch.from_numpy(Wc[:, :I].astype(np.float64)))
+        mod.weight_hh_l0.copy_(torch.from_numpy(Wc[:, I:].astype(np.float64)))
+        mod.bias_ih_l0.copy_(torch.from_numpy(bc.astype(np.float64)))
+        mod.bias_hh_l0.zero_()
+        out, hT = mod(torch.from_numpy(x.astype(np.float64)), torch.from_numpy(h0))
+    return out.numpy(), hT.numpy()
+
+
+def test_ligru_with_closed_update_gate_is_the_relu_rnn():
+    """Update gate forced to 0 (bias -800: the sigmoid is exactly 0 in float64): h' is the
+    candidate alone, which is torch's ReLU RNN -- pins the candidate rows, their operand
+    order, the ReLU and that (1 - z) multiplies the candidate."""
+    I, H, T, B = 6, 9, 7, 2
+    wl = _small(csb_inputs.LIGRU, 1, I, H, T, B, seed=5)
+    W = wl.W[0].A.copy()
+    W[:H] = 0.0
+    b = wl.bias[0].copy()
+    b[:H] = -800.0
+    h0 = np.random.default_rng(2).uniform(0.0, 0.5, (1, B, H))
+    hseq, hT, _ = oracle.rnn_forward(csb_inputs.LIGRU, [W], [b], wl.x, I, H, h0=h0)
+    rseq, rhT = _torch_relu_rnn(W[H:], b[H:], wl.x, I, H, h0)
+    assert np.abs(rseq).max() > 0.05                       # the ReLU is not idle
+    assert np.allclose(hseq, rseq, rtol=0, atol=1e-13) and np.allclose(hT, rhT, rtol=0, atol=1e-13)
+
+
+def test_ligru_closed_forms():
+    I, H, T = 4, 6, 5
+    x = np.random.default_rng(0).uniform(-1, 1, (T, 1, I)).astype(np.float32)
+    h0 = np.linspace(-1.0, 1.0, H).reshape(1, 1, H)
+    # W = 0, b = 0: z = 1/2, candidate 0 -> h halves every step
+    W0 = np.zeros((2 * H, I + H), np.float32)
+    _, hT, _ = oracle.rnn_forward(csb_inputs.LIGRU, [W0], None, x, I, H, h0=h0)
+    assert np.allclose(hT, h0 / 2.0 ** T, rtol=0, atol=1e-15)
+    # update gate open (bias +40: the sigmoid rounds to 1): h stays what it was
+    b = np.zeros(2 * H, np.float32); b[:H] = 40.0; b[H:] = 3.0
+    _, hT, _ = oracle.rnn_forward(csb_inputs.LIGRU, [W0], [b], x, I, H, h0=h0)
+    assert np.array_equal(hT, h0)
+    # W = 0, z = 1/2, candidate = relu(b_c): h_T = h0 / 2^T + relu(b_c) (1 - 2^-T); negative b_c: no push
+    b = np.zeros(2 * H, np.float32); b[H:] = np.linspace(-1.0, 1.5, H).astype(np.float32)
+    _, hT, _ = oracle.rnn_forward(csb_inputs.LIGRU, [W0], [b], x, I, H, h0=h0)
+    want = h0 / 2.0 ** T + np.maximum(b[H:].astype(np.float64), 0.0) * (1.0 - 2.0 ** -T)
+    assert np.allclose(hT, want, rtol=0, atol=1e-15)
+
+
+def test_ligru_scalar_unit_by_hand():
+    """One unit, one input: the recurrence written out with Python floats."""
+    import math
+    wzx, wzh, wcx, wch, bz, bc = 0.7, -1.3, 0.9, 0.5, 0.1, -0.2
+    W = np.array([[wzx, wzh], [wcx, wch]], np.float32)
+    b = np.array([bz, bc], np.float32)
+    x = np.array([0.5, -1.0, 2.0, 0.25], np.float32).reshape(4, 1, 1)
+    h = 0.3
+    hs = []
+    for t in range(4):
+        xt = float(x[t, 0, 0])
+        z = 1.0 / (1.0 + math.exp(-(float(W[0, 0]) * xt + float(W[0, 1]) * h + float(b[0]))))
+        cand = max(float(W[1, 0]) * xt + float(W[1, 1]) * h + float(b[1]), 0.0)
+        h = z * h + (1.0 - z) * cand
+        hs.append(h)
+    hseq, hT, _ = oracle.rnn_forward(csb_inputs.LIGRU, [W], [b], x, 1, 1, h0=np.array([[[0.3]]]))
+    assert np.allclose(hseq.ravel(), hs, rtol=0, atol=1e-15)
+
+
+def test_ligru_layers_compose_and_resume():
+    wl = _small(csb_inputs.LIGRU, 2, 5, 8, 6, 2, seed=8)
+    W = [m.A for m in wl.W]
+    hseq, hT, _ = oracle.rnn_forward(csb_inputs.LIGRU, W, wl.bias, wl.x, 5, 8)
+    s1, h1, _ = oracle.rnn_forward(csb_inputs.LIGRU, W[:1], wl.bias[:1], wl.x, 5, 8)
+    s2, h2, _ = oracle.rnn_forward(csb_inputs.LIGRU, W[1:], wl.bias[1:], s1.astype(np.float32), 8, 8)
+    # (the second layer reads float32 inputs through this interface: compare loosely)
+    assert np.allclose(hseq, s2, rtol=0, atol=1e-6)
+    a, ha, _ = oracle.rnn_forward(csb_inputs.LIGRU, W, wl.bias, wl.x[:4], 5, 8)
+    b, hb, _ = oracle.rnn_forward(csb_inputs.LIGRU, W, wl.bias, wl.x[4:], 5, 8, h0=ha)
+    assert np.array_equal(np.concatenate([a, b]), hseq) and np.array_equal(hb, hT)
+
+
+# ---------------------------------------------------------------- GRU, reset gate before the product (cell 4)
+
+def test_gru_rb_with_open_reset_gate_is_torch_gru():
+    """Reset gate forced to 1 (bias +40): r * (U h) = U (r * h), so both GRU forms agree and
+    torch.nn.GRU pins everything but the place of the reset gate."""
+    L, I, H, T, B = 2, 7, 10, 6, 2
+    wl = _small(csb_inputs.GRU_RB, L, I, H, T, B, seed=21)
+    W = [m.A.copy() for m in wl.W]
+    bias = [b.copy() for b in wl.bias]
+    for l in range(L):
+        W[l][:H] = 0.0
+        bias[l][:H] = 40.0
+    h0 = np.random.default_rng(3).uniform(-0.5, 0.5, (L, B, H))
+    hseq, hT, _ = oracle.rnn_forward(csb_inputs.GRU_RB, W, bias, wl.x, I, H, h0=h0)
+    rseq, rhT, _ = _torch_ref(1, W, bias, wl.x, I, H, h0)
+    assert np.allclose(hseq, rseq, rtol=0, atol=1e-12) and np.allclose(hT, rhT, rtol=0, atol=1e-12)
+
+
+def test_gru_rb_one_unit_is_torch_gru():
+    """With one hidden unit r (u h) = u (r h): the two forms coincide, reset gate live."""
+    I, H, T, B = 3, 1, 8, 2
+    rng = np.random.default_rng(4)
+    W = rng.normal(0, 1.0, (3, I + 1)).astype(np.float32)
+    b = rng.normal(0, 0.5, 3).astype(np.float32)
+    x = rng.uniform(-1, 1, (T, B, I)).astype(np.float32)
+    h0 = rng.uniform(-0.9, 0.9, (1, B, 1))
+    hseq, hT, _ = oracle.rnn_forward(csb_inputs.GRU_RB, [W], [b], x, I, H, h0=h0)
+    rseq, rhT, _ = _torch_ref(1, [W], [b], x, I, H, h0)
+    assert np.allclose(hseq, rseq, rtol=0, atol=1e-13)
+
+
+def test_gru_rb_place_of_the_reset_gate_by_brute_force():
+    """Tiny case in exact rational-free Python floats, straight from the definition:
+    n = tanh(Wn x + Un (r * h) + bn).  Also checks that it is NOT the reset-after result."""
+    import math
+    I, H, T = 2, 3, 4
+    rng = np.random.default_rng(6)
+    W = rng.normal(0, 0.8, (3 * H, I + H)).astype(np.float32)
+    b = rng.normal(0, 0.3, 3 * H).astype(np.float32)
+    x = rng.uniform(-1, 1, (T, 1, I)).astype(np.float32)
+    h = [0.4, -0.6, 0.2]
+    sig = lambda v: 1.0 / (1.0 + math.exp(-v))
+    Wd, bd = W.astype(np.float64), b.astype(np.float64)
+    for t in range(T):
+        xt = [float(v) for v in x[t, 0]]
+        pre = lambda row, hv: sum(Wd[row, j] * xt[j] for j in range(I)) + sum(Wd[row, I + j] * hv[j] for j in range(H)) + bd[row]
+        r = [sig(pre(k, h)) for k in range(H)]
+        z = [sig(pre(H + k, h)) for k in range(H)]
+        q = [r[k] * h[k] for k in range(H)]
+        n = [math.tanh(pre(2 * H + k, q)) for k in range(H)]
+        h = [(1.0 - z[k]) * n[k] + z[k] * h[k] for k in range(H)]
+    h0 = np.array([[[0.4, -0.6, 0.2]]])
+    _, hT, _ = oracle.rnn_forward(csb_inputs.GRU_RB, [W], [b], x, I, H, h0=h0)
+    assert np.allclose(hT.ravel(), h, rtol=0, atol=1e-14)
+    _, hA, _ = oracle.rnn_forward(csb_inputs.GRU, [W], [b], x, I, H, h0=h0)
+    assert np.abs(hA - hT).max() > 1e-3
+
+
+def test_gru_rb_zero_weights_closed_form():
+    I, H, T = 3, 5, 6
+    x = np.zeros((T, 1, I), np.float32)
+    h0 = np.linspace(-1, 1, H).reshape(1, 1, H)
+    _, hT, _ = oracle.rnn_forward(csb_inputs.GRU_RB, [np.zeros((3 * H, I + H), np.float32)], None, x, I, H, h0=h0)
+    assert np.allclose(hT, h0 / 2.0 ** T, rtol=0, atol=1e-15)
