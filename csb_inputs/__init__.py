@@ -225,6 +225,16 @@ def make_rnn(cfg: RnnConfig, T: Optional[int] = None, batch: Optional[int] = Non
     return RnnWorkload(cfg=cfg, W=Ws, bias=bias, x=x)
 
 
+def split_gru_rb(A: np.ndarray, n_in: int, hidden: int):
+    """Cuts a (3H) x (n_in + H) GRU matrix (rows r,z,n) into the two operands of the
+    reset-before form: Wa = the matrix with the n rows' recurrent-side entries removed,
+    Un = those entries as an H x H matrix.  Slicing only."""
+    Wa = A.copy()
+    Wa[2 * hidden:, n_in:] = 0.0
+    Un = np.ascontiguousarray(A[2 * hidden:, n_in:])
+    return Wa, Un
+
+
 @dataclass
 class LstmpWorkload:
     input: int

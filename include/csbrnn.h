@@ -43,6 +43,8 @@ extern "C" {
 #define CSB_CELL_LSTM 0
 #define CSB_CELL_GRU 1
 #define CSB_CELL_LSTMP 2     /* LSTM with a recurrent projection; created by csb_rnn_create_lstmp */
+#define CSB_CELL_LIGRU 3     /* Li-GRU: update gate and ReLU candidate, rows z,c               */
+#define CSB_CELL_GRU_RB 4    /* GRU, reset gate before the product; created by csb_rnn_create_gru_rb */
 
 #define CSB_MAX_BLOCK 256     /* br, bc in [1, 256]: device indices are one byte */
 
@@ -196,9 +198,12 @@ int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int
              int32_t batch, void *d_ws, void *stream);
 
 /*
- * RNN handle (Sec. 2.1).  cell: CSB_CELL_LSTM (gate rows stacked i,f,g,o; no peepholes)
- * or CSB_CELL_GRU (rows r,z,n; the reset gate multiplies the recurrent product of the n
- * rows).  Layer l has W[l] of shape (G*hidden) x (in_l + hidden), in_0 = input,
+ * RNN handle (Sec. 2.1).  cell: CSB_CELL_LSTM (gate rows stacked i,f,g,o; no peepholes),
+ * CSB_CELL_GRU (rows r,z,n; the reset gate multiplies the recurrent product of the n
+ * rows) or CSB_CELL_LIGRU (the cell of the paper's speech model SR3, Table 1, as its
+ * authors published it, the batch normalisation of the input part folded into W and the
+ * bias as it is at inference; rows z,c: z = sigmoid(a_z), cand = max(a_c, 0),
+ * h_t = z h_(t-1) + (1 - z) cand; G = 2).  Layer l has W[l] of shape (G*hidden) x (in_l + hidden), in_0 = input,
  * in_l = hidden, applied to [layer input ; h_{l,t-1}], and an optional device bias
  * d_bias[l] of G*hidden floats (d_bias NULL or d_bias[l] NULL = zero bias).
  * Each W[l] must be packed; it is planned by this call if it is not yet, in the layout
@@ -226,6 +231,26 @@ int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int32_t hidden
 int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hidden, int32_t proj,
                          csb_matrix *const *W, csb_matrix *const *Wp, const float *const *d_bias,
                          csb_rnn **out);
+
+/*
+ * GRU with the reset gate applied BEFORE the recurrent product of the candidate, the form
+ * of the work the paper cites for the GRU (Sec. 2.1): r, z as for CSB_CELL_GRU, then
+ * n = tanh(Wn u + Un (r * h_(t-1)) + b_n), h_t = (1 - z) n + z h_(t-1).  The candidate's
+ * recurrent product needs every r first, so a step is two dependent CSB products, and the
+ * caller hands the weights over in two matrices per layer:
+ *   Wa[l]: (3*hidden) x (in_l + hidden), rows r,z,n, in which the n rows hold their
+ *          input-side entries only (a non-zero in an n row at a recurrent column:
+ *          CSB_EINVAL);
+ *   Un[l]: hidden x hidden, the recurrent side of the n rows.
+ * Both packed; planned by this call if they are not yet; upload both with csb_upload.
+ * d_bias[l]: 3*hidden floats (r,z,n) or NULL.  There is no resident layout for this cell
+ * (csb_rnn_device_bytes is 0): csb_rnn_forward takes the streaming paths, per step and
+ * layer two CSB products and two element-wise kernels (batch > 1 on the matrix cores).
+ * Errors as csb_rnn_create.
+ */
+int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
+                          csb_matrix *const *Wa, csb_matrix *const *Un, const float *const *d_bias,
+                          csb_rnn **out);
 
 /*
  * Resident layout of the whole model for batch-1 inference: every row's surviving weights

@@ -10,6 +10,8 @@ import numpy as np
 CELL_LSTM = 0
 CELL_GRU = 1
 CELL_LSTMP = 2
+CELL_LIGRU = 3
+CELL_GRU_RB = 4
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libcsbrnn.so")
@@ -20,7 +22,7 @@ SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_plan
            "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
-           "csb_project_workspace_bytes", "csb_project", "csb_rnn_create_lstmp",
+           "csb_project_workspace_bytes", "csb_project", "csb_rnn_create_lstmp", "csb_rnn_create_gru_rb",
            "csb_rnn_create", "csb_rnn_device_bytes", "csb_rnn_upload", "csb_rnn_stats",
            "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
 
@@ -95,6 +97,8 @@ def load_library():
                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
     L.csb_rnn_create_lstmp.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
+    L.csb_rnn_create_gru_rb.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
+                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
     L.csb_rnn_device_bytes.argtypes = [C.c_void_p]
     L.csb_rnn_device_bytes.restype = C.c_size_t
     L.csb_rnn_upload.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -282,8 +286,9 @@ class CsbRnn:
 
     def __init__(self, cell: int, input: int, hidden: int, W: Sequence[CsbMatrix], bias=None,
                  proj: int = 0, Wp: Optional[Sequence[CsbMatrix]] = None):
-        """cell CELL_LSTM / CELL_GRU: csb_rnn_create.  cell CELL_LSTMP: csb_rnn_create_lstmp with the
-        projection width `proj` and the projection matrices `Wp`."""
+        """cell CELL_LSTM / CELL_GRU / CELL_LIGRU: csb_rnn_create.  cell CELL_LSTMP:
+        csb_rnn_create_lstmp with the projection width `proj` and the projection matrices `Wp`.
+        cell CELL_GRU_RB: csb_rnn_create_gru_rb, `W` = the Wa matrices, `Wp` = the Un matrices."""
         self.cell, self.input, self.hidden, self.W = cell, input, hidden, list(W)
         self.proj, self.Wp = proj, (list(Wp) if Wp is not None else [])
         self.bias = list(bias) if bias is not None else None
@@ -297,6 +302,10 @@ class CsbRnn:
             assert proj > 0 and len(self.Wp) == L
             Pv = (C.c_void_p * L)(*[w.handle for w in self.Wp])
             _check(lib().csb_rnn_create_lstmp(L, input, hidden, proj, Wv, Pv, Bp, C.byref(self._h)))
+        elif cell == CELL_GRU_RB:
+            assert len(self.Wp) == L
+            Pv = (C.c_void_p * L)(*[w.handle for w in self.Wp])
+            _check(lib().csb_rnn_create_gru_rb(L, input, hidden, Wv, Pv, Bp, C.byref(self._h)))
         else:
             _check(lib().csb_rnn_create(cell, L, input, hidden, Wv, Bp, C.byref(self._h)))
         self.n_layers = L

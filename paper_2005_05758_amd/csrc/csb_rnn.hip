@@ -44,7 +44,7 @@ constexpr bool kPhaseClocks = false;
 // units' gate rows); an LSTMP layer is two: the gate stage, whose output m_t is not state, and
 // a linear stage (the projection r_t = Wp m_t), whose output is the layer's state h and the
 // gate stage's recurrent input.
-constexpr uint32_t kStageLstm = 0, kStageGru = 1, kStageLinear = 2;
+constexpr uint32_t kStageLstm = 0, kStageGru = 1, kStageLinear = 2, kStageLiGru = 3;
 constexpr uint32_t kStageOwnRec = 1;     // flag: the recurrent input is this stage's own output
 constexpr uint32_t kStageIsState = 2;    // flag: the output is the layer's h state (h0 / hT)
 constexpr uint32_t kStageIsSeq = 4;      // flag: the output is the model's output sequence
@@ -170,6 +170,7 @@ static void gather_linear_rows(const csb_matrix *m, int width,
 static int build_resident_plan(csb_rnn *r) {
     RnnPlan &pl = r->plan;
     pl = RnnPlan{};
+    if (r->cell == CSB_CELL_GRU_RB) return CSB_EUNSUPPORTED;   // two dependent products per step: streaming paths only
     const bool lstmp = r->cell == CSB_CELL_LSTMP;
     const int NL = r->n_layers, L = lstmp ? 2 * NL : NL;      // L stages
     struct LayerTmp {
@@ -186,7 +187,7 @@ static int build_resident_plan(csb_rnn *r) {
         LayerTmp &t = lt[l];
         if (!lstmp) {
             t.width = r->hidden; t.real = (uint32_t)l;
-            t.kind = r->cell == CSB_CELL_LSTM ? kStageLstm : kStageGru;
+            t.kind = r->cell == CSB_CELL_LSTM ? kStageLstm : (r->cell == CSB_CELL_LIGRU ? kStageLiGru : kStageGru);
             t.n_in = l == 0 ? r->input : r->hidden;
             t.C = t.n_in + r->hidden;
             t.below = l - 1; t.rec = l;
@@ -466,7 +467,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     // (the record is the same for every lane: keep what steers branches in scalar registers)
     const uint32_t kword = __builtin_amdgcn_readfirstlane(wg.kind);
     const uint32_t kind = kword & 0xffu, real = (kword >> 8) & 0xffu, flags = kword >> 16;
-    const bool lstm = kind == kStageLstm, linear = !PLAIN && kind == kStageLinear;
+    const bool lstm = kind == kStageLstm, ligru = kind == kStageLiGru, linear = !PLAIN && kind == kStageLinear;
     const bool from_x = __builtin_amdgcn_readfirstlane(wg.below) == kNoStage;
     const bool own_rec = PLAIN || (flags & kStageOwnRec) != 0, is_state = PLAIN || (flags & kStageIsState) != 0;
     float *z = lds;                       // [C + 1], z[C] = 0
@@ -494,13 +495,15 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     const uint32_t unit = wg.u0 + tid;
     // the last lane of a row's segment ends up with the row sum: it adds the bias and applies
     // the gate's non-linearity at once (LSTM rows i,f,o: sigmoid, g: tanh; GRU rows r,z:
-    // sigmoid, the two halves of n: none yet; a linear stage: the bare sum)
+    // sigmoid, the two halves of n: none yet; Li-GRU row z: sigmoid, c: none yet; a linear
+    // stage: the bare sum)
     float row_bias = 0.0f;
     uint32_t act = 0;                       // 0 none, 1 sigmoid, 2 tanh
     if (seg_last && !linear) {
         const uint32_t g = row_slot / nu, ui = row_slot - g * nu;
         const float *b = A.bias[real];
         if (lstm) { act = g == 2 ? 2u : 1u; if (b) row_bias = b[g * H + wg.u0 + ui]; }
+        else if (ligru) { act = g == 0 ? 1u : 0u; if (b && g < 2) row_bias = b[g * H + wg.u0 + ui]; }
         else { act = g < 2 ? 1u : 0u; if (b && g < 3) row_bias = b[g * H + wg.u0 + ui]; }
     }
     const float act_k = act == 2 ? -2.0f * 1.44269504088896341f : -1.44269504088896341f;
@@ -523,6 +526,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         const float *b = linear ? nullptr : A.bias[real];
         float v = 0.0f;
         if (lstm) { if (b) v = b[g * H + wg.u0 + ui]; v = g == 2 ? fast_tanh(v) : fast_sigmoid(v); }
+        else if (ligru) { if (b && g < 2) v = b[g * H + wg.u0 + ui]; if (g == 0) v = fast_sigmoid(v); }
         else if (!linear) { if (b && g < 3) v = b[g * H + wg.u0 + ui]; if (g < 2) v = fast_sigmoid(v); }
         arow[i] = v;
     }
@@ -646,6 +650,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
                 const float cn = a1 * c_state + a0 * a2;
                 hn = a3 * fast_tanh(cn);
                 c_state = cn;
+            } else if (ligru) {                          // z activated; the candidate's sum (+ bias)
+                hn = a0 * h_state + (1.0f - a0) * fmaxf(a1, 0.0f);
             } else {                                     // r, z activated; n: input side (+ bias), recurrent side
                 const float n = fast_tanh(a2 + a0 * a3);
                 hn = (1.0f - a1) * n + a1 * h_state;
@@ -758,6 +764,48 @@ __global__ void lstmp_gates_batched_kernel(const float *__restrict__ a, const fl
     m[e] = sigmoidf_(ao) * tanhf(cn);
 }
 
+// Li-GRU, element-wise part (a is [2H][B], rows z, c; the state [H][B]; B = 1 serves the
+// batch-1 streaming path): z = sig(a_z), cand = max(a_c, 0), h = z h + (1 - z) cand.
+__global__ void ligru_gates_kernel(const float *__restrict__ a, const float *__restrict__ bias,
+                                   float *__restrict__ h, float *__restrict__ hseq, const int H, const int B) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= H * B) return;
+    const int k = e / B, n = e - k * B;
+    float az = a[(size_t)k * B + n], ac = a[(size_t)(H + k) * B + n];
+    if (bias) { az += bias[k]; ac += bias[H + k]; }
+    const float z = sigmoidf_(az);
+    const float hn = z * h[e] + (1.0f - z) * fmaxf(ac, 0.0f);
+    h[e] = hn;
+    if (hseq) hseq[(size_t)n * H + k] = hn;
+}
+
+// GRU with the reset gate before the candidate's recurrent product, first element-wise part:
+// q = sig(a_r) * h, the operand of that product (a is [3H][B], rows r, z, n).
+__global__ void gru_rb_reset_kernel(const float *__restrict__ a, const float *__restrict__ bias,
+                                    const float *__restrict__ h, float *__restrict__ q, const int H, const int B) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= H * B) return;
+    const int k = e / B, n = e - k * B;
+    float ar = a[(size_t)k * B + n];
+    if (bias) ar += bias[k];
+    q[e] = sigmoidf_(ar) * h[e];
+}
+
+// ... second part: a2 = Un q is [H][B]; n = tanh(a_n + b_n + a2), h = (1 - z) n + z h.
+__global__ void gru_rb_gates_kernel(const float *__restrict__ a, const float *__restrict__ a2,
+                                    const float *__restrict__ bias, float *__restrict__ h,
+                                    float *__restrict__ hseq, const int H, const int B) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= H * B) return;
+    const int k = e / B, n = e - k * B;
+    float az = a[(size_t)(H + k) * B + n], an = a[(size_t)(2 * H + k) * B + n] + a2[e];
+    if (bias) { az += bias[H + k]; an += bias[2 * H + k]; }
+    const float z = sigmoidf_(az);
+    const float hn = (1.0f - z) * tanhf(an) + z * h[e];
+    h[e] = hn;
+    if (hseq) hseq[(size_t)n * H + k] = hn;
+}
+
 // hseq[b][k] = h[k][b] for one step ([W][B] internal -> [B][W] caller's layout)
 __global__ void seq_out_kernel(float *__restrict__ dst, const float *__restrict__ src, int W, int B) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
@@ -803,7 +851,7 @@ static void init_state(float *dst, const float *src, size_t n, hipStream_t st) {
 static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 struct RnnWs {
-    size_t off_a, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, off_m, total;
+    size_t off_a, off_a2, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, off_m, total;
 };
 
 static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
@@ -819,6 +867,8 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     for (auto *m : r->Wp) account(m);
     const size_t HS = (size_t)r->state_width();
     w.off_a = off; off = align256(off + rows_out * sizeof(float) * (size_t)batch);
+    const bool two_products = r->cell == CSB_CELL_GRU_RB;          // second product's output, its operand
+    w.off_a2 = off; off = align256(off + (two_products ? (size_t)batch * r->hidden * sizeof(float) : 0));
     w.off_c = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     w.off_part = off; off = align256(off + part);
     w.off_biasptr = off; off = align256(off + (size_t)r->n_layers * sizeof(void *));
@@ -827,7 +877,7 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
         w.off_hint = off; off = align256(off + (size_t)r->n_layers * batch * HS * sizeof(float));
         w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     }
-    w.off_m = off; off = align256(off + (r->proj > 0 ? (size_t)batch * r->hidden * sizeof(float) : 0));
+    w.off_m = off; off = align256(off + ((r->proj > 0 || two_products) ? (size_t)batch * r->hidden * sizeof(float) : 0));
     off += 512;   // last 512 bytes: debug clocks of the resident kernel
     w.total = off;
     return w;
@@ -902,9 +952,12 @@ extern "C" int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int
     using namespace csb;
     if (!W || !out) { set_error("csb_rnn_create: NULL pointer"); return CSB_EINVAL; }
     *out = nullptr;
-    if (cell != CSB_CELL_LSTM && cell != CSB_CELL_GRU) { set_error("csb_rnn_create: unknown cell"); return CSB_EINVAL; }
+    if (cell != CSB_CELL_LSTM && cell != CSB_CELL_GRU && cell != CSB_CELL_LIGRU) {
+        set_error("csb_rnn_create: unknown cell (LSTMP and the reset-before GRU have create calls of their own)");
+        return CSB_EINVAL;
+    }
     if (n_layers <= 0 || input <= 0 || hidden <= 0) { set_error("csb_rnn_create: non-positive size"); return CSB_EINVAL; }
-    const int G = cell == CSB_CELL_LSTM ? 4 : 3;
+    const int G = cell == CSB_CELL_LSTM ? 4 : (cell == CSB_CELL_LIGRU ? 2 : 3);
     for (int l = 0; l < n_layers; ++l) {
         if (!W[l]) { set_error("csb_rnn_create: NULL weight matrix"); return CSB_EINVAL; }
         const int64_t n_in = l == 0 ? input : hidden;
@@ -972,6 +1025,58 @@ extern "C" int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hid
     }
 }
 
+extern "C" int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
+                                     csb_matrix *const *Wa, csb_matrix *const *Un, const float *const *d_bias,
+                                     csb_rnn **out) {
+    using namespace csb;
+    if (!Wa || !Un || !out) { set_error("csb_rnn_create_gru_rb: NULL pointer"); return CSB_EINVAL; }
+    *out = nullptr;
+    if (n_layers <= 0 || input <= 0 || hidden <= 0) { set_error("csb_rnn_create_gru_rb: non-positive size"); return CSB_EINVAL; }
+    for (int l = 0; l < n_layers; ++l) {
+        if (!Wa[l] || !Un[l]) { set_error("csb_rnn_create_gru_rb: NULL weight matrix"); return CSB_EINVAL; }
+        const csb_matrix *m = Wa[l];
+        const int64_t n_in = l == 0 ? input : hidden;
+        if (m->rows != (int64_t)3 * hidden || m->cols != n_in + hidden || Un[l]->rows != hidden || Un[l]->cols != hidden) {
+            set_error("csb_rnn_create_gru_rb: shapes must be (3*hidden) x (in + hidden) and hidden x hidden");
+            return CSB_EINVAL;
+        }
+        // the n rows of Wa hold input-side entries only
+        for (int32_t bi = 0; bi < m->nbr; ++bi)
+            for (int32_t bj = 0; bj < m->nbc; ++bj) {
+                const size_t b = (size_t)bi * m->nbc + bj;
+                const int nr = m->nrows[b], nc = m->ncols[b];
+                for (int a = 0; a < nr; ++a) {
+                    if ((int64_t)bi * m->br + m->rowidx[m->row_off[b] + a] < 2 * (int64_t)hidden) continue;
+                    for (int q = 0; q < nc; ++q)
+                        if ((int64_t)bj * m->bc + m->colidx[m->col_off[b] + q] >= n_in &&
+                            m->val[m->val_off[b] + (size_t)a * nc + q] != 0.0f) {
+                            set_error("csb_rnn_create_gru_rb: an n row of Wa has a recurrent-side entry (it belongs in Un)");
+                            return CSB_EINVAL;
+                        }
+                }
+            }
+    }
+    try {
+        auto *r = new csb_rnn();
+        r->cell = CSB_CELL_GRU_RB; r->n_layers = n_layers; r->input = input; r->hidden = hidden;
+        for (int l = 0; l < n_layers; ++l) {
+            for (csb_matrix *m : {Wa[l], Un[l]})
+                if (!m->plan.valid || m->plan.split.active()) {
+                    int rc = plan_matrix(m, 0, 16, SplitSpec{}, nullptr, 0);
+                    if (rc != CSB_OK) { delete r; return rc; }
+                }
+            r->W.push_back(Wa[l]);
+            r->Wp.push_back(Un[l]);
+            r->d_bias.push_back(d_bias ? d_bias[l] : nullptr);
+        }
+        *out = r;                                   // no resident layout for this cell
+        return CSB_OK;
+    } catch (const std::bad_alloc &) {
+        set_error("csb_rnn_create_gru_rb: out of host memory");
+        return CSB_ENOMEM;
+    }
+}
+
 extern "C" size_t csb_rnn_device_bytes(const csb_rnn *r) {
     return (r && r->plan.valid) ? r->plan.image.size() : 0;
 }
@@ -1015,6 +1120,7 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
     const int L = r->n_layers, H = r->hidden, I = r->input;
     const bool lstmp = r->cell == CSB_CELL_LSTMP;
     const bool lstm = r->cell == CSB_CELL_LSTM || lstmp;        // has a cell state c
+    const bool ligru = r->cell == CSB_CELL_LIGRU, gru_rb = r->cell == CSB_CELL_GRU_RB;
     const int HS = r->state_width();                             // width of h (the projection's for LSTMP)
     const size_t nstate = (size_t)L * batch * HS, ncstate = (size_t)L * batch * H;
     if (T == 0) {                                  // hand the state through
@@ -1031,14 +1137,14 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
             }
         for (auto *m : r->Wp)
             if (!m->plan.valid || !m->uploaded) {
-                set_error("csb_rnn_forward: a projection matrix is not uploaded");
+                set_error("csb_rnn_forward: a layer's second matrix (projection / candidate recurrence) is not uploaded");
                 return CSB_ESTATE;
             }
     }
     if (resident) return forward_resident(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, d_ws, st);
 
     const RnnWs wl = ws_layout(r, batch, T);
-    float *a = (float *)((uint8_t *)d_ws + wl.off_a);
+    float *a = (float *)((uint8_t *)d_ws + wl.off_a), *a2 = (float *)((uint8_t *)d_ws + wl.off_a2);
     if (batch > 1) {
         // batched: one MFMA mat-mat launch and one gate launch per step and layer; the state
         // lives as [H][B] so that the batch index is the contiguous one
@@ -1067,7 +1173,14 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
                 } else if (lstm)
                     hipLaunchKernelGGL(lstm_gates_batched_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l],
                                        ci + (size_t)l * H * batch, hl, hs, H, batch);
-                else
+                else if (ligru)
+                    hipLaunchKernelGGL(ligru_gates_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l], hl, hs, H, batch);
+                else if (gru_rb) {
+                    hipLaunchKernelGGL(gru_rb_reset_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l], hl, mb, H, batch);
+                    rc = spmm_strided(r->Wp[l], mb, (uint32_t)H, batch, 1, mb, batch, 1, a2, batch, batch, st);
+                    if (rc != CSB_OK) return rc;
+                    hipLaunchKernelGGL(gru_rb_gates_kernel, dim3(gb), dim3(256), 0, st, a, a2, r->d_bias[l], hl, hs, H, batch);
+                } else
                     hipLaunchKernelGGL(gru_gates_batched_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l], hl, hs, H, batch);
             }
         hipLaunchKernelGGL(state_out_kernel, dim3(sblocks), dim3(256), 0, st, d_hT, hi, L, batch, HS);
@@ -1101,7 +1214,14 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
                 } else if (lstm)
                     hipLaunchKernelGGL(lstm_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l],
                                        c + ((size_t)l * batch + s) * H, h, hs, H);
-                else
+                else if (ligru)
+                    hipLaunchKernelGGL(ligru_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l], h, hs, H, 1);
+                else if (gru_rb) {
+                    hipLaunchKernelGGL(gru_rb_reset_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l], (const float *)h, mb, H, 1);
+                    rc = spmv_segments(r->Wp[l], mb, (uint32_t)H, mb, a2, part, st);
+                    if (rc != CSB_OK) return rc;
+                    hipLaunchKernelGGL(gru_rb_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, a2, r->d_bias[l], h, hs, H, 1);
+                } else
                     hipLaunchKernelGGL(gru_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l], h, hs, H);
             }
     hipError_t e = hipGetLastError();
