@@ -146,7 +146,7 @@ def main():
     # launch per sequence), so its launch duration is ms_per_step
     st = rnn.stats()
     ach = bytes_step * T / (ms_per_step * 1e-3) / 1e9
-    roofline = {"kernel": f"csb::rnn_resident_kernel<{st['slots_per_lane']}>", "bound": "hbm",
+    roofline = {"kernel": f"csb::rnn_resident_kernel<{st['slots_per_lane']}, true>", "bound": "hbm",
                 "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(ach / HBM_PEAK_GBS, 5),
                 "traffic": sum(TRAFFIC_BYTES["rnn_resident_cfg2"].values()) if args.workload == "cfg2" else None,
@@ -210,6 +210,7 @@ def main():
         out["batched"] = batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
         out["projection"] = projection_leg(torch, np, sr["gbps"], not args.no_cpu)
         out["lstmp_sr1"] = lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, not args.no_cpu)
+        out["cells"] = cells_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, not args.no_cpu)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_leg(cfg, wl)
     print(json.dumps(out))
@@ -408,6 +409,76 @@ def lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
             res["cpu_baseline"] = {"value": round((time.perf_counter() - t0) / (reps * T) * 1e6, 2), "unit": "us/frame",
                                    "cores": oracle.num_threads(), "kind": "oracle",
                                    "sample": f"{reps} sequences of T={T}, batch 1 (float64 dense masked products + gates)"}
+    return res
+
+
+def cells_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
+    """The shapes of two more of the paper's speech models (Table 1), synthetic weights, batch 1:
+    SR3 = two Li-GRU layers 39 -> 512 -> 512 at 7.1x (resident and streaming path), and SR2 =
+    two GRU layers 39 -> 1024 -> 1024 at 21.7x in the reset-before form (two dependent CSB
+    products per step: streaming path only) next to the reset-after form on both paths.  The
+    paper's FPGA figure for its trained SR2 is 5.18 us per frame (context, not a baseline)."""
+    from paper_2005_05758_amd import CELL_LIGRU, CELL_GRU_RB, CELL_GRU
+    T = 100
+    res = {}
+
+    def timed(rnn, xd, n):
+        for _ in range(2):
+            rnn.forward(xd, want_hseq=True)
+        return round(time_region(lambda: rnn.forward(xd, want_hseq=True), n, torch) / n * 1000.0 / T, 3)
+
+    def cpu(cell, wl, I, H):
+        import oracle
+        W = [m.A for m in wl.W]
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 4.0:
+            oracle.rnn_forward(cell, W, wl.bias, wl.x, I, H)
+            reps += 1
+        return {"value": round((time.perf_counter() - t0) / (reps * T) * 1e6, 2), "unit": "us/frame",
+                "cores": oracle.num_threads(), "kind": "oracle",
+                "sample": f"{reps} sequences of T={T}, batch 1 (float64 dense masked products + gates)"}
+
+    # SR3 shape, Li-GRU
+    cfg = csb_inputs.RnnConfig("sr3", csb_inputs.LIGRU, 2, 39, 512, 32, 7.1, "binomial", 0.05, 1, T, 0)
+    wl = csb_inputs.make_rnn(cfg)
+    bias = [torch.from_numpy(b).cuda() for b in wl.bias]
+    xd = torch.from_numpy(wl.x).cuda()
+    Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+    rs = CsbRnn(CELL_LIGRU, 39, 512, Ws, bias)
+    for m in Ws:
+        m.upload()
+    rr = CsbRnn(CELL_LIGRU, 39, 512, [CsbMatrix(m.A, m.br, m.bc) for m in wl.W], bias)
+    rr.upload()
+    res["ligru_sr3"] = {"batch1_streaming_us_per_frame": timed(rs, xd, 3), "batch1_resident_us_per_frame": timed(rr, xd, 20),
+                        "nnz": sum(int(m.view()["nnz"]) for m in Ws), "resident_plan": rr.stats()}
+    if with_cpu:
+        res["ligru_sr3"]["cpu_baseline"] = cpu(csb_inputs.LIGRU, wl, 39, 512)
+    # SR2 shape, GRU in both forms
+    cfg = csb_inputs.RnnConfig("sr2", csb_inputs.GRU_RB, 2, 39, 1024, 32, 21.7, "binomial", 0.05, 1, T, 0)
+    wl = csb_inputs.make_rnn(cfg)
+    bias = [torch.from_numpy(b).cuda() for b in wl.bias]
+    xd = torch.from_numpy(wl.x).cuda()
+    Was, Uns = [], []
+    for l, m in enumerate(wl.W):
+        Wa, Un = csb_inputs.split_gru_rb(m.A, 39 if l == 0 else 1024, 1024)
+        Was.append(CsbMatrix(Wa, m.br, m.bc))
+        Uns.append(CsbMatrix(Un, m.br, m.bc))
+    rb = CsbRnn(CELL_GRU_RB, 39, 1024, Was, bias, Wp=Uns)
+    for m in Was + Uns:
+        m.upload()
+    Wg = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+    ga = CsbRnn(CELL_GRU, 39, 1024, Wg, bias)
+    for m in Wg:
+        m.upload()
+    gr = CsbRnn(CELL_GRU, 39, 1024, [CsbMatrix(m.A, m.br, m.bc) for m in wl.W], bias)
+    gr.upload()
+    res["gru_sr2"] = {"reset_before_streaming_us_per_frame": timed(rb, xd, 3),
+                      "reset_after_streaming_us_per_frame": timed(ga, xd, 3),
+                      "reset_after_resident_us_per_frame": timed(gr, xd, 20),
+                      "nnz": sum(int(m.view()["nnz"]) for m in Wg), "resident_plan": gr.stats()}
+    if with_cpu:
+        res["gru_sr2"]["cpu_baseline_reset_before"] = cpu(csb_inputs.GRU_RB, wl, 39, 1024)
     return res
 
 
