@@ -241,3 +241,25 @@ def lstmp_forward(W: List[np.ndarray], Wp: List[np.ndarray], bias: Optional[List
     if rc != 0:
         raise ValueError("orc_lstmp_forward failed")
     return hseq, hT, cT
+
+
+def round_weights(a: np.ndarray, fmt: str) -> np.ndarray:
+    """The float32 values nearest to `a` that a 16-bit weight format can hold (the paper
+    quantises weights to 16 bits, Sec. 6.2.2 / 6.3.1; here the two 16-bit floating-point
+    formats of the target), round to nearest, ties to even:
+      'f16'  IEEE binary16 (overflow to infinity, gradual underflow) -- numpy's conversion;
+      'bf16' the upper 16 bits of binary32 -- done on the bit patterns: add 0x7fff plus the
+             lowest kept bit, then cut; NaN stays NaN.
+    The 16-bit product is then DEFINED as the float64 product with these weights."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if fmt == "f16":
+        with np.errstate(over="ignore"):
+            return a.astype(np.float16).astype(np.float32)
+    if fmt == "bf16":
+        bits = a.view(np.uint32).astype(np.uint64)
+        lsb = (bits >> np.uint64(16)) & np.uint64(1)
+        r = ((bits + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)).astype(np.uint32)
+        nan = np.isnan(a)
+        r[nan] = (a.view(np.uint32)[nan] & np.uint32(0xFFFF0000)) | np.uint32(0x00400000)
+        return r.view(np.float32).reshape(a.shape)
+    raise ValueError(fmt)
