@@ -46,6 +46,10 @@ extern "C" {
 #define CSB_CELL_LIGRU 3     /* Li-GRU: update gate and ReLU candidate, rows z,c               */
 #define CSB_CELL_GRU_RB 4    /* GRU, reset gate before the product; created by csb_rnn_create_gru_rb */
 
+#define CSB_VAL_F32 0         /* kernel values stored as binary32 (default)               */
+#define CSB_VAL_F16 1         /* ... as IEEE binary16                                     */
+#define CSB_VAL_BF16 2        /* ... as bfloat16 (upper half of binary32)                 */
+
 #define CSB_MAX_BLOCK 256     /* br, bc in [1, 256]: device indices are one byte */
 
 typedef struct csb_matrix csb_matrix;
@@ -110,6 +114,26 @@ int csb_view_get(const csb_matrix *m, csb_view *out);
 
 /* Inverse of csb_pack: writes all rows x cols entries of `dense` (host, ld >= cols). */
 int csb_unpack(const csb_matrix *m, float *dense, int64_t ld);
+
+/*
+ * 16-bit weights (the paper evaluates its engine with weights quantised to 16 bits,
+ * Sec. 6.2.2 / 6.3.1; here the two 16-bit floating-point formats of the target take the
+ * place of its fixed-point format).  HOST ONLY.  Rounds every stored kernel value to the
+ * nearest value of the format (ties to even; binary16 overflows to infinity and underflows
+ * gradually; NaN stays NaN), so that csb_view_get / csb_unpack show the weights every device
+ * path computes with, and makes csb_plan store the value stream in 16 bits: csb_spmv and
+ * csb_spmm then read half the bytes per kernel value and widen to binary32 in registers;
+ * sums are accumulated in binary32 as before.  A value rounded to zero stays a stored
+ * (explicit) zero.  Any plan and upload of the matrix become invalid: plan and upload again.
+ * CSB_VAL_F32 only switches the stream back to 32 bits (values already rounded stay rounded).
+ * Call it before csb_rnn_create* takes the matrix: the resident layout of an RNN copies the
+ * values it finds at creation (it keeps them in binary32 registers, rounded or not).
+ * Errors: NULL handle or unknown format -> CSB_EINVAL.
+ */
+int csb_set_value_format(csb_matrix *m, int32_t format);
+
+/* The value format of the matrix (CSB_VAL_*), or -1 for a NULL handle. */
+int csb_value_format(const csb_matrix *m);
 
 /*
  * Equal-work partition and device layout (host only; replaces the SMT-based schedule of

@@ -12,13 +12,14 @@ CELL_GRU = 1
 CELL_LSTMP = 2
 CELL_LIGRU = 3
 CELL_GRU_RB = 4
+VAL_F32, VAL_F16, VAL_BF16 = 0, 1, 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libcsbrnn.so")
 _lib = None
 
 # every symbol include/csbrnn.h declares
-SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_plan", "csb_plan_ex", "csb_plan_validate",
+SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_set_value_format", "csb_value_format", "csb_plan", "csb_plan_ex", "csb_plan_validate",
            "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
@@ -73,6 +74,8 @@ def load_library():
     L.csb_pack.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
     L.csb_view_get.argtypes = [C.c_void_p, C.POINTER(csb_view)]
     L.csb_unpack.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+    L.csb_set_value_format.argtypes = [C.c_void_p, C.c_int32]
+    L.csb_value_format.argtypes = [C.c_void_p]
     L.csb_plan.argtypes = [C.c_void_p, C.c_int32, C.POINTER(csb_plan_stats)]
     L.csb_plan_ex.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(csb_plan_stats)]
     L.csb_plan_validate.argtypes = [C.c_void_p]
@@ -203,6 +206,15 @@ class CsbMatrix:
         out = np.empty((self.rows, self.cols), np.float32)
         _check(lib().csb_unpack(self._h, out.ctypes.data, self.cols))
         return out
+
+    def set_value_format(self, fmt: int):
+        """csb_set_value_format: VAL_F32 / VAL_F16 / VAL_BF16; plan and upload again afterwards."""
+        _check(lib().csb_set_value_format(self._h, fmt))
+        self.d_buf = None
+        return self
+
+    def value_format(self) -> int:
+        return int(lib().csb_value_format(self._h))
 
     def plan(self, n_chunks: int = 0, mode: int = 0):
         st = csb_plan_stats()

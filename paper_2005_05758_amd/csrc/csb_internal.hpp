@@ -106,7 +106,7 @@ struct DevHeader {
     uint32_t n_shared, n_zero_tiles, n_nz_tiles, n_partial_slots;
     uint32_t br, bc;
     uint32_t max_chunk_tiles, reserved1;       // LDS sizing: tiles per chunk
-    uint32_t meta_cap, reserved0;              // bytes of records per chunk
+    uint32_t meta_cap, val_fmt;                // bytes of records per chunk; CSB_VAL_* of the value stream
     uint64_t rows_out, cols;
     uint64_t off_chunks, off_waves, off_groups, off_vbs, off_idx, off_vals;
     uint64_t off_nz_tiles, off_zero_tiles, off_shared, off_counters;
@@ -136,7 +136,7 @@ struct DevMat {
     uint32_t br, bc;
     uint32_t rows_out, cols;
     uint32_t n_groups, n_nz_tiles;
-    uint32_t idx_bytes, pad;
+    uint32_t idx_bytes, val_fmt;   // val_fmt != 0: vals holds one 32-bit word per lane and PAIR of steps (even step low)
 };
 
 // How rows are relabelled when the image is built for a GRU: entries in rows >= split_row
@@ -158,6 +158,11 @@ struct Plan {
 };
 
 void set_error(const std::string &msg);
+// 16-bit value formats: nearest, ties to even
+uint16_t f32_to_f16_bits(float f);
+float f16_bits_to_f32(uint16_t h);
+uint16_t f32_to_bf16_bits(float f);
+inline float bf16_bits_to_f32(uint16_t h) { uint32_t u = (uint32_t)h << 16; float f; __builtin_memcpy(&f, &u, 4); return f; }
 uint32_t reserve_tags(uint32_t count, uint32_t *generation);
 
 }  // namespace csb
@@ -169,6 +174,7 @@ struct csb_matrix {
     std::vector<uint16_t> rowidx, colidx;
     std::vector<float> val;
     std::vector<int64_t> val_off, row_off, col_off;
+    int32_t val_fmt = 0;          // CSB_VAL_*: how the device value stream is stored
     csb::Plan plan;
     void *d_buf = nullptr;        // caller-owned device image, set by csb_upload
     bool uploaded = false;

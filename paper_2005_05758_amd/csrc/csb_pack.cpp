@@ -127,4 +127,73 @@ extern "C" int csb_unpack(const csb_matrix *m, float *dense, int64_t ld) {
     return CSB_OK;
 }
 
+namespace csb {
+
+// binary32 -> binary16, round to nearest even; overflow to infinity, gradual underflow.
+uint16_t f32_to_f16_bits(float f) {
+    uint32_t x;
+    std::memcpy(&x, &f, 4);
+    const uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+    x &= 0x7fffffffu;
+    if (x > 0x7f800000u) return (uint16_t)(sign | 0x7e00u | ((x >> 13) & 0x3ffu));      // NaN stays NaN (quiet)
+    if (x >= 0x477ff000u) return (uint16_t)(sign | 0x7c00u);                            // >= 65520 (or inf): infinity
+    if (x < 0x38800000u) {                                                              // below 2^-14: subnormal or zero
+        const uint32_t e = x >> 23;
+        if (e < 102u) return sign;                                                      // below 2^-25: zero (2^-25 itself ties to zero)
+        const uint32_t mant = (x & 0x7fffffu) | 0x800000u, shift = 126u - e;            // value = mant 2^(e-150); unit 2^-24
+        uint32_t q = mant >> shift;
+        const uint32_t rem = mant & ((1u << shift) - 1u), half = 1u << (shift - 1u);
+        if (rem > half || (rem == half && (q & 1u))) ++q;
+        return (uint16_t)(sign | q);
+    }
+    uint32_t q = (x - 0x38000000u) >> 13;                                               // rebias 127 -> 15, keep 10 bits
+    const uint32_t rem = x & 0x1fffu;
+    if (rem > 0x1000u || (rem == 0x1000u && (q & 1u))) ++q;
+    return (uint16_t)(sign | q);
+}
+
+float f16_bits_to_f32(uint16_t h) {
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16, e = (h >> 10) & 0x1fu, mant = h & 0x3ffu;
+    uint32_t x;
+    if (e == 0x1fu) x = sign | 0x7f800000u | (mant << 13);
+    else if (e != 0) x = sign | ((e + 112u) << 23) | (mant << 13);
+    else if (mant == 0) x = sign;
+    else {                                                                              // subnormal: mant 2^-24
+        float v = (float)mant * 5.9604644775390625e-8f;
+        std::memcpy(&x, &v, 4);
+        x |= sign;
+    }
+    float f;
+    std::memcpy(&f, &x, 4);
+    return f;
+}
+
+uint16_t f32_to_bf16_bits(float f) {
+    uint32_t x;
+    std::memcpy(&x, &f, 4);
+    if ((x & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x >> 16) | 0x40u);          // NaN stays NaN
+    return (uint16_t)((x + 0x7fffu + ((x >> 16) & 1u)) >> 16);
+}
+
+}  // namespace csb
+
+extern "C" int csb_set_value_format(csb_matrix *m, int32_t format) {
+    using namespace csb;
+    if (!m) { set_error("csb_set_value_format: NULL handle"); return CSB_EINVAL; }
+    if (format != CSB_VAL_F32 && format != CSB_VAL_F16 && format != CSB_VAL_BF16) {
+        set_error("csb_set_value_format: unknown format");
+        return CSB_EINVAL;
+    }
+    if (format == CSB_VAL_F16)
+        for (float &v : m->val) v = f16_bits_to_f32(f32_to_f16_bits(v));
+    else if (format == CSB_VAL_BF16)
+        for (float &v : m->val) v = bf16_bits_to_f32(f32_to_bf16_bits(v));
+    m->val_fmt = format;
+    m->plan.valid = false;
+    m->uploaded = false;
+    return CSB_OK;
+}
+
+extern "C" int csb_value_format(const csb_matrix *m) { return m ? m->val_fmt : -1; }
+
 extern "C" void csb_free(csb_matrix *m) { delete m; }

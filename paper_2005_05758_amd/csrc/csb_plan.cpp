@@ -223,7 +223,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         if (nnz_placed != m->val.size()) { set_error("csb_plan: internal: value count mismatch"); return CSB_EINVAL; }
         if (vals.size() + kWave >= (1ull << 32)) { set_error("csb_plan: matrix too large for 32-bit device offsets"); return CSB_EUNSUPPORTED; }
         const size_t vals_end = vals.size();
-        vals.resize(vals_end + kWave, 0.0f);   // a wavefront without work still issues one (unused) load
+        vals.resize(vals_end + 2 * kWave, 0.0f);   // a wavefront without work still issues one (unused) load of a step pair
 
         // ---- 4. cost axis, chunk and wave cuts -----------------------------------------
         // Group g occupies [P[g], P[g+1]) with P[g+1]-P[g] = overhead + cmax; a cut inside
@@ -536,7 +536,21 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         h.off_groups = place(grecs.size() * sizeof(GroupRec));
         h.off_vbs = place(vrecs.size() * sizeof(VbRec));
         h.off_idx = place(idx.size());
-        h.off_vals = place(vals.size() * sizeof(float));
+        // 16-bit value stream: one 32-bit word per lane and PAIR of steps (groups start on even
+        // steps and have an even number of them), the even step in the low half
+        std::vector<uint32_t> vals16;
+        if (m->val_fmt != CSB_VAL_F32) {
+            vals16.resize(vals.size() / 2);
+            for (size_t pr = 0; pr < vals.size() / (2 * kWave); ++pr)
+                for (size_t l = 0; l < (size_t)kWave; ++l) {
+                    const float lo = vals[(2 * pr) * kWave + l], hi = vals[(2 * pr + 1) * kWave + l];
+                    const uint32_t a = m->val_fmt == CSB_VAL_F16 ? f32_to_f16_bits(lo) : f32_to_bf16_bits(lo);
+                    const uint32_t b = m->val_fmt == CSB_VAL_F16 ? f32_to_f16_bits(hi) : f32_to_bf16_bits(hi);
+                    vals16[pr * kWave + l] = a | (b << 16);
+                }
+        }
+        h.val_fmt = (uint32_t)m->val_fmt;
+        h.off_vals = place(vals16.empty() ? vals.size() * sizeof(float) : vals16.size() * sizeof(uint32_t));
         h.off_nz_tiles = place(nz_tiles.size() * 4);
         h.off_zero_tiles = place(zero_tiles.size() * 4);
         h.off_shared = place(shared.size() * sizeof(SharedRec));
@@ -567,7 +581,8 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         put(h.off_groups, grecs.data(), grecs.size() * sizeof(GroupRec));
         put(h.off_vbs, vrecs.data(), vrecs.size() * sizeof(VbRec));
         put(h.off_idx, idx.data(), idx.size());
-        put(h.off_vals, vals.data(), vals.size() * sizeof(float));
+        if (vals16.empty()) put(h.off_vals, vals.data(), vals.size() * sizeof(float));
+        else put(h.off_vals, vals16.data(), vals16.size() * sizeof(uint32_t));
         put(h.off_nz_tiles, nz_tiles.data(), nz_tiles.size() * 4);
         put(h.off_zero_tiles, zero_tiles.data(), zero_tiles.size() * 4);
         put(h.off_shared, shared.data(), shared.size() * sizeof(SharedRec));
@@ -636,7 +651,15 @@ int validate_plan(const csb_matrix *m) {
     const auto *groups = (const GroupRec *)(im + h.off_groups);
     const auto *vbs = (const VbRec *)(im + h.off_vbs);
     const uint8_t *idx = im + h.off_idx;
-    const float *vals = (const float *)(im + h.off_vals);
+    if (h.val_fmt != (uint32_t)m->val_fmt) return fail("value format");
+    // value slot va of the stream, whatever its storage format
+    auto val_at = [&](uint64_t va) -> float {
+        if (h.val_fmt == CSB_VAL_F32) return ((const float *)(im + h.off_vals))[va];
+        const uint64_t step = va / kWave, lane = va % kWave;
+        const uint32_t w = ((const uint32_t *)(im + h.off_vals))[(step >> 1) * kWave + lane];
+        const uint16_t bits = (uint16_t)((step & 1) ? w >> 16 : w & 0xffffu);
+        return h.val_fmt == CSB_VAL_F16 ? f16_bits_to_f32(bits) : bf16_bits_to_f32(bits);
+    };
     const auto *nz_tiles = (const uint32_t *)(im + h.off_nz_tiles);
     const auto *zero_tiles = (const uint32_t *)(im + h.off_zero_tiles);
     const auto *shared = (const SharedRec *)(im + h.off_shared);
@@ -766,7 +789,7 @@ int validate_plan(const csb_matrix *m) {
                         const uint64_t va = (uint64_t)gr.val_off + (uint64_t)j * kWave + lane;
                         if (va >= h.n_vals) return fail("value offset");
                         if (va < wr.v_begin || va >= wr.v_end) return fail("value outside the wave's window");
-                        if (lane >= gr.nlanes) { if (vals[va] != 0.0f) return fail("value padding (lane)"); continue; }
+                        if (lane >= gr.nlanes) { if (val_at(va) != 0.0f) return fail("value padding (lane)"); continue; }
                         if ((size_t)gr.idx_off + 4 * lane + 3 >= h.idx_bytes) return fail("lane descriptor offset");
                         const uint8_t slot = idx[gr.idx_off + 4 * lane], k = idx[gr.idx_off + 4 * lane + 1] & 15;
                         if (k >= gr.nvb) return fail("lane vb number");
@@ -775,13 +798,13 @@ int validate_plan(const csb_matrix *m) {
                         if ((size_t)gr.idx_off + lo != (size_t)v.list_pos) return fail("lane list offset");
                         if (lane < v.lane0 || lane >= v.lane0 + v.r) return fail("lane outside its vb");
                         if (slot >= tile_h) return fail("row slot");
-                        if (j >= v.c) { if (vals[va] != 0.0f) return fail("value padding (step)"); continue; }
+                        if (j >= v.c) { if (val_at(va) != 0.0f) return fail("value padding (step)"); continue; }
                         const size_t ia = (size_t)v.list_pos + 2 * (size_t)j;
                         const int64_t gc = ((uint32_t)idx[ia] | (uint32_t)idx[ia + 1] << 8) / 4;
                         const size_t cell = (size_t)((int64_t)tile * br + slot) * cols + gc;
                         if (seen[cell]) return fail("entry referenced twice");
                         seen[cell] = 1;
-                        got[cell] = vals[va];
+                        got[cell] = val_at(va);
                         ++vals_used;
                     }
                 }

@@ -76,6 +76,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
     float *myacc = acc + (size_t)wave * br * NB;
     for (uint32_t e = lane; e < br * NB; e += 64) myacc[e] = 0.0f;
     const uint32_t rank = blockIdx.x, tile = m.nz_tiles[rank];
+    const uint32_t vf = uni_(m.val_fmt);                           // storage format of the value stream
     const uint32_t mrow = lane & 15u, kq = lane >> 4;              // A: row, column-in-4; B: column n, row-in-4
     const uint32_t ncol = bt0 + mrow;                              // this lane's right-hand side (per 16: + 16 nt)
     uint32_t noff0[NT], noff1[NT];                                 // its element offset in either source
@@ -135,6 +136,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
         // k-steps.  Out-of-range lanes load from clamped addresses; their operands are zeroed.
         auto load_pass = [&](const Pass &p, Operands<NT> &o) {
             const float *gv = m.vals + p.val_off;
+            const uint32_t *gv16 = (const uint32_t *)m.vals + (p.val_off >> 1);
             const uint16_t *colp = (const uint16_t *)(meta + p.list);
             const bool row_ok = p.m0 + mrow < p.r;
             const uint32_t arow = p.lane0 + p.m0 + (row_ok ? mrow : 0u);
@@ -144,7 +146,14 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
                 const uint32_t jj = p.kc + 4u * s8 + kq;
                 const bool ok = jj < p.c;
                 const uint32_t jc = ok ? jj : 0u;
-                const float t = gv[jc * (uint32_t)kWave + arow];
+                float t;
+                if (vf == CSB_VAL_F32) {                           // uniform
+                    t = gv[jc * (uint32_t)kWave + arow];
+                } else {                                           // one word per lane and pair of steps
+                    const uint32_t w = gv16[(jc >> 1) * (uint32_t)kWave + arow];
+                    const uint32_t bits = (jc & 1u) ? w >> 16 : w & 0xffffu;
+                    t = vf == CSB_VAL_BF16 ? __uint_as_float(bits << 16) : (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+                }
                 o.av[s8] = ok && row_ok ? t : 0.0f;
                 const uint32_t gc = (uint32_t)colp[jc] >> 2;
                 const bool first = !TWO || gc < X.n0;

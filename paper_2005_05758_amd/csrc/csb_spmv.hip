@@ -12,6 +12,8 @@
 
 #include <atomic>
 
+#include <type_traits>
+
 #include "csb_internal.hpp"
 #include "csb_kernels.hpp"
 
@@ -38,6 +40,7 @@ DevMat dev_mat(const csb_matrix *m) {
     d.n_groups = h.n_groups;
     d.n_nz_tiles = h.n_nz_tiles;
     d.idx_bytes = (uint32_t)h.idx_bytes;
+    d.val_fmt = h.val_fmt;
     d.tile_g0 = (const uint32_t *)(b + h.off_tile_g0);
     d.tile_seg0 = (const uint32_t *)(b + h.off_tile_seg0);
     d.segs = (const SegRec *)(b + h.off_segs);
@@ -98,10 +101,24 @@ constexpr int kStepsInFlight = 32;   // column steps of a wavefront whose values
 #define CSB_ST(dst, idx, n, name) \
     { const uint32_t i_ = (idx); if (i_ < (n)) (dst)[i_] = name; }
 
+// The two kernel values a word of a 16-bit value stream holds (even step low), widened.
+template <int VF>
+__device__ __forceinline__ void unpack_pair(uint32_t w, float &lo, float &hi) {
+    if constexpr (VF == CSB_VAL_BF16) {
+        lo = __uint_as_float(w << 16);
+        hi = __uint_as_float(w & 0xffff0000u);
+    } else {
+        lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
+        hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
+    }
+}
+
 // One workgroup per chunk.  Records and the input vector go to LDS; the kernel values never
 // do: a wavefront's steps are consecutive 64-float runs of the value stream, so lane l loads
 // word l of every run straight into a register (one coalesced 256-byte read per step) and
-// multiplies it there.
+// multiplies it there.  VF: storage format of the value stream (CSB_VAL_*); a 16-bit stream
+// holds one word per lane and pair of steps, so a step pair is one coalesced 256-byte read.
+template <int VF>
 __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, const float *__restrict__ x0,
                                                              const uint32_t n0, const float *__restrict__ x1,
                                                              float *__restrict__ y, unsigned long long *__restrict__ partials,
@@ -152,10 +169,13 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
     // values of the wavefront's first CAP steps (steps past its last one repeat the last)
     const uint32_t nsteps = (wr.v_end - wr.v_begin) >> 6;
     const uint32_t last_step = nsteps ? nsteps - 1u : 0u;
-    const float *wv = m.vals + wr.v_begin + lane;
-    float R[CAP];
+    constexpr int NR = VF == CSB_VAL_F32 ? CAP : CAP / 2;     // registers that hold CAP steps' values
+    using RegT = typename std::conditional<VF == CSB_VAL_F32, float, uint32_t>::type;
+    const RegT *wv = (const RegT *)m.vals + (VF == CSB_VAL_F32 ? wr.v_begin : wr.v_begin >> 1) + lane;
+    const uint32_t last_reg = VF == CSB_VAL_F32 ? last_step : last_step >> 1;
+    RegT R[NR];
 #pragma unroll
-    for (int s = 0; s < CAP; ++s) R[s] = wv[(size_t)min((uint32_t)s, last_step) * kWave];
+    for (int s = 0; s < NR; ++s) R[s] = wv[(size_t)min((uint32_t)s, last_reg) * kWave];
 
     if (st && tid == 0) st[1] = __builtin_readcyclecounter();
     // ---- independent work while the loads fly -------------------------------------------
@@ -214,7 +234,8 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
         for (uint32_t base = 0; base < nsteps; base += CAP) {
             if (base) {                          // a wavefront with more than CAP steps: next batch
 #pragma unroll
-                for (int s = 0; s < CAP; ++s) R[s] = wv[(size_t)min(base + (uint32_t)s, last_step) * kWave];
+                for (int s = 0; s < NR; ++s)
+                    R[s] = wv[(size_t)min((VF == CSB_VAL_F32 ? base : base >> 1) + (uint32_t)s, last_reg) * kWave];
             }
             const uint32_t bsteps = min((uint32_t)CAP, nsteps - base);
             uint32_t s = 0;
@@ -242,10 +263,18 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
                     if (left > 4) { z4 = *(const float *)(zb + (c2 & 0xffffu)); z5 = *(const float *)(zb + (c2 >> 16)); }
                     if (left > 6) { z6 = *(const float *)(zb + (c3 & 0xffffu)); z7 = *(const float *)(zb + (c3 >> 16)); }
                     // register of step s0 + i (uniform index)
-                    r0 = R[s0 & (CAP - 1)]; r1 = R[(s0 + 1) & (CAP - 1)];
-                    if (left > 2) { r2 = R[(s0 + 2) & (CAP - 1)]; r3 = R[(s0 + 3) & (CAP - 1)]; }
-                    if (left > 4) { r4 = R[(s0 + 4) & (CAP - 1)]; r5 = R[(s0 + 5) & (CAP - 1)]; }
-                    if (left > 6) { r6 = R[(s0 + 6) & (CAP - 1)]; r7 = R[(s0 + 7) & (CAP - 1)]; }
+                    if constexpr (VF == CSB_VAL_F32) {
+                        r0 = R[s0 & (CAP - 1)]; r1 = R[(s0 + 1) & (CAP - 1)];
+                        if (left > 2) { r2 = R[(s0 + 2) & (CAP - 1)]; r3 = R[(s0 + 3) & (CAP - 1)]; }
+                        if (left > 4) { r4 = R[(s0 + 4) & (CAP - 1)]; r5 = R[(s0 + 5) & (CAP - 1)]; }
+                        if (left > 6) { r6 = R[(s0 + 6) & (CAP - 1)]; r7 = R[(s0 + 7) & (CAP - 1)]; }
+                    } else {                     // s0 is even: a pair of steps shares a word
+                        const uint32_t p0 = s0 >> 1;
+                        unpack_pair<VF>(R[p0 & (NR - 1)], r0, r1);
+                        if (left > 2) unpack_pair<VF>(R[(p0 + 1) & (NR - 1)], r2, r3);
+                        if (left > 4) unpack_pair<VF>(R[(p0 + 2) & (NR - 1)], r4, r5);
+                        if (left > 6) unpack_pair<VF>(R[(p0 + 3) & (NR - 1)], r6, r7);
+                    }
                     a0 = fmaf(r0, z0, a0); a1 = fmaf(r1, z1, a1);
                     a0 = fmaf(r2, z2, a0); a1 = fmaf(r3, z3, a1);
                     a0 = fmaf(r4, z4, a0); a1 = fmaf(r5, z5, a1);
@@ -383,7 +412,9 @@ static hipError_t launch_spmv(const csb_matrix *mat, const float *x0, uint32_t n
         return hipGetLastError();
     };
     if (h.waves_per_chunk != (uint32_t)kSpmvWaves) return hipErrorInvalidValue;
-    return go(spmv_kernel, kSpmvWaves);
+    if (h.val_fmt == CSB_VAL_F16) return go(spmv_kernel<CSB_VAL_F16>, kSpmvWaves);
+    if (h.val_fmt == CSB_VAL_BF16) return go(spmv_kernel<CSB_VAL_BF16>, kSpmvWaves);
+    return go(spmv_kernel<CSB_VAL_F32>, kSpmvWaves);
 }
 
 int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const float *d_x1, float *d_y,

@@ -1,0 +1,139 @@
+"""16-bit weight formats (csb_set_value_format) through the C ABI: csb_spmv, csb_spmm and
+csb_rnn_forward against the float64 oracle computed with the weights the ORACLE rounded
+(numpy / bit arithmetic, pinned against torch).  The library gets the unrounded matrix and
+rounds it itself, so a different rounding shows up here.  Sums are still binary32: same
+tolerances as the 32-bit path (norm-wise 1e-5 plus the element-wise dot-product bound for the
+products, 1e-4 absolute on h)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import csb_inputs
+import oracle
+from paper_2005_05758_amd import CsbMatrix, CsbRnn, VAL_F16, VAL_BF16, CELL_LSTM, CELL_GRU
+from helpers import rel_max_err
+
+pytestmark = pytest.mark.gpu
+FORMATS = [(VAL_F16, "f16"), (VAL_BF16, "bf16")]
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def packed(A, br, bc, fmt, n_chunks=0, mode=0):
+    M = CsbMatrix(A, br, bc)
+    M.set_value_format(fmt)
+    M.plan(n_chunks, mode)
+    M.validate()
+    M.upload()
+    return M
+
+
+def check_spmv(A, br, bc, x, fmt, name, n_chunks=0, mode=0, tag=""):
+    say(f"[val16] spmv {tag} {name} shape={A.shape} block={br}x{bc} n_chunks={n_chunks} mode={mode}")
+    Aq = oracle.round_weights(A, name)
+    ref = oracle.matvec(Aq, x)
+    scale = oracle.matvec_abs(Aq, x)
+    M = packed(A, br, bc, fmt, n_chunks, mode)
+    xd = torch.from_numpy(x).cuda()
+    y = M.spmv(xd)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert rel_max_err(got, ref) <= 1e-5, rel_max_err(got, ref)
+    k = np.count_nonzero(A, axis=1)
+    assert np.all(np.abs(got - ref) <= 2.0 * np.maximum(k, 1) * 2.0 ** -24 * scale + 1e-30)
+    assert torch.equal(y, M.spmv(xd))
+    return M
+
+
+@pytest.mark.parametrize("fmt,name", FORMATS)
+@pytest.mark.parametrize("R,C,br,bc,rate", [(4, 8, 4, 4, 2.0), (1, 1, 1, 1, 1.0), (37, 53, 8, 8, 3.0), (200, 150, 16, 16, 6.0),
+                                            (130, 257, 32, 32, 5.0), (70, 300, 16, 64, 4.0), (513, 100, 256, 256, 2.0)])
+def test_spmv_small_shapes(fmt, name, R, C, br, bc, rate):
+    m = csb_inputs.small_matrix(R * 3 + C, R, C, br, bc, rate=rate)
+    x = csb_inputs.make_vectors(R + C, C, 1)
+    for n_chunks in (0, 1, 3):
+        check_spmv(m.A, br, bc, x, fmt, name, n_chunks)
+        check_spmv(m.A, br, bc, x, fmt, name, n_chunks, mode=2)
+
+
+@pytest.mark.parametrize("fmt,name", FORMATS)
+def test_spmv_long_wave_runs_and_many_chunks(fmt, name):
+    """Wide rows in one chunk (more column steps per wavefront than one batch of value
+    registers holds) and a matrix of many chunks and tiles."""
+    m = csb_inputs.small_matrix(7, 64, 4000, 32, 32, rate=1.5)
+    x = csb_inputs.make_vectors(3, 4000, 1)
+    check_spmv(m.A, 32, 32, x, fmt, name, n_chunks=1, tag="one-chunk")
+    m = csb_inputs.small_matrix(8, 2048, 1500, 32, 32, rate=8.0)
+    x = csb_inputs.make_vectors(4, 1500, 1)
+    check_spmv(m.A, 32, 32, x, fmt, name, tag="many-chunks")
+
+
+@pytest.mark.parametrize("fmt,name", FORMATS)
+def test_rounding_is_visible(fmt, name):
+    """The 16-bit product differs from the 32-bit one by far more than the tolerance, so the
+    parity above does test the rounded weights."""
+    m = csb_inputs.small_matrix(9, 256, 256, 32, 32, rate=4.0)
+    x = csb_inputs.make_vectors(5, 256, 1)
+    ref32 = oracle.matvec(m.A, x)
+    ref16 = oracle.matvec(oracle.round_weights(m.A, name), x)
+    assert rel_max_err(ref16, ref32) > 3e-5
+
+
+@pytest.mark.parametrize("fmt,name", FORMATS)
+@pytest.mark.parametrize("R,C,br,bc,B", [(37, 53, 8, 8, 1), (200, 150, 16, 16, 5), (130, 257, 32, 32, 17), (300, 200, 64, 64, 40),
+                                         (1024, 700, 32, 32, 64)])
+def test_spmm(fmt, name, R, C, br, bc, B):
+    say(f"[val16] spmm {name} {R}x{C} block {br}x{bc} batch {B}")
+    m = csb_inputs.small_matrix(R + C + B, R, C, br, bc, rate=4.0)
+    X = csb_inputs.make_vectors(B, C, B).reshape(C, B)
+    Aq = oracle.round_weights(m.A, name)
+    ref = oracle.matmat(Aq, X)
+    M = packed(m.A, br, bc, fmt)
+    Y = M.spmm(torch.from_numpy(X).cuda())
+    torch.cuda.synchronize()
+    got = Y.cpu().numpy().astype(np.float64)
+    assert rel_max_err(got, ref) <= 1e-5, rel_max_err(got, ref)
+    absr = oracle.matmat(np.abs(Aq), np.abs(X))
+    k = np.count_nonzero(m.A, axis=1)[:, None]
+    assert np.all(np.abs(got - ref) <= 2.0 * np.maximum(k, 1) * 2.0 ** -24 * absr + 1e-30)
+
+
+@pytest.mark.parametrize("fmt,name", FORMATS)
+@pytest.mark.parametrize("cell,L,I,H,T,B,block", [(csb_inputs.LSTM, 2, 12, 16, 9, 1, 8), (csb_inputs.GRU, 1, 40, 100, 12, 1, 32),
+                                                  (csb_inputs.LSTM, 1, 64, 128, 16, 1, 16), (csb_inputs.GRU, 2, 30, 96, 7, 19, 16),
+                                                  (csb_inputs.LSTM, 2, 33, 300, 9, 5, 32)])
+def test_rnn(fmt, name, cell, L, I, H, T, B, block):
+    cfg = csb_inputs.RnnConfig("t", cell, L, I, H, block, 3.0, "binomial", 0.3, B, T, 90 + L + I)
+    wl = csb_inputs.make_rnn(cfg)
+    Wq = [oracle.round_weights(m.A, name) for m in wl.W]
+    rseq, rhT, rcT = oracle.rnn_forward(cell, Wq, wl.bias, wl.x, I, H)
+    bias = [torch.from_numpy(b).cuda() for b in wl.bias]
+    xd = torch.from_numpy(wl.x).cuda()
+    for resident in ([False, True] if B == 1 else [False]):
+        say(f"[val16] rnn {name} cell={cell} L={L} I={I} H={H} T={T} B={B} resident={resident}")
+        Ws = []
+        for m in wl.W:
+            M = CsbMatrix(m.A, m.br, m.bc)
+            M.set_value_format(fmt)                    # before the handle is created over it
+            Ws.append(M)
+        rnn = CsbRnn(CELL_LSTM if cell == csb_inputs.LSTM else CELL_GRU, I, H, Ws, bias)
+        if resident:
+            rnn.upload()
+        else:
+            for M in Ws:
+                assert M.value_format() == fmt
+                M.validate()
+                M.upload()
+        hseq, hT, cT = rnn.forward(xd)
+        torch.cuda.synchronize()
+        e = max(float(np.max(np.abs(hseq.cpu().numpy() - rseq))), float(np.max(np.abs(hT.cpu().numpy() - rhT))))
+        if cell == csb_inputs.LSTM:
+            e = max(e, float(np.max(np.abs(cT.cpu().numpy() - rcT))))
+        say(f"[val16] rnn err {e:.3g}")
+        assert e <= 1e-4

@@ -191,3 +191,63 @@ def test_plan_rejects_inputs_wider_than_the_offset_lists():
     M = CsbMatrix(np.ascontiguousarray(A[:, :16383]), 8, 64)
     M.plan(0)
     M.validate()
+
+
+# ---------------------------------------------------------------- 16-bit value formats (host side)
+
+@pytest.mark.parametrize("fmt,name", [(binding.VAL_F16, "f16"), (binding.VAL_BF16, "bf16")])
+def test_value_format_rounds_like_the_oracle_bit_for_bit(fmt, name):
+    rng = np.random.default_rng(0)
+    pm = csb_inputs.small_matrix(3, 70, 90, 16, 16, rate=3.0)
+    A = pm.A.copy()
+    nz = np.flatnonzero(A)
+    # spread the magnitudes: ties, subnormals of binary16, overflow
+    A.flat[nz[:40]] = np.float32(1.0) + np.arange(40, dtype=np.float32) * np.float32(2.0 ** -12)
+    A.flat[nz[40:60]] = rng.uniform(-1e-7, 1e-7, 20).astype(np.float32)
+    A.flat[nz[60:64]] = np.array([65519.0, 65520.0, -1e5, 3.4e38], np.float32)
+    M = CsbMatrix(A, 16, 16)
+    enc = oracle.csb_encode(A, 16, 16)
+    assert M.value_format() == binding.VAL_F32
+    M.set_value_format(fmt)
+    assert M.value_format() == fmt
+    v = M.view()
+    want = oracle.round_weights(enc.val, name)
+    assert np.array_equal(v["val"].view(np.uint32), want.view(np.uint32))
+    for k in ("nrows", "ncols", "rowidx", "colidx"):                 # the pattern is untouched (zeros stay stored)
+        assert np.array_equal(v[k], getattr(enc, k))
+    assert np.array_equal(M.unpack().view(np.uint32) & 0x7FFFFFFF, oracle.round_weights(A, name).view(np.uint32) & 0x7FFFFFFF)
+    M.set_value_format(fmt)                                          # idempotent
+    assert np.array_equal(M.view()["val"].view(np.uint32), want.view(np.uint32))
+
+
+def test_value_format_halves_the_value_stream_and_validates():
+    pm = csb_inputs.small_matrix(5, 300, 500, 32, 32, rate=4.0)
+    M = CsbMatrix(pm.A, 32, 32)
+    M.plan()
+    M.validate()
+    n32 = M.device_bytes()
+    nnz = int(M.view()["nnz"])
+    for fmt in (binding.VAL_F16, binding.VAL_BF16):
+        M.set_value_format(fmt)
+        with pytest.raises(CsbError):
+            M.validate()                                             # the old plan is gone
+        M.plan()
+        M.validate()
+        assert n32 - M.device_bytes() >= 2 * nnz * 0.9               # 2 of 4 bytes per stored value
+    M.set_value_format(binding.VAL_F32)
+    M.plan()
+    M.validate()
+    assert M.device_bytes() == n32
+    with pytest.raises(CsbError):
+        M.set_value_format(7)
+
+
+def test_value_format_plan_sweep():
+    for seed, (R, Cc, br, bc) in enumerate([(5, 7, 4, 4), (64, 64, 8, 16), (100, 130, 32, 32), (257, 63, 64, 16), (40, 600, 16, 32)]):
+        pm = csb_inputs.small_matrix(seed, R, Cc, br, bc, rate=2.5)
+        for fmt in (binding.VAL_F16, binding.VAL_BF16):
+            M = CsbMatrix(pm.A, br, bc)
+            M.set_value_format(fmt)
+            for n_chunks in (0, 1, 3):
+                M.plan(n_chunks)
+                M.validate()
