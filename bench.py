@@ -38,11 +38,11 @@ TRAFFIC_BYTES = {
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 
-def spmv_alg_bytes(view, batch=1):
-    """Algorithmic bytes of one CSB mat-vec: values (f32), one byte per row/column index,
-    two count bytes per block, x read once, y written once."""
+def spmv_alg_bytes(view, batch=1, value_bytes=4):
+    """Algorithmic bytes of one CSB mat-vec: values (4 bytes, or 2 in a 16-bit format), one byte
+    per row/column index, two count bytes per block, x read once, y written once."""
     nb = int(view["nbr"]) * int(view["nbc"])
-    return (4 * int(view["nnz"]) + len(view["rowidx"]) + len(view["colidx"]) + 2 * nb
+    return (value_bytes * int(view["nnz"]) + len(view["rowidx"]) + len(view["colidx"]) + 2 * nb
             + 4 * int(view["cols"]) * batch + 4 * int(view["rows"]) * batch)
 
 
@@ -211,6 +211,7 @@ def main():
         out["projection"] = projection_leg(torch, np, sr["gbps"], not args.no_cpu)
         out["lstmp_sr1"] = lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, not args.no_cpu)
         out["cells"] = cells_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, not args.no_cpu)
+        out["weights_16bit"] = val16_leg(torch, np, csb_inputs, CsbMatrix, sr["gbps"])
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_leg(cfg, wl)
     print(json.dumps(out))
@@ -280,6 +281,56 @@ def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
                        "unit": "GB/s", "frac": best["frac_hbm_cold"], "traffic": sum(TRAFFIC_BYTES["spmv_cfg5"].values()),
                        "us_per_launch": best["us_cold"], "alg_bytes_per_launch": best["alg_bytes"],
                        "note": "cold: every launch reads a different device copy of the matrix"}
+    return res
+
+
+def val16_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
+    """csb_spmv and csb_spmm on the 8192^2 matrix with the kernel values stored in 16 bits
+    (the paper's engine works on 16-bit weights): half the value bytes on the HBM-bound path.
+    Cold as in the 32-bit leg (rotating device copies)."""
+    from paper_2005_05758_amd import VAL_F16, VAL_BF16
+    res = {}
+    m = csb_inputs.make_mat(csb_inputs.CONFIGS["cfg5"])
+    x = torch.from_numpy(csb_inputs.make_vectors(5, m.cols, 1)).cuda()
+    y = torch.empty(m.rows, dtype=torch.float32, device="cuda")
+    for fmt, name in ((VAL_F16, "f16"), (VAL_BF16, "bf16")):
+        n_copies = 40
+        copies = []
+        for _ in range(n_copies):
+            c = CsbMatrix(m.A, m.br, m.bc)
+            c.set_value_format(fmt)
+            c.plan()
+            c.upload()
+            copies.append(c)
+        M = copies[0]
+        ab = spmv_alg_bytes(M.view(), value_bytes=2)
+        for c in copies:
+            c.spmv(x, y)
+        n = 200
+        us_warm = time_region(lambda: M.spmv(x, y), n, torch) * 1000.0 / n
+        state = {"i": 0}
+
+        def cold():
+            copies[state["i"] % n_copies].spmv(x, y)
+            state["i"] += 1
+        n = 5 * n_copies
+        us_cold = time_region(cold, n, torch) * 1000.0 / n
+        entry = {"alg_bytes": ab, "device_bytes": M.device_bytes(), "us_warm": round(us_warm, 3), "us_cold": round(us_cold, 3),
+                 "gbps_cold": round(ab / us_cold / 1e3, 1), "frac_hbm_cold": round(ab / us_cold / 1e3 / HBM_PEAK_GBS, 4),
+                 "frac_of_measured_stream_read_cold": round(ab / us_cold / 1e3 / stream_gbps, 4),
+                 "cold_copies": n_copies, "cold_bytes_total": n_copies * M.device_bytes()}
+        if name == "bf16":
+            B = 128
+            X = torch.from_numpy(csb_inputs.make_vectors(6, m.cols, B).reshape(m.cols, B)).cuda()
+            Y = torch.empty((m.rows, B), dtype=torch.float32, device="cuda")
+            for _ in range(3):
+                M.spmm(X, Y)
+            n = 20
+            us = time_region(lambda: M.spmm(X, Y), n, torch) * 1000.0 / n
+            nnz = int(M.view()["nnz"])
+            entry["spmm_b128"] = {"us": round(us, 2), "tflops_algorithmic": round(2.0 * nnz * B / us / 1e6, 3)}
+        res[f"spmv_cfg5_{name}"] = entry
+        del copies, M
     return res
 
 
