@@ -359,7 +359,7 @@ def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
                                         "frac_fp32_mfma_peak": round(fl / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4)}
         del M
     best = res["spmm_cfg5_b128"]
-    res["roofline"] = {"kernel": "csb::spmm_kernel<2,false>", "bound": "mfma", "achieved": best["tflops_algorithmic"],
+    res["roofline"] = {"kernel": "csb::spmm_kernel<4, false, 16, true>", "bound": "mfma", "achieved": best["tflops_algorithmic"],
                        "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": best["frac_fp32_mfma_peak"],
                        "traffic": sum(TRAFFIC_BYTES["spmm_cfg5_b128"].values()),
                        "us_per_launch": best["us"], "flops_per_launch": 2.0 * best["nnz"] * best["batch"]}

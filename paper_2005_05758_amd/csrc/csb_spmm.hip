@@ -54,7 +54,12 @@ struct Operands {
     float bv[8][NT];
 };
 
-template <int NT, bool TWO, int NW>
+// WIDE (NT = 4, right-hand sides contiguous in memory, batch a multiple of 4): a lane reads
+// four neighbouring right-hand sides of its input row with one 16-byte load and feeds one
+// of them to each of four MFMA tiles, so tile t holds the right-hand sides 4 n + t; a
+// lane's four results of one row are then neighbours again and go to the accumulator as one
+// 16-byte word.  A quarter of the load and LDS instructions per multiply.
+template <int NT, bool TWO, int NW, bool WIDE>
 __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSrc X, float *__restrict__ Y,
                                                              const int64_t ldy, const uint32_t batch) {
     extern __shared__ float4 smem4[];
@@ -78,12 +83,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
     const uint32_t rank = blockIdx.x, tile = m.nz_tiles[rank];
     const uint32_t vf = uni_(m.val_fmt);                           // storage format of the value stream
     const uint32_t mrow = lane & 15u, kq = lane >> 4;              // A: row, column-in-4; B: column n, row-in-4
-    const uint32_t ncol = bt0 + mrow;                              // this lane's right-hand side (per 16: + 16 nt)
+    static_assert(!WIDE || NT == 4, "the wide form feeds four tiles from one load");
+    const uint32_t ncol = bt0 + (WIDE ? 4u * mrow : mrow);         // this lane's right-hand side (per 16: + 16 nt)
     uint32_t noff0[NT], noff1[NT];                                 // its element offset in either source
     bool n_ok[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const uint32_t n = ncol + 16u * nt;
+        const uint32_t n = WIDE ? ncol + (uint32_t)nt : ncol + 16u * nt;
         n_ok[nt] = n < batch;
         noff0[nt] = (n_ok[nt] ? n : 0u) * X.sn0;
         noff1[nt] = (n_ok[nt] ? n : 0u) * X.sn1;
@@ -159,10 +165,17 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
                 const bool first = !TWO || gc < X.n0;
                 const float *src = first ? X.p0 : X.p1;
                 const uint32_t joff = first ? __umul24(gc, X.sj0) : __umul24(gc - X.n0, X.sj1);
+                if constexpr (WIDE) {                              // batch % 4 == 0: the four are in or out together
+                    const float4 x4 = *(const float4 *)(src + joff + (first ? noff0[0] : noff1[0]));
+                    const bool in = ok && n_ok[0];
+                    o.bv[s8][0] = in ? x4.x : 0.0f; o.bv[s8][1] = in ? x4.y : 0.0f;
+                    o.bv[s8][2] = in ? x4.z : 0.0f; o.bv[s8][3] = in ? x4.w : 0.0f;
+                } else {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const float x = src[joff + (first ? noff0[nt] : noff1[nt])];
-                    o.bv[s8][nt] = ok && n_ok[nt] ? x : 0.0f;
+                    for (int nt = 0; nt < NT; ++nt) {
+                        const float x = src[joff + (first ? noff0[nt] : noff1[nt])];
+                        o.bv[s8][nt] = ok && n_ok[nt] ? x : 0.0f;
+                    }
                 }
             }
         };
@@ -188,7 +201,20 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
                 const uint32_t mr = p.m0 + 4u * kq + i;
                 on[i] = mr < p.r;
                 const uint32_t slot = meta[p.desc + 4u * (p.lane0 + (on[i] ? mr : 0u))];
-                at[i] = slot * NB + mrow;
+                at[i] = slot * NB + (WIDE ? 4u * mrow : mrow);
+            }
+            if constexpr (WIDE) {
+                float4 old4[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) old4[i] = *(const float4 *)(myacc + at[i]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (on[i])
+                        *(float4 *)(myacc + at[i]) = make_float4(old4[i].x + D[0][i], old4[i].y + D[1][i],
+                                                                 old4[i].z + D[2][i], old4[i].w + D[3][i]);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) D[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+                return;
             }
             float old[4][NT];
 #pragma unroll
@@ -240,13 +266,25 @@ int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj
     }
     XSrc X{p0, n0, (uint32_t)sj0, (uint32_t)sn0, p1, (uint32_t)sj1, (uint32_t)sn1};
     const bool two = n0 < (uint32_t)h.cols;
-    const int nt = h.br <= 128 ? 2 : 1;
+    // the wide form: right-hand sides contiguous, rows of the input 16-byte aligned, batch in
+    // fours, and eight wavefronts' accumulator tiles of 64 columns fit LDS
+    const bool aligned = ((uintptr_t)p0 % 16 == 0) && sj0 % 4 == 0 && sn0 == 1 &&
+                         (!two || (((uintptr_t)p1 % 16 == 0) && sj1 % 4 == 0 && sn1 == 1));
+    const bool wide_ok = aligned && batch % 4 == 0 &&
+                         (size_t)kSpmmMetaBytes + 8 * (size_t)h.br * 64 * sizeof(float) <= (size_t)kLdsBudget;
+    // batch columns per workgroup: the widest form that still gives every CU (256) a workgroup
+    const size_t tiles = (size_t)h.n_nz_tiles + h.n_zero_tiles;
+    auto wgs = [&](int n) { return tiles * (size_t)((batch + 16 * n - 1) / (16 * n)); };
+    int nt = 1;
+    if (h.br <= 128 && batch > 16 && wgs(2) >= 256) nt = 2;
+    if (wide_ok && batch >= 48 && wgs(4) >= 256) nt = 4;
+    const bool wide = nt == 4;
     const dim3 grid(h.n_nz_tiles + h.n_zero_tiles, (unsigned)((batch + 16 * nt - 1) / (16 * nt)));
     // 16 wavefronts share a tile's blocks when their accumulator tiles fit LDS and the grid
     // alone would not give every CU of an MI355X (256) two workgroups; else 8
     const size_t acc_per_wave = (size_t)h.br * 16 * nt * sizeof(float);
     const bool fits16 = (size_t)kSpmmMetaBytes + 16 * acc_per_wave <= (size_t)kLdsBudget;
-    const int nw = fits16 && (size_t)grid.x * grid.y < 2 * 256 ? 16 : 8;
+    const int nw = fits16 && (wide || (size_t)grid.x * grid.y < 2 * 256) ? 16 : 8;
     const size_t lds = (size_t)kSpmmMetaBytes + (size_t)nw * acc_per_wave;
     auto go = [&](auto kern) -> hipError_t {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -255,12 +293,15 @@ int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj
         return hipGetLastError();
     };
     hipError_t e;
-    if (nw == 16) {
-        if (nt == 2) e = two ? go(spmm_kernel<2, true, 16>) : go(spmm_kernel<2, false, 16>);
-        else e = two ? go(spmm_kernel<1, true, 16>) : go(spmm_kernel<1, false, 16>);
+    if (wide) {
+        if (nw == 16) e = two ? go(spmm_kernel<4, true, 16, true>) : go(spmm_kernel<4, false, 16, true>);
+        else e = two ? go(spmm_kernel<4, true, 8, true>) : go(spmm_kernel<4, false, 8, true>);
+    } else if (nw == 16) {
+        if (nt == 2) e = two ? go(spmm_kernel<2, true, 16, false>) : go(spmm_kernel<2, false, 16, false>);
+        else e = two ? go(spmm_kernel<1, true, 16, false>) : go(spmm_kernel<1, false, 16, false>);
     } else {
-        if (nt == 2) e = two ? go(spmm_kernel<2, true, 8>) : go(spmm_kernel<2, false, 8>);
-        else e = two ? go(spmm_kernel<1, true, 8>) : go(spmm_kernel<1, false, 8>);
+        if (nt == 2) e = two ? go(spmm_kernel<2, true, 8, false>) : go(spmm_kernel<2, false, 8, false>);
+        else e = two ? go(spmm_kernel<1, true, 8, false>) : go(spmm_kernel<1, false, 8, false>);
     }
     if (e != hipSuccess) { set_error(std::string("csb_spmm: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;

@@ -92,6 +92,17 @@ def test_rnn_batched_two_layer_shape():
     run_case(wl, tag="cfg4-T4", resident=False)
 
 
+@pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
+def test_rnn_batched_many_row_tiles(cell):
+    """Small blocks and 1024 hidden units: 192-256 row tiles per matrix, so the upper layer's
+    products (both inputs kept as [H][B]) take 64 right-hand sides per workgroup with 16-byte
+    loads, in the two-source form; batch 64 and a batch that ends inside a tile of 64."""
+    for B in (64, 52):
+        cfg = csb_inputs.RnnConfig("t", cell, 2, 48, 1024, 16, 12.0, "binomial", 0.05, B, 3, 31)
+        wl = csb_inputs.make_rnn(cfg)
+        run_case(wl, tag=f"many-tiles-B{B}", resident=False)
+
+
 def test_rnn_batched_full_size_sampled():
     """cfg4 as bench.py runs it (2 x LSTM 1024 -> 1024, batch 64, T = 256, the MFMA path).  The
     sequences of a batch are independent, so the float64 oracle runs three sampled ones on

@@ -110,3 +110,28 @@ def test_spmm_full_size_stress():
     X = csb_inputs.make_vectors(5, m.cols, 128)
     rows = np.random.default_rng(0).choice(m.rows, 256, replace=False)
     check_spmm(m.A, m.br, m.bc, X, tag="cfg5", rows=np.sort(rows))
+
+
+@pytest.mark.parametrize("R,C,br,bc,batch", [(8192, 96, 32, 32, 64), (8192, 70, 32, 16, 128), (4100, 130, 16, 32, 52),
+                                             (16384, 40, 64, 8, 48), (8192, 96, 32, 32, 60)])
+def test_spmm_wide_form(R, C, br, bc, batch):
+    """Tall matrices: enough row tiles that a workgroup takes 64 right-hand sides with 16-byte
+    loads (batch a multiple of 4; ragged last batch tile; both wavefront counts)."""
+    m = csb_inputs.small_matrix(R + C + batch, R, C, br, bc, rate=4.0)
+    X = csb_inputs.make_vectors(batch, C, batch)
+    check_spmm(m.A, br, bc, X, tag="wide-form")
+    # a strided view of a wider array (leading dimension above the batch, still 16-byte rows)
+    Xw = csb_inputs.make_vectors(batch + 1, C, batch + 12)
+    M = CsbMatrix(m.A, br, bc)
+    M.plan()
+    M.upload()
+    Xd = torch.from_numpy(Xw).cuda()
+    Y = M.spmm(Xd[:, 4:4 + batch])
+    torch.cuda.synchronize()
+    ref = oracle.matmat(m.A, np.ascontiguousarray(Xw[:, 4:4 + batch]))
+    assert rel_max_err(Y.cpu().numpy(), ref) <= 1e-5
+    # unaligned view: takes the narrow form, same result within tolerance
+    Y1 = M.spmm(Xd[:, 1:1 + batch])
+    torch.cuda.synchronize()
+    ref1 = oracle.matmat(m.A, np.ascontiguousarray(Xw[:, 1:1 + batch]))
+    assert rel_max_err(Y1.cpu().numpy(), ref1) <= 1e-5
