@@ -37,7 +37,8 @@ struct XSrc {
     uint32_t sj1, sn1;
 };
 
-// One pass: 32 columns (8 MFMA k-steps) of one 16-row slice of one virtual block.
+// One pass: 4 KS columns (KS MFMA k-steps; 8, or 4 in the wide form, whose operands take
+// four times the registers per k-step) of one 16-row slice of one virtual block.
 struct Pass {
     uint32_t k;           // virtual block, counted inside the segment
     uint32_t m0, kc;      // first row of the slice, first column of the pass
@@ -48,10 +49,10 @@ struct Pass {
     bool valid;
 };
 
-template <int NT>
+template <int NT, int KS>
 struct Operands {
-    float av[8];
-    float bv[8][NT];
+    float av[KS];
+    float bv[KS][NT];
 };
 
 // WIDE (NT = 4, right-hand sides contiguous in memory, batch a multiple of 4): a lane reads
@@ -64,6 +65,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
                                                              const int64_t ldy, const uint32_t batch) {
     extern __shared__ float4 smem4[];
     constexpr int NB = 16 * NT;                    // batch columns per workgroup
+    constexpr int KS = WIDE ? 4 : 8;               // k-steps per pass
     constexpr uint32_t NTHR = NW * 64;             // NW wavefronts
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uni_(tid >> 6);
     const uint32_t bt0 = blockIdx.y * NB;
@@ -85,14 +87,14 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
     const uint32_t mrow = lane & 15u, kq = lane >> 4;              // A: row, column-in-4; B: column n, row-in-4
     static_assert(!WIDE || NT == 4, "the wide form feeds four tiles from one load");
     const uint32_t ncol = bt0 + (WIDE ? 4u * mrow : mrow);         // this lane's right-hand side (per 16: + 16 nt)
-    uint32_t noff0[NT], noff1[NT];                                 // its element offset in either source
+    uint32_t noff0[NT], noff1[NT];                                 // its byte offset in either source
     bool n_ok[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const uint32_t n = WIDE ? ncol + (uint32_t)nt : ncol + 16u * nt;
         n_ok[nt] = n < batch;
-        noff0[nt] = (n_ok[nt] ? n : 0u) * X.sn0;
-        noff1[nt] = (n_ok[nt] ? n : 0u) * X.sn1;
+        noff0[nt] = (n_ok[nt] ? n : 0u) * X.sn0 * 4u;              // bytes
+        noff1[nt] = (n_ok[nt] ? n : 0u) * X.sn1 * 4u;
     }
 
     for (uint32_t sg = m.tile_seg0[rank]; sg < m.tile_seg0[rank + 1]; ++sg) {
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
         };
         auto next_pass = [&](const Pass &p) -> Pass {
             Pass q = p;
-            q.kc += 32;
+            q.kc += 4 * KS;
             if (q.kc < q.c) return q;
             q.kc = 0; q.m0 += 16;
             if (q.m0 < q.r) return q;
@@ -140,14 +142,14 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
         };
         // All loads of a pass are independent: kernel values and gathered inputs of up to 8
         // k-steps.  Out-of-range lanes load from clamped addresses; their operands are zeroed.
-        auto load_pass = [&](const Pass &p, Operands<NT> &o) {
+        auto load_pass = [&](const Pass &p, Operands<NT, KS> &o) {
             const float *gv = m.vals + p.val_off;
             const uint32_t *gv16 = (const uint32_t *)m.vals + (p.val_off >> 1);
             const uint16_t *colp = (const uint16_t *)(meta + p.list);
             const bool row_ok = p.m0 + mrow < p.r;
             const uint32_t arow = p.lane0 + p.m0 + (row_ok ? mrow : 0u);
 #pragma unroll
-            for (int s8 = 0; s8 < 8; ++s8) {
+            for (int s8 = 0; s8 < KS; ++s8) {
                 if (p.kc + 4u * s8 >= p.c) break;                  // uniform: k-steps the block does not have
                 const uint32_t jj = p.kc + 4u * s8 + kq;
                 const bool ok = jj < p.c;
@@ -161,36 +163,36 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
                     t = vf == CSB_VAL_BF16 ? __uint_as_float(bits << 16) : (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
                 }
                 o.av[s8] = ok && row_ok ? t : 0.0f;
-                const uint32_t gc = (uint32_t)colp[jc] >> 2;
-                const bool first = !TWO || gc < X.n0;
-                const float *src = first ? X.p0 : X.p1;
-                const uint32_t joff = first ? __umul24(gc, X.sj0) : __umul24(gc - X.n0, X.sj1);
+                // The input operand is not zeroed where the kernel operand is: a lane without a
+                // column reads the block's first column (finite wherever the block's own rows
+                // would be), one past the batch reads right-hand side 0, and its result column
+                // is never stored.
+                const uint32_t cb = colp[jc];                      // 4 * column: the list holds byte offsets
+                const bool first = !TWO || cb < 4u * X.n0;
+                const uint8_t *src = (const uint8_t *)(first ? X.p0 : X.p1);
+                const uint32_t joff = first ? __umul24(cb, X.sj0) : __umul24(cb - 4u * X.n0, X.sj1);   // bytes
                 if constexpr (WIDE) {                              // batch % 4 == 0: the four are in or out together
                     const float4 x4 = *(const float4 *)(src + joff + (first ? noff0[0] : noff1[0]));
-                    const bool in = ok && n_ok[0];
-                    o.bv[s8][0] = in ? x4.x : 0.0f; o.bv[s8][1] = in ? x4.y : 0.0f;
-                    o.bv[s8][2] = in ? x4.z : 0.0f; o.bv[s8][3] = in ? x4.w : 0.0f;
+                    o.bv[s8][0] = x4.x; o.bv[s8][1] = x4.y; o.bv[s8][2] = x4.z; o.bv[s8][3] = x4.w;
                 } else {
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        const float x = src[joff + (first ? noff0[nt] : noff1[nt])];
-                        o.bv[s8][nt] = ok && n_ok[nt] ? x : 0.0f;
-                    }
+                    for (int nt = 0; nt < NT; ++nt)
+                        o.bv[s8][nt] = *(const float *)(src + joff + (first ? noff0[nt] : noff1[nt]));
                 }
             }
         };
         floatx4 D[NT];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) D[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
-        auto mult_pass = [&](const Pass &p, const Operands<NT> &o) {
+        auto mult_pass = [&](const Pass &p, const Operands<NT, KS> &o) {
 #pragma unroll
-            for (int s8 = 0; s8 < 8; ++s8) {
+            for (int s8 = 0; s8 < KS; ++s8) {
                 if (p.kc + 4u * s8 >= p.c) break;                  // uniform
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
                     D[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.av[s8], o.bv[s8][nt], D[nt], 0, 0, 0);
             }
-            if (p.kc + 32 < p.c) return;                           // the slice has more columns
+            if (p.kc + 4 * KS < p.c) return;                       // the slice has more columns
             // lane holds rows 4*(lane/16)+i, column lane%16 of each 16 x 16 result; the rows of
             // a slice are distinct, so no two lanes meet in the accumulator: all reads, then
             // all writes
@@ -229,17 +231,37 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) D[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
         };
-        Operands<NT> oa, ob;
-        Pass pa = open_vb(wave), pb{};
-        if (pa.valid) load_pass(pa, oa);
-        while (pa.valid) {
-            pb = next_pass(pa);
-            if (pb.valid) load_pass(pb, ob);
-            mult_pass(pa, oa);
-            if (!pb.valid) break;
-            pa = next_pass(pb);
+        auto nxt = [&](const Pass &p) -> Pass { return p.valid ? next_pass(p) : p; };
+        if constexpr (WIDE) {
+            // three passes in flight (their operands are small: 4 k-steps)
+            Operands<NT, KS> oa, ob, oc;
+            Pass pa = open_vb(wave), pb = nxt(pa), pc{};
             if (pa.valid) load_pass(pa, oa);
-            mult_pass(pb, ob);
+            if (pb.valid) load_pass(pb, ob);
+            while (true) {
+                pc = nxt(pb); if (pc.valid) load_pass(pc, oc);
+                if (!pa.valid) break;
+                mult_pass(pa, oa);
+                pa = nxt(pc); if (pa.valid) load_pass(pa, oa);
+                if (!pb.valid) break;
+                mult_pass(pb, ob);
+                pb = nxt(pa); if (pb.valid) load_pass(pb, ob);
+                if (!pc.valid) break;
+                mult_pass(pc, oc);
+            }
+        } else {
+            Operands<NT, KS> oa, ob;
+            Pass pa = open_vb(wave), pb{};
+            if (pa.valid) load_pass(pa, oa);
+            while (pa.valid) {
+                pb = next_pass(pa);
+                if (pb.valid) load_pass(pb, ob);
+                mult_pass(pa, oa);
+                if (!pb.valid) break;
+                pa = next_pass(pb);
+                if (pa.valid) load_pass(pa, oa);
+                mult_pass(pb, ob);
+            }
         }
     }
     __syncthreads();
