@@ -263,3 +263,68 @@ def round_weights(a: np.ndarray, fmt: str) -> np.ndarray:
         r[nan] = (a.view(np.uint32)[nan] & np.uint32(0xFFFF0000)) | np.uint32(0x00400000)
         return r.view(np.float32).reshape(a.shape)
     raise ValueError(fmt)
+
+
+def sharing_model(nrows: np.ndarray, ncols: np.ndarray, P: int, Q: int, K: int, L: int, exact_2d: bool = False) -> dict:
+    """Cycle counts of the paper's engine schedule (Sec. 4.3.2, 5.2.2, 6.3.2) by brute force,
+    for small inputs.  nrows / ncols: [nbr, nbc] kept rows / columns of every block.  K x L
+    blocks per block iteration on K x L PEGroups of P x Q PEs; an a x b part takes
+    ceil(a/P) ceil(b/Q) cycles; an iteration lasts as long as its most loaded PEGroup.
+    Sharing: PEGroup (k,l) hands dnh columns (multiple of Q, at most n) to (k, l+1 mod L) and
+    dmv rows (multiple of P, at most m // 2) to (k+1 mod K, l), in one of the two regular
+    shapes of the partition constraints: shape 0 = horizontal part of full height (m x dnh),
+    vertical part dmv x (n - dnh); shape 1 = vertical part of full width (dmv x n), horizontal
+    part (m - dmv) x dnh; the rest (m - dmv) x (n - dnh) stays.  Every mode takes the schedule
+    with the smallest largest load (full enumeration with itertools.product)."""
+    import itertools
+    nrows = np.asarray(nrows); ncols = np.asarray(ncols)
+    nbr, nbc = nrows.shape
+    cyc = lambda a, b: 0 if a <= 0 or b <= 0 else -(-a // P) * -(-b // Q)
+
+    def parts(m, n, o):
+        dnh, dmv, shape = o
+        loc = cyc(m - dmv, n - dnh)
+        if shape == 0:
+            return loc, cyc(m, dnh), cyc(dmv, n - dnh)
+        return loc, cyc(m - dmv, dnh), cyc(dmv, n)
+
+    def best(dims, options):
+        """dims: K x L list of (m, n); options[k][l]: allowed (dnh, dmv, shape)."""
+        flat = [options[k][l] for k in range(K) for l in range(L)]
+        bestT = None
+        for choice in itertools.product(*flat):
+            T = 0
+            for k in range(K):
+                for l in range(L):
+                    m, n = dims[k][l]
+                    loc = parts(m, n, choice[k * L + l])[0]
+                    ml, nl = dims[k][(l - 1) % L]
+                    mu, nu = dims[(k - 1) % K][l]
+                    inh = parts(ml, nl, choice[k * L + (l - 1) % L])[1]
+                    inv = parts(mu, nu, choice[((k - 1) % K) * L + l])[2]
+                    T = max(T, loc + inh + inv)
+            if bestT is None or T < bestT:
+                bestT = T
+        return bestT
+
+    res = dict(work=0, iterations=0, cycles_none=0, cycles_horizontal=0, cycles_vertical=0, cycles_2d=0)
+    for bi in range(-(-nbr // K)):
+        for bj in range(-(-nbc // L)):
+            dims = [[(int(nrows[bi * K + k, bj * L + l]), int(ncols[bi * K + k, bj * L + l]))
+                     if bi * K + k < nbr and bj * L + l < nbc else (0, 0) for l in range(L)] for k in range(K)]
+            res["iterations"] += 1
+            res["work"] += sum(m * n for row in dims for m, n in row)
+            res["cycles_none"] += max(cyc(m, n) for row in dims for m, n in row)
+            oh = [[[(s, 0, 0) for s in range(0, n + 1, Q)] for (m, n) in row] for row in dims]
+            ov = [[[(0, s, 1) for s in range(0, m // 2 + 1, P)] for (m, n) in row] for row in dims]
+            res["cycles_horizontal"] += best(dims, oh)
+            res["cycles_vertical"] += best(dims, ov)
+            if exact_2d:
+                o2 = [[[(a, b, sh) for sh in (0, 1) for a in range(0, n + 1, Q) for b in range(0, m // 2 + 1, P)]
+                       for (m, n) in row] for row in dims]
+                res["cycles_2d"] += best(dims, o2)
+    denom = float(P * Q * K * L)
+    for key in ("none", "horizontal", "vertical", "2d"):
+        c = res["cycles_" + key]
+        res["eff_" + key] = res["work"] / (denom * c) if c else 0.0
+    return res
