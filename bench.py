@@ -155,7 +155,12 @@ def main():
                 "note": "weights stay in registers for all T steps (read from HBM once per launch); a step is "
                         "bound by the h_t exchange latency between workgroups, not by HBM: the figure is the "
                         "algorithmic bytes of T re-streamed mat-vecs over the launch time, as the metric defines it",
-                "resident_plan": st}
+                "resident_plan": st,
+                # the paper's own engine schedule on the same matrix, for context (Sec. 6.3.2: 4 x 4
+                # PEGroups of 4 x 4 PEs); here every lane issues the same number of multiply-adds
+                # and slot_fill is the share of them that is useful
+                "paper_schedule_model": {k: round(v, 4) for k, v in Ws[0].sharing_model(4, 4, 4, 4).items()
+                                         if k.startswith("eff_")}}
 
     # the same workload with the weights re-streamed every step (one mat-vec launch per step)
     Ws2 = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
@@ -251,6 +256,12 @@ def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
                      "nosplit_max_over_mean": round(st["nosplit_max_over_mean"], 4),
                      "lane_fill": round(st["lane_fill"], 4), "n_chunks": st["n_chunks"],
                      "shared_tiles": st["n_shared_tiles"]}
+            if mode == 0:
+                # the paper's own schedule on the same matrix (4 x 4 PEGroups of 4 x 4 PEs, Sec. 6.3.2),
+                # next to this partition's efficiency (mean / largest wavefront work)
+                sm = M.sharing_model(4, 4, 4, 4)
+                entry["paper_schedule_model"] = {k: round(v, 4) for k, v in sm.items() if k.startswith("eff_")}
+                entry["partition_efficiency"] = round(st["work_mean"] / st["work_max"], 4)
             if name == "cfg5":
                 # cold: rotate over distinct device copies so that every launch streams from HBM
                 copies = [M]

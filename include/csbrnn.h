@@ -222,6 +222,31 @@ int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int
              int32_t batch, void *d_ws, void *stream);
 
 /*
+ * Model of the paper's own schedule, for context next to csb_plan's statistics.  HOST ONLY,
+ * no device work, not on any compute path.  The paper's engine (Sec. 4.3) runs K x L blocks
+ * per block iteration on K x L PEGroups of P x Q PEs; an a x b partition of a kernel matrix
+ * takes ceil(a/P) ceil(b/Q) cycles on a PEGroup; an iteration lasts as long as its most loaded
+ * PEGroup; efficiency = multiply-adds / (P Q K L cycles) (Sec. 6.3.2).  With workload sharing
+ * (Sec. 4.3.2, 5.2.2) PEGroup (k,l) hands dnh of its columns to (k, l+1) and / or dmv of its
+ * rows (at most half) to (k+1, l), torus-wise, in one of the two regular shapes of the
+ * partition constraints of Sec. 5.2.2; shares are multiples of Q and P.  The paper finds a
+ * schedule per iteration with an SMT solver and a growing margin around the mean load; this
+ * model takes the schedule with the smallest largest load instead: exactly (exhaustive search)
+ * for horizontal-only and vertical-only sharing, and by improving one PEGroup's choice at a
+ * time from the better of those two for 2-D sharing (so eff_2d is a lower bound on what the
+ * best 2-D schedule reaches).  The paper's evaluation uses P = Q = K = L = 4.
+ * Errors: NULL pointers, P, Q < 1, K, L outside [1, 8] -> CSB_EINVAL.
+ */
+typedef struct {
+    int64_t work;                 /* multiply-adds: sum of r_b c_b                           */
+    int64_t iterations;           /* block iterations: ceil(nbr / K) ceil(nbc / L)             */
+    int64_t cycles_none, cycles_horizontal, cycles_vertical, cycles_2d;
+    double eff_none, eff_horizontal, eff_vertical, eff_2d;
+} csb_sharing_stats;
+int csb_sharing_model(const csb_matrix *m, int32_t P, int32_t Q, int32_t K, int32_t L,
+                      csb_sharing_stats *out);
+
+/*
  * RNN handle (Sec. 2.1).  cell: CSB_CELL_LSTM (gate rows stacked i,f,g,o; no peepholes),
  * CSB_CELL_GRU (rows r,z,n; the reset gate multiplies the recurrent product of the n
  * rows) or CSB_CELL_LIGRU (the cell of the paper's speech model SR3, Table 1, as its

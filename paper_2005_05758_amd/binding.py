@@ -19,13 +19,20 @@ _LIB_PATH = os.path.join(_PKG, "libcsbrnn.so")
 _lib = None
 
 # every symbol include/csbrnn.h declares
-SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_set_value_format", "csb_value_format", "csb_plan", "csb_plan_ex", "csb_plan_validate",
+SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_set_value_format", "csb_value_format", "csb_sharing_model", "csb_plan", "csb_plan_ex", "csb_plan_validate",
            "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
            "csb_project_workspace_bytes", "csb_project", "csb_rnn_create_lstmp", "csb_rnn_create_gru_rb",
            "csb_rnn_create", "csb_rnn_device_bytes", "csb_rnn_upload", "csb_rnn_stats",
            "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
+
+
+class csb_sharing_stats(C.Structure):
+    _fields_ = [("work", C.c_int64), ("iterations", C.c_int64), ("cycles_none", C.c_int64),
+                ("cycles_horizontal", C.c_int64), ("cycles_vertical", C.c_int64), ("cycles_2d", C.c_int64),
+                ("eff_none", C.c_double), ("eff_horizontal", C.c_double), ("eff_vertical", C.c_double),
+                ("eff_2d", C.c_double)]
 
 
 class CsbError(RuntimeError):
@@ -74,6 +81,7 @@ def load_library():
     L.csb_pack.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
     L.csb_view_get.argtypes = [C.c_void_p, C.POINTER(csb_view)]
     L.csb_unpack.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+    L.csb_sharing_model.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(csb_sharing_stats)]
     L.csb_set_value_format.argtypes = [C.c_void_p, C.c_int32]
     L.csb_value_format.argtypes = [C.c_void_p]
     L.csb_plan.argtypes = [C.c_void_p, C.c_int32, C.POINTER(csb_plan_stats)]
@@ -206,6 +214,12 @@ class CsbMatrix:
         out = np.empty((self.rows, self.cols), np.float32)
         _check(lib().csb_unpack(self._h, out.ctypes.data, self.cols))
         return out
+
+    def sharing_model(self, P: int = 4, Q: int = 4, K: int = 4, L: int = 4) -> dict:
+        """csb_sharing_model: PE utilisation of the paper's own engine schedule on this matrix."""
+        st = csb_sharing_stats()
+        _check(lib().csb_sharing_model(self._h, P, Q, K, L, C.byref(st)))
+        return {k: getattr(st, k) for k, _ in csb_sharing_stats._fields_}
 
     def set_value_format(self, fmt: int):
         """csb_set_value_format: VAL_F32 / VAL_F16 / VAL_BF16; plan and upload again afterwards."""

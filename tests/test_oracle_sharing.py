@@ -50,13 +50,11 @@ def test_vertical_sharing_by_hand():
 
 def test_two_dimensional_beats_both_by_hand():
     # 2 x 2 PEGroups of 2 x 2 PEs, one 8 x 8 kernel (16 cycles alone), three empty blocks.
-    # one direction: half goes away: 8 cycles.  Both: shape 0 with dnh = 4, dmv = 4:
-    # stays 4 x 4 (4), right gets 8 x 4 (8)...; shape 1 with dmv = 4, dnh = 4: down gets 4 x 8 (8);
-    # best: dnh = 2..4 / dmv = 2..4 combinations; enumerate by hand the winner:
-    # shape 0, dnh = 4, dmv = 2: stays 6 x 4 -> 3 * 2 = 6, right 8 x 4 -> 8: no.
-    # shape 1, dmv = 2, dnh = 4: down 2 x 8 -> 4, right 6 x 4 -> 6, stays 6 x 4 -> 6: largest 6.
-    # shape 1, dmv = 4, dnh = 4: down 4 x 8 -> 8.  shape 1, dmv = 2, dnh = 2: stays 6 x 6 -> 9.
-    # shape 0, dnh = 2, dmv = 4: right 8 x 2 -> 4, down 4 x 6 -> 6, stays 4 x 6 -> 6: largest 6.
+    # One direction: half of it goes away, 8 cycles.  Both directions, full-height horizontal
+    # part (shape 0) with dnh = 2, dmv = 4: right gets 8 x 2 (4 cycles), below gets 4 x 6 (6),
+    # 4 x 6 stays (6): largest load 6.  Nothing does better: the three parts hold 64
+    # multiply-adds, i.e. 16 cycles of a 2 x 2 PEGroup, so one of them takes at least 6
+    # (shares are even: part sizes are products of even numbers, 5 cycles + 5 + 5 < 16).
     r = model([[(8, 8), (0, 0)], [(0, 0), (0, 0)]], 2, 2, 2, 2)
     assert r["cycles_none"] == 16 and r["cycles_horizontal"] == 8 and r["cycles_vertical"] == 8
     assert r["cycles_2d"] == 6
