@@ -30,7 +30,8 @@ namespace csb {
 
 constexpr int kRnnThreads = 1024;      // lanes per workgroup of the resident kernel
 constexpr int kRnnSlotsMax = 48;       // weights one lane keeps in registers
-constexpr int kRnnMaxWgs = 240;        // all workgroups must be co-resident (256 CUs)
+constexpr int kRnnWgsPerXcd = 28;      // workgroups placed on one XCD (32 CUs, one workgroup per CU, a few CUs spare)
+constexpr int kRnnMaxWgs = 8 * kRnnWgsPerXcd;   // all workgroups must be co-resident
 constexpr uint32_t kPollLimit = 1u << 24;
 // Per-phase shader clocks of the resident kernel (a development aid): compiled in only on
 // request, so that the time loop of the shipped kernel carries none of it.
@@ -421,7 +422,7 @@ struct RnnArgs {
     uint32_t T, H, I, tag_base;         // H: hidden width (rows per gate, width of c)
     uint32_t off_unit_wg;               // byte offset in img of the owner table
     uint32_t poll_delay;                // s_sleep units before the first poll of a step (0 = none)
-    uint32_t wg_stride;                 // workgroup w is block w * wg_stride; other blocks exit at once
+    uint32_t xcds, per_xcd, n_wgs, xcd_step;      // workgroup w runs as block (w % per_xcd) * 8 + w / per_xcd; other blocks exit at once
     unsigned long long *dbg;            // optional: per-phase shader clocks summed over the steps (workgroup 0)
 };
 
@@ -461,8 +462,13 @@ template <int SMAX, bool PLAIN>
 __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs A) {
     extern __shared__ float lds[];
     const uint32_t tid = threadIdx.x;
-    if (blockIdx.x % A.wg_stride != 0) return;
-    const RnnWgRec wg = ((const RnnWgRec *)A.img)[blockIdx.x / A.wg_stride];
+    // Blocks go to the 8 XCDs in turn (block b to XCD b % 8); the model's workgroups are packed
+    // onto as few XCDs as hold them, consecutive ones on the same XCD: the exchange of h_t is
+    // fastest between CUs that share an L2.
+    const uint32_t xq = (blockIdx.x & 7u) / A.xcd_step, xr = (blockIdx.x & 7u) % A.xcd_step;
+    const uint32_t wgi = xq * A.per_xcd + (blockIdx.x >> 3);
+    if (xr != 0 || xq >= A.xcds || (blockIdx.x >> 3) >= A.per_xcd || wgi >= A.n_wgs) return;
+    const RnnWgRec wg = ((const RnnWgRec *)A.img)[wgi];
     const uint32_t H = A.H, T = A.T, nu = wg.nu, n_in = wg.n_in, C = wg.C, S = wg.S;
     // (the record is the same for every lane: keep what steers branches in scalar registers)
     const uint32_t kword = __builtin_amdgcn_readfirstlane(wg.kind);
@@ -907,17 +913,23 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     A.T = (uint32_t)T; A.H = (uint32_t)H; A.I = (uint32_t)r->input;
     A.tag_base = tag_base;
     A.off_unit_wg = (uint32_t)r->plan.off_unit_wg;
-    A.wg_stride = 1;
+    // at most kRnnWgsPerXcd workgroups per XCD (32 CUs each, one workgroup per CU, all resident)
+    uint32_t xcds = ((uint32_t)r->plan.n_wgs + kRnnWgsPerXcd - 1) / kRnnWgsPerXcd;
+    if (const char *e = getenv("CSB_RNN_XCDS")) xcds = std::max(xcds, (uint32_t)std::min(8, std::max(1, atoi(e))));
+    if (xcds > 8) { set_error("csb_rnn_forward: resident layout has more workgroups than the device holds at once"); return CSB_EUNSUPPORTED; }
+    A.xcds = xcds;
+    A.per_xcd = ((uint32_t)r->plan.n_wgs + xcds - 1) / xcds;
+    A.n_wgs = (uint32_t)r->plan.n_wgs;
+    A.xcd_step = 8u / xcds;                       // the XCDs in use lie this far apart
     A.poll_delay = r->plan.n_wgs > 1 ? 8u : 0u;   // fewer polls in flight while h_t cannot have arrived yet
     if (const char *e = getenv("CSB_RNN_POLL_DELAY")) A.poll_delay = (uint32_t)std::max(0, atoi(e));
     if (kPhaseClocks && getenv("CSB_RNN_DEBUG")) A.dbg = (unsigned long long *)((uint8_t *)d_ws + wl.total - 512);
-    if (const char *e = getenv("CSB_RNN_WG_STRIDE")) A.wg_stride = (uint32_t)std::max(1, atoi(e));
     const size_t cmax = r->plan.cmax;
     const size_t lds = (((cmax + 1 + 63) & ~(size_t)63) + kRnnThreads) * sizeof(float);
     auto go = [&](auto kern) -> hipError_t {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3(r->plan.n_wgs * A.wg_stride), dim3(kRnnThreads), lds, st, A);
+        hipLaunchKernelGGL(kern, dim3(A.per_xcd * 8u), dim3(kRnnThreads), lds, st, A);
         return hipGetLastError();
     };
     hipError_t e;
