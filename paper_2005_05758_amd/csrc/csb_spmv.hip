@@ -257,28 +257,48 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
                     if (left > 8) { w0 = zw[0]; w1 = zw[1]; w2_ = zw[2]; w3 = zw[3]; }   // uniform
                     // pairs of steps past the end of the run are skipped (uniform branches)
                     float z0, z1, z2 = 0.0f, z3 = 0.0f, z4 = 0.0f, z5 = 0.0f, z6 = 0.0f, z7 = 0.0f;
-                    float r0, r1, r2 = 0.0f, r3 = 0.0f, r4 = 0.0f, r5 = 0.0f, r6 = 0.0f, r7 = 0.0f;
                     z0 = *(const float *)(zb + (c0 & 0xffffu)); z1 = *(const float *)(zb + (c0 >> 16));
                     if (left > 2) { z2 = *(const float *)(zb + (c1 & 0xffffu)); z3 = *(const float *)(zb + (c1 >> 16)); }
                     if (left > 4) { z4 = *(const float *)(zb + (c2 & 0xffffu)); z5 = *(const float *)(zb + (c2 >> 16)); }
                     if (left > 6) { z6 = *(const float *)(zb + (c3 & 0xffffu)); z7 = *(const float *)(zb + (c3 >> 16)); }
-                    // register of step s0 + i (uniform index)
-                    if constexpr (VF == CSB_VAL_F32) {
-                        r0 = R[s0 & (CAP - 1)]; r1 = R[(s0 + 1) & (CAP - 1)];
-                        if (left > 2) { r2 = R[(s0 + 2) & (CAP - 1)]; r3 = R[(s0 + 3) & (CAP - 1)]; }
-                        if (left > 4) { r4 = R[(s0 + 4) & (CAP - 1)]; r5 = R[(s0 + 5) & (CAP - 1)]; }
-                        if (left > 6) { r6 = R[(s0 + 6) & (CAP - 1)]; r7 = R[(s0 + 7) & (CAP - 1)]; }
-                    } else {                     // s0 is even: a pair of steps shares a word
-                        const uint32_t p0 = s0 >> 1;
-                        unpack_pair<VF>(R[p0 & (NR - 1)], r0, r1);
-                        if (left > 2) unpack_pair<VF>(R[(p0 + 1) & (NR - 1)], r2, r3);
-                        if (left > 4) unpack_pair<VF>(R[(p0 + 2) & (NR - 1)], r4, r5);
-                        if (left > 6) unpack_pair<VF>(R[(p0 + 3) & (NR - 1)], r6, r7);
+                    // The value registers of steps s0 .. s0 + 7.  s0 is even and uniform: one of 16
+                    // copies of the multiply-adds, each with its registers named outright, is
+                    // branched to (indexing the register file with a run-time index costs five
+                    // instructions per read).
+                    auto mads = [&](auto pair0) {
+                        constexpr int P0 = decltype(pair0)::value;      // first pair of steps of the block
+                        if constexpr (VF == CSB_VAL_F32) {
+                            a0 = fmaf(R[(2 * P0) & (CAP - 1)], z0, a0); a1 = fmaf(R[(2 * P0 + 1) & (CAP - 1)], z1, a1);
+                            if (left > 2) { a0 = fmaf(R[(2 * P0 + 2) & (CAP - 1)], z2, a0); a1 = fmaf(R[(2 * P0 + 3) & (CAP - 1)], z3, a1); }
+                            if (left > 4) { a0 = fmaf(R[(2 * P0 + 4) & (CAP - 1)], z4, a0); a1 = fmaf(R[(2 * P0 + 5) & (CAP - 1)], z5, a1); }
+                            if (left > 6) { a0 = fmaf(R[(2 * P0 + 6) & (CAP - 1)], z6, a0); a1 = fmaf(R[(2 * P0 + 7) & (CAP - 1)], z7, a1); }
+                        } else {                 // a pair of steps shares a word
+                            float lo, hi;
+                            unpack_pair<VF>(R[P0 & (NR - 1)], lo, hi); a0 = fmaf(lo, z0, a0); a1 = fmaf(hi, z1, a1);
+                            if (left > 2) { unpack_pair<VF>(R[(P0 + 1) & (NR - 1)], lo, hi); a0 = fmaf(lo, z2, a0); a1 = fmaf(hi, z3, a1); }
+                            if (left > 4) { unpack_pair<VF>(R[(P0 + 2) & (NR - 1)], lo, hi); a0 = fmaf(lo, z4, a0); a1 = fmaf(hi, z5, a1); }
+                            if (left > 6) { unpack_pair<VF>(R[(P0 + 3) & (NR - 1)], lo, hi); a0 = fmaf(lo, z6, a0); a1 = fmaf(hi, z7, a1); }
+                        }
+                    };
+                    static_assert(CAP == 32, "one case per pair of steps of a batch");
+                    switch ((s0 >> 1) & 15u) {
+                    case 0: mads(std::integral_constant<int, 0>{}); break;
+                    case 1: mads(std::integral_constant<int, 1>{}); break;
+                    case 2: mads(std::integral_constant<int, 2>{}); break;
+                    case 3: mads(std::integral_constant<int, 3>{}); break;
+                    case 4: mads(std::integral_constant<int, 4>{}); break;
+                    case 5: mads(std::integral_constant<int, 5>{}); break;
+                    case 6: mads(std::integral_constant<int, 6>{}); break;
+                    case 7: mads(std::integral_constant<int, 7>{}); break;
+                    case 8: mads(std::integral_constant<int, 8>{}); break;
+                    case 9: mads(std::integral_constant<int, 9>{}); break;
+                    case 10: mads(std::integral_constant<int, 10>{}); break;
+                    case 11: mads(std::integral_constant<int, 11>{}); break;
+                    case 12: mads(std::integral_constant<int, 12>{}); break;
+                    case 13: mads(std::integral_constant<int, 13>{}); break;
+                    case 14: mads(std::integral_constant<int, 14>{}); break;
+                    default: mads(std::integral_constant<int, 15>{}); break;
                     }
-                    a0 = fmaf(r0, z0, a0); a1 = fmaf(r1, z1, a1);
-                    a0 = fmaf(r2, z2, a0); a1 = fmaf(r3, z3, a1);
-                    a0 = fmaf(r4, z4, a0); a1 = fmaf(r5, z5, a1);
-                    a0 = fmaf(r6, z6, a0); a1 = fmaf(r7, z7, a1);
                 }
                 // the next group's lane descriptors (its records have arrived by now)
                 const uint32_t nd = lane_word(uni(nlo.x), uni(nhi.x) >> 24);
