@@ -18,7 +18,7 @@
 
 namespace csb {
 
-constexpr int kProjectMaxDim = 16384;     // segments ranked by one workgroup in LDS
+constexpr int kProjectMaxDim = 16384;     // segments ranked by one workgroup: 16 keys in each of 1024 threads
 
 // Ranking key of a sum of squares: its bit pattern (sums are >= +0 or NaN, so the unsigned
 // order of the bits is the numeric order); every NaN ranks on top.
@@ -87,27 +87,135 @@ __global__ __launch_bounds__(256) void col_segment_keys_kernel(const float *__re
     keys[(size_t)bi * C + c] = rank_key(s);
 }
 
-// One workgroup ranks the n segments of one block-column (block-row): bitonic sort of
-// (key, position) words in LDS; the first k of the ascending order are the pruned ones.
+// One workgroup ranks the n <= 16384 segments of one block-column (block-row) and marks the k
+// weakest as pruned, "weaker" being the order of (key, position).  No sort: every thread keeps
+// 16 consecutive keys in registers; the key T of the k-th weakest is found bit by bit from the
+// top (per bit: how many of the still possible keys have a 0 there -- wavefront counts by
+// ballot, workgroup count through LDS); then a segment is pruned if its key is below T, or
+// equal to T and fewer than (k - #below) equal keys lie at earlier positions.
+constexpr int kSelPer = 16;          // keys per thread
 __global__ __launch_bounds__(1024) void select_kernel(const uint32_t *__restrict__ keys, uint8_t *__restrict__ keep,
-                                                       const uint32_t n, const uint32_t P, const uint32_t k) {
-    extern __shared__ unsigned long long sk[];
-    const uint32_t tid = threadIdx.x;
+                                                       const uint32_t n, const uint32_t k) {
+    __shared__ uint32_t wsum[3][16];
+    __shared__ uint32_t cand[1024];              // the keys still possible once they are few (first: scratch)
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const size_t base = (size_t)blockIdx.x * n;
-    for (uint32_t i = tid; i < P; i += 1024)
-        sk[i] = i < n ? ((unsigned long long)keys[base + i] << 32) | i : ~0ull;
-    __syncthreads();
-    for (uint32_t size = 2; size <= P; size <<= 1)
-        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            for (uint32_t t = tid; t < P / 2; t += 1024) {
-                const uint32_t i = (t / stride) * 2 * stride + (t & (stride - 1)), j = i + stride;
-                const bool ascending = (i & size) == 0;
-                const unsigned long long a = sk[i], b = sk[j];
-                if ((a > b) == ascending) { sk[i] = b; sk[j] = a; }
+    const uint32_t i0 = tid * kSelPer;
+    if (k == 0 || k >= n) {                      // nothing / everything pruned
+        for (uint32_t q = 0; q < kSelPer; ++q)
+            if (i0 + q < n) keep[base + i0 + q] = k == 0 ? 1 : 0;
+        return;
+    }
+    uint32_t key[kSelPer];
+    bool valid[kSelPer];
+    const bool vec = (n & 15u) == 0;             // 16-byte accesses: every thread's run is whole and aligned
+#pragma unroll
+    for (int q = 0; q < kSelPer; ++q) valid[q] = i0 + q < n;
+    if (vec) {
+        if (valid[0]) {
+            const uint4 *src = (const uint4 *)(keys + base + i0);
+#pragma unroll
+            for (int v = 0; v < kSelPer / 4; ++v) {
+                const uint4 w = src[v];
+                key[4 * v] = w.x; key[4 * v + 1] = w.y; key[4 * v + 2] = w.z; key[4 * v + 3] = w.w;
             }
-            __syncthreads();
+        } else {
+#pragma unroll
+            for (int q = 0; q < kSelPer; ++q) key[q] = 0u;
         }
-    for (uint32_t i = tid; i < n; i += 1024) keep[base + (uint32_t)sk[i]] = i >= k ? 1 : 0;
+    } else {
+#pragma unroll
+        for (int q = 0; q < kSelPer; ++q) key[q] = valid[q] ? keys[base + i0 + q] : 0u;
+    }
+    // workgroup sum of a per-wavefront count (uniform in the wavefront)
+    auto wg_sum = [&](uint32_t wave_count, int buf) {
+        if (lane == 0) wsum[buf][wave] = wave_count;
+        __syncthreads();
+        uint32_t s = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) s += wsum[buf][w];
+        return s;
+    };
+    // bits on which every key agrees need no counting
+    uint32_t all_and = 0xffffffffu, all_or = 0u;
+#pragma unroll
+    for (int q = 0; q < kSelPer; ++q)
+        if (valid[q]) { all_and &= key[q]; all_or |= key[q]; }
+    for (int d = 32; d > 0; d >>= 1) {
+        all_and &= (uint32_t)__shfl_xor((int)all_and, d, 64);
+        all_or |= (uint32_t)__shfl_xor((int)all_or, d, 64);
+    }
+    if (lane == 0) { cand[wave] = all_and; cand[16 + wave] = all_or; }
+    __syncthreads();
+    for (int w = 0; w < 16; ++w) { all_and &= cand[w]; all_or |= cand[16 + w]; }
+    __syncthreads();                             // cand is reused below
+    const uint32_t varying = all_and ^ all_or;
+    uint32_t prefix = 0, mask = 0, kk = k;       // the kk-th weakest of the keys that match prefix on mask
+    uint32_t act = n;                            // keys still matching
+    bool compact = false;                        // the matching keys have been gathered, one per thread
+    uint32_t ckey = 0, ncand = 0;
+    int par = 0;
+    for (int b = 31; b >= 0; --b) {
+        const uint32_t bit = 1u << b;
+        if (!(varying & bit)) { prefix |= all_and & bit; mask |= bit; continue; }
+        if (!compact && act <= 1024u) {
+            // gather the matching keys into LDS, one per thread from here on (16 times fewer
+            // ballots per bit); their order does not matter for counting
+            uint32_t mine = 0;
+#pragma unroll
+            for (int q = 0; q < kSelPer; ++q) mine += (valid[q] && (key[q] & mask) == prefix) ? 1u : 0u;
+            uint32_t incl = mine;                // inclusive scan over the wavefront's lanes
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t up = (uint32_t)__shfl_up((int)incl, d, 64);
+                if (lane >= (uint32_t)d) incl += up;
+            }
+            if (lane == 63) wsum[0][wave] = incl;
+            __syncthreads();
+            uint32_t slot = incl - mine;
+            for (uint32_t w = 0; w < wave; ++w) slot += wsum[0][w];
+#pragma unroll
+            for (int q = 0; q < kSelPer; ++q)
+                if (valid[q] && (key[q] & mask) == prefix) cand[slot++] = key[q];
+            __syncthreads();
+            ncand = act;
+            ckey = tid < ncand ? cand[tid] : 0u;
+            compact = true;
+        }
+        uint32_t c0 = 0;
+        if (compact) {
+            c0 = (uint32_t)__popcll(__ballot(tid < ncand && !(ckey & bit) && (ckey & mask) == prefix));
+        } else {
+#pragma unroll
+            for (int q = 0; q < kSelPer; ++q)
+                c0 += (uint32_t)__popcll(__ballot(valid[q] && (key[q] & mask) == prefix && !(key[q] & bit)));
+        }
+        const uint32_t zeros = wg_sum(c0, 1 + (par ^= 1));   // two buffers in turn: one barrier per counted bit
+        if (kk > zeros) { prefix |= bit; kk -= zeros; act -= zeros; } else act = zeros;
+        mask |= bit;
+    }
+    // prefix is T; kk of the keys equal to T are pruned: the first ones by position
+    uint32_t eq_wave = 0, eq_lower = 0;          // equal keys in the wavefront / in its lower lanes
+#pragma unroll
+    for (int q = 0; q < kSelPer; ++q) {
+        const unsigned long long m = __ballot(valid[q] && key[q] == prefix);
+        eq_wave += (uint32_t)__popcll(m);
+        eq_lower += __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    }
+    __syncthreads();                             // the last wg_sum's readers are done with wsum[0]
+    if (lane == 0) wsum[0][wave] = eq_wave;
+    __syncthreads();
+    uint32_t rank = eq_lower;
+    for (uint32_t w = 0; w < wave; ++w) rank += wsum[0][w];
+    uint32_t flags[kSelPer / 4] = {};            // keep flags, one byte each
+#pragma unroll
+    for (int q = 0; q < kSelPer; ++q) {
+        const bool eq = valid[q] && key[q] == prefix;
+        const bool pruned = key[q] < prefix || (eq && rank < kk);
+        rank += eq ? 1u : 0u;
+        flags[q >> 2] |= (pruned ? 0u : 1u) << (8 * (q & 3));
+        if (!vec && valid[q]) keep[base + i0 + q] = pruned ? 0 : 1;
+    }
+    if (vec && valid[0]) *(uint4 *)(keep + base + i0) = make_uint4(flags[0], flags[1], flags[2], flags[3]);
 }
 
 // Z = W where both its row segment and its column segment survive, else +0.  A thread takes
@@ -166,11 +274,6 @@ static uint32_t prune_count(int64_t n, double rate) {
     return (uint32_t)k;
 }
 
-static uint32_t pow2_at_least(uint32_t n) {
-    uint32_t p = 2;
-    while (p < n) p <<= 1;
-    return p;
-}
 
 }  // namespace csb
 
@@ -197,10 +300,8 @@ extern "C" int csb_project(const float *d_W, int64_t rows, int64_t cols, int64_t
     uint32_t *keys_r = (uint32_t *)(ws + L.keys_r), *keys_c = (uint32_t *)(ws + L.keys_c);
     uint8_t *keep_r = ws + L.keep_r, *keep_c = ws + L.keep_c;
     hipStream_t st = (hipStream_t)stream;
-    const uint32_t Pr = pow2_at_least(R), Pc = pow2_at_least(C);
-    hipError_t e = hipFuncSetAttribute((const void *)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)(std::max(Pr, Pc) * sizeof(unsigned long long)));
-    if (e == hipSuccess) {
+    hipError_t e = hipSuccess;
+    {
         // tile of the row-sum kernel: TS segments x TR rows, at most 256 threads and 48 KB of LDS
         const uint32_t BCp = BC | 1u;
         const uint32_t TS = std::max(1u, std::min({NBC, 256u, 12288u / BCp}));
@@ -215,11 +316,9 @@ extern "C" int csb_project(const float *d_W, int64_t rows, int64_t cols, int64_t
             case 6: hipLaunchKernelGGL(row_segment_keys_kernel<6>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
             default: hipLaunchKernelGGL(row_segment_keys_kernel<-1>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
         }
-        hipLaunchKernelGGL(select_kernel, dim3(NBC), dim3(1024), Pr * sizeof(unsigned long long), st, keys_r, keep_r, R, Pr,
-                           prune_count(rows, rate));
+        hipLaunchKernelGGL(select_kernel, dim3(NBC), dim3(1024), 0, st, keys_r, keep_r, R, prune_count(rows, rate));
         hipLaunchKernelGGL(col_segment_keys_kernel, dim3((C + 255) / 256, NBR), dim3(256), 0, st, d_W, ld, R, C, BR, BC, keep_r, keys_c);
-        hipLaunchKernelGGL(select_kernel, dim3(NBR), dim3(1024), Pc * sizeof(unsigned long long), st, keys_c, keep_c, C, Pc,
-                           prune_count(cols, rate));
+        hipLaunchKernelGGL(select_kernel, dim3(NBR), dim3(1024), 0, st, keys_c, keep_c, C, prune_count(cols, rate));
         // float4 accesses need 16-byte aligned rows on both sides (and flag words at multiples of 4)
         const bool vec4 = C % 4 == 0 && ld % 4 == 0 && ldz % 4 == 0 && (uintptr_t)d_W % 16 == 0 && (uintptr_t)d_Z % 16 == 0;
         hipLaunchKernelGGL(masked_copy_kernel, dim3((C + 255) / 256, (R + kMaskedCopyRows - 1) / kMaskedCopyRows), dim3(256), 0, st,
