@@ -58,7 +58,12 @@ struct LdsMap {
 };
 
 // Uniform copies of the records (every field through a scalar register).
-__device__ __forceinline__ ChunkRec load_chunk(const ChunkRec *p) {
+// The records a workgroup / wavefront starts from are read-only and their address is the same
+// for every lane: read through the constant address space they come in over the scalar path,
+// which answers sooner than a vector load and needs no lane to be picked afterwards.
+#define CSB_CONST_AS __attribute__((address_space(4)))
+__device__ __forceinline__ ChunkRec load_chunk(const ChunkRec *gp) {
+    const CSB_CONST_AS ChunkRec *p = (const CSB_CONST_AS ChunkRec *)gp;
     ChunkRec c;
     c.nzrank0 = uni(p->nzrank0); c.ntiles = uni(p->ntiles);
     c.sid_first = (int32_t)uni((uint32_t)p->sid_first); c.part_first = (int32_t)uni((uint32_t)p->part_first);
@@ -70,7 +75,8 @@ __device__ __forceinline__ ChunkRec load_chunk(const ChunkRec *p) {
     return c;
 }
 
-__device__ __forceinline__ WaveRec load_wave(const WaveRec *p) {
+__device__ __forceinline__ WaveRec load_wave(const WaveRec *gp) {
+    const CSB_CONST_AS WaveRec *p = (const CSB_CONST_AS WaveRec *)gp;
     WaveRec w;
     w.g_begin = uni(p->g_begin); w.g_end = uni(p->g_end);
     w.j_begin = (uint16_t)uni(p->j_begin); w.j_end = (uint16_t)uni(p->j_end);
