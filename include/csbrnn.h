@@ -310,7 +310,12 @@ int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
  * with batch 1 runs all timesteps of all layers in ONE kernel launch; without it, or for
  * batch > 1, it launches one CSB mat-vec per step and layer and needs every W[l] uploaded.
  * The resident kernel's workgroups wait for each other's h_t: they must all be on the GPU at
- * once, so nothing else should occupy the device while it runs.
+ * once, so nothing else should occupy the device while it runs.  The workgroups are placed on
+ * as few of the 8 XCDs as hold them (at most 28 per XCD, one per CU).
+ * Tuning knobs, read from the environment (for experiments; the defaults are the measured
+ * best): CSB_RNN_S = slots per lane of the resident layout (multiple of 4; read by
+ * csb_rnn_create*), CSB_RNN_XCDS = use at least this many XCDs, CSB_RNN_POLL_DELAY = sleeps
+ * before the first poll of a step (both read by csb_rnn_forward).
  */
 typedef struct {
     int32_t resident;          /* 1 if a resident layout exists                            */
