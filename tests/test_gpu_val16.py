@@ -137,3 +137,12 @@ def test_rnn(fmt, name, cell, L, I, H, T, B, block):
             e = max(e, float(np.max(np.abs(cT.cpu().numpy() - rcT))))
         say(f"[val16] rnn err {e:.3g}")
         assert e <= 1e-4
+
+
+@pytest.mark.parametrize("fmt,name", FORMATS)
+def test_spmv_full_size_stress(fmt, name):
+    """The 8192 x 8192 heavy-tailed matrix bench.py times, in its launch configuration (default
+    plan), every output row against the oracle."""
+    m = csb_inputs.make_mat(csb_inputs.CONFIGS["cfg5"])
+    x = csb_inputs.make_vectors(5, m.cols, 1)
+    check_spmv(m.A, m.br, m.bc, x, fmt, name, tag="cfg5")
