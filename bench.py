@@ -478,7 +478,7 @@ def cells_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
     """The shapes of two more of the paper's speech models (Table 1), synthetic weights, batch 1:
     SR3 = two Li-GRU layers 39 -> 512 -> 512 at 7.1x (resident and streaming path), and SR2 =
     two GRU layers 39 -> 1024 -> 1024 at 21.7x in the reset-before form (two dependent CSB
-    products per step: streaming path only) next to the reset-after form on both paths.  The
+    products per step) next to the reset-after form, each on the streaming and the resident path.  The
     paper's FPGA figure for its trained SR2 is 5.18 us per frame (context, not a baseline)."""
     from paper_2005_05758_amd import CELL_LIGRU, CELL_GRU_RB, CELL_GRU
     T = 100
@@ -529,6 +529,9 @@ def cells_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
     rb = CsbRnn(CELL_GRU_RB, 39, 1024, Was, bias, Wp=Uns)
     for m in Was + Uns:
         m.upload()
+    rbr = CsbRnn(CELL_GRU_RB, 39, 1024, [CsbMatrix(m.unpack(), m.br, m.bc) for m in Was], bias,
+                 Wp=[CsbMatrix(m.unpack(), m.br, m.bc) for m in Uns])
+    rbr.upload()
     Wg = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
     ga = CsbRnn(CELL_GRU, 39, 1024, Wg, bias)
     for m in Wg:
@@ -536,6 +539,8 @@ def cells_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
     gr = CsbRnn(CELL_GRU, 39, 1024, [CsbMatrix(m.A, m.br, m.bc) for m in wl.W], bias)
     gr.upload()
     res["gru_sr2"] = {"reset_before_streaming_us_per_frame": timed(rb, xd, 3),
+                      "reset_before_resident_us_per_frame": timed(rbr, xd, 20),
+                      "reset_before_resident_plan": rbr.stats(),
                       "reset_after_streaming_us_per_frame": timed(ga, xd, 3),
                       "reset_after_resident_us_per_frame": timed(gr, xd, 20),
                       "nnz": sum(int(m.view()["nnz"]) for m in Wg), "resident_plan": gr.stats()}

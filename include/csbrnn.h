@@ -292,8 +292,10 @@ int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hidden, int32_
  *          CSB_EINVAL);
  *   Un[l]: hidden x hidden, the recurrent side of the n rows.
  * Both packed; planned by this call if they are not yet; upload both with csb_upload.
- * d_bias[l]: 3*hidden floats (r,z,n) or NULL.  There is no resident layout for this cell
- * (csb_rnn_device_bytes is 0): csb_rnn_forward takes the streaming paths, per step and
+ * d_bias[l]: 3*hidden floats (r,z,n) or NULL.  Batch 1 with the resident layout uploaded
+ * (csb_rnn_upload): one kernel launch for the whole sequence, a layer being a reset stage
+ * (row r, output r * h_(t-1)) and a gate stage (rows z and n, the latter over the layer input
+ * and the reset stage's output of the same step); else the streaming paths, per step and
  * layer two CSB products and two element-wise kernels (batch > 1 on the matrix cores).
  * Errors as csb_rnn_create.
  */
@@ -305,7 +307,8 @@ int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
  * Resident layout of the whole model for batch-1 inference: every row's surviving weights
  * cut into equal slices, one slice per lane, kept in registers for the whole sequence (the
  * equal-work split of Sec. 5.2 applied to on-chip storage).  csb_rnn_device_bytes is 0 if
- * the model does not fit on chip.  After csb_rnn_upload (d_buf device, caller-owned,
+ * the model does not fit on chip (more than 224 workgroups' worth of weights, a layer input
+ * wider than 2048, or a stage whose inputs together are wider than 3072).  After csb_rnn_upload (d_buf device, caller-owned,
  * 256-byte aligned, >= csb_rnn_device_bytes, valid while the handle is used) csb_rnn_forward
  * with batch 1 runs all timesteps of all layers in ONE kernel launch; without it, or for
  * batch > 1, it launches one CSB mat-vec per step and layer and needs every W[l] uploaded.

@@ -44,8 +44,12 @@ constexpr bool kPhaseClocks = false;
 // The resident kernel works on a stack of stages.  An LSTM / GRU layer is one stage (its
 // units' gate rows); an LSTMP layer is two: the gate stage, whose output m_t is not state, and
 // a linear stage (the projection r_t = Wp m_t), whose output is the layer's state h and the
-// gate stage's recurrent input.
-constexpr uint32_t kStageLstm = 0, kStageGru = 1, kStageLinear = 2, kStageLiGru = 3;
+// gate stage's recurrent input.  A layer of the GRU with the reset gate before the candidate's
+// recurrent product is two as well: the reset stage (row r over [u ; h_(t-1)], output
+// q_t = r h_(t-1)) and the gate stage (row z over [u ; h_(t-1)], row n over u and over q_t, which
+// it takes from the reset stage at the same step as a third input; output h_t).
+constexpr uint32_t kStageLstm = 0, kStageGru = 1, kStageLinear = 2, kStageLiGru = 3, kStageGruRbReset = 4, kStageGruRbGate = 5;
+constexpr int kRnnReps = 3;              // z entries a thread stages: C <= kRnnReps * kRnnThreads
 constexpr uint32_t kStageOwnRec = 1;     // flag: the recurrent input is this stage's own output
 constexpr uint32_t kStageIsState = 2;    // flag: the output is the layer's h state (h0 / hT)
 constexpr uint32_t kStageIsSeq = 4;      // flag: the output is the model's output sequence
@@ -53,11 +57,11 @@ constexpr uint32_t kNoStage = 0xffffffffu;
 
 // One workgroup of the resident kernel.
 struct RnnWgRec {
-    uint32_t layer;           // stage
+    uint32_t aux;             // owner-table offset of a third input stage (same step, behind the recurrent input), or kNoStage
     uint32_t u0, nu;          // units [u0, u0 + nu) of the stage
     uint32_t nlanes;          // lanes that hold a slice of a row
     uint32_t S;               // slots per lane
-    uint32_t n_in, C;         // width of the input from below, C = n_in + width of the recurrent input
+    uint32_t n_in, C;         // width of the input from below, C = n_in + width of the recurrent input (+ width of the third)
     uint32_t off_rows;        // byte offset of the lane table: 1024 words (segment position, flags, row slot)
     uint32_t off_w;           // byte offset of weights  [S][1024] float
     uint32_t off_z;           // byte offset of z indices [S][1024] u16
@@ -168,25 +172,60 @@ static void gather_linear_rows(const csb_matrix *m, int width,
         }
 }
 
+// Rows [row0, row0 + nrows) of a matrix appended to rows[dst_row0 + (row - row0)], their columns
+// shifted by col_shift (entries arrive in column order per call).
+static void append_rows(const csb_matrix *m, int row0, int nrows, int dst_row0, int col_shift,
+                        std::vector<std::vector<std::pair<uint32_t, float>>> &rows) {
+    for (int32_t bi = 0; bi < m->nbr; ++bi)
+        for (int32_t bj = 0; bj < m->nbc; ++bj) {
+            const size_t b = (size_t)bi * m->nbc + bj;
+            const int nr = m->nrows[b], nc = m->ncols[b];
+            for (int a = 0; a < nr; ++a) {
+                const int64_t gr = (int64_t)bi * m->br + m->rowidx[m->row_off[b] + a];
+                if (gr < row0 || gr >= (int64_t)row0 + nrows) continue;
+                for (int q = 0; q < nc; ++q)
+                    rows[(size_t)(dst_row0 + gr - row0)].emplace_back(
+                        (uint32_t)((int64_t)bj * m->bc + m->colidx[m->col_off[b] + q] + col_shift),
+                        m->val[m->val_off[b] + (size_t)a * nc + q]);
+            }
+        }
+}
+
 static int build_resident_plan(csb_rnn *r) {
     RnnPlan &pl = r->plan;
     pl = RnnPlan{};
-    if (r->cell == CSB_CELL_GRU_RB) return CSB_EUNSUPPORTED;   // two dependent products per step: streaming paths only
-    const bool lstmp = r->cell == CSB_CELL_LSTMP;
-    const int NL = r->n_layers, L = lstmp ? 2 * NL : NL;      // L stages
+    const bool lstmp = r->cell == CSB_CELL_LSTMP, gru_rb = r->cell == CSB_CELL_GRU_RB;
+    const int NL = r->n_layers, L = (lstmp || gru_rb) ? 2 * NL : NL;      // L stages
     struct LayerTmp {
         std::vector<std::vector<std::pair<uint32_t, float>>> rows;
         int n_in, C, S, P;
         int width;                  // units of the stage
         uint32_t kind, real, flags;
-        int below, rec;             // stage indices, -1 = x / none
+        int below, rec, aux = -1;   // stage indices, -1 = x / none
         std::vector<int> u_cut;     // unit ranges per workgroup
     };
     std::vector<LayerTmp> lt(L);
     size_t total_nnz = 0;
     for (int l = 0; l < L; ++l) {
         LayerTmp &t = lt[l];
-        if (!lstmp) {
+        if (gru_rb) {
+            const int lam = l / 2, H = r->hidden;
+            t.width = H; t.real = (uint32_t)lam;
+            t.n_in = lam == 0 ? r->input : H;
+            t.below = lam == 0 ? -1 : 2 * lam - 1;           // the gate stage of the layer below
+            t.rows.assign((size_t)4 * H, {});
+            if ((l & 1) == 0) {                              // reset stage: row r
+                t.kind = kStageGruRbReset;
+                t.C = t.n_in + H; t.rec = l + 1; t.flags = 0;
+                append_rows(r->W[lam], 0, H, 0, 0, t.rows);
+            } else {                                         // gate stage: rows z and n
+                t.kind = kStageGruRbGate;
+                t.C = t.n_in + 2 * H; t.rec = l; t.aux = l - 1;
+                t.flags = kStageOwnRec | kStageIsState | (l == L - 1 ? kStageIsSeq : 0u);
+                append_rows(r->W[lam], H, 2 * H, 0, 0, t.rows);          // z, n (input side) -> rows 0..2H
+                append_rows(r->Wp[lam], 0, H, H, t.n_in + H, t.rows);    // Un -> the n rows, columns behind h
+            }
+        } else if (!lstmp) {
             t.width = r->hidden; t.real = (uint32_t)l;
             t.kind = r->cell == CSB_CELL_LSTM ? kStageLstm : (r->cell == CSB_CELL_LIGRU ? kStageLiGru : kStageGru);
             t.n_in = l == 0 ? r->input : r->hidden;
@@ -208,7 +247,7 @@ static int build_resident_plan(csb_rnn *r) {
             t.flags = kStageIsState | (l == L - 1 ? kStageIsSeq : 0u);
             gather_linear_rows(r->Wp[l / 2], r->proj, t.rows);
         }
-        if (t.C + 1 > 16000) return CSB_EUNSUPPORTED;            // z indices are 16 bit, LDS holds z
+        if (t.C > kRnnReps * kRnnThreads || t.n_in > 2 * kRnnThreads) return CSB_EUNSUPPORTED;   // z entries a thread stages
         pl.cmax = std::max<size_t>(pl.cmax, (size_t)t.C);
         for (auto &row : t.rows) total_nnz += row.size();
     }
@@ -292,7 +331,7 @@ static int build_resident_plan(csb_rnn *r) {
         smax = std::max(smax, t.S);
         for (int p = 0; p < t.P; ++p) {
             RnnWgRec w{};
-            w.layer = (uint32_t)l; w.u0 = (uint32_t)t.u_cut[p]; w.nu = (uint32_t)(t.u_cut[p + 1] - t.u_cut[p]);
+            w.aux = t.aux < 0 ? kNoStage : (uint32_t)uoff[t.aux]; w.u0 = (uint32_t)t.u_cut[p]; w.nu = (uint32_t)(t.u_cut[p + 1] - t.u_cut[p]);
             w.S = (uint32_t)t.S; w.n_in = (uint32_t)t.n_in; w.C = (uint32_t)t.C;
             w.upre = upre_run; upre_run += w.nu;
             w.kind = t.kind | t.real << 8 | t.flags << 16;
@@ -474,6 +513,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     const uint32_t kword = __builtin_amdgcn_readfirstlane(wg.kind);
     const uint32_t kind = kword & 0xffu, real = (kword >> 8) & 0xffu, flags = kword >> 16;
     const bool lstm = kind == kStageLstm, ligru = kind == kStageLiGru, linear = !PLAIN && kind == kStageLinear;
+    const bool rb_reset = !PLAIN && kind == kStageGruRbReset, rb_gate = !PLAIN && kind == kStageGruRbGate;
     const bool from_x = __builtin_amdgcn_readfirstlane(wg.below) == kNoStage;
     const bool own_rec = PLAIN || (flags & kStageOwnRec) != 0, is_state = PLAIN || (flags & kStageIsState) != 0;
     float *z = lds;                       // [C + 1], z[C] = 0
@@ -509,6 +549,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         const uint32_t g = row_slot / nu, ui = row_slot - g * nu;
         const float *b = A.bias[real];
         if (lstm) { act = g == 2 ? 2u : 1u; if (b) row_bias = b[g * H + wg.u0 + ui]; }
+        else if (rb_reset) { act = 1u; if (b && g == 0) row_bias = b[wg.u0 + ui]; }                         // r
+        else if (rb_gate) { act = g == 0 ? 1u : 0u; if (b && g < 2) row_bias = b[(g + 1) * H + wg.u0 + ui]; }  // z, n
         else if (ligru) { act = g == 0 ? 1u : 0u; if (b && g < 2) row_bias = b[g * H + wg.u0 + ui]; }
         else { act = g < 2 ? 1u : 0u; if (b && g < 3) row_bias = b[g * H + wg.u0 + ui]; }
     }
@@ -532,6 +574,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         const float *b = linear ? nullptr : A.bias[real];
         float v = 0.0f;
         if (lstm) { if (b) v = b[g * H + wg.u0 + ui]; v = g == 2 ? fast_tanh(v) : fast_sigmoid(v); }
+        else if (rb_reset) { if (b && g == 0) v = b[wg.u0 + ui]; if (g == 0) v = fast_sigmoid(v); }
+        else if (rb_gate) { if (b && g < 2) v = b[(g + 1) * H + wg.u0 + ui]; if (g == 0) v = fast_sigmoid(v); }
         else if (ligru) { if (b && g < 2) v = b[g * H + wg.u0 + ui]; if (g == 0) v = fast_sigmoid(v); }
         else if (!linear) { if (b && g < 3) v = b[g * H + wg.u0 + ui]; if (g < 2) v = fast_sigmoid(v); }
         arow[i] = v;
@@ -552,17 +596,18 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     // polled entry has the address of its word at step 0 (one step's stride back for a
     // recurrent one, whose first poll is at step 1), the words per step of the workgroup that
     // publishes it, and the tag it carries at step 0.
-    const unsigned long long *pp[2] = {nullptr, nullptr};
-    uint32_t pstride[2] = {0, 0}, ptmin[2] = {~0u, ~0u}, ptag[2] = {0, 0};
+    const unsigned long long *pp[kRnnReps] = {nullptr, nullptr, nullptr};
+    uint32_t pstride[kRnnReps] = {0, 0, 0}, ptmin[kRnnReps] = {~0u, ~0u, ~0u}, ptag[kRnnReps] = {0, 0, 0};
+    const uint32_t rec_end = n_in + wg.rec_width;      // entries behind it come from the third input (same step)
 #pragma unroll
-    for (int rep = 0; rep < 2; ++rep) {
+    for (int rep = 0; rep < kRnnReps; ++rep) {
         const uint32_t e = zt + rep * kRnnThreads;
         if (e >= C) continue;
-        const bool rec = e >= n_in;
-        const uint32_t us = rec ? e - n_in : e;
+        const bool rec = e >= n_in && e < rec_end, third = e >= rec_end;
+        const uint32_t us = third ? e - rec_end : (rec ? e - n_in : e);
         if (rec) z[e] = A.h0 ? A.h0[(size_t)real * wg.rec_width + us] : 0.0f;
-        if (rec ? (own_rec && us - wg.u0 < nu) : from_x) continue;
-        const RnnWgRec *q = (const RnnWgRec *)A.img + unit_wg[(size_t)(rec ? wg.rec : wg.below) + us];
+        if (rec ? (own_rec && us - wg.u0 < nu) : (!third && from_x)) continue;
+        const RnnWgRec *q = (const RnnWgRec *)A.img + unit_wg[(size_t)(third ? wg.aux : (rec ? wg.rec : wg.below)) + us];
         const uint32_t back = rec ? 1u : 0u;
         pp[rep] = A.seq + ((size_t)T * q->upre + (us - q->u0)) - (size_t)back * q->nu;
         pstride[rep] = q->nu;
@@ -577,8 +622,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         if (xl1) xnext1 = A.x[zt + kRnnThreads];
     }
     // does this wavefront poll at all (any lane with a remote source)?
-    const bool polls = __ballot(ptmin[0] != ~0u || ptmin[1] != ~0u) != 0ull;
-    const bool two = C > kRnnThreads;           // second entries exist
+    const bool polls = __ballot(ptmin[0] != ~0u || ptmin[1] != ~0u || ptmin[2] != ~0u) != 0ull;
+    const bool two = C > kRnnThreads, three = C > 2 * kRnnThreads;           // second / third entries exist
     uint32_t delay = A.poll_delay, streak = 0;
     unsigned long long wave_arrive = 0, after_b = 0;
     unsigned long long ph0 = 0, ph1 = 0, ph2 = 0, ph3 = 0, c0_ = 0, c1_ = 0;
@@ -596,6 +641,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         bool retried = false;
         if (t >= ptmin[0]) z[zt] = poll_word(pp[0] + (size_t)t * pstride[0], ptag[0] + t, retried);
         if (two && t >= ptmin[1]) z[zt + kRnnThreads] = poll_word(pp[1] + (size_t)t * pstride[1], ptag[1] + t, retried);
+        if (three && t >= ptmin[2]) z[zt + 2 * kRnnThreads] = poll_word(pp[2] + (size_t)t * pstride[2], ptag[2] + t, retried);
         if (kPhaseClocks && A.dbg && blockIdx.x == 0 && (tid & 63u) == 0 && t > 0) wave_arrive += __builtin_readcyclecounter() - after_b;
         if (polls) {
             if (__ballot(retried) != 0ull) { delay += 3; streak = 0; }
@@ -652,6 +698,10 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
             float hn;
             if (linear) {                                // the row sum is the output
                 hn = a0;
+            } else if (rb_reset) {                       // r activated: hand on q = r h_(t-1)
+                hn = a0 * z[n_in + unit];
+            } else if (rb_gate) {                        // z activated; n: input side + Un q (+ bias)
+                hn = (1.0f - a0) * fast_tanh(a1) + a0 * h_state;
             } else if (lstm) {                           // activated rows i, f, g, o
                 const float cn = a1 * c_state + a0 * a2;
                 hn = a3 * fast_tanh(cn);
@@ -878,7 +928,9 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     w.off_c = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     w.off_part = off; off = align256(off + part);
     w.off_biasptr = off; off = align256(off + (size_t)r->n_layers * sizeof(void *));
-    w.off_seq = off; off = align256(off + (size_t)r->n_layers * (size_t)std::max(T, 1) * (size_t)(r->hidden + r->proj) * 8);
+    // exchange words of the resident kernel: one per unit of every stage and step
+    const size_t seq_units = r->plan.valid ? r->plan.total_units : 0;
+    w.off_seq = off; off = align256(off + (size_t)std::max(T, 1) * seq_units * 8);
     if (batch > 1) {
         w.off_hint = off; off = align256(off + (size_t)r->n_layers * batch * HS * sizeof(float));
         w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
@@ -934,7 +986,7 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     };
     hipError_t e;
     const int smax = r->plan.smax;
-    if (r->cell != CSB_CELL_LSTMP) {
+    if (r->cell != CSB_CELL_LSTMP && r->cell != CSB_CELL_GRU_RB) {      // one stage per layer
         if (smax <= 4) e = go(rnn_resident_kernel<4, true>);
         else if (smax <= 8) e = go(rnn_resident_kernel<8, true>);
         else if (smax <= 12) e = go(rnn_resident_kernel<12, true>);
@@ -1081,7 +1133,8 @@ extern "C" int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hi
             r->Wp.push_back(Un[l]);
             r->d_bias.push_back(d_bias ? d_bias[l] : nullptr);
         }
-        *out = r;                                   // no resident layout for this cell
+        if (n_layers <= 8) build_resident_plan(r);     // stays invalid if the model does not fit on chip
+        *out = r;
         return CSB_OK;
     } catch (const std::bad_alloc &) {
         set_error("csb_rnn_create_gru_rb: out of host memory");

@@ -1,7 +1,7 @@
 """Parity of the further cells of Table 1 / Sec. 2.1 against the float64 oracle, through the
 C ABI: Li-GRU (csb_rnn_create with CSB_CELL_LIGRU; streaming, resident and batched paths) and
 the GRU with the reset gate before the candidate's recurrent product (csb_rnn_create_gru_rb;
-streaming and batched paths).  max |h - oracle| <= 1e-4 on every h_t and h_T; the Li-GRU's
+streaming, resident and batched paths).  max |h - oracle| <= 1e-4 on every h_t and h_T; the Li-GRU's
 state is not bounded by 1 (its candidate is a ReLU), so there the bound is 1e-4 times
 max(1, max |h|) and the weights are drawn small enough for the recurrence to stay stable."""
 import sys
@@ -94,6 +94,9 @@ def test_gru_rb_small(L, I, H, T, B, block):
     h0 = np.random.default_rng(2).uniform(-0.5, 0.5, (L, B, H)).astype(np.float32).astype(np.float64)
     run_case(wl, h0, tag="gru_rb")
     run_case(wl, None, tag="gru_rb-zero-state")
+    if B == 1:
+        run_case(wl, h0, tag="gru_rb-resident", resident=True)
+        run_case(wl, None, tag="gru_rb-resident-zero-state", resident=True)
 
 
 def test_ligru_speech_model_shape():
@@ -110,6 +113,8 @@ def test_gru_rb_speech_model_shape():
     and batch 16."""
     wl = workload(csb_inputs.GRU_RB, 2, 39, 1024, 12, 1, 32, seed=0, rate=21.7, sigma=0.05)
     run_case(wl, tag="sr2-rb")
+    rnn = run_case(wl, tag="sr2-rb-resident", resident=True)      # the gate stages stage 39 + 2 x 1024 inputs: three per thread
+    say(f"[cells] sr2-rb resident plan {rnn.stats()}")
     wl = workload(csb_inputs.GRU_RB, 2, 39, 1024, 6, 16, 32, seed=1, rate=21.7, sigma=0.05)
     run_case(wl, tag="sr2-rb-batch16")
 

@@ -103,6 +103,18 @@ def test_rnn_batched_many_row_tiles(cell):
         run_case(wl, tag=f"many-tiles-B{B}", resident=False)
 
 
+@pytest.mark.parametrize("cell,I,H", [(csb_inputs.LSTM, 1100, 1000), (csb_inputs.GRU, 40, 1500), (csb_inputs.LSTM, 2040, 700)])
+def test_rnn_resident_wide_inputs(cell, I, H):
+    """Input plus state wider than 2048: a thread of the resident kernel stages three entries
+    (and layer 0 reads two input words per thread when the input alone is wider than 1024)."""
+    cfg = csb_inputs.RnnConfig("t", cell, 1, I, H, 50, 40.0, "binomial", 0.05, 1, 4, 17)
+    wl = csb_inputs.make_rnn(cfg)
+    rng = np.random.default_rng(3)
+    h0 = rng.uniform(-0.5, 0.5, (1, 1, H)).astype(np.float32).astype(np.float64)
+    c0 = rng.uniform(-0.5, 0.5, (1, 1, H)).astype(np.float32).astype(np.float64) if cell == csb_inputs.LSTM else None
+    run_case(wl, h0, c0, tag="wide-inputs", resident=True)
+
+
 def test_rnn_batched_full_size_sampled():
     """cfg4 as bench.py runs it (2 x LSTM 1024 -> 1024, batch 64, T = 256, the MFMA path).  The
     sequences of a batch are independent, so the float64 oracle runs three sampled ones on

@@ -251,3 +251,23 @@ def test_value_format_plan_sweep():
             for n_chunks in (0, 1, 3):
                 M.plan(n_chunks)
                 M.validate()
+
+
+def test_resident_layout_limits():
+    """csb_rnn_create is host work: a model whose stage inputs are wider than a workgroup can
+    stage gets no resident layout (and still has the streaming paths); a small one gets it."""
+    from paper_2005_05758_amd import CsbRnn, CELL_LSTM, CELL_GRU_RB
+    wl = csb_inputs.make_rnn(csb_inputs.RnnConfig("t", csb_inputs.LSTM, 1, 2100, 1000, 50, 40.0, "binomial", 0.05, 1, 1, 0))
+    rnn = CsbRnn(CELL_LSTM, 2100, 1000, [CsbMatrix(wl.W[0].A, 50, 50)], None)       # 2100 + 1000 > 3072
+    assert rnn.stats()["resident"] == 0 and rnn.device_bytes() == 0
+    wl = csb_inputs.make_rnn(csb_inputs.RnnConfig("t", csb_inputs.LSTM, 1, 1500, 1500, 50, 40.0, "binomial", 0.05, 1, 1, 0))
+    rnn = CsbRnn(CELL_LSTM, 1500, 1500, [CsbMatrix(wl.W[0].A, 50, 50)], None)       # 3000: three entries per thread
+    assert rnn.stats()["resident"] == 1
+    wl = csb_inputs.make_rnn(csb_inputs.RnnConfig("t", csb_inputs.GRU_RB, 2, 24, 64, 8, 4.0, "binomial", 0.1, 1, 1, 0))
+    Was, Uns = [], []
+    for l, m in enumerate(wl.W):
+        Wa, Un = csb_inputs.split_gru_rb(m.A, 24 if l == 0 else 64, 64)
+        Was.append(CsbMatrix(Wa, 8, 8)); Uns.append(CsbMatrix(Un, 8, 8))
+    rnn = CsbRnn(CELL_GRU_RB, 24, 64, Was, None, Wp=Uns)
+    st = rnn.stats()
+    assert st["resident"] == 1 and st["n_workgroups"] >= 4                      # two stages per layer
