@@ -495,8 +495,9 @@ __device__ __forceinline__ float poll_word(const unsigned long long *word, uint3
     return (uint32_t)(v >> 32) == tag ? __uint_as_float((uint32_t)v) : __builtin_nanf("");
 }
 
-// PLAIN: every stage is an LSTM / GRU layer (its own recurrent source, its output the layer's
-// state), so the stage-kind tests of the time loop fold away at compile time.
+// PLAIN: every stage is an LSTM / GRU / Li-GRU layer (its own recurrent source, its output the
+// layer's state) with inputs at most 2048 wide, so the stage-kind tests and the third z entry
+// of the time loop fold away at compile time.
 template <int SMAX, bool PLAIN>
 __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs A) {
     extern __shared__ float lds[];
@@ -623,7 +624,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     }
     // does this wavefront poll at all (any lane with a remote source)?
     const bool polls = __ballot(ptmin[0] != ~0u || ptmin[1] != ~0u || ptmin[2] != ~0u) != 0ull;
-    const bool two = C > kRnnThreads, three = C > 2 * kRnnThreads;           // second / third entries exist
+    const bool two = C > kRnnThreads, three = !PLAIN && C > 2 * kRnnThreads;           // second / third entries exist
     uint32_t delay = A.poll_delay, streak = 0;
     unsigned long long wave_arrive = 0, after_b = 0;
     unsigned long long ph0 = 0, ph1 = 0, ph2 = 0, ph3 = 0, c0_ = 0, c1_ = 0;
@@ -986,7 +987,8 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     };
     hipError_t e;
     const int smax = r->plan.smax;
-    if (r->cell != CSB_CELL_LSTMP && r->cell != CSB_CELL_GRU_RB) {      // one stage per layer
+    // one stage per layer and at most two entries per thread: the specialised form
+    if (r->cell != CSB_CELL_LSTMP && r->cell != CSB_CELL_GRU_RB && cmax <= 2 * (size_t)kRnnThreads) {
         if (smax <= 4) e = go(rnn_resident_kernel<4, true>);
         else if (smax <= 8) e = go(rnn_resident_kernel<8, true>);
         else if (smax <= 12) e = go(rnn_resident_kernel<12, true>);
