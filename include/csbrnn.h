@@ -324,7 +324,7 @@ typedef struct {
     int32_t resident;          /* 1 if a resident layout exists                            */
     int32_t n_workgroups;      /* workgroups (all layers)                                  */
     int32_t slots_per_lane;    /* multiply-adds every lane issues per step (largest layer) */
-    int32_t reserved;
+    int32_t reserved;          /* (diagnostic) words left sharing an LDS bank within a 32-lane gather */
     double slot_fill;          /* non-zeros / issued multiply-adds (1 = no padding)        */
     double lanes_max_over_mean;/* largest / mean number of busy lanes per workgroup        */
 } csb_rnn_plan_stats;

@@ -59,7 +59,7 @@ constexpr uint32_t kNoStage = 0xffffffffu;
 struct RnnWgRec {
     uint32_t aux;             // owner-table offset of a third input stage (same step, behind the recurrent input), or kNoStage
     uint32_t u0, nu;          // units [u0, u0 + nu) of the stage
-    uint32_t nlanes;          // lanes that hold a slice of a row
+    uint32_t off_zpos;        // byte offset of the z permutation: u16 position in LDS of every input entry [C]
     uint32_t S;               // slots per lane
     uint32_t n_in, C;         // width of the input from below, C = n_in + width of the recurrent input (+ width of the third)
     uint32_t off_rows;        // byte offset of the lane table: 1024 words (segment position, flags, row slot)
@@ -83,6 +83,7 @@ struct RnnPlan {
     size_t cmax = 0;           // largest C of any stage (LDS sizing)
     double slot_fill = 0;      // non-zeros / (1024 * S * workgroups): the useful share of issued multiply-adds
     double lanes_max_over_mean = 0;
+    long lds_conflicts = 0;    // words that share an LDS bank with another word of the same 32-lane gather (all workgroups)
 };
 
 }  // namespace csb
@@ -324,6 +325,7 @@ static int build_resident_plan(csb_rnn *r) {
     std::vector<uint16_t> unit_wg(uoff[L], 0);
     pl.total_units = uoff[L];
     int smax = 0;
+    long conflicts_total = 0;
     double lanes_max = 0, lanes_sum = 0;
     for (int l = 0; l < L; ++l) {
         const LayerTmp &t = lt[l];
@@ -367,33 +369,92 @@ static int build_resident_plan(csb_rnn *r) {
                 }
             }
             // Which of a lane's S slots each of its entries takes is free (it only fixes the
-            // order of the lane's sum).  The LDS serves 32 lanes at a time from 32 banks of
-            // 4 bytes: place the entries so that, slot by slot, the 32 lanes of a half
-            // wavefront hit different banks, or the very same word, as far as possible.
-            for (uint32_t h0 = 0; h0 < (uint32_t)kRnnThreads; h0 += 32) {
-                std::vector<std::vector<uint32_t>> seen((size_t)t.S * 32);   // [slot][bank] -> distinct words
-                for (uint32_t ln = h0; ln < h0 + 32; ++ln) {
-                    std::vector<char> used(t.S, 0);
-                    for (auto &el : lane_elems[ln]) {
-                        const uint32_t bank = el.first & 31u;
-                        int best = -1, best_cost = 1 << 30;
-                        for (int sl = 0; sl < t.S; ++sl) {
-                            if (used[sl]) continue;
-                            auto &words = seen[(size_t)sl * 32 + bank];
-                            int cost = (int)words.size() * 2;
-                            for (uint32_t wd : words) if (wd == el.first) { cost = -1; break; }   // broadcast
-                            if (cost < best_cost) { best_cost = cost; best = sl; }
+            // order of the lane's sum), and so is the place of every input entry in the staged
+            // vector (each workgroup stages its own copy).  The LDS serves 32 lanes at a time
+            // from 32 banks of 4 bytes: choose slots and places so that, slot by slot, the 32
+            // lanes of a half wavefront hit different banks, or the very same word, as far as
+            // possible.  Slots are chosen greedily for given places, places (a bank per entry,
+            // every bank filled to its share of [0, C)) greedily for given slots, in turn.
+            std::vector<uint16_t> zpos((size_t)t.C);
+            for (int e = 0; e < t.C; ++e) zpos[(size_t)e] = (uint16_t)e;
+            std::vector<std::vector<int>> slot_of(kRnnThreads);          // per lane: slot of each of its entries
+            auto assign_slots = [&](const std::vector<uint16_t> &pos) -> long {
+                long cost_total = 0;
+                for (uint32_t h0 = 0; h0 < (uint32_t)kRnnThreads; h0 += 32) {
+                    std::vector<std::vector<uint32_t>> seen((size_t)t.S * 32);   // [slot][bank] -> distinct words
+                    for (uint32_t ln = h0; ln < h0 + 32; ++ln) {
+                        std::vector<char> used(t.S, 0);
+                        slot_of[ln].assign(lane_elems[ln].size(), 0);
+                        for (size_t k = 0; k < lane_elems[ln].size(); ++k) {
+                            const uint32_t col = lane_elems[ln][k].first, bank = pos[col] & 31u;
+                            int best = -1, best_cost = 1 << 30;
+                            for (int sl = 0; sl < t.S; ++sl) {
+                                if (used[sl]) continue;
+                                auto &words = seen[(size_t)sl * 32 + bank];
+                                int cost = (int)words.size() * 2;
+                                for (uint32_t wd : words) if (wd == col) { cost = -1; break; }   // broadcast
+                                if (cost < best_cost) { best_cost = cost; best = sl; }
+                            }
+                            used[best] = 1;
+                            auto &words = seen[(size_t)best * 32 + bank];
+                            if (std::find(words.begin(), words.end(), col) == words.end()) {
+                                cost_total += (long)words.size() ? 1 : 0;             // one more word in an occupied bank
+                                words.push_back(col);
+                            }
+                            slot_of[ln][k] = best;
                         }
-                        used[best] = 1;
-                        auto &words = seen[(size_t)best * 32 + bank];
-                        if (std::find(words.begin(), words.end(), el.first) == words.end()) words.push_back(el.first);
-                        wv[(size_t)best * kRnnThreads + ln] = el.second;
-                        zi[(size_t)best * kRnnThreads + ln] = (uint16_t)el.first;
                     }
                 }
+                return cost_total;
+            };
+            auto choose_places = [&](std::vector<uint16_t> &pos) {
+                // groups = (half wavefront, slot); an entry should not share a bank with another
+                // entry of any of its groups
+                const size_t n_groups = (size_t)(kRnnThreads / 32) * t.S;
+                std::vector<std::vector<uint32_t>> groups_of((size_t)t.C);
+                for (uint32_t ln = 0; ln < (uint32_t)kRnnThreads; ++ln)
+                    for (size_t k = 0; k < lane_elems[ln].size(); ++k) {
+                        auto &gl = groups_of[lane_elems[ln][k].first];
+                        const uint32_t gid = (ln / 32) * (uint32_t)t.S + (uint32_t)slot_of[ln][k];
+                        if (std::find(gl.begin(), gl.end(), gid) == gl.end()) gl.push_back(gid);
+                    }
+                std::vector<int> order((size_t)t.C);
+                for (int e = 0; e < t.C; ++e) order[(size_t)e] = e;
+                std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return groups_of[(size_t)x].size() > groups_of[(size_t)y].size(); });
+                std::vector<uint8_t> cnt(n_groups * 32, 0);                           // [group][bank] entries placed
+                int cap[32], fill[32];
+                for (int bk = 0; bk < 32; ++bk) { cap[bk] = (t.C - bk + 31) / 32; fill[bk] = 0; }
+                for (int e : order) {
+                    int best = -1;
+                    long best_cost = 1L << 60;
+                    for (int bk = 0; bk < 32; ++bk) {
+                        if (fill[bk] >= cap[bk]) continue;
+                        long c = 0;
+                        for (uint32_t gid : groups_of[(size_t)e]) c += cnt[(size_t)gid * 32 + bk];
+                        c = c * 64 + fill[bk];                                        // ties: the emptier bank
+                        if (c < best_cost) { best_cost = c; best = bk; }
+                    }
+                    for (uint32_t gid : groups_of[(size_t)e]) if (cnt[(size_t)gid * 32 + best] < 255) ++cnt[(size_t)gid * 32 + best];
+                    pos[(size_t)e] = (uint16_t)(best + 32 * fill[best]);
+                    ++fill[best];
+                }
+            };
+            long best_cost = assign_slots(zpos);
+            const long first_cost = best_cost;
+            for (int round = 0; round < 2 && best_cost > 0; ++round) {
+                std::vector<uint16_t> trial = zpos;
+                choose_places(trial);
+                const long c = assign_slots(trial);
+                if (c < best_cost) { best_cost = c; zpos = trial; } else { assign_slots(zpos); break; }
             }
+            conflicts_total += best_cost;
+            if (getenv("CSB_RNN_VERBOSE")) fprintf(stderr, "wg %zu: bank conflicts %ld -> %ld\n", wgs.size(), first_cost, best_cost);
+            for (uint32_t ln = 0; ln < (uint32_t)kRnnThreads; ++ln)
+                for (size_t k = 0; k < lane_elems[ln].size(); ++k) {
+                    wv[(size_t)slot_of[ln][k] * kRnnThreads + ln] = lane_elems[ln][k].second;
+                    zi[(size_t)slot_of[ln][k] * kRnnThreads + ln] = zpos[lane_elems[ln][k].first];
+                }
             if (lane > (uint32_t)kRnnThreads) { set_error("csb_rnn_create: internal: lane overflow"); return CSB_EINVAL; }
-            w.nlanes = busy;
             align(256);
             w.off_rows = (uint32_t)body.size();
             body.insert(body.end(), (uint8_t *)lanetab.data(), (uint8_t *)(lanetab.data() + lanetab.size()));
@@ -403,6 +464,9 @@ static int build_resident_plan(csb_rnn *r) {
             align(256);
             w.off_z = (uint32_t)body.size();
             body.insert(body.end(), (uint8_t *)zi.data(), (uint8_t *)(zi.data() + zi.size()));
+            align(256);
+            w.off_zpos = (uint32_t)body.size();
+            body.insert(body.end(), (uint8_t *)zpos.data(), (uint8_t *)(zpos.data() + zpos.size()));
             wgs.push_back(w);
             slots_total += (size_t)kRnnThreads * t.S;
             lanes_max = std::max<double>(lanes_max, busy);
@@ -416,13 +480,14 @@ static int build_resident_plan(csb_rnn *r) {
     const size_t hdr = (wgs.size() * sizeof(RnnWgRec) + 255) / 256 * 256;
     pl.off_unit_wg = hdr + off_uw_body;
     pl.image.assign(hdr + body.size() + 256, 0);
-    for (auto &w : wgs) { w.off_rows += (uint32_t)hdr; w.off_w += (uint32_t)hdr; w.off_z += (uint32_t)hdr; }
+    for (auto &w : wgs) { w.off_rows += (uint32_t)hdr; w.off_w += (uint32_t)hdr; w.off_z += (uint32_t)hdr; w.off_zpos += (uint32_t)hdr; }
     std::memcpy(pl.image.data(), wgs.data(), wgs.size() * sizeof(RnnWgRec));
     std::memcpy(pl.image.data() + hdr, body.data(), body.size());
     pl.n_wgs = (int)wgs.size();
     pl.smax = smax;
     pl.slot_fill = slots_total ? (double)total_nnz / (double)slots_total : 0.0;
     pl.lanes_max_over_mean = lanes_sum > 0 ? lanes_max / (lanes_sum / (double)wgs.size()) : 0.0;
+    pl.lds_conflicts = conflicts_total;
     pl.valid = true;
     return CSB_OK;
 }
@@ -564,6 +629,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     uint32_t scan_mb = seg_pos >= 16 ? ~0u : 0u;
     asm volatile("" : "+v"(scan_m1), "+v"(scan_m2), "+v"(scan_m4), "+v"(scan_m8), "+v"(scan_mb));
     float c_state = 0.0f, h_state = 0.0f;
+    // where this owner's unit sits in the staged vector's recurrent part (if that part is this stage's own or its state)
+    const uint32_t zown = (owner && n_in + unit < C) ? ((const uint16_t *)(A.img + wg.off_zpos))[n_in + unit] : C;
     if (owner) {
         if (A.c0 && lstm) c_state = A.c0[(size_t)real * H + unit];
         if (A.h0 && is_state) h_state = A.h0[(size_t)real * wg.width + unit];
@@ -597,6 +664,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     // polled entry has the address of its word at step 0 (one step's stride back for a
     // recurrent one, whose first poll is at step 1), the words per step of the workgroup that
     // publishes it, and the tag it carries at step 0.
+    const uint16_t *zpos = (const uint16_t *)(A.img + wg.off_zpos);       // where entry e lives in z
+    uint32_t zp[kRnnReps] = {C, C, C};
     const unsigned long long *pp[kRnnReps] = {nullptr, nullptr, nullptr};
     uint32_t pstride[kRnnReps] = {0, 0, 0}, ptmin[kRnnReps] = {~0u, ~0u, ~0u}, ptag[kRnnReps] = {0, 0, 0};
     const uint32_t rec_end = n_in + wg.rec_width;      // entries behind it come from the third input (same step)
@@ -604,9 +673,10 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     for (int rep = 0; rep < kRnnReps; ++rep) {
         const uint32_t e = zt + rep * kRnnThreads;
         if (e >= C) continue;
+        zp[rep] = zpos[e];
         const bool rec = e >= n_in && e < rec_end, third = e >= rec_end;
         const uint32_t us = third ? e - rec_end : (rec ? e - n_in : e);
-        if (rec) z[e] = A.h0 ? A.h0[(size_t)real * wg.rec_width + us] : 0.0f;
+        if (rec) z[zp[rep]] = A.h0 ? A.h0[(size_t)real * wg.rec_width + us] : 0.0f;
         if (rec ? (own_rec && us - wg.u0 < nu) : (!third && from_x)) continue;
         const RnnWgRec *q = (const RnnWgRec *)A.img + unit_wg[(size_t)(third ? wg.aux : (rec ? wg.rec : wg.below)) + us];
         const uint32_t back = rec ? 1u : 0u;
@@ -640,17 +710,17 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         if (polls)
             for (uint32_t d = 0; d < delay; ++d) __builtin_amdgcn_s_sleep(1);
         bool retried = false;
-        if (t >= ptmin[0]) z[zt] = poll_word(pp[0] + (size_t)t * pstride[0], ptag[0] + t, retried);
-        if (two && t >= ptmin[1]) z[zt + kRnnThreads] = poll_word(pp[1] + (size_t)t * pstride[1], ptag[1] + t, retried);
-        if (three && t >= ptmin[2]) z[zt + 2 * kRnnThreads] = poll_word(pp[2] + (size_t)t * pstride[2], ptag[2] + t, retried);
+        if (t >= ptmin[0]) z[zp[0]] = poll_word(pp[0] + (size_t)t * pstride[0], ptag[0] + t, retried);
+        if (two && t >= ptmin[1]) z[zp[1]] = poll_word(pp[1] + (size_t)t * pstride[1], ptag[1] + t, retried);
+        if (three && t >= ptmin[2]) z[zp[2]] = poll_word(pp[2] + (size_t)t * pstride[2], ptag[2] + t, retried);
         if (kPhaseClocks && A.dbg && blockIdx.x == 0 && (tid & 63u) == 0 && t > 0) wave_arrive += __builtin_readcyclecounter() - after_b;
         if (polls) {
             if (__ballot(retried) != 0ull) { delay += 3; streak = 0; }
             else if (++streak >= 16) { delay -= delay > 0 ? 1u : 0u; streak = 0; }
         }
         if (from_x) {
-            if (xl0) z[zt] = xnext0;
-            if (xl1) z[zt + kRnnThreads] = xnext1;
+            if (xl0) z[zp[0]] = xnext0;
+            if (xl1) z[zp[1]] = xnext1;
             if (t + 1 < T) {
                 if (xl0) xnext0 = A.x[(size_t)(t + 1) * A.I + zt];
                 if (xl1) xnext1 = A.x[(size_t)(t + 1) * A.I + zt + kRnnThreads];
@@ -700,7 +770,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
             if (linear) {                                // the row sum is the output
                 hn = a0;
             } else if (rb_reset) {                       // r activated: hand on q = r h_(t-1)
-                hn = a0 * z[n_in + unit];
+                hn = a0 * z[zown];
             } else if (rb_gate) {                        // z activated; n: input side + Un q (+ bias)
                 hn = (1.0f - a0) * fast_tanh(a1) + a0 * h_state;
             } else if (lstm) {                           // activated rows i, f, g, o
@@ -714,7 +784,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
                 hn = (1.0f - a1) * n + a1 * h_state;
             }
             h_state = hn;
-            if (own_rec) z[n_in + unit] = hn;        // next step's input, read only after the next barrier
+            if (own_rec) z[zown] = hn;               // next step's input, read only after the next barrier
             const unsigned long long pk = ((unsigned long long)tag_now << 32) | (unsigned long long)__float_as_uint(hn);
             __hip_atomic_store(pub + (size_t)t * nu, pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (A.hseq && (flags & kStageIsSeq)) A.hseq[(size_t)t * wg.width + unit] = hn;
@@ -1168,6 +1238,7 @@ extern "C" int csb_rnn_stats(const csb_rnn *r, csb_rnn_plan_stats *out) {
     out->slots_per_lane = r->plan.smax;
     out->slot_fill = r->plan.slot_fill;
     out->lanes_max_over_mean = r->plan.lanes_max_over_mean;
+    out->reserved = (int32_t)std::min<long>(r->plan.lds_conflicts, 0x7fffffff);
     return CSB_OK;
 }
 
