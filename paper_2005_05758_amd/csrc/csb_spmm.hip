@@ -182,15 +182,23 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
             }
         };
         floatx4 D[NT];
+        const floatx4 zero4 = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) D[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int nt = 0; nt < NT; ++nt) D[nt] = zero4;
         auto mult_pass = [&](const Pass &p, const Operands<NT, KS> &o) {
 #pragma unroll
             for (int s8 = 0; s8 < KS; ++s8) {
                 if (p.kc + 4u * s8 >= p.c) break;                  // uniform
+                // a slice's first k-step starts from a zero operand: the accumulators need no clearing
+                if (s8 == 0 && p.kc == 0) {                        // uniform
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    D[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.av[s8], o.bv[s8][nt], D[nt], 0, 0, 0);
+                    for (int nt = 0; nt < NT; ++nt)
+                        D[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.av[s8], o.bv[s8][nt], zero4, 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        D[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.av[s8], o.bv[s8][nt], D[nt], 0, 0, 0);
+                }
             }
             if (p.kc + 4 * KS < p.c) return;                       // the slice has more columns
             // lane holds rows 4*(lane/16)+i, column lane%16 of each 16 x 16 result; the rows of
@@ -214,8 +222,6 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
                     if (on[i])
                         *(float4 *)(myacc + at[i]) = make_float4(old4[i].x + D[0][i], old4[i].y + D[1][i],
                                                                  old4[i].z + D[2][i], old4[i].w + D[3][i]);
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) D[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
                 return;
             }
             float old[4][NT];
@@ -228,8 +234,6 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
                     if (on[i]) myacc[at[i] + 16u * nt] = old[i][nt] + D[nt][i];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) D[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
         };
         auto nxt = [&](const Pass &p) -> Pass { return p.valid ? next_pass(p) : p; };
         if constexpr (WIDE) {
