@@ -90,8 +90,24 @@ def stream_read_leg(torch, stream_read):
     ms = time_region(lambda: stream_read(buf, out), n, torch) / n
     gbps = buf.numel() * 4 / (ms * 1e-3) / 1e9
     del buf
-    return {"bytes": 512 * 1024 * 1024 * 4, "ms": round(ms, 4), "gbps": round(gbps, 1),
-            "frac_of_nominal_peak": round(gbps / HBM_PEAK_GBS, 4)}
+    res = {"bytes": 512 * 1024 * 1024 * 4, "ms": round(ms, 4), "gbps": round(gbps, 1),
+           "frac_of_nominal_peak": round(gbps / HBM_PEAK_GBS, 4)}
+    # the same plain read at the size of the 8192^2 matrix image (28 MB per launch), cold: 24
+    # distinct buffers in turn, as the mat-vec's cold figure is taken -- what one launch of that
+    # size costs when all it does is read
+    small = [torch.ones(7 * 1024 * 1024, dtype=torch.float32, device="cuda") for _ in range(24)]
+    for b in small:
+        stream_read(b, out)
+    state = {"i": 0}
+
+    def cold():
+        stream_read(small[state["i"] % len(small)], out)
+        state["i"] += 1
+    n = 5 * len(small)
+    us = time_region(cold, n, torch) * 1000.0 / n
+    res["image_sized_cold"] = {"bytes": small[0].numel() * 4, "us": round(us, 3),
+                               "gbps": round(small[0].numel() * 4 / us / 1e3, 1)}
+    return res
 
 
 def main():
@@ -211,7 +227,7 @@ def main():
         sr = stream_read_leg(torch, stream_read)
         out["hbm_stream_read"] = sr
         out["pct_of_measured_stream_read"] = round(100.0 * gbps / sr["gbps"], 4)
-        out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix, sr["gbps"])
+        out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix, sr["gbps"], sr["image_sized_cold"]["us"])
         out["batched"] = batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
         out["projection"] = projection_leg(torch, np, sr["gbps"], not args.no_cpu)
         out["lstmp_sr1"] = lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, not args.no_cpu)
@@ -222,7 +238,7 @@ def main():
     print(json.dumps(out))
 
 
-def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
+def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps, image_read_us=None):
     """csb_spmv on the 8192^2 heavy-tailed matrices (the HBM-bound case): warm (matrix in the
     Infinity Cache) and cold (rotating over distinct device copies, > 512 MB in all), for
     the default plan (whole row tiles per workgroup) and the equal-split plan (mode 2)."""
@@ -284,6 +300,10 @@ def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
                               "frac_hbm_cold": round(ab / us_cold / 1e3 / HBM_PEAK_GBS, 4),
                               "frac_of_measured_stream_read_cold": round(ab / us_cold / 1e3 / stream_gbps, 4),
                               "cold_copies": n_copies, "cold_bytes_total": n_copies * M.device_bytes()})
+                if image_read_us:
+                    # against a plain cold read of the same number of bytes in one launch
+                    entry["plain_read_of_image_size_us"] = image_read_us
+                    entry["time_over_plain_read"] = round(us_cold / image_read_us, 3)
                 del copies
             res[f"{name}_{tag}"] = entry
             del M
