@@ -344,6 +344,10 @@ size_t csb_rnn_workspace_bytes(const csb_rnn *r, int32_t batch, int32_t T);
  * T = 0 copies h0/c0 to hT/cT.  The time loop runs on the device side of `stream`
  * without host synchronisation.  Errors: NULL / batch <= 0 / T < 0 -> CSB_EINVAL;
  * a W[l] not uploaded -> CSB_ESTATE.
+ * Not for replay from a captured HIP graph: the resident kernel (and csb_spmv / csb_spmm on a
+ * matrix planned with shared row tiles) tell this call's exchange words from stale ones by a
+ * launch tag that the HOST draws per call; a replay would reuse the tag.  Calls on one handle
+ * must not overlap either (they share the workspace's exchange words).
  */
 int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0,
                     float *d_hseq, float *d_hT, float *d_cT, int32_t T, int32_t batch,
