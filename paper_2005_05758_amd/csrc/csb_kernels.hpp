@@ -1,6 +1,8 @@
 // Internal entry points between the translation units of the library.
 #pragma once
 
+#include <hip/hip_runtime.h>
+
 #include "csb_internal.hpp"
 
 namespace csb {
@@ -13,5 +15,10 @@ int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const flo
 // p0[j*sj0 + n*sn0] for j < n0 and p1[(j-n0)*sj1 + n*sn1] otherwise; Y is [rows_out][ldy].
 int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj0, int64_t sn0, const float *p1,
                  int64_t sj1, int64_t sn1, float *d_Y, int64_t ldy, int32_t batch, void *stream);
+
+// Raises a kernel's limit of dynamic LDS on the current device to `bytes` if it is below it.
+// (The limit sticks to the kernel; setting it is a runtime call of its own, too slow to repeat
+// before every launch of a path that launches a kernel per timestep.)
+hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes);
 
 }  // namespace csb

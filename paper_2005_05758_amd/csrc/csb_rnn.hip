@@ -1050,7 +1050,7 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     const size_t cmax = r->plan.cmax;
     const size_t lds = (((cmax + 1 + 63) & ~(size_t)63) + kRnnThreads) * sizeof(float);
     auto go = [&](auto kern) -> hipError_t {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds((const void *)kern, lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3(A.per_xcd * 8u), dim3(kRnnThreads), lds, st, A);
         return hipGetLastError();

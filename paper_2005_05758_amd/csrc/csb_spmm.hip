@@ -313,7 +313,7 @@ int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj
     const int nw = fits16 && (wide || (size_t)grid.x * grid.y < 2 * 256) ? 16 : 8;
     const size_t lds = (size_t)kSpmmMetaBytes + (size_t)nw * acc_per_wave;
     auto go = [&](auto kern) -> hipError_t {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds((const void *)kern, lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, dim3(nw * 64), lds, (hipStream_t)stream, dm, X, d_Y, ldy, (uint32_t)batch);
         return hipGetLastError();

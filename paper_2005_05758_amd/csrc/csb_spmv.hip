@@ -11,7 +11,8 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
-
+#include <map>
+#include <mutex>
 #include <type_traits>
 
 #include "csb_internal.hpp"
@@ -401,6 +402,20 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
     if (st && tid == 0) st[5] = __builtin_readcyclecounter();
 }
 
+hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes) {
+    static std::mutex mu;
+    static std::map<std::pair<const void *, int>, size_t> have;   // (kernel, device) -> limit set so far
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    size_t &limit = have[{kernel, dev}];
+    if (bytes <= limit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) limit = bytes;
+    return e;
+}
+
 __global__ void clear_words_kernel(unsigned long long *p, size_t n) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
 }
@@ -432,7 +447,7 @@ static hipError_t launch_spmv(const csb_matrix *mat, const float *x0, uint32_t n
         }
     }
     auto go = [&](auto kern, int nw) -> hipError_t {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds((const void *)kern, lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3(h.n_chunks), dim3(nw * 64), lds, stream, dm, x0, n0, x1, y, partials, epoch, L, stamps);
         return hipGetLastError();
