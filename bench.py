@@ -571,7 +571,8 @@ def cells_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
 
 def cpu_leg(cfg, wl):
     """The CPU oracle as it stands, on the host cores of this machine: float64 LSTM/GRU on the
-    decompressed dense matrix, whole T-frame sequences until about 10 s have passed."""
+    decompressed dense matrix, whole T-frame sequences until about 10 s have passed; beside it
+    the oracle's float32 mat-vec on the CSB arrays (what a CPU does with the same format)."""
     import oracle
     W = [m.A for m in wl.W]
     oracle.rnn_forward(cfg.cell, W, wl.bias, wl.x[:2], cfg.input, cfg.hidden)   # warm-up
@@ -598,6 +599,30 @@ def cpu_leg(cfg, wl):
         res["one_core_us_per_timestep"] = round((time.perf_counter() - t0) / (r1 * cfg.T) * 1e6, 3)
     finally:
         oracle.set_threads(all_threads)
+    # like for like: the oracle's float32 CSB-MVM on the encoded arrays (mat-vec only, no gates),
+    # on this workload's first layer and on the 8192^2 stress matrix, all cores and one core
+    def time_csb(enc, x, budget):
+        oracle.csb_matvec_f32(enc, x)
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < budget:
+            oracle.csb_matvec_f32(enc, x)
+            n += 1
+        return round((time.perf_counter() - t0) / n * 1e6, 2)
+    import csb_inputs
+    big = csb_inputs.make_mat(csb_inputs.CONFIGS["cfg5"])
+    cases = {f"{cfg.name}_layer0": (wl.W[0].A, wl.W[0].br, wl.W[0].bc), "cfg5": (big.A, big.br, big.bc)}
+    res["csb_f32_matvec"] = {}
+    for name, (A, br, bc) in cases.items():
+        enc = oracle.csb_encode(A, br, bc)
+        x = csb_inputs.make_vectors(5, A.shape[1], 1)
+        entry = {"nnz": int(enc.nnz), "us_all_cores": time_csb(enc, x, 1.5)}
+        try:
+            oracle.set_threads(1)
+            entry["us_one_core"] = time_csb(enc, x, 1.5)
+        finally:
+            oracle.set_threads(all_threads)
+        res["csb_f32_matvec"][name] = entry
     return res
 
 

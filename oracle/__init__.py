@@ -118,6 +118,20 @@ def matvec(A: np.ndarray, x: np.ndarray) -> np.ndarray:
     return y
 
 
+def csb_matvec_f32(m: CsbArrays, x: np.ndarray) -> np.ndarray:
+    """CSB-MVM on the encoded arrays in float32 (Sec. 4.3.1): the like-for-like CPU baseline
+    that the benchmark times; checked against `matvec`, never used as a parity reference."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert x.shape == (m.cols,)
+    y = np.empty(m.rows, np.float32)
+    vo, ro, co = (np.ascontiguousarray(a, dtype=np.int64) for a in (m.val_off, m.row_off, m.col_off))
+    lib.orc_csb_matvec_f32(C.c_int64(m.rows), C.c_int64(m.cols), C.c_int32(m.br), C.c_int32(m.bc),
+                           _p(m.nrows), _p(m.ncols), _p(m.rowidx), _p(m.colidx), _p(m.val),
+                           _p(vo), _p(ro), _p(co), _p(x), _p(y))
+    return y
+
+
 def matvec_abs(A: np.ndarray, x: np.ndarray) -> np.ndarray:
     lib = _load()
     A = np.ascontiguousarray(A, dtype=np.float32)

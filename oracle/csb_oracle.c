@@ -9,7 +9,9 @@
  *     surviving rows and columns, and the kernel values of successive blocks, blocks in
  *     row-major order, concatenated);
  *   - y = A x and Y = A X on the DECOMPRESSED dense matrix, float64 accumulation
- *     (CSB is a lossless encoding, so CSB-MVM of Sec. 4.3.1 equals the plain product);
+ *     (CSB is a lossless encoding, so CSB-MVM of Sec. 4.3.1 equals the plain product); beside
+ *     it CSB-MVM on the encoded arrays in float32, a timed baseline that is itself checked
+ *     against the float64 product;
  *   - LSTM and GRU inference over a sequence (Sec. 2.1: mat-vec of the weight matrices
  *     with input and hidden vectors, then sigmoid / tanh / element-wise products and
  *     sums, with c_{t-1}, h_{t-1} carried to the next step), float64 throughout; also the
@@ -175,6 +177,38 @@ void orc_matvec(const float *A, int64_t R, int64_t C, int64_t ld, const float *x
         double s = 0.0;
         for (int64_t j = 0; j < C; ++j) s += (double)A[i * ld + j] * (double)x[j];
         y[i] = s;
+    }
+}
+
+/*
+ * CSB-MVM straight on the encoded arrays, in float32 (Sec. 4.3.1: for every block the kernel
+ * matrix times the inputs that its column indices select, added to the outputs that its row
+ * indices name; the blocks of a block-row accumulate one after another).  The like-for-like
+ * CPU baseline of the device kernels, timed by the benchmark; NOT the parity reference, which
+ * is orc_matvec on the decompressed matrix in float64 (this function is itself checked
+ * against it).  val_off / row_off / col_off are the exclusive prefix sums of the counts.
+ */
+void orc_csb_matvec_f32(int64_t R, int64_t C, int32_t BR, int32_t BC,
+                        const int32_t *nrows, const int32_t *ncols,
+                        const uint16_t *rowidx, const uint16_t *colidx, const float *val,
+                        const int64_t *val_off, const int64_t *row_off, const int64_t *col_off,
+                        const float *x, float *y) {
+    int64_t nbr = (R + BR - 1) / BR, nbc = (C + BC - 1) / BC;
+#pragma omp parallel for schedule(static)
+    for (int64_t bi = 0; bi < nbr; ++bi) {
+        int64_t r0 = bi * BR, h = imin64(BR, R - r0);
+        for (int64_t i = 0; i < h; ++i) y[r0 + i] = 0.0f;
+        for (int64_t bj = 0; bj < nbc; ++bj) {
+            int64_t b = bi * nbc + bj;
+            int32_t rb = nrows[b], cb = ncols[b];
+            const float *k = val + val_off[b];
+            const uint16_t *ri = rowidx + row_off[b], *ci = colidx + col_off[b];
+            for (int32_t i = 0; i < rb; ++i) {
+                float s = 0.0f;
+                for (int32_t j = 0; j < cb; ++j) s += k[(int64_t)i * cb + j] * x[bj * BC + ci[j]];
+                y[r0 + ri[i]] += s;
+            }
+        }
     }
 }
 

@@ -70,3 +70,43 @@ def test_transposed_operand_would_fail():
     assert oracle.matvec(A, x).tolist() == [210.0, 543.0]
     X = np.array([[1, 0], [0, 1], [1, 1]], np.float32)
     assert oracle.matmat(A, X).tolist() == [[2.0, 3.0], [8.0, 9.0]]
+
+
+# ---- the float32 CSB-MVM on the encoded arrays (the benchmark's like-for-like CPU baseline) ----
+
+def test_csb_matvec_f32_hand_worked_example():
+    """The two-block example of tests/golden: y = [10, 25, -8, 35] for x = 1..8."""
+    A = np.array([[0, 1, 0, 2, 0, 0, 0, 0],
+                  [0, 0, 0, 0, 5, 0, 0, 0],
+                  [0, 3, 0, 4, -6, 0, 0, 0],
+                  [0, 0, 0, 0, 7, 0, 0, 0]], np.float32)
+    x = np.arange(1, 9, dtype=np.float32)
+    y = oracle.csb_matvec_f32(oracle.csb_encode(A, 4, 4), x)
+    assert y.dtype == np.float32 and np.array_equal(y, np.array([10, 25, -8, 35], np.float32))
+
+
+@pytest.mark.parametrize("R,C,br,bc", [(1, 1, 1, 1), (12, 7, 4, 3), (37, 53, 8, 8), (130, 257, 32, 32), (70, 300, 16, 64)])
+def test_csb_matvec_f32_exact_on_small_integers(R, C, br, bc):
+    """Small integer entries make every float32 product and sum exact, so the walk over the
+    encoded arrays must reproduce the float64 product of the dense matrix bit for bit: a wrong
+    offset, a swapped index array or a missed block cannot hide behind rounding."""
+    rng = np.random.default_rng(R * 7 + C)
+    A = rng.integers(-8, 9, size=(R, C)).astype(np.float32)
+    A[rng.random((R, C)) < 0.6] = 0.0
+    A[:, rng.random(C) < 0.2] = 0.0                       # whole columns and rows pruned away
+    A[rng.random(R) < 0.2, :] = 0.0
+    x = rng.integers(-8, 9, size=C).astype(np.float32)
+    y = oracle.csb_matvec_f32(oracle.csb_encode(A, br, bc), x)
+    assert np.array_equal(y.astype(np.float64), oracle.matvec(A, x))
+
+
+def test_csb_matvec_f32_within_the_float32_dot_product_bound():
+    m = csb_inputs.small_matrix(9, 300, 421, 32, 32, rate=5.0)
+    x = csb_inputs.make_vectors(9, 421, 1)
+    y = oracle.csb_matvec_f32(oracle.csb_encode(m.A, 32, 32), x).astype(np.float64)
+    ref, scale = oracle.matvec(m.A, x), oracle.matvec_abs(m.A, x)
+    k = np.count_nonzero(m.A, axis=1)
+    assert np.all(np.abs(y - ref) <= 2.0 * np.maximum(k, 1) * 2.0 ** -24 * scale + 1e-30)
+    assert np.any(y != ref)                               # it does round: a float32 path, as claimed
+    Z = np.zeros((40, 48), np.float32)
+    assert np.array_equal(oracle.csb_matvec_f32(oracle.csb_encode(Z, 16, 16), x[:48]), np.zeros(40, np.float32))
