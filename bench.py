@@ -384,16 +384,24 @@ def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
             M.spmm(X, Y)
         n = 20
         us = time_region(lambda: M.spmm(X, Y), n, torch) * 1000.0 / n
-        fl = 2.0 * int(M.view()["nnz"]) * batch
-        res[f"spmm_{name}_b{batch}"] = {"shape": [int(m.rows), int(m.cols)], "nnz": int(M.view()["nnz"]), "batch": batch,
+        v = M.view()
+        fl = 2.0 * int(v["nnz"]) * batch
+        # what the kernel's access pattern pulls through L2 -> L1: every block gathers the rows of X
+        # of its own kept columns (no reuse inside a workgroup), plus the kernel values once
+        gather = 4.0 * float(np.asarray(v["ncols"], dtype=np.int64).sum()) * batch + 4.0 * int(v["nnz"])
+        res[f"spmm_{name}_b{batch}"] = {"shape": [int(m.rows), int(m.cols)], "nnz": int(v["nnz"]), "batch": batch,
                                         "us": round(us, 2), "tflops_algorithmic": round(fl / us / 1e6, 3),
-                                        "frac_fp32_mfma_peak": round(fl / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4)}
+                                        "frac_fp32_mfma_peak": round(fl / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4),
+                                        "l2_gather_bytes": int(gather), "l2_gather_gbps": round(gather / us / 1e3, 1)}
         del M
     best = res["spmm_cfg5_b128"]
     res["roofline"] = {"kernel": "csb::spmm_kernel<4, false, 16, true>", "bound": "mfma", "achieved": best["tflops_algorithmic"],
                        "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": best["frac_fp32_mfma_peak"],
                        "traffic": sum(TRAFFIC_BYTES["spmm_cfg5_b128"].values()),
-                       "us_per_launch": best["us"], "flops_per_launch": 2.0 * best["nnz"] * best["batch"]}
+                       "us_per_launch": best["us"], "flops_per_launch": 2.0 * best["nnz"] * best["batch"],
+                       "note": "the matrix cores are the nominal roof; counters show the launch bound by the gather of X "
+                               "rows through L2 -> L1 (l2_gather_bytes at l2_gather_gbps; MFMA pipe a quarter busy, L1 "
+                               "stalled on outstanding misses half of the launch: profiles/spmm_cfg5_b128_pmc.txt)"}
     cfg = csb_inputs.CONFIGS["cfg4"]
     wl = csb_inputs.make_rnn(cfg)
     Ws = [CsbMatrix(w.A, w.br, w.bc) for w in wl.W]
