@@ -7,9 +7,31 @@
 
 namespace csb {
 
+// A segment of the mat-vec's input that is not in memory yet: the output h_t of a recurrent
+// cell whose gate sums `a` an earlier launch on the same stream has produced.  The mat-vec
+// kernel applies the cell's element-wise part (Sec. 2.1) while it stages its input, so a
+// timestep of the streaming path is one launch per layer instead of two; every workgroup
+// recomputes the (cheap) gates, workgroup 0 also stores the new state where the next step
+// reads it.  kind 0: a plain vector at `a`.
+struct GateSrc {
+    const float *a;        // kind 0: the vector itself; else the sums, rows stacked as the cell stacks them
+    const float *bias;     // may be null
+    const float *c_in;     // LSTM: c_(t-1)
+    const float *h_in;     // GRU, Li-GRU: h_(t-1)
+    float *c_out, *h_out;  // where c_t (LSTM) and h_t go; distinct from c_in / h_in
+    float *hseq;           // also h_t, or null
+    uint32_t kind;         // 0 plain, else 1 + CSB_CELL_LSTM / _GRU / _LIGRU
+    uint32_t H;
+};
+__device__ __host__ inline GateSrc plain_src(const float *v) { return GateSrc{v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u, 0u}; }
+
 // y = A [x0[0..n0) ; x1[0..cols-n0)] on `stream`; y has the image's rows_out entries.
 int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const float *d_x1, float *d_y,
                   void *d_ws, void *stream, unsigned long long *d_stamps = nullptr);
+// ... with either segment possibly a cell output still to be computed (see GateSrc).
+int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *d_ws, void *stream);
+// The element-wise part alone, one thread per unit: stores c_t, h_t (and hseq) of `s`.
+int commit_gates(const GateSrc &s, void *stream);
 
 // Y = A Z for `batch` right-hand sides.  Element (column j, right-hand side n) of Z is
 // p0[j*sj0 + n*sn0] for j < n0 and p1[(j-n0)*sj1 + n*sn1] otherwise; Y is [rows_out][ldy].

@@ -802,37 +802,6 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
 
 // ------------------------------------------------------------------ streaming path
 
-// Element-wise part of the LSTM cell: a = W [u; h] (+ bias), rows i,f,g,o.
-__global__ void lstm_gates_kernel(const float *__restrict__ a, const float *__restrict__ bias,
-                                  float *__restrict__ c, float *__restrict__ h, float *__restrict__ hseq,
-                                  const int H) {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= H) return;
-    float ai = a[k], af = a[H + k], ag = a[2 * H + k], ao = a[3 * H + k];
-    if (bias) { ai += bias[k]; af += bias[H + k]; ag += bias[2 * H + k]; ao += bias[3 * H + k]; }
-    const float cn = sigmoidf_(af) * c[k] + sigmoidf_(ai) * tanhf(ag);
-    const float hn = sigmoidf_(ao) * tanhf(cn);
-    c[k] = cn;
-    h[k] = hn;
-    if (hseq) hseq[k] = hn;
-}
-
-// Element-wise part of the GRU cell.  a has 4H rows: r, z (input + recurrent sums),
-// then the n rows' input-side sum, then the n rows' recurrent-side sum.
-__global__ void gru_gates_kernel(const float *__restrict__ a, const float *__restrict__ bias,
-                                 float *__restrict__ h, float *__restrict__ hseq, const int H) {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= H) return;
-    float ar = a[k], az = a[H + k], anx = a[2 * H + k];
-    const float anh = a[3 * H + k];
-    if (bias) { ar += bias[k]; az += bias[H + k]; anx += bias[2 * H + k]; }
-    const float r = sigmoidf_(ar), z = sigmoidf_(az);
-    const float n = tanhf(anx + r * anh);
-    const float hn = (1.0f - z) * n + z * h[k];
-    h[k] = hn;
-    if (hseq) hseq[k] = hn;
-}
-
 // Batched element-wise parts: a is [rows][B], the state is kept as [H][B].
 __global__ void lstm_gates_batched_kernel(const float *__restrict__ a, const float *__restrict__ bias,
                                           float *__restrict__ c, float *__restrict__ h, float *__restrict__ hseq,
@@ -978,7 +947,7 @@ static void init_state(float *dst, const float *src, size_t n, hipStream_t st) {
 static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 struct RnnWs {
-    size_t off_a, off_a2, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, off_m, total;
+    size_t off_a, off_a2, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, off_m, off_fa, off_fs, rows_out, total;
 };
 
 static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
@@ -1007,6 +976,12 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
         w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     }
     w.off_m = off; off = align256(off + ((r->proj > 0 || two_products) ? (size_t)batch * r->hidden * sizeof(float) : 0));
+    // one-launch-per-step streaming (batch 1, LSTM / GRU / Li-GRU): per layer two buffers of gate
+    // sums and two of (c, h), used alternately by even and odd steps
+    const bool fused = batch == 1 && (r->cell == CSB_CELL_LSTM || r->cell == CSB_CELL_GRU || r->cell == CSB_CELL_LIGRU);
+    w.rows_out = rows_out;
+    w.off_fa = off; off = align256(off + (fused ? 2 * (size_t)r->n_layers * rows_out * sizeof(float) : 0));
+    w.off_fs = off; off = align256(off + (fused ? 4 * (size_t)r->n_layers * r->hidden * sizeof(float) : 0));
     off += 512;   // last 512 bytes: debug clocks of the resident kernel
     w.total = off;
     return w;
@@ -1327,9 +1302,49 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         if (eb != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(eb)); return CSB_EDEVICE; }
         return CSB_OK;
     }
+    void *part = (uint8_t *)d_ws + wl.off_part;
+    if (r->cell == CSB_CELL_LSTM || r->cell == CSB_CELL_GRU || r->cell == CSB_CELL_LIGRU) {
+        // One launch per step and layer: the element-wise part of a cell (Sec. 2.1) runs inside
+        // the mat-vec launches that consume its output h_(l,t) -- layer l + 1 at step t and layer
+        // l at step t + 1 -- while they stage their input (see GateSrc).  Gate sums and states of
+        // step t live in buffer t & 1 of their layer (the initial state in buffer 1), so a launch
+        // never writes what another workgroup of the same launch still reads.
+        float *fa = (float *)((uint8_t *)d_ws + wl.off_fa), *fs = (float *)((uint8_t *)d_ws + wl.off_fs);
+        auto sums = [&](int l, int t) { return fa + ((size_t)l * 2 + (size_t)(t & 1)) * wl.rows_out; };
+        auto c_of = [&](int l, int t) { return fs + (((size_t)l * 2 + (size_t)(t & 1)) * 2) * H; };
+        auto h_of = [&](int l, int t) { return c_of(l, t) + H; };
+        for (int l = 0; l < L; ++l) {
+            init_state(h_of(l, -1), d_h0 ? d_h0 + (size_t)l * H : nullptr, (size_t)H, st);
+            if (lstm) init_state(c_of(l, -1), d_c0 ? d_c0 + (size_t)l * H : nullptr, (size_t)H, st);
+        }
+        auto cell_output = [&](int l, int t) {                   // h_(l,t), still to be computed from the sums of step t
+            GateSrc g{};
+            g.a = sums(l, t); g.bias = r->d_bias[l];
+            g.c_in = lstm ? c_of(l, t - 1) : nullptr; g.h_in = h_of(l, t - 1);
+            g.c_out = lstm ? c_of(l, t) : nullptr; g.h_out = h_of(l, t);
+            g.hseq = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * H : nullptr;
+            g.kind = 1u + (uint32_t)r->cell; g.H = (uint32_t)H;
+            return g;
+        };
+        for (int t = 0; t < T; ++t)
+            for (int l = 0; l < L; ++l) {
+                const GateSrc below = l == 0 ? plain_src(d_x + (size_t)t * I) : cell_output(l - 1, t);
+                const GateSrc back = t == 0 ? plain_src(h_of(l, -1)) : cell_output(l, t - 1);
+                int rc = spmv_gated(r->W[l], below, l == 0 ? (uint32_t)I : (uint32_t)H, back, sums(l, t), part, st);
+                if (rc != CSB_OK) return rc;
+            }
+        // the last step's cells have no consumer: apply them here, into the caller's state arrays
+        for (int l = 0; l < L; ++l) {
+            GateSrc g = cell_output(l, T - 1);
+            g.h_out = d_hT + (size_t)l * H;
+            g.c_out = (lstm && d_cT) ? d_cT + (size_t)l * H : nullptr;
+            int rc = commit_gates(g, st);
+            if (rc != CSB_OK) return rc;
+        }
+        return CSB_OK;
+    }
     float *c = (lstm && d_cT) ? d_cT : (float *)((uint8_t *)d_ws + wl.off_c);
     float *mb = (float *)((uint8_t *)d_ws + wl.off_m);
-    void *part = (uint8_t *)d_ws + wl.off_part;
     // the outputs double as the running state
     init_state(d_hT, d_h0, nstate, st);
     if (lstm) init_state(c, d_c0, ncstate, st);
@@ -1349,18 +1364,12 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
                     rc = spmv_segments(r->Wp[l], mb, (uint32_t)H, mb, h, part, st);
                     if (rc != CSB_OK) return rc;
                     if (hs) hipLaunchKernelGGL(copy_kernel, dim3((HS + 255) / 256), dim3(256), 0, st, hs, (const float *)h, (size_t)HS);
-                } else if (lstm)
-                    hipLaunchKernelGGL(lstm_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l],
-                                       c + ((size_t)l * batch + s) * H, h, hs, H);
-                else if (ligru)
-                    hipLaunchKernelGGL(ligru_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l], h, hs, H, 1);
-                else if (gru_rb) {
+                } else {                                     // reset-before GRU (the other cells took the one-launch path above)
                     hipLaunchKernelGGL(gru_rb_reset_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l], (const float *)h, mb, H, 1);
                     rc = spmv_segments(r->Wp[l], mb, (uint32_t)H, mb, a2, part, st);
                     if (rc != CSB_OK) return rc;
                     hipLaunchKernelGGL(gru_rb_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, a2, r->d_bias[l], h, hs, H, 1);
-                } else
-                    hipLaunchKernelGGL(gru_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l], h, hs, H);
+                }
             }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }

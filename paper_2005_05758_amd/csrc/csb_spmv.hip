@@ -120,14 +120,66 @@ __device__ __forceinline__ void unpack_pair(uint32_t w, float &lo, float &hi) {
     }
 }
 
+__device__ __forceinline__ float sigmoid_(float v) { return 1.0f / (1.0f + expf(-v)); }
+
+// h_t of unit u of the cell whose gate sums are s.a (Sec. 2.1; LSTM rows i,f,g,o; GRU rows r,z,
+// input side of n, recurrent side of n; Li-GRU rows z, candidate), the same arithmetic as the
+// stand-alone gate kernels.  `store`: also write the new state (and the output sequence).
+__device__ __forceinline__ float gate_value(const GateSrc &s, uint32_t u, bool store) {
+    const uint32_t H = s.H;
+    const float *a = s.a, *b = s.bias;
+    float hn, cn = 0.0f;
+    if (s.kind == 1u + CSB_CELL_LSTM) {
+        float ai = a[u], af = a[H + u], ag = a[2 * H + u], ao = a[3 * H + u];
+        if (b) { ai += b[u]; af += b[H + u]; ag += b[2 * H + u]; ao += b[3 * H + u]; }
+        cn = sigmoid_(af) * s.c_in[u] + sigmoid_(ai) * tanhf(ag);
+        hn = sigmoid_(ao) * tanhf(cn);
+    } else if (s.kind == 1u + CSB_CELL_GRU) {
+        float ar = a[u], az = a[H + u], anx = a[2 * H + u];
+        const float anh = a[3 * H + u];
+        if (b) { ar += b[u]; az += b[H + u]; anx += b[2 * H + u]; }
+        const float r = sigmoid_(ar), z = sigmoid_(az);
+        hn = (1.0f - z) * tanhf(anx + r * anh) + z * s.h_in[u];
+    } else {                                                   // Li-GRU
+        float az = a[u], ac = a[H + u];
+        if (b) { az += b[u]; ac += b[H + u]; }
+        const float z = sigmoid_(az);
+        hn = z * s.h_in[u] + (1.0f - z) * fmaxf(ac, 0.0f);
+    }
+    if (store) {
+        if (s.c_out) s.c_out[u] = cn;
+        if (s.h_out) s.h_out[u] = hn;
+        if (s.hseq) s.hseq[u] = hn;
+    }
+    return hn;
+}
+
+// One segment of the input vector into LDS: a plain copy, or the cell outputs computed on the way.
+__device__ __forceinline__ void stage_segment(float *z, const GateSrc &s, uint32_t n, uint32_t tid, uint32_t nthreads, bool store) {
+    if (s.kind == 0u) {                                        // uniform
+        for (uint32_t u = tid; u < n; u += nthreads) z[u] = s.a[u];
+    } else {
+        for (uint32_t u = tid; u < n; u += nthreads) z[u] = gate_value(s, u, store);
+    }
+}
+
+__global__ void commit_gates_kernel(const GateSrc s) {
+    const uint32_t u = blockIdx.x * blockDim.x + threadIdx.x;
+    if (u < s.H) gate_value(s, u, true);
+}
+
 // One workgroup per chunk.  Records and the input vector go to LDS; the kernel values never
 // do: a wavefront's steps are consecutive 64-float runs of the value stream, so lane l loads
 // word l of every run straight into a register (one coalesced 256-byte read per step) and
 // multiplies it there.  VF: storage format of the value stream (CSB_VAL_*); a 16-bit stream
 // holds one word per lane and pair of steps, so a step pair is one coalesced 256-byte read.
-template <int VF>
-__global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, const float *__restrict__ x0,
-                                                             const uint32_t n0, const float *__restrict__ x1,
+// GATED: the two input segments are GateSrc records (cell outputs computed while staging);
+// otherwise plain vectors, and the kernel takes only their pointers.
+template <bool GATED> struct SpmvSrc { const float *a; };
+template <> struct SpmvSrc<true> : GateSrc {};
+template <int VF, bool GATED>
+__global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, const SpmvSrc<GATED> g0,
+                                                             const uint32_t n0, const SpmvSrc<GATED> g1,
                                                              float *__restrict__ y, unsigned long long *__restrict__ partials,
                                                              const uint32_t epoch, const LdsMap L,
                                                              unsigned long long *__restrict__ stamps) {
@@ -166,13 +218,20 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
     CSB_LD2(rg0, gsrc8, tid, gu) CSB_LD2(rg1, gsrc8, tid + NT, gu) CSB_LD2(rg2, gsrc8, tid + 2 * NT, gu)
     CSB_LD4(ri0, isrc, tid, iu) CSB_LD4(ri1, isrc, tid + NT, iu)
     // input vector: aligned single-source fast path, else element-wise from two sources
-    const bool zfast = n0 >= m.cols && (m.cols & 3u) == 0 && ((uintptr_t)x0 & 15u) == 0;
+    const float *x0 = g0.a;
+    const bool zfast = !GATED && n0 >= m.cols && (m.cols & 3u) == 0 && ((uintptr_t)x0 & 15u) == 0;
     const uint32_t z4 = zfast ? (m.cols >> 2) : 0u;
     const float4 *zsrc = (const float4 *)x0;
     CSB_LD4(rz0, zsrc, tid, z4) CSB_LD4(rz1, zsrc, tid + NT, z4) CSB_LD4(rz2, zsrc, tid + 2 * NT, z4)
     CSB_LD4(rz3, zsrc, tid + 3 * NT, z4)
-    if (!zfast)
+    if constexpr (GATED) {                       // two segments, either one possibly a cell output still to be computed
+        const uint32_t na = min(n0, m.cols);
+        stage_segment(z, g0, na, tid, NT, c == 0);
+        stage_segment(z + na, g1, m.cols - na, tid, NT, c == 0);
+    } else if (!zfast) {
+        const float *x1 = g1.a;
         for (uint32_t i = tid; i < m.cols; i += NT) z[i] = i < n0 ? x0[i] : x1[i - n0];
+    }
     // values of the wavefront's first CAP steps (steps past its last one repeat the last)
     const uint32_t nsteps = (wr.v_end - wr.v_begin) >> 6;
     const uint32_t last_step = nsteps ? nsteps - 1u : 0u;
@@ -420,7 +479,8 @@ __global__ void clear_words_kernel(unsigned long long *p, size_t n) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
 }
 
-static hipError_t launch_spmv(const csb_matrix *mat, const float *x0, uint32_t n0, const float *x1, float *y,
+template <bool GATED>
+static hipError_t launch_spmv(const csb_matrix *mat, const SpmvSrc<GATED> &g0, uint32_t n0, const SpmvSrc<GATED> &g1, float *y,
                               unsigned long long *partials, hipStream_t stream, unsigned long long *stamps = nullptr) {
     const DevHeader &h = mat->plan.hdr;
     const DevMat dm = dev_mat(mat);
@@ -449,13 +509,13 @@ static hipError_t launch_spmv(const csb_matrix *mat, const float *x0, uint32_t n
     auto go = [&](auto kern, int nw) -> hipError_t {
         hipError_t e = ensure_dynamic_lds((const void *)kern, lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3(h.n_chunks), dim3(nw * 64), lds, stream, dm, x0, n0, x1, y, partials, epoch, L, stamps);
+        hipLaunchKernelGGL(kern, dim3(h.n_chunks), dim3(nw * 64), lds, stream, dm, g0, n0, g1, y, partials, epoch, L, stamps);
         return hipGetLastError();
     };
     if (h.waves_per_chunk != (uint32_t)kSpmvWaves) return hipErrorInvalidValue;
-    if (h.val_fmt == CSB_VAL_F16) return go(spmv_kernel<CSB_VAL_F16>, kSpmvWaves);
-    if (h.val_fmt == CSB_VAL_BF16) return go(spmv_kernel<CSB_VAL_BF16>, kSpmvWaves);
-    return go(spmv_kernel<CSB_VAL_F32>, kSpmvWaves);
+    if (h.val_fmt == CSB_VAL_F16) return go(spmv_kernel<CSB_VAL_F16, GATED>, kSpmvWaves);
+    if (h.val_fmt == CSB_VAL_BF16) return go(spmv_kernel<CSB_VAL_BF16, GATED>, kSpmvWaves);
+    return go(spmv_kernel<CSB_VAL_F32, GATED>, kSpmvWaves);
 }
 
 int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const float *d_x1, float *d_y,
@@ -463,8 +523,33 @@ int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const flo
     if (!m->plan.valid || !m->uploaded || !m->d_buf) { set_error("csb_spmv: matrix not planned and uploaded"); return CSB_ESTATE; }
     if (m->plan.hdr.cols > (uint64_t)kMaxStageCols) { set_error("csb_spmv: more columns than the LDS staging covers"); return CSB_EUNSUPPORTED; }
     if (m->plan.hdr.n_partial_slots && !d_ws) { set_error("csb_spmv: workspace is NULL"); return CSB_EINVAL; }
-    hipError_t e = launch_spmv(m, d_x0, n0, d_x1, d_y, (unsigned long long *)d_ws, (hipStream_t)stream, d_stamps);
+    hipError_t e = launch_spmv<false>(m, SpmvSrc<false>{d_x0}, n0, SpmvSrc<false>{d_x1}, d_y, (unsigned long long *)d_ws,
+                                      (hipStream_t)stream, d_stamps);
     if (e != hipSuccess) { set_error(std::string("csb_spmv: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    return CSB_OK;
+}
+
+int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *d_ws, void *stream) {
+    if (!m->plan.valid || !m->uploaded || !m->d_buf) { set_error("csb_spmv: matrix not planned and uploaded"); return CSB_ESTATE; }
+    if (m->plan.hdr.cols > (uint64_t)kMaxStageCols) { set_error("csb_spmv: more columns than the LDS staging covers"); return CSB_EUNSUPPORTED; }
+    if (m->plan.hdr.n_partial_slots && !d_ws) { set_error("csb_spmv: workspace is NULL"); return CSB_EINVAL; }
+    // a computed segment has exactly one entry per unit of its cell
+    if ((s0.kind && s0.H != n0) || (s1.kind && (uint64_t)s1.H + n0 != m->plan.hdr.cols)) {
+        set_error("csb_spmv: a computed input segment does not match the matrix's column split");
+        return CSB_EINVAL;
+    }
+    SpmvSrc<true> g0, g1;
+    static_cast<GateSrc &>(g0) = s0;
+    static_cast<GateSrc &>(g1) = s1;
+    hipError_t e = launch_spmv<true>(m, g0, n0, g1, d_y, (unsigned long long *)d_ws, (hipStream_t)stream, nullptr);
+    if (e != hipSuccess) { set_error(std::string("csb_spmv: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    return CSB_OK;
+}
+
+int commit_gates(const GateSrc &s, void *stream) {
+    hipLaunchKernelGGL(commit_gates_kernel, dim3((s.H + 255) / 256), dim3(256), 0, (hipStream_t)stream, s);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
 }
 
