@@ -175,7 +175,12 @@ size_t csb_device_bytes(const csb_matrix *m);
 int csb_upload(csb_matrix *m, void *d_buf, size_t bytes, void *stream);
 
 /* Bytes of scratch csb_spmv / csb_spmm need for `batch` right-hand sides (partial sums of
- * row tiles that several workgroups share).  Contents need no initialisation. */
+ * row tiles that several workgroups share).  Contents need no initialisation.
+ * Workspaces in general (this one, csb_rnn_forward's, csb_project's): a buffer may be handed to
+ * different handles and entry points in turn, never to two calls that overlap in time.  The
+ * library identifies a workspace by its base address and clears the words that workgroups
+ * exchange through it whenever another handle or entry point has used the buffer in between;
+ * writing into a workspace yourself between two calls on the same handle is not allowed. */
 size_t csb_workspace_bytes(const csb_matrix *m, int32_t batch);
 
 /*

@@ -164,6 +164,11 @@ float f16_bits_to_f32(uint16_t h);
 uint16_t f32_to_bf16_bits(float f);
 inline float bf16_bits_to_f32(uint16_t h) { uint32_t u = (uint32_t)h << 16; float f; __builtin_memcpy(&f, &u, 4); return f; }
 uint32_t reserve_tags(uint32_t count, uint32_t *generation);
+// Records `user` as the last user of the caller's workspace `ws` (a workspace is identified by
+// its base address) and tells whether somebody else has used it since `user` last did.  What
+// that somebody wrote there may look like anything, a tagged word included, so the tagged words
+// that `user` keeps in the workspace have to be cleared again before they are polled.
+bool workspace_changed_hands(const void *ws, const void *user);
 
 }  // namespace csb
 

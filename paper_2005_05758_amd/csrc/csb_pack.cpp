@@ -3,6 +3,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <unordered_map>
 
 #include "csb_internal.hpp"
 
@@ -24,6 +25,17 @@ uint32_t reserve_tags(uint32_t count, uint32_t *generation) {
     next = n0 + count;
     *generation = (uint32_t)(n0 >> 32);
     return (uint32_t)n0;
+}
+
+bool workspace_changed_hands(const void *ws, const void *user) {
+    static std::mutex mu;
+    static std::unordered_map<const void *, const void *> last_user;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = last_user.find(ws);
+    if (it == last_user.end()) { last_user.emplace(ws, user); return true; }
+    const bool changed = it->second != user;
+    it->second = user;
+    return changed;
 }
 }  // namespace csb
 

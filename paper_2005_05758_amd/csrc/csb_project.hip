@@ -293,6 +293,8 @@ extern "C" int csb_project(const float *d_W, int64_t rows, int64_t cols, int64_t
         set_error("csb_project: more than 16384 rows or columns (one workgroup ranks a block-column in LDS)");
         return CSB_EUNSUPPORTED;
     }
+    static const char project_user = 0;                    // this entry point as a user of workspaces
+    workspace_changed_hands(d_ws, &project_user);
     const uint32_t R = (uint32_t)rows, C = (uint32_t)cols, BR = (uint32_t)br, BC = (uint32_t)bc;
     const uint32_t NBR = (R + BR - 1) / BR, NBC = (C + BC - 1) / BC;
     const ProjectLayout L = project_layout(rows, cols, br, bc);

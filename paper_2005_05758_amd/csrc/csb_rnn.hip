@@ -1254,6 +1254,13 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
                 return CSB_ESTATE;
             }
     }
+    // Another handle (or another kind of call) may have used this workspace since this one did:
+    // whatever it left there must not be taken for tagged words of this call.
+    if (d_ws && workspace_changed_hands(d_ws, r)) {
+        r->ws_seen = nullptr;
+        for (auto *m : r->W) m->ws_seen = nullptr;
+        for (auto *m : r->Wp) m->ws_seen = nullptr;
+    }
     if (resident) return forward_resident(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, d_ws, st);
 
     const RnnWs wl = ws_layout(r, batch, T);

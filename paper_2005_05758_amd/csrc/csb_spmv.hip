@@ -571,6 +571,7 @@ extern "C" int csb_upload(csb_matrix *m, void *d_buf, size_t bytes, void *stream
 extern "C" int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws, void *stream) {
     if (!m || !d_x || !d_y) { csb::set_error("csb_spmv: NULL pointer"); return CSB_EINVAL; }
     if (m->plan.valid && m->plan.split.active()) { csb::set_error("csb_spmv: matrix is planned for a GRU step"); return CSB_ESTATE; }
+    if (d_ws && csb::workspace_changed_hands(d_ws, m)) m->ws_seen = nullptr;   // merge words: clear again
     return csb::spmv_segments(m, d_x, (uint32_t)m->cols, d_x, d_y, d_ws, stream, nullptr);
 }
 
@@ -611,5 +612,6 @@ extern "C" int csb_debug_spmv_stamps(const csb_matrix *m, const float *d_x, floa
                                      unsigned long long *d_stamps, void *stream) {
     if (!m || !d_x || !d_y || !d_stamps) { csb::set_error("csb_debug_spmv_stamps: NULL pointer"); return CSB_EINVAL; }
     if (m->plan.valid && m->plan.split.active()) { csb::set_error("csb_debug_spmv_stamps: matrix is planned for a GRU step"); return CSB_ESTATE; }
+    if (d_ws && csb::workspace_changed_hands(d_ws, m)) m->ws_seen = nullptr;
     return csb::spmv_segments(m, d_x, (uint32_t)m->cols, d_x, d_y, d_ws, stream, d_stamps);
 }

@@ -192,3 +192,50 @@ def test_rnn_zero_weights_closed_form(B, resident):
             assert np.allclose(hT.cpu().numpy(), 0.5 * np.tanh(c0.astype(np.float64) / 2.0 ** T), rtol=1e-5, atol=1e-9)
         else:
             assert np.allclose(hT.cpu().numpy(), h0 / 2.0 ** T, rtol=1e-6, atol=0)
+
+
+def test_rnn_handles_sharing_one_workspace_with_changing_lengths():
+    """Three models take turns on ONE workspace buffer (a resident LSTM, a resident GRU, a
+    streaming LSTM whose matrices are cut with shared row tiles, so its mat-vecs merge partial
+    sums through tagged words), with sequence lengths going down and up again: the words that
+    workgroups hand to each other carry launch tags, and stale words of another model, or of a
+    longer earlier call, must never be taken for current ones."""
+    T_max = 40
+    cfgs = [csb_inputs.RnnConfig("a", csb_inputs.LSTM, 2, 20, 96, 16, 3.0, "binomial", 0.2, 1, T_max, 11),
+            csb_inputs.RnnConfig("b", csb_inputs.GRU, 1, 33, 300, 32, 4.0, "binomial", 0.1, 1, T_max, 12),
+            csb_inputs.RnnConfig("c", csb_inputs.LSTM, 1, 24, 64, 16, 2.0, "binomial", 0.2, 1, T_max, 13)]
+    wls = [csb_inputs.make_rnn(c) for c in cfgs]
+    rnns = []
+    for k, wl in enumerate(wls):
+        cfg = wl.cfg
+        Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+        bias = [torch.from_numpy(b).cuda() for b in wl.bias]
+        if k == 2:
+            for w in Ws:
+                w.plan(7, 2)                                   # equal split: row tiles shared between workgroups
+                assert w.stats["n_shared_tiles"] > 0
+        rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, bias)
+        if k < 2:
+            assert rnn.stats()["resident"] == 1 and rnn.stats()["n_workgroups"] > 1
+            rnn.upload()
+        else:
+            for w in Ws:
+                w.upload()
+        rnns.append(rnn)
+    need = max(r.workspace_bytes(1, T_max) for r in rnns)
+    shared = torch.empty(need // 4 + 64, dtype=torch.float32, device="cuda")
+    shared.fill_(float("nan"))                                 # whatever an allocator may hand out
+    for r in rnns:
+        r._ws = shared
+    refs = {}
+    for k, T in [(0, 40), (1, 40), (2, 40), (0, 7), (1, 13), (2, 5), (1, 40), (0, 40), (2, 40), (0, 1), (0, 40)]:
+        wl, cfg = wls[k], wls[k].cfg
+        say(f"[rnn] shared workspace: model {k} T={T}")
+        if (k, T) not in refs:
+            refs[(k, T)] = oracle.rnn_forward(cfg.cell, [m.A for m in wl.W], wl.bias, wl.x[:T], cfg.input, cfg.hidden)
+        rseq, rhT, _ = refs[(k, T)]
+        hseq, hT, _ = rnns[k].forward(torch.from_numpy(wl.x[:T]).cuda())
+        torch.cuda.synchronize()
+        assert rnns[k]._ws is shared
+        assert float(np.max(np.abs(hseq.cpu().numpy() - rseq))) <= TOL
+        assert float(np.max(np.abs(hT.cpu().numpy() - rhT))) <= TOL
