@@ -731,11 +731,17 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         // ---- this lane's slice of its row ----------------------------------------------------
         float acc = 0.0f;
         const uint8_t *zb = (const uint8_t *)z;
-        float zv[SMAX];
+        // all gathers of a lane first, then its multiply-adds; with many slots in batches of 8,
+        // or the gathered values alone would push the weights out of the register file
+        constexpr int CH = SMAX > 24 ? 8 : SMAX;
 #pragma unroll
-        for (int s = 0; s < SMAX; ++s) zv[s] = *(const float *)(zb + za[s]);   // unused slots read the zero entry
+        for (int s0 = 0; s0 < SMAX; s0 += CH) {
+            float zv[CH];
 #pragma unroll
-        for (int s = 0; s < SMAX; ++s) acc = fmaf(w[s], zv[s], acc);
+            for (int s = 0; s < CH; ++s) zv[s] = *(const float *)(zb + za[s0 + s]);   // unused slots read the zero entry
+#pragma unroll
+            for (int s = 0; s < CH; ++s) acc = fmaf(w[s0 + s], zv[s], acc);
+        }
         // ---- row sum: inclusive scan over the segment's lanes (inside a 32-lane half) ---------
         // (every lane executes the shifts; only the add is conditional).  A segment of up to
         // 16 lanes lies inside one 16-lane row; a longer one fills an even row and continues at

@@ -239,3 +239,16 @@ def test_rnn_handles_sharing_one_workspace_with_changing_lengths():
         assert rnns[k]._ws is shared
         assert float(np.max(np.abs(hseq.cpu().numpy() - rseq))) <= TOL
         assert float(np.max(np.abs(hT.cpu().numpy() - rhT))) <= TOL
+
+
+@pytest.mark.parametrize("slots,rate", [(4, 8.0), (8, 4.0), (12, 1.5), (16, 1.5), (24, 1.5), (32, 1.5), (40, 1.5), (48, 1.5)])
+@pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
+def test_rnn_resident_every_slot_count(cell, slots, rate, monkeypatch):
+    """The resident kernel is compiled once per number of weights a lane keeps (4 to 48 in fours); the
+    layout normally picks the smallest that fits.  CSB_RNN_S forces each of them in turn on a
+    model dense enough to fill the slots (the forms beyond 24 slots gather in batches)."""
+    monkeypatch.setenv("CSB_RNN_S", str(slots))
+    cfg = csb_inputs.RnnConfig("t", cell, 2, 60, 160, 32, rate, "binomial", 0.08, 1, 12, 21 + slots)
+    wl = csb_inputs.make_rnn(cfg)
+    rnn, _ = run_case(wl, tag=f"slots-{slots}", resident=True)
+    assert rnn.stats()["slots_per_lane"] == slots
