@@ -456,7 +456,7 @@ def projection_leg(torch, np, stream_gbps, with_cpu):
 def lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
     """The shape of the paper's speech model SR1 (Table 1): two LSTMP layers, 153 -> 1024 and
     512 -> 1024 with a 512-wide projection, 13x in 32 x 32 blocks, synthetic weights.  Batch 1
-    (one frame at a time: two CSB mat-vecs and a gate kernel per layer and frame) and batch 32
+    (one frame at a time: streaming, two CSB mat-vec launches per layer and frame; and resident) and batch 32
     on the matrix cores.  The paper's FPGA figure for its trained SR1 is 6.58 us per frame
     (another machine, 16-bit fixed point: context, not a baseline)."""
     from paper_2005_05758_amd import CELL_LSTMP

@@ -279,8 +279,8 @@ int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int32_t hidden
  * state c (d_c0, d_cT) hidden wide.  Batch 1 with the resident layout uploaded
  * (csb_rnn_upload): one kernel launch for the whole sequence, the gate rows and the
  * projection rows of a layer being two stages that hand m_t and r_t to each other; else the
- * streaming paths (two CSB products and one gate kernel per step and layer; batch > 1 on the
- * matrix cores).  Errors as csb_rnn_create.
+ * streaming paths (two CSB products per step and layer; batch > 1 on the matrix cores, with
+ * an element-wise kernel between them).  Errors as csb_rnn_create.
  */
 int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hidden, int32_t proj,
                          csb_matrix *const *W, csb_matrix *const *Wp, const float *const *d_bias,
@@ -317,8 +317,8 @@ int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
  * 256-byte aligned, >= csb_rnn_device_bytes, valid while the handle is used) csb_rnn_forward
  * with batch 1 runs all timesteps of all layers in ONE kernel launch; without it, or for
  * batch > 1, it launches one CSB product per step and layer and needs every W[l] uploaded
- * (batch 1, LSTM / GRU / Li-GRU: nothing else -- the gates of a step are computed by the
- * launches that consume its output; otherwise an element-wise kernel follows each product).
+ * (batch 1: nothing else -- the gates of a step are computed by the launches that consume its
+ * output; batch > 1: an element-wise kernel follows each product).
  * The resident kernel's workgroups wait for each other's h_t: they must all be on the GPU at
  * once, so nothing else should occupy the device while it runs.  The workgroups are placed on
  * as few of the 8 XCDs as hold them (at most 28 per XCD, one per CU).

@@ -15,15 +15,22 @@ namespace csb {
 // reads it.  kind 0: a plain vector at `a`.
 struct GateSrc {
     const float *a;        // kind 0: the vector itself; else the sums, rows stacked as the cell stacks them
+    const float *a2;       // reset-before GRU, gate part: the candidate's recurrent sums Un (r h_(t-1))
     const float *bias;     // may be null
     const float *c_in;     // LSTM: c_(t-1)
     const float *h_in;     // GRU, Li-GRU: h_(t-1)
     float *c_out, *h_out;  // where c_t (LSTM) and h_t go; distinct from c_in / h_in
     float *hseq;           // also h_t, or null
-    uint32_t kind;         // 0 plain, else 1 + CSB_CELL_LSTM / _GRU / _LIGRU
+    uint32_t kind;         // 0 plain, else 1 + CSB_CELL_LSTM / _GRU / _LIGRU, or one of the two below
     uint32_t H;
 };
-__device__ __host__ inline GateSrc plain_src(const float *v) { return GateSrc{v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u, 0u}; }
+constexpr uint32_t kGateRbReset = 6;   // reset-before GRU: q = sigmoid(a_r) h_(t-1), the operand of the second product
+constexpr uint32_t kGateRbGate = 7;    // reset-before GRU: h_t from the z and n rows of a, and a2
+__device__ __host__ inline GateSrc plain_src(const float *v) {
+    GateSrc g{};
+    g.a = v;
+    return g;
+}
 
 // y = A [x0[0..n0) ; x1[0..cols-n0)] on `stream`; y has the image's rows_out entries.
 int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const float *d_x1, float *d_y,

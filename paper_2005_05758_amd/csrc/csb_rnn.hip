@@ -840,19 +840,8 @@ __global__ void gru_gates_batched_kernel(const float *__restrict__ a, const floa
     if (hseq) hseq[(size_t)n * H + k] = hn;
 }
 
-// LSTMP: the cell output m_t = o tanh(c_t) goes to a buffer of its own; the projection
-// r_t = Wp m_t (a CSB mat-vec) follows.
-__global__ void lstmp_gates_kernel(const float *__restrict__ a, const float *__restrict__ bias,
-                                   float *__restrict__ c, float *__restrict__ m, const int H) {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= H) return;
-    float ai = a[k], af = a[H + k], ag = a[2 * H + k], ao = a[3 * H + k];
-    if (bias) { ai += bias[k]; af += bias[H + k]; ag += bias[2 * H + k]; ao += bias[3 * H + k]; }
-    const float cn = sigmoidf_(af) * c[k] + sigmoidf_(ai) * tanhf(ag);
-    c[k] = cn;
-    m[k] = sigmoidf_(ao) * tanhf(cn);
-}
-
+// LSTMP, batched: the cell output m_t = o tanh(c_t) goes to a buffer of its own ([H][B]); the
+// projection r_t = Wp m_t (a CSB product) follows.
 __global__ void lstmp_gates_batched_kernel(const float *__restrict__ a, const float *__restrict__ bias,
                                            float *__restrict__ c, float *__restrict__ m, const int H, const int B) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
@@ -982,12 +971,12 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
         w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     }
     w.off_m = off; off = align256(off + ((r->proj > 0 || two_products) ? (size_t)batch * r->hidden * sizeof(float) : 0));
-    // one-launch-per-step streaming (batch 1, LSTM / GRU / Li-GRU): per layer two buffers of gate
-    // sums and two of (c, h), used alternately by even and odd steps
-    const bool fused = batch == 1 && (r->cell == CSB_CELL_LSTM || r->cell == CSB_CELL_GRU || r->cell == CSB_CELL_LIGRU);
+    // streaming at batch 1: per layer two buffers of gate sums (plus the second product's sums of
+    // the reset-before GRU) and two of (c, h), used alternately by even and odd steps
+    const bool fused = batch == 1;
     w.rows_out = rows_out;
-    w.off_fa = off; off = align256(off + (fused ? 2 * (size_t)r->n_layers * rows_out * sizeof(float) : 0));
-    w.off_fs = off; off = align256(off + (fused ? 4 * (size_t)r->n_layers * r->hidden * sizeof(float) : 0));
+    w.off_fa = off; off = align256(off + (fused ? 2 * (size_t)r->n_layers * (rows_out + r->hidden) * sizeof(float) : 0));
+    w.off_fs = off; off = align256(off + (fused ? 4 * (size_t)r->n_layers * std::max<size_t>(r->hidden, HS) * sizeof(float) : 0));
     off += 512;   // last 512 bytes: debug clocks of the resident kernel
     w.total = off;
     return w;
@@ -1356,34 +1345,68 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         }
         return CSB_OK;
     }
-    float *c = (lstm && d_cT) ? d_cT : (float *)((uint8_t *)d_ws + wl.off_c);
-    float *mb = (float *)((uint8_t *)d_ws + wl.off_m);
-    // the outputs double as the running state
-    init_state(d_hT, d_h0, nstate, st);
-    if (lstm) init_state(c, d_c0, ncstate, st);
-    const int gblocks = (H + 255) / 256;
-    for (int t = 0; t < T; ++t)
-        for (int s = 0; s < batch; ++s)
+    // LSTMP and the reset-before GRU: two products per step and layer, the element-wise parts
+    // again inside the launches that consume them (two launches per step and layer).
+    float *fa = (float *)((uint8_t *)d_ws + wl.off_fa), *fs = (float *)((uint8_t *)d_ws + wl.off_fs);
+    const size_t SW = (size_t)std::max(H, HS);                   // room of one state vector
+    auto sums = [&](int l, int t) { return fa + ((size_t)l * 2 + (size_t)(t & 1)) * (wl.rows_out + (size_t)H); };
+    auto sums2 = [&](int l, int t) { return sums(l, t) + wl.rows_out; };       // reset-before GRU: Un q
+    auto c_of = [&](int l, int t) { return fs + (((size_t)l * 2 + (size_t)(t & 1)) * 2) * SW; };
+    auto h_buf = [&](int l, int t) { return c_of(l, t) + SW; };
+    for (int l = 0; l < L; ++l) {
+        init_state(h_buf(l, -1), d_h0 ? d_h0 + (size_t)l * HS : nullptr, (size_t)HS, st);
+        if (lstmp) init_state(c_of(l, -1), d_c0 ? d_c0 + (size_t)l * H : nullptr, (size_t)H, st);
+    }
+    if (lstmp) {
+        // r_(l,t), the projected output, is a plain vector (the result of the layer's second
+        // product); the last layer's goes straight into the output sequence when one is asked for
+        auto r_of = [&](int l, int t) {
+            return (t >= 0 && d_hseq && l == L - 1) ? d_hseq + (size_t)t * HS : h_buf(l, t);
+        };
+        for (int t = 0; t < T; ++t)
             for (int l = 0; l < L; ++l) {
-                const float *u = l == 0 ? d_x + ((size_t)t * batch + s) * I : d_hT + ((size_t)(l - 1) * batch + s) * HS;
-                const uint32_t n_in = l == 0 ? (uint32_t)I : (uint32_t)HS;
-                float *h = d_hT + ((size_t)l * batch + s) * HS;
-                int rc = spmv_segments(r->W[l], u, n_in, h, a, part, st);
+                const float *u = l == 0 ? d_x + (size_t)t * I : (const float *)r_of(l - 1, t);
+                int rc = spmv_segments(r->W[l], u, l == 0 ? (uint32_t)I : (uint32_t)HS, r_of(l, t - 1), sums(l, t), part, st);
                 if (rc != CSB_OK) return rc;
-                float *hs = (d_hseq && l == L - 1) ? d_hseq + ((size_t)t * batch + s) * HS : nullptr;
-                if (lstmp) {
-                    hipLaunchKernelGGL(lstmp_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l],
-                                       c + ((size_t)l * batch + s) * H, mb, H);
-                    rc = spmv_segments(r->Wp[l], mb, (uint32_t)H, mb, h, part, st);
-                    if (rc != CSB_OK) return rc;
-                    if (hs) hipLaunchKernelGGL(copy_kernel, dim3((HS + 255) / 256), dim3(256), 0, st, hs, (const float *)h, (size_t)HS);
-                } else {                                     // reset-before GRU (the other cells took the one-launch path above)
-                    hipLaunchKernelGGL(gru_rb_reset_kernel, dim3(gblocks), dim3(256), 0, st, a, r->d_bias[l], (const float *)h, mb, H, 1);
-                    rc = spmv_segments(r->Wp[l], mb, (uint32_t)H, mb, a2, part, st);
-                    if (rc != CSB_OK) return rc;
-                    hipLaunchKernelGGL(gru_rb_gates_kernel, dim3(gblocks), dim3(256), 0, st, a, a2, r->d_bias[l], h, hs, H, 1);
-                }
+                GateSrc m{};                                     // m_t = o tanh(c_t): the LSTM cell on the sums
+                m.a = sums(l, t); m.bias = r->d_bias[l];
+                m.c_in = c_of(l, t - 1); m.c_out = c_of(l, t);
+                m.kind = 1u + CSB_CELL_LSTM; m.H = (uint32_t)H;
+                rc = spmv_gated(r->Wp[l], m, (uint32_t)H, plain_src(m.a), r_of(l, t), part, st);
+                if (rc != CSB_OK) return rc;
             }
+        for (int l = 0; l < L; ++l) {
+            init_state(d_hT + (size_t)l * HS, r_of(l, T - 1), (size_t)HS, st);
+            if (d_cT) init_state(d_cT + (size_t)l * H, c_of(l, T - 1), (size_t)H, st);
+        }
+    } else {
+        auto cell_output = [&](int l, int t) {                   // h_(l,t) from the two sums of step t
+            GateSrc g{};
+            g.a = sums(l, t); g.a2 = sums2(l, t); g.bias = r->d_bias[l];
+            g.h_in = h_buf(l, t - 1); g.h_out = h_buf(l, t);
+            g.hseq = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * H : nullptr;
+            g.kind = kGateRbGate; g.H = (uint32_t)H;
+            return g;
+        };
+        for (int t = 0; t < T; ++t)
+            for (int l = 0; l < L; ++l) {
+                const GateSrc below = l == 0 ? plain_src(d_x + (size_t)t * I) : cell_output(l - 1, t);
+                const GateSrc back = t == 0 ? plain_src(h_buf(l, -1)) : cell_output(l, t - 1);
+                int rc = spmv_gated(r->W[l], below, l == 0 ? (uint32_t)I : (uint32_t)H, back, sums(l, t), part, st);
+                if (rc != CSB_OK) return rc;
+                GateSrc q{};                                     // q = r h_(t-1); h_(t-1) was stored by the launch above
+                q.a = sums(l, t); q.bias = r->d_bias[l]; q.h_in = h_buf(l, t - 1);
+                q.kind = kGateRbReset; q.H = (uint32_t)H;
+                rc = spmv_gated(r->Wp[l], q, (uint32_t)H, plain_src(q.a), sums2(l, t), part, st);
+                if (rc != CSB_OK) return rc;
+            }
+        for (int l = 0; l < L; ++l) {
+            GateSrc g = cell_output(l, T - 1);
+            g.h_out = d_hT + (size_t)l * H;
+            int rc = commit_gates(g, st);
+            if (rc != CSB_OK) return rc;
+        }
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;

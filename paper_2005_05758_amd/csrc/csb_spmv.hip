@@ -140,6 +140,15 @@ __device__ __forceinline__ float gate_value(const GateSrc &s, uint32_t u, bool s
         if (b) { ar += b[u]; az += b[H + u]; anx += b[2 * H + u]; }
         const float r = sigmoid_(ar), z = sigmoid_(az);
         hn = (1.0f - z) * tanhf(anx + r * anh) + z * s.h_in[u];
+    } else if (s.kind == kGateRbReset) {                       // rows r,z,n; only r is needed here
+        float ar = a[u];
+        if (b) ar += b[u];
+        hn = sigmoid_(ar) * s.h_in[u];
+    } else if (s.kind == kGateRbGate) {
+        float az = a[H + u], an = a[2 * H + u] + s.a2[u];
+        if (b) { az += b[H + u]; an += b[2 * H + u]; }
+        const float z = sigmoid_(az);
+        hn = (1.0f - z) * tanhf(an) + z * s.h_in[u];
     } else {                                                   // Li-GRU
         float az = a[u], ac = a[H + u];
         if (b) { az += b[u]; ac += b[H + u]; }

@@ -138,3 +138,43 @@ def test_gru_rb_rejects_recurrent_entries_in_the_n_rows_of_wa():
     with pytest.raises(CsbError):                      # wrong shape of Un
         Wa, _ = csb_inputs.split_gru_rb(A, 6, 8)
         CsbRnn(CELL_GRU_RB, 6, 8, [CsbMatrix(Wa, 4, 4)], None, Wp=[CsbMatrix(A[:8, :7].copy(), 4, 4)])
+
+
+@pytest.mark.parametrize("kind", ["lstm", "gru", "ligru", "gru_rb", "lstmp"])
+@pytest.mark.parametrize("resident", [False, True])
+def test_final_state_does_not_depend_on_asking_for_the_sequence(kind, resident):
+    """Without an output sequence the streaming paths keep h_t in workspace buffers only (with
+    one, the last layer's goes straight into it): both must end in the same state, bit for bit."""
+    from paper_2005_05758_amd import CELL_LSTM, CELL_GRU, CELL_LSTMP
+    L, I, H, P, T, block = 2, 20, 48, 24, 9, 16
+    if kind == "lstmp":
+        wl = csb_inputs.make_lstmp(5, L, I, H, P, block, 3.0, T, 1, sigma=0.2)
+        Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+        Ps = [CsbMatrix(m.A, m.br, m.bc) for m in wl.Wp]
+        rnn = CsbRnn(CELL_LSTMP, I, H, Ws, [torch.from_numpy(b).cuda() for b in wl.bias], proj=P, Wp=Ps)
+        mats = Ws + Ps
+    elif kind == "gru_rb":
+        wl = workload(csb_inputs.GRU_RB, L, I, H, T, 1, block, 5, sigma=0.2)
+        parts = [csb_inputs.split_gru_rb(m.A, I if l == 0 else H, H) for l, m in enumerate(wl.W)]
+        Was = [CsbMatrix(p[0], block, block) for p in parts]
+        Uns = [CsbMatrix(p[1], block, block) for p in parts]
+        rnn = CsbRnn(CELL_GRU_RB, I, H, Was, [torch.from_numpy(b).cuda() for b in wl.bias], Wp=Uns)
+        mats = Was + Uns
+    else:
+        cell = {"lstm": CELL_LSTM, "gru": CELL_GRU, "ligru": CELL_LIGRU}[kind]
+        wl = workload(cell, L, I, H, T, 1, block, 5, sigma=0.2)
+        mats = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+        rnn = CsbRnn(cell, I, H, mats, [torch.from_numpy(b).cuda() for b in wl.bias])
+    if resident:
+        rnn.upload()
+    else:
+        for m in mats:
+            m.upload()
+    say(f"[cells] with / without sequence: {kind} resident={resident}")
+    xd = torch.from_numpy(wl.x).cuda()
+    s1, h1, c1 = rnn.forward(xd, want_hseq=True)
+    s2, h2, c2 = rnn.forward(xd, want_hseq=False)
+    torch.cuda.synchronize()
+    assert s2 is None and torch.equal(h1, h2) and torch.equal(s1[-1, 0], h1[-1, 0])
+    if c1 is not None:
+        assert torch.equal(c1, c2)
