@@ -10,9 +10,13 @@ better) with the algorithmic GB/s beside it.
 
 Also reported on the same JSON line:
   roofline      -- the dominant kernel of the headline workload
+  streaming_path-- the same workload without the resident layout (weights re-streamed per step)
+  rnn_configs   -- the other batch-1 workloads per timestep; csb_spmv on every RNN matrix, warm / cold
   spmv_stress   -- csb_spmv on the 8192 x 8192 heavy-tailed matrix (the HBM-bound case),
                    warm (matrix resident in the Infinity Cache) and cold (rotating over
                    distinct device copies of the matrix, > 512 MB in total)
+  batched       -- csb_spmm on the matrix cores (8192^2 x 128, cfg4 x 64) and the cfg4 model at batch 64
+  projection, lstmp_sr1, cells, weights_16bit -- the rows built after the hot path
   cpu_baseline  -- the CPU oracle timed on this machine's host cores on the same workload
 """
 from __future__ import annotations
@@ -227,6 +231,7 @@ def main():
         sr = stream_read_leg(torch, stream_read)
         out["hbm_stream_read"] = sr
         out["pct_of_measured_stream_read"] = round(100.0 * gbps / sr["gbps"], 4)
+        out["rnn_configs"] = rnn_configs_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, stream_read, args.workload)
         out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix, sr["gbps"], sr["image_sized_cold"]["us"])
         out["batched"] = batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
         out["projection"] = projection_leg(torch, np, sr["gbps"], not args.no_cpu)
@@ -236,6 +241,70 @@ def main():
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_leg(cfg, wl)
     print(json.dumps(out))
+
+
+def rnn_configs_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, stream_read, headline):
+    """The other batch-1 workloads (the headline one is timed above): microseconds per timestep
+    with the resident layout and streaming, and csb_spmv on the first layer's matrix of every
+    batch-1 workload, warm (back to back) and cold (a 2 GiB streaming read between launches
+    empties the caches; one event pair around each launch, median)."""
+    res = {}
+    flush = torch.ones(512 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    sink = stream_read(flush)
+    for name in ("cfg1", "cfg2", "cfg3"):
+        cfg = csb_inputs.CONFIGS[name]
+        wl = csb_inputs.make_rnn(cfg)
+        entry = {"workload": f"{'LSTM' if cfg.cell == 0 else 'GRU'} {cfg.input}->{cfg.hidden} x{cfg.n_layers}, block {cfg.block}, "
+                             f"{cfg.rate:g}x, T={cfg.T}"}
+        Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+        views = [w.view() for w in Ws]
+        bytes_step = rnn_step_alg_bytes(views, cfg.cell, cfg.hidden, 1)
+        entry["alg_bytes_per_timestep"] = bytes_step
+        if name != headline:
+            bias = [torch.from_numpy(b).cuda() for b in wl.bias]
+            xd = torch.from_numpy(wl.x).cuda()
+            for mode in ("resident", "streaming"):
+                rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, bias)
+                if mode == "resident":
+                    rnn.upload()
+                else:
+                    for w in Ws:
+                        w.upload()
+                for _ in range(5):
+                    rnn.forward(xd, want_hseq=True)
+                n = 30
+                us = time_region(lambda: rnn.forward(xd, want_hseq=True), n, torch) * 1000.0 / (n * cfg.T)
+                entry[f"{mode}_us_per_timestep"] = round(us, 3)
+                entry[f"{mode}_gbps_algorithmic"] = round(bytes_step / us / 1e3, 1)
+                del rnn
+        M = CsbMatrix(wl.W[0].A, wl.W[0].br, wl.W[0].bc)
+        M.plan()
+        M.upload()
+        ab = spmv_alg_bytes(M.view())
+        x = torch.from_numpy(csb_inputs.make_vectors(5, wl.W[0].cols, 1)).cuda()
+        y = torch.empty(wl.W[0].rows, dtype=torch.float32, device="cuda")
+        for _ in range(10):
+            M.spmv(x, y)
+        n = 200
+        us_warm = time_region(lambda: M.spmv(x, y), n, torch) * 1000.0 / n
+        cold = []
+        for _ in range(15):
+            stream_read(flush, sink)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            M.spmv(x, y)
+            b.record()
+            torch.cuda.synchronize()
+            cold.append(a.elapsed_time(b) * 1000.0)
+        cold.sort()
+        us_cold = cold[len(cold) // 2]
+        entry["spmv_layer0"] = {"shape": [int(wl.W[0].rows), int(wl.W[0].cols)], "nnz": int(M.view()["nnz"]), "alg_bytes": ab,
+                                "us_warm": round(us_warm, 2), "us_cold": round(us_cold, 2),
+                                "gbps_cold": round(ab / us_cold / 1e3, 1)}
+        res[name] = entry
+    res["note"] = ("at these sizes a mat-vec launch is a fixed chain of dependent phases (about 6.5 us of kernel time "
+                   "whatever the matrix holds): the resident kernel exists because of that")
+    return res
 
 
 def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps, image_read_us=None):
