@@ -105,7 +105,7 @@ struct DevHeader {
     uint32_t n_chunks, waves_per_chunk, n_groups, n_vbs;
     uint32_t n_shared, n_zero_tiles, n_nz_tiles, n_partial_slots;
     uint32_t br, bc;
-    uint32_t max_chunk_tiles, reserved1;       // LDS sizing: tiles per chunk
+    uint32_t max_chunk_tiles, seg_meta;        // LDS sizing: tiles per chunk; bytes of the largest record segment (batched kernel)
     uint32_t meta_cap, val_fmt;                // bytes of records per chunk; CSB_VAL_* of the value stream
     uint64_t rows_out, cols;
     uint64_t off_chunks, off_waves, off_groups, off_vbs, off_idx, off_vals;
@@ -137,6 +137,7 @@ struct DevMat {
     uint32_t rows_out, cols;
     uint32_t n_groups, n_nz_tiles;
     uint32_t idx_bytes, val_fmt;   // val_fmt != 0: vals holds one 32-bit word per lane and PAIR of steps (even step low)
+    uint32_t seg_meta, pad_;       // LDS bytes the batched kernel sets aside for one record segment
 };
 
 // How rows are relabelled when the image is built for a GRU: entries in rows >= split_row

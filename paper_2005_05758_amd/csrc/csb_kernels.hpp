@@ -50,4 +50,20 @@ int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj
 // before every launch of a path that launches a kernel per timestep.)
 hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes);
 
+// One product of spmm_strided_multi (the arguments of spmm_strided).
+struct SpmmCall {
+    const csb_matrix *mat;
+    const float *p0;
+    uint32_t n0;
+    int64_t sj0, sn0;
+    const float *p1;
+    int64_t sj1, sn1;
+    float *Y;
+    int64_t ldy;
+};
+constexpr int kSpmmMaxJobs = 4;
+// Several independent products of the same batch on `stream`: one launch when their launch
+// shapes agree (the layers of a stacked model), else one launch each.
+int spmm_strided_multi(const SpmmCall *calls, int n, int32_t batch, void *stream);
+
 }  // namespace csb

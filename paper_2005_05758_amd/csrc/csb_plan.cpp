@@ -567,6 +567,9 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
             sr.nvbs = grecs[gb - 1].vb_off + grecs[gb - 1].nvb - sr.vb0;
             sr.idx0 = grecs[ga].idx_off & ~15u;
             sr.idx_bytes = (uint32_t)align_up(idx_end[gb - 1] - sr.idx0, 16);
+            // what the batched kernel stages of it: group records, block records, index bytes
+            const size_t staged = align_up(sr.ng * sizeof(GroupRec), 16) + align_up(sr.nvbs * sizeof(VbRec), 16) + sr.idx_bytes;
+            h.seg_meta = std::max<uint32_t>(h.seg_meta, (uint32_t)align_up(staged + 16, 256));
         }
         h.off_segs = place(segs.size() * sizeof(SegRec));
         h.n_segs = segs.size();

@@ -808,36 +808,45 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
 
 // ------------------------------------------------------------------ streaming path
 
-// Batched element-wise parts: a is [rows][B], the state is kept as [H][B].
-__global__ void lstm_gates_batched_kernel(const float *__restrict__ a, const float *__restrict__ bias,
-                                          float *__restrict__ c, float *__restrict__ h, float *__restrict__ hseq,
-                                          const int H, const int B) {
+// Batched element-wise parts: a is [rows][B], the state is kept as [H][B].  One launch serves
+// the cells of up to kSpmmMaxJobs layers (blockIdx.y), whose products shared a launch too.
+struct GateJobs {
+    const float *a[kSpmmMaxJobs];
+    const float *bias[kSpmmMaxJobs];
+    float *c[kSpmmMaxJobs];       // LSTM only
+    float *h[kSpmmMaxJobs];
+    float *hseq[kSpmmMaxJobs];    // [B][H] of this step, or null
+};
+__global__ void gates_batched_kernel(const GateJobs J, const int cell, const int H, const int B) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= H * B) return;
+    const int j = blockIdx.y;
+    const float *__restrict__ a = J.a[j], *__restrict__ bias = J.bias[j];
+    float *__restrict__ h = J.h[j];
     const int k = e / B, n = e - k * B;
-    float ai = a[(size_t)k * B + n], af = a[(size_t)(H + k) * B + n], ag = a[(size_t)(2 * H + k) * B + n],
-          ao = a[(size_t)(3 * H + k) * B + n];
-    if (bias) { ai += bias[k]; af += bias[H + k]; ag += bias[2 * H + k]; ao += bias[3 * H + k]; }
-    const float cn = sigmoidf_(af) * c[e] + sigmoidf_(ai) * tanhf(ag);
-    const float hn = sigmoidf_(ao) * tanhf(cn);
-    c[e] = cn;
+    float hn;
+    if (cell == CSB_CELL_LSTM) {                       // rows i, f, g, o
+        float *__restrict__ c = J.c[j];
+        float ai = a[(size_t)k * B + n], af = a[(size_t)(H + k) * B + n], ag = a[(size_t)(2 * H + k) * B + n],
+              ao = a[(size_t)(3 * H + k) * B + n];
+        if (bias) { ai += bias[k]; af += bias[H + k]; ag += bias[2 * H + k]; ao += bias[3 * H + k]; }
+        const float cn = sigmoidf_(af) * c[e] + sigmoidf_(ai) * tanhf(ag);
+        hn = sigmoidf_(ao) * tanhf(cn);
+        c[e] = cn;
+    } else if (cell == CSB_CELL_GRU) {                 // rows r, z, input side of n, recurrent side of n
+        float ar = a[(size_t)k * B + n], az = a[(size_t)(H + k) * B + n], anx = a[(size_t)(2 * H + k) * B + n];
+        const float anh = a[(size_t)(3 * H + k) * B + n];
+        if (bias) { ar += bias[k]; az += bias[H + k]; anx += bias[2 * H + k]; }
+        const float r = sigmoidf_(ar), z = sigmoidf_(az);
+        hn = (1.0f - z) * tanhf(anx + r * anh) + z * h[e];
+    } else {                                           // Li-GRU: rows z, candidate
+        float az = a[(size_t)k * B + n], ac = a[(size_t)(H + k) * B + n];
+        if (bias) { az += bias[k]; ac += bias[H + k]; }
+        const float z = sigmoidf_(az);
+        hn = z * h[e] + (1.0f - z) * fmaxf(ac, 0.0f);
+    }
     h[e] = hn;
-    if (hseq) hseq[(size_t)n * H + k] = hn;
-}
-
-__global__ void gru_gates_batched_kernel(const float *__restrict__ a, const float *__restrict__ bias,
-                                         float *__restrict__ h, float *__restrict__ hseq, const int H, const int B) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= H * B) return;
-    const int k = e / B, n = e - k * B;
-    float ar = a[(size_t)k * B + n], az = a[(size_t)(H + k) * B + n], anx = a[(size_t)(2 * H + k) * B + n];
-    const float anh = a[(size_t)(3 * H + k) * B + n];
-    if (bias) { ar += bias[k]; az += bias[H + k]; anx += bias[2 * H + k]; }
-    const float r = sigmoidf_(ar), z = sigmoidf_(az);
-    const float nn = tanhf(anx + r * anh);
-    const float hn = (1.0f - z) * nn + z * h[e];
-    h[e] = hn;
-    if (hseq) hseq[(size_t)n * H + k] = hn;
+    if (J.hseq[j]) J.hseq[j][(size_t)n * H + k] = hn;
 }
 
 // LSTMP, batched: the cell output m_t = o tanh(c_t) goes to a buffer of its own ([H][B]); the
@@ -853,21 +862,6 @@ __global__ void lstmp_gates_batched_kernel(const float *__restrict__ a, const fl
     const float cn = sigmoidf_(af) * c[e] + sigmoidf_(ai) * tanhf(ag);
     c[e] = cn;
     m[e] = sigmoidf_(ao) * tanhf(cn);
-}
-
-// Li-GRU, element-wise part (a is [2H][B], rows z, c; the state [H][B]; B = 1 serves the
-// batch-1 streaming path): z = sig(a_z), cand = max(a_c, 0), h = z h + (1 - z) cand.
-__global__ void ligru_gates_kernel(const float *__restrict__ a, const float *__restrict__ bias,
-                                   float *__restrict__ h, float *__restrict__ hseq, const int H, const int B) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= H * B) return;
-    const int k = e / B, n = e - k * B;
-    float az = a[(size_t)k * B + n], ac = a[(size_t)(H + k) * B + n];
-    if (bias) { az += bias[k]; ac += bias[H + k]; }
-    const float z = sigmoidf_(az);
-    const float hn = z * h[e] + (1.0f - z) * fmaxf(ac, 0.0f);
-    h[e] = hn;
-    if (hseq) hseq[(size_t)n * H + k] = hn;
 }
 
 // GRU with the reset gate before the candidate's recurrent product, first element-wise part:
@@ -957,7 +951,8 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     for (auto *m : r->W) account(m);
     for (auto *m : r->Wp) account(m);
     const size_t HS = (size_t)r->state_width();
-    w.off_a = off; off = align256(off + rows_out * sizeof(float) * (size_t)batch);
+    // (batched: one buffer of gate sums per layer -- the products of different layers share launches)
+    w.off_a = off; off = align256(off + rows_out * sizeof(float) * (size_t)batch * (batch > 1 ? (size_t)r->n_layers : 1));
     const bool two_products = r->cell == CSB_CELL_GRU_RB;          // second product's output, its operand
     w.off_a2 = off; off = align256(off + (two_products ? (size_t)batch * r->hidden * sizeof(float) : 0));
     w.off_c = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
@@ -1228,7 +1223,7 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
     const int L = r->n_layers, H = r->hidden, I = r->input;
     const bool lstmp = r->cell == CSB_CELL_LSTMP;
     const bool lstm = r->cell == CSB_CELL_LSTM || lstmp;        // has a cell state c
-    const bool ligru = r->cell == CSB_CELL_LIGRU, gru_rb = r->cell == CSB_CELL_GRU_RB;
+    const bool gru_rb = r->cell == CSB_CELL_GRU_RB;
     const int HS = r->state_width();                             // width of h (the projection's for LSTMP)
     const size_t nstate = (size_t)L * batch * HS, ncstate = (size_t)L * batch * H;
     if (T == 0) {                                  // hand the state through
@@ -1269,6 +1264,47 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, hi, d_h0, L, batch, HS);
         if (lstm) hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, ci, d_c0, L, batch, H);
         const int gb = (H * batch + 255) / 256;
+        if (!lstmp && !gru_rb) {
+            // One product per layer and step.  Layer l at step t needs layer l - 1 at step t and
+            // itself at step t - 1: everything on the diagonal l + t = d is independent, so a
+            // diagonal takes ONE product launch and ONE gate launch (for up to kSpmmMaxJobs
+            // layers each) instead of one pair per layer -- a single layer's product is too small
+            // to fill the GPU.  The states are updated in place: the products of a diagonal all
+            // run before its gates.
+            const size_t a_stride = wl.rows_out * (size_t)batch;
+            for (int d = 0; d < T + L - 1; ++d) {
+                const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
+                for (int l0 = lo; l0 <= hi_l; l0 += kSpmmMaxJobs) {
+                    SpmmCall calls[kSpmmMaxJobs];
+                    const int n = std::min(kSpmmMaxJobs, hi_l - l0 + 1);
+                    for (int i = 0; i < n; ++i) {
+                        const int l = l0 + i, t = d - l;
+                        float *hl = hi + (size_t)l * HS * batch;
+                        if (l == 0)
+                            calls[i] = SpmmCall{r->W[l], d_x + (size_t)t * batch * I, (uint32_t)I, 1, I, hl, batch, 1,
+                                                a + (size_t)l * a_stride, batch};
+                        else
+                            calls[i] = SpmmCall{r->W[l], hi + (size_t)(l - 1) * HS * batch, (uint32_t)HS, batch, 1, hl, batch, 1,
+                                                a + (size_t)l * a_stride, batch};
+                    }
+                    int rc = spmm_strided_multi(calls, n, batch, st);
+                    if (rc != CSB_OK) return rc;
+                }
+                for (int l0 = lo; l0 <= hi_l; l0 += kSpmmMaxJobs) {
+                    GateJobs J{};
+                    const int n = std::min(kSpmmMaxJobs, hi_l - l0 + 1);
+                    for (int i = 0; i < n; ++i) {
+                        const int l = l0 + i, t = d - l;
+                        J.a[i] = a + (size_t)l * a_stride;
+                        J.bias[i] = r->d_bias[l];
+                        J.c[i] = lstm ? ci + (size_t)l * H * batch : nullptr;
+                        J.h[i] = hi + (size_t)l * HS * batch;
+                        J.hseq[i] = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * batch * HS : nullptr;
+                    }
+                    hipLaunchKernelGGL(gates_batched_kernel, dim3(gb, n), dim3(256), 0, st, J, (int)r->cell, H, batch);
+                }
+            }
+        } else
         for (int t = 0; t < T; ++t)
             for (int l = 0; l < L; ++l) {
                 float *hl = hi + (size_t)l * HS * batch;
@@ -1285,18 +1321,12 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
                     rc = spmm_strided(r->Wp[l], mb, (uint32_t)H, batch, 1, mb, batch, 1, hl, batch, batch, st);
                     if (rc != CSB_OK) return rc;
                     if (hs) hipLaunchKernelGGL(seq_out_kernel, dim3((HS * batch + 255) / 256), dim3(256), 0, st, hs, hl, HS, batch);
-                } else if (lstm)
-                    hipLaunchKernelGGL(lstm_gates_batched_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l],
-                                       ci + (size_t)l * H * batch, hl, hs, H, batch);
-                else if (ligru)
-                    hipLaunchKernelGGL(ligru_gates_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l], hl, hs, H, batch);
-                else if (gru_rb) {
+                } else {                                     // reset-before GRU
                     hipLaunchKernelGGL(gru_rb_reset_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l], hl, mb, H, batch);
                     rc = spmm_strided(r->Wp[l], mb, (uint32_t)H, batch, 1, mb, batch, 1, a2, batch, batch, st);
                     if (rc != CSB_OK) return rc;
                     hipLaunchKernelGGL(gru_rb_gates_kernel, dim3(gb), dim3(256), 0, st, a, a2, r->d_bias[l], hl, hs, H, batch);
-                } else
-                    hipLaunchKernelGGL(gru_gates_batched_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l], hl, hs, H, batch);
+                }
             }
         hipLaunchKernelGGL(state_out_kernel, dim3(sblocks), dim3(256), 0, st, d_hT, hi, L, batch, HS);
         if (lstm && d_cT) hipLaunchKernelGGL(state_out_kernel, dim3(sblocks), dim3(256), 0, st, d_cT, ci, L, batch, H);

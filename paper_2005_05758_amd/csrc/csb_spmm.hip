@@ -23,7 +23,6 @@ namespace csb {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kSpmmMetaBytes = kChunkMetaMax + 256;   // LDS window of one record segment
 
 __device__ __forceinline__ uint32_t uni_(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -61,17 +60,17 @@ struct Operands {
 // lane's four results of one row are then neighbours again and go to the accumulator as one
 // 16-byte word.  A quarter of the load and LDS instructions per multiply.
 template <int NT, bool TWO, int NW, bool WIDE>
-__global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSrc X, float *__restrict__ Y,
-                                                             const int64_t ldy, const uint32_t batch) {
+__device__ __forceinline__ void spmm_body(const DevMat &m, const XSrc &X, float *__restrict__ Y, const int64_t ldy,
+                                          const uint32_t batch, const uint32_t block_x, const uint32_t block_y) {
     extern __shared__ float4 smem4[];
     constexpr int NB = 16 * NT;                    // batch columns per workgroup
     constexpr int KS = WIDE ? 4 : 8;               // k-steps per pass
     constexpr uint32_t NTHR = NW * 64;             // NW wavefronts
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uni_(tid >> 6);
-    const uint32_t bt0 = blockIdx.y * NB;
+    const uint32_t bt0 = block_y * NB;
     const uint32_t br = m.br;
-    if (blockIdx.x >= m.n_nz_tiles) {              // a row tile without work: zeros
-        const uint32_t tile = m.zero_tiles[blockIdx.x - m.n_nz_tiles];
+    if (block_x >= m.n_nz_tiles) {                 // a row tile without work: zeros
+        const uint32_t tile = m.zero_tiles[block_x - m.n_nz_tiles];
         for (uint32_t e = tid; e < br * NB; e += NTHR) {
             const uint32_t row = tile * br + e / NB, n = bt0 + e % NB;
             if (row < m.rows_out && n < batch) Y[(size_t)row * ldy + n] = 0.0f;
@@ -79,10 +78,10 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
         return;
     }
     uint8_t *meta = (uint8_t *)smem4;                              // one record segment
-    float *acc = (float *)(meta + kSpmmMetaBytes);                 // [waves][br][NB]
+    float *acc = (float *)(meta + m.seg_meta);                     // [waves][br][NB]
     float *myacc = acc + (size_t)wave * br * NB;
     for (uint32_t e = lane; e < br * NB; e += 64) myacc[e] = 0.0f;
-    const uint32_t rank = blockIdx.x, tile = m.nz_tiles[rank];
+    const uint32_t rank = block_x, tile = m.nz_tiles[rank];
     const uint32_t vf = uni_(m.val_fmt);                           // storage format of the value stream
     const uint32_t mrow = lane & 15u, kq = lane >> 4;              // A: row, column-in-4; B: column n, row-in-4
     static_assert(!WIDE || NT == 4, "the wide form feeds four tiles from one load");
@@ -278,58 +277,146 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
     }
 }
 
-int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj0, int64_t sn0, const float *p1,
-                 int64_t sj1, int64_t sn1, float *d_Y, int64_t ldy, int32_t batch, void *stream) {
+template <int NT, bool TWO, int NW, bool WIDE>
+__global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSrc X, float *__restrict__ Y,
+                                                             const int64_t ldy, const uint32_t batch) {
+    spmm_body<NT, TWO, NW, WIDE>(m, X, Y, ldy, batch, blockIdx.x, blockIdx.y);
+}
+
+// Several independent products in one launch (blockIdx.z picks the product): the per-step
+// products of different layers of a batched recurrent model, each too small to fill the GPU.
+struct SpmmJobs {
+    DevMat m[kSpmmMaxJobs];
+    XSrc X[kSpmmMaxJobs];
+    float *Y[kSpmmMaxJobs];
+    int64_t ldy[kSpmmMaxJobs];
+};
+template <int NT, bool TWO, int NW, bool WIDE>
+__global__ __launch_bounds__(NW * 64) void spmm_multi_kernel(const SpmmJobs J, const uint32_t batch) {
+    const uint32_t j = blockIdx.z;
+    if (blockIdx.x >= J.m[j].n_nz_tiles + J.m[j].n_zero_tiles) return;      // the grid is as wide as the widest product
+    spmm_body<NT, TWO, NW, WIDE>(J.m[j], J.X[j], J.Y[j], J.ldy[j], batch, blockIdx.x, blockIdx.y);
+}
+
+// Launch shape of one product: batch columns per workgroup (16 nt), wavefronts per workgroup.
+struct SpmmShape {
+    int nt, nw;
+    bool two, wide;
+    size_t lds;
+    unsigned tiles, batch_tiles;
+};
+
+// Checks one product's operands and chooses its launch shape; `launch_wgs_factor` products of
+// this size share the launch, which counts when the launch is sized against the GPU's 256 CUs.
+static int spmm_shape(const SpmmCall &c, int32_t batch, size_t launch_wgs_factor, SpmmShape *out, XSrc *X) {
+    const csb_matrix *mat = c.mat;
     if (!mat->plan.valid || !mat->uploaded || !mat->d_buf) { set_error("csb_spmm: matrix not planned and uploaded"); return CSB_ESTATE; }
     const DevHeader &h = mat->plan.hdr;
-    const DevMat dm = dev_mat(mat);
     // 32-bit element offsets, 24-bit multiplies
-    const int64_t smax_j = std::max(sj0, sj1), smax_n = std::max(sn0, sn1);
-    if (sj0 < 0 || sj1 < 0 || sn0 < 0 || sn1 < 0 || smax_j >= (1 << 24) || (int64_t)h.cols >= (1 << 24) ||
+    const int64_t smax_j = std::max(c.sj0, c.sj1), smax_n = std::max(c.sn0, c.sn1);
+    if (c.sj0 < 0 || c.sj1 < 0 || c.sn0 < 0 || c.sn1 < 0 || smax_j >= (1 << 24) || (int64_t)h.cols >= (1 << 24) ||
         (int64_t)h.cols * smax_j + (int64_t)batch * smax_n >= (1ll << 30)) {
         set_error("csb_spmm: strides or sizes beyond the kernel's 32-bit element offsets");
         return CSB_EUNSUPPORTED;
     }
-    XSrc X{p0, n0, (uint32_t)sj0, (uint32_t)sn0, p1, (uint32_t)sj1, (uint32_t)sn1};
-    const bool two = n0 < (uint32_t)h.cols;
+    *X = XSrc{c.p0, c.n0, (uint32_t)c.sj0, (uint32_t)c.sn0, c.p1, (uint32_t)c.sj1, (uint32_t)c.sn1};
+    const bool two = c.n0 < (uint32_t)h.cols;
     // the wide form: right-hand sides contiguous, rows of the input 16-byte aligned, batch in
     // fours, and eight wavefronts' accumulator tiles of 64 columns fit LDS
-    const bool aligned = ((uintptr_t)p0 % 16 == 0) && sj0 % 4 == 0 && sn0 == 1 &&
-                         (!two || (((uintptr_t)p1 % 16 == 0) && sj1 % 4 == 0 && sn1 == 1));
+    const bool aligned = ((uintptr_t)c.p0 % 16 == 0) && c.sj0 % 4 == 0 && c.sn0 == 1 &&
+                         (!two || (((uintptr_t)c.p1 % 16 == 0) && c.sj1 % 4 == 0 && c.sn1 == 1));
     const bool wide_ok = aligned && batch % 4 == 0 &&
-                         (size_t)kSpmmMetaBytes + 8 * (size_t)h.br * 64 * sizeof(float) <= (size_t)kLdsBudget;
-    // batch columns per workgroup: the widest form that still gives every CU (256) a workgroup
+                         (size_t)h.seg_meta + 8 * (size_t)h.br * 64 * sizeof(float) <= (size_t)kLdsBudget;
+    // batch columns per workgroup: the widest form whose launch still gives every CU (256) a workgroup
     const size_t tiles = (size_t)h.n_nz_tiles + h.n_zero_tiles;
     auto wgs = [&](int n) { return tiles * (size_t)((batch + 16 * n - 1) / (16 * n)); };
     int nt = 1;
-    if (h.br <= 128 && batch > 16 && wgs(2) >= 256) nt = 2;
-    if (wide_ok && batch >= 48 && wgs(4) >= 256) nt = 4;
+    if (h.br <= 128 && batch > 16 && wgs(2) * launch_wgs_factor >= 256) nt = 2;
+    if (wide_ok && batch >= 48 && wgs(4) * launch_wgs_factor >= 256) nt = 4;
     const bool wide = nt == 4;
-    const dim3 grid(h.n_nz_tiles + h.n_zero_tiles, (unsigned)((batch + 16 * nt - 1) / (16 * nt)));
-    // 16 wavefronts share a tile's blocks when their accumulator tiles fit LDS and the grid
+    // 16 wavefronts share a tile's blocks when their accumulator tiles fit LDS and the launch
     // alone would not give every CU of an MI355X (256) two workgroups; else 8
     const size_t acc_per_wave = (size_t)h.br * 16 * nt * sizeof(float);
-    const bool fits16 = (size_t)kSpmmMetaBytes + 16 * acc_per_wave <= (size_t)kLdsBudget;
-    const int nw = fits16 && (wide || (size_t)grid.x * grid.y < 2 * 256) ? 16 : 8;
-    const size_t lds = (size_t)kSpmmMetaBytes + (size_t)nw * acc_per_wave;
-    auto go = [&](auto kern) -> hipError_t {
-        hipError_t e = ensure_dynamic_lds((const void *)kern, lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, dim3(nw * 64), lds, (hipStream_t)stream, dm, X, d_Y, ldy, (uint32_t)batch);
-        return hipGetLastError();
-    };
-    hipError_t e;
-    if (wide) {
-        if (nw == 16) e = two ? go(spmm_kernel<4, true, 16, true>) : go(spmm_kernel<4, false, 16, true>);
-        else e = two ? go(spmm_kernel<4, true, 8, true>) : go(spmm_kernel<4, false, 8, true>);
-    } else if (nw == 16) {
-        if (nt == 2) e = two ? go(spmm_kernel<2, true, 16, false>) : go(spmm_kernel<2, false, 16, false>);
-        else e = two ? go(spmm_kernel<1, true, 16, false>) : go(spmm_kernel<1, false, 16, false>);
-    } else {
-        if (nt == 2) e = two ? go(spmm_kernel<2, true, 8, false>) : go(spmm_kernel<2, false, 8, false>);
-        else e = two ? go(spmm_kernel<1, true, 8, false>) : go(spmm_kernel<1, false, 8, false>);
+    const bool fits16 = (size_t)h.seg_meta + 16 * acc_per_wave <= (size_t)kLdsBudget;
+    const int nw = fits16 && (wide || wgs(nt) * launch_wgs_factor < 2 * 256) ? 16 : 8;
+    *out = SpmmShape{nt, nw, two, wide, (size_t)h.seg_meta + (size_t)nw * acc_per_wave, (unsigned)tiles,
+                     (unsigned)((batch + 16 * nt - 1) / (16 * nt))};
+    return CSB_OK;
+}
+
+// The kernel instantiation for a launch shape (one product per launch, or several).
+template <bool MULTI>
+static const void *spmm_kernel_for(const SpmmShape &sh) {
+#define CSB_SPMM_K(NT, TWO, NW, WIDE) \
+    (MULTI ? (const void *)spmm_multi_kernel<NT, TWO, NW, WIDE> : (const void *)spmm_kernel<NT, TWO, NW, WIDE>)
+    if (sh.wide) {
+        if (sh.nw == 16) return sh.two ? CSB_SPMM_K(4, true, 16, true) : CSB_SPMM_K(4, false, 16, true);
+        return sh.two ? CSB_SPMM_K(4, true, 8, true) : CSB_SPMM_K(4, false, 8, true);
     }
+    if (sh.nw == 16) {
+        if (sh.nt == 2) return sh.two ? CSB_SPMM_K(2, true, 16, false) : CSB_SPMM_K(2, false, 16, false);
+        return sh.two ? CSB_SPMM_K(1, true, 16, false) : CSB_SPMM_K(1, false, 16, false);
+    }
+    if (sh.nt == 2) return sh.two ? CSB_SPMM_K(2, true, 8, false) : CSB_SPMM_K(2, false, 8, false);
+    return sh.two ? CSB_SPMM_K(1, true, 8, false) : CSB_SPMM_K(1, false, 8, false);
+#undef CSB_SPMM_K
+}
+
+int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj0, int64_t sn0, const float *p1,
+                 int64_t sj1, int64_t sn1, float *d_Y, int64_t ldy, int32_t batch, void *stream) {
+    const SpmmCall c{mat, p0, n0, sj0, sn0, p1, sj1, sn1, d_Y, ldy};
+    SpmmShape sh;
+    XSrc X;
+    int rc = spmm_shape(c, batch, 1, &sh, &X);
+    if (rc != CSB_OK) return rc;
+    DevMat dm = dev_mat(mat);
+    uint32_t b = (uint32_t)batch;
+    int64_t ld = ldy;
+    void *args[] = {&dm, &X, &d_Y, &ld, &b};
+    const void *kern = spmm_kernel_for<false>(sh);
+    hipError_t e = ensure_dynamic_lds(kern, sh.lds);
+    if (e == hipSuccess)
+        e = hipLaunchKernel(kern, dim3(sh.tiles, sh.batch_tiles), dim3(sh.nw * 64), args, sh.lds, (hipStream_t)stream);
     if (e != hipSuccess) { set_error(std::string("csb_spmm: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    return CSB_OK;
+}
+
+// Up to kSpmmMaxJobs independent products in ONE launch when they agree on the launch shape
+// (same-shaped layers do); otherwise one launch each.
+int spmm_strided_multi(const SpmmCall *calls, int n, int32_t batch, void *stream) {
+    if (n <= 0) return CSB_OK;
+    SpmmShape sh[kSpmmMaxJobs];
+    SpmmJobs J{};
+    bool same = n <= kSpmmMaxJobs && n > 1;
+    if (same) {
+        size_t lds = 0;
+        unsigned tiles = 0;
+        for (int i = 0; i < n; ++i) {
+            int rc = spmm_shape(calls[i], batch, (size_t)n, &sh[i], &J.X[i]);
+            if (rc != CSB_OK) return rc;
+            same = same && sh[i].nt == sh[0].nt && sh[i].nw == sh[0].nw && sh[i].two == sh[0].two && sh[i].wide == sh[0].wide;
+            lds = std::max(lds, sh[i].lds);
+            tiles = std::max(tiles, sh[i].tiles);
+            J.m[i] = dev_mat(calls[i].mat);
+            J.Y[i] = calls[i].Y;
+            J.ldy[i] = calls[i].ldy;
+        }
+        if (same) {
+            uint32_t b = (uint32_t)batch;
+            void *args[] = {&J, &b};
+            const void *kern = spmm_kernel_for<true>(sh[0]);
+            hipError_t e = ensure_dynamic_lds(kern, lds);
+            if (e == hipSuccess)
+                e = hipLaunchKernel(kern, dim3(tiles, sh[0].batch_tiles, (unsigned)n), dim3(sh[0].nw * 64), args, lds, (hipStream_t)stream);
+            if (e != hipSuccess) { set_error(std::string("csb_spmm: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+            return CSB_OK;
+        }
+    }
+    for (int i = 0; i < n; ++i) {
+        const SpmmCall &c = calls[i];
+        int rc = spmm_strided(c.mat, c.p0, c.n0, c.sj0, c.sn0, c.p1, c.sj1, c.sn1, c.Y, c.ldy, batch, stream);
+        if (rc != CSB_OK) return rc;
+    }
     return CSB_OK;
 }
 

@@ -42,6 +42,8 @@ DevMat dev_mat(const csb_matrix *m) {
     d.n_nz_tiles = h.n_nz_tiles;
     d.idx_bytes = (uint32_t)h.idx_bytes;
     d.val_fmt = h.val_fmt;
+    d.seg_meta = h.seg_meta;
+    d.pad_ = 0;
     d.tile_g0 = (const uint32_t *)(b + h.off_tile_g0);
     d.tile_seg0 = (const uint32_t *)(b + h.off_tile_seg0);
     d.segs = (const SegRec *)(b + h.off_segs);
