@@ -35,9 +35,9 @@ MFMA_F32_PEAK_TFLOPS = 157.3
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very command, scaled by
 # the readings of a plain 256 MiB copy (profiles/bench_hbm_traffic_pmc.txt has the commands and raw readings)
 TRAFFIC_BYTES = {
-    "rnn_resident_cfg2": {"read": int(921.4375 * 2.0 * 1024), "written": int(633.6875 * 1024)},
-    "spmv_cfg5": {"read": int(14450.625 * 2.0 * 1024), "written": 32768},
-    "spmm_cfg5_b128": {"read": int(44973.1875 * 2.0 * 1024), "written": 4194304},
+    "rnn_resident_cfg2": {"read": int(914.125 * 2.0 * 1024), "written": int(633.6875 * 1024)},
+    "spmv_cfg5": {"read": int(14446.625 * 2.0 * 1024), "written": 32768},
+    "spmm_cfg5_b128": {"read": int(44941.8125 * 2.0 * 1024), "written": 4194304},
 }
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
