@@ -813,10 +813,17 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
 struct GateJobs {
     const float *a[kSpmmMaxJobs];
     const float *bias[kSpmmMaxJobs];
-    float *c[kSpmmMaxJobs];       // LSTM only
+    const float *a2[kSpmmMaxJobs];   // reset-before GRU, gate part: the second product's sums
+    float *c[kSpmmMaxJobs];       // LSTM, LSTMP
     float *h[kSpmmMaxJobs];
+    float *m[kSpmmMaxJobs];       // LSTMP: cell output m_t; reset-before GRU, reset part: q = r h
     float *hseq[kSpmmMaxJobs];    // [B][H] of this step, or null
 };
+// what gates_batched_kernel computes: a cell (CSB_CELL_LSTM / _GRU / _LIGRU) or one of the
+// element-wise parts of the cells with two products per step
+constexpr int kEwLstmpCell = 100;   // c_t, m_t = o tanh(c_t) (the projection product follows)
+constexpr int kEwRbReset = 101;     // q = sigmoid(a_r) h (the candidate's recurrent product follows)
+constexpr int kEwRbGate = 102;      // h_t from the z and n rows of a, and a2
 __global__ void gates_batched_kernel(const GateJobs J, const int cell, const int H, const int B) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= H * B) return;
@@ -825,7 +832,18 @@ __global__ void gates_batched_kernel(const GateJobs J, const int cell, const int
     float *__restrict__ h = J.h[j];
     const int k = e / B, n = e - k * B;
     float hn;
-    if (cell == CSB_CELL_LSTM) {                       // rows i, f, g, o
+    if (cell == kEwRbReset) {
+        float ar = a[(size_t)k * B + n];
+        if (bias) ar += bias[k];
+        J.m[j][e] = sigmoidf_(ar) * h[e];
+        return;
+    }
+    if (cell == kEwRbGate) {
+        float az = a[(size_t)(H + k) * B + n], an = a[(size_t)(2 * H + k) * B + n] + J.a2[j][e];
+        if (bias) { az += bias[H + k]; an += bias[2 * H + k]; }
+        const float z = sigmoidf_(az);
+        hn = (1.0f - z) * tanhf(an) + z * h[e];
+    } else if (cell == CSB_CELL_LSTM || cell == kEwLstmpCell) {   // rows i, f, g, o
         float *__restrict__ c = J.c[j];
         float ai = a[(size_t)k * B + n], af = a[(size_t)(H + k) * B + n], ag = a[(size_t)(2 * H + k) * B + n],
               ao = a[(size_t)(3 * H + k) * B + n];
@@ -833,6 +851,7 @@ __global__ void gates_batched_kernel(const GateJobs J, const int cell, const int
         const float cn = sigmoidf_(af) * c[e] + sigmoidf_(ai) * tanhf(ag);
         hn = sigmoidf_(ao) * tanhf(cn);
         c[e] = cn;
+        if (cell == kEwLstmpCell) { J.m[j][e] = hn; return; }      // m_t; the state is the projection's result
     } else if (cell == CSB_CELL_GRU) {                 // rows r, z, input side of n, recurrent side of n
         float ar = a[(size_t)k * B + n], az = a[(size_t)(H + k) * B + n], anx = a[(size_t)(2 * H + k) * B + n];
         const float anh = a[(size_t)(3 * H + k) * B + n];
@@ -847,48 +866,6 @@ __global__ void gates_batched_kernel(const GateJobs J, const int cell, const int
     }
     h[e] = hn;
     if (J.hseq[j]) J.hseq[j][(size_t)n * H + k] = hn;
-}
-
-// LSTMP, batched: the cell output m_t = o tanh(c_t) goes to a buffer of its own ([H][B]); the
-// projection r_t = Wp m_t (a CSB product) follows.
-__global__ void lstmp_gates_batched_kernel(const float *__restrict__ a, const float *__restrict__ bias,
-                                           float *__restrict__ c, float *__restrict__ m, const int H, const int B) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= H * B) return;
-    const int k = e / B, n = e - k * B;
-    float ai = a[(size_t)k * B + n], af = a[(size_t)(H + k) * B + n], ag = a[(size_t)(2 * H + k) * B + n],
-          ao = a[(size_t)(3 * H + k) * B + n];
-    if (bias) { ai += bias[k]; af += bias[H + k]; ag += bias[2 * H + k]; ao += bias[3 * H + k]; }
-    const float cn = sigmoidf_(af) * c[e] + sigmoidf_(ai) * tanhf(ag);
-    c[e] = cn;
-    m[e] = sigmoidf_(ao) * tanhf(cn);
-}
-
-// GRU with the reset gate before the candidate's recurrent product, first element-wise part:
-// q = sig(a_r) * h, the operand of that product (a is [3H][B], rows r, z, n).
-__global__ void gru_rb_reset_kernel(const float *__restrict__ a, const float *__restrict__ bias,
-                                    const float *__restrict__ h, float *__restrict__ q, const int H, const int B) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= H * B) return;
-    const int k = e / B, n = e - k * B;
-    float ar = a[(size_t)k * B + n];
-    if (bias) ar += bias[k];
-    q[e] = sigmoidf_(ar) * h[e];
-}
-
-// ... second part: a2 = Un q is [H][B]; n = tanh(a_n + b_n + a2), h = (1 - z) n + z h.
-__global__ void gru_rb_gates_kernel(const float *__restrict__ a, const float *__restrict__ a2,
-                                    const float *__restrict__ bias, float *__restrict__ h,
-                                    float *__restrict__ hseq, const int H, const int B) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= H * B) return;
-    const int k = e / B, n = e - k * B;
-    float az = a[(size_t)(H + k) * B + n], an = a[(size_t)(2 * H + k) * B + n] + a2[e];
-    if (bias) { az += bias[H + k]; an += bias[2 * H + k]; }
-    const float z = sigmoidf_(az);
-    const float hn = (1.0f - z) * tanhf(an) + z * h[e];
-    h[e] = hn;
-    if (hseq) hseq[(size_t)n * H + k] = hn;
 }
 
 // hseq[b][k] = h[k][b] for one step ([W][B] internal -> [B][W] caller's layout)
@@ -954,7 +931,8 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     // (batched: one buffer of gate sums per layer -- the products of different layers share launches)
     w.off_a = off; off = align256(off + rows_out * sizeof(float) * (size_t)batch * (batch > 1 ? (size_t)r->n_layers : 1));
     const bool two_products = r->cell == CSB_CELL_GRU_RB;          // second product's output, its operand
-    w.off_a2 = off; off = align256(off + (two_products ? (size_t)batch * r->hidden * sizeof(float) : 0));
+    const size_t per_layer = batch > 1 ? (size_t)r->n_layers : 1;
+    w.off_a2 = off; off = align256(off + (two_products ? (size_t)batch * r->hidden * sizeof(float) * per_layer : 0));
     w.off_c = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     w.off_part = off; off = align256(off + part);
     w.off_biasptr = off; off = align256(off + (size_t)r->n_layers * sizeof(void *));
@@ -965,7 +943,7 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
         w.off_hint = off; off = align256(off + (size_t)r->n_layers * batch * HS * sizeof(float));
         w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
     }
-    w.off_m = off; off = align256(off + ((r->proj > 0 || two_products) ? (size_t)batch * r->hidden * sizeof(float) : 0));
+    w.off_m = off; off = align256(off + ((r->proj > 0 || two_products) ? (size_t)batch * r->hidden * sizeof(float) * per_layer : 0));
     // streaming at batch 1: per layer two buffers of gate sums (plus the second product's sums of
     // the reset-before GRU) and two of (c, h), used alternately by even and odd steps
     const bool fused = batch == 1;
@@ -1264,70 +1242,80 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, hi, d_h0, L, batch, HS);
         if (lstm) hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, ci, d_c0, L, batch, H);
         const int gb = (H * batch + 255) / 256;
-        if (!lstmp && !gru_rb) {
-            // One product per layer and step.  Layer l at step t needs layer l - 1 at step t and
-            // itself at step t - 1: everything on the diagonal l + t = d is independent, so a
-            // diagonal takes ONE product launch and ONE gate launch (for up to kSpmmMaxJobs
-            // layers each) instead of one pair per layer -- a single layer's product is too small
-            // to fill the GPU.  The states are updated in place: the products of a diagonal all
-            // run before its gates.
-            const size_t a_stride = wl.rows_out * (size_t)batch;
-            for (int d = 0; d < T + L - 1; ++d) {
-                const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
+        // Layer l at step t needs layer l - 1 at step t and itself at step t - 1: everything on
+        // the diagonal l + t = d is independent, so a diagonal takes ONE product launch and ONE
+        // element-wise launch per phase (for up to kSpmmMaxJobs layers each) instead of one per
+        // layer -- a single layer's product is too small to fill the GPU.  The states are updated
+        // in place: within a diagonal every phase of all layers runs before the next phase.
+        // LSTM / GRU / Li-GRU have one phase (product, gates); LSTMP has two (gate product, cell;
+        // projection product into the state), the reset-before GRU too (first product, reset;
+        // second product, gates).
+        const size_t a_stride = wl.rows_out * (size_t)batch, hb = (size_t)H * batch;
+        const bool two_phase = lstmp || gru_rb;
+        for (int d = 0; d < T + L - 1; ++d) {
+            const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
+            auto for_groups = [&](auto body) -> int {           // body(first layer, layers in the group)
                 for (int l0 = lo; l0 <= hi_l; l0 += kSpmmMaxJobs) {
-                    SpmmCall calls[kSpmmMaxJobs];
-                    const int n = std::min(kSpmmMaxJobs, hi_l - l0 + 1);
-                    for (int i = 0; i < n; ++i) {
-                        const int l = l0 + i, t = d - l;
-                        float *hl = hi + (size_t)l * HS * batch;
-                        if (l == 0)
-                            calls[i] = SpmmCall{r->W[l], d_x + (size_t)t * batch * I, (uint32_t)I, 1, I, hl, batch, 1,
-                                                a + (size_t)l * a_stride, batch};
-                        else
-                            calls[i] = SpmmCall{r->W[l], hi + (size_t)(l - 1) * HS * batch, (uint32_t)HS, batch, 1, hl, batch, 1,
-                                                a + (size_t)l * a_stride, batch};
-                    }
-                    int rc = spmm_strided_multi(calls, n, batch, st);
+                    int rc = body(l0, std::min(kSpmmMaxJobs, hi_l - l0 + 1));
                     if (rc != CSB_OK) return rc;
                 }
-                for (int l0 = lo; l0 <= hi_l; l0 += kSpmmMaxJobs) {
+                return CSB_OK;
+            };
+            auto ew = [&](int mode) {                            // one element-wise launch per group
+                return for_groups([&](int l0, int n) {
                     GateJobs J{};
-                    const int n = std::min(kSpmmMaxJobs, hi_l - l0 + 1);
                     for (int i = 0; i < n; ++i) {
                         const int l = l0 + i, t = d - l;
                         J.a[i] = a + (size_t)l * a_stride;
+                        J.a2[i] = a2 + (size_t)l * hb;
                         J.bias[i] = r->d_bias[l];
-                        J.c[i] = lstm ? ci + (size_t)l * H * batch : nullptr;
+                        J.c[i] = lstm ? ci + (size_t)l * hb : nullptr;
                         J.h[i] = hi + (size_t)l * HS * batch;
+                        J.m[i] = mb + (size_t)l * hb;
                         J.hseq[i] = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * batch * HS : nullptr;
                     }
-                    hipLaunchKernelGGL(gates_batched_kernel, dim3(gb, n), dim3(256), 0, st, J, (int)r->cell, H, batch);
+                    hipLaunchKernelGGL(gates_batched_kernel, dim3(gb, n), dim3(256), 0, st, J, mode, H, batch);
+                    return (int)CSB_OK;
+                });
+            };
+            // first (or only) product: W_l [input ; state]
+            int rc = for_groups([&](int l0, int n) {
+                SpmmCall calls[kSpmmMaxJobs];
+                for (int i = 0; i < n; ++i) {
+                    const int l = l0 + i, t = d - l;
+                    float *hl = hi + (size_t)l * HS * batch;
+                    if (l == 0)
+                        calls[i] = SpmmCall{r->W[l], d_x + (size_t)t * batch * I, (uint32_t)I, 1, I, hl, batch, 1,
+                                            a + (size_t)l * a_stride, batch};
+                    else
+                        calls[i] = SpmmCall{r->W[l], hi + (size_t)(l - 1) * HS * batch, (uint32_t)HS, batch, 1, hl, batch, 1,
+                                            a + (size_t)l * a_stride, batch};
                 }
+                return spmm_strided_multi(calls, n, batch, st);
+            });
+            if (rc != CSB_OK) return rc;
+            if (!two_phase) {
+                ew((int)r->cell);
+                continue;
             }
-        } else
-        for (int t = 0; t < T; ++t)
-            for (int l = 0; l < L; ++l) {
-                float *hl = hi + (size_t)l * HS * batch;
-                int rc;
-                if (l == 0)
-                    rc = spmm_strided(r->W[l], d_x + (size_t)t * batch * I, (uint32_t)I, 1, I, hl, batch, 1, a, batch, batch, st);
-                else
-                    rc = spmm_strided(r->W[l], hi + (size_t)(l - 1) * HS * batch, (uint32_t)HS, batch, 1, hl, batch, 1, a, batch, batch, st);
-                if (rc != CSB_OK) return rc;
-                float *hs = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * batch * HS : nullptr;
-                if (lstmp) {
-                    hipLaunchKernelGGL(lstmp_gates_batched_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l],
-                                       ci + (size_t)l * H * batch, mb, H, batch);
-                    rc = spmm_strided(r->Wp[l], mb, (uint32_t)H, batch, 1, mb, batch, 1, hl, batch, batch, st);
-                    if (rc != CSB_OK) return rc;
-                    if (hs) hipLaunchKernelGGL(seq_out_kernel, dim3((HS * batch + 255) / 256), dim3(256), 0, st, hs, hl, HS, batch);
-                } else {                                     // reset-before GRU
-                    hipLaunchKernelGGL(gru_rb_reset_kernel, dim3(gb), dim3(256), 0, st, a, r->d_bias[l], hl, mb, H, batch);
-                    rc = spmm_strided(r->Wp[l], mb, (uint32_t)H, batch, 1, mb, batch, 1, a2, batch, batch, st);
-                    if (rc != CSB_OK) return rc;
-                    hipLaunchKernelGGL(gru_rb_gates_kernel, dim3(gb), dim3(256), 0, st, a, a2, r->d_bias[l], hl, hs, H, batch);
+            ew(lstmp ? kEwLstmpCell : kEwRbReset);               // m_t, or q = r h_(t-1)
+            // second product: the projection r_t = Wp m_t straight into the state, or Un q
+            rc = for_groups([&](int l0, int n) {
+                SpmmCall calls[kSpmmMaxJobs];
+                for (int i = 0; i < n; ++i) {
+                    const int l = l0 + i;
+                    float *ml = mb + (size_t)l * hb;
+                    float *dst = lstmp ? hi + (size_t)l * HS * batch : a2 + (size_t)l * hb;
+                    calls[i] = SpmmCall{r->Wp[l], ml, (uint32_t)H, batch, 1, ml, batch, 1, dst, batch};
                 }
-            }
+                return spmm_strided_multi(calls, n, batch, st);
+            });
+            if (rc != CSB_OK) return rc;
+            if (gru_rb) ew(kEwRbGate);
+            else if (d_hseq && d >= L - 1 && d - (L - 1) < T)    // the last layer is on this diagonal
+                hipLaunchKernelGGL(seq_out_kernel, dim3((HS * batch + 255) / 256), dim3(256), 0, st,
+                                   d_hseq + (size_t)(d - (L - 1)) * batch * HS, hi + (size_t)(L - 1) * HS * batch, HS, batch);
+        }
         hipLaunchKernelGGL(state_out_kernel, dim3(sblocks), dim3(256), 0, st, d_hT, hi, L, batch, HS);
         if (lstm && d_cT) hipLaunchKernelGGL(state_out_kernel, dim3(sblocks), dim3(256), 0, st, d_cT, ci, L, batch, H);
         hipError_t eb = hipGetLastError();
