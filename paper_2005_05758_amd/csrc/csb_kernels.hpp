@@ -7,6 +7,8 @@
 
 namespace csb {
 
+constexpr int kSpmmMaxJobs = 4;   // independent products that may share one launch
+
 // A segment of the mat-vec's input that is not in memory yet: the output h_t of a recurrent
 // cell whose gate sums `a` an earlier launch on the same stream has produced.  The mat-vec
 // kernel applies the cell's element-wise part (Sec. 2.1) while it stages its input, so a
@@ -39,6 +41,18 @@ int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const flo
 int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *d_ws, void *stream);
 // The element-wise part alone, one thread per unit: stores c_t, h_t (and hseq) of `s`.
 int commit_gates(const GateSrc &s, void *stream);
+// One product of spmv_gated_multi (the arguments of spmv_gated).
+struct SpmvGatedCall {
+    const csb_matrix *mat;
+    GateSrc s0;
+    uint32_t n0;
+    GateSrc s1;
+    float *y;
+    void *ws;
+};
+// Several independent gated mat-vecs on `stream`: one launch when there are two to four of one
+// value format (the layers of a stacked model on one diagonal), else a launch each.
+int spmv_gated_multi(const SpmvGatedCall *calls, int n, void *stream);
 
 // Y = A Z for `batch` right-hand sides.  Element (column j, right-hand side n) of Z is
 // p0[j*sj0 + n*sn0] for j < n0 and p1[(j-n0)*sj1 + n*sn1] otherwise; Y is [rows_out][ldy].
@@ -61,7 +75,6 @@ struct SpmmCall {
     float *Y;
     int64_t ldy;
 };
-constexpr int kSpmmMaxJobs = 4;
 // Several independent products of the same batch on `stream`: one launch when their launch
 // shapes agree (the layers of a stacked model), else one launch each.
 int spmm_strided_multi(const SpmmCall *calls, int n, int32_t batch, void *stream);

@@ -913,7 +913,7 @@ static void init_state(float *dst, const float *src, size_t n, hipStream_t st) {
 static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 struct RnnWs {
-    size_t off_a, off_a2, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, off_m, off_fa, off_fs, rows_out, total;
+    size_t off_a, off_a2, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, off_m, off_fa, off_fs, rows_out, part_stride, total;
 };
 
 static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
@@ -934,7 +934,10 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     const size_t per_layer = batch > 1 ? (size_t)r->n_layers : 1;
     w.off_a2 = off; off = align256(off + (two_products ? (size_t)batch * r->hidden * sizeof(float) * per_layer : 0));
     w.off_c = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
-    w.off_part = off; off = align256(off + part);
+    // (batch 1: the mat-vecs of different layers share launches, so each layer's two matrices
+    // have a region of merge words of their own)
+    w.part_stride = align256(part);
+    w.off_part = off; off = align256(off + w.part_stride * (batch == 1 ? 2 * (size_t)r->n_layers : 1));
     w.off_biasptr = off; off = align256(off + (size_t)r->n_layers * sizeof(void *));
     // exchange words of the resident kernel: one per unit of every stage and step
     const size_t seq_units = r->plan.valid ? r->plan.total_units : 0;
@@ -1322,49 +1325,16 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         if (eb != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(eb)); return CSB_EDEVICE; }
         return CSB_OK;
     }
-    void *part = (uint8_t *)d_ws + wl.off_part;
-    if (r->cell == CSB_CELL_LSTM || r->cell == CSB_CELL_GRU || r->cell == CSB_CELL_LIGRU) {
-        // One launch per step and layer: the element-wise part of a cell (Sec. 2.1) runs inside
-        // the mat-vec launches that consume its output h_(l,t) -- layer l + 1 at step t and layer
-        // l at step t + 1 -- while they stage their input (see GateSrc).  Gate sums and states of
-        // step t live in buffer t & 1 of their layer (the initial state in buffer 1), so a launch
-        // never writes what another workgroup of the same launch still reads.
-        float *fa = (float *)((uint8_t *)d_ws + wl.off_fa), *fs = (float *)((uint8_t *)d_ws + wl.off_fs);
-        auto sums = [&](int l, int t) { return fa + ((size_t)l * 2 + (size_t)(t & 1)) * wl.rows_out; };
-        auto c_of = [&](int l, int t) { return fs + (((size_t)l * 2 + (size_t)(t & 1)) * 2) * H; };
-        auto h_of = [&](int l, int t) { return c_of(l, t) + H; };
-        for (int l = 0; l < L; ++l) {
-            init_state(h_of(l, -1), d_h0 ? d_h0 + (size_t)l * H : nullptr, (size_t)H, st);
-            if (lstm) init_state(c_of(l, -1), d_c0 ? d_c0 + (size_t)l * H : nullptr, (size_t)H, st);
-        }
-        auto cell_output = [&](int l, int t) {                   // h_(l,t), still to be computed from the sums of step t
-            GateSrc g{};
-            g.a = sums(l, t); g.bias = r->d_bias[l];
-            g.c_in = lstm ? c_of(l, t - 1) : nullptr; g.h_in = h_of(l, t - 1);
-            g.c_out = lstm ? c_of(l, t) : nullptr; g.h_out = h_of(l, t);
-            g.hseq = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * H : nullptr;
-            g.kind = 1u + (uint32_t)r->cell; g.H = (uint32_t)H;
-            return g;
-        };
-        for (int t = 0; t < T; ++t)
-            for (int l = 0; l < L; ++l) {
-                const GateSrc below = l == 0 ? plain_src(d_x + (size_t)t * I) : cell_output(l - 1, t);
-                const GateSrc back = t == 0 ? plain_src(h_of(l, -1)) : cell_output(l, t - 1);
-                int rc = spmv_gated(r->W[l], below, l == 0 ? (uint32_t)I : (uint32_t)H, back, sums(l, t), part, st);
-                if (rc != CSB_OK) return rc;
-            }
-        // the last step's cells have no consumer: apply them here, into the caller's state arrays
-        for (int l = 0; l < L; ++l) {
-            GateSrc g = cell_output(l, T - 1);
-            g.h_out = d_hT + (size_t)l * H;
-            g.c_out = (lstm && d_cT) ? d_cT + (size_t)l * H : nullptr;
-            int rc = commit_gates(g, st);
-            if (rc != CSB_OK) return rc;
-        }
-        return CSB_OK;
-    }
-    // LSTMP and the reset-before GRU: two products per step and layer, the element-wise parts
-    // again inside the launches that consume them (two launches per step and layer).
+    // ---- streaming path, batch 1 -------------------------------------------------------------
+    // The element-wise part of a cell (Sec. 2.1) is no launch of its own: the mat-vec launches
+    // that consume a cell's output -- layer l + 1 at step t, layer l at step t + 1 -- compute it
+    // from the gate sums while they stage their input (see GateSrc).  Sums and states of step t
+    // live in buffer t & 1 of their layer (the initial state in buffer 1), so a launch never
+    // writes what another workgroup of the same launch still reads.  And the steps run by
+    // DIAGONALS: layer l at step t needs layer l - 1 at step t and itself at step t - 1, so
+    // the pairs with l + t = d are independent and share one launch per product phase.
+    uint8_t *part0 = (uint8_t *)d_ws + wl.off_part;
+    auto part_of = [&](int l, int which) { return (void *)(part0 + ((size_t)l * 2 + (size_t)which) * wl.part_stride); };
     float *fa = (float *)((uint8_t *)d_ws + wl.off_fa), *fs = (float *)((uint8_t *)d_ws + wl.off_fs);
     const size_t SW = (size_t)std::max(H, HS);                   // room of one state vector
     auto sums = [&](int l, int t) { return fa + ((size_t)l * 2 + (size_t)(t & 1)) * (wl.rows_out + (size_t)H); };
@@ -1373,57 +1343,72 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
     auto h_buf = [&](int l, int t) { return c_of(l, t) + SW; };
     for (int l = 0; l < L; ++l) {
         init_state(h_buf(l, -1), d_h0 ? d_h0 + (size_t)l * HS : nullptr, (size_t)HS, st);
-        if (lstmp) init_state(c_of(l, -1), d_c0 ? d_c0 + (size_t)l * H : nullptr, (size_t)H, st);
+        if (lstm) init_state(c_of(l, -1), d_c0 ? d_c0 + (size_t)l * H : nullptr, (size_t)H, st);
     }
-    if (lstmp) {
-        // r_(l,t), the projected output, is a plain vector (the result of the layer's second
-        // product); the last layer's goes straight into the output sequence when one is asked for
-        auto r_of = [&](int l, int t) {
-            return (t >= 0 && d_hseq && l == L - 1) ? d_hseq + (size_t)t * HS : h_buf(l, t);
-        };
-        for (int t = 0; t < T; ++t)
-            for (int l = 0; l < L; ++l) {
-                const float *u = l == 0 ? d_x + (size_t)t * I : (const float *)r_of(l - 1, t);
-                int rc = spmv_segments(r->W[l], u, l == 0 ? (uint32_t)I : (uint32_t)HS, r_of(l, t - 1), sums(l, t), part, st);
-                if (rc != CSB_OK) return rc;
-                GateSrc m{};                                     // m_t = o tanh(c_t): the LSTM cell on the sums
-                m.a = sums(l, t); m.bias = r->d_bias[l];
-                m.c_in = c_of(l, t - 1); m.c_out = c_of(l, t);
-                m.kind = 1u + CSB_CELL_LSTM; m.H = (uint32_t)H;
-                rc = spmv_gated(r->Wp[l], m, (uint32_t)H, plain_src(m.a), r_of(l, t), part, st);
-                if (rc != CSB_OK) return rc;
+    // LSTMP: r_(l,t), the projected output, is a plain vector (the result of the layer's second
+    // product); the last layer's goes straight into the output sequence when one is asked for
+    auto r_of = [&](int l, int t) { return (t >= 0 && d_hseq && l == L - 1) ? d_hseq + (size_t)t * HS : h_buf(l, t); };
+    // h_(l,t) of the other cells, still to be computed from the sums of step t
+    auto cell_output = [&](int l, int t) {
+        GateSrc g{};
+        g.a = sums(l, t); g.a2 = sums2(l, t); g.bias = r->d_bias[l];
+        g.c_in = lstm ? c_of(l, t - 1) : nullptr; g.h_in = h_buf(l, t - 1);
+        g.c_out = lstm ? c_of(l, t) : nullptr; g.h_out = h_buf(l, t);
+        g.hseq = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * H : nullptr;
+        g.kind = gru_rb ? kGateRbGate : 1u + (uint32_t)r->cell; g.H = (uint32_t)H;
+        return g;
+    };
+    for (int d = 0; d < T + L - 1; ++d) {
+        const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
+        // first (or only) product of every pair on the diagonal: W_l [input ; state]
+        for (int l0 = lo; l0 <= hi_l; l0 += kSpmmMaxJobs) {
+            SpmvGatedCall calls[kSpmmMaxJobs];
+            const int n = std::min(kSpmmMaxJobs, hi_l - l0 + 1);
+            for (int i = 0; i < n; ++i) {
+                const int l = l0 + i, t = d - l;
+                GateSrc below, back;
+                if (lstmp) {
+                    below = plain_src(l == 0 ? d_x + (size_t)t * I : (const float *)r_of(l - 1, t));
+                    back = plain_src(r_of(l, t - 1));
+                } else {
+                    below = l == 0 ? plain_src(d_x + (size_t)t * I) : cell_output(l - 1, t);
+                    back = t == 0 ? plain_src(h_buf(l, -1)) : cell_output(l, t - 1);
+                }
+                calls[i] = SpmvGatedCall{r->W[l], below, l == 0 ? (uint32_t)I : (uint32_t)HS, back, sums(l, t), part_of(l, 0)};
             }
-        for (int l = 0; l < L; ++l) {
-            init_state(d_hT + (size_t)l * HS, r_of(l, T - 1), (size_t)HS, st);
-            if (d_cT) init_state(d_cT + (size_t)l * H, c_of(l, T - 1), (size_t)H, st);
-        }
-    } else {
-        auto cell_output = [&](int l, int t) {                   // h_(l,t) from the two sums of step t
-            GateSrc g{};
-            g.a = sums(l, t); g.a2 = sums2(l, t); g.bias = r->d_bias[l];
-            g.h_in = h_buf(l, t - 1); g.h_out = h_buf(l, t);
-            g.hseq = (d_hseq && l == L - 1) ? d_hseq + (size_t)t * H : nullptr;
-            g.kind = kGateRbGate; g.H = (uint32_t)H;
-            return g;
-        };
-        for (int t = 0; t < T; ++t)
-            for (int l = 0; l < L; ++l) {
-                const GateSrc below = l == 0 ? plain_src(d_x + (size_t)t * I) : cell_output(l - 1, t);
-                const GateSrc back = t == 0 ? plain_src(h_buf(l, -1)) : cell_output(l, t - 1);
-                int rc = spmv_gated(r->W[l], below, l == 0 ? (uint32_t)I : (uint32_t)H, back, sums(l, t), part, st);
-                if (rc != CSB_OK) return rc;
-                GateSrc q{};                                     // q = r h_(t-1); h_(t-1) was stored by the launch above
-                q.a = sums(l, t); q.bias = r->d_bias[l]; q.h_in = h_buf(l, t - 1);
-                q.kind = kGateRbReset; q.H = (uint32_t)H;
-                rc = spmv_gated(r->Wp[l], q, (uint32_t)H, plain_src(q.a), sums2(l, t), part, st);
-                if (rc != CSB_OK) return rc;
-            }
-        for (int l = 0; l < L; ++l) {
-            GateSrc g = cell_output(l, T - 1);
-            g.h_out = d_hT + (size_t)l * H;
-            int rc = commit_gates(g, st);
+            int rc = spmv_gated_multi(calls, n, st);
             if (rc != CSB_OK) return rc;
         }
+        if (!lstmp && !gru_rb) continue;
+        // second product: LSTMP r_t = Wp m_t with m_t = o tanh(c_t) computed on the way in; the
+        // reset-before GRU's Un q with q = r h_(t-1) (h_(t-1) was stored by the launch above)
+        for (int l0 = lo; l0 <= hi_l; l0 += kSpmmMaxJobs) {
+            SpmvGatedCall calls[kSpmmMaxJobs];
+            const int n = std::min(kSpmmMaxJobs, hi_l - l0 + 1);
+            for (int i = 0; i < n; ++i) {
+                const int l = l0 + i, t = d - l;
+                GateSrc g{};
+                g.a = sums(l, t); g.bias = r->d_bias[l]; g.H = (uint32_t)H;
+                if (lstmp) { g.c_in = c_of(l, t - 1); g.c_out = c_of(l, t); g.kind = 1u + CSB_CELL_LSTM; }
+                else { g.h_in = h_buf(l, t - 1); g.kind = kGateRbReset; }
+                calls[i] = SpmvGatedCall{r->Wp[l], g, (uint32_t)H, plain_src(g.a), lstmp ? r_of(l, t) : sums2(l, t), part_of(l, 1)};
+            }
+            int rc = spmv_gated_multi(calls, n, st);
+            if (rc != CSB_OK) return rc;
+        }
+    }
+    // the last step's cells have no consumer: apply them here, into the caller's state arrays
+    for (int l = 0; l < L; ++l) {
+        if (lstmp) {
+            init_state(d_hT + (size_t)l * HS, r_of(l, T - 1), (size_t)HS, st);
+            if (d_cT) init_state(d_cT + (size_t)l * H, c_of(l, T - 1), (size_t)H, st);
+            continue;
+        }
+        GateSrc g = cell_output(l, T - 1);
+        g.h_out = d_hT + (size_t)l * H;
+        g.c_out = (lstm && d_cT) ? d_cT + (size_t)l * H : nullptr;
+        int rc = commit_gates(g, st);
+        if (rc != CSB_OK) return rc;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }

@@ -189,11 +189,10 @@ __global__ void commit_gates_kernel(const GateSrc s) {
 template <bool GATED> struct SpmvSrc { const float *a; };
 template <> struct SpmvSrc<true> : GateSrc {};
 template <int VF, bool GATED>
-__global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, const SpmvSrc<GATED> g0,
-                                                             const uint32_t n0, const SpmvSrc<GATED> g1,
-                                                             float *__restrict__ y, unsigned long long *__restrict__ partials,
-                                                             const uint32_t epoch, const LdsMap L,
-                                                             unsigned long long *__restrict__ stamps) {
+__device__ __forceinline__ void spmv_body(const DevMat &m, const SpmvSrc<GATED> &g0, const uint32_t n0,
+                                          const SpmvSrc<GATED> &g1, float *__restrict__ y,
+                                          unsigned long long *__restrict__ partials, const uint32_t epoch, const LdsMap &L,
+                                          unsigned long long *__restrict__ stamps, const uint32_t c) {
     extern __shared__ float4 smem4[];
     __shared__ uint32_t s_last;
     uint8_t *smem = (uint8_t *)smem4;
@@ -204,7 +203,6 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
     constexpr int NW = kSpmvWaves, NT = kSpmvThreads, CAP = kStepsInFlight, Q = kStepQuantum;
     const uint32_t tid = threadIdx.x;
     const int lane = tid & 63, wave = (int)uni(tid >> 6);
-    const uint32_t c = blockIdx.x;
     static_assert(kMaxStageCols / 4 <= 4 * NT, "input vector loads");
     static_assert(kChunkMetaMax <= 3 * NT * 8, "record loads");
     static_assert(kChunkMetaMax + 16 <= 2 * NT * 16, "index byte loads");
@@ -472,6 +470,32 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
     if (st && tid == 0) st[5] = __builtin_readcyclecounter();
 }
 
+template <int VF, bool GATED>
+__global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, const SpmvSrc<GATED> g0,
+                                                             const uint32_t n0, const SpmvSrc<GATED> g1,
+                                                             float *__restrict__ y, unsigned long long *__restrict__ partials,
+                                                             const uint32_t epoch, const LdsMap L,
+                                                             unsigned long long *__restrict__ stamps) {
+    spmv_body<VF, GATED>(m, g0, n0, g1, y, partials, epoch, L, stamps, blockIdx.x);
+}
+
+// Several independent mat-vecs in one launch (blockIdx.y picks one): the per-step products of
+// different layers of a stacked model on the streaming path.
+struct SpmvJobs {
+    DevMat m[kSpmmMaxJobs];
+    SpmvSrc<true> g0[kSpmmMaxJobs], g1[kSpmmMaxJobs];
+    uint32_t n0[kSpmmMaxJobs], epoch[kSpmmMaxJobs];
+    float *y[kSpmmMaxJobs];
+    unsigned long long *partials[kSpmmMaxJobs];
+    LdsMap L[kSpmmMaxJobs];
+};
+template <int VF>
+__global__ __launch_bounds__(kSpmvThreads) void spmv_multi_kernel(const SpmvJobs J) {
+    const uint32_t j = blockIdx.y;
+    if (blockIdx.x >= J.m[j].n_chunks) return;              // the grid is as wide as the job with most chunks
+    spmv_body<VF, true>(J.m[j], J.g0[j], J.n0[j], J.g1[j], J.y[j], J.partials[j], J.epoch[j], J.L[j], nullptr, blockIdx.x);
+}
+
 hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes) {
     static std::mutex mu;
     static std::map<std::pair<const void *, int>, size_t> have;   // (kernel, device) -> limit set so far
@@ -490,21 +514,18 @@ __global__ void clear_words_kernel(unsigned long long *p, size_t n) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
 }
 
-template <bool GATED>
-static hipError_t launch_spmv(const csb_matrix *mat, const SpmvSrc<GATED> &g0, uint32_t n0, const SpmvSrc<GATED> &g1, float *y,
-                              unsigned long long *partials, hipStream_t stream, unsigned long long *stamps = nullptr) {
+// What a launch needs besides its operands: the LDS map, and the launch tag of the merge words
+// (a workspace seen for the first time, or a wrapped tag, is cleared first so that no stale
+// word can carry the tag; tags are unique per launch across the process -- workspaces may be
+// shared between matrices -- and every 2^32 launches a new generation starts).
+static size_t prepare_spmv(const csb_matrix *mat, unsigned long long *partials, hipStream_t stream, LdsMap *Lout,
+                           uint32_t *epoch_out) {
     const DevHeader &h = mat->plan.hdr;
-    const DevMat dm = dev_mat(mat);
     LdsMap L{};
     L.zpad = ((uint32_t)h.cols + 1u + 63u) & ~63u;
     L.meta_off = L.zpad * 4u;
     L.acc_off = L.meta_off + h.meta_cap;
     L.red_off = L.acc_off + h.waves_per_chunk * kAccPlanes * h.max_chunk_tiles * h.br * (uint32_t)sizeof(float);
-    const size_t lds = (size_t)L.red_off + 4 * 256 * sizeof(float);
-    // Launch tag of the merge words; a workspace seen for the first time (or a wrapped tag)
-    // is cleared so that no stale word can carry the tag.
-    // Tags are unique per launch across the process (workspaces may be shared between
-    // matrices); every 2^32 launches a new generation starts and workspaces are cleared again.
     uint32_t epoch = 0;
     if (h.n_partial_slots) {
         uint32_t gen = 0;
@@ -517,13 +538,26 @@ static hipError_t launch_spmv(const csb_matrix *mat, const SpmvSrc<GATED> &g0, u
             mat->epoch = gen;
         }
     }
+    *Lout = L;
+    *epoch_out = epoch;
+    return (size_t)L.red_off + 4 * 256 * sizeof(float);
+}
+
+template <bool GATED>
+static hipError_t launch_spmv(const csb_matrix *mat, const SpmvSrc<GATED> &g0, uint32_t n0, const SpmvSrc<GATED> &g1, float *y,
+                              unsigned long long *partials, hipStream_t stream, unsigned long long *stamps = nullptr) {
+    const DevHeader &h = mat->plan.hdr;
+    if (h.waves_per_chunk != (uint32_t)kSpmvWaves) return hipErrorInvalidValue;
+    const DevMat dm = dev_mat(mat);
+    LdsMap L;
+    uint32_t epoch;
+    const size_t lds = prepare_spmv(mat, partials, stream, &L, &epoch);
     auto go = [&](auto kern, int nw) -> hipError_t {
         hipError_t e = ensure_dynamic_lds((const void *)kern, lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3(h.n_chunks), dim3(nw * 64), lds, stream, dm, g0, n0, g1, y, partials, epoch, L, stamps);
         return hipGetLastError();
     };
-    if (h.waves_per_chunk != (uint32_t)kSpmvWaves) return hipErrorInvalidValue;
     if (h.val_fmt == CSB_VAL_F16) return go(spmv_kernel<CSB_VAL_F16, GATED>, kSpmvWaves);
     if (h.val_fmt == CSB_VAL_BF16) return go(spmv_kernel<CSB_VAL_BF16, GATED>, kSpmvWaves);
     return go(spmv_kernel<CSB_VAL_F32, GATED>, kSpmvWaves);
@@ -553,6 +587,55 @@ int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSr
     static_cast<GateSrc &>(g0) = s0;
     static_cast<GateSrc &>(g1) = s1;
     hipError_t e = launch_spmv<true>(m, g0, n0, g1, d_y, (unsigned long long *)d_ws, (hipStream_t)stream, nullptr);
+    if (e != hipSuccess) { set_error(std::string("csb_spmv: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    return CSB_OK;
+}
+
+// Up to kSpmmMaxJobs independent gated mat-vecs in ONE launch (same value format); otherwise,
+// or for a single one, a launch each.
+int spmv_gated_multi(const SpmvGatedCall *calls, int n, void *stream) {
+    bool together = n > 1 && n <= kSpmmMaxJobs;
+    for (int i = 0; i < n && together; ++i) {
+        const csb_matrix *m = calls[i].mat;
+        together = m->plan.valid && m->uploaded && m->d_buf && m->plan.hdr.val_fmt == calls[0].mat->plan.hdr.val_fmt &&
+                   m->plan.hdr.waves_per_chunk == (uint32_t)kSpmvWaves && m->plan.hdr.cols <= (uint64_t)kMaxStageCols &&
+                   !(m->plan.hdr.n_partial_slots && !calls[i].ws);
+    }
+    if (!together) {
+        for (int i = 0; i < n; ++i) {
+            int rc = spmv_gated(calls[i].mat, calls[i].s0, calls[i].n0, calls[i].s1, calls[i].y, calls[i].ws, stream);
+            if (rc != CSB_OK) return rc;
+        }
+        return CSB_OK;
+    }
+    SpmvJobs J{};
+    size_t lds = 0;
+    unsigned chunks = 0;
+    for (int i = 0; i < n; ++i) {
+        const SpmvGatedCall &c = calls[i];
+        const DevHeader &h = c.mat->plan.hdr;
+        if ((c.s0.kind && c.s0.H != c.n0) || (c.s1.kind && (uint64_t)c.s1.H + c.n0 != h.cols)) {
+            set_error("csb_spmv: a computed input segment does not match the matrix's column split");
+            return CSB_EINVAL;
+        }
+        J.m[i] = dev_mat(c.mat);
+        static_cast<GateSrc &>(J.g0[i]) = c.s0;
+        static_cast<GateSrc &>(J.g1[i]) = c.s1;
+        J.n0[i] = c.n0;
+        J.y[i] = c.y;
+        J.partials[i] = (unsigned long long *)c.ws;
+        lds = std::max(lds, prepare_spmv(c.mat, J.partials[i], (hipStream_t)stream, &J.L[i], &J.epoch[i]));
+        chunks = std::max(chunks, (unsigned)h.n_chunks);
+    }
+    const uint32_t vf = calls[0].mat->plan.hdr.val_fmt;
+    auto go = [&](auto kern) -> hipError_t {
+        hipError_t e = ensure_dynamic_lds((const void *)kern, lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3(chunks, (unsigned)n), dim3(kSpmvThreads), lds, (hipStream_t)stream, J);
+        return hipGetLastError();
+    };
+    const hipError_t e = vf == CSB_VAL_F16 ? go(spmv_multi_kernel<CSB_VAL_F16>)
+                       : vf == CSB_VAL_BF16 ? go(spmv_multi_kernel<CSB_VAL_BF16>) : go(spmv_multi_kernel<CSB_VAL_F32>);
     if (e != hipSuccess) { set_error(std::string("csb_spmv: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
 }
