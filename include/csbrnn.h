@@ -316,9 +316,11 @@ int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
  * wider than 2048, or a stage whose inputs together are wider than 3072).  After csb_rnn_upload (d_buf device, caller-owned,
  * 256-byte aligned, >= csb_rnn_device_bytes, valid while the handle is used) csb_rnn_forward
  * with batch 1 runs all timesteps of all layers in ONE kernel launch; without it, or for
- * batch > 1, it launches one CSB product per step and layer and needs every W[l] uploaded
- * (batch 1: nothing else -- the gates of a step are computed by the launches that consume its
- * output; batch > 1: an element-wise kernel follows each product).
+ * batch > 1, it launches CSB products step by step and needs every W[l] uploaded: stacked
+ * layers run by diagonals (layer l at step t with l + t constant are independent and share a
+ * launch); at batch 1 nothing else is launched -- the gates of a step are computed by the
+ * products that consume its output -- and at batch > 1 one element-wise kernel follows each
+ * product launch.
  * The resident kernel's workgroups wait for each other's h_t: they must all be on the GPU at
  * once, so nothing else should occupy the device while it runs.  The workgroups are placed on
  * as few of the 8 XCDs as hold them (at most 28 per XCD, one per CU).
