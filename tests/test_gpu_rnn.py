@@ -255,13 +255,15 @@ def test_rnn_resident_every_slot_count(cell, slots, rate, monkeypatch):
 
 
 @pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
+@pytest.mark.parametrize("B", [3, 1])
 @pytest.mark.parametrize("L,T", [(5, 7), (6, 2), (3, 1)])
-def test_rnn_batched_deep_stacks(cell, L, T):
-    """Batched stacks run by diagonals (layer l at step t with l + t constant share a launch, up
-    to four layers per launch): more layers than a launch takes, more layers than steps, one step."""
-    cfg = csb_inputs.RnnConfig("t", cell, L, 12, 16, 8, 2.0, "binomial", 0.3, 3, T, 40 + L)
+def test_rnn_deep_stacks_by_diagonals(cell, L, T, B):
+    """The streaming (B = 1) and batched paths run stacks by diagonals (layer l at step t with
+    l + t constant share a launch, up to four layers per launch): more layers than a launch takes,
+    more layers than steps, one step."""
+    cfg = csb_inputs.RnnConfig("t", cell, L, 12, 16, 8, 2.0, "binomial", 0.3, B, T, 40 + L)
     wl = csb_inputs.make_rnn(cfg)
     rng = np.random.default_rng(L)
-    h0 = rng.uniform(-0.5, 0.5, (L, 3, 16)).astype(np.float32)
-    c0 = rng.uniform(-0.5, 0.5, (L, 3, 16)).astype(np.float32) if cell == csb_inputs.LSTM else None
-    run_case(wl, h0, c0, tag=f"deep-{L}x{T}", resident=False)
+    h0 = rng.uniform(-0.5, 0.5, (L, B, 16)).astype(np.float32)
+    c0 = rng.uniform(-0.5, 0.5, (L, B, 16)).astype(np.float32) if cell == csb_inputs.LSTM else None
+    run_case(wl, h0, c0, tag=f"deep-{L}x{T}-b{B}", resident=False)
