@@ -74,7 +74,8 @@ def workload(cell, L, I, H, T, B, block, seed, rate=3.0, sigma=0.3):
 
 
 SHAPES = [(1, 5, 8, 6, 1, 4), (2, 12, 16, 9, 3, 8), (3, 7, 12, 4, 2, 4), (1, 40, 100, 12, 1, 32),
-          (2, 30, 96, 7, 19, 16), (2, 33, 300, 9, 1, 32), (3, 16, 64, 20, 1, 16)]
+          (2, 30, 96, 7, 19, 16), (2, 33, 300, 9, 1, 32), (3, 16, 64, 20, 1, 16),
+          (5, 9, 16, 6, 1, 8), (6, 9, 16, 3, 4, 8)]
 
 
 @pytest.mark.parametrize("L,I,H,T,B,block", SHAPES)

@@ -65,7 +65,8 @@ def run_case(wl, h0=None, c0=None, tag="", resident=None):
 
 @pytest.mark.parametrize("L,I,H,P,T,B,block", [(1, 5, 8, 3, 6, 1, 4), (2, 12, 16, 8, 9, 3, 8), (3, 7, 12, 11, 4, 2, 4),
                                               (1, 40, 100, 37, 12, 1, 32), (2, 30, 96, 48, 7, 19, 16), (2, 9, 8, 16, 5, 2, 8),
-                                              (2, 33, 300, 130, 9, 1, 32), (3, 16, 64, 24, 20, 1, 16)])
+                                              (2, 33, 300, 130, 9, 1, 32), (3, 16, 64, 24, 20, 1, 16),
+                                              (5, 10, 16, 12, 6, 1, 8), (6, 10, 16, 8, 3, 4, 8)])   # more layers than one launch takes
 def test_lstmp_small(L, I, H, P, T, B, block):
     wl = csb_inputs.make_lstmp(40 + L + I, L, I, H, P, block, 3.0, T, B, sigma=0.3)
     rng = np.random.default_rng(1)
