@@ -312,7 +312,7 @@ int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
  * Resident layout of the whole model for batch-1 inference: every row's surviving weights
  * cut into equal slices, one slice per lane, kept in registers for the whole sequence (the
  * equal-work split of Sec. 5.2 applied to on-chip storage).  csb_rnn_device_bytes is 0 if
- * the model does not fit on chip (more than 224 workgroups' worth of weights, a layer input
+ * the model does not fit on chip (more than 8 layers, more than 224 workgroups' worth of weights, a layer input
  * wider than 2048, or a stage whose inputs together are wider than 3072).  After csb_rnn_upload (d_buf device, caller-owned,
  * 256-byte aligned, >= csb_rnn_device_bytes, valid while the handle is used) csb_rnn_forward
  * with batch 1 runs all timesteps of all layers in ONE kernel launch; without it, or for

@@ -30,6 +30,7 @@ namespace csb {
 
 constexpr int kRnnThreads = 1024;      // lanes per workgroup of the resident kernel
 constexpr int kRnnSlotsMax = 48;       // weights one lane keeps in registers
+constexpr int kRnnMaxLayers = 8;       // model layers of a resident layout (more: streaming path)
 constexpr int kRnnWgsPerXcd = 28;      // workgroups placed on one XCD (32 CUs, one workgroup per CU, a few CUs spare)
 constexpr int kRnnMaxWgs = 8 * kRnnWgsPerXcd;   // all workgroups must be co-resident
 constexpr uint32_t kPollLimit = 1u << 24;
@@ -197,6 +198,7 @@ static int build_resident_plan(csb_rnn *r) {
     pl = RnnPlan{};
     const bool lstmp = r->cell == CSB_CELL_LSTMP, gru_rb = r->cell == CSB_CELL_GRU_RB;
     const int NL = r->n_layers, L = (lstmp || gru_rb) ? 2 * NL : NL;      // L stages
+    if (NL > kRnnMaxLayers) return CSB_EUNSUPPORTED;                      // the kernel takes that many bias pointers
     struct LayerTmp {
         std::vector<std::vector<std::pair<uint32_t, float>>> rows;
         int n_in, C, S, P;
@@ -519,7 +521,7 @@ struct RnnArgs {
     const uint8_t *img;                 // resident image
     const float *x;                     // [T][I]
     const float *h0, *c0;               // [layers][state width], [layers][H] or null
-    const float *bias[8];               // per model layer, entries may be null
+    const float *bias[kRnnMaxLayers];   // per model layer, entries may be null
     float *hseq;                        // [T][state width] or null
     float *hT, *cT;                     // [layers][state width], [layers][H]; cT may be null
     unsigned long long *seq;            // tagged words: per workgroup [T][its units]
@@ -977,7 +979,7 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     RnnArgs A{};
     A.img = (const uint8_t *)r->d_img;
     A.x = d_x; A.h0 = d_h0; A.c0 = d_c0;
-    for (int l = 0; l < L && l < 8; ++l) A.bias[l] = r->d_bias[l];
+    for (int l = 0; l < L && l < kRnnMaxLayers; ++l) A.bias[l] = r->d_bias[l];
     A.hseq = d_hseq; A.hT = d_hT; A.cT = d_cT; A.seq = seq;
     A.T = (uint32_t)T; A.H = (uint32_t)H; A.I = (uint32_t)r->input;
     A.tag_base = tag_base;

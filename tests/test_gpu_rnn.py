@@ -256,7 +256,7 @@ def test_rnn_resident_every_slot_count(cell, slots, rate, monkeypatch):
 
 @pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
 @pytest.mark.parametrize("B", [3, 1])
-@pytest.mark.parametrize("L,T", [(5, 7), (6, 2), (3, 1)])
+@pytest.mark.parametrize("L,T", [(5, 7), (6, 2), (3, 1), (9, 4)])
 def test_rnn_deep_stacks_by_diagonals(cell, L, T, B):
     """The streaming (B = 1) and batched paths run stacks by diagonals (layer l at step t with
     l + t constant share a launch, up to four layers per launch): more layers than a launch takes,
@@ -267,3 +267,10 @@ def test_rnn_deep_stacks_by_diagonals(cell, L, T, B):
     h0 = rng.uniform(-0.5, 0.5, (L, B, 16)).astype(np.float32)
     c0 = rng.uniform(-0.5, 0.5, (L, B, 16)).astype(np.float32) if cell == csb_inputs.LSTM else None
     run_case(wl, h0, c0, tag=f"deep-{L}x{T}-b{B}", resident=False)
+
+
+@pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
+def test_rnn_resident_eight_layers(cell):
+    """Eight layers is the deepest stack the resident kernel takes (one bias pointer per layer)."""
+    cfg = csb_inputs.RnnConfig("t", cell, 8, 10, 24, 8, 2.0, "binomial", 0.3, 1, 6, 77)
+    run_case(csb_inputs.make_rnn(cfg), tag="eight-layers", resident=True)

@@ -271,3 +271,8 @@ def test_resident_layout_limits():
     rnn = CsbRnn(CELL_GRU_RB, 24, 64, Was, None, Wp=Uns)
     st = rnn.stats()
     assert st["resident"] == 1 and st["n_workgroups"] >= 4                      # two stages per layer
+    # the resident kernel takes the bias pointers of at most 8 layers: a deeper stack streams
+    for L, want in ((8, 1), (9, 0)):
+        wl = csb_inputs.make_rnn(csb_inputs.RnnConfig("t", csb_inputs.LSTM, L, 6, 8, 4, 2.0, "binomial", 0.1, 1, 1, 0))
+        rnn = CsbRnn(CELL_LSTM, 6, 8, [CsbMatrix(m.A, 4, 4) for m in wl.W], None)
+        assert rnn.stats()["resident"] == want
