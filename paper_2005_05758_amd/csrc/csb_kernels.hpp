@@ -7,7 +7,7 @@
 
 namespace csb {
 
-constexpr int kSpmmMaxJobs = 4;   // independent products that may share one launch
+constexpr int kMaxJobsPerLaunch = 4;   // independent products that may share one launch
 
 // A segment of the mat-vec's input that is not in memory yet: the output h_t of a recurrent
 // cell whose gate sums `a` an earlier launch on the same stream has produced.  The mat-vec

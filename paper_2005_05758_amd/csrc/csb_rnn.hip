@@ -811,15 +811,15 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
 // ------------------------------------------------------------------ streaming path
 
 // Batched element-wise parts: a is [rows][B], the state is kept as [H][B].  One launch serves
-// the cells of up to kSpmmMaxJobs layers (blockIdx.y), whose products shared a launch too.
+// the cells of up to kMaxJobsPerLaunch layers (blockIdx.y), whose products shared a launch too.
 struct GateJobs {
-    const float *a[kSpmmMaxJobs];
-    const float *bias[kSpmmMaxJobs];
-    const float *a2[kSpmmMaxJobs];   // reset-before GRU, gate part: the second product's sums
-    float *c[kSpmmMaxJobs];       // LSTM, LSTMP
-    float *h[kSpmmMaxJobs];
-    float *m[kSpmmMaxJobs];       // LSTMP: cell output m_t; reset-before GRU, reset part: q = r h
-    float *hseq[kSpmmMaxJobs];    // [B][H] of this step, or null
+    const float *a[kMaxJobsPerLaunch];
+    const float *bias[kMaxJobsPerLaunch];
+    const float *a2[kMaxJobsPerLaunch];   // reset-before GRU, gate part: the second product's sums
+    float *c[kMaxJobsPerLaunch];       // LSTM, LSTMP
+    float *h[kMaxJobsPerLaunch];
+    float *m[kMaxJobsPerLaunch];       // LSTMP: cell output m_t; reset-before GRU, reset part: q = r h
+    float *hseq[kMaxJobsPerLaunch];    // [B][H] of this step, or null
 };
 // what gates_batched_kernel computes: a cell (CSB_CELL_LSTM / _GRU / _LIGRU) or one of the
 // element-wise parts of the cells with two products per step
@@ -1249,7 +1249,7 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         const int gb = (H * batch + 255) / 256;
         // Layer l at step t needs layer l - 1 at step t and itself at step t - 1: everything on
         // the diagonal l + t = d is independent, so a diagonal takes ONE product launch and ONE
-        // element-wise launch per phase (for up to kSpmmMaxJobs layers each) instead of one per
+        // element-wise launch per phase (for up to kMaxJobsPerLaunch layers each) instead of one per
         // layer -- a single layer's product is too small to fill the GPU.  The states are updated
         // in place: within a diagonal every phase of all layers runs before the next phase.
         // LSTM / GRU / Li-GRU have one phase (product, gates); LSTMP has two (gate product, cell;
@@ -1260,8 +1260,8 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         for (int d = 0; d < T + L - 1; ++d) {
             const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
             auto for_groups = [&](auto body) -> int {           // body(first layer, layers in the group)
-                for (int l0 = lo; l0 <= hi_l; l0 += kSpmmMaxJobs) {
-                    int rc = body(l0, std::min(kSpmmMaxJobs, hi_l - l0 + 1));
+                for (int l0 = lo; l0 <= hi_l; l0 += kMaxJobsPerLaunch) {
+                    int rc = body(l0, std::min(kMaxJobsPerLaunch, hi_l - l0 + 1));
                     if (rc != CSB_OK) return rc;
                 }
                 return CSB_OK;
@@ -1285,7 +1285,7 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
             };
             // first (or only) product: W_l [input ; state]
             int rc = for_groups([&](int l0, int n) {
-                SpmmCall calls[kSpmmMaxJobs];
+                SpmmCall calls[kMaxJobsPerLaunch];
                 for (int i = 0; i < n; ++i) {
                     const int l = l0 + i, t = d - l;
                     float *hl = hi + (size_t)l * HS * batch;
@@ -1306,7 +1306,7 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
             ew(lstmp ? kEwLstmpCell : kEwRbReset);               // m_t, or q = r h_(t-1)
             // second product: the projection r_t = Wp m_t straight into the state, or Un q
             rc = for_groups([&](int l0, int n) {
-                SpmmCall calls[kSpmmMaxJobs];
+                SpmmCall calls[kMaxJobsPerLaunch];
                 for (int i = 0; i < n; ++i) {
                     const int l = l0 + i;
                     float *ml = mb + (size_t)l * hb;
@@ -1363,9 +1363,9 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
     for (int d = 0; d < T + L - 1; ++d) {
         const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
         // first (or only) product of every pair on the diagonal: W_l [input ; state]
-        for (int l0 = lo; l0 <= hi_l; l0 += kSpmmMaxJobs) {
-            SpmvGatedCall calls[kSpmmMaxJobs];
-            const int n = std::min(kSpmmMaxJobs, hi_l - l0 + 1);
+        for (int l0 = lo; l0 <= hi_l; l0 += kMaxJobsPerLaunch) {
+            SpmvGatedCall calls[kMaxJobsPerLaunch];
+            const int n = std::min(kMaxJobsPerLaunch, hi_l - l0 + 1);
             for (int i = 0; i < n; ++i) {
                 const int l = l0 + i, t = d - l;
                 GateSrc below, back;
@@ -1384,9 +1384,9 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         if (!lstmp && !gru_rb) continue;
         // second product: LSTMP r_t = Wp m_t with m_t = o tanh(c_t) computed on the way in; the
         // reset-before GRU's Un q with q = r h_(t-1) (h_(t-1) was stored by the launch above)
-        for (int l0 = lo; l0 <= hi_l; l0 += kSpmmMaxJobs) {
-            SpmvGatedCall calls[kSpmmMaxJobs];
-            const int n = std::min(kSpmmMaxJobs, hi_l - l0 + 1);
+        for (int l0 = lo; l0 <= hi_l; l0 += kMaxJobsPerLaunch) {
+            SpmvGatedCall calls[kMaxJobsPerLaunch];
+            const int n = std::min(kMaxJobsPerLaunch, hi_l - l0 + 1);
             for (int i = 0; i < n; ++i) {
                 const int l = l0 + i, t = d - l;
                 GateSrc g{};

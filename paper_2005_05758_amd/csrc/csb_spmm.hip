@@ -286,10 +286,10 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
 // Several independent products in one launch (blockIdx.z picks the product): the per-step
 // products of different layers of a batched recurrent model, each too small to fill the GPU.
 struct SpmmJobs {
-    DevMat m[kSpmmMaxJobs];
-    XSrc X[kSpmmMaxJobs];
-    float *Y[kSpmmMaxJobs];
-    int64_t ldy[kSpmmMaxJobs];
+    DevMat m[kMaxJobsPerLaunch];
+    XSrc X[kMaxJobsPerLaunch];
+    float *Y[kMaxJobsPerLaunch];
+    int64_t ldy[kMaxJobsPerLaunch];
 };
 template <int NT, bool TWO, int NW, bool WIDE>
 __global__ __launch_bounds__(NW * 64) void spmm_multi_kernel(const SpmmJobs J, const uint32_t batch) {
@@ -381,13 +381,13 @@ int spmm_strided(const csb_matrix *mat, const float *p0, uint32_t n0, int64_t sj
     return CSB_OK;
 }
 
-// Up to kSpmmMaxJobs independent products in ONE launch when they agree on the launch shape
+// Up to kMaxJobsPerLaunch independent products in ONE launch when they agree on the launch shape
 // (same-shaped layers do); otherwise one launch each.
 int spmm_strided_multi(const SpmmCall *calls, int n, int32_t batch, void *stream) {
     if (n <= 0) return CSB_OK;
-    SpmmShape sh[kSpmmMaxJobs];
+    SpmmShape sh[kMaxJobsPerLaunch];
     SpmmJobs J{};
-    bool same = n <= kSpmmMaxJobs && n > 1;
+    bool same = n <= kMaxJobsPerLaunch && n > 1;
     if (same) {
         size_t lds = 0;
         unsigned tiles = 0;

@@ -482,12 +482,12 @@ __global__ __launch_bounds__(kSpmvThreads) void spmv_kernel(const DevMat m, cons
 // Several independent mat-vecs in one launch (blockIdx.y picks one): the per-step products of
 // different layers of a stacked model on the streaming path.
 struct SpmvJobs {
-    DevMat m[kSpmmMaxJobs];
-    SpmvSrc<true> g0[kSpmmMaxJobs], g1[kSpmmMaxJobs];
-    uint32_t n0[kSpmmMaxJobs], epoch[kSpmmMaxJobs];
-    float *y[kSpmmMaxJobs];
-    unsigned long long *partials[kSpmmMaxJobs];
-    LdsMap L[kSpmmMaxJobs];
+    DevMat m[kMaxJobsPerLaunch];
+    SpmvSrc<true> g0[kMaxJobsPerLaunch], g1[kMaxJobsPerLaunch];
+    uint32_t n0[kMaxJobsPerLaunch], epoch[kMaxJobsPerLaunch];
+    float *y[kMaxJobsPerLaunch];
+    unsigned long long *partials[kMaxJobsPerLaunch];
+    LdsMap L[kMaxJobsPerLaunch];
 };
 template <int VF>
 __global__ __launch_bounds__(kSpmvThreads) void spmv_multi_kernel(const SpmvJobs J) {
@@ -591,10 +591,10 @@ int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSr
     return CSB_OK;
 }
 
-// Up to kSpmmMaxJobs independent gated mat-vecs in ONE launch (same value format); otherwise,
+// Up to kMaxJobsPerLaunch independent gated mat-vecs in ONE launch (same value format); otherwise,
 // or for a single one, a launch each.
 int spmv_gated_multi(const SpmvGatedCall *calls, int n, void *stream) {
-    bool together = n > 1 && n <= kSpmmMaxJobs;
+    bool together = n > 1 && n <= kMaxJobsPerLaunch;
     for (int i = 0; i < n && together; ++i) {
         const csb_matrix *m = calls[i].mat;
         together = m->plan.valid && m->uploaded && m->d_buf && m->plan.hdr.val_fmt == calls[0].mat->plan.hdr.val_fmt &&
