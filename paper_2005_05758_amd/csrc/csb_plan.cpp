@@ -244,7 +244,9 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
             // default: one workgroup per CU of an MI355X (256) once every wavefront has a group's
             // worth of work: a launch costs several microseconds of dependent latencies whatever
             // its size, so a small matrix is spread over many workgroups rather than few
-            const uint64_t per_wave_min = kGroupOverhead + 4;
+            // (measured on the batch-1 RNN matrices: 6 cost units per wavefront beat 14 by 8 % of
+            // the launch's kernel time; below that nothing more is gained)
+            const uint64_t per_wave_min = 6;
             uint64_t want = total / (per_wave_min * (uint64_t)NW);
             want = std::min<uint64_t>(std::max<uint64_t>(want, 1), 256);
             n_chunks = (int)want;
