@@ -101,6 +101,8 @@ struct csb_rnn {
     bool uploaded = false;
     mutable const void *ws_seen = nullptr;
     mutable uint32_t ws_gen = 0xffffffffu;
+    mutable size_t ws_words = 0;             // exchange words cleared there so far
+    mutable int64_t ws_use = -1;             // batch and path of the last forward call (they fix what lies where)
 };
 
 namespace csb {
@@ -529,6 +531,11 @@ struct RnnArgs {
     uint32_t off_unit_wg;               // byte offset in img of the owner table
     uint32_t poll_delay;                // s_sleep units before the first poll of a step (0 = none)
     uint32_t xcds, per_xcd, n_wgs, xcd_step;      // workgroup w runs as block (w % per_xcd) * 8 + w / per_xcd; other blocks exit at once
+    // Independent sequences side by side: instance i runs the whole model on the XCDs one place
+    // further on (i < xcd_step) over its own x, states, outputs and exchange words, each this
+    // many elements behind the instance before.
+    uint32_t n_inst;
+    size_t s_x, s_h, s_c, s_hseq, s_seq;
     unsigned long long *dbg;            // optional: per-phase shader clocks summed over the steps (workgroup 0)
 };
 
@@ -574,7 +581,14 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     // fastest between CUs that share an L2.
     const uint32_t xq = (blockIdx.x & 7u) / A.xcd_step, xr = (blockIdx.x & 7u) % A.xcd_step;
     const uint32_t wgi = xq * A.per_xcd + (blockIdx.x >> 3);
-    if (xr != 0 || xq >= A.xcds || (blockIdx.x >> 3) >= A.per_xcd || wgi >= A.n_wgs) return;
+    if (xr >= A.n_inst || xq >= A.xcds || (blockIdx.x >> 3) >= A.per_xcd || wgi >= A.n_wgs) return;
+    const float *const x_in = A.x + (size_t)xr * A.s_x;
+    const float *const h0 = A.h0 ? A.h0 + (size_t)xr * A.s_h : nullptr;
+    const float *const c0 = A.c0 ? A.c0 + (size_t)xr * A.s_c : nullptr;
+    float *const hseq = A.hseq ? A.hseq + (size_t)xr * A.s_hseq : nullptr;
+    float *const hT = A.hT + (size_t)xr * A.s_h;
+    float *const cT = A.cT ? A.cT + (size_t)xr * A.s_c : nullptr;
+    unsigned long long *const seq = A.seq + (size_t)xr * A.s_seq;
     const RnnWgRec wg = ((const RnnWgRec *)A.img)[wgi];
     const uint32_t H = A.H, T = A.T, nu = wg.nu, n_in = wg.n_in, C = wg.C, S = wg.S;
     // (the record is the same for every lane: keep what steers branches in scalar registers)
@@ -634,8 +648,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     // where this owner's unit sits in the staged vector's recurrent part (if that part is this stage's own or its state)
     const uint32_t zown = (owner && n_in + unit < C) ? ((const uint16_t *)(A.img + wg.off_zpos))[n_in + unit] : C;
     if (owner) {
-        if (A.c0 && lstm) c_state = A.c0[(size_t)real * H + unit];
-        if (A.h0 && is_state) h_state = A.h0[(size_t)real * wg.width + unit];
+        if (c0 && lstm) c_state = c0[(size_t)real * H + unit];
+        if (h0 && is_state) h_state = h0[(size_t)real * wg.width + unit];
     }
     if (tid == 0) z[C] = 0.0f;
     // rows without survivors have no lane: their entry keeps the activation of the bare bias
@@ -653,7 +667,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     // Exchange words: every workgroup publishes the outputs of its units into a region of its
     // own, [t][unit of the workgroup]; the regions of different workgroups lie T * nu words
     // apart, which spreads the polling over the memory channels.
-    unsigned long long *pub = A.seq + (size_t)T * wg.upre + tid;     // + t * nu
+    unsigned long long *pub = seq + (size_t)T * wg.upre + tid;     // + t * nu
     const uint16_t *unit_wg = (const uint16_t *)(A.img + A.off_unit_wg);
     // z entries are staged from the top of the workgroup: thread tid handles entries
     // zt and zt + 1024.  The unit owners (low tids) publish with global stores, and a
@@ -678,11 +692,11 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         zp[rep] = zpos[e];
         const bool rec = e >= n_in && e < rec_end, third = e >= rec_end;
         const uint32_t us = third ? e - rec_end : (rec ? e - n_in : e);
-        if (rec) z[zp[rep]] = A.h0 ? A.h0[(size_t)real * wg.rec_width + us] : 0.0f;
+        if (rec) z[zp[rep]] = h0 ? h0[(size_t)real * wg.rec_width + us] : 0.0f;
         if (rec ? (own_rec && us - wg.u0 < nu) : (!third && from_x)) continue;
         const RnnWgRec *q = (const RnnWgRec *)A.img + unit_wg[(size_t)(third ? wg.aux : (rec ? wg.rec : wg.below)) + us];
         const uint32_t back = rec ? 1u : 0u;
-        pp[rep] = A.seq + ((size_t)T * q->upre + (us - q->u0)) - (size_t)back * q->nu;
+        pp[rep] = seq + ((size_t)T * q->upre + (us - q->u0)) - (size_t)back * q->nu;
         pstride[rep] = q->nu;
         ptmin[rep] = back;
         ptag[rep] = A.tag_base - back;
@@ -691,8 +705,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     const bool xl0 = from_x && zt < n_in, xl1 = from_x && zt + kRnnThreads < n_in;
     float xnext0 = 0.0f, xnext1 = 0.0f;
     if (T > 0) {
-        if (xl0) xnext0 = A.x[zt];
-        if (xl1) xnext1 = A.x[zt + kRnnThreads];
+        if (xl0) xnext0 = x_in[zt];
+        if (xl1) xnext1 = x_in[zt + kRnnThreads];
     }
     // does this wavefront poll at all (any lane with a remote source)?
     const bool polls = __ballot(ptmin[0] != ~0u || ptmin[1] != ~0u || ptmin[2] != ~0u) != 0ull;
@@ -724,8 +738,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
             if (xl0) z[zp[0]] = xnext0;
             if (xl1) z[zp[1]] = xnext1;
             if (t + 1 < T) {
-                if (xl0) xnext0 = A.x[(size_t)(t + 1) * A.I + zt];
-                if (xl1) xnext1 = A.x[(size_t)(t + 1) * A.I + zt + kRnnThreads];
+                if (xl0) xnext0 = x_in[(size_t)(t + 1) * A.I + zt];
+                if (xl1) xnext1 = x_in[(size_t)(t + 1) * A.I + zt + kRnnThreads];
             }
         }
         lds_barrier();
@@ -795,7 +809,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
             if (own_rec) z[zown] = hn;               // next step's input, read only after the next barrier
             const unsigned long long pk = ((unsigned long long)tag_now << 32) | (unsigned long long)__float_as_uint(hn);
             __hip_atomic_store(pub + (size_t)t * nu, pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (A.hseq && (flags & kStageIsSeq)) A.hseq[(size_t)t * wg.width + unit] = hn;
+            if (hseq && (flags & kStageIsSeq)) hseq[(size_t)t * wg.width + unit] = hn;
         }
         if (dbg) { c1_ = __builtin_readcyclecounter(); ph3 += c1_ - c0_; }
     }
@@ -803,8 +817,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     if (kPhaseClocks && A.dbg && blockIdx.x == 0 && (tid & 63u) == 0) A.dbg[8 + (tid >> 6)] = wave_arrive;
     if (kPhaseClocks && A.dbg && blockIdx.x == 0 && tid == 512) A.dbg[6] = delay;
     if (owner) {
-        if (is_state) A.hT[(size_t)real * wg.width + unit] = h_state;
-        if (A.cT && lstm) A.cT[(size_t)real * H + unit] = c_state;
+        if (is_state) hT[(size_t)real * wg.width + unit] = h_state;
+        if (cT && lstm) cT[(size_t)real * H + unit] = c_state;
     }
 }
 
@@ -916,7 +930,20 @@ static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 struct RnnWs {
     size_t off_a, off_a2, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, off_m, off_fa, off_fs, rows_out, part_stride, total;
+    size_t off_rx, off_rseq, off_rh, off_rc;      // a batch on the resident kernel: per-sequence copies
 };
+
+// XCDs one instance of the resident kernel occupies, and how many instances fit side by side
+static uint32_t resident_xcds(const csb_rnn *r) {
+    uint32_t xcds = ((uint32_t)r->plan.n_wgs + kRnnWgsPerXcd - 1) / kRnnWgsPerXcd;
+    if (const char *e = getenv("CSB_RNN_XCDS")) xcds = std::max(xcds, (uint32_t)std::min(8, std::max(1, atoi(e))));
+    return xcds;
+}
+static int resident_instances(const csb_rnn *r, int32_t batch) {
+    if (!r->plan.valid) return 1;
+    const uint32_t xcds = resident_xcds(r);
+    return xcds > 8 ? 1 : (int)std::min<uint32_t>(8u / xcds, (uint32_t)batch);
+}
 
 static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     RnnWs w{};
@@ -942,8 +969,18 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     w.off_part = off; off = align256(off + w.part_stride * (batch == 1 ? 2 * (size_t)r->n_layers : 1));
     w.off_biasptr = off; off = align256(off + (size_t)r->n_layers * sizeof(void *));
     // exchange words of the resident kernel: one per unit of every stage and step
+    // (a batch may run as several instances of the resident kernel side by side, each with
+    // exchange words of its own and with its sequence, states and outputs stored on their own)
     const size_t seq_units = r->plan.valid ? r->plan.total_units : 0;
-    w.off_seq = off; off = align256(off + (size_t)std::max(T, 1) * seq_units * 8);
+    const size_t inst = batch > 1 ? (size_t)resident_instances(r, batch) : 1;
+    w.off_seq = off; off = align256(off + (size_t)std::max(T, 1) * seq_units * 8 * inst);
+    if (batch > 1 && r->plan.valid) {
+        const size_t B = (size_t)batch, Tn = (size_t)std::max(T, 1);
+        w.off_rx = off; off = align256(off + B * Tn * r->input * sizeof(float));
+        w.off_rseq = off; off = align256(off + B * Tn * HS * sizeof(float));
+        w.off_rh = off; off = align256(off + 2 * B * r->n_layers * HS * sizeof(float));      // h0, hT
+        w.off_rc = off; off = align256(off + 2 * B * r->n_layers * r->hidden * sizeof(float));  // c0, cT
+    }
     if (batch > 1) {
         w.off_hint = off; off = align256(off + (size_t)r->n_layers * batch * HS * sizeof(float));
         w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
@@ -960,19 +997,27 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     return w;
 }
 
+// One launch of the resident kernel: `n_inst` sequences side by side (instance i on the XCDs
+// one place further on), their x / states / outputs `s_*` elements apart.
 static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0, float *d_hseq,
-                            float *d_hT, float *d_cT, int32_t T, void *d_ws, hipStream_t st) {
-    const RnnWs wl = ws_layout(r, 1, T);
+                            float *d_hT, float *d_cT, int32_t T, void *d_ws, const RnnWs &wl, hipStream_t st, int n_inst = 1,
+                            size_t s_x = 0, size_t s_h = 0, size_t s_c = 0, size_t s_hseq = 0, size_t region_words = 0) {
     const int L = r->n_layers, H = r->hidden;
     unsigned long long *seq = (unsigned long long *)((uint8_t *)d_ws + wl.off_seq);
-    const size_t words = r->plan.total_units * (size_t)T;
-    // unique tags for this call's T steps; a workspace seen for the first time (or a new tag
-    // generation) is cleared so that no stale word can carry a tag of this call
+    const size_t words_inst = r->plan.total_units * (size_t)T, words = words_inst * (size_t)n_inst;
+    // Unique tags for this call's T steps; a workspace seen for the first time (or a new tag
+    // generation) is cleared so that no stale word can carry a tag of this call.  A single
+    // sequence writes nothing but these words into the workspace, so there a region that was
+    // cleared once stays good while it does not grow; a batch keeps float buffers behind the
+    // words, at places that move with T, so there any other size is cleared again.
+    const size_t region = region_words ? region_words : words;
+    const bool other_size = region_words ? region != r->ws_words : region > r->ws_words;
     uint32_t gen = 0;
     const uint32_t tag_base = reserve_tags((uint32_t)T, &gen);
-    if (r->ws_seen != (const void *)seq || r->ws_gen != gen) {
-        hipLaunchKernelGGL(clear_tags_kernel, dim3((unsigned)std::min<size_t>((words + 255) / 256, 2048)), dim3(256), 0, st,
-                           seq, words);
+    if (r->ws_seen != (const void *)seq || r->ws_gen != gen || other_size) {
+        hipLaunchKernelGGL(clear_tags_kernel, dim3((unsigned)std::min<size_t>((region + 255) / 256, 2048)), dim3(256), 0, st,
+                           seq, region);
+        r->ws_words = region;
         r->ws_seen = seq;
         r->ws_gen = gen;
     }
@@ -985,13 +1030,15 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     A.tag_base = tag_base;
     A.off_unit_wg = (uint32_t)r->plan.off_unit_wg;
     // at most kRnnWgsPerXcd workgroups per XCD (32 CUs each, one workgroup per CU, all resident)
-    uint32_t xcds = ((uint32_t)r->plan.n_wgs + kRnnWgsPerXcd - 1) / kRnnWgsPerXcd;
-    if (const char *e = getenv("CSB_RNN_XCDS")) xcds = std::max(xcds, (uint32_t)std::min(8, std::max(1, atoi(e))));
+    const uint32_t xcds = resident_xcds(r);
     if (xcds > 8) { set_error("csb_rnn_forward: resident layout has more workgroups than the device holds at once"); return CSB_EUNSUPPORTED; }
     A.xcds = xcds;
     A.per_xcd = ((uint32_t)r->plan.n_wgs + xcds - 1) / xcds;
     A.n_wgs = (uint32_t)r->plan.n_wgs;
     A.xcd_step = 8u / xcds;                       // the XCDs in use lie this far apart
+    if (n_inst < 1 || (uint32_t)n_inst > A.xcd_step) { set_error("csb_rnn_forward: more instances than XCD groups"); return CSB_EINVAL; }
+    A.n_inst = (uint32_t)n_inst;
+    A.s_x = s_x; A.s_h = s_h; A.s_c = s_c; A.s_hseq = s_hseq; A.s_seq = words_inst;
     A.poll_delay = r->plan.n_wgs > 1 ? 8u : 0u;   // fewer polls in flight while h_t cannot have arrived yet
     if (const char *e = getenv("CSB_RNN_POLL_DELAY")) A.poll_delay = (uint32_t)std::max(0, atoi(e));
     if (kPhaseClocks && getenv("CSB_RNN_DEBUG")) A.dbg = (unsigned long long *)((uint8_t *)d_ws + wl.total - 512);
@@ -1027,6 +1074,72 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     }
     if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
+}
+
+// dst[b][a][:] = src[a][b][:] for src of shape [A][B][C]
+__global__ void swap_outer_kernel(float *__restrict__ dst, const float *__restrict__ src, size_t A, size_t B, size_t C) {
+    const size_t n = A * B * C;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t c = i % C, ab = i / C, b = ab % B, a = ab / B;
+        dst[(b * A + a) * C + c] = src[i];
+    }
+}
+static void swap_outer(float *dst, const float *src, size_t A, size_t B, size_t C, hipStream_t st) {
+    const size_t n = A * B * C;
+    if (!n) return;
+    hipLaunchKernelGGL(swap_outer_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 4096)), dim3(256), 0, st, dst, src, A, B, C);
+}
+
+// A batch on the resident kernel: the sequences are independent, and a model that fills only
+// some of the 8 XCDs leaves room for further instances of itself beside it.  x, the states and
+// the outputs are regrouped per sequence in the workspace; every launch then runs as many
+// sequences as instances fit, each on XCDs of its own.
+static int forward_resident_batch(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0, float *d_hseq,
+                                  float *d_hT, float *d_cT, int32_t T, int32_t batch, void *d_ws, hipStream_t st) {
+    const RnnWs wl = ws_layout(r, batch, T);
+    const size_t L = (size_t)r->n_layers, H = (size_t)r->hidden, HS = (size_t)r->state_width(), I = (size_t)r->input;
+    const size_t B = (size_t)batch, Tn = (size_t)T;
+    const bool lstm = r->cell == CSB_CELL_LSTM || r->cell == CSB_CELL_LSTMP;
+    float *xs = (float *)((uint8_t *)d_ws + wl.off_rx), *seqs = (float *)((uint8_t *)d_ws + wl.off_rseq);
+    float *h0s = (float *)((uint8_t *)d_ws + wl.off_rh), *hTs = h0s + B * L * HS;
+    float *c0s = (float *)((uint8_t *)d_ws + wl.off_rc), *cTs = c0s + B * L * H;
+    swap_outer(xs, d_x, Tn, B, I, st);                          // [T][B][I] -> [B][T][I]
+    if (d_h0) swap_outer(h0s, d_h0, L, B, HS, st);              // [L][B][HS] -> [B][L][HS]
+    if (d_c0 && lstm) swap_outer(c0s, d_c0, L, B, H, st);
+    const int R = resident_instances(r, batch);
+    for (int32_t b0 = 0; b0 < batch; b0 += R) {
+        const int n = std::min<int32_t>(R, batch - b0);
+        const size_t b = (size_t)b0;
+        int rc = forward_resident(r, xs + b * Tn * I, d_h0 ? h0s + b * L * HS : nullptr, (d_c0 && lstm) ? c0s + b * L * H : nullptr,
+                                  d_hseq ? seqs + b * Tn * HS : nullptr, hTs + b * L * HS, (d_cT && lstm) ? cTs + b * L * H : nullptr,
+                                  T, d_ws, wl, st, n, Tn * I, L * HS, L * H, Tn * HS,
+                                  (size_t)R * r->plan.total_units * Tn);
+        if (rc != CSB_OK) return rc;
+    }
+    if (d_hseq) swap_outer(d_hseq, seqs, B, Tn, HS, st);
+    swap_outer(d_hT, hTs, B, L, HS, st);
+    if (d_cT && lstm) swap_outer(d_cT, cTs, B, L, H, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    return CSB_OK;
+}
+
+// Rough cost of one time step of a batch, in microseconds, on the two paths that can run it
+// (fitted to measurements on MI355X): the resident kernel takes about a microsecond per step
+// and XCD it spans, twice that for the cells with two dependent products per step, and runs
+// the batch in rounds of as many sequences as instances fit; the batched MFMA path pays its
+// launches per diagonal whatever the batch.
+static bool batch_prefers_resident(const csb_rnn *r, int32_t batch) {
+    if (const char *e = getenv("CSB_RNN_BATCH_PATH")) {
+        if (!strcmp(e, "resident")) return true;
+        if (!strcmp(e, "batched")) return false;
+    }
+    const bool two = r->cell == CSB_CELL_LSTMP || r->cell == CSB_CELL_GRU_RB;
+    const int R = resident_instances(r, batch);
+    const double rounds = (double)((batch + R - 1) / R);
+    const double resident_us = rounds * (0.9 + 0.3 * resident_xcds(r)) * (two ? 2.2 : 1.0);
+    const double batched_us = (10.0 + 4.0 * r->n_layers) * (two ? 1.25 : 1.0);
+    return resident_us * 1.1 < batched_us;
 }
 
 }  // namespace csb
@@ -1214,7 +1327,11 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         if (lstm && d_cT) init_state(d_cT, d_c0, ncstate, st);
         return CSB_OK;
     }
-    const bool resident = batch == 1 && r->plan.valid && r->uploaded;
+    bool streams_ready = true;
+    for (auto *m : r->W) streams_ready = streams_ready && m->plan.valid && m->uploaded;
+    for (auto *m : r->Wp) streams_ready = streams_ready && m->plan.valid && m->uploaded;
+    const bool can_reside = r->plan.valid && r->uploaded && resident_xcds(r) <= 8;
+    const bool resident = can_reside && (batch == 1 || !streams_ready || batch_prefers_resident(r, batch));
     if (!resident) {
         for (auto *m : r->W)
             if (!m->plan.valid || !m->uploaded) {
@@ -1234,7 +1351,17 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         for (auto *m : r->W) m->ws_seen = nullptr;
         for (auto *m : r->Wp) m->ws_seen = nullptr;
     }
-    if (resident) return forward_resident(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, d_ws, st);
+    // The paths lay the workspace out differently, and so do different batch sizes: what was a
+    // float buffer of the last call may be tagged words of this one.
+    const int64_t use = (int64_t)batch * 2 + (resident ? 1 : 0);
+    if (r->ws_use != use) {
+        r->ws_use = use;
+        r->ws_seen = nullptr;
+        for (auto *m : r->W) m->ws_seen = nullptr;
+        for (auto *m : r->Wp) m->ws_seen = nullptr;
+    }
+    if (resident && batch == 1) return forward_resident(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, d_ws, ws_layout(r, 1, T), st);
+    if (resident) return forward_resident_batch(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, batch, d_ws, st);
 
     const RnnWs wl = ws_layout(r, batch, T);
     float *a = (float *)((uint8_t *)d_ws + wl.off_a), *a2 = (float *)((uint8_t *)d_ws + wl.off_a2);
