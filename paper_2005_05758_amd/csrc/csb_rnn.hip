@@ -531,10 +531,11 @@ struct RnnArgs {
     uint32_t off_unit_wg;               // byte offset in img of the owner table
     uint32_t poll_delay;                // s_sleep units before the first poll of a step (0 = none)
     uint32_t xcds, per_xcd, n_wgs, xcd_step;      // workgroup w runs as block (w % per_xcd) * 8 + w / per_xcd; other blocks exit at once
-    // Independent sequences side by side: instance i runs the whole model on the XCDs one place
-    // further on (i < xcd_step) over its own x, states, outputs and exchange words, each this
-    // many elements behind the instance before.
-    uint32_t n_inst;
+    // Independent sequences side by side: instance i runs the whole model on the XCDs
+    // i % xcd_step places further on (a model that fills at most half an XCD: `share` instances
+    // behind each other on the same XCD, i / xcd_step the place) over its own x, states, outputs
+    // and exchange words, each this many elements behind the instance before.
+    uint32_t n_inst, share;
     size_t s_x, s_h, s_c, s_hseq, s_seq;
     unsigned long long *dbg;            // optional: per-phase shader clocks summed over the steps (workgroup 0)
 };
@@ -580,15 +581,17 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     // onto as few XCDs as hold them, consecutive ones on the same XCD: the exchange of h_t is
     // fastest between CUs that share an L2.
     const uint32_t xq = (blockIdx.x & 7u) / A.xcd_step, xr = (blockIdx.x & 7u) % A.xcd_step;
-    const uint32_t wgi = xq * A.per_xcd + (blockIdx.x >> 3);
-    if (xr >= A.n_inst || xq >= A.xcds || (blockIdx.x >> 3) >= A.per_xcd || wgi >= A.n_wgs) return;
-    const float *const x_in = A.x + (size_t)xr * A.s_x;
-    const float *const h0 = A.h0 ? A.h0 + (size_t)xr * A.s_h : nullptr;
-    const float *const c0 = A.c0 ? A.c0 + (size_t)xr * A.s_c : nullptr;
-    float *const hseq = A.hseq ? A.hseq + (size_t)xr * A.s_hseq : nullptr;
-    float *const hT = A.hT + (size_t)xr * A.s_h;
-    float *const cT = A.cT ? A.cT + (size_t)xr * A.s_c : nullptr;
-    unsigned long long *const seq = A.seq + (size_t)xr * A.s_seq;
+    const uint32_t sub = (blockIdx.x >> 3) / A.per_xcd, pos = (blockIdx.x >> 3) - sub * A.per_xcd;
+    const uint32_t wgi = xq * A.per_xcd + pos;
+    const uint32_t inst = sub * A.xcd_step + xr;
+    if (inst >= A.n_inst || sub >= A.share || xq >= A.xcds || wgi >= A.n_wgs) return;
+    const float *const x_in = A.x + (size_t)inst * A.s_x;
+    const float *const h0 = A.h0 ? A.h0 + (size_t)inst * A.s_h : nullptr;
+    const float *const c0 = A.c0 ? A.c0 + (size_t)inst * A.s_c : nullptr;
+    float *const hseq = A.hseq ? A.hseq + (size_t)inst * A.s_hseq : nullptr;
+    float *const hT = A.hT + (size_t)inst * A.s_h;
+    float *const cT = A.cT ? A.cT + (size_t)inst * A.s_c : nullptr;
+    unsigned long long *const seq = A.seq + (size_t)inst * A.s_seq;
     const RnnWgRec wg = ((const RnnWgRec *)A.img)[wgi];
     const uint32_t H = A.H, T = A.T, nu = wg.nu, n_in = wg.n_in, C = wg.C, S = wg.S;
     // (the record is the same for every lane: keep what steers branches in scalar registers)
@@ -942,7 +945,10 @@ static uint32_t resident_xcds(const csb_rnn *r) {
 static int resident_instances(const csb_rnn *r, int32_t batch) {
     if (!r->plan.valid) return 1;
     const uint32_t xcds = resident_xcds(r);
-    return xcds > 8 ? 1 : (int)std::min<uint32_t>(8u / xcds, (uint32_t)batch);
+    if (xcds > 8) return 1;
+    // a model of at most half an XCD's workgroups: several instances on each XCD
+    const uint32_t share = xcds == 1 ? std::max<uint32_t>(1u, (uint32_t)kRnnWgsPerXcd / (uint32_t)std::max(1, r->plan.n_wgs)) : 1u;
+    return (int)std::min<uint32_t>(8u / xcds * share, (uint32_t)batch);
 }
 
 static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
@@ -1036,8 +1042,12 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     A.per_xcd = ((uint32_t)r->plan.n_wgs + xcds - 1) / xcds;
     A.n_wgs = (uint32_t)r->plan.n_wgs;
     A.xcd_step = 8u / xcds;                       // the XCDs in use lie this far apart
-    if (n_inst < 1 || (uint32_t)n_inst > A.xcd_step) { set_error("csb_rnn_forward: more instances than XCD groups"); return CSB_EINVAL; }
     A.n_inst = (uint32_t)n_inst;
+    A.share = ((uint32_t)n_inst + A.xcd_step - 1) / A.xcd_step;
+    if (n_inst < 1 || (A.share > 1 && (xcds > 1 || A.share * A.per_xcd > (uint32_t)kRnnWgsPerXcd))) {
+        set_error("csb_rnn_forward: more instances than the XCDs hold");
+        return CSB_EINVAL;
+    }
     A.s_x = s_x; A.s_h = s_h; A.s_c = s_c; A.s_hseq = s_hseq; A.s_seq = words_inst;
     A.poll_delay = r->plan.n_wgs > 1 ? 8u : 0u;   // fewer polls in flight while h_t cannot have arrived yet
     if (const char *e = getenv("CSB_RNN_POLL_DELAY")) A.poll_delay = (uint32_t)std::max(0, atoi(e));
@@ -1047,7 +1057,7 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     auto go = [&](auto kern) -> hipError_t {
         hipError_t e = ensure_dynamic_lds((const void *)kern, lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3(A.per_xcd * 8u), dim3(kRnnThreads), lds, st, A);
+        hipLaunchKernelGGL(kern, dim3(A.per_xcd * A.share * 8u), dim3(kRnnThreads), lds, st, A);
         return hipGetLastError();
     };
     hipError_t e;

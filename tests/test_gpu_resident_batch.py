@@ -82,7 +82,9 @@ def check(got, want, what):
 
 CASES = [  # kind, L, I, H, proj, block, rate, T, B
     ("lstm", 2, 20, 64, 0, 16, 3.0, 7, 2),
-    ("lstm", 1, 33, 100, 0, 4, 2.0, 12, 9),          # 8 instances, then a round of one
+    ("lstm", 1, 33, 100, 0, 4, 2.0, 12, 9),
+    ("lstm", 1, 10, 24, 0, 4, 2.0, 6, 250),          # a one-workgroup model: many instances per XCD, two rounds
+    ("gru", 2, 33, 160, 0, 8, 2.0, 5, 40),
     ("gru", 2, 16, 48, 0, 8, 3.0, 9, 5),
     ("gru", 3, 12, 40, 0, 8, 2.0, 1, 19),
     ("ligru", 2, 24, 64, 0, 16, 4.0, 10, 8),
