@@ -232,6 +232,7 @@ def main():
         out["hbm_stream_read"] = sr
         out["pct_of_measured_stream_read"] = round(100.0 * gbps / sr["gbps"], 4)
         out["rnn_configs"] = rnn_configs_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, stream_read, args.workload)
+        out["resident_batches"] = resident_batches_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
         out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix, sr["gbps"], sr["image_sized_cold"]["us"])
         out["batched"] = batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
         out["projection"] = projection_leg(torch, np, sr["gbps"], not args.no_cpu)
@@ -304,6 +305,48 @@ def rnn_configs_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, stream_read, headl
         res[name] = entry
     res["note"] = ("at these sizes a mat-vec launch is a fixed chain of dependent phases (about 6.5 us of kernel time "
                    "whatever the matrix holds): the resident kernel exists because of that")
+    return res
+
+
+def resident_batches_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
+    """Batches of the batch-1 workloads: the sequences of a batch are independent, so a model that
+    leaves XCDs free runs them as instances of the resident kernel side by side.  Per workload and
+    batch: the path csb_rnn_forward picks by itself, and each of the two paths when named."""
+    import os
+    res = {}
+    old = os.environ.get("CSB_RNN_BATCH_PATH")
+    try:
+        for name in ("cfg1", "cfg2", "cfg3"):
+            cfg = csb_inputs.CONFIGS[name]
+            wl = csb_inputs.make_rnn(cfg)
+            Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+            rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, [torch.from_numpy(b).cuda() for b in wl.bias])
+            rnn.upload()
+            for w in Ws:
+                w.upload()
+            entry = {"workgroups_per_instance": rnn.stats()["n_workgroups"], "T": cfg.T}
+            for B in (8, 64):
+                xd = torch.from_numpy(np.random.default_rng(B).uniform(-1, 1, (cfg.T, B, cfg.input)).astype(np.float32)).cuda()
+                row = {}
+                for path in ("resident", "batched", None):
+                    if path is None:
+                        os.environ.pop("CSB_RNN_BATCH_PATH", None)
+                    else:
+                        os.environ["CSB_RNN_BATCH_PATH"] = path
+                    for _ in range(3):
+                        rnn.forward(xd, want_hseq=True)
+                    n = 10
+                    ms = time_region(lambda: rnn.forward(xd, want_hseq=True), n, torch) / n
+                    row[path or "picked"] = {"ms_per_batch": round(ms, 4), "us_per_timestep": round(ms * 1e3 / cfg.T, 3),
+                                             "sequences_per_s": round(B / (ms * 1e-3))}
+                entry[f"batch{B}"] = row
+            res[name] = entry
+            del rnn
+    finally:
+        if old is None:
+            os.environ.pop("CSB_RNN_BATCH_PATH", None)
+        else:
+            os.environ["CSB_RNN_BATCH_PATH"] = old
     return res
 
 

@@ -315,19 +315,26 @@ int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
  * the model does not fit on chip (more than 8 layers, more than 224 workgroups' worth of weights, a layer input
  * wider than 2048, or a stage whose inputs together are wider than 3072).  After csb_rnn_upload (d_buf device, caller-owned,
  * 256-byte aligned, >= csb_rnn_device_bytes, valid while the handle is used) csb_rnn_forward
- * with batch 1 runs all timesteps of all layers in ONE kernel launch; without it, or for
- * batch > 1, it launches CSB products step by step and needs every W[l] uploaded: stacked
+ * with batch 1 runs all timesteps of all layers in ONE kernel launch.  A batch can run there
+ * too: its sequences are independent, so a model that leaves XCDs free runs them as instances
+ * of itself side by side (8 / XCDs-per-instance of them per launch; a model of at most half
+ * an XCD several per XCD), the batch in rounds of that many, with x, the states and the
+ * outputs regrouped per sequence in the workspace.  Without the resident layout
+ * csb_rnn_forward launches CSB products step by step and needs every W[l] uploaded: stacked
  * layers run by diagonals (layer l at step t with l + t constant are independent and share a
  * launch); at batch 1 nothing else is launched -- the gates of a step are computed by the
- * products that consume its output -- and at batch > 1 one element-wise kernel follows each
- * product launch.
+ * products that consume its output -- and at batch > 1 (the products on the matrix cores) one
+ * element-wise kernel follows each product launch.  With both uploaded, batch 1 takes the
+ * resident kernel and a larger batch whichever an estimate of the time per step favours
+ * (rounds of the resident kernel against the batched products' launches per diagonal).
  * The resident kernel's workgroups wait for each other's h_t: they must all be on the GPU at
  * once, so nothing else should occupy the device while it runs.  The workgroups are placed on
  * as few of the 8 XCDs as hold them (at most 28 per XCD, one per CU).
  * Tuning knobs, read from the environment (for experiments; the defaults are the measured
  * best): CSB_RNN_S = slots per lane of the resident layout (multiple of 4; read by
  * csb_rnn_create*), CSB_RNN_XCDS = use at least this many XCDs, CSB_RNN_POLL_DELAY = sleeps
- * before the first poll of a step (both read by csb_rnn_forward).
+ * before the first poll of a step, CSB_RNN_BATCH_PATH = "resident" or "batched": the path of a
+ * batch when both are uploaded (all three read by csb_rnn_forward).
  */
 typedef struct {
     int32_t resident;          /* 1 if a resident layout exists                            */
@@ -352,7 +359,7 @@ size_t csb_rnn_workspace_bytes(const csb_rnn *r, int32_t batch, int32_t T);
  *   d_ws   csb_rnn_workspace_bytes(r, batch, T) bytes
  * T = 0 copies h0/c0 to hT/cT.  The time loop runs on the device side of `stream`
  * without host synchronisation.  Errors: NULL / batch <= 0 / T < 0 -> CSB_EINVAL;
- * a W[l] not uploaded -> CSB_ESTATE.
+ * neither the resident layout nor every W[l] uploaded -> CSB_ESTATE.
  * Not for replay from a captured HIP graph: the resident kernel (and csb_spmv / csb_spmm on a
  * matrix planned with shared row tiles) tell this call's exchange words from stale ones by a
  * launch tag that the HOST draws per call; a replay would reuse the tag.  Calls on one handle
