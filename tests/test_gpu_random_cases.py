@@ -118,7 +118,8 @@ def test_random_recurrent_models(group):
                 mats = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
                 rnn = CsbRnn(cell, I, H, mats, bias)
             rseq, rhT, rcT = oracle.rnn_forward(cell, [m.A for m in wl.W], wl.bias, wl.x, I, H, h0=h0, c0=c0)
-        resident = B == 1 and want_resident and rnn.stats()["resident"] == 1
+        # (a batch on the resident kernel in every second case that asks for the resident layout)
+        resident = (B == 1 or tr % 2 == 0) and want_resident and rnn.stats()["resident"] == 1
         say(f"[random models] case {tr}: {kind} L={L} I={I} H={H} proj={proj if kind == 'lstmp' else 0} block={block} "
             f"rate={rate} T={T} B={B} resident={resident} state={with_state}")
         if resident:
