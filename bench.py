@@ -340,6 +340,21 @@ def resident_batches_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
                     row[path or "picked"] = {"ms_per_batch": round(ms, 4), "us_per_timestep": round(ms * 1e3 / cfg.T, 3),
                                              "sequences_per_s": round(B / (ms * 1e-3))}
                 entry[f"batch{B}"] = row
+            # the resident layout planned for the batch (csb_rnn_plan_resident): smaller instances, fewer rounds
+            os.environ["CSB_RNN_BATCH_PATH"] = "resident"
+            for B in (8, 64):
+                rnn.plan_resident(B)
+                rnn.upload()
+                st = rnn.stats()
+                xd = torch.from_numpy(np.random.default_rng(B).uniform(-1, 1, (cfg.T, B, cfg.input)).astype(np.float32)).cuda()
+                for _ in range(3):
+                    rnn.forward(xd, want_hseq=True)
+                n = 10
+                ms = time_region(lambda: rnn.forward(xd, want_hseq=True), n, torch) / n
+                entry[f"batch{B}"]["resident_planned_for_batch"] = {
+                    "workgroups_per_instance": st["n_workgroups"], "slots_per_lane": st["slots_per_lane"],
+                    "ms_per_batch": round(ms, 4), "us_per_timestep": round(ms * 1e3 / cfg.T, 3),
+                    "sequences_per_s": round(B / (ms * 1e-3))}
             res[name] = entry
             del rnn
     finally:

@@ -346,6 +346,15 @@ typedef struct {
 } csb_rnn_plan_stats;
 size_t csb_rnn_device_bytes(const csb_rnn *r);
 int csb_rnn_upload(csb_rnn *r, void *d_buf, size_t bytes, void *stream);
+/* Lay the resident kernel out for batches of `batch` sequences (host only; the equal-work
+ * split of Sec. 5.2 with another slice length).  csb_rnn_create* lays it out for ONE
+ * sequence: few slots per lane, the shortest step.  More slots per lane make an instance
+ * smaller, so that more of them run side by side and the batch takes fewer rounds, at a longer
+ * step: this call takes the slot count with the smallest estimated time for `batch` (batch 1
+ * gives the layout of create back).  The handle is no longer uploaded afterwards:
+ * csb_rnn_device_bytes and csb_rnn_upload again (a launch still in flight keeps reading the old
+ * image).  Errors: NULL / batch <= 0 -> CSB_EINVAL; no resident layout -> CSB_EUNSUPPORTED. */
+int csb_rnn_plan_resident(csb_rnn *r, int32_t batch);
 int csb_rnn_stats(const csb_rnn *r, csb_rnn_plan_stats *out);
 
 size_t csb_rnn_workspace_bytes(const csb_rnn *r, int32_t batch, int32_t T);

@@ -24,7 +24,7 @@ SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_set_
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
            "csb_project_workspace_bytes", "csb_project", "csb_rnn_create_lstmp", "csb_rnn_create_gru_rb",
-           "csb_rnn_create", "csb_rnn_device_bytes", "csb_rnn_upload", "csb_rnn_stats",
+           "csb_rnn_create", "csb_rnn_device_bytes", "csb_rnn_upload", "csb_rnn_plan_resident", "csb_rnn_stats",
            "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
 
 
@@ -113,6 +113,7 @@ def load_library():
     L.csb_rnn_device_bytes.argtypes = [C.c_void_p]
     L.csb_rnn_device_bytes.restype = C.c_size_t
     L.csb_rnn_upload.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.csb_rnn_plan_resident.argtypes = [C.c_void_p, C.c_int32]
     L.csb_rnn_stats.argtypes = [C.c_void_p, C.POINTER(csb_rnn_plan_stats)]
     L.csb_rnn_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     L.csb_rnn_workspace_bytes.restype = C.c_size_t
@@ -348,8 +349,15 @@ class CsbRnn:
     def device_bytes(self) -> int:
         return int(lib().csb_rnn_device_bytes(self._h))
 
+    def plan_resident(self, batch: int):
+        """Lay the resident kernel out for batches of this size (1: one sequence, as created);
+        upload() afterwards."""
+        _check(lib().csb_rnn_plan_resident(self._h, batch))
+        self._d_img = None
+        return self
+
     def upload(self, device="cuda", stream=None):
-        """Upload the resident (batch-1) layout; without it forward() streams the matrices."""
+        """Upload the resident layout; without it forward() streams the matrices."""
         import torch
         n = self.device_bytes()
         if n == 0:

@@ -84,6 +84,7 @@ struct RnnPlan {
     size_t cmax = 0;           // largest C of any stage (LDS sizing)
     double slot_fill = 0;      // non-zeros / (1024 * S * workgroups): the useful share of issued multiply-adds
     double lanes_max_over_mean = 0;
+    size_t total_nnz = 0;      // surviving weights of the whole model
     long lds_conflicts = 0;    // words that share an LDS bank with another word of the same 32-lane gather (all workgroups)
 };
 
@@ -195,7 +196,9 @@ static void append_rows(const csb_matrix *m, int row0, int nrows, int dst_row0, 
         }
 }
 
-static int build_resident_plan(csb_rnn *r) {
+// `slots` > 0: that many slots per lane in every stage; 0: per stage whatever the step-time
+// model below favours for one sequence.
+static int build_resident_plan(csb_rnn *r, int slots = 0) {
     RnnPlan &pl = r->plan;
     pl = RnnPlan{};
     const bool lstmp = r->cell == CSB_CELL_LSTMP, gru_rb = r->cell == CSB_CELL_GRU_RB;
@@ -265,6 +268,7 @@ static int build_resident_plan(csb_rnn *r) {
     constexpr int kBins = kRnnThreads / 16;        // 16-lane rows per workgroup
     int s_lo = 4, s_hi = kRnnSlotsMax;
     if (const char *e = getenv("CSB_RNN_S")) s_lo = s_hi = std::max(4, std::min(kRnnSlotsMax, atoi(e) / 4 * 4));
+    if (slots > 0) s_lo = s_hi = std::max(4, std::min(kRnnSlotsMax, slots / 4 * 4));
     int total_wgs = 0;
     for (int l = 0; l < L; ++l) {
         LayerTmp &t = lt[l];
@@ -489,6 +493,7 @@ static int build_resident_plan(csb_rnn *r) {
     std::memcpy(pl.image.data() + hdr, body.data(), body.size());
     pl.n_wgs = (int)wgs.size();
     pl.smax = smax;
+    pl.total_nnz = total_nnz;
     pl.slot_fill = slots_total ? (double)total_nnz / (double)slots_total : 0.0;
     pl.lanes_max_over_mean = lanes_sum > 0 ? lanes_max / (lanes_sum / (double)wgs.size()) : 0.0;
     pl.lds_conflicts = conflicts_total;
@@ -1135,21 +1140,30 @@ static int forward_resident_batch(const csb_rnn *r, const float *d_x, const floa
 }
 
 // Rough cost of one time step of a batch, in microseconds, on the two paths that can run it
-// (fitted to measurements on MI355X): the resident kernel takes about a microsecond per step
-// and XCD it spans, twice that for the cells with two dependent products per step, and runs
-// the batch in rounds of as many sequences as instances fit; the batched MFMA path pays its
-// launches per diagonal whatever the batch.
+// (fitted to measurements on MI355X).  Resident kernel: the planner's step model (60 clocks per
+// slot, 1700 for the exchange of h_t, 6 per workgroup; the forms above 32 slots spill and cost
+// half as much again) times 1.3, plus 0.12 us per further XCD an instance spans, twice for the
+// cells with two dependent products per step; the batch runs in rounds of as many sequences
+// as instances fit.  Batched MFMA path: its launches per diagonal, plus the products at about
+// 12 TFLOP/s.
+static double resident_batch_us(const csb_rnn *r, int32_t batch) {
+    const bool two = r->cell == CSB_CELL_LSTMP || r->cell == CSB_CELL_GRU_RB;
+    const int R = resident_instances(r, batch);
+    const double rounds = (double)((batch + R - 1) / R);
+    const int S = r->plan.smax;
+    const double clocks = (60.0 * S + 1700.0 + 6.0 * r->plan.n_wgs) * (S > 32 ? 1.5 : 1.0);
+    return rounds * (clocks / 2400.0 * 1.3 + 0.12 * (resident_xcds(r) - 1)) * (two ? 2.0 : 1.0);
+}
+static double batched_us(const csb_rnn *r, int32_t batch) {
+    const bool two = r->cell == CSB_CELL_LSTMP || r->cell == CSB_CELL_GRU_RB;
+    return (10.0 + 4.0 * r->n_layers) * (two ? 1.25 : 1.0) + 2.0 * (double)r->plan.total_nnz * batch / 12e6;
+}
 static bool batch_prefers_resident(const csb_rnn *r, int32_t batch) {
     if (const char *e = getenv("CSB_RNN_BATCH_PATH")) {
         if (!strcmp(e, "resident")) return true;
         if (!strcmp(e, "batched")) return false;
     }
-    const bool two = r->cell == CSB_CELL_LSTMP || r->cell == CSB_CELL_GRU_RB;
-    const int R = resident_instances(r, batch);
-    const double rounds = (double)((batch + R - 1) / R);
-    const double resident_us = rounds * (0.9 + 0.3 * resident_xcds(r)) * (two ? 2.2 : 1.0);
-    const double batched_us = (10.0 + 4.0 * r->n_layers) * (two ? 1.25 : 1.0);
-    return resident_us * 1.1 < batched_us;
+    return resident_batch_us(r, batch) * 1.1 < batched_us(r, batch);
 }
 
 }  // namespace csb
@@ -1300,6 +1314,35 @@ extern "C" int csb_rnn_upload(csb_rnn *r, void *d_buf, size_t bytes, void *strea
     r->d_img = d_buf;
     r->uploaded = true;
     return CSB_OK;
+}
+
+extern "C" int csb_rnn_plan_resident(csb_rnn *r, int32_t batch) {
+    using namespace csb;
+    if (!r || batch <= 0) { set_error("csb_rnn_plan_resident: NULL handle or batch <= 0"); return CSB_EINVAL; }
+    if (!r->plan.valid) { set_error("csb_rnn_plan_resident: this model has no resident layout"); return CSB_EUNSUPPORTED; }
+    r->uploaded = false;
+    r->d_img = nullptr;
+    r->ws_seen = nullptr;
+    try {
+        // More slots per lane make an instance smaller (more of them per launch, fewer rounds)
+        // and its step longer: take the slot count with the smallest estimate for this batch.
+        int best = 0;
+        double best_us = 1e300;
+        if (batch > 1)
+            for (int S : {0, 8, 12, 16, 24, 32}) {
+                if (build_resident_plan(r, S) != CSB_OK) continue;
+                const double us = resident_batch_us(r, batch);
+                if (us < best_us) { best_us = us; best = S; }
+            }
+        int rc = build_resident_plan(r, best);
+        if (rc != CSB_OK) rc = build_resident_plan(r, 0);       // (the default layout existed before)
+        if (rc != CSB_OK) { set_error("csb_rnn_plan_resident: the layout could not be rebuilt"); return rc; }
+        return CSB_OK;
+    } catch (const std::bad_alloc &) {
+        r->plan = RnnPlan{};
+        set_error("csb_rnn_plan_resident: out of host memory");
+        return CSB_ENOMEM;
+    }
 }
 
 extern "C" int csb_rnn_stats(const csb_rnn *r, csb_rnn_plan_stats *out) {

@@ -163,3 +163,41 @@ def test_headline_model_batch_of_eight():
     got = rnn.forward(dev(wl.x))
     torch.cuda.synchronize()
     check(got, oracle.rnn_forward(cfg.cell, [m.A for m in wl.W], wl.bias, wl.x, cfg.input, cfg.hidden), "cfg2 x 8")
+
+
+PLANNED = [  # kind, L, I, H, proj, block, rate, T, B
+    ("lstm", 1, 153, 512, 0, 32, 10.0, 9, 40),        # the headline model's shape
+    ("gru", 2, 64, 256, 0, 16, 8.0, 7, 64),
+    ("ligru", 2, 39, 512, 0, 32, 7.1, 5, 24),
+    ("gru_rb", 2, 24, 128, 0, 8, 4.0, 6, 33),
+    ("lstmp", 2, 40, 256, 96, 16, 6.0, 6, 20),
+    ("lstm", 2, 20, 64, 0, 16, 3.0, 7, 300),
+]
+
+
+@pytest.mark.parametrize("kind,L,I,H,proj,block,rate,T,B", PLANNED)
+def test_layout_planned_for_the_batch(kind, L, I, H, proj, block, rate, T, B):
+    """csb_rnn_plan_resident(batch): another slot count per lane, smaller instances, more of them
+    per launch -- the same results to the same bar, for one sequence on that layout too."""
+    wl, rnn, mats, ref = make(kind, L, I, H, proj, block, rate, T, B, seed=500 + L + I, sigma=0.05 if H >= 256 else None)
+    before = rnn.stats()
+    rnn.plan_resident(B)
+    after = rnn.stats()
+    say(f"[resident batch] planned for {B}: {kind} L={L} H={H}: {before['n_workgroups']} workgroups x {before['slots_per_lane']} slots"
+        f" -> {after['n_workgroups']} x {after['slots_per_lane']}")
+    rnn.upload()
+    h0, c0 = states(kind, L, B, H, proj, 11)
+    got = rnn.forward(dev(wl.x), dev(h0), dev(c0))
+    torch.cuda.synchronize()
+    check(got, ref(wl.x, h0, c0), f"{kind} planned for {B}")
+    one = rnn.forward(dev(wl.x[:, 3:4]), dev(h0[:, 3:4]), dev(None if c0 is None else c0[:, 3:4]))
+    torch.cuda.synchronize()
+    assert torch.equal(one[0][:, 0], got[0][:, 3]) and torch.equal(one[1][:, 0], got[1][:, 3])
+    rnn.plan_resident(1)                              # and back: the handle must be uploaded again
+    with pytest.raises(P.CsbError):
+        rnn.forward(dev(wl.x))
+    rnn.upload()
+    assert rnn.stats() == before
+    got = rnn.forward(dev(wl.x), dev(h0), dev(c0))
+    torch.cuda.synchronize()
+    check(got, ref(wl.x, h0, c0), f"{kind} back on the one-sequence layout")

@@ -276,3 +276,29 @@ def test_resident_layout_limits():
         wl = csb_inputs.make_rnn(csb_inputs.RnnConfig("t", csb_inputs.LSTM, L, 6, 8, 4, 2.0, "binomial", 0.1, 1, 1, 0))
         rnn = CsbRnn(CELL_LSTM, 6, 8, [CsbMatrix(m.A, 4, 4) for m in wl.W], None)
         assert rnn.stats()["resident"] == want
+
+
+def test_resident_layout_for_batches():
+    """csb_rnn_plan_resident is host work: for a batch it trades slots per lane for smaller
+    instances (the headline model: 20 workgroups at 8 slots fill an XCD alone; laid out for a
+    batch of 64 several instances share one), batch 1 gives the layout of create back, and a
+    model without a resident layout is refused."""
+    from paper_2005_05758_amd import CsbRnn, CsbError, CELL_LSTM
+    cfg = csb_inputs.CONFIGS["cfg2"]
+    wl = csb_inputs.make_rnn(cfg, T=1)
+    rnn = CsbRnn(CELL_LSTM, cfg.input, cfg.hidden, [CsbMatrix(m.A, m.br, m.bc) for m in wl.W], None)
+    one = rnn.stats()
+    bytes_one = rnn.device_bytes()
+    rnn.plan_resident(64)
+    many = rnn.stats()
+    assert many["resident"] == 1 and many["slots_per_lane"] > one["slots_per_lane"]
+    assert many["n_workgroups"] <= 14 < one["n_workgroups"]
+    assert rnn.device_bytes() > 0
+    rnn.plan_resident(1)
+    assert rnn.stats() == one and rnn.device_bytes() == bytes_one
+    with pytest.raises(CsbError):
+        rnn.plan_resident(0)
+    wl = csb_inputs.make_rnn(csb_inputs.RnnConfig("t", csb_inputs.LSTM, 1, 2100, 1000, 50, 40.0, "binomial", 0.05, 1, 1, 0))
+    big = CsbRnn(CELL_LSTM, 2100, 1000, [CsbMatrix(wl.W[0].A, 50, 50)], None)
+    with pytest.raises(CsbError):
+        big.plan_resident(8)
