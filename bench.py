@@ -316,9 +316,9 @@ def resident_batches_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
     res = {}
     old = os.environ.get("CSB_RNN_BATCH_PATH")
     try:
-        for name in ("cfg1", "cfg2", "cfg3"):
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4"):
             cfg = csb_inputs.CONFIGS[name]
-            wl = csb_inputs.make_rnn(cfg)
+            wl = csb_inputs.make_rnn(cfg, batch=1)
             Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
             rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, [torch.from_numpy(b).cuda() for b in wl.bias])
             rnn.upload()

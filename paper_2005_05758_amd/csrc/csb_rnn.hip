@@ -1141,7 +1141,7 @@ static int forward_resident_batch(const csb_rnn *r, const float *d_x, const floa
 
 // Rough cost of one time step of a batch, in microseconds, on the two paths that can run it
 // (fitted to measurements on MI355X).  Resident kernel: the planner's step model (60 clocks per
-// slot, 1700 for the exchange of h_t, 6 per workgroup; the forms above 32 slots spill and cost
+// slot, 1700 for the exchange of h_t between workgroups, 6 per workgroup; the forms above 32 slots spill and cost
 // half as much again) times 1.3, plus 0.12 us per further XCD an instance spans, twice for the
 // cells with two dependent products per step; the batch runs in rounds of as many sequences
 // as instances fit.  Batched MFMA path: its launches per diagonal, plus the products at about
@@ -1151,7 +1151,7 @@ static double resident_batch_us(const csb_rnn *r, int32_t batch) {
     const int R = resident_instances(r, batch);
     const double rounds = (double)((batch + R - 1) / R);
     const int S = r->plan.smax;
-    const double clocks = (60.0 * S + 1700.0 + 6.0 * r->plan.n_wgs) * (S > 32 ? 1.5 : 1.0);
+    const double clocks = (60.0 * S + (r->plan.n_wgs > 1 ? 1700.0 : 0.0) + 6.0 * r->plan.n_wgs) * (S > 32 ? 1.5 : 1.0);
     return rounds * (clocks / 2400.0 * 1.3 + 0.12 * (resident_xcds(r) - 1)) * (two ? 2.0 : 1.0);
 }
 static double batched_us(const csb_rnn *r, int32_t batch) {
