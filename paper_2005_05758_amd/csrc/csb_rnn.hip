@@ -1329,7 +1329,7 @@ extern "C" int csb_rnn_plan_resident(csb_rnn *r, int32_t batch) {
         int best = 0;
         double best_us = 1e300;
         if (batch > 1)
-            for (int S : {0, 8, 12, 16, 24, 32}) {
+            for (int S : {8, 12, 16, 24, 32}) {       // (none fits: the layout of create, 0 below)
                 if (build_resident_plan(r, S) != CSB_OK) continue;
                 const double us = resident_batch_us(r, batch);
                 if (us < best_us) { best_us = us; best = S; }
