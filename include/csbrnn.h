@@ -318,8 +318,7 @@ int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
  * with batch 1 runs all timesteps of all layers in ONE kernel launch.  A batch can run there
  * too: its sequences are independent, so a model that leaves XCDs free runs them as instances
  * of itself side by side (8 / XCDs-per-instance of them per launch; a model of at most half
- * an XCD several per XCD), the batch in rounds of that many, with x, the states and the
- * outputs regrouped per sequence in the workspace.  Without the resident layout
+ * an XCD several per XCD), the batch in rounds of that many.  Without the resident layout
  * csb_rnn_forward launches CSB products step by step and needs every W[l] uploaded: stacked
  * layers run by diagonals (layer l at step t with l + t constant are independent and share a
  * launch); at batch 1 nothing else is launched -- the gates of a step are computed by the

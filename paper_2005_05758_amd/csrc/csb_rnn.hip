@@ -542,6 +542,9 @@ struct RnnArgs {
     // and exchange words, each this many elements behind the instance before.
     uint32_t n_inst, share;
     size_t s_x, s_h, s_c, s_hseq, s_seq;
+    // x, the states and the outputs of a batch stay where the caller has them, [.][batch][width]:
+    // consecutive steps (or layers) of one sequence lie `nb` rows apart (1 for a single sequence)
+    uint32_t nb;
     unsigned long long *dbg;            // optional: per-phase shader clocks summed over the steps (workgroup 0)
 };
 
@@ -599,6 +602,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     unsigned long long *const seq = A.seq + (size_t)inst * A.s_seq;
     const RnnWgRec wg = ((const RnnWgRec *)A.img)[wgi];
     const uint32_t H = A.H, T = A.T, nu = wg.nu, n_in = wg.n_in, C = wg.C, S = wg.S;
+    const size_t x_step = (size_t)A.I * A.nb, hseq_step = (size_t)wg.width * A.nb;
     // (the record is the same for every lane: keep what steers branches in scalar registers)
     const uint32_t kword = __builtin_amdgcn_readfirstlane(wg.kind);
     const uint32_t kind = kword & 0xffu, real = (kword >> 8) & 0xffu, flags = kword >> 16;
@@ -656,8 +660,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     // where this owner's unit sits in the staged vector's recurrent part (if that part is this stage's own or its state)
     const uint32_t zown = (owner && n_in + unit < C) ? ((const uint16_t *)(A.img + wg.off_zpos))[n_in + unit] : C;
     if (owner) {
-        if (c0 && lstm) c_state = c0[(size_t)real * H + unit];
-        if (h0 && is_state) h_state = h0[(size_t)real * wg.width + unit];
+        if (c0 && lstm) c_state = c0[(size_t)real * H * A.nb + unit];
+        if (h0 && is_state) h_state = h0[(size_t)real * wg.width * A.nb + unit];
     }
     if (tid == 0) z[C] = 0.0f;
     // rows without survivors have no lane: their entry keeps the activation of the bare bias
@@ -700,7 +704,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         zp[rep] = zpos[e];
         const bool rec = e >= n_in && e < rec_end, third = e >= rec_end;
         const uint32_t us = third ? e - rec_end : (rec ? e - n_in : e);
-        if (rec) z[zp[rep]] = h0 ? h0[(size_t)real * wg.rec_width + us] : 0.0f;
+        if (rec) z[zp[rep]] = h0 ? h0[(size_t)real * wg.rec_width * A.nb + us] : 0.0f;
         if (rec ? (own_rec && us - wg.u0 < nu) : (!third && from_x)) continue;
         const RnnWgRec *q = (const RnnWgRec *)A.img + unit_wg[(size_t)(third ? wg.aux : (rec ? wg.rec : wg.below)) + us];
         const uint32_t back = rec ? 1u : 0u;
@@ -746,8 +750,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
             if (xl0) z[zp[0]] = xnext0;
             if (xl1) z[zp[1]] = xnext1;
             if (t + 1 < T) {
-                if (xl0) xnext0 = x_in[(size_t)(t + 1) * A.I + zt];
-                if (xl1) xnext1 = x_in[(size_t)(t + 1) * A.I + zt + kRnnThreads];
+                if (xl0) xnext0 = x_in[(size_t)(t + 1) * x_step + zt];
+                if (xl1) xnext1 = x_in[(size_t)(t + 1) * x_step + zt + kRnnThreads];
             }
         }
         lds_barrier();
@@ -817,7 +821,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
             if (own_rec) z[zown] = hn;               // next step's input, read only after the next barrier
             const unsigned long long pk = ((unsigned long long)tag_now << 32) | (unsigned long long)__float_as_uint(hn);
             __hip_atomic_store(pub + (size_t)t * nu, pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (hseq && (flags & kStageIsSeq)) hseq[(size_t)t * wg.width + unit] = hn;
+            if (hseq && (flags & kStageIsSeq)) hseq[(size_t)t * hseq_step + unit] = hn;
         }
         if (dbg) { c1_ = __builtin_readcyclecounter(); ph3 += c1_ - c0_; }
     }
@@ -825,8 +829,8 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     if (kPhaseClocks && A.dbg && blockIdx.x == 0 && (tid & 63u) == 0) A.dbg[8 + (tid >> 6)] = wave_arrive;
     if (kPhaseClocks && A.dbg && blockIdx.x == 0 && tid == 512) A.dbg[6] = delay;
     if (owner) {
-        if (is_state) hT[(size_t)real * wg.width + unit] = h_state;
-        if (cT && lstm) cT[(size_t)real * H + unit] = c_state;
+        if (is_state) hT[(size_t)real * wg.width * A.nb + unit] = h_state;
+        if (cT && lstm) cT[(size_t)real * H * A.nb + unit] = c_state;
     }
 }
 
@@ -938,7 +942,6 @@ static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 struct RnnWs {
     size_t off_a, off_a2, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, off_m, off_fa, off_fs, rows_out, part_stride, total;
-    size_t off_rx, off_rseq, off_rh, off_rc;      // a batch on the resident kernel: per-sequence copies
 };
 
 // XCDs one instance of the resident kernel occupies, and how many instances fit side by side
@@ -981,17 +984,10 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     w.off_biasptr = off; off = align256(off + (size_t)r->n_layers * sizeof(void *));
     // exchange words of the resident kernel: one per unit of every stage and step
     // (a batch may run as several instances of the resident kernel side by side, each with
-    // exchange words of its own and with its sequence, states and outputs stored on their own)
+    // exchange words of its own)
     const size_t seq_units = r->plan.valid ? r->plan.total_units : 0;
     const size_t inst = batch > 1 ? (size_t)resident_instances(r, batch) : 1;
     w.off_seq = off; off = align256(off + (size_t)std::max(T, 1) * seq_units * 8 * inst);
-    if (batch > 1 && r->plan.valid) {
-        const size_t B = (size_t)batch, Tn = (size_t)std::max(T, 1);
-        w.off_rx = off; off = align256(off + B * Tn * r->input * sizeof(float));
-        w.off_rseq = off; off = align256(off + B * Tn * HS * sizeof(float));
-        w.off_rh = off; off = align256(off + 2 * B * r->n_layers * HS * sizeof(float));      // h0, hT
-        w.off_rc = off; off = align256(off + 2 * B * r->n_layers * r->hidden * sizeof(float));  // c0, cT
-    }
     if (batch > 1) {
         w.off_hint = off; off = align256(off + (size_t)r->n_layers * batch * HS * sizeof(float));
         w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
@@ -1012,17 +1008,16 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
 // one place further on), their x / states / outputs `s_*` elements apart.
 static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0, float *d_hseq,
                             float *d_hT, float *d_cT, int32_t T, void *d_ws, const RnnWs &wl, hipStream_t st, int n_inst = 1,
-                            size_t s_x = 0, size_t s_h = 0, size_t s_c = 0, size_t s_hseq = 0, size_t region_words = 0) {
+                            size_t s_x = 0, size_t s_h = 0, size_t s_c = 0, size_t s_hseq = 0, size_t region_words = 0, uint32_t nb = 1) {
     const int L = r->n_layers, H = r->hidden;
     unsigned long long *seq = (unsigned long long *)((uint8_t *)d_ws + wl.off_seq);
     const size_t words_inst = r->plan.total_units * (size_t)T, words = words_inst * (size_t)n_inst;
     // Unique tags for this call's T steps; a workspace seen for the first time (or a new tag
-    // generation) is cleared so that no stale word can carry a tag of this call.  A single
-    // sequence writes nothing but these words into the workspace, so there a region that was
-    // cleared once stays good while it does not grow; a batch keeps float buffers behind the
-    // words, at places that move with T, so there any other size is cleared again.
+    // generation) is cleared so that no stale word can carry a tag of this call.  The resident
+    // kernel writes nothing but these words into the workspace, so a region that was cleared
+    // once stays good while it does not grow (all rounds of a batch use the same region).
     const size_t region = region_words ? region_words : words;
-    const bool other_size = region_words ? region != r->ws_words : region > r->ws_words;
+    const bool other_size = region > r->ws_words;
     uint32_t gen = 0;
     const uint32_t tag_base = reserve_tags((uint32_t)T, &gen);
     if (r->ws_seen != (const void *)seq || r->ws_gen != gen || other_size) {
@@ -1054,6 +1049,7 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
         return CSB_EINVAL;
     }
     A.s_x = s_x; A.s_h = s_h; A.s_c = s_c; A.s_hseq = s_hseq; A.s_seq = words_inst;
+    A.nb = nb;
     A.poll_delay = r->plan.n_wgs > 1 ? 8u : 0u;   // fewer polls in flight while h_t cannot have arrived yet
     if (const char *e = getenv("CSB_RNN_POLL_DELAY")) A.poll_delay = (uint32_t)std::max(0, atoi(e));
     if (kPhaseClocks && getenv("CSB_RNN_DEBUG")) A.dbg = (unsigned long long *)((uint8_t *)d_ws + wl.total - 512);
@@ -1091,51 +1087,25 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     return CSB_OK;
 }
 
-// dst[b][a][:] = src[a][b][:] for src of shape [A][B][C]
-__global__ void swap_outer_kernel(float *__restrict__ dst, const float *__restrict__ src, size_t A, size_t B, size_t C) {
-    const size_t n = A * B * C;
-    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-        const size_t c = i % C, ab = i / C, b = ab % B, a = ab / B;
-        dst[(b * A + a) * C + c] = src[i];
-    }
-}
-static void swap_outer(float *dst, const float *src, size_t A, size_t B, size_t C, hipStream_t st) {
-    const size_t n = A * B * C;
-    if (!n) return;
-    hipLaunchKernelGGL(swap_outer_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 4096)), dim3(256), 0, st, dst, src, A, B, C);
-}
-
 // A batch on the resident kernel: the sequences are independent, and a model that fills only
-// some of the 8 XCDs leaves room for further instances of itself beside it.  x, the states and
-// the outputs are regrouped per sequence in the workspace; every launch then runs as many
-// sequences as instances fit, each on XCDs of its own.
+// some of the 8 XCDs leaves room for further instances of itself beside it.  Every launch runs
+// as many sequences as instances fit, each on XCDs (or a share of one) of its own; x, the
+// states and the outputs are read and written where the caller has them ([.][batch][width]:
+// sequence b starts b rows in, its steps and layers lie `batch` rows apart).
 static int forward_resident_batch(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0, float *d_hseq,
                                   float *d_hT, float *d_cT, int32_t T, int32_t batch, void *d_ws, hipStream_t st) {
     const RnnWs wl = ws_layout(r, batch, T);
-    const size_t L = (size_t)r->n_layers, H = (size_t)r->hidden, HS = (size_t)r->state_width(), I = (size_t)r->input;
-    const size_t B = (size_t)batch, Tn = (size_t)T;
+    const size_t H = (size_t)r->hidden, HS = (size_t)r->state_width(), I = (size_t)r->input;
     const bool lstm = r->cell == CSB_CELL_LSTM || r->cell == CSB_CELL_LSTMP;
-    float *xs = (float *)((uint8_t *)d_ws + wl.off_rx), *seqs = (float *)((uint8_t *)d_ws + wl.off_rseq);
-    float *h0s = (float *)((uint8_t *)d_ws + wl.off_rh), *hTs = h0s + B * L * HS;
-    float *c0s = (float *)((uint8_t *)d_ws + wl.off_rc), *cTs = c0s + B * L * H;
-    swap_outer(xs, d_x, Tn, B, I, st);                          // [T][B][I] -> [B][T][I]
-    if (d_h0) swap_outer(h0s, d_h0, L, B, HS, st);              // [L][B][HS] -> [B][L][HS]
-    if (d_c0 && lstm) swap_outer(c0s, d_c0, L, B, H, st);
     const int R = resident_instances(r, batch);
     for (int32_t b0 = 0; b0 < batch; b0 += R) {
         const int n = std::min<int32_t>(R, batch - b0);
         const size_t b = (size_t)b0;
-        int rc = forward_resident(r, xs + b * Tn * I, d_h0 ? h0s + b * L * HS : nullptr, (d_c0 && lstm) ? c0s + b * L * H : nullptr,
-                                  d_hseq ? seqs + b * Tn * HS : nullptr, hTs + b * L * HS, (d_cT && lstm) ? cTs + b * L * H : nullptr,
-                                  T, d_ws, wl, st, n, Tn * I, L * HS, L * H, Tn * HS,
-                                  (size_t)R * r->plan.total_units * Tn);
+        int rc = forward_resident(r, d_x + b * I, d_h0 ? d_h0 + b * HS : nullptr, (d_c0 && lstm) ? d_c0 + b * H : nullptr,
+                                  d_hseq ? d_hseq + b * HS : nullptr, d_hT + b * HS, (d_cT && lstm) ? d_cT + b * H : nullptr,
+                                  T, d_ws, wl, st, n, I, HS, H, HS, (size_t)R * r->plan.total_units * (size_t)T, (uint32_t)batch);
         if (rc != CSB_OK) return rc;
     }
-    if (d_hseq) swap_outer(d_hseq, seqs, B, Tn, HS, st);
-    swap_outer(d_hT, hTs, B, L, HS, st);
-    if (d_cT && lstm) swap_outer(d_cT, cTs, B, L, H, st);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
 }
 
