@@ -545,7 +545,9 @@ def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
                                    f"{cfg.rate:g}x, batch {cfg.batch}, T={cfg.T}",
                        "us_per_timestep": round(ms * 1000.0 / cfg.T, 2),
                        "tflops_algorithmic": round(fl_step / (ms * 1e-3 / cfg.T) / 1e12, 3),
-                       "sequences_per_s": round(cfg.batch / (ms * 1e-3), 1)}
+                       "sequences_per_s": round(cfg.batch / (ms * 1e-3), 1),
+                       "note": "the matrix-core path (csb_spmm per diagonal); the same workload as instances of the resident "
+                               "kernel laid out for this batch is timed in resident_batches.cfg4.batch64"}
     return res
 
 
