@@ -227,6 +227,22 @@ int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int
              int32_t batch, void *d_ws, void *stream);
 
 /*
+ * Batched CSB-MVM with bfloat16 operands on the matrix cores (the 16-bit datapath of
+ * Sec. 6.3.1 taken to the batched product): the matrix stores bfloat16 values
+ * (csb_set_value_format(CSB_VAL_BF16) before csb_plan) and the right-hand sides arrive as
+ * bfloat16 bit patterns, d_Xb [cols][ldx] (device, entry (j,k) at d_Xb[j*ldx + k]); the
+ * products are exact in binary32 and are accumulated in binary32 into d_Y [rows][ldy] float.
+ * Y equals A X for the rounded operands to the float32 dot-product bound of csb_spmm.
+ * Errors: NULL / batch <= 0 / a leading dimension below batch -> CSB_EINVAL; matrix not
+ * planned and uploaded, planned for a GRU step, or not storing bfloat16 -> CSB_ESTATE; batch or
+ * ldx not a multiple of 4, d_Xb not 8-byte aligned, block rows too tall for the accumulator
+ * tiles -> CSB_EUNSUPPORTED.  Needs no workspace; runs on `stream` without host
+ * synchronisation.
+ */
+int csb_spmm_bfloat(const csb_matrix *m, const uint16_t *d_Xb, int64_t ldx, float *d_Y, int64_t ldy,
+                  int32_t batch, void *stream);
+
+/*
  * Model of the paper's own schedule, for context next to csb_plan's statistics.  HOST ONLY,
  * no device work, not on any compute path.  The paper's engine (Sec. 4.3) runs K x L blocks
  * per block iteration on K x L PEGroups of P x Q PEs; an a x b partition of a kernel matrix

@@ -283,6 +283,185 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
     spmm_body<NT, TWO, NW, WIDE>(m, X, Y, ldy, batch, blockIdx.x, blockIdx.y);
 }
 
+// ---------------------------------------------------------------------------------------
+// bfloat16 operands (v_mfma_f32_16x16x16_bf16): the kernel values are stored as bfloat16
+// (csb_set_value_format) and the right-hand sides arrive as bfloat16, [cols][ldx] with the
+// batch contiguous; products are exact in binary32 and are accumulated in binary32.  One
+// MFMA takes 16 columns of a block (four times the f32 instruction's) and the gather of X --
+// what bounds the f32 kernel -- moves half the bytes.  Same tiling as the wide f32 form: a
+// lane loads four neighbouring right-hand sides of an input row at once (8 bytes), tile t
+// holds the right-hand sides 4 n + t.
+typedef short bf16x4 __attribute__((ext_vector_type(4)));
+
+template <int KS>
+struct OperandsBf {
+    uint2 a[KS];          // four consecutive columns of this lane's row
+    uint2 b[KS][4];       // per tile: the same four columns of its right-hand side
+};
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void spmm_bf16_kernel(const DevMat m, const uint16_t *__restrict__ Xb, const uint32_t ldx,
+                                                           float *__restrict__ Y, const int64_t ldy, const uint32_t batch) {
+    extern __shared__ float4 smem4[];
+    constexpr int NT = 4, NB = 64, KS = 2;         // 64 batch columns per workgroup, 32 block columns per pass
+    constexpr uint32_t NTHR = NW * 64;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uni_(tid >> 6);
+    const uint32_t bt0 = blockIdx.y * NB;
+    const uint32_t br = m.br;
+    if (blockIdx.x >= m.n_nz_tiles) {              // a row tile without work: zeros
+        const uint32_t tile = m.zero_tiles[blockIdx.x - m.n_nz_tiles];
+        for (uint32_t e = tid; e < br * NB; e += NTHR) {
+            const uint32_t row = tile * br + e / NB, n = bt0 + e % NB;
+            if (row < m.rows_out && n < batch) Y[(size_t)row * ldy + n] = 0.0f;
+        }
+        return;
+    }
+    uint8_t *meta = (uint8_t *)smem4;
+    float *acc = (float *)(meta + m.seg_meta);     // [waves][br][NB]
+    float *myacc = acc + (size_t)wave * br * NB;
+    for (uint32_t e = lane; e < br * NB; e += 64) myacc[e] = 0.0f;
+    const uint32_t rank = blockIdx.x, tile = m.nz_tiles[rank];
+    const uint32_t mrow = lane & 15u, kq = lane >> 4;
+    const uint32_t ncol = bt0 + 4u * mrow;         // first of this lane's four right-hand sides (batch % 4 == 0)
+    const uint32_t noff = (ncol < batch ? ncol : 0u) * 2u;   // bytes; one past the batch reads 0..3, never stored
+
+    for (uint32_t sg = m.tile_seg0[rank]; sg < m.tile_seg0[rank + 1]; ++sg) {
+        const SegRec *sp = m.segs + sg;
+        const uint32_t ga = sp->g0, ng = sp->ng, vb0 = sp->vb0, nvbs = sp->nvbs, idx0 = sp->idx0, idx_bytes = sp->idx_bytes;
+        const uint32_t voff = (ng * (uint32_t)sizeof(GroupRec) + 15u) & ~15u;
+        const uint32_t ioff = voff + ((nvbs * (uint32_t)sizeof(VbRec) + 15u) & ~15u);
+        __syncthreads();
+        {
+            const uint2 *gs = (const uint2 *)(m.groups + ga);
+            uint2 *gd = (uint2 *)meta;
+            for (uint32_t i = tid; i < ng * 3u; i += NTHR) gd[i] = gs[i];
+            const float4 *vs = (const float4 *)(m.vbs + vb0);
+            float4 *vd = (float4 *)(meta + voff);
+            for (uint32_t i = tid; i < nvbs; i += NTHR) vd[i] = vs[i];
+            const float4 *is = (const float4 *)(m.idx + idx0);
+            float4 *id = (float4 *)(meta + ioff);
+            for (uint32_t i = tid; i < idx_bytes >> 4; i += NTHR) id[i] = is[i];
+        }
+        __syncthreads();
+
+        auto open_vb = [&](uint32_t k) -> Pass {
+            Pass p{};
+            p.k = k;
+            p.valid = k < nvbs;
+            if (!p.valid) return p;
+            const uint4 v = *(const uint4 *)(meta + voff + k * (uint32_t)sizeof(VbRec));
+            const uint32_t v0 = uni_(v.x);
+            p.r = v0 & 0xffu; p.lane0 = (v0 >> 8) & 0xffu; p.c = v0 >> 16;
+            p.val_off = uni_(v.y);
+            p.desc = ioff + (uni_(v.z) - idx0);
+            p.list = ioff + (uni_(v.w) - idx0);
+            p.m0 = 0; p.kc = 0;
+            return p;
+        };
+        auto next_pass = [&](const Pass &p) -> Pass {
+            Pass q = p;
+            q.kc += 16 * KS;
+            if (q.kc < q.c) return q;
+            q.kc = 0; q.m0 += 16;
+            if (q.m0 < q.r) return q;
+            return open_vb(p.k + NW);
+        };
+        auto load_pass = [&](const Pass &p, OperandsBf<KS> &o) {
+            // one word per lane and pair of columns, the even column in the low half; a block
+            // with an odd number of columns has a zero in its last word's high half
+            const uint32_t *gv16 = (const uint32_t *)m.vals + (p.val_off >> 1);
+            const uint16_t *colp = (const uint16_t *)(meta + p.list);
+            const bool row_ok = p.m0 + mrow < p.r;
+            const uint32_t arow = p.lane0 + p.m0 + (row_ok ? mrow : 0u);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                if (p.kc + 16u * s >= p.c) break;                  // uniform: columns the block does not have
+                const uint32_t j0 = p.kc + 16u * s + 4u * kq;      // this lane's four columns
+                const bool ok0 = j0 < p.c, ok1 = j0 + 2u < p.c;
+                const uint32_t w0 = gv16[((ok0 ? j0 : 0u) >> 1) * (uint32_t)kWave + arow];
+                const uint32_t w1 = gv16[((ok1 ? j0 + 2u : 0u) >> 1) * (uint32_t)kWave + arow];
+                o.a[s] = make_uint2(ok0 && row_ok ? w0 : 0u, ok1 && row_ok ? w1 : 0u);
+                // (a lane without a column reads the block's first one: finite, times a zero)
+                uint2 x[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t jj = j0 + (uint32_t)i;
+                    const uint32_t cb = colp[jj < p.c ? jj : 0u];  // 4 * column
+                    x[i] = *(const uint2 *)((const uint8_t *)Xb + (__umul24(cb, ldx) >> 1) + noff);
+                }
+                // x[i] = right-hand sides 0..3 at column i; tile t wants columns 0..3 at right-hand side t
+                o.b[s][0] = make_uint2((x[0].x & 0xffffu) | (x[1].x << 16), (x[2].x & 0xffffu) | (x[3].x << 16));
+                o.b[s][1] = make_uint2((x[0].x >> 16) | (x[1].x & 0xffff0000u), (x[2].x >> 16) | (x[3].x & 0xffff0000u));
+                o.b[s][2] = make_uint2((x[0].y & 0xffffu) | (x[1].y << 16), (x[2].y & 0xffffu) | (x[3].y << 16));
+                o.b[s][3] = make_uint2((x[0].y >> 16) | (x[1].y & 0xffff0000u), (x[2].y >> 16) | (x[3].y & 0xffff0000u));
+            }
+        };
+        floatx4 D[NT];
+        const floatx4 zero4 = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) D[nt] = zero4;
+        auto mult_pass = [&](const Pass &p, const OperandsBf<KS> &o) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                if (p.kc + 16u * s >= p.c) break;                  // uniform
+                const bf16x4 av = __builtin_bit_cast(bf16x4, o.a[s]);
+                if (s == 0 && p.kc == 0) {                         // uniform: a slice starts from a zero operand
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        D[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, __builtin_bit_cast(bf16x4, o.b[s][nt]), zero4, 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        D[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, __builtin_bit_cast(bf16x4, o.b[s][nt]), D[nt], 0, 0, 0);
+                }
+            }
+            if (p.kc + 16 * KS < p.c) return;                      // the slice has more columns
+            // lane holds rows 4*(lane/16)+i, right-hand side group lane%16 of each result tile
+            uint32_t at[4];
+            bool on[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t mr = p.m0 + 4u * kq + i;
+                on[i] = mr < p.r;
+                const uint32_t slot = meta[p.desc + 4u * (p.lane0 + (on[i] ? mr : 0u))];
+                at[i] = slot * NB + 4u * mrow;
+            }
+            float4 old4[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) old4[i] = *(const float4 *)(myacc + at[i]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (on[i])
+                    *(float4 *)(myacc + at[i]) = make_float4(old4[i].x + D[0][i], old4[i].y + D[1][i],
+                                                             old4[i].z + D[2][i], old4[i].w + D[3][i]);
+        };
+        auto nxt = [&](const Pass &p) -> Pass { return p.valid ? next_pass(p) : p; };
+        OperandsBf<KS> oa, ob, oc;                                  // three passes in flight
+        Pass pa = open_vb(wave), pb = nxt(pa), pc{};
+        if (pa.valid) load_pass(pa, oa);
+        if (pb.valid) load_pass(pb, ob);
+        while (true) {
+            pc = nxt(pb); if (pc.valid) load_pass(pc, oc);
+            if (!pa.valid) break;
+            mult_pass(pa, oa);
+            pa = nxt(pc); if (pa.valid) load_pass(pa, oa);
+            if (!pb.valid) break;
+            mult_pass(pb, ob);
+            pb = nxt(pa); if (pb.valid) load_pass(pb, ob);
+            if (!pc.valid) break;
+            mult_pass(pc, oc);
+        }
+    }
+    __syncthreads();
+    for (uint32_t e = tid; e < br * NB; e += NTHR) {
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += acc[(size_t)w * br * NB + e];
+        const uint32_t row = tile * br + e / NB, n = bt0 + e % NB;
+        if (row < m.rows_out && n < batch) Y[(size_t)row * ldy + n] = s;
+    }
+}
+
 // Several independent products in one launch (blockIdx.z picks the product): the per-step
 // products of different layers of a batched recurrent model, each too small to fill the GPU.
 struct SpmmJobs {
@@ -421,6 +600,45 @@ int spmm_strided_multi(const SpmmCall *calls, int n, int32_t batch, void *stream
 }
 
 }  // namespace csb
+
+extern "C" int csb_spmm_bfloat(const csb_matrix *m, const uint16_t *d_Xb, int64_t ldx, float *d_Y, int64_t ldy,
+                             int32_t batch, void *stream) {
+    using namespace csb;
+    if (!m || !d_Xb || !d_Y) { set_error("csb_spmm_bfloat: NULL pointer"); return CSB_EINVAL; }
+    if (batch <= 0 || ldx < batch || ldy < batch) { set_error("csb_spmm_bfloat: batch <= 0 or a leading dimension below batch"); return CSB_EINVAL; }
+    if (!m->plan.valid || !m->uploaded || !m->d_buf) { set_error("csb_spmm_bfloat: matrix not planned and uploaded"); return CSB_ESTATE; }
+    if (m->plan.split.active()) { set_error("csb_spmm_bfloat: matrix is planned for a GRU step"); return CSB_ESTATE; }
+    const DevHeader &h = m->plan.hdr;
+    if (h.val_fmt != CSB_VAL_BF16) { set_error("csb_spmm_bfloat: the matrix does not store bfloat16 values (csb_set_value_format)"); return CSB_ESTATE; }
+    // four right-hand sides per 8-byte load; 32-bit byte offsets and a 24-bit multiply
+    if (batch % 4 != 0 || ldx % 4 != 0 || (uintptr_t)d_Xb % 8 != 0) {
+        set_error("csb_spmm_bfloat: batch and ldx must be multiples of 4 and X 8-byte aligned");
+        return CSB_EUNSUPPORTED;
+    }
+    if (ldx >= (1 << 24) || (int64_t)h.cols * ldx + batch >= (1ll << 30)) {
+        set_error("csb_spmm_bfloat: sizes beyond the kernel's 32-bit offsets");
+        return CSB_EUNSUPPORTED;
+    }
+    const size_t acc_per_wave = (size_t)h.br * 64 * sizeof(float);
+    const bool fits16 = (size_t)h.seg_meta + 16 * acc_per_wave <= (size_t)kLdsBudget;
+    if ((size_t)h.seg_meta + 8 * acc_per_wave > (size_t)kLdsBudget) {
+        set_error("csb_spmm_bfloat: the block rows are too tall for the accumulator tiles");
+        return CSB_EUNSUPPORTED;
+    }
+    const int nw = fits16 ? 16 : 8;
+    const size_t lds = (size_t)h.seg_meta + (size_t)nw * acc_per_wave;
+    DevMat dm = dev_mat(m);
+    uint32_t b = (uint32_t)batch, ld = (uint32_t)ldx;
+    int64_t ldy_ = ldy;
+    void *args[] = {&dm, &d_Xb, &ld, &d_Y, &ldy_, &b};
+    const void *kern = nw == 16 ? (const void *)spmm_bf16_kernel<16> : (const void *)spmm_bf16_kernel<8>;
+    hipError_t e = ensure_dynamic_lds(kern, lds);
+    if (e == hipSuccess)
+        e = hipLaunchKernel(kern, dim3((unsigned)(h.n_nz_tiles + h.n_zero_tiles), (unsigned)((batch + 63) / 64)), dim3(nw * 64), args, lds,
+                            (hipStream_t)stream);
+    if (e != hipSuccess) { set_error(std::string("csb_spmm_bfloat: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    return CSB_OK;
+}
 
 extern "C" int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int64_t ldy,
                         int32_t batch, void *d_ws, void *stream) {
