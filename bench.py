@@ -486,7 +486,24 @@ def val16_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
             n = 20
             us = time_region(lambda: M.spmm(X, Y), n, torch) * 1000.0 / n
             nnz = int(M.view()["nnz"])
-            entry["spmm_b128"] = {"us": round(us, 2), "tflops_algorithmic": round(2.0 * nnz * B / us / 1e6, 3)}
+            entry["spmm_b128"] = {"us": round(us, 2), "tflops_algorithmic": round(2.0 * nnz * B / us / 1e6, 3),
+                                  "note": "bfloat16 kernel values, float32 right-hand sides, f32 matrix cores (csb_spmm)"}
+            # bfloat16 right-hand sides too: csb_spmm_bfloat on the bf16 matrix cores
+            bf = {}
+            for Bb in (128, 512):
+                Xb = torch.from_numpy(csb_inputs.make_vectors(6, m.cols, Bb).reshape(m.cols, Bb)).cuda().to(torch.bfloat16)
+                Yb = torch.empty((m.rows, Bb), dtype=torch.float32, device="cuda")
+                for _ in range(3):
+                    M.spmm_bfloat(Xb, Yb)
+                us = time_region(lambda: M.spmm_bfloat(Xb, Yb), n, torch) * 1000.0 / n
+                tf = 2.0 * nnz * Bb / us / 1e6
+                bf[f"batch{Bb}"] = {"us": round(us, 2), "tflops_algorithmic": round(tf, 3)}
+            tf = bf["batch512"]["tflops_algorithmic"]
+            entry["spmm_bfloat"] = dict(bf, roofline={
+                "kernel": "csb::spmm_bf16_kernel<16>", "bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
+                "frac": round(tf / 2500.0, 5), "traffic": None,
+                "note": "dense bf16 MFMA peak as the nominal roof; like the f32 kernel the launch is bound by the gather of X "
+                        "through L2 (half the bytes here), not by the matrix cores"})
         res[f"spmv_cfg5_{name}"] = entry
         del copies, M
     return res
