@@ -74,6 +74,16 @@ def test_random_products(group):
         got = Y.cpu().numpy().astype(np.float64)
         assert got.shape == ref.shape
         assert np.all(np.abs(got - ref) <= dot_bound(D, oracle.matmat(np.abs(D), np.abs(X))))
+        if fmt == P.VAL_BF16 and batch % 4 == 0:          # bfloat16 right-hand sides too, on the bf16 matrix cores
+            Xq = oracle.round_weights(X, "bf16").astype(np.float32)
+            try:
+                Yb = M.spmm_bfloat(torch.from_numpy(Xq).cuda().to(torch.bfloat16))
+            except P.CsbError:
+                assert br > 64                             # refused only when the accumulator tiles do not fit
+            else:
+                torch.cuda.synchronize()
+                ref = oracle.matmat(D, Xq)
+                assert np.all(np.abs(Yb.cpu().numpy().astype(np.float64) - ref) <= dot_bound(D, oracle.matmat(np.abs(D), np.abs(Xq))))
         M.close()
 
 
