@@ -240,6 +240,10 @@ int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int
  * synchronisation.
  */
 int csb_spmm_bfloat(const csb_matrix *m, const uint16_t *d_Xb, int64_t ldx, float *d_Y, int64_t ldy,
+                    int32_t batch, void *stream);
+/* The same with IEEE binary16 operands (matrix: CSB_VAL_F16; d_Xh: binary16 bit patterns):
+ * products of two binary16 numbers are exact in binary32 too.  Same layout, bound and errors. */
+int csb_spmm_half(const csb_matrix *m, const uint16_t *d_Xh, int64_t ldx, float *d_Y, int64_t ldy,
                   int32_t batch, void *stream);
 
 /*

@@ -20,7 +20,7 @@ _lib = None
 
 # every symbol include/csbrnn.h declares
 SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_set_value_format", "csb_value_format", "csb_sharing_model", "csb_plan", "csb_plan_ex", "csb_plan_validate",
-           "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm", "csb_spmm_bfloat",
+           "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm", "csb_spmm_bfloat", "csb_spmm_half",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
            "csb_project_workspace_bytes", "csb_project", "csb_rnn_create_lstmp", "csb_rnn_create_gru_rb",
@@ -105,6 +105,7 @@ def load_library():
                               C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     L.csb_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     L.csb_spmm_bfloat.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
+    L.csb_spmm_half.argtypes = L.csb_spmm_bfloat.argtypes
     L.csb_rnn_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
     L.csb_rnn_create_lstmp.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
@@ -296,6 +297,17 @@ class CsbMatrix:
             Y = torch.empty((self.rows, batch), dtype=torch.float32, device=Xb.device)
         assert Xb.is_cuda and Y.is_cuda and Xb.dtype == torch.bfloat16 and Xb.stride(1) == 1 and Y.stride(1) == 1
         _check(lib().csb_spmm_bfloat(self._h, Xb.data_ptr(), Xb.stride(0), Y.data_ptr(), Y.stride(0), batch,
+                                   _stream_ptr(stream)))
+        return Y
+
+    def spmm_half(self, Xh, Y=None, stream=None):
+        """Xh: [cols, batch] torch.float16 cuda (rows may be strided, the batch contiguous)."""
+        import torch
+        cols, batch = Xh.shape
+        if Y is None:
+            Y = torch.empty((self.rows, batch), dtype=torch.float32, device=Xh.device)
+        assert Xh.is_cuda and Y.is_cuda and Xh.dtype == torch.float16 and Xh.stride(1) == 1 and Y.stride(1) == 1
+        _check(lib().csb_spmm_half(self._h, Xh.data_ptr(), Xh.stride(0), Y.data_ptr(), Y.stride(0), batch,
                                    _stream_ptr(stream)))
         return Y
 

@@ -291,7 +291,15 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(const DevMat m, const XSr
 // what bounds the f32 kernel -- moves half the bytes.  Same tiling as the wide f32 form: a
 // lane loads four neighbouring right-hand sides of an input row at once (8 bytes), tile t
 // holds the right-hand sides 4 n + t.
+// The same kernel serves binary16 (HALF: v_mfma_f32_16x16x16_f16, values and right-hand sides
+// as binary16, whose products are exact in binary32 as well).
 typedef short bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+template <bool HALF>
+__device__ __forceinline__ floatx4 mfma_16bit(const uint2 a, const uint2 b, const floatx4 c) {
+    if constexpr (HALF) return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, a), __builtin_bit_cast(f16x4, b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, a), __builtin_bit_cast(bf16x4, b), c, 0, 0, 0);
+}
 
 template <int KS>
 struct OperandsBf {
@@ -299,7 +307,7 @@ struct OperandsBf {
     uint2 b[KS][4];       // per tile: the same four columns of its right-hand side
 };
 
-template <int NW>
+template <int NW, bool HALF>
 __global__ __launch_bounds__(NW * 64) void spmm_bf16_kernel(const DevMat m, const uint16_t *__restrict__ Xb, const uint32_t ldx,
                                                            float *__restrict__ Y, const int64_t ldy, const uint32_t batch) {
     extern __shared__ float4 smem4[];
@@ -404,15 +412,12 @@ __global__ __launch_bounds__(NW * 64) void spmm_bf16_kernel(const DevMat m, cons
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 if (p.kc + 16u * s >= p.c) break;                  // uniform
-                const bf16x4 av = __builtin_bit_cast(bf16x4, o.a[s]);
                 if (s == 0 && p.kc == 0) {                         // uniform: a slice starts from a zero operand
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        D[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, __builtin_bit_cast(bf16x4, o.b[s][nt]), zero4, 0, 0, 0);
+                    for (int nt = 0; nt < NT; ++nt) D[nt] = mfma_16bit<HALF>(o.a[s], o.b[s][nt], zero4);
                 } else {
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        D[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, __builtin_bit_cast(bf16x4, o.b[s][nt]), D[nt], 0, 0, 0);
+                    for (int nt = 0; nt < NT; ++nt) D[nt] = mfma_16bit<HALF>(o.a[s], o.b[s][nt], D[nt]);
                 }
             }
             if (p.kc + 16 * KS < p.c) return;                      // the slice has more columns
@@ -601,28 +606,30 @@ int spmm_strided_multi(const SpmmCall *calls, int n, int32_t batch, void *stream
 
 }  // namespace csb
 
-extern "C" int csb_spmm_bfloat(const csb_matrix *m, const uint16_t *d_Xb, int64_t ldx, float *d_Y, int64_t ldy,
-                             int32_t batch, void *stream) {
-    using namespace csb;
-    if (!m || !d_Xb || !d_Y) { set_error("csb_spmm_bfloat: NULL pointer"); return CSB_EINVAL; }
-    if (batch <= 0 || ldx < batch || ldy < batch) { set_error("csb_spmm_bfloat: batch <= 0 or a leading dimension below batch"); return CSB_EINVAL; }
-    if (!m->plan.valid || !m->uploaded || !m->d_buf) { set_error("csb_spmm_bfloat: matrix not planned and uploaded"); return CSB_ESTATE; }
-    if (m->plan.split.active()) { set_error("csb_spmm_bfloat: matrix is planned for a GRU step"); return CSB_ESTATE; }
+namespace csb {
+// csb_spmm_bfloat / csb_spmm_half: both operands in the 16-bit format `fmt`
+static int spmm_16bit(const char *who, int fmt, const csb_matrix *m, const uint16_t *d_X, int64_t ldx, float *d_Y, int64_t ldy,
+                      int32_t batch, void *stream) {
+    const std::string w(who);
+    if (!m || !d_X || !d_Y) { set_error(w + ": NULL pointer"); return CSB_EINVAL; }
+    if (batch <= 0 || ldx < batch || ldy < batch) { set_error(w + ": batch <= 0 or a leading dimension below batch"); return CSB_EINVAL; }
+    if (!m->plan.valid || !m->uploaded || !m->d_buf) { set_error(w + ": matrix not planned and uploaded"); return CSB_ESTATE; }
+    if (m->plan.split.active()) { set_error(w + ": matrix is planned for a GRU step"); return CSB_ESTATE; }
     const DevHeader &h = m->plan.hdr;
-    if (h.val_fmt != CSB_VAL_BF16) { set_error("csb_spmm_bfloat: the matrix does not store bfloat16 values (csb_set_value_format)"); return CSB_ESTATE; }
+    if ((int)h.val_fmt != fmt) { set_error(w + ": the matrix does not store its values in this format (csb_set_value_format)"); return CSB_ESTATE; }
     // four right-hand sides per 8-byte load; 32-bit byte offsets and a 24-bit multiply
-    if (batch % 4 != 0 || ldx % 4 != 0 || (uintptr_t)d_Xb % 8 != 0) {
-        set_error("csb_spmm_bfloat: batch and ldx must be multiples of 4 and X 8-byte aligned");
+    if (batch % 4 != 0 || ldx % 4 != 0 || (uintptr_t)d_X % 8 != 0) {
+        set_error(w + ": batch and ldx must be multiples of 4 and X 8-byte aligned");
         return CSB_EUNSUPPORTED;
     }
     if (ldx >= (1 << 24) || (int64_t)h.cols * ldx + batch >= (1ll << 30)) {
-        set_error("csb_spmm_bfloat: sizes beyond the kernel's 32-bit offsets");
+        set_error(w + ": sizes beyond the kernel's 32-bit offsets");
         return CSB_EUNSUPPORTED;
     }
     const size_t acc_per_wave = (size_t)h.br * 64 * sizeof(float);
     const bool fits16 = (size_t)h.seg_meta + 16 * acc_per_wave <= (size_t)kLdsBudget;
     if ((size_t)h.seg_meta + 8 * acc_per_wave > (size_t)kLdsBudget) {
-        set_error("csb_spmm_bfloat: the block rows are too tall for the accumulator tiles");
+        set_error(w + ": the block rows are too tall for the accumulator tiles");
         return CSB_EUNSUPPORTED;
     }
     const int nw = fits16 ? 16 : 8;
@@ -630,14 +637,27 @@ extern "C" int csb_spmm_bfloat(const csb_matrix *m, const uint16_t *d_Xb, int64_
     DevMat dm = dev_mat(m);
     uint32_t b = (uint32_t)batch, ld = (uint32_t)ldx;
     int64_t ldy_ = ldy;
-    void *args[] = {&dm, &d_Xb, &ld, &d_Y, &ldy_, &b};
-    const void *kern = nw == 16 ? (const void *)spmm_bf16_kernel<16> : (const void *)spmm_bf16_kernel<8>;
+    void *args[] = {&dm, &d_X, &ld, &d_Y, &ldy_, &b};
+    const bool half = fmt == CSB_VAL_F16;
+    const void *kern = nw == 16 ? (half ? (const void *)spmm_bf16_kernel<16, true> : (const void *)spmm_bf16_kernel<16, false>)
+                                : (half ? (const void *)spmm_bf16_kernel<8, true> : (const void *)spmm_bf16_kernel<8, false>);
     hipError_t e = ensure_dynamic_lds(kern, lds);
     if (e == hipSuccess)
         e = hipLaunchKernel(kern, dim3((unsigned)(h.n_nz_tiles + h.n_zero_tiles), (unsigned)((batch + 63) / 64)), dim3(nw * 64), args, lds,
                             (hipStream_t)stream);
-    if (e != hipSuccess) { set_error(std::string("csb_spmm_bfloat: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    if (e != hipSuccess) { set_error(w + ": " + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
+}
+}  // namespace csb
+
+extern "C" int csb_spmm_bfloat(const csb_matrix *m, const uint16_t *d_Xb, int64_t ldx, float *d_Y, int64_t ldy,
+                               int32_t batch, void *stream) {
+    return csb::spmm_16bit("csb_spmm_bfloat", CSB_VAL_BF16, m, d_Xb, ldx, d_Y, ldy, batch, stream);
+}
+
+extern "C" int csb_spmm_half(const csb_matrix *m, const uint16_t *d_Xh, int64_t ldx, float *d_Y, int64_t ldy,
+                             int32_t batch, void *stream) {
+    return csb::spmm_16bit("csb_spmm_half", CSB_VAL_F16, m, d_Xh, ldx, d_Y, ldy, batch, stream);
 }
 
 extern "C" int csb_spmm(const csb_matrix *m, const float *d_X, int64_t ldx, float *d_Y, int64_t ldy,

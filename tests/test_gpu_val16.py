@@ -153,31 +153,41 @@ BF_SHAPES = [(37, 53, 8, 8, 4, 4.0), (4, 8, 4, 4, 8, 2.0), (1, 1, 1, 1, 4, 1.0),
              (90, 90, 3, 5, 16, 1.5), (64, 2048, 32, 32, 32, 1.0)]
 
 
+def run16(M, name, Xq_dev32):
+    """csb_spmm_bfloat / csb_spmm_half on float32 values that the format holds exactly."""
+    if name == "bf16":
+        return M.spmm_bfloat(Xq_dev32.to(torch.bfloat16))
+    return M.spmm_half(Xq_dev32.to(torch.float16))
+
+
+@pytest.mark.parametrize("fmt,name", FORMATS)
 @pytest.mark.parametrize("R,C,br,bc,B,rate", BF_SHAPES)
-def test_spmm_bfloat(R, C, br, bc, B, rate):
-    """csb_spmm_bfloat: bfloat16 kernel values times bfloat16 right-hand sides on the bf16 matrix
-    cores, accumulated in binary32.  Against the float64 product of the operands as the ORACLE
-    rounds them (the products of two bfloat16 numbers are exact in binary32, so the float32
-    dot-product bound of csb_spmm holds), blocks with more than 16 and more than 32 columns,
-    odd column counts, batches that are not a multiple of 64, a strided X."""
-    say(f"[val16] spmm_bfloat {R}x{C} block {br}x{bc} batch {B} rate {rate}")
+def test_spmm_bfloat(fmt, name, R, C, br, bc, B, rate):
+    """csb_spmm_bfloat / csb_spmm_half: 16-bit kernel values times 16-bit right-hand sides on the
+    16-bit matrix cores, accumulated in binary32.  Against the float64 product of the operands
+    as the ORACLE rounds them (the products of two such numbers are exact in binary32, so the
+    float32 dot-product bound of csb_spmm holds), blocks with more than 16 and more than 32
+    columns, odd column counts, batches that are not a multiple of 64, a strided X."""
+    say(f"[val16] spmm 16-bit operands {name} {R}x{C} block {br}x{bc} batch {B} rate {rate}")
     m = csb_inputs.small_matrix(R + C + B, R, C, br, bc, rate=rate)
     X = csb_inputs.make_vectors(B + 1, C, B).reshape(C, B)
-    Aq = oracle.round_weights(m.A, "bf16")
-    Xq = oracle.round_weights(X, "bf16").astype(np.float32)
+    Aq = oracle.round_weights(m.A, name)
+    Xq = oracle.round_weights(X, name).astype(np.float32)
     ref = oracle.matmat(Aq, Xq)
-    M = packed(m.A, br, bc, VAL_BF16)
-    buf = torch.zeros((C, B + 8), dtype=torch.bfloat16, device="cuda")
-    buf[:, :B] = torch.from_numpy(Xq).cuda().to(torch.bfloat16)         # exact: the values are bfloat16 already
+    M = packed(m.A, br, bc, fmt)
+    dt = torch.bfloat16 if name == "bf16" else torch.float16
+    buf = torch.zeros((C, B + 8), dtype=dt, device="cuda")
+    buf[:, :B] = torch.from_numpy(Xq).cuda().to(dt)                      # exact: the values are in the format already
     assert torch.equal(buf[:, :B].float().cpu(), torch.from_numpy(Xq))
-    Y = M.spmm_bfloat(buf[:, :B])
+    call = M.spmm_bfloat if name == "bf16" else M.spmm_half
+    Y = call(buf[:, :B])
     torch.cuda.synchronize()
     got = Y.cpu().numpy().astype(np.float64)
     assert got.shape == ref.shape and np.all(np.isfinite(got))
     absr = oracle.matmat(np.abs(Aq), np.abs(Xq))
     k = np.count_nonzero(m.A, axis=1)[:, None]
     assert np.all(np.abs(got - ref) <= 2.0 * np.maximum(k, 1) * 2.0 ** -24 * absr + 1e-30)
-    assert torch.equal(Y, M.spmm_bfloat(buf[:, :B]))                     # run to run the same bits
+    assert torch.equal(Y, call(buf[:, :B]))                              # run to run the same bits
 
 
 def test_spmm_bfloat_refusals():
@@ -193,20 +203,23 @@ def test_spmm_bfloat_refusals():
         M.spmm_bfloat(torch.zeros((64, 6), dtype=torch.bfloat16, device="cuda"))
     with pytest.raises(CsbError):                      # rows of X not 8-byte aligned
         M.spmm_bfloat(torch.zeros((64, 10), dtype=torch.bfloat16, device="cuda")[:, :8])
+    with pytest.raises(CsbError):                      # a bfloat16 matrix is not a binary16 one
+        M.spmm_half(torch.zeros((64, 8), dtype=torch.float16, device="cuda"))
 
 
-def test_spmm_bfloat_full_size():
+@pytest.mark.parametrize("fmt,name", FORMATS)
+def test_spmm_bfloat_full_size(fmt, name):
     """The 8192 x 8192 heavy-tailed matrix at batch 128, the launch bench.py times: sampled rows
     against the oracle."""
     m = csb_inputs.make_mat(csb_inputs.CONFIGS["cfg5"])
     B = 128
     X = csb_inputs.make_vectors(9, m.cols, B).reshape(m.cols, B)
-    Xq = oracle.round_weights(X, "bf16").astype(np.float32)
-    M = packed(m.A, m.br, m.bc, VAL_BF16)
-    Y = M.spmm_bfloat(torch.from_numpy(Xq).cuda().to(torch.bfloat16))
+    Xq = oracle.round_weights(X, name).astype(np.float32)
+    M = packed(m.A, m.br, m.bc, fmt)
+    Y = run16(M, name, torch.from_numpy(Xq).cuda())
     torch.cuda.synchronize()
     rows = np.unique(np.concatenate([np.arange(0, 64), np.random.default_rng(0).integers(0, m.rows, 400), [m.rows - 1]]))
-    Aq = oracle.round_weights(m.A[rows], "bf16")
+    Aq = oracle.round_weights(m.A[rows], name)
     ref = oracle.matmat(Aq, Xq)
     got = Y.cpu().numpy()[rows].astype(np.float64)
     absr = oracle.matmat(np.abs(Aq), np.abs(Xq))
