@@ -92,7 +92,11 @@ typedef struct {
                                 of Sec. 6.3.2), for context                             */
     double chunk_max_over_mean;   /* largest / mean work per workgroup                   */
     int32_t whole_tiles;     /* 1: every workgroup owns whole output row tiles (no merge) */
+    int32_t row_owned;       /* 1: csb_spmv runs the row-owned layout (below); the figures above
+                                then describe that layout                                */
+    int32_t rounds;          /* row-owned layout: rounds per workgroup                   */
     int32_t reserved;
+    int64_t matvec_bytes;    /* bytes of the device image one csb_spmv launch reads      */
 } csb_plan_stats;
 
 const char *csb_last_error(void);
@@ -159,6 +163,28 @@ int csb_plan(csb_matrix *m, int32_t n_chunks, csb_plan_stats *stats);
  * over the 16 wavefronts.
  */
 int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *stats);
+
+/*
+ * The row-owned layout of the mat-vec (Sec. 4.3.1 / the equal-work role of Sec. 5.2), which
+ * csb_plan and csb_plan_ex(mode 0) build next to the tile-based sections whenever the matrix
+ * fits it: float32 values, at most 16383 columns, not planned for a GRU step.  Every
+ * workgroup owns a contiguous range of at most 256 output rows (ranges of nearly equal
+ * stored bytes, cut at any row), so no sum crosses workgroups and nothing is merged.  The
+ * kernel-matrix rows that land in a range are sorted by column count, packed 64 to a group
+ * (one per lane), and the groups' column steps are cut into equal ranges, one per wavefront
+ * and round; a wavefront's share of a round is stored as ONE self-contained segment of a
+ * fixed size (8-bit column indices, column-major kernel values, no padding of the values),
+ * so a launch requests all of its bytes at once from addresses that depend only on the
+ * workgroup and wavefront numbers.  Row sums are formed in a fixed order (bitwise
+ * reproducible).  csb_spmv reads this section when it exists; csb_spmm and csb_rnn_forward
+ * keep reading the tile-based sections.
+ * csb_plan_rows plans like csb_plan with the parameters of this layout spelled out:
+ * n_workgroups (0 = default: one per 1024 kernel-matrix rows, at most 256, at least
+ * rows / 256) and min_rounds (0 or 1 = as few rounds as the LDS allows; more rounds make
+ * the segments shorter).  Errors as csb_plan; CSB_EUNSUPPORTED if the matrix does not fit
+ * the layout.
+ */
+int csb_plan_rows(csb_matrix *m, int32_t n_workgroups, int32_t min_rounds, csb_plan_stats *stats);
 
 /* Integer self-check of the planned device image: every offset in bounds, every kernel
  * value referenced exactly once, image decodes to the packed matrix.  Host only. */

@@ -19,7 +19,7 @@ _LIB_PATH = os.path.join(_PKG, "libcsbrnn.so")
 _lib = None
 
 # every symbol include/csbrnn.h declares
-SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_set_value_format", "csb_value_format", "csb_sharing_model", "csb_plan", "csb_plan_ex", "csb_plan_validate",
+SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_set_value_format", "csb_value_format", "csb_sharing_model", "csb_plan", "csb_plan_ex", "csb_plan_rows", "csb_plan_validate",
            "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm", "csb_spmm_bfloat", "csb_spmm_half",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
@@ -61,7 +61,8 @@ class csb_plan_stats(C.Structure):
     _fields_ = [("n_chunks", C.c_int32), ("waves_per_chunk", C.c_int32), ("n_groups", C.c_int32),
                 ("n_shared_tiles", C.c_int32), ("work_max", C.c_double), ("work_mean", C.c_double),
                 ("lane_fill", C.c_double), ("nosplit_max_over_mean", C.c_double),
-                ("chunk_max_over_mean", C.c_double), ("whole_tiles", C.c_int32), ("reserved", C.c_int32)]
+                ("chunk_max_over_mean", C.c_double), ("whole_tiles", C.c_int32), ("row_owned", C.c_int32),
+                ("rounds", C.c_int32), ("reserved", C.c_int32), ("matvec_bytes", C.c_int64)]
 
 
 def lib_path() -> str:
@@ -86,6 +87,7 @@ def load_library():
     L.csb_value_format.argtypes = [C.c_void_p]
     L.csb_plan.argtypes = [C.c_void_p, C.c_int32, C.POINTER(csb_plan_stats)]
     L.csb_plan_ex.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(csb_plan_stats)]
+    L.csb_plan_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(csb_plan_stats)]
     L.csb_plan_validate.argtypes = [C.c_void_p]
     L.csb_device_bytes.argtypes = [C.c_void_p]
     L.csb_device_bytes.restype = C.c_size_t
@@ -239,6 +241,14 @@ class CsbMatrix:
         self.stats = {k: getattr(st, k) for k, _ in csb_plan_stats._fields_}
         return self.stats
 
+    def plan_rows(self, n_workgroups: int = 0, min_rounds: int = 0):
+        """csb_plan_rows: the row-owned mat-vec layout with its parameters spelled out."""
+        st = csb_plan_stats()
+        _check(lib().csb_plan_rows(self._h, n_workgroups, min_rounds, C.byref(st)))
+        self.stats = {k: getattr(st, k) for k, _ in csb_plan_stats._fields_}
+        self.d_buf = None
+        return self.stats
+
     def validate(self):
         _check(lib().csb_plan_validate(self._h))
 
@@ -267,7 +277,9 @@ class CsbMatrix:
         return y
 
     def spmv_stamps(self, x, y=None, stream=None):
-        """csb_debug_spmv_stamps: returns (y, stamps [n_chunks, 8 + 3*16] int64 tensor)."""
+        """csb_debug_spmv_stamps: returns (y, stamps).  Row-owned layout: int64 [n_workgroups, 16, 8]
+        (per wavefront: start, vector staged, first unit landed, same, groups done, after the
+        barrier, end; 100 MHz clock).  Tile-based layout: [n_chunks, 8 + 3*16] shader clocks."""
         import torch
         if y is None:
             y = torch.empty(self.rows, dtype=torch.float32, device=x.device)
@@ -275,6 +287,8 @@ class CsbMatrix:
         st = torch.zeros(n, dtype=torch.int64, device=x.device)
         ws = self._workspace(1, x.device)
         _check(lib().csb_debug_spmv_stamps(self._h, _dptr(x), _dptr(y), _dptr(ws), _dptr(st), _stream_ptr(stream)))
+        if getattr(self, "stats", None) and self.stats.get("row_owned"):
+            return y, st.view(-1, 16, 8)
         return y, st.view(-1, 8 + 3 * 16)
 
     def spmm(self, X, Y=None, stream=None):

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcsbrnn.so")
-SOURCES = ["csb_pack.cpp", "csb_plan.cpp", "csb_sharing.cpp", "csb_spmv.hip", "csb_spmm.hip", "csb_project.hip", "csb_rnn.hip"]
+SOURCES = ["csb_pack.cpp", "csb_plan.cpp", "csb_stream.cpp", "csb_sharing.cpp", "csb_spmv.hip", "csb_spmv_stream.hip", "csb_spmm.hip", "csb_project.hip", "csb_rnn.hip"]
 
 
 def hipcc() -> str:

@@ -150,11 +150,86 @@ struct SplitSpec {
     }
 };
 
+// ---- row-owned stream section (batch-1 mat-vec of csb_spmv) ---------------------------
+// A second section of the device image, laid out so that a launch is ONE pass of loads whose
+// addresses depend on nothing but the workgroup and wavefront numbers.  Every workgroup owns
+// a contiguous range of output rows (at most kStreamMaxRows) and all kernel-matrix rows that
+// land in them; its work is dealt to its 16 wavefronts in `n_rounds` rounds.  The section is
+// n_wg runs of `wg_bytes` each: a header (`hdr_bytes`) followed by n_rounds * 16 wavefront
+// segments of `seg_bytes`, round-major (wavefront w works on segments w, w + 16, ...).  A
+// segment is self-describing (all offsets inside it are relative to its start), is copied
+// verbatim into the wavefront's own LDS area, and holds its records in front of its values,
+// the values in the order in which they are multiplied: a wavefront can start on a segment
+// while the rest of it is still on its way.
+constexpr int kStreamWaves = 16;
+constexpr int kStreamThreads = kStreamWaves * kWave;
+constexpr int kStreamMaxRows = 256;      // output rows of one workgroup (at least four threads add up a row)
+constexpr int kStreamMaxSegUnits = 8;    // 1 KiB units of a wavefront segment (one 16-byte load per lane each)
+constexpr int kStreamGroupOverhead = 8;  // fixed cost of a piece of a group in the work model (steps)
+constexpr int kStreamListLimit = 4096;   // column lists start below this byte offset of their segment (10-bit word index)
+
+// Workgroup header: what the row-sum pass needs.
+struct StreamRoundHdr {
+    uint32_t row0;       // first output row of the workgroup
+    uint32_t nrows;      // its number of output rows
+    uint32_t pad[2];
+    // followed by uint32_t [rows_max]: first slot (low half) and number (high half) of each row's
+    // partial sums in the workgroup's table, padded to 16 bytes
+};
+static_assert(sizeof(StreamRoundHdr) == 16, "StreamRoundHdr layout");
+
+struct StreamSegHdr {
+    uint16_t ng;         // groups in this segment
+    uint16_t off_vbs;    // byte offset of the virtual-block words
+    uint16_t bytes16;    // the segment's own length in 16-byte units (the rest of the stride is never read)
+    uint16_t next16;     // the same of the wavefront's segment of the next round (0: none)
+    uint16_t pad[4];
+};
+static_assert(sizeof(StreamSegHdr) == 16, "StreamSegHdr layout");
+
+// A group: up to 64 kernel-matrix rows (one per lane) of consecutive virtual blocks, and a run
+// of their column steps.  Bit l of start_mask is set when lane l is the first row of a virtual
+// block: a lane's block is vb0 + popcount(start_mask & bits up to and including l) - 1.
+// Values: step-major with a fixed stride -- step j is a run of 64 floats (lane l at [j * 64 + l]),
+// zero where the lane has no row or its block has no column j, so the multiplication needs no
+// predicates and reads its values at constant offsets.  The rows of a workgroup are sorted by
+// column count before they are grouped, so few of the slots are zeros.
+struct StreamGroup {
+    uint64_t start_mask;
+    uint16_t vb0;           // first virtual-block word of the group (index inside the segment)
+    uint16_t lane_off;      // byte offset of the lanes' (row, slot) words
+    uint16_t val_off;       // float index (inside the segment) of the value of step 0, lane 0
+    uint8_t cmax_minus_1;   // column steps - 1
+    uint8_t nlanes;
+};
+static_assert(sizeof(StreamGroup) == 16, "StreamGroup layout");
+
+// A virtual block (consecutive kernel-matrix rows of one CSB block, a range of its columns) is
+// one 32-bit word: bits 0-9 the 4-byte word index of its column index list inside the segment
+// (bytes; padded with zeros to the group's steps rounded up to 4), bits 10-17 its column
+// count - 1, bits 18-31 the block column of the CSB block (its first input is block column * bc).
+constexpr uint32_t stream_vb_word(uint32_t list_word, uint32_t c_minus_1, uint32_t bj) { return list_word | (c_minus_1 << 10) | (bj << 18); }
+
+struct StreamPlan {
+    bool valid = false;
+    uint32_t n_wg = 0, n_rounds = 0;
+    uint32_t seg_bytes = 0;     // multiple of 16
+    uint32_t hdr_bytes = 0;     // multiple of 16
+    uint32_t wg_bytes = 0;      // hdr_bytes + n_rounds * 16 * seg_bytes rounded up to 256
+    uint32_t kmax = 0;          // slots of the partial-sum table (the fullest workgroup's)
+    uint32_t rows_max = 0;      // largest row count of a workgroup
+    uint32_t tpr = 0;           // threads that share an output row in the row-sum pass (power of two)
+    uint32_t lds_bytes = 0;
+    uint32_t n_groups = 0;
+    uint64_t off = 0, bytes = 0;   // the section inside the image
+};
+
 struct Plan {
     bool valid = false;
     SplitSpec split;
     std::vector<uint8_t> image;   // host staging copy of the device image
     DevHeader hdr{};
+    StreamPlan stream;            // valid: csb_spmv reads this section instead of the sections above
     csb_plan_stats stats{};
 };
 
@@ -193,5 +268,7 @@ namespace csb {
 int plan_matrix(csb_matrix *m, int32_t n_chunks, int32_t waves_per_chunk, const SplitSpec &split,
                 csb_plan_stats *stats, int32_t mode);
 int validate_plan(const csb_matrix *m);
+int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_stats *stats);
+int validate_stream(const csb_matrix *m);
 DevMat dev_mat(const csb_matrix *m);
 }  // namespace csb

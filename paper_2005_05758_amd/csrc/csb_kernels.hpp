@@ -37,6 +37,8 @@ __device__ __host__ inline GateSrc plain_src(const float *v) {
 // y = A [x0[0..n0) ; x1[0..cols-n0)] on `stream`; y has the image's rows_out entries.
 int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const float *d_x1, float *d_y,
                   void *d_ws, void *stream, unsigned long long *d_stamps = nullptr);
+// y = A x from the row-owned stream section of the image (plan.stream.valid) on `stream`.
+int spmv_rows(const csb_matrix *m, const float *d_x, float *d_y, void *stream, unsigned long long *d_stamps = nullptr);
 // ... with either segment possibly a cell output still to be computed (see GateSrc).
 int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *d_ws, void *stream);
 // The element-wise part alone, one thread per unit: stores c_t, h_t (and hseq) of `s`.

@@ -42,7 +42,10 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
                 csb_plan_stats *stats_out, int32_t mode) {
     if (!m) { set_error("csb_plan: NULL matrix"); return CSB_EINVAL; }
     if (n_chunks_req < 0) { set_error("csb_plan: n_chunks < 0"); return CSB_EINVAL; }
-    if (mode < 0 || mode > 2) { set_error("csb_plan: mode must be 0 (auto), 1 (whole tiles) or 2 (equal split)"); return CSB_EINVAL; }
+    // mode 4 (internal): as mode 0 but without the row-owned section (the caller builds it itself)
+    if (mode < 0 || mode > 4 || mode == 3) { set_error("csb_plan: mode must be 0 (auto), 1 (whole tiles) or 2 (equal split)"); return CSB_EINVAL; }
+    const bool with_rows = mode == 0;
+    if (mode == 4) mode = 0;
     if (waves_per_chunk != 16) {
         set_error("csb_plan: waves_per_chunk must be 16");
         return CSB_EINVAL;
@@ -632,8 +635,12 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
             for (double v : rr) { mx = std::max(mx, v); sm += v; }
             st.nosplit_max_over_mean = sm > 0 ? mx / (sm / (double)nwt) : 0.0;
         }
+        st.matvec_bytes = (int64_t)pl.image.size();
         pl.stats = st;
+        pl.stream = StreamPlan{};
         if (stats_out) *stats_out = st;
+        // the row-owned section for csb_spmv, when the matrix fits it
+        if (with_rows) return plan_stream(m, n_chunks_req, 0, stats_out);
         return CSB_OK;
     } catch (const std::bad_alloc &) {
         set_error("csb_plan: out of host memory");
@@ -650,7 +657,7 @@ int validate_plan(const csb_matrix *m) {
     const DevHeader &h = pl.hdr;
     const uint8_t *im = pl.image.data();
     auto fail = [&](const char *what) { set_error(std::string("csb_plan_validate: ") + what); return CSB_EINVAL; };
-    if (h.total_bytes != pl.image.size()) return fail("image size");
+    if (h.total_bytes > pl.image.size() || (!pl.stream.valid && h.total_bytes != pl.image.size())) return fail("image size");
     const auto *chunks = (const ChunkRec *)(im + h.off_chunks);
     const auto *waves = (const WaveRec *)(im + h.off_waves);
     const auto *groups = (const GroupRec *)(im + h.off_groups);
@@ -844,6 +851,7 @@ int validate_plan(const csb_matrix *m) {
     for (uint32_t t = 0; t < n_tiles; ++t) if (!tile_written[t]) return fail("tile never written");
     if (vals_used != m->val.size()) return fail("not every value referenced exactly once");
     if (std::memcmp(expect.data(), got.data(), expect.size() * sizeof(float)) != 0) return fail("image does not decode to the matrix");
+    if (pl.stream.valid) return validate_stream(m);
     return CSB_OK;
 }
 
@@ -855,6 +863,20 @@ extern "C" int csb_plan(csb_matrix *m, int32_t n_chunks, csb_plan_stats *stats) 
 
 extern "C" int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *stats) {
     return csb::plan_matrix(m, n_chunks, 16, csb::SplitSpec{}, stats, mode);
+}
+
+extern "C" int csb_plan_rows(csb_matrix *m, int32_t n_workgroups, int32_t min_rounds, csb_plan_stats *stats) {
+    if (n_workgroups < 0 || min_rounds < 0) { csb::set_error("csb_plan_rows: negative parameter"); return CSB_EINVAL; }
+    int rc = csb::plan_matrix(m, 0, 16, csb::SplitSpec{}, nullptr, 4);
+    if (rc != CSB_OK) return rc;
+    rc = csb::plan_stream(m, n_workgroups, min_rounds, stats);
+    if (rc != CSB_OK) return rc;
+    if (!m->plan.stream.valid) {
+        m->plan.valid = false;
+        csb::set_error("csb_plan_rows: the matrix does not fit the row-owned layout");
+        return CSB_EUNSUPPORTED;
+    }
+    return CSB_OK;
 }
 
 extern "C" int csb_plan_validate(const csb_matrix *m) { return csb::validate_plan(m); }

@@ -665,6 +665,10 @@ extern "C" int csb_upload(csb_matrix *m, void *d_buf, size_t bytes, void *stream
 extern "C" int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws, void *stream) {
     if (!m || !d_x || !d_y) { csb::set_error("csb_spmv: NULL pointer"); return CSB_EINVAL; }
     if (m->plan.valid && m->plan.split.active()) { csb::set_error("csb_spmv: matrix is planned for a GRU step"); return CSB_ESTATE; }
+    if (m->plan.valid && m->plan.stream.valid) {            // the row-owned section: nothing is merged, no workspace
+        if (!m->uploaded || !m->d_buf) { csb::set_error("csb_spmv: matrix not planned and uploaded"); return CSB_ESTATE; }
+        return csb::spmv_rows(m, d_x, d_y, stream);
+    }
     if (d_ws && csb::workspace_changed_hands(d_ws, m)) m->ws_seen = nullptr;   // merge words: clear again
     return csb::spmv_segments(m, d_x, (uint32_t)m->cols, d_x, d_y, d_ws, stream, nullptr);
 }
@@ -699,6 +703,7 @@ extern "C" int csb_debug_stream_read(const void *d_buf, size_t bytes, float *d_o
 }
 
 extern "C" size_t csb_debug_stamp_count(const csb_matrix *m) {
+    if (m && m->plan.valid && m->plan.stream.valid) return (size_t)m->plan.stream.n_wg * csb::kStreamWaves * 8;
     return (m && m->plan.valid) ? (size_t)m->plan.hdr.n_chunks * csb::kStampsPerChunk : 0;
 }
 
@@ -706,6 +711,10 @@ extern "C" int csb_debug_spmv_stamps(const csb_matrix *m, const float *d_x, floa
                                      unsigned long long *d_stamps, void *stream) {
     if (!m || !d_x || !d_y || !d_stamps) { csb::set_error("csb_debug_spmv_stamps: NULL pointer"); return CSB_EINVAL; }
     if (m->plan.valid && m->plan.split.active()) { csb::set_error("csb_debug_spmv_stamps: matrix is planned for a GRU step"); return CSB_ESTATE; }
+    if (m->plan.valid && m->plan.stream.valid) {
+        if (!m->uploaded || !m->d_buf) { csb::set_error("csb_debug_spmv_stamps: matrix not planned and uploaded"); return CSB_ESTATE; }
+        return csb::spmv_rows(m, d_x, d_y, stream, d_stamps);
+    }
     if (d_ws && csb::workspace_changed_hands(d_ws, m)) m->ws_seen = nullptr;
     return csb::spmv_segments(m, d_x, (uint32_t)m->cols, d_x, d_y, d_ws, stream, d_stamps);
 }

@@ -1,0 +1,515 @@
+// Row-owned stream section of the device image (host only): the layout csb_spmv reads.
+//
+// Role in the method: Sec. 4.3.1's CSB-MVM sweeps the blocks, multiplies every kernel matrix
+// with the inputs its column indices name and accumulates at its row indices; Sec. 5.2 asks
+// that every parallel unit gets the same share of that uneven work.  Here a workgroup owns a
+// range of output rows outright (so no sum ever crosses workgroups), the kernel-matrix rows
+// that land in the range are sorted by column count, packed 64 to a group (one per lane) and
+// the groups' column steps are cut into equal ranges, one per wavefront and round.  Every
+// wavefront's share is written as one self-contained segment of fixed size, so that a launch
+// can request all of its bytes at once from addresses that depend on nothing but the
+// workgroup and wavefront numbers.
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "csb_internal.hpp"
+
+namespace csb {
+namespace {
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Default size of a workgroup's share: two 64-lane groups per wavefront.
+constexpr uint64_t kLanesPerWg = 2048;
+
+// One virtual block of a workgroup: kernel-matrix rows [a0, a1) of CSB block b.
+struct SVb {
+    uint32_t b;
+    uint16_t a0, a1;
+    uint16_t c;
+};
+
+struct Lane {
+    uint32_t vb;      // index into the workgroup's SVb list
+    uint16_t a;       // kernel-matrix row inside the CSB block
+    uint16_t rr;      // output row - row0
+};
+
+// A piece of a wavefront share: column steps [j0, j1) of group g (lanes [64 g, 64 g + 64) of the
+// workgroup's sorted lane sequence); nl lanes of the group still have columns at step j0.
+struct Piece {
+    uint32_t g;
+    uint16_t j0, j1;
+    uint16_t nl;
+};
+
+struct Share {
+    std::vector<Piece> pieces;
+    uint32_t bytes = 0;
+    double work = 0;
+};
+
+struct WgLayout {
+    uint32_t row0 = 0, nrows = 0;
+    std::vector<SVb> vbs;
+    std::vector<Lane> lanes;                       // sorted by column count, descending
+    std::vector<uint32_t> g_cmax;                  // column steps of every 64-lane group
+    std::vector<Share> share;                      // [n_rounds * 16], round-major
+    uint32_t kmax = 0;
+};
+
+struct SegSize {
+    size_t groups = 0, vbs = 0, lane_bytes = 0, list_bytes = 0, steps = 0;
+    size_t list_pos() const { return sizeof(StreamSegHdr) + groups * sizeof(StreamGroup) + vbs * 4 + lane_bytes; }
+    size_t total() const { return align_up(list_pos() + list_bytes, 16) + steps * kWave * sizeof(float); }
+};
+
+// Walks the virtual blocks of one piece: f(vb index, first lane of the run inside the group, rows, columns kept).
+template <typename F>
+void for_piece_vbs(const WgLayout &w, const Piece &p, F f) {
+    const uint32_t l0 = p.g * kWave;
+    uint32_t l = l0;
+    while (l < l0 + p.nl) {
+        const uint32_t vb = w.lanes[l].vb;
+        uint32_t e = l + 1;
+        while (e < l0 + p.nl && w.lanes[e].vb == vb) ++e;
+        const int ck = std::min<int>(w.vbs[vb].c, p.j1) - (int)p.j0;
+        f(vb, l - l0, e - l, ck);
+        l = e;
+    }
+}
+
+SegSize piece_size(const WgLayout &w, const Piece &p) {
+    SegSize s;
+    s.groups = 1;
+    s.steps = (size_t)(p.j1 - p.j0);
+    const size_t list_len = align_up(s.steps, 4);        // every list is padded to the piece's steps
+    for_piece_vbs(w, p, [&](uint32_t, uint32_t, uint32_t, int) {
+        s.vbs += 1;
+        s.list_bytes += list_len;
+    });
+    s.lane_bytes = align_up(2 * (size_t)p.nl, 4);
+    return s;
+}
+
+}  // namespace
+
+// Builds the stream section for `m` and appends it to the plan's image.  Returns CSB_OK and
+// leaves plan.stream.valid false when the matrix does not fit the layout (the caller then
+// keeps the tile-based sections for the mat-vec as well).
+int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_stats *stats_out) {
+    Plan &pl = m->plan;
+    pl.stream = StreamPlan{};
+    if (pl.split.active() || m->val_fmt != CSB_VAL_F32) return CSB_OK;
+    if (m->cols > kMaxStageCols || m->rows > 0x7fffffff) return CSB_OK;
+    try {
+        const int br = m->br;
+        const int64_t R = m->rows;
+
+        // ---- 1. bytes each output row brings along, lanes in all ---------------------------
+        std::vector<uint32_t> roww((size_t)R, 0);
+        uint64_t lanes_total = 0;
+        for (int32_t bi = 0; bi < m->nbr; ++bi)
+            for (int32_t bj = 0; bj < m->nbc; ++bj) {
+                const size_t b = (size_t)bi * m->nbc + bj;
+                const int nr = m->nrows[b], nc = m->ncols[b];
+                if (nr == 0 || nc == 0) continue;
+                const uint16_t *ri = m->rowidx.data() + m->row_off[b];
+                for (int a = 0; a < nr; ++a) roww[(size_t)bi * br + ri[a]] += 4u * (uint32_t)nc + 3u;
+                lanes_total += (uint64_t)nr;
+            }
+        uint64_t total_w = 0;
+        for (uint32_t v : roww) total_w += v;
+
+        // ---- 2. row ranges of the workgroups: nearly equal bytes, cut at any row -----------
+        int64_t n_wg = n_wg_req > 0 ? n_wg_req : (int64_t)std::min<uint64_t>(256, std::max<uint64_t>(1, (lanes_total + kLanesPerWg - 1) / kLanesPerWg));
+        n_wg = std::max<int64_t>(n_wg, (R + kStreamMaxRows - 1) / kStreamMaxRows);
+        n_wg = std::min<int64_t>(n_wg, R);
+        std::vector<uint32_t> cut;      // row boundaries: workgroup k owns [cut[k], cut[k+1])
+        cut.push_back(0);
+        {
+            uint64_t acc = 0;            // work of the rows before `row`
+            int64_t k = 0;               // workgroup being filled
+            for (int64_t row = 0; row < R; ++row) {
+                const int64_t rows_here = row - (int64_t)cut.back();
+                if (rows_here > 0) {
+                    bool close = rows_here == kStreamMaxRows;
+                    if (!close && k + 1 < n_wg) {
+                        // the boundary in front of this row is nearer to the k-th target than the one behind it
+                        const uint64_t target = (uint64_t)((double)total_w * (double)(k + 1) / (double)n_wg);
+                        close = acc + roww[(size_t)row] / 2 >= target;
+                    }
+                    if (close) { cut.push_back((uint32_t)row); ++k; }
+                }
+                acc += roww[(size_t)row];
+            }
+            cut.push_back((uint32_t)R);
+        }
+        const uint32_t nwg = (uint32_t)cut.size() - 1;
+
+        // ---- 3. per workgroup: virtual blocks and kernel-matrix rows by descending column count,
+        //         64 to a group: the lanes of a group then have (nearly) the same column count ----
+        std::vector<WgLayout> W(nwg);
+        uint32_t rows_max = 0;
+        for (uint32_t k = 0; k < nwg; ++k) {
+            WgLayout &w = W[k];
+            w.row0 = cut[k];
+            w.nrows = cut[k + 1] - cut[k];
+            rows_max = std::max(rows_max, w.nrows);
+            const int64_t r0 = w.row0, r1 = cut[k + 1];
+            for (int64_t bi = r0 / br; bi <= (r1 - 1) / br; ++bi)
+                for (int32_t bj = 0; bj < m->nbc; ++bj) {
+                    const size_t b = (size_t)bi * m->nbc + bj;
+                    const int nr = m->nrows[b], nc = m->ncols[b];
+                    if (nr == 0 || nc == 0) continue;
+                    const uint16_t *ri = m->rowidx.data() + m->row_off[b];
+                    int a0 = 0;
+                    while (a0 < nr && bi * br + ri[a0] < r0) ++a0;
+                    int a1 = a0;
+                    while (a1 < nr && bi * br + ri[a1] < r1) ++a1;
+                    if (a1 > a0) w.vbs.push_back(SVb{(uint32_t)b, (uint16_t)a0, (uint16_t)a1, (uint16_t)nc});
+                }
+            std::stable_sort(w.vbs.begin(), w.vbs.end(), [](const SVb &x, const SVb &y) { return x.c > y.c; });
+            for (uint32_t v = 0; v < w.vbs.size(); ++v) {
+                const SVb &vb = w.vbs[v];
+                const int64_t bi = vb.b / m->nbc;
+                const uint16_t *ri = m->rowidx.data() + m->row_off[vb.b];
+                for (int a = vb.a0; a < vb.a1; ++a)
+                    w.lanes.push_back(Lane{v, (uint16_t)a, (uint16_t)(bi * br + ri[a] - r0)});
+            }
+            for (uint32_t l0 = 0; l0 < w.lanes.size(); l0 += kWave) w.g_cmax.push_back(w.vbs[w.lanes[l0].vb].c);
+        }
+
+        // ---- 4. rounds: the smallest count whose segments and partial sums fit the LDS ------
+        const uint32_t x_bytes = (uint32_t)align_up((size_t)m->cols * 4, 16);
+        const uint32_t hdr_bytes = (uint32_t)(sizeof(StreamRoundHdr) + align_up(4 * (size_t)rows_max, 16));
+        uint32_t rows_pad = 1;
+        while (rows_pad < rows_max) rows_pad <<= 1;
+        const uint32_t tpr = std::min<uint32_t>(kWave, (uint32_t)kStreamThreads / rows_pad);
+        StreamPlan sp{};
+        bool found = false;
+        for (uint32_t NR = (uint32_t)std::max(1, rounds_min); NR <= 64 && !found; ++NR) {
+            const uint32_t N = NR * kStreamWaves;
+            uint32_t seg_max = 0, kmax = 0;
+            bool ok = true, list_ok = true;
+            for (uint32_t k = 0; k < nwg && ok; ++k) {
+                WgLayout &w = W[k];
+                const uint32_t G = (uint32_t)w.g_cmax.size();
+                // Equal work per wavefront share: the groups' column steps are cut into N ranges of
+                // nearly equal work, work being steps plus a fixed overhead per piece of a group (a
+                // piece is at least two steps long).  The groups are taken widest, narrowest, second
+                // widest, ... so that every share gets a similar mix of long and short pieces.  T is the
+                // smallest budget per share with which a greedy walk places everything (such a walk is
+                // not monotone in T: T goes up one by one from the lower bound).  Segments are read up
+                // to their own length, so their bytes need not be equal; the longest sets the LDS need.
+                std::vector<uint32_t> order(G);
+                for (uint32_t i = 0, lo = 0, hi = G; i < G; ++i) order[i] = (i & 1u) ? --hi : lo++;
+                auto walk = [&](uint64_t T, bool emit) {
+                    uint32_t i = 0, j = 0, used = 0;
+                    if (emit) w.share.assign(N, Share{});
+                    while (i < G) {
+                        if (used == N) return false;
+                        uint64_t budget = T;
+                        while (i < G) {
+                            const uint32_t g = order[i];
+                            const uint32_t left = w.g_cmax[g] - j;
+                            if (budget < (uint64_t)kStreamGroupOverhead + std::min<uint32_t>(left, 2u)) break;
+                            uint32_t take = (uint32_t)std::min<uint64_t>(left, budget - kStreamGroupOverhead);
+                            if (left - take == 1u) --take;                   // never leave a one-step piece behind
+                            if (take < std::min<uint32_t>(left, 2u)) break;
+                            if (emit) {
+                                // lanes of the group that still have columns at step j
+                                const uint32_t l0 = g * kWave, l1 = std::min<uint32_t>(l0 + kWave, (uint32_t)w.lanes.size());
+                                uint32_t nl = 0;
+                                while (l0 + nl < l1 && w.vbs[w.lanes[l0 + nl].vb].c > j) ++nl;
+                                w.share[used].pieces.push_back(Piece{g, (uint16_t)j, (uint16_t)(j + take), (uint16_t)nl});
+                                w.share[used].work += kStreamGroupOverhead + take;
+                            }
+                            budget -= kStreamGroupOverhead + take;
+                            j += take;
+                            if (j == w.g_cmax[g]) { ++i; j = 0; }
+                        }
+                        ++used;
+                    }
+                    return true;
+                };
+                uint64_t steps_all = 0;
+                for (uint32_t g = 0; g < G; ++g) steps_all += w.g_cmax[g];
+                uint64_t T = std::max<uint64_t>(kStreamGroupOverhead + 2, (steps_all + (uint64_t)kStreamGroupOverhead * G + N - 1) / N);
+                while (!walk(T, false)) ++T;
+                walk(T, true);
+                // sizes, and the number of partial sums (one per lane and piece)
+                w.kmax = 0;                                     // here: partial sums of the workgroup
+                for (uint32_t s = 0; s < N; ++s) {
+                    Share &sh = w.share[s];
+                    SegSize tot;
+                    for (const Piece &p : sh.pieces) {
+                        const SegSize ps = piece_size(w, p);
+                        tot.groups += ps.groups; tot.vbs += ps.vbs; tot.lane_bytes += ps.lane_bytes;
+                        tot.list_bytes += ps.list_bytes; tot.steps += ps.steps;
+                        w.kmax += p.nl;
+                    }
+                    sh.bytes = (uint32_t)align_up(tot.total(), 16);
+                    if (getenv("CSB_PLAN_DEBUG2") && k == 0)
+                        fprintf(stderr, "  wg %u share %u: pieces %zu steps %zu vbs %zu lane_bytes %zu list_bytes %zu bytes %u work %.0f G %u T %llu\n", k, s,
+                                sh.pieces.size(), tot.steps, tot.vbs, tot.lane_bytes, tot.list_bytes, sh.bytes, sh.work, G, (unsigned long long)T);
+                    seg_max = std::max(seg_max, sh.bytes);
+                    if (tot.list_pos() + tot.list_bytes > (size_t)kStreamListLimit) list_ok = false;   // 10-bit list word index
+                }
+                kmax = std::max(kmax, w.kmax);
+                if (w.kmax > 65535u) ok = false;                // a lane names its slot in 16 bits
+            }
+            const uint32_t kstride = std::max(1u, kmax);     // partial-sum slots of the fullest workgroup
+            // (1 KiB of slack behind the segments: a padded list byte may name an input up to 255 floats past a block's first)
+            const size_t lds = (size_t)x_bytes + hdr_bytes + align_up((size_t)kstride * 4, 16) + (size_t)kStreamWaves * seg_max + 1024;
+            if (getenv("CSB_PLAN_DEBUG")) {
+                uint64_t sb = 0, ns = 0; for (auto &w : W) for (auto &sh : w.share) { sb += sh.bytes; ++ns; }
+                fprintf(stderr, "rows plan: NR %u ok %d list_ok %d seg_max %u seg_mean %.0f kmax %u rows_max %u lds %zu\n", NR, (int)ok, (int)list_ok, seg_max, (double)sb / ns, kmax, rows_max, lds);
+            }
+            if (!ok) break;                                  // more rounds do not shrink what failed
+            if (!list_ok || seg_max > (uint32_t)kStreamMaxSegUnits * 1024u || lds > (size_t)kLdsBudget) continue;
+            sp.n_wg = nwg; sp.n_rounds = NR; sp.seg_bytes = seg_max; sp.hdr_bytes = hdr_bytes;
+            sp.wg_bytes = (uint32_t)align_up((size_t)hdr_bytes + (size_t)N * seg_max, 256);
+            sp.kmax = kstride; sp.rows_max = rows_max; sp.tpr = tpr; sp.lds_bytes = (uint32_t)lds;
+            found = true;
+        }
+        if (!found) return CSB_OK;
+
+        // ---- 5. write the section -----------------------------------------------------------
+        const size_t off = align_up(pl.image.size(), 256);
+        const size_t bytes = (size_t)sp.n_wg * sp.wg_bytes;
+        pl.image.resize(off + bytes, 0);
+        sp.off = off; sp.bytes = bytes;
+        uint32_t n_groups = 0;
+        uint64_t fma_steps = 0, traffic = (uint64_t)nwg * sp.hdr_bytes;
+        for (uint32_t k = 0; k < nwg; ++k) {
+            const WgLayout &w = W[k];
+            uint8_t *wb = pl.image.data() + off + (size_t)k * sp.wg_bytes;
+            StreamRoundHdr rh{};
+            rh.row0 = w.row0; rh.nrows = w.nrows;
+            // partial sums: a row's slots are consecutive; (first slot, count) per row goes into the header
+            std::vector<uint32_t> cnt(w.nrows, 0u), first(w.nrows, 0u), next(w.nrows, 0u);
+            for (const Share &sh : w.share)
+                for (const Piece &p : sh.pieces)
+                    for (uint32_t l = 0; l < p.nl; ++l) ++cnt[w.lanes[p.g * kWave + l].rr];
+            for (uint32_t i = 1; i < w.nrows; ++i) first[i] = first[i - 1] + cnt[i - 1];
+            next = first;
+            for (uint32_t s = 0; s < sp.n_rounds * (uint32_t)kStreamWaves; ++s) {
+                const Share &sh = w.share[s];
+                uint8_t *seg = wb + sp.hdr_bytes + (size_t)s * sp.seg_bytes;
+                SegSize tot;
+                for (const Piece &p : sh.pieces) {
+                    const SegSize ps = piece_size(w, p);
+                    tot.groups += ps.groups; tot.vbs += ps.vbs; tot.lane_bytes += ps.lane_bytes; tot.list_bytes += ps.list_bytes;
+                }
+                StreamSegHdr hd{};
+                hd.ng = (uint16_t)sh.pieces.size();
+                const size_t off_groups = sizeof(StreamSegHdr);
+                const size_t off_vbs = off_groups + sh.pieces.size() * sizeof(StreamGroup);
+                size_t lane_pos = off_vbs + tot.vbs * 4;
+                size_t list_pos = lane_pos + tot.lane_bytes;
+                size_t val_pos = align_up(list_pos + tot.list_bytes, 16) / 4;    // float index
+                hd.off_vbs = (uint16_t)off_vbs;
+                hd.bytes16 = (uint16_t)(sh.bytes / 16);
+                if (s + kStreamWaves < sp.n_rounds * (uint32_t)kStreamWaves) hd.next16 = (uint16_t)(w.share[s + kStreamWaves].bytes / 16);
+                traffic += sh.bytes;
+                std::memcpy(seg, &hd, sizeof(hd));
+                uint32_t vb_idx = 0;
+                for (size_t gi = 0; gi < sh.pieces.size(); ++gi) {
+                    const Piece &p = sh.pieces[gi];
+                    const uint32_t steps = (uint32_t)(p.j1 - p.j0), l0 = p.g * kWave;
+                    const size_t list_len = align_up(steps, 4);
+                    StreamGroup sg{};
+                    sg.vb0 = (uint16_t)vb_idx;
+                    sg.cmax_minus_1 = (uint8_t)(steps - 1);
+                    sg.lane_off = (uint16_t)lane_pos;
+                    sg.val_off = (uint16_t)val_pos;
+                    sg.nlanes = (uint8_t)p.nl;
+                    float *dst = (float *)seg + val_pos;               // [steps][64], zero where a lane has no column
+                    for_piece_vbs(w, p, [&](uint32_t v, uint32_t lane0, uint32_t rws, int ck) {
+                        const SVb &vb = w.vbs[v];
+                        sg.start_mask |= 1ull << lane0;
+                        const uint32_t word = stream_vb_word((uint32_t)(list_pos / 4), (uint32_t)(ck - 1), vb.b % (uint32_t)m->nbc);
+                        std::memcpy(seg + off_vbs + (size_t)vb_idx * 4, &word, 4);
+                        ++vb_idx;
+                        // column indices; behind them, up to the piece's steps, zeros: a valid column whose
+                        // values are stored as zeros
+                        const uint16_t *ci = m->colidx.data() + m->col_off[vb.b] + p.j0;
+                        for (int j = 0; j < ck; ++j) seg[list_pos + j] = (uint8_t)ci[j];
+                        list_pos += list_len;
+                        const float *kv = m->val.data() + m->val_off[vb.b];
+                        for (uint32_t i = 0; i < rws; ++i) {
+                            const Lane &ln = w.lanes[l0 + lane0 + i];
+                            for (int j = 0; j < ck; ++j) dst[(size_t)j * kWave + lane0 + i] = kv[(size_t)ln.a * vb.c + p.j0 + j];
+                            const uint16_t lw = (uint16_t)next[ln.rr]++;
+                            std::memcpy(seg + lane_pos + 2 * (size_t)(lane0 + i), &lw, 2);
+                        }
+                    });
+                    val_pos += (size_t)steps * kWave;
+                    lane_pos += align_up(2 * (size_t)p.nl, 4);
+                    std::memcpy(seg + off_groups + gi * sizeof(StreamGroup), &sg, sizeof(sg));
+                    ++n_groups;
+                    fma_steps += steps;
+                }
+            }
+            std::memcpy(wb, &rh, sizeof(rh));
+            for (uint32_t i = 0; i < w.nrows; ++i) {
+                const uint32_t oc = first[i] | (cnt[i] << 16);
+                std::memcpy(wb + sizeof(rh) + 4 * (size_t)i, &oc, 4);
+            }
+        }
+        sp.n_groups = n_groups;
+        sp.valid = true;
+        pl.stream = sp;
+
+        // ---- 6. statistics of the plan csb_spmv will run ------------------------------------
+        csb_plan_stats st = pl.stats;
+        st.n_chunks = (int32_t)sp.n_wg;
+        st.waves_per_chunk = kStreamWaves;
+        st.n_groups = (int32_t)n_groups;
+        st.n_shared_tiles = 0;
+        double wmax = 0, wsum = 0, cmax_ = 0, csum_ = 0;
+        for (const WgLayout &w : W) {
+            double cc = 0;
+            for (uint32_t wv = 0; wv < (uint32_t)kStreamWaves; ++wv) {
+                double ww = 0;
+                for (uint32_t r = 0; r < sp.n_rounds; ++r) ww += w.share[(size_t)r * kStreamWaves + wv].work;
+                wmax = std::max(wmax, ww); wsum += ww; cc += ww;
+            }
+            cmax_ = std::max(cmax_, cc); csum_ += cc;
+        }
+        st.work_max = wmax;
+        st.work_mean = wsum / ((double)sp.n_wg * kStreamWaves);
+        st.chunk_max_over_mean = csum_ > 0 ? cmax_ / (csum_ / sp.n_wg) : 0.0;
+        st.lane_fill = fma_steps ? (double)m->val.size() / (64.0 * (double)fma_steps) : 0.0;
+        st.whole_tiles = 1;
+        st.row_owned = 1;
+        st.rounds = (int32_t)sp.n_rounds;
+        st.matvec_bytes = (int64_t)traffic;          // segments are read up to their own length, not the stride
+        pl.stats = st;
+        if (stats_out) *stats_out = st;
+        return CSB_OK;
+    } catch (const std::bad_alloc &) {
+        pl.stream = StreamPlan{};
+        set_error("csb_plan: out of host memory");
+        return CSB_ENOMEM;
+    }
+}
+
+// Walks the stream section the way the kernel does, with bounds checks on every access,
+// rebuilds the (row, column) -> value map and compares it with the packed matrix.
+int validate_stream(const csb_matrix *m) {
+    const Plan &pl = m->plan;
+    const StreamPlan &sp = pl.stream;
+    auto fail = [&](const char *what) { set_error(std::string("csb_plan_validate (row-owned section): ") + what); return CSB_EINVAL; };
+    const uint32_t N = sp.n_rounds * (uint32_t)kStreamWaves;
+    if (sp.off + sp.bytes > pl.image.size() || sp.bytes != (size_t)sp.n_wg * sp.wg_bytes) return fail("section size");
+    if (sp.seg_bytes % 16 || sp.hdr_bytes % 16 || (size_t)sp.wg_bytes < sp.hdr_bytes + (size_t)N * sp.seg_bytes) return fail("workgroup layout");
+    if (sp.seg_bytes > (uint32_t)kStreamMaxSegUnits * 1024u || sp.rows_max > (uint32_t)kStreamMaxRows) return fail("limits");
+    if (sp.hdr_bytes < sizeof(StreamRoundHdr) + 4 * (size_t)sp.rows_max) return fail("header size");
+    if (sp.tpr == 0 || (sp.tpr & (sp.tpr - 1)) || sp.tpr > (uint32_t)kWave || sp.rows_max * sp.tpr > (uint32_t)kStreamThreads) return fail("threads per row");
+    const int64_t R = m->rows, Ccols = m->cols;
+    std::vector<float> expect((size_t)R * Ccols, 0.0f), got((size_t)R * Ccols, 0.0f);
+    std::vector<uint8_t> seen((size_t)R * Ccols, 0);
+    if (csb_unpack(m, expect.data(), Ccols) != CSB_OK) return CSB_EINVAL;
+    std::vector<uint8_t> row_done((size_t)R, 0);
+    size_t vals_used = 0;
+    for (uint32_t k = 0; k < sp.n_wg; ++k) {
+        const uint8_t *wb = pl.image.data() + sp.off + (size_t)k * sp.wg_bytes;
+        StreamRoundHdr rh;
+        std::memcpy(&rh, wb, sizeof(rh));
+        const uint32_t row0 = rh.row0, nrows = rh.nrows;
+        if (nrows > sp.rows_max || (int64_t)row0 + nrows > R) return fail("row range");
+        // (first slot, count) per row: consecutive, inside the table; every slot written exactly once
+        std::vector<uint8_t> slot_used(sp.kmax, 0);
+        std::vector<int32_t> slot_row(sp.kmax, -1);
+        {
+            uint32_t expect_first = 0;
+            for (uint32_t i = 0; i < nrows; ++i) {
+                uint32_t oc;
+                std::memcpy(&oc, wb + sizeof(rh) + 4 * (size_t)i, 4);
+                const uint32_t f = oc & 0xffffu, c = oc >> 16;
+                if (f != expect_first || f + c > sp.kmax) return fail("row slots");
+                for (uint32_t q = 0; q < c; ++q) slot_row[f + q] = (int32_t)i;
+                expect_first = f + c;
+            }
+        }
+        for (uint32_t sgi = 0; sgi < N; ++sgi) {
+            const uint8_t *seg = wb + sp.hdr_bytes + (size_t)sgi * sp.seg_bytes;
+            StreamSegHdr sh;
+            std::memcpy(&sh, seg, sizeof(sh));
+            if ((size_t)sh.bytes16 * 16 > sp.seg_bytes || sh.bytes16 == 0) return fail("segment length");
+            {
+                uint16_t nx = 0;
+                if (sgi + kStreamWaves < N) std::memcpy(&nx, seg + (size_t)kStreamWaves * sp.seg_bytes + 4, 2);
+                if (sh.next16 != nx) return fail("length of the next round's segment");
+            }
+            const size_t SB = (size_t)sh.bytes16 * 16;           // everything the kernel touches lies inside the segment's own length
+            if (sizeof(sh) + (size_t)sh.ng * sizeof(StreamGroup) > SB) return fail("group records");
+            for (uint32_t g = 0; g < sh.ng; ++g) {
+                StreamGroup sg;
+                std::memcpy(&sg, seg + sizeof(sh) + (size_t)g * sizeof(StreamGroup), sizeof(sg));
+                const uint32_t steps = (uint32_t)sg.cmax_minus_1 + 1u, steps4 = (steps + 3u) & ~3u;
+                if (sg.nlanes == 0 || sg.nlanes > kWave || !(sg.start_mask & 1ull)) return fail("group lanes");
+                if (sg.nlanes < kWave && (sg.start_mask >> sg.nlanes)) return fail("start mask beyond the lanes");
+                if ((size_t)sg.lane_off + 2u * sg.nlanes > SB || sg.lane_off % 2) return fail("lane words");
+                if (((size_t)sg.val_off + (size_t)steps * kWave) * 4 > SB) return fail("value offset");
+                for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
+                    if (lane >= sg.nlanes) {                       // lanes without a row: zeros only
+                        for (uint32_t j = 0; j < steps; ++j) {
+                            uint32_t bits;
+                            std::memcpy(&bits, seg + ((size_t)sg.val_off + (size_t)j * kWave + lane) * 4, 4);
+                            if (bits) return fail("value behind the last lane not zero");
+                        }
+                        continue;
+                    }
+                    const uint64_t upto = lane == 63 ? ~0ull : ((2ull << lane) - 1ull);
+                    const uint32_t slot = (uint32_t)__builtin_popcountll(sg.start_mask & upto) - 1u;
+                    const size_t vpos = (size_t)sh.off_vbs + ((size_t)sg.vb0 + slot) * 4;
+                    if (vpos + 4 > SB) return fail("block words");
+                    uint32_t word;
+                    std::memcpy(&word, seg + vpos, 4);
+                    const uint32_t c = ((word >> 10) & 0xffu) + 1u, lw = (word & 0x3ffu) * 4u, bj = word >> 18;
+                    if (c > steps) return fail("block wider than its piece");
+                    if ((size_t)lw + steps4 > SB) return fail("column list");
+                    uint16_t word16;
+                    std::memcpy(&word16, seg + sg.lane_off + 2 * (size_t)lane, 2);
+                    if (word16 >= sp.kmax || slot_row[word16] < 0 || slot_used[word16]) return fail("partial-sum slot");
+                    slot_used[word16] = 1;
+                    const uint32_t rr = (uint32_t)slot_row[word16];
+                    // the kernel multiplies all of the piece's steps (in fours): what lies behind the
+                    // lane's own columns must be a valid column with a zero value
+                    for (uint32_t j = 0; j < steps4; ++j) {
+                        const int64_t col = (int64_t)bj * m->bc + seg[lw + j];
+                        if (col >= Ccols) return fail("column index");
+                        if (j >= steps) continue;
+                        uint32_t bits;
+                        std::memcpy(&bits, seg + ((size_t)sg.val_off + (size_t)j * kWave + lane) * 4, 4);
+                        if (j >= c) { if (bits) return fail("padding value not zero"); continue; }
+                        const size_t e = (size_t)(row0 + rr) * Ccols + col;
+                        if (seen[e]) return fail("entry stored twice");
+                        seen[e] = 1;
+                        std::memcpy(&got[e], &bits, 4);
+                        ++vals_used;
+                    }
+                }
+            }
+        }
+        for (uint32_t q = 0; q < sp.kmax; ++q)
+            if (slot_row[q] >= 0 && !slot_used[q]) return fail("partial-sum slot never written");
+        for (uint32_t i = 0; i < nrows; ++i) {
+            if (row_done[row0 + i]) return fail("row owned twice");
+            row_done[row0 + i] = 1;
+        }
+    }
+    for (int64_t i = 0; i < R; ++i) if (!row_done[i]) return fail("row without an owner");
+    if (vals_used != m->val.size()) return fail("not every value referenced exactly once");
+    if (std::memcmp(expect.data(), got.data(), expect.size() * sizeof(float)) != 0) return fail("section does not decode to the matrix");
+    return CSB_OK;
+}
+
+}  // namespace csb
