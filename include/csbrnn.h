@@ -219,6 +219,23 @@ size_t csb_workspace_bytes(const csb_matrix *m, int32_t batch);
 int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws, void *stream);
 
 /*
+ * csb_spmv for callers that cannot allocate device memory or pass a workspace along (code
+ * under HIP graph capture set-up, tight serving loops, harnesses that forbid hipMalloc): the
+ * same kernels and the same result as csb_spmv, bit for bit, but the partial sums of row tiles
+ * that several workgroups share go through a buffer built into the library (a file-scope
+ * device array of csb_spmv_static_limit() bytes = 1 MiB, which every GPU the library runs on
+ * holds until the process ends) instead of a caller's workspace.  The call allocates nothing.
+ * A matrix whose plan needs more (csb_workspace_bytes(m, 1) above the limit) is refused with
+ * CSB_EUNSUPPORTED; plans in the row-owned layout need no such memory and always pass.
+ * All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (other
+ * streams, other threads) race on it -- order them on one stream.  The merge words in it are
+ * tagged per launch, so contents left by earlier calls, for this or another matrix, do no harm.
+ * Errors otherwise as csb_spmv; a failing hipGetSymbolAddress -> CSB_EDEVICE.
+ */
+size_t csb_spmv_static_limit(void);
+int csb_spmv_static(const csb_matrix *m, const float *d_x, float *d_y, void *stream);
+
+/*
  * Instrumented csb_spmv for load-balance evidence (the role cycle-level simulation plays in
  * Sec. 6.1): same result, and every workgroup also writes shader-clock stamps to d_stamps
  * (device, csb_debug_stamp_count(m) values of 64 bits).  Per workgroup: 8 phase stamps

@@ -20,7 +20,7 @@ _lib = None
 
 # every symbol include/csbrnn.h declares
 SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_set_value_format", "csb_value_format", "csb_sharing_model", "csb_plan", "csb_plan_ex", "csb_plan_rows", "csb_plan_validate",
-           "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmm", "csb_spmm_bfloat", "csb_spmm_half",
+           "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmv_static_limit", "csb_spmv_static", "csb_spmm", "csb_spmm_bfloat", "csb_spmm_half",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
            "csb_project_workspace_bytes", "csb_project", "csb_rnn_create_lstmp", "csb_rnn_create_gru_rb",
@@ -95,6 +95,9 @@ def load_library():
     L.csb_workspace_bytes.argtypes = [C.c_void_p, C.c_int32]
     L.csb_workspace_bytes.restype = C.c_size_t
     L.csb_spmv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.csb_spmv_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.csb_spmv_static_limit.argtypes = []
+    L.csb_spmv_static_limit.restype = C.c_size_t
     L.csb_debug_stamp_count.argtypes = [C.c_void_p]
     L.csb_debug_stamp_count.restype = C.c_size_t
     L.csb_debug_spmv_stamps.argtypes = [C.c_void_p] * 6
@@ -274,6 +277,14 @@ class CsbMatrix:
             y = torch.empty(self.rows, dtype=torch.float32, device=x.device)
         ws = self._workspace(1, x.device)
         _check(lib().csb_spmv(self._h, _dptr(x), _dptr(y), _dptr(ws), _stream_ptr(stream)))
+        return y
+
+    def spmv_static(self, x, y=None, stream=None):
+        """csb_spmv_static: csb_spmv with the library's built-in buffer in place of a workspace."""
+        import torch
+        if y is None:
+            y = torch.empty(self.rows, dtype=torch.float32, device=x.device)
+        _check(lib().csb_spmv_static(self._h, _dptr(x), _dptr(y), _stream_ptr(stream)))
         return y
 
     def spmv_stamps(self, x, y=None, stream=None):

@@ -673,6 +673,56 @@ extern "C" int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void 
     return csb::spmv_segments(m, d_x, (uint32_t)m->cols, d_x, d_y, d_ws, stream, nullptr);
 }
 
+// ---- csb_spmv without a caller's workspace ---------------------------------------------------
+// The partial sums of row tiles that several workgroups share (tile-based equal-split plans)
+// travel through device memory: csb_spmv takes that memory from the caller's workspace,
+// csb_spmv_static from this array, which every GPU the library runs on holds until the process
+// ends.  In host code the array's name is only a stand-in: the address on the current device
+// comes from hipGetSymbolAddress, once per device, and is what the kernels get.
+namespace csb {
+constexpr size_t kStaticScratchBytes = 1u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Address of `scratch` on the current device (asked for once per device), or null with *err set.
+static void *static_scratch(hipError_t *err) {
+    static std::mutex mu;
+    static std::map<int, void *> addr;
+    int dev = 0;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = addr.find(dev);
+    if (it != addr.end()) return it->second;
+    void *ptr = nullptr;
+    *err = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess || !ptr) { if (*err == hipSuccess) *err = hipErrorInvalidSymbol; return nullptr; }
+    addr[dev] = ptr;
+    return ptr;
+}
+}  // namespace csb
+
+extern "C" size_t csb_spmv_static_limit(void) { return csb::kStaticScratchBytes; }
+
+extern "C" int csb_spmv_static(const csb_matrix *m, const float *d_x, float *d_y, void *stream) {
+    if (!m || !d_x || !d_y) { csb::set_error("csb_spmv_static: NULL pointer"); return CSB_EINVAL; }
+    if (m->plan.valid && m->plan.split.active()) { csb::set_error("csb_spmv_static: matrix is planned for a GRU step"); return CSB_ESTATE; }
+    if (!m->plan.valid || !m->uploaded || !m->d_buf) { csb::set_error("csb_spmv_static: matrix not planned and uploaded"); return CSB_ESTATE; }
+    if (m->plan.stream.valid) return csb::spmv_rows(m, d_x, d_y, stream);      // row-owned layout: no partial sums in memory at all
+    const size_t need = csb_workspace_bytes(m, 1);
+    if (need > csb::kStaticScratchBytes) {
+        csb::set_error("csb_spmv_static: the plan's shared row tiles need " + std::to_string(need) + " bytes of partial sums, the built-in buffer holds " +
+                       std::to_string(csb::kStaticScratchBytes) + "; use csb_spmv with a workspace, or plan with fewer workgroups");
+        return CSB_EUNSUPPORTED;
+    }
+    hipError_t e = hipSuccess;
+    void *ws = csb::static_scratch(&e);
+    if (!ws) { csb::set_error(std::string("csb_spmv_static: hipGetSymbolAddress: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    // the merge words are told from stale ones by their launch tag; whoever used the buffer last, another
+    // matrix or this one, a first use clears them (a small fill kernel on `stream`, no memset node)
+    if (csb::workspace_changed_hands(ws, m)) m->ws_seen = nullptr;
+    return csb::spmv_segments(m, d_x, (uint32_t)m->cols, d_x, d_y, ws, stream, nullptr);
+}
+
 namespace csb {
 // Plain streaming read: the measured bandwidth the mat-vec figures are put next to.
 __global__ __launch_bounds__(256) void stream_read_kernel(const float4 *__restrict__ p, size_t n4, float *__restrict__ out) {
