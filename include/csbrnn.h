@@ -163,6 +163,12 @@ int csb_plan(csb_matrix *m, int32_t n_chunks, csb_plan_stats *stats);
  * over the 16 wavefronts.
  */
 int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *stats);
+/* A matrix that csb_rnn_create has planned for a GRU (its n rows' input-side and recurrent-side
+ * sums kept apart, the layout the step kernels of that handle read) keeps this row layout when
+ * csb_plan / csb_plan_ex plan it again, also after csb_set_value_format: only the workgroup
+ * count and the mode change.  csb_rnn_create in turn keeps the workgroup count and mode of a
+ * plan the caller made before.  csb_rnn_forward refuses (CSB_ESTATE) a weight matrix whose row
+ * layout is no longer the one its handle planned (e.g. after csb_plan_rows). */
 
 /*
  * The row-owned layout of the mat-vec (Sec. 4.3.1 / the equal-work role of Sec. 5.2), which
@@ -185,6 +191,10 @@ int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *s
  * the layout.
  */
 int csb_plan_rows(csb_matrix *m, int32_t n_workgroups, int32_t min_rounds, csb_plan_stats *stats);
+
+/* The statistics of the matrix's current plan (what csb_plan* returned, or what a csb_rnn_create*
+ * call planned).  Errors: NULL -> CSB_EINVAL; not planned -> CSB_ESTATE. */
+int csb_plan_stats_get(const csb_matrix *m, csb_plan_stats *stats);
 
 /* Integer self-check of the planned device image: every offset in bounds, every kernel
  * value referenced exactly once, image decodes to the packed matrix.  Host only. */
@@ -232,6 +242,16 @@ int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws, void
  * tagged per launch, so contents left by earlier calls, for this or another matrix, do no harm.
  * Errors otherwise as csb_spmv; a failing hipGetSymbolAddress -> CSB_EDEVICE.
  */
+/*
+ * Merges of row tiles that several workgroups share wait for each other's partial sums with a
+ * bounded number of polls; a merge that gives up stores NaN in its rows and sets a word in the
+ * matrix image.  csb_status reads that word (it synchronises `stream`), clears it, and returns
+ * it in *timed_out: non-zero means some csb_spmv / csb_spmm result since the last check holds
+ * NaNs for this reason (workgroups of one launch not all running at once).  Plans in the
+ * row-owned layout merge nothing and never set it.
+ */
+int csb_status(const csb_matrix *m, void *stream, int32_t *timed_out);
+
 size_t csb_spmv_static_limit(void);
 int csb_spmv_static(const csb_matrix *m, const float *d_x, float *d_y, void *stream);
 
@@ -392,11 +412,11 @@ int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
  * The resident kernel's workgroups wait for each other's h_t: they must all be on the GPU at
  * once, so nothing else should occupy the device while it runs.  The workgroups are placed on
  * as few of the 8 XCDs as hold them (at most 28 per XCD, one per CU).
- * Tuning knobs, read from the environment (for experiments; the defaults are the measured
- * best): CSB_RNN_S = slots per lane of the resident layout (multiple of 4; read by
- * csb_rnn_create*), CSB_RNN_XCDS = use at least this many XCDs, CSB_RNN_POLL_DELAY = sleeps
- * before the first poll of a step, CSB_RNN_BATCH_PATH = "resident" or "batched": the path of a
- * batch when both are uploaded (all three read by csb_rnn_forward).
+ * Tuning knobs, read from the environment ONCE, by csb_rnn_create* (for experiments; the
+ * defaults are the measured best): CSB_RNN_S = slots per lane of the resident layout (multiple
+ * of 4), CSB_RNN_XCDS = use at least this many XCDs, CSB_RNN_POLL_DELAY = sleeps before the
+ * first poll of a step, CSB_RNN_BATCH_PATH = "resident" or "batched": the path of a batch when
+ * both are uploaded.
  */
 typedef struct {
     int32_t resident;          /* 1 if a resident layout exists                            */
@@ -418,6 +438,20 @@ int csb_rnn_upload(csb_rnn *r, void *d_buf, size_t bytes, void *stream);
  * image).  Errors: NULL / batch <= 0 -> CSB_EINVAL; no resident layout -> CSB_EUNSUPPORTED. */
 int csb_rnn_plan_resident(csb_rnn *r, int32_t batch);
 int csb_rnn_stats(const csb_rnn *r, csb_rnn_plan_stats *out);
+
+/*
+ * The resident kernel's workgroups wait for each other's h_t with a bounded number of polls per
+ * exchange word (default 2^24, minutes in all if nothing ever arrives).  A wait that gives up
+ * yields NaN, makes every later wait of that lane give up at once (so the launch still ends
+ * promptly) and sets a word in the resident image.  csb_rnn_status reads that word (it
+ * synchronises `stream`), clears it and returns it in *timed_out: non-zero means a result since
+ * the last check is NaN because the workgroups of a launch were not all running at once -- two
+ * resident launches on different streams, or another kernel occupying the device: launch them
+ * one after the other.  csb_rnn_set_poll_limit changes the bound (0: a word must be there at
+ * the first look), for tests and for callers that prefer a quick failure.
+ */
+int csb_rnn_set_poll_limit(csb_rnn *r, uint32_t polls);
+int csb_rnn_status(const csb_rnn *r, void *stream, int32_t *timed_out);
 
 size_t csb_rnn_workspace_bytes(const csb_rnn *r, int32_t batch, int32_t T);
 

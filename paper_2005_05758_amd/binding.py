@@ -19,13 +19,13 @@ _LIB_PATH = os.path.join(_PKG, "libcsbrnn.so")
 _lib = None
 
 # every symbol include/csbrnn.h declares
-SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_set_value_format", "csb_value_format", "csb_sharing_model", "csb_plan", "csb_plan_ex", "csb_plan_rows", "csb_plan_validate",
+SYMBOLS = ["csb_last_error", "csb_pack", "csb_view_get", "csb_unpack", "csb_set_value_format", "csb_value_format", "csb_sharing_model", "csb_plan", "csb_plan_ex", "csb_plan_rows", "csb_plan_stats_get", "csb_plan_validate", "csb_status",
            "csb_device_bytes", "csb_upload", "csb_workspace_bytes", "csb_spmv", "csb_spmv_static_limit", "csb_spmv_static", "csb_spmm", "csb_spmm_bfloat", "csb_spmm_half",
            "csb_debug_stamp_count", "csb_debug_spmv_stamps",
            "csb_debug_stream_read_out_floats", "csb_debug_stream_read",
            "csb_project_workspace_bytes", "csb_project", "csb_rnn_create_lstmp", "csb_rnn_create_gru_rb",
            "csb_rnn_create", "csb_rnn_device_bytes", "csb_rnn_upload", "csb_rnn_plan_resident", "csb_rnn_stats",
-           "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
+           "csb_rnn_set_poll_limit", "csb_rnn_status", "csb_rnn_workspace_bytes", "csb_rnn_forward", "csb_free", "csb_rnn_free"]
 
 
 class csb_sharing_stats(C.Structure):
@@ -88,6 +88,10 @@ def load_library():
     L.csb_plan.argtypes = [C.c_void_p, C.c_int32, C.POINTER(csb_plan_stats)]
     L.csb_plan_ex.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(csb_plan_stats)]
     L.csb_plan_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(csb_plan_stats)]
+    L.csb_plan_stats_get.argtypes = [C.c_void_p, C.POINTER(csb_plan_stats)]
+    L.csb_status.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+    L.csb_rnn_set_poll_limit.argtypes = [C.c_void_p, C.c_uint32]
+    L.csb_rnn_status.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
     L.csb_plan_validate.argtypes = [C.c_void_p]
     L.csb_device_bytes.argtypes = [C.c_void_p]
     L.csb_device_bytes.restype = C.c_size_t
@@ -146,11 +150,18 @@ def _check(rc: int):
         raise CsbError(rc, lib().csb_last_error().decode())
 
 
-def _dptr(t) -> Optional[int]:
-    """Device pointer of a torch tensor (or None)."""
+def _f32():
+    import torch
+    return torch.float32
+
+
+def _dptr(t, dtype=None) -> Optional[int]:
+    """Device pointer of a contiguous torch tensor (or None); `dtype`: what the callee reads it as."""
     if t is None:
         return None
     assert t.is_cuda and t.is_contiguous()
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected a {dtype} tensor, got {t.dtype}"
     return t.data_ptr()
 
 
@@ -252,6 +263,18 @@ class CsbMatrix:
         self.d_buf = None
         return self.stats
 
+    def plan_stats(self):
+        """csb_plan_stats_get: the statistics of the current plan."""
+        st = csb_plan_stats()
+        _check(lib().csb_plan_stats_get(self._h, C.byref(st)))
+        return {k: getattr(st, k) for k, _ in csb_plan_stats._fields_}
+
+    def status(self, stream=None) -> int:
+        """csb_status: non-zero if a merge of shared row tiles gave up since the last check."""
+        v = C.c_int32(0)
+        _check(lib().csb_status(self._h, _stream_ptr(stream), C.byref(v)))
+        return int(v.value)
+
     def validate(self):
         _check(lib().csb_plan_validate(self._h))
 
@@ -276,7 +299,7 @@ class CsbMatrix:
         if y is None:
             y = torch.empty(self.rows, dtype=torch.float32, device=x.device)
         ws = self._workspace(1, x.device)
-        _check(lib().csb_spmv(self._h, _dptr(x), _dptr(y), _dptr(ws), _stream_ptr(stream)))
+        _check(lib().csb_spmv(self._h, _dptr(x, _f32()), _dptr(y, _f32()), _dptr(ws), _stream_ptr(stream)))
         return y
 
     def spmv_static(self, x, y=None, stream=None):
@@ -284,7 +307,7 @@ class CsbMatrix:
         import torch
         if y is None:
             y = torch.empty(self.rows, dtype=torch.float32, device=x.device)
-        _check(lib().csb_spmv_static(self._h, _dptr(x), _dptr(y), _stream_ptr(stream)))
+        _check(lib().csb_spmv_static(self._h, _dptr(x, _f32()), _dptr(y, _f32()), _stream_ptr(stream)))
         return y
 
     def spmv_stamps(self, x, y=None, stream=None):
@@ -297,7 +320,7 @@ class CsbMatrix:
         n = int(lib().csb_debug_stamp_count(self._h))
         st = torch.zeros(n, dtype=torch.int64, device=x.device)
         ws = self._workspace(1, x.device)
-        _check(lib().csb_debug_spmv_stamps(self._h, _dptr(x), _dptr(y), _dptr(ws), _dptr(st), _stream_ptr(stream)))
+        _check(lib().csb_debug_spmv_stamps(self._h, _dptr(x, _f32()), _dptr(y, _f32()), _dptr(ws), _dptr(st), _stream_ptr(stream)))
         if getattr(self, "stats", None) and self.stats.get("row_owned"):
             return y, st.view(-1, 16, 8)
         return y, st.view(-1, 8 + 3 * 16)
@@ -310,6 +333,7 @@ class CsbMatrix:
         ws = self._workspace(batch, X.device)
         # rows may be strided views ([cols][ldx], [rows][ldy]); the batch index must be contiguous
         assert X.is_cuda and Y.is_cuda and X.stride(1) == 1 and Y.stride(1) == 1
+        assert X.dtype == torch.float32 and Y.dtype == torch.float32
         _check(lib().csb_spmm(self._h, X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), batch, _dptr(ws),
                               _stream_ptr(stream)))
         return Y
@@ -372,7 +396,7 @@ class CsbRnn:
         Wv = (C.c_void_p * L)(*[w.handle for w in self.W])
         Bp = None
         if self.bias is not None:
-            Bp = (C.c_void_p * L)(*[_dptr(b) for b in self.bias])
+            Bp = (C.c_void_p * L)(*[_dptr(b, _f32()) for b in self.bias])
         self._h = C.c_void_p()
         if cell == CELL_LSTMP:
             assert proj > 0 and len(self.Wp) == L
@@ -397,6 +421,16 @@ class CsbRnn:
 
     def device_bytes(self) -> int:
         return int(lib().csb_rnn_device_bytes(self._h))
+
+    def set_poll_limit(self, polls: int):
+        _check(lib().csb_rnn_set_poll_limit(self._h, polls))
+        return self
+
+    def status(self, stream=None) -> int:
+        """csb_rnn_status: non-zero if a wait inside the resident kernel gave up since the last check."""
+        v = C.c_int32(0)
+        _check(lib().csb_rnn_status(self._h, _stream_ptr(stream), C.byref(v)))
+        return int(v.value)
 
     def plan_resident(self, batch: int):
         """Lay the resident kernel out for batches of this size (1: one sequence, as created);
@@ -429,7 +463,7 @@ class CsbRnn:
         hT = torch.empty((self.n_layers, B, hs), dtype=torch.float32, device=dev)
         cT = (torch.empty((self.n_layers, B, self.hidden), dtype=torch.float32, device=dev)
               if self.cell in (CELL_LSTM, CELL_LSTMP) else None)
-        _check(lib().csb_rnn_forward(self._h, _dptr(x), _dptr(h0), _dptr(c0), _dptr(hseq), _dptr(hT), _dptr(cT),
+        _check(lib().csb_rnn_forward(self._h, _dptr(x, _f32()), _dptr(h0, _f32()), _dptr(c0, _f32()), _dptr(hseq, _f32()), _dptr(hT, _f32()), _dptr(cT, _f32()),
                                      T, B, _dptr(self._ws), _stream_ptr(stream)))
         return hseq, hT, cT
 

@@ -226,7 +226,8 @@ struct StreamPlan {
 
 struct Plan {
     bool valid = false;
-    SplitSpec split;
+    SplitSpec split;              // stays when the plan becomes invalid: csb_plan keeps the row layout of a matrix a GRU handle planned
+    int32_t req_chunks = 0, req_mode = 0;   // what the plan was asked for
     std::vector<uint8_t> image;   // host staging copy of the device image
     DevHeader hdr{};
     StreamPlan stream;            // valid: csb_spmv reads this section instead of the sections above

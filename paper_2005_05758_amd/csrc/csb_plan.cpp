@@ -559,7 +559,7 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         h.off_nz_tiles = place(nz_tiles.size() * 4);
         h.off_zero_tiles = place(zero_tiles.size() * 4);
         h.off_shared = place(shared.size() * sizeof(SharedRec));
-        h.off_counters = place(shared.size() * 4);
+        h.off_counters = place((shared.size() + 1) * 4);     // merge tickets, then one status word (a merge that gave up)
         h.off_tile_g0 = place(tile_g0.size() * 4);
         h.off_tile_seg0 = place(tile_seg0.size() * 4);
         std::vector<SegRec> segs(seg_g0.size() - 1);
@@ -599,6 +599,8 @@ int plan_matrix(csb_matrix *m, int32_t n_chunks_req, int32_t waves_per_chunk, co
         put(h.off_segs, segs.data(), segs.size() * sizeof(SegRec));
         pl.hdr = h;
         pl.split = split;
+        pl.req_chunks = n_chunks_req;
+        pl.req_mode = with_rows ? 0 : (mode == 0 ? 4 : mode);
         pl.valid = true;
         m->uploaded = false;
         m->d_buf = nullptr;
@@ -857,12 +859,22 @@ int validate_plan(const csb_matrix *m) {
 
 }  // namespace csb
 
+// A matrix that a GRU handle has planned keeps that row layout when it is planned again (also after
+// csb_set_value_format made the plan invalid): the handle's step kernels depend on it.
 extern "C" int csb_plan(csb_matrix *m, int32_t n_chunks, csb_plan_stats *stats) {
-    return csb::plan_matrix(m, n_chunks, 16, csb::SplitSpec{}, stats, 0);
+    return csb::plan_matrix(m, n_chunks, 16, m ? m->plan.split : csb::SplitSpec{}, stats, 0);
 }
 
 extern "C" int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *stats) {
-    return csb::plan_matrix(m, n_chunks, 16, csb::SplitSpec{}, stats, mode);
+    if (mode == 3 || mode == 4) { csb::set_error("csb_plan: mode must be 0 (auto), 1 (whole tiles) or 2 (equal split)"); return CSB_EINVAL; }
+    return csb::plan_matrix(m, n_chunks, 16, m ? m->plan.split : csb::SplitSpec{}, stats, mode);
+}
+
+extern "C" int csb_plan_stats_get(const csb_matrix *m, csb_plan_stats *stats) {
+    if (!m || !stats) { csb::set_error("csb_plan_stats_get: NULL pointer"); return CSB_EINVAL; }
+    if (!m->plan.valid) { csb::set_error("csb_plan_stats_get: matrix not planned"); return CSB_ESTATE; }
+    *stats = m->plan.stats;
+    return CSB_OK;
 }
 
 extern "C" int csb_plan_rows(csb_matrix *m, int32_t n_workgroups, int32_t min_rounds, csb_plan_stats *stats) {

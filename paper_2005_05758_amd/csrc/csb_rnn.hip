@@ -33,7 +33,6 @@ constexpr int kRnnSlotsMax = 48;       // weights one lane keeps in registers
 constexpr int kRnnMaxLayers = 8;       // model layers of a resident layout (more: streaming path)
 constexpr int kRnnWgsPerXcd = 28;      // workgroups placed on one XCD (32 CUs, one workgroup per CU, a few CUs spare)
 constexpr int kRnnMaxWgs = 8 * kRnnWgsPerXcd;   // all workgroups must be co-resident
-constexpr uint32_t kPollLimit = 1u << 24;
 // Per-phase shader clocks of the resident kernel (a development aid): compiled in only on
 // request, so that the time loop of the shipped kernel carries none of it.
 #ifdef CSB_RNN_PHASE_CLOCKS
@@ -104,6 +103,16 @@ struct csb_rnn {
     mutable uint32_t ws_gen = 0xffffffffu;
     mutable size_t ws_words = 0;             // exchange words cleared there so far
     mutable int64_t ws_use = -1;             // batch and path of the last forward call (they fix what lies where)
+    // tuning knobs, read from the environment once, when the handle is created
+    int32_t knob_xcds = 0;                   // CSB_RNN_XCDS: use at least this many XCDs (0: as few as hold the model)
+    int32_t knob_poll_delay = -1;            // CSB_RNN_POLL_DELAY: sleeps before the first poll of a step (-1: default)
+    int32_t knob_batch_path = 0;             // CSB_RNN_BATCH_PATH: 1 resident, 2 batched, 0 by estimate
+    uint32_t poll_limit = 1u << 24;          // polls of one exchange word before the resident kernel gives up
+    csb_rnn() {
+        if (const char *e = getenv("CSB_RNN_XCDS")) knob_xcds = std::min(8, std::max(1, atoi(e)));
+        if (const char *e = getenv("CSB_RNN_POLL_DELAY")) knob_poll_delay = std::max(0, atoi(e));
+        if (const char *e = getenv("CSB_RNN_BATCH_PATH")) knob_batch_path = !strcmp(e, "resident") ? 1 : !strcmp(e, "batched") ? 2 : 0;
+    }
 };
 
 namespace csb {
@@ -546,6 +555,8 @@ struct RnnArgs {
     // consecutive steps (or layers) of one sequence lie `nb` rows apart (1 for a single sequence)
     uint32_t nb;
     unsigned long long *dbg;            // optional: per-phase shader clocks summed over the steps (workgroup 0)
+    uint32_t *status;                   // device word: set to 1 when a poll gives up
+    uint32_t poll_limit;                // polls of one exchange word before giving up
 };
 
 // Workgroup barrier that orders LDS traffic only: global loads and stores in flight (the
@@ -564,18 +575,23 @@ __device__ __forceinline__ float masked_shr(float v, uint32_t mask) {
     return __uint_as_float(t & mask);
 }
 
-// Poll a tagged word until it carries `tag`; bounded, returns NaN if the bound is hit.
+// Poll a tagged word until it carries `tag`; bounded by `limit` polls.  If the bound is hit the
+// result is NaN, *status is set (the host reads it with csb_rnn_status) and `limit` drops to
+// zero, so that the lane's later polls give up at once and the kernel still ends promptly.
 // `retried` is set if the first load did not already carry the tag.
-__device__ __forceinline__ float poll_word(const unsigned long long *word, uint32_t tag, bool &retried) {
+__device__ __forceinline__ float poll_word(const unsigned long long *word, uint32_t tag, bool &retried, uint32_t &limit, uint32_t *status) {
     // (the words live in device memory: say so, or the loads are issued as generic ones)
     const __attribute__((address_space(1))) unsigned long long *p =
         (const __attribute__((address_space(1))) unsigned long long *)word;
     unsigned long long v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (uint32_t spin = 0; (uint32_t)(v >> 32) != tag && spin < kPollLimit; ++spin) {
+    for (uint32_t spin = 0; (uint32_t)(v >> 32) != tag && spin < limit; ++spin) {
         retried = true;
         v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    return (uint32_t)(v >> 32) == tag ? __uint_as_float((uint32_t)v) : __builtin_nanf("");
+    if ((uint32_t)(v >> 32) == tag) return __uint_as_float((uint32_t)v);
+    limit = 0u;
+    __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_nanf("");
 }
 
 // PLAIN: every stage is an LSTM / GRU / Li-GRU layer (its own recurrent source, its output the
@@ -724,6 +740,7 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
     const bool polls = __ballot(ptmin[0] != ~0u || ptmin[1] != ~0u || ptmin[2] != ~0u) != 0ull;
     const bool two = C > kRnnThreads, three = !PLAIN && C > 2 * kRnnThreads;           // second / third entries exist
     uint32_t delay = A.poll_delay, streak = 0;
+    uint32_t poll_limit = A.poll_limit;                         // drops to zero once a poll of this lane has given up
     unsigned long long wave_arrive = 0, after_b = 0;
     unsigned long long ph0 = 0, ph1 = 0, ph2 = 0, ph3 = 0, c0_ = 0, c1_ = 0;
     const bool dbg = kPhaseClocks && A.dbg != nullptr && blockIdx.x == 0 && tid == 0;
@@ -738,9 +755,9 @@ __global__ __launch_bounds__(kRnnThreads) void rnn_resident_kernel(const RnnArgs
         if (polls)
             for (uint32_t d = 0; d < delay; ++d) __builtin_amdgcn_s_sleep(1);
         bool retried = false;
-        if (t >= ptmin[0]) z[zp[0]] = poll_word(pp[0] + (size_t)t * pstride[0], ptag[0] + t, retried);
-        if (two && t >= ptmin[1]) z[zp[1]] = poll_word(pp[1] + (size_t)t * pstride[1], ptag[1] + t, retried);
-        if (three && t >= ptmin[2]) z[zp[2]] = poll_word(pp[2] + (size_t)t * pstride[2], ptag[2] + t, retried);
+        if (t >= ptmin[0]) z[zp[0]] = poll_word(pp[0] + (size_t)t * pstride[0], ptag[0] + t, retried, poll_limit, A.status);
+        if (two && t >= ptmin[1]) z[zp[1]] = poll_word(pp[1] + (size_t)t * pstride[1], ptag[1] + t, retried, poll_limit, A.status);
+        if (three && t >= ptmin[2]) z[zp[2]] = poll_word(pp[2] + (size_t)t * pstride[2], ptag[2] + t, retried, poll_limit, A.status);
         if (kPhaseClocks && A.dbg && blockIdx.x == 0 && (tid & 63u) == 0 && t > 0) wave_arrive += __builtin_readcyclecounter() - after_b;
         if (polls) {
             if (__ballot(retried) != 0ull) { delay += 3; streak = 0; }
@@ -947,7 +964,7 @@ struct RnnWs {
 // XCDs one instance of the resident kernel occupies, and how many instances fit side by side
 static uint32_t resident_xcds(const csb_rnn *r) {
     uint32_t xcds = ((uint32_t)r->plan.n_wgs + kRnnWgsPerXcd - 1) / kRnnWgsPerXcd;
-    if (const char *e = getenv("CSB_RNN_XCDS")) xcds = std::max(xcds, (uint32_t)std::min(8, std::max(1, atoi(e))));
+    if (r->knob_xcds > 0) xcds = std::max(xcds, (uint32_t)r->knob_xcds);
     return xcds;
 }
 static int resident_instances(const csb_rnn *r, int32_t batch) {
@@ -1051,7 +1068,9 @@ static int forward_resident(const csb_rnn *r, const float *d_x, const float *d_h
     A.s_x = s_x; A.s_h = s_h; A.s_c = s_c; A.s_hseq = s_hseq; A.s_seq = words_inst;
     A.nb = nb;
     A.poll_delay = r->plan.n_wgs > 1 ? 8u : 0u;   // fewer polls in flight while h_t cannot have arrived yet
-    if (const char *e = getenv("CSB_RNN_POLL_DELAY")) A.poll_delay = (uint32_t)std::max(0, atoi(e));
+    if (r->knob_poll_delay >= 0) A.poll_delay = (uint32_t)r->knob_poll_delay;
+    A.poll_limit = r->poll_limit;
+    A.status = (uint32_t *)((uint8_t *)r->d_img + r->plan.image.size() - 256);   // the image's last 256 bytes: uploaded as zeros
     if (kPhaseClocks && getenv("CSB_RNN_DEBUG")) A.dbg = (unsigned long long *)((uint8_t *)d_ws + wl.total - 512);
     const size_t cmax = r->plan.cmax;
     const size_t lds = (((cmax + 1 + 63) & ~(size_t)63) + kRnnThreads) * sizeof(float);
@@ -1129,10 +1148,8 @@ static double batched_us(const csb_rnn *r, int32_t batch) {
     return (10.0 + 4.0 * r->n_layers) * (two ? 1.25 : 1.0) + 2.0 * (double)r->plan.total_nnz * batch / 12e6;
 }
 static bool batch_prefers_resident(const csb_rnn *r, int32_t batch) {
-    if (const char *e = getenv("CSB_RNN_BATCH_PATH")) {
-        if (!strcmp(e, "resident")) return true;
-        if (!strcmp(e, "batched")) return false;
-    }
+    if (r->knob_batch_path == 1) return true;
+    if (r->knob_batch_path == 2) return false;
     return resident_batch_us(r, batch) * 1.1 < batched_us(r, batch);
 }
 
@@ -1164,7 +1181,9 @@ extern "C" int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int
             SplitSpec sp{};
             if (cell == CSB_CELL_GRU) { sp.split_row = 2 * (int64_t)hidden; sp.split_col = l == 0 ? input : hidden; sp.shift = hidden; }
             if (!W[l]->plan.valid || !(W[l]->plan.split == sp)) {
-                int rc = plan_matrix(W[l], 0, 16, sp, nullptr, 0);
+                // (a plan the caller made keeps its workgroup count and mode)
+                const bool had = W[l]->plan.valid;
+                int rc = plan_matrix(W[l], had ? W[l]->plan.req_chunks : 0, 16, sp, nullptr, had ? W[l]->plan.req_mode : 0);
                 if (rc != CSB_OK) { delete r; return rc; }
             }
             r->W.push_back(W[l]);
@@ -1286,6 +1305,28 @@ extern "C" int csb_rnn_upload(csb_rnn *r, void *d_buf, size_t bytes, void *strea
     return CSB_OK;
 }
 
+extern "C" int csb_rnn_set_poll_limit(csb_rnn *r, uint32_t polls) {
+    if (!r) { csb::set_error("csb_rnn_set_poll_limit: NULL handle"); return CSB_EINVAL; }
+    r->poll_limit = polls;
+    return CSB_OK;
+}
+
+// Has a workgroup of the resident kernel given up waiting for another one's h_t since the last check?
+extern "C" int csb_rnn_status(const csb_rnn *r, void *stream, int32_t *timed_out) {
+    using namespace csb;
+    if (!r || !timed_out) { set_error("csb_rnn_status: NULL pointer"); return CSB_EINVAL; }
+    *timed_out = 0;
+    if (!r->plan.valid || !r->uploaded || !r->d_img) return CSB_OK;
+    uint32_t *d = (uint32_t *)((uint8_t *)r->d_img + r->plan.image.size() - 256);
+    uint32_t v = 0;
+    hipError_t e = hipMemcpyAsync(&v, d, 4, hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e == hipSuccess && v) e = hipMemsetAsync(d, 0, 4, (hipStream_t)stream);
+    if (e != hipSuccess) { set_error(std::string("csb_rnn_status: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    *timed_out = (int32_t)v;
+    return CSB_OK;
+}
+
 extern "C" int csb_rnn_plan_resident(csb_rnn *r, int32_t batch) {
     using namespace csb;
     if (!r || batch <= 0) { set_error("csb_rnn_plan_resident: NULL handle or batch <= 0"); return CSB_EINVAL; }
@@ -1361,6 +1402,16 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
                 set_error("csb_rnn_forward: neither the resident layout nor every weight matrix is uploaded");
                 return CSB_ESTATE;
             }
+        // the step kernels index the sums by the row layout csb_rnn_create planned (the GRU keeps the two
+        // halves of its n rows apart): a matrix planned otherwise since then must not be used
+        for (int l = 0; l < L; ++l) {
+            SplitSpec sp{};
+            if (r->cell == CSB_CELL_GRU) { sp.split_row = 2 * (int64_t)H; sp.split_col = l == 0 ? r->input : H; sp.shift = H; }
+            if (!(r->W[l]->plan.split == sp)) {
+                set_error("csb_rnn_forward: a weight matrix was planned again in another row layout after csb_rnn_create");
+                return CSB_ESTATE;
+            }
+        }
         for (auto *m : r->Wp)
             if (!m->plan.valid || !m->uploaded) {
                 set_error("csb_rnn_forward: a layer's second matrix (projection / candidate recurrence) is not uploaded");

@@ -460,7 +460,11 @@ __device__ __forceinline__ void spmv_body(const DevMat &m, const SpmvSrc<GATED> 
                         __builtin_amdgcn_s_sleep(1);
                         v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
-                    s += (uint32_t)(v >> 32) == epoch ? __uint_as_float((uint32_t)v) : __builtin_nanf("");
+                    if ((uint32_t)(v >> 32) == epoch) s += __uint_as_float((uint32_t)v);
+                    else {                       // gave up: poison the row and tell the host (csb_status)
+                        s = __builtin_nanf("");
+                        __hip_atomic_store(&m.counters[m.n_shared], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
                 y[row] = s;
             }
@@ -700,6 +704,21 @@ static void *static_scratch(hipError_t *err) {
     return ptr;
 }
 }  // namespace csb
+
+// Has a merge of shared row tiles given up waiting since the last check?  Synchronises `stream`.
+extern "C" int csb_status(const csb_matrix *m, void *stream, int32_t *timed_out) {
+    if (!m || !timed_out) { csb::set_error("csb_status: NULL pointer"); return CSB_EINVAL; }
+    *timed_out = 0;
+    if (!m->plan.valid || !m->uploaded || !m->d_buf) return CSB_OK;
+    uint32_t *d = (uint32_t *)((uint8_t *)m->d_buf + m->plan.hdr.off_counters) + m->plan.hdr.n_shared;
+    uint32_t v = 0;
+    hipError_t e = hipMemcpyAsync(&v, d, 4, hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e == hipSuccess && v) e = hipMemsetAsync(d, 0, 4, (hipStream_t)stream);
+    if (e != hipSuccess) { csb::set_error(std::string("csb_status: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    *timed_out = (int32_t)v;
+    return CSB_OK;
+}
 
 extern "C" size_t csb_spmv_static_limit(void) { return csb::kStaticScratchBytes; }
 

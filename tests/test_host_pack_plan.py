@@ -302,3 +302,35 @@ def test_resident_layout_for_batches():
     big = CsbRnn(CELL_LSTM, 2100, 1000, [CsbMatrix(wl.W[0].A, 50, 50)], None)
     with pytest.raises(CsbError):
         big.plan_resident(8)
+
+
+def test_gru_matrix_keeps_its_row_layout_when_planned_again():
+    """A matrix planned by csb_rnn_create for a GRU keeps the layout in which the n rows'
+    input-side and recurrent-side sums stay apart when csb_plan / csb_plan_ex plan it again,
+    also after csb_set_value_format; csb_rnn_create keeps the workgroup count and mode of an
+    earlier plan of the caller's.  (No device needed: csb_spmv refuses such a matrix before it
+    touches anything.)"""
+    import ctypes as C
+    from paper_2005_05758_amd.binding import CsbError, CsbRnn, CELL_GRU, lib
+    cfg = csb_inputs.CONFIGS["cfg3"]
+    wl = csb_inputs.make_rnn(cfg, T=2)
+    m = wl.W[0]
+    M = CsbMatrix(m.A, m.br, m.bc)
+    M.plan(7, 2)                                  # the caller's choice: 7 workgroups, equal split
+    rnn = CsbRnn(CELL_GRU, cfg.input, cfg.hidden, [M], None)
+    st = M.plan_stats()                           # csb_rnn_create planned again, for the GRU, with the caller's parameters
+
+    def refused_as_gru():
+        rc = lib().csb_spmv(M.handle, C.c_void_p(256), C.c_void_p(256), None, None)
+        return rc == -5 and b"GRU" in lib().csb_last_error()
+
+    assert refused_as_gru()
+    assert M.plan(7, 2) == st                     # the same request on the GRU layout gives the same plan
+    st_default = M.plan()
+    assert st_default["n_chunks"] != st["n_chunks"] and refused_as_gru()     # other count, same row layout
+    M.validate()
+    M.set_value_format(binding.VAL_BF16)          # invalidates the plan
+    M.plan()
+    assert refused_as_gru()
+    M.validate()
+    del rnn
