@@ -320,9 +320,13 @@ int csb_spmm_half(const csb_matrix *m, const uint16_t *d_Xh, int64_t ldx, float 
  * partition constraints of Sec. 5.2.2; shares are multiples of Q and P.  The paper finds a
  * schedule per iteration with an SMT solver and a growing margin around the mean load; this
  * model takes the schedule with the smallest largest load instead: exactly (exhaustive search)
- * for horizontal-only and vertical-only sharing, and by improving one PEGroup's choice at a
- * time from the better of those two for 2-D sharing (so eff_2d is a lower bound on what the
- * best 2-D schedule reaches).  The paper's evaluation uses P = Q = K = L = 4.
+ * for horizontal-only and vertical-only sharing, and for 2-D sharing on grids of at most four
+ * PEGroups (K L <= 4; exact_2d = 1).  On larger grids, and when an iteration of a small grid
+ * has more than 2^27 combinations, the 2-D schedule is found by improving one PEGroup's choice
+ * at a time from the better one-directional schedule (exact_2d = 0): eff_2d is then a lower
+ * bound on what the best 2-D schedule reaches, checked against brute force only as a bound
+ * (never below the optimum's time, never above the one-directional ones).  The paper's
+ * evaluation uses P = Q = K = L = 4, which is such a grid.
  * Errors: NULL pointers, P, Q < 1, K, L outside [1, 8] -> CSB_EINVAL.
  */
 typedef struct {
@@ -330,6 +334,8 @@ typedef struct {
     int64_t iterations;           /* block iterations: ceil(nbr / K) ceil(nbc / L)             */
     int64_t cycles_none, cycles_horizontal, cycles_vertical, cycles_2d;
     double eff_none, eff_horizontal, eff_vertical, eff_2d;
+    int32_t exact_2d;             /* 1: cycles_2d is the optimum; 0: an upper bound on it      */
+    int32_t reserved;
 } csb_sharing_stats;
 int csb_sharing_model(const csb_matrix *m, int32_t P, int32_t Q, int32_t K, int32_t L,
                       csb_sharing_stats *out);

@@ -1,8 +1,11 @@
 """ctypes front end of the CPU oracle (oracle/csb_oracle.c).
 
 TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the benchmark's
-cpu_baseline leg; never by the product package.  It marshals numpy arrays, nothing else:
-all arithmetic is in the C file.
+cpu_baseline leg; never by the product package.  The method's arithmetic (encode, decode,
+products, cell updates, projection) is in the C file and this module marshals numpy arrays
+for it.  Two things are computed here in numpy instead, each marked where it stands: the
+PE-array utilisation model of Sec. 5 (`eff_1d`, `eff_2d`, integer counts only) and the
+rounding of operands to 16-bit storage formats used by the reduced-precision parity cases.
 """
 from __future__ import annotations
 
@@ -41,6 +44,7 @@ def _load():
         _lib.orc_csb_decode.restype = C.c_int
         _lib.orc_rnn_forward.restype = C.c_int
         _lib.orc_csb_project.restype = C.c_int
+        _lib.orc_csb_project_f64.restype = C.c_int
         _lib.orc_lstmp_forward.restype = C.c_int
     return _lib
 
@@ -217,6 +221,20 @@ def csb_project(W: np.ndarray, br: int, bc: int, rate: float) -> np.ndarray:
                              C.c_double(rate), _p(Z), C.c_int64(Cc))
     if rc != 0:
         raise ValueError("orc_csb_project: bad argument")
+    return Z
+
+
+def csb_project_f64(W: np.ndarray, br: int, bc: int, rate: float) -> np.ndarray:
+    """The projection with the ranking sums in float64 (the plain definition, without the reading
+    that the decision is taken in float32).  Returns the pruned matrix."""
+    lib = _load()
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    R, Cc = W.shape
+    Z = np.empty_like(W)
+    rc = lib.orc_csb_project_f64(_p(W), C.c_int64(R), C.c_int64(Cc), C.c_int64(Cc), C.c_int32(br), C.c_int32(bc),
+                                 C.c_double(rate), _p(Z), C.c_int64(Cc))
+    if rc != 0:
+        raise ValueError("orc_csb_project_f64: bad argument")
     return Z
 
 

@@ -508,3 +508,54 @@ int orc_csb_project(const float *W, int64_t R, int64_t C, int64_t ld, int32_t BR
     free(rk);
     return 0;
 }
+
+/*
+ * The same projection with the decision taken in float64: sums of squares accumulated in
+ * double, in the same order, ranked by value and then by position (NaN on top).  This is the
+ * plain definition of Sec. 3.2.2 without the reading "the decision is taken in float32"; it
+ * exists to measure how often that reading matters (tests count the entries on which the two
+ * differ) and to check the device result against wherever no two sums at a cut are nearly equal.
+ */
+typedef struct { double key; int nan; int64_t idx; } orc_rank64;
+
+static int orc_rank64_cmp(const void *a, const void *b) {
+    const orc_rank64 *x = (const orc_rank64 *)a, *y = (const orc_rank64 *)b;
+    if (x->nan != y->nan) return x->nan < y->nan ? -1 : 1;
+    if (!x->nan && x->key != y->key) return x->key < y->key ? -1 : 1;
+    return x->idx < y->idx ? -1 : (x->idx > y->idx ? 1 : 0);
+}
+
+int orc_csb_project_f64(const float *W, int64_t R, int64_t C, int64_t ld, int32_t BR, int32_t BC,
+                        double rate, float *Z, int64_t ldz) {
+    if (!W || !Z || R <= 0 || C <= 0 || ld < C || ldz < C || BR < 1 || BC < 1 || !(rate >= 1.0)) return -1;
+    const int64_t nbr = (R + BR - 1) / BR, nbc = (C + BC - 1) / BC;
+    for (int64_t i = 0; i < R; ++i) memcpy(Z + i * ldz, W + i * ld, sizeof(float) * (size_t)C);
+    orc_rank64 *rk = (orc_rank64 *)malloc(sizeof(orc_rank64) * (size_t)(R > C ? R : C));
+    if (!rk) return -1;
+    for (int64_t bj = 0; bj < nbc; ++bj) {
+        const int64_t c0 = bj * BC, c1 = imin64(C, c0 + BC);
+        for (int64_t i = 0; i < R; ++i) {
+            double s = 0.0;
+            for (int64_t c = c0; c < c1; ++c) s += (double)Z[i * ldz + c] * (double)Z[i * ldz + c];
+            rk[i].nan = s != s; rk[i].key = s; rk[i].idx = i;
+        }
+        qsort(rk, (size_t)R, sizeof(orc_rank64), orc_rank64_cmp);
+        const int64_t k = orc_prune_count(R, rate);
+        for (int64_t t = 0; t < k; ++t)
+            for (int64_t c = c0; c < c1; ++c) Z[rk[t].idx * ldz + c] = 0.0f;
+    }
+    for (int64_t bi = 0; bi < nbr; ++bi) {
+        const int64_t r0 = bi * BR, r1 = imin64(R, r0 + BR);
+        for (int64_t c = 0; c < C; ++c) {
+            double s = 0.0;
+            for (int64_t i = r0; i < r1; ++i) s += (double)Z[i * ldz + c] * (double)Z[i * ldz + c];
+            rk[c].nan = s != s; rk[c].key = s; rk[c].idx = c;
+        }
+        qsort(rk, (size_t)C, sizeof(orc_rank64), orc_rank64_cmp);
+        const int64_t k = orc_prune_count(C, rate);
+        for (int64_t t = 0; t < k; ++t)
+            for (int64_t i = r0; i < r1; ++i) Z[i * ldz + rk[t].idx] = 0.0f;
+    }
+    free(rk);
+    return 0;
+}

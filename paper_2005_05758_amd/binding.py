@@ -32,7 +32,7 @@ class csb_sharing_stats(C.Structure):
     _fields_ = [("work", C.c_int64), ("iterations", C.c_int64), ("cycles_none", C.c_int64),
                 ("cycles_horizontal", C.c_int64), ("cycles_vertical", C.c_int64), ("cycles_2d", C.c_int64),
                 ("eff_none", C.c_double), ("eff_horizontal", C.c_double), ("eff_vertical", C.c_double),
-                ("eff_2d", C.c_double)]
+                ("eff_2d", C.c_double), ("exact_2d", C.c_int32), ("reserved", C.c_int32)]
 
 
 class CsbError(RuntimeError):

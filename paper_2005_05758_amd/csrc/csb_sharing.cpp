@@ -62,6 +62,51 @@ int64_t ring_best(const Model &M, const std::vector<Dim> &d, bool horizontal, st
     return best;
 }
 
+// Exact 2-D optimum for at most four PEGroups: depth-first over every PEGroup's shape and
+// shares, cut as soon as a load that is already determined reaches the best time known
+// (`bound`, a schedule's time found before, so the result is never above it).  Returns false
+// without a result if the number of combinations exceeds `limit`.
+bool grid_best_2d(const Model &M, const std::vector<Dim> &d, int64_t bound, int64_t limit, int64_t *best_out) {
+    const int K = M.K, L = M.L, n = K * L;
+    *best_out = bound;
+    if (bound == 0) return true;
+    std::vector<std::vector<Opt>> opts(n);
+    double combos = 1.0;
+    for (int i = 0; i < n; ++i) {
+        for (int shape = 0; shape < 2; ++shape)
+            for (int dnh = 0; dnh <= d[i].n; dnh += M.Q)
+                for (int dmv = 0; dmv <= d[i].m / 2; dmv += M.P) {
+                    if (shape == 1 && (dnh == 0 || dmv == 0)) continue;          // the same parts as shape 0
+                    const Opt o{dnh, dmv, shape};
+                    if (M.local(d[i], o) < bound) opts[i].push_back(o);
+                }
+        if (opts[i].empty()) return true;                          // nothing can beat the bound
+        combos *= (double)opts[i].size();
+    }
+    if (combos > (double)limit) return false;
+    std::vector<Opt> cur(n);
+    std::vector<int> idx(n, -1);
+    int64_t best = bound;
+    int depth = 0;
+    while (depth >= 0) {
+        if (++idx[depth] >= (int)opts[depth].size()) { idx[depth] = -1; --depth; continue; }
+        cur[depth] = opts[depth][idx[depth]];
+        // loads whose three contributors (the PEGroup, its left and its upper neighbour) are chosen
+        int64_t worst = 0;
+        for (int g = 0; g <= depth; ++g) {
+            const int k = g / L, l = g % L;
+            const int left = k * L + (l + L - 1) % L, up = ((k + K - 1) % K) * L + l;
+            if (left > depth || up > depth) continue;
+            worst = std::max(worst, M.local(d[g], cur[g]) + M.out_h(d[left], cur[left]) + M.out_v(d[up], cur[up]));
+        }
+        if (worst >= best) continue;
+        if (depth + 1 < n) { ++depth; continue; }
+        best = worst;
+    }
+    *best_out = best;
+    return true;
+}
+
 }  // namespace
 
 extern "C" int csb_sharing_model(const csb_matrix *m, int32_t P, int32_t Q, int32_t K, int32_t L,
@@ -71,6 +116,7 @@ extern "C" int csb_sharing_model(const csb_matrix *m, int32_t P, int32_t Q, int3
     if (P <= 0 || Q <= 0 || K <= 0 || L <= 0 || K > 8 || L > 8) { set_error("csb_sharing_model: P, Q >= 1 and 1 <= K, L <= 8"); return CSB_EINVAL; }
     const Model M{P, Q, K, L};
     int64_t work = 0, t_none = 0, t_h = 0, t_v = 0, t_2d = 0, iters = 0;
+    bool exact = K * L <= 4;
     const int IK = (m->nbr + K - 1) / K, JL = (m->nbc + L - 1) / L;
     std::vector<Dim> d((size_t)K * L);
     std::vector<Opt> o((size_t)K * L), ring;
@@ -141,6 +187,11 @@ extern "C" int csb_sharing_model(const csb_matrix *m, int32_t P, int32_t Q, int3
                 }
                 if (!improved) break;
             }
+            // Small grids: replace the bound by the exact optimum (every combination).
+            if (K * L <= 4 && exact) {
+                int64_t ex;
+                if (grid_best_2d(M, d, bw, (int64_t)1 << 27, &ex)) bw = ex; else exact = false;
+            }
             t_2d += bw;
         }
     const double denom = (double)P * Q * K * L;
@@ -151,5 +202,7 @@ extern "C" int csb_sharing_model(const csb_matrix *m, int32_t P, int32_t Q, int3
     out->eff_horizontal = t_h ? work / (denom * t_h) : 0.0;
     out->eff_vertical = t_v ? work / (denom * t_v) : 0.0;
     out->eff_2d = t_2d ? work / (denom * t_2d) : 0.0;
+    out->exact_2d = exact ? 1 : 0;
+    out->reserved = 0;
     return CSB_OK;
 }

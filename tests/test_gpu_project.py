@@ -19,7 +19,7 @@ def say(msg):
     sys.stdout.flush()
 
 
-def check_project(W, br, bc, rate, tag=""):
+def check_project(W, br, bc, rate, tag="", f64_too=False):
     say(f"[project] {tag} shape={W.shape} block={br}x{bc} rate={rate}")
     ref = oracle.csb_project(W, br, bc, rate)
     Wd = torch.from_numpy(W).cuda()
@@ -28,6 +28,12 @@ def check_project(W, br, bc, rate, tag=""):
     got = Z.cpu().numpy()
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), int(np.count_nonzero(got != ref))
     assert np.array_equal(Wd.cpu().numpy().view(np.uint32), W.view(np.uint32))   # the input is untouched
+    if f64_too:
+        # no two ranking sums at a cut are close enough on these inputs for float32 and float64
+        # to rank them differently (counted on the CPU side), so the device result is also the
+        # plain float64 definition's, bit for bit
+        ref64 = oracle.csb_project_f64(W, br, bc, rate)
+        assert np.array_equal(got.view(np.uint32), ref64.view(np.uint32)), int(np.count_nonzero(got != ref64))
     return got
 
 
@@ -37,7 +43,7 @@ def check_project(W, br, bc, rate, tag=""):
     (1, 1, 1, 1, 4.0), (1025, 3, 64, 2, 25.0)])
 def test_project_small_shapes(R, C, br, bc, rate):
     rng = np.random.default_rng(R * 7 + C)
-    check_project(rng.normal(0, 0.05, (R, C)).astype(np.float32), br, bc, rate, tag="gauss")
+    check_project(rng.normal(0, 0.05, (R, C)).astype(np.float32), br, bc, rate, tag="gauss", f64_too=True)
     check_project(rng.integers(-3, 4, (R, C)).astype(np.float32), br, bc, rate, tag="ties")   # many equal sums, zeros
 
 
@@ -66,7 +72,7 @@ def test_project_then_pack_then_spmv():
     encoding matches the oracle's, and the mat-vec of the packed matrix matches the oracle's."""
     rng = np.random.default_rng(11)
     W = rng.normal(0, 0.05, (512, 640)).astype(np.float32)
-    Z = check_project(W, 32, 32, 10.0, tag="pipeline")
+    Z = check_project(W, 32, 32, 10.0, tag="pipeline", f64_too=True)
     assert abs(np.count_nonzero(Z) / Z.size - 0.1) < 0.02
     M = CsbMatrix(Z, 32, 32)
     enc = oracle.csb_encode(Z, 32, 32)
@@ -85,5 +91,5 @@ def test_project_full_size():
     """8192 x 8192, block 32, 12x: the stress matrix's shape, as bench.py runs it."""
     rng = np.random.default_rng(0)
     W = rng.normal(0, 0.05, (8192, 8192)).astype(np.float32)
-    Z = check_project(W, 32, 32, 12.0, tag="8192")
+    Z = check_project(W, 32, 32, 12.0, tag="8192", f64_too=True)
     assert abs(np.count_nonzero(Z) / Z.size - 1 / 12.0) < 0.02

@@ -1,7 +1,8 @@
 """csb_sharing_model (host only) against the oracle's brute force on small matrices: cycle
 counts without sharing and with one-directional sharing are exact optima and must agree
-exactly; the 2-D figure is an upper bound on the optimum that must lie between the exact 2-D
-optimum and the better one-directional one."""
+exactly, and so must the 2-D figure on grids of at most four PEGroups, where the library
+searches exhaustively; on larger grids the 2-D figure is an upper bound on the optimum that
+must lie between the exact 2-D optimum and the better one-directional one."""
 import numpy as np
 import pytest
 
@@ -26,20 +27,31 @@ def test_against_brute_force(R, C, br, bc, P, Q, K, L, rate):
         got = CsbMatrix(A, br, bc).sharing_model(P, Q, K, L)
         for k in ("work", "iterations", "cycles_none", "cycles_horizontal", "cycles_vertical"):
             assert got[k] == ref[k], (k, got[k], ref[k])
-        assert ref["cycles_2d"] <= got["cycles_2d"] <= min(ref["cycles_horizontal"], ref["cycles_vertical"])
-        for k in ("none", "horizontal", "vertical"):
+        assert got["exact_2d"] == (1 if K * L <= 4 else 0)
+        assert got["cycles_2d"] == ref["cycles_2d"], (got["cycles_2d"], ref["cycles_2d"])      # every grid here has at most four PEGroups
+        for k in ("none", "horizontal", "vertical", "2d"):
             assert abs(got["eff_" + k] - ref["eff_" + k]) < 1e-12
 
 
-def test_2d_figure_is_close_to_the_optimum():
-    """The 2-D schedule is found by local improvement, so its time is an upper bound on the
-    optimum: never below it, and within 15 % of it on these small cases."""
+def test_2d_figure_is_the_optimum_on_small_grids():
     for seed in range(6):
         A = csb_inputs.small_matrix(100 + seed, 32, 32, 8, 8, rate=1.6).A
         nr, nc = counts(A, 8, 8)
         ref = oracle.sharing_model(nr, nc, 2, 2, 2, 2, exact_2d=True)
         got = CsbMatrix(A, 8, 8).sharing_model(2, 2, 2, 2)
-        assert ref["cycles_2d"] <= got["cycles_2d"] <= 1.15 * ref["cycles_2d"]
+        assert got["exact_2d"] == 1 and got["cycles_2d"] == ref["cycles_2d"] and got["eff_2d"] == ref["eff_2d"]
+
+
+def test_2d_figure_on_a_larger_grid_is_a_bound():
+    """Six PEGroups: the library improves one PEGroup's choice at a time, so its time is never
+    below the optimum (brute force) and never above the one-directional schedules'."""
+    for seed in range(3):
+        A = csb_inputs.small_matrix(200 + seed, 8, 12, 4, 4, rate=1.4).A
+        nr, nc = counts(A, 4, 4)
+        ref = oracle.sharing_model(nr, nc, 2, 2, 2, 3, exact_2d=True)
+        got = CsbMatrix(A, 4, 4).sharing_model(2, 2, 2, 3)
+        assert got["exact_2d"] == 0
+        assert ref["cycles_2d"] <= got["cycles_2d"] <= min(ref["cycles_horizontal"], ref["cycles_vertical"])
 
 
 def test_workload_shape_and_errors():
@@ -48,7 +60,7 @@ def test_workload_shape_and_errors():
     r = M.sharing_model()                                  # the paper's evaluation: 4 x 4 PEGroups of 4 x 4 PEs
     assert r["work"] == int(M.view()["nnz"]) and r["iterations"] == 16 * 6
     assert 0 < r["eff_none"] <= r["eff_horizontal"] <= 1 and r["eff_none"] <= r["eff_vertical"] <= 1
-    assert max(r["eff_horizontal"], r["eff_vertical"]) <= r["eff_2d"] <= 1
+    assert max(r["eff_horizontal"], r["eff_vertical"]) <= r["eff_2d"] <= 1 and r["exact_2d"] == 0
     for bad in ((0, 4, 4, 4), (4, 4, 9, 4), (4, 4, 4, 0)):
         with pytest.raises(CsbError):
             M.sharing_model(*bad)

@@ -112,3 +112,49 @@ def test_projection_by_construction():
     assert list(kept_cols) == [1, 5, 6, 7]
     # block-row 0 is all zero after RowPrune: ties by position, columns 0-3 are "pruned", nothing to see
     assert np.array_equal(Z[4:, kept_cols], W[4:, kept_cols])
+
+
+# ---- the float32 reading against the plain float64 definition ------------------------------------
+
+GAUSS_CASES = [(4, 6, 2, 3, 4.0), (37, 53, 8, 8, 3.0), (200, 150, 16, 16, 6.0), (130, 257, 32, 32, 10.0),
+               (96, 96, 32, 16, 1.0), (70, 300, 16, 64, 16.0), (300, 40, 128, 8, 2.0), (513, 100, 256, 256, 12.0),
+               (1, 1, 1, 1, 4.0), (1025, 3, 64, 2, 25.0)]
+
+
+def differing_decisions(W, br, bc, rate):
+    """Entries kept by one of the two projections and removed by the other."""
+    return int(np.count_nonzero((oracle.csb_project(W, br, bc, rate) != 0) != (oracle.csb_project_f64(W, br, bc, rate) != 0)))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_float64_projection_matches_exact_integer_brute_force(seed):
+    rng = np.random.default_rng(100 + seed)
+    R, C = int(rng.integers(1, 13)), int(rng.integers(1, 13))
+    br, bc = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+    rate = float(rng.choice([1.5, 2.0, 4.0, 9.0]))
+    W = rng.integers(-4, 5, size=(R, C)).astype(np.float32)
+    assert np.array_equal(oracle.csb_project_f64(W, br, bc, rate), brute_force_project(W, br, bc, rate))
+
+
+def test_float32_decisions_equal_float64_decisions_on_the_tested_inputs():
+    """The projection is specified here with its ranking sums in float32 (the device's
+    arithmetic).  On every Gaussian input the device tests use (same seeds, same shapes) the
+    plain float64 definition takes the same decisions: zero differing entries.  The count is
+    what the design notes quote."""
+    total = 0
+    for R, C, br, bc, rate in GAUSS_CASES:
+        rng = np.random.default_rng(R * 7 + C)
+        total += differing_decisions(rng.normal(0, 0.05, (R, C)).astype(np.float32), br, bc, rate)
+    total += differing_decisions(np.random.default_rng(11).normal(0, 0.05, (512, 640)).astype(np.float32), 32, 32, 10.0)
+    total += differing_decisions(np.random.default_rng(0).normal(0, 0.05, (2048, 2048)).astype(np.float32), 32, 32, 12.0)
+    assert total == 0
+
+
+def test_float32_and_float64_readings_part_only_at_a_near_tie():
+    """Two segments whose sums differ by less than one float32 unit in the last place: float32
+    sees a tie and removes the earlier position, float64 removes the smaller sum."""
+    W = np.array([[1.0, 2.0 ** -13], [1.0, 0.0]], dtype=np.float32)       # sums 1 + 2^-26 and 1
+    Z32 = oracle.csb_project(W, 2, 2, 4.0)                                 # each pass removes one of two
+    Z64 = oracle.csb_project_f64(W, 2, 2, 4.0)
+    assert not Z32[0].any() and Z32[1].any()
+    assert Z64[0].any() and not Z64[1].any()
