@@ -32,13 +32,27 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3
-# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very command, scaled by
-# the readings of a plain 256 MiB copy (profiles/bench_hbm_traffic_pmc.txt has the commands and raw readings)
-TRAFFIC_BYTES = {
-    "rnn_resident_cfg2": {"read": int(914.125 * 2.0 * 1024), "written": int(633.6875 * 1024)},
-    "spmv_cfg5": {"read": int(14446.625 * 2.0 * 1024), "written": 32768},
-    "spmm_cfg5_b128": {"read": int(44941.8125 * 2.0 * 1024), "written": 4194304},
-}
+
+
+def load_traffic():
+    """HBM-side bytes per launch of the roofline kernels, from the committed summary of the
+    rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/hbm_traffic_pmc.txt: lines
+    'traffic <key> read_bytes=<n> written_bytes=<n>', already scaled by the readings of a plain
+    copy of known size; the file has the commands and the raw readings).  No file, no figure."""
+    table = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic_pmc.txt")) as f:
+            for line in f:
+                w = line.split()
+                if len(w) >= 4 and w[0] == "traffic":
+                    kv = dict(t.split("=", 1) for t in w[2:] if "=" in t)
+                    table[w[1]] = int(float(kv["read_bytes"])) + int(float(kv["written_bytes"]))
+    except (OSError, KeyError, ValueError):
+        pass
+    return table
+
+
+TRAFFIC_BYTES = load_traffic()
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 
@@ -83,6 +97,30 @@ def time_each(fn, reps, torch):
     return ts[len(ts) // 2], ts[0]
 
 
+_blocker = {}
+
+
+def time_queued(calls, reps, torch):
+    """Microseconds per call with every launch queued behind a long kernel, so that the host's
+    launch rate (several microseconds per call from Python) does not show: two large matrix
+    products go first, the start event sits behind them, and by the time they end the
+    launches are all in the queue.  HIP events on the current stream."""
+    if "a" not in _blocker:
+        _blocker["a"] = torch.randn(6144, 6144, device="cuda")
+        _blocker["c"] = torch.empty(6144, 6144, device="cuda")
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    torch.mm(_blocker["a"], _blocker["a"], out=_blocker["c"])
+    torch.mm(_blocker["a"], _blocker["a"], out=_blocker["c"])
+    start.record()
+    for _ in range(reps):
+        for c in calls:
+            c()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) * 1000.0 / (reps * len(calls))
+
+
 def stream_read_leg(torch, stream_read):
     """Measured HBM read bandwidth of this GPU: a plain streaming read of 2 GiB (8 x the
     Infinity Cache), the practical roofline the mat-vec figures are also quoted against."""
@@ -96,22 +134,75 @@ def stream_read_leg(torch, stream_read):
     del buf
     res = {"bytes": 512 * 1024 * 1024 * 4, "ms": round(ms, 4), "gbps": round(gbps, 1),
            "frac_of_nominal_peak": round(gbps / HBM_PEAK_GBS, 4)}
-    # the same plain read at the size of the 8192^2 matrix image (28 MB per launch), cold: 24
-    # distinct buffers in turn, as the mat-vec's cold figure is taken -- what one launch of that
-    # size costs when all it does is read
-    small = [torch.ones(7 * 1024 * 1024, dtype=torch.float32, device="cuda") for _ in range(24)]
-    for b in small:
-        stream_read(b, out)
-    state = {"i": 0}
-
-    def cold():
-        stream_read(small[state["i"] % len(small)], out)
-        state["i"] += 1
-    n = 5 * len(small)
-    us = time_region(cold, n, torch) * 1000.0 / n
-    res["image_sized_cold"] = {"bytes": small[0].numel() * 4, "us": round(us, 3),
-                               "gbps": round(small[0].numel() * 4 / us / 1e3, 1)}
     return res
+
+
+def plain_read_cold_us(torch, stream_read, nbytes, total=700e6):
+    """A plain read of `nbytes` per launch, cold: distinct buffers in turn (more than 2 x the
+    Infinity Cache in all), launches queued -- what one launch of that size costs when all it
+    does is read."""
+    n4 = max(64, int(nbytes) // 16)
+    bufs = [torch.ones(n4 * 4, dtype=torch.float32, device="cuda") for _ in range(max(3, int(total / (n4 * 16)) + 1))]
+    out = stream_read(bufs[0])
+    for b in bufs:
+        stream_read(b, out)
+    us = time_queued([lambda b=b: stream_read(b, out) for b in bufs], 4, torch)
+    return {"bytes": n4 * 16, "us": round(us, 3), "gbps": round(n4 * 16 / us / 1e3, 1), "buffers": len(bufs)}
+
+
+ONLY = ["headline", "hbm_stream_read", "rnn_configs", "resident_batches", "spmv_stress", "spmv_cfg5", "spmv_tall",
+        "batched", "spmm_cfg5", "projection", "lstmp_sr1", "cells", "weights_16bit", "spmv_cfg5_bf16", "spmm_bfloat",
+        "calib_copy", "cpu_baseline"]
+
+
+def only_leg(args, torch, np, csb_inputs, CsbMatrix, CsbRnn, stream_read):
+    """One leg by name; legs that quote a fraction of the measured stream read run without it."""
+    o = args.only
+    if o == "hbm_stream_read":
+        return stream_read_leg(torch, stream_read)
+    if o == "rnn_configs":
+        return rnn_configs_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, stream_read, None)
+    if o == "resident_batches":
+        return resident_batches_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
+    if o == "spmv_stress":
+        return stress_leg(torch, np, csb_inputs, CsbMatrix, stream_read)
+    if o == "spmv_cfg5":          # cold launches of the default plan only
+        return stress_leg(torch, np, csb_inputs, CsbMatrix, stream_read, names=("cfg5",), modes=((0, "default_plan"),), cold_only=True)
+    if o == "spmv_tall":
+        return tall_leg(torch, np, csb_inputs, CsbMatrix, stream_read)
+    if o == "batched":
+        return batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
+    if o == "spmm_cfg5":
+        return batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, cases=(("cfg5", 128),), with_rnn=False)
+    if o == "projection":
+        return projection_leg(torch, np, None, False)
+    if o == "lstmp_sr1":
+        return lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, not args.no_cpu)
+    if o == "cells":
+        return cells_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, not args.no_cpu)
+    if o == "weights_16bit":
+        return val16_leg(torch, np, csb_inputs, CsbMatrix, None)
+    if o == "spmv_cfg5_bf16":
+        return val16_leg(torch, np, csb_inputs, CsbMatrix, None, formats=("bf16",), cold_only=True, what=("spmv",))
+    if o == "spmm_bfloat":
+        return val16_leg(torch, np, csb_inputs, CsbMatrix, None, formats=("bf16",), what=("spmm_bfloat",))
+    if o == "calib_copy":
+        return calib_copy_leg(torch)
+    if o == "cpu_baseline":
+        cfg = csb_inputs.CONFIGS[args.workload]
+        return cpu_leg(cfg, csb_inputs.make_rnn(cfg))
+    raise ValueError(o)
+
+
+def calib_copy_leg(torch):
+    """Plain 256 MiB device copies: the known-size kernel that scales rocprofv3's FETCH_SIZE /
+    WRITE_SIZE readings."""
+    src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    return {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "launches": 5}
 
 
 def main():
@@ -122,6 +213,9 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-stress", action="store_true", help="skip the 8192^2 SpMV stress leg")
+    ap.add_argument("--only", default=None, choices=ONLY,
+                    help="run one leg alone (its kernels are then the only ones of their kind in a rocprofv3 trace) "
+                         "and print that leg's JSON; the contract line needs the default run")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run plain 256 MiB device copies: the known-size kernel that scales rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE readings")
@@ -140,6 +234,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.only and args.only != "headline":
+        print(json.dumps({"only": args.only, args.only: only_leg(args, torch, np, csb_inputs, CsbMatrix, CsbRnn, stream_read)}))
+        return
     cfg = csb_inputs.CONFIGS[args.workload]
     wl = csb_inputs.make_rnn(cfg)
     Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
@@ -169,7 +266,7 @@ def main():
     roofline = {"kernel": f"csb::rnn_resident_kernel<{st['slots_per_lane']}, true>", "bound": "hbm",
                 "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(ach / HBM_PEAK_GBS, 5),
-                "traffic": sum(TRAFFIC_BYTES["rnn_resident_cfg2"].values()) if args.workload == "cfg2" else None,
+                "traffic": TRAFFIC_BYTES.get("rnn_resident_cfg2") if args.workload == "cfg2" else None,
                 "us_per_launch": round(ms_per_step * 1e3, 3), "alg_bytes_per_launch": bytes_step * T,
                 "units_per_launch": T,
                 "note": "weights stay in registers for all T steps (read from HBM once per launch); a step is "
@@ -220,20 +317,18 @@ def main():
     }
 
     if args.calib_copy:
-        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        out["calib_copy"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "launches": 5}
-        del src, dst
+        out["calib_copy"] = calib_copy_leg(torch)
+    if args.only == "headline":
+        print(json.dumps(out))
+        return
     if not args.no_stress:
         sr = stream_read_leg(torch, stream_read)
         out["hbm_stream_read"] = sr
         out["pct_of_measured_stream_read"] = round(100.0 * gbps / sr["gbps"], 4)
         out["rnn_configs"] = rnn_configs_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, stream_read, args.workload)
         out["resident_batches"] = resident_batches_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
-        out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix, sr["gbps"], sr["image_sized_cold"]["us"])
+        out["spmv_stress"] = stress_leg(torch, np, csb_inputs, CsbMatrix, stream_read, sr["gbps"])
+        out["spmv_tall"] = tall_leg(torch, np, csb_inputs, CsbMatrix, stream_read)
         out["batched"] = batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn)
         out["projection"] = projection_leg(torch, np, sr["gbps"], not args.no_cpu)
         out["lstmp_sr1"] = lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, not args.no_cpu)
@@ -286,17 +381,18 @@ def rnn_configs_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, stream_read, headl
         y = torch.empty(wl.W[0].rows, dtype=torch.float32, device="cuda")
         for _ in range(10):
             M.spmv(x, y)
-        n = 200
-        us_warm = time_region(lambda: M.spmv(x, y), n, torch) * 1000.0 / n
-        cold = []
-        for _ in range(15):
+        us_warm = time_queued([lambda: M.spmv(x, y)] * 50, 4, torch)
+        # cold: a 2 GiB read before every launch, one event pair around each launch; nothing waits
+        # for the host in between (the read is long enough for the next calls to be queued)
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(15)]
+        torch.cuda.synchronize()
+        for a, b in pairs:
             stream_read(flush, sink)
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
             M.spmv(x, y)
             b.record()
-            torch.cuda.synchronize()
-            cold.append(a.elapsed_time(b) * 1000.0)
+        torch.cuda.synchronize()
+        cold = [a.elapsed_time(b) * 1000.0 for a, b in pairs]
         cold.sort()
         us_cold = cold[len(cold) // 2]
         entry["spmv_layer0"] = {"shape": [int(wl.W[0].rows), int(wl.W[0].cols)], "nnz": int(M.view()["nnz"]), "alg_bytes": ab,
@@ -365,46 +461,58 @@ def resident_batches_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
     return res
 
 
-def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps, image_read_us=None):
+def wave_spread(stamps, np):
+    """Largest / mean time a wavefront (a workgroup) spends multiplying, from the clock stamps of
+    one launch: [workgroups][16 wavefronts][8 stamps] for the row-owned kernel (stamp 3 = first
+    segment in LDS, 4 = products done), [workgroups][stamps] for the tile kernel."""
+    sp = stamps.cpu().numpy().astype(np.float64)
+    wv = sp[:, :, 4] - sp[:, :, 3] if sp.ndim == 3 else sp[:, 10::3] - sp[:, 8::3]
+    wg = wv.max(axis=1)
+    return round(float(wv.max() / wv.mean()), 4), round(float(wg.max() / wg.mean()), 4)
+
+
+def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_read, stream_gbps=None, names=("cfg5", "cfg5_diag"),
+               modes=((0, "default_plan"), (2, "equal_split")), cold_only=False):
     """csb_spmv on the 8192^2 heavy-tailed matrices (the HBM-bound case): warm (matrix in the
     Infinity Cache) and cold (rotating over distinct device copies, > 512 MB in all), for
-    the default plan (whole row tiles per workgroup) and the equal-split plan (mode 2)."""
+    the default plan (row-owned layout) and the tile-based equal-split plan (mode 2).  Launches
+    are queued behind a long kernel, so the figures are the device's, not the host's."""
     res = {}
-    for name in ("cfg5", "cfg5_diag"):
+    for name in names:
         m = csb_inputs.make_mat(csb_inputs.CONFIGS[name])
         x = torch.from_numpy(csb_inputs.make_vectors(5, m.cols, 1)).cuda()
         y = torch.empty(m.rows, dtype=torch.float32, device="cuda")
-        for mode, tag in ((0, "whole_tiles"), (2, "equal_split")):
+        for mode, tag in modes:
             M = CsbMatrix(m.A, m.br, m.bc)
             st = M.plan(0, mode)
             M.upload()
             v = M.view()
             ab = spmv_alg_bytes(v)
-            for _ in range(10):
-                M.spmv(x, y)
-            n = 200
-            us_warm = time_region(lambda: M.spmv(x, y), n, torch) * 1000.0 / n
-            # dynamic balance: clocks each wavefront spends on its share (stamps of one launch)
-            _, stamps = M.spmv_stamps(x)
-            torch.cuda.synchronize()
-            sp = stamps.cpu().numpy().astype(np.float64)
-            wv = sp[:, 10::3] - sp[:, 8::3]
-            wg = wv.max(axis=1)
-            entry = {"nnz": int(v["nnz"]), "alg_bytes": ab, "us_warm": round(us_warm, 3),
-                     "dyn_wave_max_over_mean": round(float(wv.max() / wv.mean()), 4),
-                     "dyn_workgroup_max_over_mean": round(float(wg.max() / wg.mean()), 4),
-                     "gbps_warm": round(ab / us_warm / 1e3, 1),
+            entry = {"nnz": int(v["nnz"]), "alg_bytes": ab,
+                     "kernel": "csb::spmv_rows_kernel<2>" if st["row_owned"] else "csb::spmv_kernel",
+                     "image_bytes_per_launch": int(st["matvec_bytes"]),
+                     "image_over_algorithmic": round(st["matvec_bytes"] / ab, 4),
                      "wave_max_over_mean": round(st["work_max"] / st["work_mean"], 4),
                      "workgroup_max_over_mean": round(st["chunk_max_over_mean"], 4),
                      "nosplit_max_over_mean": round(st["nosplit_max_over_mean"], 4),
-                     "lane_fill": round(st["lane_fill"], 4), "n_chunks": st["n_chunks"],
+                     "lane_fill": round(st["lane_fill"], 4), "n_chunks": st["n_chunks"], "rounds": st["rounds"],
                      "shared_tiles": st["n_shared_tiles"]}
-            if mode == 0:
-                # the paper's own schedule on the same matrix (4 x 4 PEGroups of 4 x 4 PEs, Sec. 6.3.2),
-                # next to this partition's efficiency (mean / largest wavefront work)
-                sm = M.sharing_model(4, 4, 4, 4)
-                entry["paper_schedule_model"] = {k: round(v, 4) for k, v in sm.items() if k.startswith("eff_")}
-                entry["partition_efficiency"] = round(st["work_mean"] / st["work_max"], 4)
+            if not cold_only:
+                for _ in range(10):
+                    M.spmv(x, y)
+                us_warm = time_queued([lambda: M.spmv(x, y)] * 20, 5, torch)
+                # dynamic balance: clocks each wavefront spends on its share (stamps of one launch)
+                _, stamps = M.spmv_stamps(x)
+                torch.cuda.synchronize()
+                dw, dg = wave_spread(stamps, np)
+                entry.update({"us_warm": round(us_warm, 3), "gbps_warm": round(ab / us_warm / 1e3, 1),
+                              "dyn_wave_max_over_mean": dw, "dyn_workgroup_max_over_mean": dg})
+                if mode == 0:
+                    # the paper's own schedule on the same matrix (4 x 4 PEGroups of 4 x 4 PEs, Sec. 6.3.2),
+                    # next to this partition's efficiency (mean / largest wavefront work)
+                    sm = M.sharing_model(4, 4, 4, 4)
+                    entry["paper_schedule_model"] = {k: round(v, 4) for k, v in sm.items() if k.startswith("eff_")}
+                    entry["partition_efficiency"] = round(st["work_mean"] / st["work_max"], 4)
             if name == "cfg5":
                 # cold: rotate over distinct device copies so that every launch streams from HBM
                 copies = [M]
@@ -416,33 +524,60 @@ def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps, image_read_us=None
                     copies.append(c)
                 for c in copies:
                     c.spmv(x, y)
-                state = {"i": 0}
-
-                def cold():
-                    copies[state["i"] % n_copies].spmv(x, y)
-                    state["i"] += 1
-                n = 5 * n_copies
-                us_cold = time_region(cold, n, torch) * 1000.0 / n
+                us_cold = time_queued([lambda c=c: c.spmv(x, y) for c in copies], 5, torch)
                 entry.update({"us_cold": round(us_cold, 3), "gbps_cold": round(ab / us_cold / 1e3, 1),
                               "frac_hbm_cold": round(ab / us_cold / 1e3 / HBM_PEAK_GBS, 4),
-                              "frac_of_measured_stream_read_cold": round(ab / us_cold / 1e3 / stream_gbps, 4),
                               "cold_copies": n_copies, "cold_bytes_total": n_copies * M.device_bytes()})
-                if image_read_us:
+                if stream_gbps:
+                    entry["frac_of_measured_stream_read_cold"] = round(ab / us_cold / 1e3 / stream_gbps, 4)
+                if not cold_only:
                     # against a plain cold read of the same number of bytes in one launch
-                    entry["plain_read_of_image_size_us"] = image_read_us
-                    entry["time_over_plain_read"] = round(us_cold / image_read_us, 3)
+                    pr = plain_read_cold_us(torch, stream_read, st["matvec_bytes"])
+                    entry["plain_read_of_image_size"] = pr
+                    entry["plain_read_over_time"] = round(pr["us"] / us_cold, 3)
                 del copies
             res[f"{name}_{tag}"] = entry
             del M
-    best = min((e for k, e in res.items() if k.startswith("cfg5_") and "us_cold" in e), key=lambda e: e["us_cold"])
-    res["roofline"] = {"kernel": "csb::spmv_kernel", "bound": "hbm", "achieved": best["gbps_cold"], "peak": HBM_PEAK_GBS,
-                       "unit": "GB/s", "frac": best["frac_hbm_cold"], "traffic": sum(TRAFFIC_BYTES["spmv_cfg5"].values()),
-                       "us_per_launch": best["us_cold"], "alg_bytes_per_launch": best["alg_bytes"],
-                       "note": "cold: every launch reads a different device copy of the matrix"}
+    colds = [e for k, e in res.items() if k.startswith("cfg5_") and "us_cold" in e]
+    if colds:
+        best = min(colds, key=lambda e: e["us_cold"])
+        res["roofline"] = {"kernel": best["kernel"], "bound": "hbm", "achieved": best["gbps_cold"], "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": best["frac_hbm_cold"], "traffic": TRAFFIC_BYTES.get("spmv_cfg5"),
+                           "us_per_launch": best["us_cold"], "alg_bytes_per_launch": best["alg_bytes"],
+                           "note": "cold: every launch reads a different device copy of the matrix"}
     return res
 
 
-def val16_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
+def tall_leg(torch, np, csb_inputs, CsbMatrix, stream_read, rows=32768):
+    """csb_spmv on a matrix four times as tall as the stress matrix (32768 x 8192, same block,
+    rate and heavy-tailed recipe, seed 0): 95 MB of algorithmic bytes per launch, so the fixed
+    part of a launch weighs a quarter as much and the figure shows the streaming rate."""
+    cfg = csb_inputs.MatConfig("tall", rows, 8192, 32, 12.0, "heavy", 0.05, 0)
+    m = csb_inputs.make_mat(cfg)
+    x = torch.from_numpy(csb_inputs.make_vectors(5, m.cols, 1)).cuda()
+    y = torch.empty(m.rows, dtype=torch.float32, device="cuda")
+    copies = []
+    for _ in range(7):
+        c = CsbMatrix(m.A, m.br, m.bc)
+        st = c.plan()
+        c.upload()
+        copies.append(c)
+    for c in copies:
+        c.spmv(x, y)
+    ab = spmv_alg_bytes(copies[0].view())
+    us_cold = time_queued([lambda c=c: c.spmv(x, y) for c in copies], 6, torch)
+    us_warm = time_queued([lambda: copies[0].spmv(x, y)] * 8, 4, torch)
+    pr = plain_read_cold_us(torch, stream_read, st["matvec_bytes"])
+    return {"shape": [int(m.rows), int(m.cols)], "nnz": int(copies[0].view()["nnz"]), "alg_bytes": ab,
+            "image_bytes_per_launch": int(st["matvec_bytes"]), "image_over_algorithmic": round(st["matvec_bytes"] / ab, 4),
+            "n_chunks": st["n_chunks"], "rounds": st["rounds"], "row_owned": st["row_owned"],
+            "wave_max_over_mean": round(st["work_max"] / st["work_mean"], 4),
+            "us_cold": round(us_cold, 3), "gbps_cold": round(ab / us_cold / 1e3, 1),
+            "frac_hbm_cold": round(ab / us_cold / 1e3 / HBM_PEAK_GBS, 4), "us_warm": round(us_warm, 3),
+            "cold_copies": len(copies), "plain_read_of_image_size": pr, "plain_read_over_time": round(pr["us"] / us_cold, 3)}
+
+
+def val16_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps, formats=("f16", "bf16"), cold_only=False, what=("spmv", "spmm", "spmm_bfloat")):
     """csb_spmv and csb_spmm on the 8192^2 matrix with the kernel values stored in 16 bits
     (the paper's engine works on 16-bit weights): half the value bytes on the HBM-bound path.
     Cold as in the 32-bit leg (rotating device copies)."""
@@ -452,7 +587,9 @@ def val16_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
     x = torch.from_numpy(csb_inputs.make_vectors(5, m.cols, 1)).cuda()
     y = torch.empty(m.rows, dtype=torch.float32, device="cuda")
     for fmt, name in ((VAL_F16, "f16"), (VAL_BF16, "bf16")):
-        n_copies = 40
+        if name not in formats:
+            continue
+        n_copies = 40 if "spmv" in what else 1
         copies = []
         for _ in range(n_copies):
             c = CsbMatrix(m.A, m.br, m.bc)
@@ -464,20 +601,17 @@ def val16_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
         ab = spmv_alg_bytes(M.view(), value_bytes=2)
         for c in copies:
             c.spmv(x, y)
-        n = 200
-        us_warm = time_region(lambda: M.spmv(x, y), n, torch) * 1000.0 / n
-        state = {"i": 0}
-
-        def cold():
-            copies[state["i"] % n_copies].spmv(x, y)
-            state["i"] += 1
-        n = 5 * n_copies
-        us_cold = time_region(cold, n, torch) * 1000.0 / n
-        entry = {"alg_bytes": ab, "device_bytes": M.device_bytes(), "us_warm": round(us_warm, 3), "us_cold": round(us_cold, 3),
-                 "gbps_cold": round(ab / us_cold / 1e3, 1), "frac_hbm_cold": round(ab / us_cold / 1e3 / HBM_PEAK_GBS, 4),
-                 "frac_of_measured_stream_read_cold": round(ab / us_cold / 1e3 / stream_gbps, 4),
-                 "cold_copies": n_copies, "cold_bytes_total": n_copies * M.device_bytes()}
-        if name == "bf16":
+        entry = {"alg_bytes": ab, "device_bytes": M.device_bytes()}
+        if "spmv" in what:
+            if not cold_only:
+                entry["us_warm"] = round(time_queued([lambda: M.spmv(x, y)] * 20, 5, torch), 3)
+            us_cold = time_queued([lambda c=c: c.spmv(x, y) for c in copies], 4, torch)
+            entry.update({"us_cold": round(us_cold, 3), "gbps_cold": round(ab / us_cold / 1e3, 1),
+                          "frac_hbm_cold": round(ab / us_cold / 1e3 / HBM_PEAK_GBS, 4),
+                          "cold_copies": n_copies, "cold_bytes_total": n_copies * M.device_bytes()})
+            if stream_gbps:
+                entry["frac_of_measured_stream_read_cold"] = round(ab / us_cold / 1e3 / stream_gbps, 4)
+        if name == "bf16" and "spmm" in what:
             B = 128
             X = torch.from_numpy(csb_inputs.make_vectors(6, m.cols, B).reshape(m.cols, B)).cuda()
             Y = torch.empty((m.rows, B), dtype=torch.float32, device="cuda")
@@ -488,7 +622,10 @@ def val16_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
             nnz = int(M.view()["nnz"])
             entry["spmm_b128"] = {"us": round(us, 2), "tflops_algorithmic": round(2.0 * nnz * B / us / 1e6, 3),
                                   "note": "bfloat16 kernel values, float32 right-hand sides, f32 matrix cores (csb_spmm)"}
+        if name == "bf16" and "spmm_bfloat" in what:
             # bfloat16 right-hand sides too: csb_spmm_bfloat on the bf16 matrix cores
+            n = 20
+            nnz = int(M.view()["nnz"])
             bf = {}
             for Bb in (128, 512):
                 Xb = torch.from_numpy(csb_inputs.make_vectors(6, m.cols, Bb).reshape(m.cols, Bb)).cuda().to(torch.bfloat16)
@@ -509,12 +646,12 @@ def val16_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps):
     return res
 
 
-def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
+def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, cases=(("cfg5", 128), ("cfg4", 64)), with_rnn=True):
     """The batched (matrix-core) path: csb_spmm on the 8192^2 matrix with 128 right-hand sides
     and on a cfg4 layer matrix with 64, then the whole cfg4 workload (2-layer LSTM, batch 64,
     T = 256) through csb_rnn_forward.  Flops are the algorithmic 2 * nnz * batch."""
     res = {}
-    for name, batch in (("cfg5", 128), ("cfg4", 64)):
+    for name, batch in cases:
         if name == "cfg5":
             m = csb_inputs.make_mat(csb_inputs.CONFIGS[name])
         else:
@@ -538,14 +675,17 @@ def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn):
                                         "frac_fp32_mfma_peak": round(fl / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4),
                                         "l2_gather_bytes": int(gather), "l2_gather_gbps": round(gather / us / 1e3, 1)}
         del M
-    best = res["spmm_cfg5_b128"]
-    res["roofline"] = {"kernel": "csb::spmm_kernel<4, false, 16, true>", "bound": "mfma", "achieved": best["tflops_algorithmic"],
-                       "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": best["frac_fp32_mfma_peak"],
-                       "traffic": sum(TRAFFIC_BYTES["spmm_cfg5_b128"].values()),
-                       "us_per_launch": best["us"], "flops_per_launch": 2.0 * best["nnz"] * best["batch"],
-                       "note": "the matrix cores are the nominal roof; counters show the launch bound by the gather of X "
-                               "rows through L2 -> L1 (l2_gather_bytes at l2_gather_gbps; MFMA pipe a quarter busy, L1 "
-                               "stalled on outstanding misses half of the launch: profiles/spmm_cfg5_b128_pmc.txt)"}
+    best = res.get("spmm_cfg5_b128")
+    if best:
+        res["roofline"] = {"kernel": "csb::spmm_kernel<4, false, 16, true>", "bound": "mfma", "achieved": best["tflops_algorithmic"],
+                           "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": best["frac_fp32_mfma_peak"],
+                           "traffic": TRAFFIC_BYTES.get("spmm_cfg5_b128"),
+                           "us_per_launch": best["us"], "flops_per_launch": 2.0 * best["nnz"] * best["batch"],
+                           "note": "the matrix cores are the nominal roof; counters show the launch bound by the gather of X "
+                                   "rows through L2 -> L1 (l2_gather_bytes at l2_gather_gbps; MFMA pipe a quarter busy, L1 "
+                                   "stalled on outstanding misses half of the launch: profiles/spmm_cfg5_b128_pmc.txt)"}
+    if not with_rnn:
+        return res
     cfg = csb_inputs.CONFIGS["cfg4"]
     wl = csb_inputs.make_rnn(cfg)
     Ws = [CsbMatrix(w.A, w.br, w.bc) for w in wl.W]
@@ -588,7 +728,7 @@ def projection_leg(torch, np, stream_gbps, with_cpu):
            "roofline": {"kernel": "csb_project (5 kernels: row sums, select, column sums, select, masked copy)",
                         "bound": "hbm", "achieved": round(ab / (ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": round(ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
-                        "frac_of_measured_stream_read": round(ab / (ms * 1e-3) / 1e9 / stream_gbps, 4)},
+                        "frac_of_measured_stream_read": round(ab / (ms * 1e-3) / 1e9 / stream_gbps, 4) if stream_gbps else None},
            "density_out": round(float((Z != 0).float().mean()), 5)}
     if with_cpu:
         import oracle

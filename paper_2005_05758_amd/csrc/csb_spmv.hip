@@ -743,28 +743,42 @@ extern "C" int csb_spmv_static(const csb_matrix *m, const float *d_x, float *d_y
 }
 
 namespace csb {
-// Plain streaming read: the measured bandwidth the mat-vec figures are put next to.
-__global__ __launch_bounds__(256) void stream_read_kernel(const float4 *__restrict__ p, size_t n4, float *__restrict__ out) {
-    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n4; i += 4 * stride) {       // four independent loads in flight per thread
-        const float4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
-        s0 += a.x + a.y + a.z + a.w; s1 += b.x + b.y + b.z + b.w;
-        s2 += c.x + c.y + c.z + c.w; s3 += d.x + d.y + d.z + d.w;
+// Plain streaming read: the measured bandwidth the mat-vec figures are put next to.  Every
+// wavefront owns a contiguous range of 1-KiB units and keeps eight 16-byte non-temporal loads
+// per lane in flight (the fastest of the plain forms measured on this machine at 25 MB,
+// 100 MB and 1 GiB per launch).
+__global__ __launch_bounds__(1024) void stream_read_kernel(const float4 *__restrict__ p, size_t n4, float *__restrict__ out) {
+    typedef float f4v __attribute__((ext_vector_type(4)));
+    constexpr int K = 8;
+    const size_t nw = (size_t)gridDim.x * (blockDim.x >> 6);
+    const size_t w = (size_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t units = n4 >> 6;
+    const size_t u0 = units / nw * w + (w < units % nw ? w : units % nw);
+    const size_t u1 = u0 + units / nw + (w < units % nw ? 1 : 0);
+    float s = 0.0f;
+    for (size_t u = u0; u < u1; u += K) {
+        f4v r[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const size_t uu = u + k < u1 ? u + k : u1 - 1;            // the tail re-reads the last unit (cached)
+            r[k] = __builtin_nontemporal_load((const f4v *)(p + (uu << 6) + lane));
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) s += (r[k].x + r[k].y) + (r[k].z + r[k].w);
     }
-    for (; i < n4; i += stride) { const float4 a = p[i]; s0 += a.x + a.y + a.z + a.w; }
-    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = (s0 + s1) + (s2 + s3);
+    if (w == 0 && (size_t)lane < (n4 & 63)) { const float4 a = p[(units << 6) + lane]; s += (a.x + a.y) + (a.z + a.w); }
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
-constexpr int kStreamReadBlocks = 256 * 8;               // 8 workgroups of 256 threads per CU
+constexpr int kStreamReadBlocks = 256;                   // one workgroup of 16 wavefronts per CU
 }  // namespace csb
 
-extern "C" size_t csb_debug_stream_read_out_floats(void) { return (size_t)csb::kStreamReadBlocks * 256; }
+extern "C" size_t csb_debug_stream_read_out_floats(void) { return (size_t)csb::kStreamReadBlocks * 1024; }
 
 extern "C" int csb_debug_stream_read(const void *d_buf, size_t bytes, float *d_out, void *stream) {
     if (!d_buf || !d_out) { csb::set_error("csb_debug_stream_read: NULL pointer"); return CSB_EINVAL; }
     if (bytes % 16 || (uintptr_t)d_buf % 16) { csb::set_error("csb_debug_stream_read: buffer not a multiple of 16 bytes"); return CSB_EINVAL; }
-    hipLaunchKernelGGL(csb::stream_read_kernel, dim3(csb::kStreamReadBlocks), dim3(256), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(csb::stream_read_kernel, dim3(csb::kStreamReadBlocks), dim3(1024), 0, (hipStream_t)stream,
                        (const float4 *)d_buf, bytes / 16, d_out);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { csb::set_error(std::string("csb_debug_stream_read: ") + hipGetErrorString(e)); return CSB_EDEVICE; }

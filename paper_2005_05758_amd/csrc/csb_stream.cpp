@@ -10,8 +10,6 @@
 // can request all of its bytes at once from addresses that depend on nothing but the
 // workgroup and wavefront numbers.
 #include <algorithm>
-#include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -23,8 +21,9 @@ namespace {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Default size of a workgroup's share: two 64-lane groups per wavefront.
-constexpr uint64_t kLanesPerWg = 2048;
+// Default size of a workgroup's share: one 64-lane group per wavefront (small matrices spread over more
+// compute units; large ones are capped at 256 workgroups anyway).
+constexpr uint64_t kLanesPerWg = 1024;
 
 // One virtual block of a workgroup: kernel-matrix rows [a0, a1) of CSB block b.
 struct SVb {
@@ -119,20 +118,31 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                 const int nr = m->nrows[b], nc = m->ncols[b];
                 if (nr == 0 || nc == 0) continue;
                 const uint16_t *ri = m->rowidx.data() + m->row_off[b];
-                for (int a = 0; a < nr; ++a) roww[(size_t)bi * br + ri[a]] += 4u * (uint32_t)nc + 3u;
+                for (int a = 0; a < nr; ++a) roww[(size_t)bi * br + ri[a]] += (uint32_t)nc + (uint32_t)kStreamGroupOverhead;
                 lanes_total += (uint64_t)nr;
             }
-        uint64_t total_w = 0;
-        for (uint32_t v : roww) total_w += v;
+        // Steps 2 to 4 run several times: first with the rows weighted by the work they bring
+        // (column steps plus the per-piece overhead, per lane), then with corrected weights (below).
+        std::vector<double> rw(roww.begin(), roww.end());
+        std::vector<uint32_t> cut;      // row boundaries: workgroup k owns [cut[k], cut[k+1])
+        std::vector<WgLayout> W;
+        uint32_t nwg = 0, rows_max = 0, hdr_bytes = 0, tpr = 0;
+        const uint32_t x_bytes = (uint32_t)align_up((size_t)m->cols * 4, 16);
+        StreamPlan sp{};
+        bool found = false;
+        uint32_t nr_start = 1;
+        auto attempt = [&]() {
+        double total_w = 0;
+        for (double v : rw) total_w += v;
 
-        // ---- 2. row ranges of the workgroups: nearly equal bytes, cut at any row -----------
+        // ---- 2. row ranges of the workgroups: nearly equal weight, cut at any row ----------
         int64_t n_wg = n_wg_req > 0 ? n_wg_req : (int64_t)std::min<uint64_t>(256, std::max<uint64_t>(1, (lanes_total + kLanesPerWg - 1) / kLanesPerWg));
         n_wg = std::max<int64_t>(n_wg, (R + kStreamMaxRows - 1) / kStreamMaxRows);
         n_wg = std::min<int64_t>(n_wg, R);
-        std::vector<uint32_t> cut;      // row boundaries: workgroup k owns [cut[k], cut[k+1])
+        cut.clear();
         cut.push_back(0);
         {
-            uint64_t acc = 0;            // work of the rows before `row`
+            double acc = 0;              // weight of the rows before `row`
             int64_t k = 0;               // workgroup being filled
             for (int64_t row = 0; row < R; ++row) {
                 const int64_t rows_here = row - (int64_t)cut.back();
@@ -140,21 +150,21 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                     bool close = rows_here == kStreamMaxRows;
                     if (!close && k + 1 < n_wg) {
                         // the boundary in front of this row is nearer to the k-th target than the one behind it
-                        const uint64_t target = (uint64_t)((double)total_w * (double)(k + 1) / (double)n_wg);
-                        close = acc + roww[(size_t)row] / 2 >= target;
+                        const double target = total_w * (double)(k + 1) / (double)n_wg;
+                        close = acc + rw[(size_t)row] / 2 >= target;
                     }
                     if (close) { cut.push_back((uint32_t)row); ++k; }
                 }
-                acc += roww[(size_t)row];
+                acc += rw[(size_t)row];
             }
             cut.push_back((uint32_t)R);
         }
-        const uint32_t nwg = (uint32_t)cut.size() - 1;
+        nwg = (uint32_t)cut.size() - 1;
 
         // ---- 3. per workgroup: virtual blocks and kernel-matrix rows by descending column count,
         //         64 to a group: the lanes of a group then have (nearly) the same column count ----
-        std::vector<WgLayout> W(nwg);
-        uint32_t rows_max = 0;
+        W.assign(nwg, WgLayout{});
+        rows_max = 0;
         for (uint32_t k = 0; k < nwg; ++k) {
             WgLayout &w = W[k];
             w.row0 = cut[k];
@@ -185,53 +195,100 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
         }
 
         // ---- 4. rounds: the smallest count whose segments and partial sums fit the LDS ------
-        const uint32_t x_bytes = (uint32_t)align_up((size_t)m->cols * 4, 16);
-        const uint32_t hdr_bytes = (uint32_t)(sizeof(StreamRoundHdr) + align_up(4 * (size_t)rows_max, 16));
+        hdr_bytes = (uint32_t)(sizeof(StreamRoundHdr) + align_up(4 * (size_t)rows_max, 16));
         uint32_t rows_pad = 1;
         while (rows_pad < rows_max) rows_pad <<= 1;
-        const uint32_t tpr = std::min<uint32_t>(kWave, (uint32_t)kStreamThreads / rows_pad);
-        StreamPlan sp{};
-        bool found = false;
-        for (uint32_t NR = (uint32_t)std::max(1, rounds_min); NR <= 64 && !found; ++NR) {
+        tpr = std::min<uint32_t>(kWave, (uint32_t)kStreamThreads / rows_pad);
+        sp = StreamPlan{};
+        found = false;
+        // room for one segment if the partial sums took what the lanes and some cut pieces need
+        size_t lanes_max = 0;
+        for (const WgLayout &w : W) lanes_max = std::max(lanes_max, w.lanes.size());
+        const size_t fixed_lds = (size_t)x_bytes + hdr_bytes + 1024 + align_up(4 * (lanes_max + 24 * kWave), 16);
+        const size_t seg_room = fixed_lds + 16 * 1024 < (size_t)kLdsBudget
+            ? std::min<size_t>((size_t)kStreamMaxSegUnits * 1024, ((size_t)kLdsBudget - fixed_lds) / kStreamWaves / 16 * 16) : 1024;
+        // trials: rounds from the smallest on; per round count, smaller and smaller pieces while the
+        // largest piece is what keeps the segments from fitting
+        uint32_t NR = std::max<uint32_t>(nr_start, (uint32_t)std::max(1, rounds_min)), shrink = 0;
+        for (; NR <= 64 && !found;) {
             const uint32_t N = NR * kStreamWaves;
             uint32_t seg_max = 0, kmax = 0;
+            size_t piece_max = 0;
             bool ok = true, list_ok = true;
+            if (seg_room < 1024 + 512 * (size_t)shrink) break;
+            const size_t kPieceCap = seg_room - 512 * (size_t)shrink - sizeof(StreamSegHdr) - 16;
             for (uint32_t k = 0; k < nwg && ok; ++k) {
                 WgLayout &w = W[k];
                 const uint32_t G = (uint32_t)w.g_cmax.size();
-                // Equal work per wavefront share: the groups' column steps are cut into N ranges of
-                // nearly equal work, work being steps plus a fixed overhead per piece of a group (a
-                // piece is at least two steps long).  The groups are taken widest, narrowest, second
-                // widest, ... so that every share gets a similar mix of long and short pieces.  T is the
-                // smallest budget per share with which a greedy walk places everything (such a walk is
-                // not monotone in T: T goes up one by one from the lower bound).  Segments are read up
-                // to their own length, so their bytes need not be equal; the longest sets the LDS need.
+                // Equal work per wavefront: the groups' column steps are dealt to the 16 wavefronts, work
+                // being steps plus a fixed overhead per piece of a group (a piece is at least two steps
+                // long and its bytes fit one segment).  A wavefront is filled greedily up to a budget
+                // S: a group that does not fit is cut where the budget ends and goes on with the next
+                // wavefront; when a new group is started, the first one (in the order widest,
+                // narrowest, second widest, ... so that wavefronts get a mix of long and short pieces)
+                // that fills the rest of the budget exactly is taken, else the first that leaves room
+                // for another piece or overflows (and is cut), and only then one that would leave a
+                // rest too small to use.  S is the smallest budget with which everything is placed
+                // (such a walk is not monotone in S: S goes up one by one from the lower bound).
+                // The pieces of a wavefront are then dealt to its NR rounds in order, so that the
+                // largest segment is as small as can be; segments are read up to their own length,
+                // so their bytes need not be equal; the longest sets the LDS need.
                 std::vector<uint32_t> order(G);
                 for (uint32_t i = 0, lo = 0, hi = G; i < G; ++i) order[i] = (i & 1u) ? --hi : lo++;
-                auto walk = [&](uint64_t T, bool emit) {
-                    uint32_t i = 0, j = 0, used = 0;
-                    if (emit) w.share.assign(N, Share{});
-                    while (i < G) {
-                        if (used == N) return false;
-                        uint64_t budget = T;
-                        while (i < G) {
-                            const uint32_t g = order[i];
+                std::vector<uint8_t> done(G);
+                constexpr uint64_t kOv = kStreamGroupOverhead;
+                // lanes and virtual blocks of group g that still have columns at step j
+                auto live = [&](uint32_t g, uint32_t j, uint32_t *nl_out, uint32_t *nvb_out) {
+                    const uint32_t l0 = g * kWave, l1 = std::min<uint32_t>(l0 + kWave, (uint32_t)w.lanes.size());
+                    uint32_t nl = 0, nvb = 0;
+                    while (l0 + nl < l1 && w.vbs[w.lanes[l0 + nl].vb].c > j) {
+                        if (nl == 0 || w.lanes[l0 + nl].vb != w.lanes[l0 + nl - 1].vb) ++nvb;
+                        ++nl;
+                    }
+                    *nl_out = nl; *nvb_out = nvb;
+                };
+                std::vector<std::vector<Piece>> wave_pieces(kStreamWaves);
+                auto walk = [&](uint64_t S, bool emit) {
+                    uint32_t placed = 0, j = 0, used = 0, first_open = 0;
+                    int64_t cur = -1;
+                    std::fill(done.begin(), done.end(), (uint8_t)0);
+                    if (emit) for (auto &v : wave_pieces) v.clear();
+                    while (placed < G) {
+                        if (used == (uint32_t)kStreamWaves) return false;
+                        uint64_t budget = S;
+                        while (placed < G) {
+                            if (cur < 0) {
+                                while (first_open < G && done[order[first_open]]) ++first_open;
+                                int64_t exact = -1, roomy = -1, any = -1;
+                                for (uint32_t i = first_open; i < G && exact < 0; ++i) {
+                                    const uint32_t g = order[i];
+                                    if (done[g]) continue;
+                                    const uint64_t need = kOv + w.g_cmax[g];
+                                    if (budget < kOv + std::min<uint32_t>(w.g_cmax[g], 2u)) continue;   // cannot even start it
+                                    if (any < 0) any = g;
+                                    if (need == budget) exact = g;
+                                    else if (roomy < 0 && (need + kOv + 2 <= budget || (need > budget && need - budget >= 2))) roomy = g;
+                                }
+                                cur = exact >= 0 ? exact : roomy >= 0 ? roomy : any;
+                                if (cur < 0) break;                              // nothing can start in what is left
+                                j = 0;
+                            }
+                            const uint32_t g = (uint32_t)cur;
                             const uint32_t left = w.g_cmax[g] - j;
-                            if (budget < (uint64_t)kStreamGroupOverhead + std::min<uint32_t>(left, 2u)) break;
-                            uint32_t take = (uint32_t)std::min<uint64_t>(left, budget - kStreamGroupOverhead);
+                            if (budget < kOv + std::min<uint32_t>(left, 2u)) break;
+                            uint32_t nl, nvb;
+                            live(g, j, &nl, &nvb);
+                            // steps whose bytes (record, block words, lane words, padded lists, values) fit a segment
+                            const size_t fixed = sizeof(StreamGroup) + 4 * (size_t)nvb + align_up(2 * (size_t)nl, 4) + 3 * (size_t)nvb;
+                            const uint32_t fit = (uint32_t)((kPieceCap - std::min(kPieceCap, fixed)) / (kWave * sizeof(float) + nvb));
+                            if (fit < std::min<uint32_t>(left, 2u)) return false;
+                            uint32_t take = (uint32_t)std::min<uint64_t>(std::min(left, fit), budget - kOv);
                             if (left - take == 1u) --take;                   // never leave a one-step piece behind
                             if (take < std::min<uint32_t>(left, 2u)) break;
-                            if (emit) {
-                                // lanes of the group that still have columns at step j
-                                const uint32_t l0 = g * kWave, l1 = std::min<uint32_t>(l0 + kWave, (uint32_t)w.lanes.size());
-                                uint32_t nl = 0;
-                                while (l0 + nl < l1 && w.vbs[w.lanes[l0 + nl].vb].c > j) ++nl;
-                                w.share[used].pieces.push_back(Piece{g, (uint16_t)j, (uint16_t)(j + take), (uint16_t)nl});
-                                w.share[used].work += kStreamGroupOverhead + take;
-                            }
-                            budget -= kStreamGroupOverhead + take;
+                            if (emit) wave_pieces[used].push_back(Piece{g, (uint16_t)j, (uint16_t)(j + take), (uint16_t)nl});
+                            budget -= kOv + take;
                             j += take;
-                            if (j == w.g_cmax[g]) { ++i; j = 0; }
+                            if (j == w.g_cmax[g]) { done[g] = 1; ++placed; cur = -1; }
                         }
                         ++used;
                     }
@@ -239,9 +296,35 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                 };
                 uint64_t steps_all = 0;
                 for (uint32_t g = 0; g < G; ++g) steps_all += w.g_cmax[g];
-                uint64_t T = std::max<uint64_t>(kStreamGroupOverhead + 2, (steps_all + (uint64_t)kStreamGroupOverhead * G + N - 1) / N);
-                while (!walk(T, false)) ++T;
-                walk(T, true);
+                uint64_t S = std::max<uint64_t>(kOv + 2, (steps_all + kOv * G + kStreamWaves - 1) / kStreamWaves);
+                const uint64_t S_stop = steps_all + kOv * G + kOv * kStreamWaves + 64;    // one wavefront could take it all
+                while (S <= S_stop && !walk(S, false)) ++S;
+                if (S > S_stop) { ok = false; break; }
+                walk(S, true);
+                // deal every wavefront's pieces to its rounds: the smallest limit on a round's bytes
+                // with which NR runs in order hold them all
+                w.share.assign(N, Share{});
+                for (uint32_t wv = 0; wv < (uint32_t)kStreamWaves; ++wv) {
+                    const std::vector<Piece> &pc = wave_pieces[wv];
+                    std::vector<size_t> pb(pc.size());
+                    size_t lo = 0, hi = 0;
+                    for (size_t i = 0; i < pc.size(); ++i) { pb[i] = piece_size(w, pc[i]).total(); lo = std::max(lo, pb[i]); hi += pb[i]; }
+                    piece_max = std::max(piece_max, lo);
+                    auto runs_needed = [&](size_t limit) {
+                        uint32_t runs = 1; size_t acc = 0;
+                        for (size_t v : pb) { if (acc + v > limit && acc > 0) { ++runs; acc = 0; } acc += v; }
+                        return runs;
+                    };
+                    while (lo < hi) { const size_t mid = (lo + hi) / 2; if (runs_needed(mid) <= NR) hi = mid; else lo = mid + 1; }
+                    uint32_t r = 0; size_t acc = 0;
+                    for (size_t i = 0; i < pc.size(); ++i) {
+                        if (acc + pb[i] > lo && acc > 0) { ++r; acc = 0; }
+                        acc += pb[i];
+                        Share &sh = w.share[(size_t)r * kStreamWaves + wv];
+                        sh.pieces.push_back(pc[i]);
+                        sh.work += (double)(kOv + (pc[i].j1 - pc[i].j0));
+                    }
+                }
                 // sizes, and the number of partial sums (one per lane and piece)
                 w.kmax = 0;                                     // here: partial sums of the workgroup
                 for (uint32_t s = 0; s < N; ++s) {
@@ -254,9 +337,6 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                         w.kmax += p.nl;
                     }
                     sh.bytes = (uint32_t)align_up(tot.total(), 16);
-                    if (getenv("CSB_PLAN_DEBUG2") && k == 0)
-                        fprintf(stderr, "  wg %u share %u: pieces %zu steps %zu vbs %zu lane_bytes %zu list_bytes %zu bytes %u work %.0f G %u T %llu\n", k, s,
-                                sh.pieces.size(), tot.steps, tot.vbs, tot.lane_bytes, tot.list_bytes, sh.bytes, sh.work, G, (unsigned long long)T);
                     seg_max = std::max(seg_max, sh.bytes);
                     if (tot.list_pos() + tot.list_bytes > (size_t)kStreamListLimit) list_ok = false;   // 10-bit list word index
                 }
@@ -266,18 +346,58 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
             const uint32_t kstride = std::max(1u, kmax);     // partial-sum slots of the fullest workgroup
             // (1 KiB of slack behind the segments: a padded list byte may name an input up to 255 floats past a block's first)
             const size_t lds = (size_t)x_bytes + hdr_bytes + align_up((size_t)kstride * 4, 16) + (size_t)kStreamWaves * seg_max + 1024;
-            if (getenv("CSB_PLAN_DEBUG")) {
-                uint64_t sb = 0, ns = 0; for (auto &w : W) for (auto &sh : w.share) { sb += sh.bytes; ++ns; }
-                fprintf(stderr, "rows plan: NR %u ok %d list_ok %d seg_max %u seg_mean %.0f kmax %u rows_max %u lds %zu\n", NR, (int)ok, (int)list_ok, seg_max, (double)sb / ns, kmax, rows_max, lds);
-            }
             if (!ok) break;                                  // more rounds do not shrink what failed
-            if (!list_ok || seg_max > (uint32_t)kStreamMaxSegUnits * 1024u || lds > (size_t)kLdsBudget) continue;
+            if (!list_ok || seg_max > (uint32_t)kStreamMaxSegUnits * 1024u || lds > (size_t)kLdsBudget) {
+                // segments of one piece: smaller pieces help; else more rounds do
+                if ((size_t)seg_max <= piece_max + sizeof(StreamSegHdr) + 16 && shrink < 10) ++shrink; else { ++NR; }
+                continue;
+            }
             sp.n_wg = nwg; sp.n_rounds = NR; sp.seg_bytes = seg_max; sp.hdr_bytes = hdr_bytes;
             sp.wg_bytes = (uint32_t)align_up((size_t)hdr_bytes + (size_t)N * seg_max, 256);
             sp.kmax = kstride; sp.rows_max = rows_max; sp.tpr = tpr; sp.lds_bytes = (uint32_t)lds;
             found = true;
         }
+        };   // attempt
+
+        // largest wavefront work of a workgroup
+        auto wg_max = [&](const WgLayout &w) {
+            double v = 0;
+            for (uint32_t wv = 0; wv < (uint32_t)kStreamWaves; ++wv) {
+                double ww = 0;
+                for (uint32_t r = 0; r < sp.n_rounds; ++r) ww += w.share[(size_t)r * kStreamWaves + wv].work;
+                v = std::max(v, ww);
+            }
+            return v;
+        };
+        attempt();
         if (!found) return CSB_OK;
+        nr_start = sp.n_rounds;                                 // the later passes do not look below it
+        if (nwg > 1) {
+            // Feedback on the row cuts: a workgroup whose fullest wavefront is above the average gives
+            // rows away (its rows weigh more in the next pass).  The best pass is kept: the one with
+            // the smallest largest wavefront work, then the smallest sum of the workgroups' largest.
+            std::vector<double> best_rw = rw;
+            double best_max = 0, best_sum = 0;
+            for (const WgLayout &w : W) { const double v = wg_max(w); best_max = std::max(best_max, v); best_sum += v; }
+            bool last_is_best = true;
+            for (int pass = 0; pass < 8 && best_max * nwg > best_sum * 1.02; ++pass) {
+                double sum = 0;
+                for (const WgLayout &w : W) sum += wg_max(w);
+                const double target = sum / nwg;
+                for (uint32_t k = 0; k < nwg; ++k) {
+                    const double f = 1.0 + 0.7 * (wg_max(W[k]) / target - 1.0);
+                    for (uint32_t r = cut[k]; r < cut[k + 1]; ++r) rw[r] *= f;
+                }
+                attempt();
+                last_is_best = false;
+                if (!found) break;
+                double mx = 0, sm = 0;
+                for (const WgLayout &w : W) { const double v = wg_max(w); mx = std::max(mx, v); sm += v; }
+                if (mx < best_max || (mx == best_max && sm < best_sum)) { best_max = mx; best_sum = sm; best_rw = rw; last_is_best = true; }
+            }
+            if (!last_is_best) { rw = best_rw; attempt(); }
+            if (!found) return CSB_OK;
+        }
 
         // ---- 5. write the section -----------------------------------------------------------
         const size_t off = align_up(pl.image.size(), 256);

@@ -334,3 +334,35 @@ def test_gru_matrix_keeps_its_row_layout_when_planned_again():
     assert refused_as_gru()
     M.validate()
     del rnn
+
+
+@pytest.mark.parametrize("name,limit", [("cfg5", 1.10), ("cfg5_diag", 1.10)])
+def test_default_plan_balances_the_stress_matrices(name, limit):
+    """The plan csb_spmv runs by default (row-owned layout): largest wavefront work over the mean
+    stays within 10 % on the 8192^2 heavy-tailed matrices, and the bytes one launch reads stay
+    within 15 % of the algorithmic bytes."""
+    m = csb_inputs.make_mat(csb_inputs.CONFIGS[name])
+    M = CsbMatrix(m.A, m.br, m.bc)
+    st = M.plan()
+    assert st["row_owned"] == 1 and st["n_chunks"] == 256
+    assert st["work_max"] / st["work_mean"] <= limit, (st["work_max"], st["work_mean"])
+    v = M.view()
+    alg = 4 * int(v["nnz"]) + len(v["rowidx"]) + len(v["colidx"]) + 2 * int(v["nbr"]) * int(v["nbc"]) + 4 * int(v["cols"]) + 4 * int(v["rows"])
+    assert st["matvec_bytes"] <= 1.15 * alg
+    M.validate()
+
+
+def test_small_matrix_plans_trade_balance_for_short_wavefronts():
+    """On the RNN matrices a wavefront holds one or two groups, and a group costs a fixed amount
+    whatever its width, so the ratio largest / mean cannot be small AND the wavefronts short; the
+    default takes short wavefronts (more workgroups).  With half as many workgroups the same
+    matrix balances within 10 %, and the largest wavefront's work is then at least as large."""
+    m = csb_inputs.make_rnn(csb_inputs.CONFIGS["cfg3"], T=1).W[0]
+    M = CsbMatrix(m.A, m.br, m.bc)
+    st = M.plan()
+    assert st["row_owned"] == 1
+    M2 = CsbMatrix(m.A, m.br, m.bc)
+    st2 = M2.plan_rows(max(1, (3 * st["n_chunks"]) // 4), 0)
+    assert st2["work_max"] / st2["work_mean"] <= 1.10
+    assert st2["work_max"] >= st["work_max"]
+    M.validate(); M2.validate()
