@@ -206,7 +206,7 @@ static_assert(sizeof(StreamGroup) == 16, "StreamGroup layout");
 
 // A virtual block (consecutive kernel-matrix rows of one CSB block, a range of its columns) is
 // one 32-bit word: bits 0-9 the 4-byte word index of its column index list inside the segment
-// (bytes; padded with zeros to the group's steps rounded up to 4), bits 10-17 its column
+// (bytes; padded with its first byte to the piece's steps rounded up to 4), bits 10-17 its column
 // count - 1, bits 18-31 the block column of the CSB block (its first input is block column * bc).
 constexpr uint32_t stream_vb_word(uint32_t list_word, uint32_t c_minus_1, uint32_t bj) { return list_word | (c_minus_1 << 10) | (bj << 18); }
 
@@ -221,6 +221,7 @@ struct StreamPlan {
     uint32_t tpr = 0;           // threads that share an output row in the row-sum pass (power of two)
     uint32_t lds_bytes = 0;
     uint32_t n_groups = 0;
+    uint32_t val_fmt = 0;       // CSB_VAL_*: 32-bit values, or 16-bit ones (a column step is then a run of 64 half words)
     uint64_t off = 0, bytes = 0;   // the section inside the image
 };
 

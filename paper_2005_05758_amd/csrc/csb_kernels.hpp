@@ -34,11 +34,70 @@ __device__ __host__ inline GateSrc plain_src(const float *v) {
     return g;
 }
 
+#ifdef __HIPCC__
+__device__ __forceinline__ float sigmoid_(float v) { return 1.0f / (1.0f + expf(-v)); }
+
+// h_t of unit u of the cell whose gate sums are s.a (Sec. 2.1; LSTM rows i,f,g,o; GRU rows r,z,
+// input side of n, recurrent side of n; Li-GRU rows z, candidate), the same arithmetic as the
+// stand-alone gate kernels.  `store`: also write the new state (and the output sequence).
+__device__ __forceinline__ float gate_value(const GateSrc &s, uint32_t u, bool store) {
+    const uint32_t H = s.H;
+    const float *a = s.a, *b = s.bias;
+    float hn, cn = 0.0f;
+    if (s.kind == 1u + CSB_CELL_LSTM) {
+        float ai = a[u], af = a[H + u], ag = a[2 * H + u], ao = a[3 * H + u];
+        if (b) { ai += b[u]; af += b[H + u]; ag += b[2 * H + u]; ao += b[3 * H + u]; }
+        cn = sigmoid_(af) * s.c_in[u] + sigmoid_(ai) * tanhf(ag);
+        hn = sigmoid_(ao) * tanhf(cn);
+    } else if (s.kind == 1u + CSB_CELL_GRU) {
+        float ar = a[u], az = a[H + u], anx = a[2 * H + u];
+        const float anh = a[3 * H + u];
+        if (b) { ar += b[u]; az += b[H + u]; anx += b[2 * H + u]; }
+        const float r = sigmoid_(ar), z = sigmoid_(az);
+        hn = (1.0f - z) * tanhf(anx + r * anh) + z * s.h_in[u];
+    } else if (s.kind == kGateRbReset) {                       // rows r,z,n; only r is needed here
+        float ar = a[u];
+        if (b) ar += b[u];
+        hn = sigmoid_(ar) * s.h_in[u];
+    } else if (s.kind == kGateRbGate) {
+        float az = a[H + u], an = a[2 * H + u] + s.a2[u];
+        if (b) { az += b[H + u]; an += b[2 * H + u]; }
+        const float z = sigmoid_(az);
+        hn = (1.0f - z) * tanhf(an) + z * s.h_in[u];
+    } else {                                                   // Li-GRU
+        float az = a[u], ac = a[H + u];
+        if (b) { az += b[u]; ac += b[H + u]; }
+        const float z = sigmoid_(az);
+        hn = z * s.h_in[u] + (1.0f - z) * fmaxf(ac, 0.0f);
+    }
+    if (store) {
+        if (s.c_out) s.c_out[u] = cn;
+        if (s.h_out) s.h_out[u] = hn;
+        if (s.hseq) s.hseq[u] = hn;
+    }
+    return hn;
+}
+
+// One segment of the input vector into LDS: a plain copy, or the cell outputs computed on the way.
+__device__ __forceinline__ void stage_segment(float *z, const GateSrc &s, uint32_t n, uint32_t tid, uint32_t nthreads, bool store) {
+    if (s.kind == 0u) {                                        // uniform
+        for (uint32_t u = tid; u < n; u += nthreads) z[u] = s.a[u];
+    } else {
+        for (uint32_t u = tid; u < n; u += nthreads) z[u] = gate_value(s, u, store);
+    }
+}
+#endif
+
 // y = A [x0[0..n0) ; x1[0..cols-n0)] on `stream`; y has the image's rows_out entries.
 int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const float *d_x1, float *d_y,
                   void *d_ws, void *stream, unsigned long long *d_stamps = nullptr);
 // y = A x from the row-owned stream section of the image (plan.stream.valid) on `stream`.
 int spmv_rows(const csb_matrix *m, const float *d_x, float *d_y, void *stream, unsigned long long *d_stamps = nullptr);
+// The same with the input vector in two segments, either one possibly a cell output still to be
+// computed (see GateSrc); several independent such products in one launch (at most kMaxJobsPerLaunch).
+int spmv_rows_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *stream);
+struct SpmvGatedCall;
+int spmv_rows_gated_multi(const SpmvGatedCall *calls, int n, void *stream);
 // ... with either segment possibly a cell output still to be computed (see GateSrc).
 int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *d_ws, void *stream);
 // The element-wise part alone, one thread per unit: stores c_t, h_t (and hseq) of `s`.

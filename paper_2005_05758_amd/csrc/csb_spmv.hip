@@ -122,58 +122,6 @@ __device__ __forceinline__ void unpack_pair(uint32_t w, float &lo, float &hi) {
     }
 }
 
-__device__ __forceinline__ float sigmoid_(float v) { return 1.0f / (1.0f + expf(-v)); }
-
-// h_t of unit u of the cell whose gate sums are s.a (Sec. 2.1; LSTM rows i,f,g,o; GRU rows r,z,
-// input side of n, recurrent side of n; Li-GRU rows z, candidate), the same arithmetic as the
-// stand-alone gate kernels.  `store`: also write the new state (and the output sequence).
-__device__ __forceinline__ float gate_value(const GateSrc &s, uint32_t u, bool store) {
-    const uint32_t H = s.H;
-    const float *a = s.a, *b = s.bias;
-    float hn, cn = 0.0f;
-    if (s.kind == 1u + CSB_CELL_LSTM) {
-        float ai = a[u], af = a[H + u], ag = a[2 * H + u], ao = a[3 * H + u];
-        if (b) { ai += b[u]; af += b[H + u]; ag += b[2 * H + u]; ao += b[3 * H + u]; }
-        cn = sigmoid_(af) * s.c_in[u] + sigmoid_(ai) * tanhf(ag);
-        hn = sigmoid_(ao) * tanhf(cn);
-    } else if (s.kind == 1u + CSB_CELL_GRU) {
-        float ar = a[u], az = a[H + u], anx = a[2 * H + u];
-        const float anh = a[3 * H + u];
-        if (b) { ar += b[u]; az += b[H + u]; anx += b[2 * H + u]; }
-        const float r = sigmoid_(ar), z = sigmoid_(az);
-        hn = (1.0f - z) * tanhf(anx + r * anh) + z * s.h_in[u];
-    } else if (s.kind == kGateRbReset) {                       // rows r,z,n; only r is needed here
-        float ar = a[u];
-        if (b) ar += b[u];
-        hn = sigmoid_(ar) * s.h_in[u];
-    } else if (s.kind == kGateRbGate) {
-        float az = a[H + u], an = a[2 * H + u] + s.a2[u];
-        if (b) { az += b[H + u]; an += b[2 * H + u]; }
-        const float z = sigmoid_(az);
-        hn = (1.0f - z) * tanhf(an) + z * s.h_in[u];
-    } else {                                                   // Li-GRU
-        float az = a[u], ac = a[H + u];
-        if (b) { az += b[u]; ac += b[H + u]; }
-        const float z = sigmoid_(az);
-        hn = z * s.h_in[u] + (1.0f - z) * fmaxf(ac, 0.0f);
-    }
-    if (store) {
-        if (s.c_out) s.c_out[u] = cn;
-        if (s.h_out) s.h_out[u] = hn;
-        if (s.hseq) s.hseq[u] = hn;
-    }
-    return hn;
-}
-
-// One segment of the input vector into LDS: a plain copy, or the cell outputs computed on the way.
-__device__ __forceinline__ void stage_segment(float *z, const GateSrc &s, uint32_t n, uint32_t tid, uint32_t nthreads, bool store) {
-    if (s.kind == 0u) {                                        // uniform
-        for (uint32_t u = tid; u < n; u += nthreads) z[u] = s.a[u];
-    } else {
-        for (uint32_t u = tid; u < n; u += nthreads) z[u] = gate_value(s, u, store);
-    }
-}
-
 __global__ void commit_gates_kernel(const GateSrc s) {
     const uint32_t u = blockIdx.x * blockDim.x + threadIdx.x;
     if (u < s.H) gate_value(s, u, true);
@@ -581,12 +529,13 @@ int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const flo
 int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *d_ws, void *stream) {
     if (!m->plan.valid || !m->uploaded || !m->d_buf) { set_error("csb_spmv: matrix not planned and uploaded"); return CSB_ESTATE; }
     if (m->plan.hdr.cols > (uint64_t)kMaxStageCols) { set_error("csb_spmv: more columns than the LDS staging covers"); return CSB_EUNSUPPORTED; }
-    if (m->plan.hdr.n_partial_slots && !d_ws) { set_error("csb_spmv: workspace is NULL"); return CSB_EINVAL; }
     // a computed segment has exactly one entry per unit of its cell
     if ((s0.kind && s0.H != n0) || (s1.kind && (uint64_t)s1.H + n0 != m->plan.hdr.cols)) {
         set_error("csb_spmv: a computed input segment does not match the matrix's column split");
         return CSB_EINVAL;
     }
+    if (m->plan.stream.valid) return spmv_rows_gated(m, s0, n0, s1, d_y, stream);      // row-owned layout: no workspace
+    if (m->plan.hdr.n_partial_slots && !d_ws) { set_error("csb_spmv: workspace is NULL"); return CSB_EINVAL; }
     SpmvSrc<true> g0, g1;
     static_cast<GateSrc &>(g0) = s0;
     static_cast<GateSrc &>(g1) = s1;
@@ -598,6 +547,15 @@ int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSr
 // Up to kMaxJobsPerLaunch independent gated mat-vecs in ONE launch (same value format); otherwise,
 // or for a single one, a launch each.
 int spmv_gated_multi(const SpmvGatedCall *calls, int n, void *stream) {
+    bool rows = n > 1 && n <= kMaxJobsPerLaunch;            // every product in the row-owned layout: one launch of that kernel
+    for (int i = 0; i < n && rows; ++i) {
+        const csb_matrix *m = calls[i].mat;
+        rows = m->plan.valid && m->uploaded && m->d_buf && m->plan.stream.valid && m->plan.hdr.cols <= (uint64_t)kMaxStageCols &&
+               m->plan.stream.val_fmt == calls[0].mat->plan.stream.val_fmt &&
+               !(calls[i].s0.kind && calls[i].s0.H != calls[i].n0) &&
+               !(calls[i].s1.kind && (uint64_t)calls[i].s1.H + calls[i].n0 != m->plan.hdr.cols);
+    }
+    if (rows) return spmv_rows_gated_multi(calls, n, stream);
     bool together = n > 1 && n <= kMaxJobsPerLaunch;
     for (int i = 0; i < n && together; ++i) {
         const csb_matrix *m = calls[i].mat;

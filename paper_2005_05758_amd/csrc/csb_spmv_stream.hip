@@ -40,6 +40,13 @@ struct RowsArgs {
     uint32_t cols, kmax, tpr_log2, x_fast;
     uint32_t off_hdr, off_part, off_seg, bc;     // LDS map (bytes); width of a block column
     unsigned long long *stamps;                  // optional clock stamps (debug): 8 per wavefront
+    uint32_t n_wg, n0;                           // workgroups of this matrix; gated form: entries of the first input segment
+    GateSrc g0, g1;                              // gated form: the two segments of the input vector
+};
+
+// The arguments of up to kMaxJobsPerLaunch independent products that share a launch (blockIdx.y).
+struct RowsJobs {
+    RowsArgs a[kMaxJobsPerLaunch];
 };
 
 // LDS accesses by LDS byte address.
@@ -83,13 +90,25 @@ __device__ __forceinline__ void wait_outstanding() {
     else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
 }
 
-// W: units of round 0 a wavefront requests ahead of its multiplication.
-template <int W>
-__global__ __launch_bounds__(kStreamThreads) void spmv_rows_kernel(const RowsArgs A) {
+// W: units of round 0 a wavefront requests ahead of its multiplication.  GATED: the input vector
+// is two segments, either one possibly the output of a cell whose gate sums an earlier launch
+// left behind (the streaming RNN step: the cell arithmetic of step t - 1 is done while step t
+// stages its input, every workgroup for itself, workgroup 0 also storing the new state).
+// VF: storage format of the kernel values (CSB_VAL_*); a column step is a run of 64 values.
+template <int VF>
+__device__ __forceinline__ float lds_val(uint32_t a) {
+    if constexpr (VF == CSB_VAL_F32) return lds_f32(a);
+    else if constexpr (VF == CSB_VAL_BF16) return __uint_as_float(lds_u16(a) << 16);
+    else return (float)__builtin_bit_cast(_Float16, (uint16_t)lds_u16(a));
+}
+
+template <int W, bool GATED, int VF>
+__device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) {
+    constexpr uint32_t VB = VF == CSB_VAL_F32 ? 4u : 2u, SS = 64u * VB;      // bytes of a value, of a column step
     extern __shared__ float4 smem4[];
     uint8_t *smem = (uint8_t *)smem4;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uni_(tid >> 6);
-    const uint8_t *wb = A.img + (size_t)blockIdx.x * A.wg_bytes;
+    const uint8_t *wb = A.img + (size_t)wg * A.wg_bytes;
     const uint32_t seg16 = A.seg_bytes >> 4, hdr16 = A.hdr_bytes >> 4;
     uint32_t NU = (A.seg_bytes + 1023u) >> 10;                // 1 KiB units of a segment (of the current one, once its header is in)
     uint32_t own16 = seg16;                                    // its length in 16-byte pieces
@@ -100,7 +119,10 @@ __global__ __launch_bounds__(kStreamThreads) void spmv_rows_kernel(const RowsArg
     if (A.stamps) t_start = wall_clock64();
 
     // ---- requests: the input vector and the header first, then the whole segment of round 0 --
-    if (A.x_fast) {                                            // every wavefront's first requests: they arrive first
+    if constexpr (GATED) {
+        // (the segment's first units are requested below, before the cell arithmetic, whose loads
+        // come back behind them)
+    } else if (A.x_fast) {                                     // every wavefront's first requests: they arrive first
         const uint32_t x16 = A.cols >> 2;                      // 16-byte pieces of the vector
         for (uint32_t u = wave; u * 64u < x16; u += kStreamWaves) {
             if (u * 64u + lane < x16) dma16((const uint8_t *)A.x + (size_t)u * 1024u + lane * 16u, lds0 + u * 1024u);
@@ -128,7 +150,12 @@ __global__ __launch_bounds__(kStreamThreads) void spmv_rows_kernel(const RowsArg
         if (u + (uint32_t)W <= NU) wait_outstanding<W - 1>(); else wait_outstanding<0>();
     };
     want_unit(0u);
-    if (A.x_fast) { if (NU >= (uint32_t)W) wait_outstanding<W>(); else wait_outstanding<0>(); }   // the wavefront's part of the vector has landed
+    if constexpr (GATED) {
+        float *xl = (float *)smem;
+        const uint32_t na = min(A.n0, A.cols);
+        stage_segment(xl, A.g0, na, tid, kStreamThreads, wg == 0u);
+        stage_segment(xl + na, A.g1, A.cols - na, tid, kStreamThreads, wg == 0u);
+    } else if (A.x_fast) { if (NU >= (uint32_t)W) wait_outstanding<W>(); else wait_outstanding<0>(); }   // the wavefront's part of the vector has landed
     // (a plain barrier: the fence builtins would also wait for the segment, which is still on its way)
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     if (A.stamps) t_x = wall_clock64();
@@ -184,25 +211,25 @@ __global__ __launch_bounds__(kStreamThreads) void spmv_rows_kernel(const RowsArg
             const uint32_t word = lds_u16(s0 + lane_off + 2u * (act ? lane : 0u));
             const uint32_t la = s0 + (vbw & 0x3ffu) * 4u;                               // its block's column list
             const uint32_t xb = lds0 + (vbw >> 18) * A.bc * 4u;                         // the block's first input
-            const uint32_t vb0a = s0 + (val_off + lane) * 4u;                           // the lane's value of step 0
+            const uint32_t vb0a = s0 + val_off * 4u + lane * VB;                        // the lane's value of step 0
             if (r == 0u) {                                      // round 0: have the group's values landed?
-                const uint32_t need = (val_off * 4u + cmax * 256u + 1023u) >> 10;       // units up to its last step
+                const uint32_t need = (val_off * 4u + cmax * SS + 1023u) >> 10;         // units up to its last step
                 if (need > have) { want_unit(need - 1u); wait_unit(need - 1u); have = need; want_unit(need); }
             }
             float a0 = 0.0f, a1 = 0.0f;
             // Eight (then four) column steps at a time, all loads issued before the first use: the
             // values at constant offsets (a step is a run of 64 floats, zero where a lane has no
             // column left), the inputs where the list bytes point.  No predicates: a zero value times
-            // the input a padded list byte names (column 0 of the block) adds nothing.
+            // the input a padded list byte names (the first column of the slice, one the row uses anyway) adds nothing.
             uint32_t j = 0;
             uint32_t cw = lds_u32(la);
             for (; j + 8u <= cmax; j += 8u) {
-                const uint32_t vj = vb0a + j * 256u;
+                const uint32_t vj = vb0a + j * SS;
                 const uint32_t cw2 = lds_u32(la + j + 4u);
-                const float v0 = lds_f32(vj), v1 = lds_f32(vj + 256u), v2 = lds_f32(vj + 512u), v3 = lds_f32(vj + 768u);
+                const float v0 = lds_val<VF>(vj), v1 = lds_val<VF>(vj + SS), v2 = lds_val<VF>(vj + 2u * SS), v3 = lds_val<VF>(vj + 3u * SS);
                 const float x0 = lds_f32(xb + (cw & 0xffu) * 4u), x1 = lds_f32(xb + ((cw >> 8) & 0xffu) * 4u);
                 const float x2 = lds_f32(xb + ((cw >> 16) & 0xffu) * 4u), x3 = lds_f32(xb + (cw >> 24) * 4u);
-                const float v4 = lds_f32(vj + 1024u), v5 = lds_f32(vj + 1280u), v6 = lds_f32(vj + 1536u), v7 = lds_f32(vj + 1792u);
+                const float v4 = lds_val<VF>(vj + 4u * SS), v5 = lds_val<VF>(vj + 5u * SS), v6 = lds_val<VF>(vj + 6u * SS), v7 = lds_val<VF>(vj + 7u * SS);
                 const float x4 = lds_f32(xb + (cw2 & 0xffu) * 4u), x5 = lds_f32(xb + ((cw2 >> 8) & 0xffu) * 4u);
                 const float x6 = lds_f32(xb + ((cw2 >> 16) & 0xffu) * 4u), x7 = lds_f32(xb + (cw2 >> 24) * 4u);
                 cw = lds_u32(la + j + 8u);                      // the next steps' list bytes
@@ -210,8 +237,8 @@ __global__ __launch_bounds__(kStreamThreads) void spmv_rows_kernel(const RowsArg
                 a0 = fmaf(v4, x4, a0); a1 = fmaf(v5, x5, a1); a0 = fmaf(v6, x6, a0); a1 = fmaf(v7, x7, a1);
             }
             if (j + 4u <= cmax) {
-                const uint32_t vj = vb0a + j * 256u;
-                const float v0 = lds_f32(vj), v1 = lds_f32(vj + 256u), v2 = lds_f32(vj + 512u), v3 = lds_f32(vj + 768u);
+                const uint32_t vj = vb0a + j * SS;
+                const float v0 = lds_val<VF>(vj), v1 = lds_val<VF>(vj + SS), v2 = lds_val<VF>(vj + 2u * SS), v3 = lds_val<VF>(vj + 3u * SS);
                 const float x0 = lds_f32(xb + (cw & 0xffu) * 4u), x1 = lds_f32(xb + ((cw >> 8) & 0xffu) * 4u);
                 const float x2 = lds_f32(xb + ((cw >> 16) & 0xffu) * 4u), x3 = lds_f32(xb + (cw >> 24) * 4u);
                 cw = lds_u32(la + j + 4u);
@@ -219,14 +246,14 @@ __global__ __launch_bounds__(kStreamThreads) void spmv_rows_kernel(const RowsArg
                 j += 4u;
             }
             if (j < cmax) {                                     // one to three steps left
-                const uint32_t vj = vb0a + j * 256u;
-                a0 = fmaf(lds_f32(vj), lds_f32(xb + (cw & 0xffu) * 4u), a0);
-                if (j + 1u < cmax) a1 = fmaf(lds_f32(vj + 256u), lds_f32(xb + ((cw >> 8) & 0xffu) * 4u), a1);
-                if (j + 2u < cmax) a0 = fmaf(lds_f32(vj + 512u), lds_f32(xb + ((cw >> 16) & 0xffu) * 4u), a0);
+                const uint32_t vj = vb0a + j * SS;
+                a0 = fmaf(lds_val<VF>(vj), lds_f32(xb + (cw & 0xffu) * 4u), a0);
+                if (j + 1u < cmax) a1 = fmaf(lds_val<VF>(vj + SS), lds_f32(xb + ((cw >> 8) & 0xffu) * 4u), a1);
+                if (j + 2u < cmax) a0 = fmaf(lds_val<VF>(vj + 2u * SS), lds_f32(xb + ((cw >> 16) & 0xffu) * 4u), a0);
             }
             if (act) part[word] = a0 + a1;
             if (more) {                                         // units behind us: request them for the next round
-                const uint32_t cur = (val_off * 4u + cmax * 256u) >> 10;
+                const uint32_t cur = (val_off * 4u + cmax * SS) >> 10;
                 if (released < cur && released < NUn) {
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                     while (released < cur && released < NUn) request_unit(r + 1u, released++, next16);
@@ -260,22 +287,38 @@ __global__ __launch_bounds__(kStreamThreads) void spmv_rows_kernel(const RowsArg
         if (sub == 0u && rr < nrows) A.y[row0 + rr] = s;
     }
     if (A.stamps && lane == 0u) {
-        unsigned long long *st = A.stamps + ((size_t)blockIdx.x * kStreamWaves + wave) * 8;
+        unsigned long long *st = A.stamps + ((size_t)wg * kStreamWaves + wave) * 8;
         st[0] = t_start; st[1] = t_x; st[2] = t_first; st[3] = t_first; st[4] = t_done; st[5] = t_bar; st[6] = wall_clock64();
     }
 }
 
-}  // namespace
+template <int W, int VF>
+__global__ __launch_bounds__(kStreamThreads) void spmv_rows_kernel(const RowsArgs A) {
+    rows_body<W, false, VF>(A, blockIdx.x);
+}
 
-int spmv_rows(const csb_matrix *m, const float *d_x, float *d_y, void *stream, unsigned long long *d_stamps) {
+template <int W, int VF>
+__global__ __launch_bounds__(kStreamThreads) void spmv_rows_gated_kernel(const RowsArgs A) {
+    rows_body<W, true, VF>(A, blockIdx.x);
+}
+
+// blockIdx.y selects the product; the grid is as wide as the largest of them.
+template <int W, int VF>
+__global__ __launch_bounds__(kStreamThreads) void spmv_rows_gated_multi_kernel(const RowsJobs J) {
+    const RowsArgs &A = J.a[blockIdx.y];
+    if (blockIdx.x >= A.n_wg) return;
+    rows_body<W, true, VF>(A, blockIdx.x);
+}
+
+// Kernel arguments of one product and the dynamic LDS it needs (0 with the error set if it does not fit).
+size_t rows_args(const csb_matrix *m, RowsArgs *out) {
     const StreamPlan &sp = m->plan.stream;
     RowsArgs A{};
     A.img = (const uint8_t *)m->d_buf + sp.off;
-    A.x = d_x; A.y = d_y; A.stamps = d_stamps;
     A.n_rounds = sp.n_rounds; A.wg_bytes = sp.wg_bytes; A.hdr_bytes = sp.hdr_bytes; A.seg_bytes = sp.seg_bytes;
     A.cols = (uint32_t)m->cols; A.kmax = sp.kmax; A.bc = (uint32_t)m->bc;
     A.tpr_log2 = (uint32_t)__builtin_ctz(sp.tpr);
-    A.x_fast = ((uintptr_t)d_x % 16 == 0 && m->cols % 4 == 0) ? 1u : 0u;
+    A.n_wg = sp.n_wg;
     const uint32_t x_bytes = (uint32_t)(((size_t)m->cols * 4 + 15) / 16 * 16);
     const uint32_t part_bytes = (uint32_t)(((size_t)sp.kmax * 4 + 15) / 16 * 16);
     A.off_hdr = x_bytes;
@@ -283,17 +326,63 @@ int spmv_rows(const csb_matrix *m, const float *d_x, float *d_y, void *stream, u
     A.off_seg = A.off_part + part_bytes;
     // 1 KiB of slack behind the last segment: lanes that are done keep reading a little further
     const size_t lds = (size_t)A.off_seg + (size_t)kStreamWaves * sp.seg_bytes + 1024;
-    if (lds > (size_t)160 * 1024) { set_error("csb_spmv: row-owned layout does not fit the LDS"); return CSB_EUNSUPPORTED; }
-    auto go = [&](auto kern) -> hipError_t {
-        hipError_t e_ = ensure_dynamic_lds((const void *)kern, lds);
-        if (e_ != hipSuccess) return e_;
-        hipLaunchKernelGGL(kern, dim3(sp.n_wg), dim3(kStreamThreads), lds, (hipStream_t)stream, A);
-        return hipGetLastError();
-    };
-    // two units ahead: measured best on the 8192 x 8192 stress matrix (8.9 us cold; three: 9.2, four: 9.6)
-    const hipError_t e = go(spmv_rows_kernel<2>);
+    if (lds > (size_t)160 * 1024) { set_error("csb_spmv: row-owned layout does not fit the LDS"); return 0; }
+    *out = A;
+    return lds;
+}
+
+template <typename Kern, typename Arg>
+int launch_rows(Kern kern, dim3 grid, size_t lds, void *stream, const Arg &arg) {
+    hipError_t e = ensure_dynamic_lds((const void *)kern, lds);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), lds, (hipStream_t)stream, arg);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) { set_error(std::string("csb_spmv: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
+}
+
+}  // namespace
+
+int spmv_rows(const csb_matrix *m, const float *d_x, float *d_y, void *stream, unsigned long long *d_stamps) {
+    RowsArgs A;
+    const size_t lds = rows_args(m, &A);
+    if (!lds) return CSB_EUNSUPPORTED;
+    A.x = d_x; A.y = d_y; A.stamps = d_stamps;
+    A.x_fast = ((uintptr_t)d_x % 16 == 0 && m->cols % 4 == 0) ? 1u : 0u;
+    // two units ahead: measured best on the 8192 x 8192 stress matrix (8.9 us cold; three: 9.2, four: 9.6)
+    const uint32_t vf = m->plan.stream.val_fmt;
+    if (vf == CSB_VAL_F16) return launch_rows(spmv_rows_kernel<2, CSB_VAL_F16>, dim3(A.n_wg), lds, stream, A);
+    if (vf == CSB_VAL_BF16) return launch_rows(spmv_rows_kernel<2, CSB_VAL_BF16>, dim3(A.n_wg), lds, stream, A);
+    return launch_rows(spmv_rows_kernel<2, CSB_VAL_F32>, dim3(A.n_wg), lds, stream, A);
+}
+
+int spmv_rows_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *stream) {
+    RowsArgs A;
+    const size_t lds = rows_args(m, &A);
+    if (!lds) return CSB_EUNSUPPORTED;
+    A.y = d_y; A.g0 = s0; A.g1 = s1; A.n0 = n0;
+    const uint32_t vf = m->plan.stream.val_fmt;
+    if (vf == CSB_VAL_F16) return launch_rows(spmv_rows_gated_kernel<2, CSB_VAL_F16>, dim3(A.n_wg), lds, stream, A);
+    if (vf == CSB_VAL_BF16) return launch_rows(spmv_rows_gated_kernel<2, CSB_VAL_BF16>, dim3(A.n_wg), lds, stream, A);
+    return launch_rows(spmv_rows_gated_kernel<2, CSB_VAL_F32>, dim3(A.n_wg), lds, stream, A);
+}
+
+int spmv_rows_gated_multi(const SpmvGatedCall *calls, int n, void *stream) {
+    RowsJobs J{};
+    size_t lds = 0;
+    uint32_t wgs = 0;
+    for (int i = 0; i < n; ++i) {
+        const size_t l = rows_args(calls[i].mat, &J.a[i]);
+        if (!l) return CSB_EUNSUPPORTED;
+        J.a[i].y = calls[i].y; J.a[i].g0 = calls[i].s0; J.a[i].g1 = calls[i].s1; J.a[i].n0 = calls[i].n0;
+        lds = std::max(lds, l);
+        wgs = std::max(wgs, J.a[i].n_wg);
+    }
+    const uint32_t vf = calls[0].mat->plan.stream.val_fmt;             // (the caller has checked: one format for all)
+    if (vf == CSB_VAL_F16) return launch_rows(spmv_rows_gated_multi_kernel<2, CSB_VAL_F16>, dim3(wgs, (unsigned)n), lds, stream, J);
+    if (vf == CSB_VAL_BF16) return launch_rows(spmv_rows_gated_multi_kernel<2, CSB_VAL_BF16>, dim3(wgs, (unsigned)n), lds, stream, J);
+    return launch_rows(spmv_rows_gated_multi_kernel<2, CSB_VAL_F32>, dim3(wgs, (unsigned)n), lds, stream, J);
 }
 
 }  // namespace csb

@@ -63,8 +63,9 @@ struct WgLayout {
 
 struct SegSize {
     size_t groups = 0, vbs = 0, lane_bytes = 0, list_bytes = 0, steps = 0;
+    size_t vbytes = 4;                                    // bytes of one kernel value (4, or 2 in a 16-bit format)
     size_t list_pos() const { return sizeof(StreamSegHdr) + groups * sizeof(StreamGroup) + vbs * 4 + lane_bytes; }
-    size_t total() const { return align_up(list_pos() + list_bytes, 16) + steps * kWave * sizeof(float); }
+    size_t total() const { return align_up(list_pos() + list_bytes, 16) + steps * kWave * vbytes; }
 };
 
 // Walks the virtual blocks of one piece: f(vb index, first lane of the run inside the group, rows, columns kept).
@@ -82,8 +83,9 @@ void for_piece_vbs(const WgLayout &w, const Piece &p, F f) {
     }
 }
 
-SegSize piece_size(const WgLayout &w, const Piece &p) {
+SegSize piece_size(const WgLayout &w, const Piece &p, size_t vbytes) {
     SegSize s;
+    s.vbytes = vbytes;
     s.groups = 1;
     s.steps = (size_t)(p.j1 - p.j0);
     const size_t list_len = align_up(s.steps, 4);        // every list is padded to the piece's steps
@@ -103,7 +105,8 @@ SegSize piece_size(const WgLayout &w, const Piece &p) {
 int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_stats *stats_out) {
     Plan &pl = m->plan;
     pl.stream = StreamPlan{};
-    if (pl.split.active() || m->val_fmt != CSB_VAL_F32) return CSB_OK;
+    if (pl.split.active()) return CSB_OK;
+    const size_t vbytes = m->val_fmt == CSB_VAL_F32 ? 4 : 2;
     if (m->cols > kMaxStageCols || m->rows > 0x7fffffff) return CSB_OK;
     try {
         const int br = m->br;
@@ -280,7 +283,7 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                             live(g, j, &nl, &nvb);
                             // steps whose bytes (record, block words, lane words, padded lists, values) fit a segment
                             const size_t fixed = sizeof(StreamGroup) + 4 * (size_t)nvb + align_up(2 * (size_t)nl, 4) + 3 * (size_t)nvb;
-                            const uint32_t fit = (uint32_t)((kPieceCap - std::min(kPieceCap, fixed)) / (kWave * sizeof(float) + nvb));
+                            const uint32_t fit = (uint32_t)((kPieceCap - std::min(kPieceCap, fixed)) / (kWave * vbytes + nvb));
                             if (fit < std::min<uint32_t>(left, 2u)) return false;
                             uint32_t take = (uint32_t)std::min<uint64_t>(std::min(left, fit), budget - kOv);
                             if (left - take == 1u) --take;                   // never leave a one-step piece behind
@@ -308,7 +311,7 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                     const std::vector<Piece> &pc = wave_pieces[wv];
                     std::vector<size_t> pb(pc.size());
                     size_t lo = 0, hi = 0;
-                    for (size_t i = 0; i < pc.size(); ++i) { pb[i] = piece_size(w, pc[i]).total(); lo = std::max(lo, pb[i]); hi += pb[i]; }
+                    for (size_t i = 0; i < pc.size(); ++i) { pb[i] = piece_size(w, pc[i], vbytes).total(); lo = std::max(lo, pb[i]); hi += pb[i]; }
                     piece_max = std::max(piece_max, lo);
                     auto runs_needed = [&](size_t limit) {
                         uint32_t runs = 1; size_t acc = 0;
@@ -330,8 +333,9 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                 for (uint32_t s = 0; s < N; ++s) {
                     Share &sh = w.share[s];
                     SegSize tot;
+                    tot.vbytes = vbytes;
                     for (const Piece &p : sh.pieces) {
-                        const SegSize ps = piece_size(w, p);
+                        const SegSize ps = piece_size(w, p, vbytes);
                         tot.groups += ps.groups; tot.vbs += ps.vbs; tot.lane_bytes += ps.lane_bytes;
                         tot.list_bytes += ps.list_bytes; tot.steps += ps.steps;
                         w.kmax += p.nl;
@@ -423,7 +427,7 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                 uint8_t *seg = wb + sp.hdr_bytes + (size_t)s * sp.seg_bytes;
                 SegSize tot;
                 for (const Piece &p : sh.pieces) {
-                    const SegSize ps = piece_size(w, p);
+                    const SegSize ps = piece_size(w, p, vbytes);
                     tot.groups += ps.groups; tot.vbs += ps.vbs; tot.lane_bytes += ps.lane_bytes; tot.list_bytes += ps.list_bytes;
                 }
                 StreamSegHdr hd{};
@@ -449,27 +453,36 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                     sg.lane_off = (uint16_t)lane_pos;
                     sg.val_off = (uint16_t)val_pos;
                     sg.nlanes = (uint8_t)p.nl;
-                    float *dst = (float *)seg + val_pos;               // [steps][64], zero where a lane has no column
+                    uint8_t *dst = seg + val_pos * 4;                  // [steps][64] values (32 or 16 bits), zero where a lane has no column
                     for_piece_vbs(w, p, [&](uint32_t v, uint32_t lane0, uint32_t rws, int ck) {
                         const SVb &vb = w.vbs[v];
                         sg.start_mask |= 1ull << lane0;
                         const uint32_t word = stream_vb_word((uint32_t)(list_pos / 4), (uint32_t)(ck - 1), vb.b % (uint32_t)m->nbc);
                         std::memcpy(seg + off_vbs + (size_t)vb_idx * 4, &word, 4);
                         ++vb_idx;
-                        // column indices; behind them, up to the piece's steps, zeros: a valid column whose
-                        // values are stored as zeros
+                        // column indices; behind them, up to the piece's steps, the slice's first column again:
+                        // an input every row of the block multiplies anyway (so a non-finite input
+                        // reaches only rows that use it), here with values stored as zeros
                         const uint16_t *ci = m->colidx.data() + m->col_off[vb.b] + p.j0;
-                        for (int j = 0; j < ck; ++j) seg[list_pos + j] = (uint8_t)ci[j];
+                        for (size_t j = 0; j < list_len; ++j) seg[list_pos + j] = (uint8_t)ci[j < (size_t)ck ? j : 0];
                         list_pos += list_len;
                         const float *kv = m->val.data() + m->val_off[vb.b];
                         for (uint32_t i = 0; i < rws; ++i) {
                             const Lane &ln = w.lanes[l0 + lane0 + i];
-                            for (int j = 0; j < ck; ++j) dst[(size_t)j * kWave + lane0 + i] = kv[(size_t)ln.a * vb.c + p.j0 + j];
+                            for (int j = 0; j < ck; ++j) {
+                                const float v = kv[(size_t)ln.a * vb.c + p.j0 + j];
+                                const size_t at = (size_t)j * kWave + lane0 + i;
+                                if (vbytes == 4) std::memcpy(dst + at * 4, &v, 4);
+                                else {
+                                    const uint16_t b16 = m->val_fmt == CSB_VAL_F16 ? f32_to_f16_bits(v) : f32_to_bf16_bits(v);
+                                    std::memcpy(dst + at * 2, &b16, 2);
+                                }
+                            }
                             const uint16_t lw = (uint16_t)next[ln.rr]++;
                             std::memcpy(seg + lane_pos + 2 * (size_t)(lane0 + i), &lw, 2);
                         }
                     });
-                    val_pos += (size_t)steps * kWave;
+                    val_pos += (size_t)steps * kWave * vbytes / 4;
                     lane_pos += align_up(2 * (size_t)p.nl, 4);
                     std::memcpy(seg + off_groups + gi * sizeof(StreamGroup), &sg, sizeof(sg));
                     ++n_groups;
@@ -483,6 +496,7 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
             }
         }
         sp.n_groups = n_groups;
+        sp.val_fmt = (uint32_t)m->val_fmt;
         sp.valid = true;
         pl.stream = sp;
 
@@ -532,6 +546,19 @@ int validate_stream(const csb_matrix *m) {
     if (sp.seg_bytes > (uint32_t)kStreamMaxSegUnits * 1024u || sp.rows_max > (uint32_t)kStreamMaxRows) return fail("limits");
     if (sp.hdr_bytes < sizeof(StreamRoundHdr) + 4 * (size_t)sp.rows_max) return fail("header size");
     if (sp.tpr == 0 || (sp.tpr & (sp.tpr - 1)) || sp.tpr > (uint32_t)kWave || sp.rows_max * sp.tpr > (uint32_t)kStreamThreads) return fail("threads per row");
+    if (sp.val_fmt != (uint32_t)m->val_fmt) return fail("value format");
+    const size_t vbytes = sp.val_fmt == CSB_VAL_F32 ? 4 : 2;
+    // bits of the value of lane `lane` at step j of a piece whose values start at 4-byte word val_off, widened to float bits
+    auto value_bits = [&](const uint8_t *seg, uint32_t val_off, uint32_t j, uint32_t lane) {
+        const uint8_t *at = seg + (size_t)val_off * 4 + ((size_t)j * kWave + lane) * vbytes;
+        uint32_t bits = 0;
+        if (vbytes == 4) { std::memcpy(&bits, at, 4); return bits; }
+        uint16_t b16;
+        std::memcpy(&b16, at, 2);
+        const float f = sp.val_fmt == CSB_VAL_F16 ? f16_bits_to_f32(b16) : bf16_bits_to_f32(b16);
+        std::memcpy(&bits, &f, 4);
+        return bits;
+    };
     const int64_t R = m->rows, Ccols = m->cols;
     std::vector<float> expect((size_t)R * Ccols, 0.0f), got((size_t)R * Ccols, 0.0f);
     std::vector<uint8_t> seen((size_t)R * Ccols, 0);
@@ -577,14 +604,11 @@ int validate_stream(const csb_matrix *m) {
                 if (sg.nlanes == 0 || sg.nlanes > kWave || !(sg.start_mask & 1ull)) return fail("group lanes");
                 if (sg.nlanes < kWave && (sg.start_mask >> sg.nlanes)) return fail("start mask beyond the lanes");
                 if ((size_t)sg.lane_off + 2u * sg.nlanes > SB || sg.lane_off % 2) return fail("lane words");
-                if (((size_t)sg.val_off + (size_t)steps * kWave) * 4 > SB) return fail("value offset");
+                if ((size_t)sg.val_off * 4 + (size_t)steps * kWave * vbytes > SB) return fail("value offset");
                 for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                     if (lane >= sg.nlanes) {                       // lanes without a row: zeros only
-                        for (uint32_t j = 0; j < steps; ++j) {
-                            uint32_t bits;
-                            std::memcpy(&bits, seg + ((size_t)sg.val_off + (size_t)j * kWave + lane) * 4, 4);
-                            if (bits) return fail("value behind the last lane not zero");
-                        }
+                        for (uint32_t j = 0; j < steps; ++j)
+                            if (value_bits(seg, sg.val_off, j, lane)) return fail("value behind the last lane not zero");
                         continue;
                     }
                     const uint64_t upto = lane == 63 ? ~0ull : ((2ull << lane) - 1ull);
@@ -607,9 +631,12 @@ int validate_stream(const csb_matrix *m) {
                         const int64_t col = (int64_t)bj * m->bc + seg[lw + j];
                         if (col >= Ccols) return fail("column index");
                         if (j >= steps) continue;
-                        uint32_t bits;
-                        std::memcpy(&bits, seg + ((size_t)sg.val_off + (size_t)j * kWave + lane) * 4, 4);
-                        if (j >= c) { if (bits) return fail("padding value not zero"); continue; }
+                        const uint32_t bits = value_bits(seg, sg.val_off, j, lane);
+                        if (j >= c) {
+                            if (bits) return fail("padding value not zero");
+                            if (seg[lw + j] != seg[lw]) return fail("padding column is not the block's first");
+                            continue;
+                        }
                         const size_t e = (size_t)(row0 + rr) * Ccols + col;
                         if (seen[e]) return fail("entry stored twice");
                         seen[e] = 1;
