@@ -22,7 +22,20 @@ _LIB = os.path.join(_HERE, "libcsb_oracle.so")
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (plain -O2, OpenMP over output rows)."""
+    """Compile the oracle with gcc (plain -O2, OpenMP over output rows).  With
+    CSB_ORACLE_SANITIZE=<path of a clang> in the environment it is compiled by that clang with
+    AddressSanitizer and UndefinedBehaviorSanitizer instead (single-threaded, a library of its
+    own name), for runs of the CPU test suite under the sanitizer runtime."""
+    san = os.environ.get("CSB_ORACLE_SANITIZE")
+    if san:
+        lib = os.path.join(_HERE, "libcsb_oracle_sanitize.so")
+        if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+            tmp = lib + f".tmp{os.getpid()}"
+            subprocess.check_call([san, "-O1", "-g", "-std=c99", "-fPIC", "-shared", "-fsanitize=address,undefined",
+                                   "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-shared-libsan",
+                                   "-Wno-unknown-pragmas", "-o", tmp, _SRC, "-lm"])
+            os.replace(tmp, lib)
+        return lib
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
@@ -37,8 +50,7 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = C.CDLL(_LIB)
+        _lib = C.CDLL(build())
         _lib.orc_num_threads.restype = C.c_int
         _lib.orc_csb_encode.restype = C.c_int
         _lib.orc_csb_decode.restype = C.c_int

@@ -19,13 +19,33 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every source for gfx950 and link the shared library.  Always compiles."""
+def sanitizer_runtime() -> str:
+    """The shared AddressSanitizer runtime of hipcc's clang (what a sanitized build needs preloaded)."""
+    out = subprocess.run([hipcc(), "-print-file-name=libclang_rt.asan-x86_64.so"], stdout=subprocess.PIPE, text=True).stdout.strip()
+    if os.path.isabs(out) and os.path.exists(out):
+        return out
+    import glob
+    hits = sorted(glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so"))
+    return hits[-1] if hits else out
+
+
+def build(verbose: bool = False, sanitize: bool = False) -> str:
+    """Compile every source for gfx950 and link the shared library.  Always compiles.
+    sanitize: the HOST code (packer, planners, validators, launch wrappers) is built with
+    AddressSanitizer and UndefinedBehaviorSanitizer; device code is untouched.  The CPU test suite
+    then runs as
+        LD_PRELOAD=<sanitizer_runtime()> ASAN_OPTIONS=detect_leaks=0 python -m pytest tests -m "not gpu"
+    (the interpreter itself is not instrumented, hence the preload and no leak report).  Build
+    again without the flag afterwards: a sanitized library is not for the GPU machine."""
     cmd = [hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
            # packed-FP32 VALU forms are switched off for all device code
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-command-line-argument"]
+    if sanitize:
+        cmd[1] = "-O1"
+        cmd += ["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                "-Xarch_host", "-fno-omit-frame-pointer", "-Xarch_host", "-fno-sanitize-recover=undefined", "-shared-libsan"]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     tmp = LIB + f".tmp{os.getpid()}"
     cmd += ["-o", tmp]
@@ -41,4 +61,7 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    san = "--sanitize" in sys.argv[1:]
+    print(build(verbose=True, sanitize=san))
+    if san:
+        print("run the CPU tests with: LD_PRELOAD=" + sanitizer_runtime() + " ASAN_OPTIONS=detect_leaks=0 python -m pytest tests -m 'not gpu'")

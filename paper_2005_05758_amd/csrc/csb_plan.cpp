@@ -833,8 +833,10 @@ int validate_plan(const csb_matrix *m) {
             if (sid >= 0) {
                 if ((uint32_t)sid >= h.n_shared || shared[sid].tile != tile) return fail("shared tile record");
                 if ((uint32_t)part >= shared[sid].nparts) return fail("shared part number");
-                if (parts_seen[sid] >> part & 1 && shared[sid].nparts <= 32) return fail("shared part twice");
-                if (shared[sid].nparts <= 32) parts_seen[sid] |= 1u << part;
+                if (shared[sid].nparts <= 32) {                // (the seen-mask covers tiles of up to 32 parts)
+                    if (parts_seen[sid] >> part & 1u) return fail("shared part twice");
+                    parts_seen[sid] |= 1u << part;
+                }
                 if (shared[sid].partial_off + shared[sid].nparts > h.n_partial_slots) return fail("partial slot");
                 tile_written[tile] = 1;   // by the last part to arrive
             } else {
