@@ -75,6 +75,13 @@ __device__ __forceinline__ void dma16(const uint8_t *g, uint32_t lds_base) {
     __builtin_amdgcn_global_load_lds((glb_void_t *)g, (lds_void_t *)(uintptr_t)lds_base, 16, 0, 0);
 }
 
+// The value of another lane by a data-parallel-primitive move (CTRL: which lane; lanes the move
+// has no source for read zero).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), CTRL, 0xf, 0xf, true));
+}
+
 // Waits until at most N of the wavefront's vector memory operations are outstanding.
 template <int N>
 __device__ __forceinline__ void wait_outstanding() {
@@ -283,7 +290,14 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
             const float *pr = part + (oc & 0xffffu);
             for (uint32_t k = sub; k < (oc >> 16); k += tpr) s += pr[k];
         }
-        for (uint32_t o = tpr >> 1; o; o >>= 1) s += __shfl_xor(s, (int)o);
+        // the row's threads are neighbours: the first of them collects the sum, a fixed tree of
+        // cross-lane moves (inside a 16-lane row without going through the LDS crossbar)
+        if (tpr >= 2u) s += dpp_f32<0xB1>(s);                  // lanes 1,0,3,2 of every four
+        if (tpr >= 4u) s += dpp_f32<0x4E>(s);                  // lanes 2,3,0,1
+        if (tpr >= 8u) s += dpp_f32<0x104>(s);                 // the lane four further on (zero past the row's end)
+        if (tpr >= 16u) s += dpp_f32<0x108>(s);                // eight further on
+        if (tpr >= 32u) s += __shfl_down(s, 16);
+        if (tpr >= 64u) s += __shfl_down(s, 32);
         if (sub == 0u && rr < nrows) A.y[row0 + rr] = s;
     }
     if (A.stamps && lane == 0u) {
@@ -350,7 +364,8 @@ int spmv_rows(const csb_matrix *m, const float *d_x, float *d_y, void *stream, u
     if (!lds) return CSB_EUNSUPPORTED;
     A.x = d_x; A.y = d_y; A.stamps = d_stamps;
     A.x_fast = ((uintptr_t)d_x % 16 == 0 && m->cols % 4 == 0) ? 1u : 0u;
-    // two units ahead: measured best on the 8192 x 8192 stress matrix (8.9 us cold; three: 9.2, four: 9.6)
+    // two units ahead: measured best on the 8192 x 8192 stress matrix (cold, us: 8.1 with two, 8.6 with three, 9.0 with
+    // four, 10.0 with six units ahead after the first): what a wavefront asks for far ahead delays what its neighbours need next
     const uint32_t vf = m->plan.stream.val_fmt;
     if (vf == CSB_VAL_F16) return launch_rows(spmv_rows_kernel<2, CSB_VAL_F16>, dim3(A.n_wg), lds, stream, A);
     if (vf == CSB_VAL_BF16) return launch_rows(spmv_rows_kernel<2, CSB_VAL_BF16>, dim3(A.n_wg), lds, stream, A);
