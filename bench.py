@@ -677,13 +677,14 @@ def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, cases=(("cfg5", 128), 
         del M
     best = res.get("spmm_cfg5_b128")
     if best:
-        res["roofline"] = {"kernel": "csb::spmm_kernel<4, false, 16, true>", "bound": "mfma", "achieved": best["tflops_algorithmic"],
+        res["roofline"] = {"kernel": "csb::spmm_reg_kernel<false, 16, 2>", "bound": "mfma", "achieved": best["tflops_algorithmic"],
                            "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": best["frac_fp32_mfma_peak"],
                            "traffic": TRAFFIC_BYTES.get("spmm_cfg5_b128"),
                            "us_per_launch": best["us"], "flops_per_launch": 2.0 * best["nnz"] * best["batch"],
-                           "note": "the matrix cores are the nominal roof; counters show the launch bound by the gather of X "
-                                   "rows through L2 -> L1 (l2_gather_bytes at l2_gather_gbps; MFMA pipe a quarter busy, L1 "
-                                   "stalled on outstanding misses half of the launch: profiles/spmm_cfg5_b128_pmc.txt)"}
+                           "note": "the matrix cores are the roof; counters (profiles/spmm_cfg5_b128_pmc.txt): the matrix pipe is "
+                                   "busy about half of the launch, with 1.65 x the MFMAs of the kernel-row form (rows are "
+                                   "scattered to their tile rows in the operand, which keeps the results in registers); the "
+                                   "gather of X rows is not the bound (all gathers pointed at one row: 3 % faster)"}
     if not with_rnn:
         return res
     cfg = csb_inputs.CONFIGS["cfg4"]

@@ -137,7 +137,7 @@ struct DevMat {
     uint32_t rows_out, cols;
     uint32_t n_groups, n_nz_tiles;
     uint32_t idx_bytes, val_fmt;   // val_fmt != 0: vals holds one 32-bit word per lane and PAIR of steps (even step low)
-    uint32_t seg_meta, pad_;       // LDS bytes the batched kernel sets aside for one record segment
+    uint32_t seg_meta, vals_bytes; // LDS bytes the batched kernel sets aside for one record segment; bytes of the value stream (saturated)
 };
 
 // How rows are relabelled when the image is built for a GRU: entries in rows >= split_row

@@ -467,6 +467,209 @@ __global__ __launch_bounds__(NW * 64) void spmm_bf16_kernel(const DevMat m, cons
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// The wide form for float32 kernel values and row tiles of 16 or 32 rows, with the results
+// kept in registers.  Counters of the general kernel above on the 8192 x 8192 matrix with 128
+// right-hand sides show what its launch time is made of: the LDS is busy 90 % of the launch
+// (every 16-row slice of every block adds its 16 x 64 results into the wavefront's accumulator
+// tile: four 16-byte reads and four writes per lane, 16 clocks each), the matrix pipe a
+// quarter, and pointing every gather at ONE row of X makes it only 7 % faster -- the gather is
+// not the bound.  Here the kernel operand of an MFMA is not the block's kernel matrix but its
+// rows ALREADY SCATTERED to their places in the row tile: for each 16-row part of the tile, lane
+// (row, k) holds the block's value at that tile row, or zero if the block does not keep the
+// row.  The 16 x 64 results of a part then add up in the SAME registers over all blocks the
+// wavefront works on, and go to LDS once, at the end.  The price is matrix-pipe work for parts
+// a block has few rows in (parts it has none in are skipped).  Which kernel row sits at a tile
+// row comes from a 64-byte map per wavefront in LDS that the block's lanes fill from their row
+// slots.  A pass ALWAYS issues 4 NH kernel-value loads and four 16-byte input loads (k-steps and
+// parts a block does not have repeat a valid address and are not multiplied), so the loads of
+// the NEXT pass are in flight while this pass multiplies and the compiler's counted waits hold.
+// Same records, same value layout, same merge of the wavefronts' tiles as the general kernel.
+template <int NH>
+struct RegOps {
+    float av[NH][4];
+    float4 bv[4];
+    uint32_t parts;              // bit h: the block has rows in part h (uniform)
+};
+struct RegPass {
+    uint32_t k, kc;              // virtual block (inside the segment), first column of the pass
+    uint32_t r, c, lane0;        // the block's rows, columns, first lane
+    uint32_t val_off, desc, list;
+    bool valid;
+};
+
+template <bool TWO, int NW, int NH>
+__device__ __forceinline__ void spmm_reg_body(const DevMat &m, const XSrc &X, float *__restrict__ Y, const int64_t ldy,
+                                              const uint32_t batch, const uint32_t block_x, const uint32_t block_y) {
+    extern __shared__ float4 smem4[];
+    constexpr uint32_t NB = 64, NTHR = NW * 64;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uni_(tid >> 6);
+    const uint32_t bt0 = block_y * NB;
+    const uint32_t br = m.br;                                      // == 16 NH
+    if (block_x >= m.n_nz_tiles) {                 // a row tile without work: zeros
+        const uint32_t tile = m.zero_tiles[block_x - m.n_nz_tiles];
+        for (uint32_t e = tid; e < br * NB; e += NTHR) {
+            const uint32_t row = tile * br + e / NB, n = bt0 + e % NB;
+            if (row < m.rows_out && n < batch) Y[(size_t)row * ldy + n] = 0.0f;
+        }
+        return;
+    }
+    uint8_t *meta = (uint8_t *)smem4;                              // one record segment
+    float *acc = (float *)(meta + m.seg_meta);                     // [waves][br][NB]
+    float *myacc = acc + (size_t)wave * br * NB;
+    uint8_t *inv = (uint8_t *)(acc + (size_t)NW * br * NB) + wave * 64u;   // tile row -> kernel row of the current block, 0xff: none
+    const uint32_t rank = block_x, tile = m.nz_tiles[rank];
+    const uint32_t mrow = lane & 15u, kq = lane >> 4;              // A: tile row in its part, column-in-4; B: right-hand sides 4 mrow .. + 3, row-in-4
+    const uint32_t ncol = bt0 + 4u * mrow;
+    const uint32_t nbyte = (ncol < batch ? ncol : 0u) * 4u;        // (batch is a multiple of 4: the four are in or out together)
+    const uint8_t *const x0 = (const uint8_t *)X.p0 + nbyte, *const x1 = (const uint8_t *)X.p1 + nbyte;
+    const uint32_t split4 = 4u * X.n0;
+    floatx4 D[NH][4];
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) D[h][nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    for (uint32_t sg = m.tile_seg0[rank]; sg < m.tile_seg0[rank + 1]; ++sg) {
+        // ---- stage the segment's records ------------------------------------------------
+        const SegRec *sp = m.segs + sg;
+        const uint32_t ga = sp->g0, ng = sp->ng, vb0 = sp->vb0, nvbs = sp->nvbs, idx0 = sp->idx0, idx_bytes = sp->idx_bytes;
+        const uint32_t voff = (ng * (uint32_t)sizeof(GroupRec) + 15u) & ~15u;
+        const uint32_t ioff = voff + ((nvbs * (uint32_t)sizeof(VbRec) + 15u) & ~15u);
+        __syncthreads();                                           // the previous segment is done with
+        {
+            const uint2 *gs = (const uint2 *)(m.groups + ga);
+            uint2 *gd = (uint2 *)meta;
+            for (uint32_t i = tid; i < ng * 3u; i += NTHR) gd[i] = gs[i];
+            const float4 *vs = (const float4 *)(m.vbs + vb0);
+            float4 *vd = (float4 *)(meta + voff);
+            for (uint32_t i = tid; i < nvbs; i += NTHR) vd[i] = vs[i];
+            const float4 *is = (const float4 *)(m.idx + idx0);
+            float4 *id = (float4 *)(meta + ioff);
+            for (uint32_t i = tid; i < idx_bytes >> 4; i += NTHR) id[i] = is[i];
+        }
+        __syncthreads();
+        if (wave >= nvbs) continue;                                // (uniform per wavefront; the barriers above are passed by all)
+
+        // Kernel values come through a buffer descriptor over the value stream: a load whose offset lies
+        // past the stream returns zero, which is what a lane without a row or a column gets (its offset
+        // is pushed there), so no operand is ever masked after the load.
+        const __amdgpu_buffer_rsrc_t vrsrc = __builtin_amdgcn_make_buffer_rsrc((void *)m.vals, 0, (int)m.vals_bytes, 0x00020000);
+        uint32_t irow4[NH];                                        // byte offset of this lane's kernel row in the current block's values, per part (bit 31: none)
+        uint32_t parts = 0;
+        // Opens virtual block k < nvbs: its record, and the map from tile rows to its kernel rows.
+        auto open_vb = [&](uint32_t k, RegPass &p) {
+            const uint4 v = *(const uint4 *)(meta + voff + k * (uint32_t)sizeof(VbRec));
+            const uint32_t v0 = uni_(v.x);
+            p.k = k; p.valid = true; p.kc = 0;
+            p.r = v0 & 0xffu; p.lane0 = (v0 >> 8) & 0xffu; p.c = v0 >> 16;
+            p.val_off = uni_(v.y);
+            p.desc = ioff + (uni_(v.z) - idx0);
+            p.list = ioff + (uni_(v.w) - idx0);
+            // the map: cleared, then every kernel row of the block enters itself at its tile row (the
+            // wavefront's LDS operations execute in order)
+            const uint32_t slot = meta[p.desc + 4u * (p.lane0 + (lane < p.r ? lane : 0u))];
+            if (lane < 16u) ((uint32_t *)inv)[lane] = 0xffffffffu;
+            if (lane < p.r) inv[slot] = (uint8_t)lane;
+            parts = 0;
+            const uint32_t base4 = (p.val_off + p.lane0) * 4u;
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                const uint32_t ir = inv[16u * h + mrow];
+                irow4[h] = ir != 0xffu ? base4 + ir * 4u : 0x80000000u;
+                parts |= __ballot(ir != 0xffu) != 0ull ? 1u << h : 0u;
+            }
+        };
+        // The pass after p.  Without a branch: the block is opened again even when the pass stays in it
+        // (same record, same map), so that no path through here differs in the memory operations it
+        // issues and the compiler's counted waits stay exact.  Past the wavefront's last pass the
+        // fields stay (their loads are issued once more and dropped) and only `valid` goes off.
+        auto advance = [&](const RegPass &p) -> RegPass {
+            const bool same = p.kc + 16u < p.c, more = p.k + NW < nvbs;
+            const uint32_t kc2 = same ? p.kc + 16u : (more ? 0u : p.kc);
+            RegPass q;
+            open_vb(same || !more ? p.k : p.k + NW, q);
+            q.kc = kc2;
+            q.valid = same || more;
+            return q;
+        };
+        // 4 NH + 4 loads, always.  (Uses irow4 / parts of the block opened last: p's.)
+        auto issue = [&](const RegPass &p, RegOps<NH> &o) {
+            uint32_t cb[4], ja[4];
+            o.parts = parts;
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                const uint32_t jj = p.kc + 4u * s4 + kq;
+                ja[s4] = jj < p.c ? jj : 0x7fffffu;                             // a column the block lacks: past the stream
+                cb[s4] = *(const uint16_t *)(meta + p.list + 2u * min(jj, p.c - 1u));      // 4 * column
+            }
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+#pragma unroll
+                for (int h = 0; h < NH; ++h)
+                    o.av[h][s4] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(vrsrc, (int)(ja[s4] * 256u + irow4[h]), 0, 0));
+                if constexpr (TWO) {
+                    const bool first = cb[s4] < split4;
+                    const uint8_t *src = first ? x0 + __umul24(cb[s4], X.sj0) : x1 + __umul24(cb[s4] - split4, X.sj1);
+                    o.bv[s4] = *(const float4 *)src;
+                } else {
+                    o.bv[s4] = *(const float4 *)((const uint8_t *)X.p0 + (size_t)(__umul24(cb[s4], X.sj0) + nbyte));
+                }
+            }
+        };
+        auto multiply = [&](const RegPass &p, const RegOps<NH> &o) {
+            const uint32_t nk = min(4u, (p.c - p.kc + 3u) >> 2);      // k-steps the block has in this pass (uniform)
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                if (!((o.parts >> h) & 1u)) continue;              // (uniform) no row of the block in this part
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) {
+                    if ((uint32_t)s4 >= nk) break;
+                    const float a = o.av[h][s4];
+                    D[h][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, o.bv[s4].x, D[h][0], 0, 0, 0);
+                    D[h][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, o.bv[s4].y, D[h][1], 0, 0, 0);
+                    D[h][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, o.bv[s4].z, D[h][2], 0, 0, 0);
+                    D[h][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, o.bv[s4].w, D[h][3], 0, 0, 0);
+                }
+            }
+        };
+        RegOps<NH> oa, ob;
+        RegPass pa, pb;
+        open_vb(wave, pa);
+        issue(pa, oa);
+        while (true) {
+            pb = advance(pa);
+            issue(pb, ob);
+            multiply(pa, oa);
+            if (!pb.valid) break;
+            pa = advance(pb);
+            issue(pa, oa);
+            multiply(pb, ob);
+            if (!pa.valid) break;
+        }
+    }
+    // the wavefront's tile: lane holds rows 16 h + 4 kq + i, right-hand sides 4 mrow + t (tile t)
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *(float4 *)(myacc + (16u * h + 4u * kq + i) * NB + 4u * mrow) = make_float4(D[h][0][i], D[h][1][i], D[h][2][i], D[h][3][i]);
+    __syncthreads();
+    for (uint32_t e = tid; e < br * NB; e += NTHR) {
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += acc[(size_t)w * br * NB + e];
+        const uint32_t row = tile * br + e / NB, n = bt0 + e % NB;
+        if (row < m.rows_out && n < batch) Y[(size_t)row * ldy + n] = s;
+    }
+}
+
+template <bool TWO, int NW, int NH>
+__global__ __launch_bounds__(NW * 64) void spmm_reg_kernel(const DevMat m, const XSrc X, float *__restrict__ Y,
+                                                           const int64_t ldy, const uint32_t batch) {
+    spmm_reg_body<TWO, NW, NH>(m, X, Y, ldy, batch, blockIdx.x, blockIdx.y);
+}
+
 // Several independent products in one launch (blockIdx.z picks the product): the per-step
 // products of different layers of a batched recurrent model, each too small to fill the GPU.
 struct SpmmJobs {
@@ -482,10 +685,20 @@ __global__ __launch_bounds__(NW * 64) void spmm_multi_kernel(const SpmmJobs J, c
     spmm_body<NT, TWO, NW, WIDE>(J.m[j], J.X[j], J.Y[j], J.ldy[j], batch, blockIdx.x, blockIdx.y);
 }
 
+template <bool TWO, int NW, int NH>
+__global__ __launch_bounds__(NW * 64) void spmm_reg_multi_kernel(const SpmmJobs J, const uint32_t batch) {
+    const uint32_t j = blockIdx.z;
+    if (blockIdx.x >= J.m[j].n_nz_tiles + J.m[j].n_zero_tiles) return;      // the grid is as wide as the widest product
+    spmm_reg_body<TWO, NW, NH>(J.m[j], J.X[j], J.Y[j], J.ldy[j], batch, blockIdx.x, blockIdx.y);
+}
+
 // Launch shape of one product: batch columns per workgroup (16 nt), wavefronts per workgroup.
 struct SpmmShape {
     int nt, nw;
     bool two, wide;
+    int reg_parts;          // wide form, float32 kernel values, row tiles of 16 or 32 rows: the kernel that keeps the
+                            // results in registers, with this many 16-row parts (else 0; four parts do not fit the
+                            // registers of a 16-wavefront workgroup)
     size_t lds;
     unsigned tiles, batch_tiles;
 };
@@ -523,7 +736,10 @@ static int spmm_shape(const SpmmCall &c, int32_t batch, size_t launch_wgs_factor
     const size_t acc_per_wave = (size_t)h.br * 16 * nt * sizeof(float);
     const bool fits16 = (size_t)h.seg_meta + 16 * acc_per_wave <= (size_t)kLdsBudget;
     const int nw = fits16 && (wide || wgs(nt) * launch_wgs_factor < 2 * 256) ? 16 : 8;
-    *out = SpmmShape{nt, nw, two, wide, (size_t)h.seg_meta + (size_t)nw * acc_per_wave, (unsigned)tiles,
+    // (its 32-bit byte offsets into the value stream must stay below the out-of-range marker)
+    const int reg_parts = (wide && h.val_fmt == CSB_VAL_F32 && (h.br == 16 || h.br == 32) && h.n_vals * 4 < 0x7fffff00ull &&
+                           (size_t)h.seg_meta + (size_t)nw * acc_per_wave + (size_t)nw * 64 <= (size_t)160 * 1024) ? (int)h.br / 16 : 0;
+    *out = SpmmShape{nt, nw, two, wide, reg_parts, (size_t)h.seg_meta + (size_t)nw * acc_per_wave + (reg_parts ? (size_t)nw * 64 : 0), (unsigned)tiles,
                      (unsigned)((batch + 16 * nt - 1) / (16 * nt))};
     return CSB_OK;
 }
@@ -533,6 +749,16 @@ template <bool MULTI>
 static const void *spmm_kernel_for(const SpmmShape &sh) {
 #define CSB_SPMM_K(NT, TWO, NW, WIDE) \
     (MULTI ? (const void *)spmm_multi_kernel<NT, TWO, NW, WIDE> : (const void *)spmm_kernel<NT, TWO, NW, WIDE>)
+    if (sh.reg_parts) {
+#define CSB_SPMM_R(TWO, NW, NH) (MULTI ? (const void *)spmm_reg_multi_kernel<TWO, NW, NH> : (const void *)spmm_reg_kernel<TWO, NW, NH>)
+#define CSB_SPMM_RN(NH) \
+        if (sh.nw == 16) return sh.two ? CSB_SPMM_R(true, 16, NH) : CSB_SPMM_R(false, 16, NH); \
+        return sh.two ? CSB_SPMM_R(true, 8, NH) : CSB_SPMM_R(false, 8, NH);
+        if (sh.reg_parts == 1) { CSB_SPMM_RN(1) }
+        CSB_SPMM_RN(2)
+#undef CSB_SPMM_RN
+#undef CSB_SPMM_R
+    }
     if (sh.wide) {
         if (sh.nw == 16) return sh.two ? CSB_SPMM_K(4, true, 16, true) : CSB_SPMM_K(4, false, 16, true);
         return sh.two ? CSB_SPMM_K(4, true, 8, true) : CSB_SPMM_K(4, false, 8, true);
@@ -578,7 +804,7 @@ int spmm_strided_multi(const SpmmCall *calls, int n, int32_t batch, void *stream
         for (int i = 0; i < n; ++i) {
             int rc = spmm_shape(calls[i], batch, (size_t)n, &sh[i], &J.X[i]);
             if (rc != CSB_OK) return rc;
-            same = same && sh[i].nt == sh[0].nt && sh[i].nw == sh[0].nw && sh[i].two == sh[0].two && sh[i].wide == sh[0].wide;
+            same = same && sh[i].nt == sh[0].nt && sh[i].nw == sh[0].nw && sh[i].two == sh[0].two && sh[i].wide == sh[0].wide && sh[i].reg_parts == sh[0].reg_parts;
             lds = std::max(lds, sh[i].lds);
             tiles = std::max(tiles, sh[i].tiles);
             J.m[i] = dev_mat(calls[i].mat);

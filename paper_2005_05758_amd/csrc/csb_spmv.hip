@@ -43,7 +43,7 @@ DevMat dev_mat(const csb_matrix *m) {
     d.idx_bytes = (uint32_t)h.idx_bytes;
     d.val_fmt = h.val_fmt;
     d.seg_meta = h.seg_meta;
-    d.pad_ = 0;
+    d.vals_bytes = (uint32_t)std::min<uint64_t>(h.n_vals * (h.val_fmt == CSB_VAL_F32 ? 4u : 2u), 0x7fffff00u);
     d.tile_g0 = (const uint32_t *)(b + h.off_tile_g0);
     d.tile_seg0 = (const uint32_t *)(b + h.off_tile_seg0);
     d.segs = (const SegRec *)(b + h.off_segs);
