@@ -256,27 +256,6 @@ size_t csb_spmv_static_limit(void);
 int csb_spmv_static(const csb_matrix *m, const float *d_x, float *d_y, void *stream);
 
 /*
- * Instrumented csb_spmv for load-balance evidence (the role cycle-level simulation plays in
- * Sec. 6.1): same result, and every workgroup also writes shader-clock stamps to d_stamps
- * (device, csb_debug_stamp_count(m) values of 64 bits).  Per workgroup: 8 phase stamps
- * (start, loads issued, staged in LDS, mat-vec done, tile sums written, end, 2 unused), then
- * three stamps for each of its 16 wavefronts: begin of its mat-vec share, its kernel values
- * arrived, end of the share.
- */
-size_t csb_debug_stamp_count(const csb_matrix *m);
-
-/*
- * Measurement aid (Sec. 6.1 reports throughput against the platform's capability): a plain
- * streaming read of d_buf (device, 16-byte aligned, `bytes` a multiple of 16) whose timing
- * gives the HBM read bandwidth this GPU reaches in practice.  Every thread writes its partial
- * sum to d_out (device, csb_debug_stream_read_out_floats() floats).  Asynchronous on `stream`.
- */
-size_t csb_debug_stream_read_out_floats(void);
-int csb_debug_stream_read(const void *d_buf, size_t bytes, float *d_out, void *stream);
-int csb_debug_spmv_stamps(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws,
-                          unsigned long long *d_stamps, void *stream);
-
-/*
  * Batched CSB-MVM: Y = A X for `batch` right-hand sides.  d_X is [cols][ldx] (entry
  * (j,k) at d_X[j*ldx + k], ldx >= batch), d_Y is [rows][ldy] (ldy >= batch).
  * d_ws: csb_workspace_bytes(m, batch) (may be NULL when that is 0).  Runs on the matrix
@@ -418,8 +397,9 @@ int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
  * The resident kernel's workgroups wait for each other's h_t: they must all be on the GPU at
  * once, so nothing else should occupy the device while it runs.  The workgroups are placed on
  * as few of the 8 XCDs as hold them (at most 28 per XCD, one per CU).
- * Tuning knobs, read from the environment ONCE, by csb_rnn_create* (for experiments; the
- * defaults are the measured best): CSB_RNN_S = slots per lane of the resident layout (multiple
+ * Development knobs (NOT part of the interface: they exist for the experiments behind the
+ * defaults, which are the measured best, and may go away), read from the environment ONCE, by
+ * csb_rnn_create*: CSB_RNN_S = slots per lane of the resident layout (multiple
  * of 4), CSB_RNN_XCDS = use at least this many XCDs, CSB_RNN_POLL_DELAY = sleeps before the
  * first poll of a step, CSB_RNN_BATCH_PATH = "resident" or "batched": the path of a batch when
  * both are uploaded.

@@ -108,7 +108,12 @@ struct csb_rnn {
     int32_t knob_poll_delay = -1;            // CSB_RNN_POLL_DELAY: sleeps before the first poll of a step (-1: default)
     int32_t knob_batch_path = 0;             // CSB_RNN_BATCH_PATH: 1 resident, 2 batched, 0 by estimate
     uint32_t poll_limit = 1u << 24;          // polls of one exchange word before the resident kernel gives up
+    double clock_mhz = 2400.0;               // shader clock of the device the handle was created on (the path estimate uses it)
     csb_rnn() {
+        int dev = 0, khz = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) == hipSuccess && khz > 0)
+            clock_mhz = khz / 1000.0;
+        (void)hipGetLastError();             // (no device: the default stands)
         if (const char *e = getenv("CSB_RNN_XCDS")) knob_xcds = std::min(8, std::max(1, atoi(e)));
         if (const char *e = getenv("CSB_RNN_POLL_DELAY")) knob_poll_delay = std::max(0, atoi(e));
         if (const char *e = getenv("CSB_RNN_BATCH_PATH")) knob_batch_path = !strcmp(e, "resident") ? 1 : !strcmp(e, "batched") ? 2 : 0;
@@ -1141,7 +1146,7 @@ static double resident_batch_us(const csb_rnn *r, int32_t batch) {
     const double rounds = (double)((batch + R - 1) / R);
     const int S = r->plan.smax;
     const double clocks = (60.0 * S + (r->plan.n_wgs > 1 ? 1700.0 : 0.0) + 6.0 * r->plan.n_wgs) * (S > 32 ? 1.5 : 1.0);
-    return rounds * (clocks / 2400.0 * 1.3 + 0.12 * (resident_xcds(r) - 1)) * (two ? 2.0 : 1.0);
+    return rounds * (clocks / r->clock_mhz * 1.3 + 0.12 * (resident_xcds(r) - 1)) * (two ? 2.0 : 1.0);
 }
 static double batched_us(const csb_rnn *r, int32_t batch) {
     const bool two = r->cell == CSB_CELL_LSTMP || r->cell == CSB_CELL_GRU_RB;

@@ -15,6 +15,7 @@
 #include <mutex>
 #include <type_traits>
 
+#include "csbrnn_debug.h"
 #include "csb_internal.hpp"
 #include "csb_kernels.hpp"
 
