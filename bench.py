@@ -14,10 +14,15 @@ Also reported on the same JSON line:
   rnn_configs   -- the other batch-1 workloads per timestep; csb_spmv on every RNN matrix, warm / cold
   spmv_stress   -- csb_spmv on the 8192 x 8192 heavy-tailed matrix (the HBM-bound case),
                    warm (matrix resident in the Infinity Cache) and cold (rotating over
-                   distinct device copies of the matrix, > 512 MB in total)
+                   distinct device copies of the matrix, > 512 MB in total), launches queued
+                   behind a long kernel so that the host's call overhead does not show
+  spmv_tall     -- the same on a matrix four times as tall (the streaming rate away from the
+                   launch floor), next to a plain read of the same number of bytes
   batched       -- csb_spmm on the matrix cores (8192^2 x 128, cfg4 x 64) and the cfg4 model at batch 64
   projection, lstmp_sr1, cells, weights_16bit -- the rows built after the hot path
   cpu_baseline  -- the CPU oracle timed on this machine's host cores on the same workload
+--only <leg> runs one leg alone and prints that leg's JSON (for rocprofv3 runs whose summaries
+are kept under profiles/).
 """
 from __future__ import annotations
 

@@ -156,3 +156,28 @@ def test_spmv_full_size_stress(name, mode):
     assert np.all(np.abs(got - ref) <= 2.0 * k * 2.0 ** -24 * scale + 1e-30)
     for _ in range(3):
         assert torch.equal(M.spmv(xd), y)
+
+
+@pytest.mark.parametrize("R,C,br,bc,rate", [
+    (4, 8, 4, 4, 2.0), (37, 53, 8, 8, 3.0), (200, 150, 16, 16, 6.0), (130, 257, 32, 32, 5.0),
+    (70, 300, 16, 64, 4.0), (300, 40, 128, 8, 3.0), (513, 100, 256, 256, 2.0), (1030, 96, 32, 32, 3.0)])
+def test_spmv_row_owned_plans(R, C, br, bc, rate):
+    """csb_plan_rows with workgroup and round counts of the caller's choosing (several rounds make
+    a wavefront request its next segment while it multiplies the current one): same bar as the
+    default plan, and the same bits whatever the partition of the rows' slots over rounds."""
+    m = csb_inputs.small_matrix(R * 3 + C, R, C, br, bc, rate=rate)
+    x = csb_inputs.make_vectors(R + C, C, 1)
+    ref = oracle.matvec(oracle.csb_decode(oracle.csb_encode(m.A, br, bc)), x)
+    xd = torch.from_numpy(x).cuda()
+    for n_wg in (0, 1, 3):
+        for rounds in (0, 2, 5):
+            say(f"[spmv] row-owned shape={m.A.shape} n_wg={n_wg} rounds>={rounds}")
+            M = CsbMatrix(m.A, br, bc)
+            st = M.plan_rows(n_wg, rounds)
+            assert st["row_owned"] == 1
+            M.validate()
+            M.upload()
+            y = M.spmv(xd)
+            torch.cuda.synchronize()
+            assert rel_max_err(y.cpu().numpy().astype(np.float64), ref) <= 1e-5
+            assert torch.equal(M.spmv(xd), y) and torch.equal(M.spmv_static(xd), y)

@@ -366,3 +366,28 @@ def test_small_matrix_plans_trade_balance_for_short_wavefronts():
     assert st2["work_max"] / st2["work_mean"] <= 1.10
     assert st2["work_max"] >= st["work_max"]
     M.validate(); M2.validate()
+
+
+def test_plan_rows_sweep():
+    """csb_plan_rows on small shapes: every workgroup count and round count asked for gives a
+    section the validator decodes back to the matrix, in all three value formats; the statistics
+    describe that section; a workgroup never owns more than 256 rows."""
+    shapes = [(4, 8, 4, 4, 2.0), (1, 1, 1, 1, 1.0), (37, 53, 8, 8, 3.0), (200, 150, 16, 16, 6.0), (130, 257, 32, 32, 5.0),
+              (70, 300, 16, 64, 4.0), (300, 40, 128, 8, 3.0), (513, 100, 256, 256, 2.0), (64, 64, 64, 64, 1.0), (1030, 96, 32, 32, 3.0)]
+    for (R, C, br, bc, rate) in shapes:
+        A = csb_inputs.small_matrix(R * 3 + C, R, C, br, bc, rate=rate).A
+        for fmt in (binding.VAL_F32, binding.VAL_F16, binding.VAL_BF16):
+            for n_wg in (0, 1, 3):
+                for rounds in (0, 2, 5):
+                    M = CsbMatrix(A, br, bc)
+                    if fmt != binding.VAL_F32:
+                        M.set_value_format(fmt)
+                    st = M.plan_rows(n_wg, rounds)
+                    assert st["row_owned"] == 1 and st["rounds"] >= max(1, rounds)
+                    assert st["n_chunks"] >= max(1, -(-R // 256)) and st["n_chunks"] >= min(max(n_wg, 1), R) or n_wg == 0
+                    assert st["work_max"] >= st["work_mean"] > 0 or int(M.view()["nnz"]) == 0
+                    assert st["matvec_bytes"] > 0 and st == M.plan_stats()
+                    M.validate()
+    Z = CsbMatrix(np.zeros((40, 48), np.float32), 16, 16)
+    assert Z.plan_rows(0, 0)["row_owned"] == 1
+    Z.validate()
