@@ -109,8 +109,21 @@ __device__ __forceinline__ float lds_val(uint32_t a) {
     else return (float)__builtin_bit_cast(_Float16, (uint16_t)lds_u16(a));
 }
 
-template <int W, bool GATED, int VF>
+// FORM: which of the run-time cases the kernel is compiled for.  These kernels run for a few
+// microseconds, every launch with a cold instruction cache, and their run time follows their
+// code size (measured: about 0.4 us per KiB of code on the path), so the common cases get
+// kernels of their own without the code of the others.
+enum : int {
+    kRowsOneRound = 0,     // one round, the vector 16-byte aligned, no clock stamps
+    kRowsRounds = 1,       // several rounds, the vector aligned, no stamps
+    kRowsAny = 2,          // everything decided at run time
+};
+
+template <int W, bool GATED, int VF, int FORM>
 __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) {
+    const bool stamps = FORM == kRowsAny && A.stamps != nullptr;
+    const bool x_fast = FORM != kRowsAny || A.x_fast != 0u;
+    const uint32_t n_rounds = FORM == kRowsOneRound ? 1u : A.n_rounds;
     constexpr uint32_t VB = VF == CSB_VAL_F32 ? 4u : 2u, SS = 64u * VB;      // bytes of a value, of a column step
     extern __shared__ float4 smem4[];
     uint8_t *smem = (uint8_t *)smem4;
@@ -123,13 +136,13 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const uint32_t s0 = lds0 + A.off_seg + wave * A.seg_bytes;
     unsigned long long t_start = 0, t_x = 0, t_first = 0, t_done = 0, t_bar = 0;
-    if (A.stamps) t_start = wall_clock64();
+    if (stamps) t_start = wall_clock64();
 
     // ---- requests: the input vector and the header first, then the whole segment of round 0 --
     if constexpr (GATED) {
         // (the segment's first units are requested below, before the cell arithmetic, whose loads
         // come back behind them)
-    } else if (A.x_fast) {                                     // every wavefront's first requests: they arrive first
+    } else if (x_fast) {                                     // every wavefront's first requests: they arrive first
         const uint32_t x16 = A.cols >> 2;                      // 16-byte pieces of the vector
         for (uint32_t u = wave; u * 64u < x16; u += kStreamWaves) {
             if (u * 64u + lane < x16) dma16((const uint8_t *)A.x + (size_t)u * 1024u + lane * 16u, lds0 + u * 1024u);
@@ -160,12 +173,16 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
     if constexpr (GATED) {
         float *xl = (float *)smem;
         const uint32_t na = min(A.n0, A.cols);
-        stage_segment(xl, A.g0, na, tid, kStreamThreads, wg == 0u);
-        stage_segment(xl + na, A.g1, A.cols - na, tid, kStreamThreads, wg == 0u);
-    } else if (A.x_fast) { if (NU >= (uint32_t)W) wait_outstanding<W>(); else wait_outstanding<0>(); }   // the wavefront's part of the vector has landed
+        // (one copy of the cell arithmetic in the code, passed twice: see FORM)
+#pragma clang loop unroll(disable)
+        for (uint32_t k = 0; k < 2u; ++k) {
+            const GateSrc &gs = k ? A.g1 : A.g0;
+            stage_segment(xl + (k ? na : 0u), gs, k ? A.cols - na : na, tid, kStreamThreads, wg == 0u);
+        }
+    } else if (x_fast) { if (NU >= (uint32_t)W) wait_outstanding<W>(); else wait_outstanding<0>(); }   // the wavefront's part of the vector has landed
     // (a plain barrier: the fence builtins would also wait for the segment, which is still on its way)
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if (A.stamps) t_x = wall_clock64();
+    if (stamps) t_x = wall_clock64();
     if (wave == 0u)                                            // the header: needed for the row sums only
         for (uint32_t u = 0; u * 64u < hdr16; ++u)
             if (u * 64u + lane < hdr16) dma16_stream(wb + (size_t)u * 1024u + lane * 16u, lds0 + A.off_hdr + u * 1024u);
@@ -174,8 +191,8 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
     uint32_t have = 0;                                         // units of round 0 known to have landed
 
     // ---- the wavefront's rounds: no barrier between them ------------------------------------
-    for (uint32_t r = 0; r < A.n_rounds; ++r) {
-        const bool more = r + 1u < A.n_rounds;
+    for (uint32_t r = 0; r < n_rounds; ++r) {
+        const bool more = r + 1u < n_rounds;
         if (r == 0u) {                                         // the records sit in the first unit(s)
             wait_unit(0u);
             have = 1u;
@@ -184,7 +201,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
             wait_outstanding<0>();                             // requested while the previous round was multiplied
             have = NU;
         }
-        if (A.stamps && r == 0u) t_first = wall_clock64();
+        if (stamps && r == 0u) t_first = wall_clock64();
         const uint32_t h0 = uni_(lds_u32(s0));
         const uint32_t ng = h0 & 0xffffu, off_vbs = h0 >> 16;
         // the segment's own length: what lies behind it (up to the stride) is never requested
@@ -273,10 +290,10 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
             for (uint32_t u = 0; u < meta_units && u < NUn; ++u) request_unit(r + 1u, u, next16);
         }
     }
-    if (A.stamps) t_done = wall_clock64();
+    if (stamps) t_done = wall_clock64();
     wait_outstanding<0>();                                     // (wavefront 0: the header)
     lds_barrier();
-    if (A.stamps) t_bar = wall_clock64();
+    if (stamps) t_bar = wall_clock64();
 
     // ---- row sums: the threads of a row add its slots in a fixed order -----------------------
     {
@@ -300,28 +317,28 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
         if (tpr >= 64u) s += __shfl_down(s, 32);
         if (sub == 0u && rr < nrows) A.y[row0 + rr] = s;
     }
-    if (A.stamps && lane == 0u) {
+    if (stamps && lane == 0u) {
         unsigned long long *st = A.stamps + ((size_t)wg * kStreamWaves + wave) * 8;
         st[0] = t_start; st[1] = t_x; st[2] = t_first; st[3] = t_first; st[4] = t_done; st[5] = t_bar; st[6] = wall_clock64();
     }
 }
 
-template <int W, int VF>
+template <int W, int VF, int FORM>
 __global__ __launch_bounds__(kStreamThreads) void spmv_rows_kernel(const RowsArgs A) {
-    rows_body<W, false, VF>(A, blockIdx.x);
+    rows_body<W, false, VF, FORM>(A, blockIdx.x);
 }
 
-template <int W, int VF>
+template <int W, int VF, int FORM>
 __global__ __launch_bounds__(kStreamThreads) void spmv_rows_gated_kernel(const RowsArgs A) {
-    rows_body<W, true, VF>(A, blockIdx.x);
+    rows_body<W, true, VF, FORM>(A, blockIdx.x);
 }
 
 // blockIdx.y selects the product; the grid is as wide as the largest of them.
-template <int W, int VF>
+template <int W, int VF, int FORM>
 __global__ __launch_bounds__(kStreamThreads) void spmv_rows_gated_multi_kernel(const RowsJobs J) {
     const RowsArgs &A = J.a[blockIdx.y];
     if (blockIdx.x >= A.n_wg) return;
-    rows_body<W, true, VF>(A, blockIdx.x);
+    rows_body<W, true, VF, FORM>(A, blockIdx.x);
 }
 
 // Kernel arguments of one product and the dynamic LDS it needs (0 with the error set if it does not fit).
@@ -358,18 +375,24 @@ int launch_rows(Kern kern, dim3 grid, size_t lds, void *stream, const Arg &arg) 
 
 }  // namespace
 
+// Launch of KERN<2, format, form>: two units ahead -- measured best on the 8192 x 8192 stress matrix
+// (cold, us: 8.1 with two, 8.6 with three, 9.0 with four, 10.0 with six units ahead after the first):
+// what a wavefront asks for far ahead delays what its neighbours need next.
+#define CSB_ROWS_LAUNCH(KERN, vf, form, grid, lds, stream, arg)                                                  \
+    ((vf) == CSB_VAL_F16    ? launch_rows(KERN<2, CSB_VAL_F16, form>, grid, lds, stream, arg)                    \
+     : (vf) == CSB_VAL_BF16 ? launch_rows(KERN<2, CSB_VAL_BF16, form>, grid, lds, stream, arg)                   \
+                            : launch_rows(KERN<2, CSB_VAL_F32, form>, grid, lds, stream, arg))
+
 int spmv_rows(const csb_matrix *m, const float *d_x, float *d_y, void *stream, unsigned long long *d_stamps) {
     RowsArgs A;
     const size_t lds = rows_args(m, &A);
     if (!lds) return CSB_EUNSUPPORTED;
     A.x = d_x; A.y = d_y; A.stamps = d_stamps;
     A.x_fast = ((uintptr_t)d_x % 16 == 0 && m->cols % 4 == 0) ? 1u : 0u;
-    // two units ahead: measured best on the 8192 x 8192 stress matrix (cold, us: 8.1 with two, 8.6 with three, 9.0 with
-    // four, 10.0 with six units ahead after the first): what a wavefront asks for far ahead delays what its neighbours need next
     const uint32_t vf = m->plan.stream.val_fmt;
-    if (vf == CSB_VAL_F16) return launch_rows(spmv_rows_kernel<2, CSB_VAL_F16>, dim3(A.n_wg), lds, stream, A);
-    if (vf == CSB_VAL_BF16) return launch_rows(spmv_rows_kernel<2, CSB_VAL_BF16>, dim3(A.n_wg), lds, stream, A);
-    return launch_rows(spmv_rows_kernel<2, CSB_VAL_F32>, dim3(A.n_wg), lds, stream, A);
+    if (d_stamps || !A.x_fast) return CSB_ROWS_LAUNCH(spmv_rows_kernel, vf, kRowsAny, dim3(A.n_wg), lds, stream, A);
+    if (A.n_rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_kernel, vf, kRowsOneRound, dim3(A.n_wg), lds, stream, A);
+    return CSB_ROWS_LAUNCH(spmv_rows_kernel, vf, kRowsRounds, dim3(A.n_wg), lds, stream, A);
 }
 
 int spmv_rows_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *stream) {
@@ -378,26 +401,28 @@ int spmv_rows_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const G
     if (!lds) return CSB_EUNSUPPORTED;
     A.y = d_y; A.g0 = s0; A.g1 = s1; A.n0 = n0;
     const uint32_t vf = m->plan.stream.val_fmt;
-    if (vf == CSB_VAL_F16) return launch_rows(spmv_rows_gated_kernel<2, CSB_VAL_F16>, dim3(A.n_wg), lds, stream, A);
-    if (vf == CSB_VAL_BF16) return launch_rows(spmv_rows_gated_kernel<2, CSB_VAL_BF16>, dim3(A.n_wg), lds, stream, A);
-    return launch_rows(spmv_rows_gated_kernel<2, CSB_VAL_F32>, dim3(A.n_wg), lds, stream, A);
+    if (A.n_rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_gated_kernel, vf, kRowsOneRound, dim3(A.n_wg), lds, stream, A);
+    return CSB_ROWS_LAUNCH(spmv_rows_gated_kernel, vf, kRowsRounds, dim3(A.n_wg), lds, stream, A);
 }
 
 int spmv_rows_gated_multi(const SpmvGatedCall *calls, int n, void *stream) {
     RowsJobs J{};
     size_t lds = 0;
-    uint32_t wgs = 0;
+    uint32_t wgs = 0, rounds = 1;
     for (int i = 0; i < n; ++i) {
         const size_t l = rows_args(calls[i].mat, &J.a[i]);
         if (!l) return CSB_EUNSUPPORTED;
         J.a[i].y = calls[i].y; J.a[i].g0 = calls[i].s0; J.a[i].g1 = calls[i].s1; J.a[i].n0 = calls[i].n0;
         lds = std::max(lds, l);
         wgs = std::max(wgs, J.a[i].n_wg);
+        rounds = std::max(rounds, J.a[i].n_rounds);
     }
     const uint32_t vf = calls[0].mat->plan.stream.val_fmt;             // (the caller has checked: one format for all)
-    if (vf == CSB_VAL_F16) return launch_rows(spmv_rows_gated_multi_kernel<2, CSB_VAL_F16>, dim3(wgs, (unsigned)n), lds, stream, J);
-    if (vf == CSB_VAL_BF16) return launch_rows(spmv_rows_gated_multi_kernel<2, CSB_VAL_BF16>, dim3(wgs, (unsigned)n), lds, stream, J);
-    return launch_rows(spmv_rows_gated_multi_kernel<2, CSB_VAL_F32>, dim3(wgs, (unsigned)n), lds, stream, J);
+    const dim3 grid(wgs, (unsigned)n);
+    if (rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_gated_multi_kernel, vf, kRowsOneRound, grid, lds, stream, J);
+    return CSB_ROWS_LAUNCH(spmv_rows_gated_multi_kernel, vf, kRowsRounds, grid, lds, stream, J);
 }
+
+#undef CSB_ROWS_LAUNCH
 
 }  // namespace csb
