@@ -35,7 +35,25 @@ __device__ __host__ inline GateSrc plain_src(const float *v) {
 }
 
 #ifdef __HIPCC__
-__device__ __forceinline__ float sigmoid_(float v) { return 1.0f / (1.0f + expf(-v)); }
+// Gate non-linearities of every path, built on the hardware exp2 and reciprocal
+// (each within 1 ulp): sigmoid(v) = 1 / (1 + 2^(-v log2 e)); tanh(v) = 2 sigmoid(2v) - 1 for
+// |v| >= 0.1 and its odd Taylor polynomial up to v^5 below (truncation 17 v^7 / 315 < 6e-9
+// there), which keeps the relative error near zero small.  Absolute error below 5e-7 for any v
+// (the argument scaling adds |v| 2^-24 relative error to the exponential, which only matters
+// while the exponential is not negligible against 1).  A few instructions each: the kernels
+// that stage a cell's output on their way in run for microseconds and pay for their code size.
+__device__ __forceinline__ float fast_sigmoid(float v) {
+    const float e = __builtin_amdgcn_exp2f(-1.44269504088896341f * v);
+    return __builtin_amdgcn_rcpf(1.0f + e);
+}
+__device__ __forceinline__ float tanh_small(float v) {
+    const float v2 = v * v;
+    return v * fmaf(v2, fmaf(v2, 2.0f / 15.0f, -1.0f / 3.0f), 1.0f);
+}
+__device__ __forceinline__ float fast_tanh(float v) {
+    const float big = fmaf(2.0f, fast_sigmoid(2.0f * v), -1.0f);
+    return fabsf(v) < 0.1f ? tanh_small(v) : big;
+}
 
 // h_t of unit u of the cell whose gate sums are s.a (Sec. 2.1; LSTM rows i,f,g,o; GRU rows r,z,
 // input side of n, recurrent side of n; Li-GRU rows z, candidate), the same arithmetic as the
@@ -47,27 +65,27 @@ __device__ __forceinline__ float gate_value(const GateSrc &s, uint32_t u, bool s
     if (s.kind == 1u + CSB_CELL_LSTM) {
         float ai = a[u], af = a[H + u], ag = a[2 * H + u], ao = a[3 * H + u];
         if (b) { ai += b[u]; af += b[H + u]; ag += b[2 * H + u]; ao += b[3 * H + u]; }
-        cn = sigmoid_(af) * s.c_in[u] + sigmoid_(ai) * tanhf(ag);
-        hn = sigmoid_(ao) * tanhf(cn);
+        cn = fast_sigmoid(af) * s.c_in[u] + fast_sigmoid(ai) * fast_tanh(ag);
+        hn = fast_sigmoid(ao) * fast_tanh(cn);
     } else if (s.kind == 1u + CSB_CELL_GRU) {
         float ar = a[u], az = a[H + u], anx = a[2 * H + u];
         const float anh = a[3 * H + u];
         if (b) { ar += b[u]; az += b[H + u]; anx += b[2 * H + u]; }
-        const float r = sigmoid_(ar), z = sigmoid_(az);
-        hn = (1.0f - z) * tanhf(anx + r * anh) + z * s.h_in[u];
+        const float r = fast_sigmoid(ar), z = fast_sigmoid(az);
+        hn = (1.0f - z) * fast_tanh(anx + r * anh) + z * s.h_in[u];
     } else if (s.kind == kGateRbReset) {                       // rows r,z,n; only r is needed here
         float ar = a[u];
         if (b) ar += b[u];
-        hn = sigmoid_(ar) * s.h_in[u];
+        hn = fast_sigmoid(ar) * s.h_in[u];
     } else if (s.kind == kGateRbGate) {
         float az = a[H + u], an = a[2 * H + u] + s.a2[u];
         if (b) { az += b[H + u]; an += b[2 * H + u]; }
-        const float z = sigmoid_(az);
-        hn = (1.0f - z) * tanhf(an) + z * s.h_in[u];
+        const float z = fast_sigmoid(az);
+        hn = (1.0f - z) * fast_tanh(an) + z * s.h_in[u];
     } else {                                                   // Li-GRU
         float az = a[u], ac = a[H + u];
         if (b) { az += b[u]; ac += b[H + u]; }
-        const float z = sigmoid_(az);
+        const float z = fast_sigmoid(az);
         hn = z * s.h_in[u] + (1.0f - z) * fmaxf(ac, 0.0f);
     }
     if (store) {

@@ -517,27 +517,6 @@ static int build_resident_plan(csb_rnn *r, int slots = 0) {
 
 // ------------------------------------------------------------------ device side
 
-__device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
-
-// Gate non-linearities of the resident kernel, built on the hardware exp2 and reciprocal
-// (each within 1 ulp): sigmoid(v) = 1 / (1 + 2^(-v log2 e)); tanh(v) = 2 sigmoid(2v) - 1 for
-// |v| >= 0.1 and its odd Taylor polynomial up to v^5 below (truncation 17 v^7 / 315 < 6e-9
-// there), which keeps the relative error near zero small.  Absolute error below 5e-7 for any v
-// (the argument scaling adds |v| 2^-24 relative error to the exponential, which only matters
-// while the exponential is not negligible against 1).
-__device__ __forceinline__ float fast_sigmoid(float v) {
-    const float e = __builtin_amdgcn_exp2f(-1.44269504088896341f * v);
-    return __builtin_amdgcn_rcpf(1.0f + e);
-}
-__device__ __forceinline__ float tanh_small(float v) {
-    const float v2 = v * v;
-    return v * fmaf(v2, fmaf(v2, 2.0f / 15.0f, -1.0f / 3.0f), 1.0f);
-}
-__device__ __forceinline__ float fast_tanh(float v) {
-    const float big = fmaf(2.0f, fast_sigmoid(2.0f * v), -1.0f);
-    return fabsf(v) < 0.1f ? tanh_small(v) : big;
-}
-
 struct RnnArgs {
     const uint8_t *img;                 // resident image
     const float *x;                     // [T][I]
@@ -885,33 +864,33 @@ __global__ void gates_batched_kernel(const GateJobs J, const int cell, const int
     if (cell == kEwRbReset) {
         float ar = a[(size_t)k * B + n];
         if (bias) ar += bias[k];
-        J.m[j][e] = sigmoidf_(ar) * h[e];
+        J.m[j][e] = fast_sigmoid(ar) * h[e];
         return;
     }
     if (cell == kEwRbGate) {
         float az = a[(size_t)(H + k) * B + n], an = a[(size_t)(2 * H + k) * B + n] + J.a2[j][e];
         if (bias) { az += bias[H + k]; an += bias[2 * H + k]; }
-        const float z = sigmoidf_(az);
-        hn = (1.0f - z) * tanhf(an) + z * h[e];
+        const float z = fast_sigmoid(az);
+        hn = (1.0f - z) * fast_tanh(an) + z * h[e];
     } else if (cell == CSB_CELL_LSTM || cell == kEwLstmpCell) {   // rows i, f, g, o
         float *__restrict__ c = J.c[j];
         float ai = a[(size_t)k * B + n], af = a[(size_t)(H + k) * B + n], ag = a[(size_t)(2 * H + k) * B + n],
               ao = a[(size_t)(3 * H + k) * B + n];
         if (bias) { ai += bias[k]; af += bias[H + k]; ag += bias[2 * H + k]; ao += bias[3 * H + k]; }
-        const float cn = sigmoidf_(af) * c[e] + sigmoidf_(ai) * tanhf(ag);
-        hn = sigmoidf_(ao) * tanhf(cn);
+        const float cn = fast_sigmoid(af) * c[e] + fast_sigmoid(ai) * fast_tanh(ag);
+        hn = fast_sigmoid(ao) * fast_tanh(cn);
         c[e] = cn;
         if (cell == kEwLstmpCell) { J.m[j][e] = hn; return; }      // m_t; the state is the projection's result
     } else if (cell == CSB_CELL_GRU) {                 // rows r, z, input side of n, recurrent side of n
         float ar = a[(size_t)k * B + n], az = a[(size_t)(H + k) * B + n], anx = a[(size_t)(2 * H + k) * B + n];
         const float anh = a[(size_t)(3 * H + k) * B + n];
         if (bias) { ar += bias[k]; az += bias[H + k]; anx += bias[2 * H + k]; }
-        const float r = sigmoidf_(ar), z = sigmoidf_(az);
-        hn = (1.0f - z) * tanhf(anx + r * anh) + z * h[e];
+        const float r = fast_sigmoid(ar), z = fast_sigmoid(az);
+        hn = (1.0f - z) * fast_tanh(anx + r * anh) + z * h[e];
     } else {                                           // Li-GRU: rows z, candidate
         float az = a[(size_t)k * B + n], ac = a[(size_t)(H + k) * B + n];
         if (bias) { az += bias[k]; ac += bias[H + k]; }
-        const float z = sigmoidf_(az);
+        const float z = fast_sigmoid(az);
         hn = z * h[e] + (1.0f - z) * fmaxf(ac, 0.0f);
     }
     h[e] = hn;

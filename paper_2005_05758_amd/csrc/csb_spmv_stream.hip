@@ -71,6 +71,9 @@ __device__ __forceinline__ void lds_barrier() {
 __device__ __forceinline__ void dma16_stream(const uint8_t *g, uint32_t lds_base) {     // read-once data
     __builtin_amdgcn_global_load_lds((glb_void_t *)g, (lds_void_t *)(uintptr_t)lds_base, 16, 0, 2);
 }
+__device__ __forceinline__ void dma4(const uint8_t *g, uint32_t lds_base) {      // 4 bytes per lane: lane l's land at lds_base + 4 l
+    __builtin_amdgcn_global_load_lds((glb_void_t *)g, (lds_void_t *)(uintptr_t)lds_base, 4, 0, 0);
+}
 __device__ __forceinline__ void dma16(const uint8_t *g, uint32_t lds_base) {
     __builtin_amdgcn_global_load_lds((glb_void_t *)g, (lds_void_t *)(uintptr_t)lds_base, 16, 0, 0);
 }
@@ -114,15 +117,15 @@ __device__ __forceinline__ float lds_val(uint32_t a) {
 // code size (measured: about 0.4 us per KiB of code on the path), so the common cases get
 // kernels of their own without the code of the others.
 enum : int {
-    kRowsOneRound = 0,     // one round, the vector 16-byte aligned, no clock stamps
-    kRowsRounds = 1,       // several rounds, the vector aligned, no stamps
+    kRowsOneRound = 0,     // one round, no clock stamps
+    kRowsRounds = 1,       // several rounds, no stamps
     kRowsAny = 2,          // everything decided at run time
 };
 
 template <int W, bool GATED, int VF, int FORM>
 __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) {
     const bool stamps = FORM == kRowsAny && A.stamps != nullptr;
-    const bool x_fast = FORM != kRowsAny || A.x_fast != 0u;
+    const bool x_fast = A.x_fast != 0u;
     const uint32_t n_rounds = FORM == kRowsOneRound ? 1u : A.n_rounds;
     constexpr uint32_t VB = VF == CSB_VAL_F32 ? 4u : 2u, SS = 64u * VB;      // bytes of a value, of a column step
     extern __shared__ float4 smem4[];
@@ -147,10 +150,10 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
         for (uint32_t u = wave; u * 64u < x16; u += kStreamWaves) {
             if (u * 64u + lane < x16) dma16((const uint8_t *)A.x + (size_t)u * 1024u + lane * 16u, lds0 + u * 1024u);
         }
-    } else {                                                   // unaligned vector: through registers, before anything else
-        float *xl = (float *)smem;
-        for (uint32_t i = tid; i < A.cols; i += kStreamThreads) xl[i] = A.x[i];
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {                                                   // a vector that is not 16-byte aligned: 4 bytes per lane
+        for (uint32_t u = wave; u * 64u < A.cols; u += kStreamWaves) {
+            if (u * 64u + lane < A.cols) dma4((const uint8_t *)A.x + (size_t)u * 256u + lane * 4u, lds0 + u * 256u);
+        }
     }
     uint32_t req = 0;                                          // units of round 0 requested so far
     auto request_unit = [&](uint32_t round, uint32_t u, uint32_t len16) {     // len16: the segment's length in 16-byte pieces
@@ -179,7 +182,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
             const GateSrc &gs = k ? A.g1 : A.g0;
             stage_segment(xl + (k ? na : 0u), gs, k ? A.cols - na : na, tid, kStreamThreads, wg == 0u);
         }
-    } else if (x_fast) { if (NU >= (uint32_t)W) wait_outstanding<W>(); else wait_outstanding<0>(); }   // the wavefront's part of the vector has landed
+    } else { if (NU >= (uint32_t)W) wait_outstanding<W>(); else wait_outstanding<0>(); }   // the wavefront's part of the vector has landed
     // (a plain barrier: the fence builtins would also wait for the segment, which is still on its way)
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     if (stamps) t_x = wall_clock64();
@@ -390,7 +393,7 @@ int spmv_rows(const csb_matrix *m, const float *d_x, float *d_y, void *stream, u
     A.x = d_x; A.y = d_y; A.stamps = d_stamps;
     A.x_fast = ((uintptr_t)d_x % 16 == 0 && m->cols % 4 == 0) ? 1u : 0u;
     const uint32_t vf = m->plan.stream.val_fmt;
-    if (d_stamps || !A.x_fast) return CSB_ROWS_LAUNCH(spmv_rows_kernel, vf, kRowsAny, dim3(A.n_wg), lds, stream, A);
+    if (d_stamps) return CSB_ROWS_LAUNCH(spmv_rows_kernel, vf, kRowsAny, dim3(A.n_wg), lds, stream, A);
     if (A.n_rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_kernel, vf, kRowsOneRound, dim3(A.n_wg), lds, stream, A);
     return CSB_ROWS_LAUNCH(spmv_rows_kernel, vf, kRowsRounds, dim3(A.n_wg), lds, stream, A);
 }
