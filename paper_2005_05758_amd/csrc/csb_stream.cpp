@@ -21,9 +21,12 @@ namespace {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Default size of a workgroup's share: one 64-lane group per wavefront (small matrices spread over more
-// compute units; large ones are capped at 256 workgroups anyway).
-constexpr uint64_t kLanesPerWg = 1024;
+// Default size of a workgroup's share: four 64-lane groups, cut along their column steps into a
+// piece per wavefront.  Small matrices spread over more compute units and their wavefronts get
+// short runs (measured, us per launch warm, 1024 / 512 / 256 / 128 lanes per workgroup: 2048 x 665:
+// 3.67 / 3.43 / 3.16 / 3.16; streaming LSTM step on it 5.15 / 4.87 / 4.57 / 4.53; LSTMP step
+// 11.3 / 11.1 / 10.7 / 12.2); large matrices are capped at 256 workgroups anyway.
+constexpr uint64_t kLanesPerWg = 256;
 
 // One virtual block of a workgroup: kernel-matrix rows [a0, a1) of CSB block b.
 struct SVb {
