@@ -494,7 +494,8 @@ def stress_leg(torch, np, csb_inputs, CsbMatrix, stream_read, stream_gbps=None, 
             v = M.view()
             ab = spmv_alg_bytes(v)
             entry = {"nnz": int(v["nnz"]), "alg_bytes": ab,
-                     "kernel": "csb::spmv_rows_kernel<2, 0>" if st["row_owned"] else "csb::spmv_kernel<0, false>",
+                     "kernel": (f"csb::spmv_rows_kernel<2, 0, {1 if st['rounds'] > 1 else 0}>" if st["row_owned"]
+                                else "csb::spmv_kernel<0, false>"),
                      "image_bytes_per_launch": int(st["matvec_bytes"]),
                      "image_over_algorithmic": round(st["matvec_bytes"] / ab, 4),
                      "wave_max_over_mean": round(st["work_max"] / st["work_mean"], 4),

@@ -470,11 +470,12 @@ __global__ __launch_bounds__(NW * 64) void spmm_bf16_kernel(const DevMat m, cons
 // ---------------------------------------------------------------------------------------
 // The wide form for float32 kernel values and row tiles of 16 or 32 rows, with the results
 // kept in registers.  Counters of the general kernel above on the 8192 x 8192 matrix with 128
-// right-hand sides show what its launch time is made of: the LDS is busy 90 % of the launch
-// (every 16-row slice of every block adds its 16 x 64 results into the wavefront's accumulator
-// tile: four 16-byte reads and four writes per lane, 16 clocks each), the matrix pipe a
-// quarter, and pointing every gather at ONE row of X makes it only 7 % faster -- the gather is
-// not the bound.  Here the kernel operand of an MFMA is not the block's kernel matrix but its
+// right-hand sides show what its launch time is made of: vector instructions other than MFMA
+// keep every SIMD busy for 38 % of the launch (about 480 instructions per pass of at most 16
+// MFMAs, among them the accumulate of every 16-row slice's 16 x 64 results into the wavefront's
+// LDS tile: four 16-byte reads and four writes per lane), the matrix pipe a quarter, and
+// pointing every gather at ONE row of X makes it only 7 % faster -- the gather is not the
+// bound.  Here the kernel operand of an MFMA is not the block's kernel matrix but its
 // rows ALREADY SCATTERED to their places in the row tile: for each 16-row part of the tile, lane
 // (row, k) holds the block's value at that tile row, or zero if the block does not keep the
 // row.  The 16 x 64 results of a part then add up in the SAME registers over all blocks the
