@@ -77,6 +77,31 @@ def test_rnn_small(cell, L, I, H, T, B, block):
     run_case(wl, tag="small-zero-state")
 
 
+@pytest.mark.parametrize("L", [1, 2])
+@pytest.mark.parametrize("n_wg,rounds", [(0, 3), (2, 2), (5, 4), (1, 1)])
+def test_rnn_streaming_on_row_owned_plans_of_the_callers_choosing(L, n_wg, rounds):
+    """The per-step launches of the streaming path on matrices re-planned with csb_plan_rows:
+    several rounds per wavefront (the kernels compiled for that case, one product per launch and,
+    with two layers, two products of a diagonal in one launch), few and many workgroups."""
+    cfg = csb_inputs.RnnConfig("t", csb_inputs.LSTM, L, 24, 96, 16, 3.0, "binomial", 0.3, 1, 7, 50 + L)
+    wl = csb_inputs.make_rnn(cfg)
+    W = [oracle.csb_decode(oracle.csb_encode(m.A, m.br, m.bc)) for m in wl.W]
+    rseq, rhT, rcT = oracle.rnn_forward(cfg.cell, W, wl.bias, wl.x, cfg.input, cfg.hidden)
+    Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+    rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, [torch.from_numpy(b).cuda() for b in wl.bias])
+    for w in Ws:
+        st = w.plan_rows(n_wg, rounds)
+        say(f"[rnn] re-planned: {st['n_chunks']} workgroups, {st['rounds']} rounds")
+        assert st["row_owned"] == 1 and st["rounds"] >= rounds
+        w.validate()
+        w.upload()
+    hseq, hT, cT = rnn.forward(torch.from_numpy(wl.x).cuda())
+    torch.cuda.synchronize()
+    assert float(np.max(np.abs(hseq.cpu().numpy() - rseq))) <= TOL
+    assert float(np.max(np.abs(hT.cpu().numpy() - rhT))) <= TOL
+    assert float(np.max(np.abs(cT.cpu().numpy() - rcT))) <= TOL
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3"])
 def test_rnn_workloads_full_size(name):
     cfg = csb_inputs.CONFIGS[name]

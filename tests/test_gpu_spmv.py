@@ -181,3 +181,28 @@ def test_spmv_row_owned_plans(R, C, br, bc, rate):
             torch.cuda.synchronize()
             assert rel_max_err(y.cpu().numpy().astype(np.float64), ref) <= 1e-5
             assert torch.equal(M.spmv(xd), y) and torch.equal(M.spmv_static(xd), y)
+
+
+@pytest.mark.parametrize("shift", [1, 2, 3])
+def test_spmv_input_vector_at_any_four_byte_address(shift):
+    """An input vector that starts 4, 8 or 12 bytes past a 16-byte boundary (the kernel then
+    stages it 4 bytes per lane), default plan and a plan with several rounds: the same bits as
+    with the aligned vector."""
+    m = csb_inputs.small_matrix(31, 300, 512, 32, 32, rate=4.0)
+    x = csb_inputs.make_vectors(8, 512, 1).reshape(-1)
+    buf = torch.zeros(512 + 8, dtype=torch.float32, device="cuda")
+    assert buf.data_ptr() % 16 == 0
+    xs = buf[shift:shift + 512]
+    xs.copy_(torch.from_numpy(x))
+    xa = torch.from_numpy(x).cuda()
+    ref = oracle.matvec(oracle.csb_decode(oracle.csb_encode(m.A, 32, 32)), x)
+    for rounds in (0, 3):
+        say(f"[spmv] x at byte offset {4 * shift}, rounds>={rounds}")
+        M = CsbMatrix(m.A, 32, 32)
+        M.plan_rows(0, rounds)
+        M.upload()
+        ya = M.spmv(xa)
+        ys = M.spmv(xs)
+        torch.cuda.synchronize()
+        assert torch.equal(ya, ys)
+        assert rel_max_err(ys.cpu().numpy().astype(np.float64), ref) <= 1e-5
