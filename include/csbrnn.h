@@ -173,7 +173,8 @@ int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *s
 /*
  * The row-owned layout of the mat-vec (Sec. 4.3.1 / the equal-work role of Sec. 5.2), which
  * csb_plan and csb_plan_ex(mode 0) build next to the tile-based sections whenever the matrix
- * fits it: float32 values, at most 16383 columns, not planned for a GRU step.  Every
+ * fits it: at most 16383 columns, not planned for a GRU step (kernel values in any of the
+ * three storage formats).  Every
  * workgroup owns a contiguous range of at most 256 output rows (ranges of nearly equal
  * stored bytes, cut at any row), so no sum crosses workgroups and nothing is merged.  The
  * kernel-matrix rows that land in a range are sorted by column count, packed 64 to a group
@@ -182,10 +183,10 @@ int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *s
  * fixed size (8-bit column indices, column-major kernel values, no padding of the values),
  * so a launch requests all of its bytes at once from addresses that depend only on the
  * workgroup and wavefront numbers.  Row sums are formed in a fixed order (bitwise
- * reproducible).  csb_spmv reads this section when it exists; csb_spmm and csb_rnn_forward
- * keep reading the tile-based sections.
+ * reproducible).  csb_spmv and the per-step launches of csb_rnn_forward's streaming path read
+ * this section when it exists; csb_spmm keeps reading the tile-based sections.
  * csb_plan_rows plans like csb_plan with the parameters of this layout spelled out:
- * n_workgroups (0 = default: one per 1024 kernel-matrix rows, at most 256, at least
+ * n_workgroups (0 = default: one per 256 kernel-matrix rows, at most 256, at least
  * rows / 256) and min_rounds (0 or 1 = as few rounds as the LDS allows; more rounds make
  * the segments shorter).  Errors as csb_plan; CSB_EUNSUPPORTED if the matrix does not fit
  * the layout.
