@@ -205,10 +205,15 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
             have = NU;
         }
         if (stamps && r == 0u) t_first = wall_clock64();
-        const uint32_t h0 = uni_(lds_u32(s0));
+        // header and the first group's record in one go (both lie at the start of the first unit;
+        // the record is read whether there is a group or not: one LDS round trip less in front of
+        // the first group)
+        const uint4 hdr = lds_u128(s0);
+        uint4 rec = lds_u128(s0 + (uint32_t)sizeof(StreamSegHdr));   // record of the current group; the next one is fetched while this one runs
+        const uint32_t h0 = uni_(hdr.x);
         const uint32_t ng = h0 & 0xffffu, off_vbs = h0 >> 16;
         // the segment's own length: what lies behind it (up to the stride) is never requested
-        const uint32_t h1 = uni_(lds_u32(s0 + 4u));
+        const uint32_t h1 = uni_(hdr.y);
         own16 = h1 & 0xffffu;
         NU = (own16 + 63u) >> 6;
         const uint32_t next16 = h1 >> 16, NUn = (next16 + 63u) >> 6;      // this wavefront's segment of the next round
@@ -216,14 +221,12 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
         // (for the next round) as soon as the multiplication has left them
         uint32_t meta_units = NU, released = NU;
         if (ng) {
-            const uint32_t v0 = uni_(lds_u32(s0 + (uint32_t)sizeof(StreamSegHdr) + 12u)) & 0xffffu;   // val_off of group 0
+            const uint32_t v0 = uni_(rec.w) & 0xffffu;          // val_off of group 0
             // (records may spill past the first unit: wait for them)
             const uint32_t mu = (v0 * 4u + 1023u) >> 10;
             if (r == 0u && mu > have) { want_unit(mu - 1u); wait_unit(mu - 1u); have = mu; want_unit(mu); }
             meta_units = mu; released = mu;
         }
-        uint4 rec = make_uint4(0u, 0u, 0u, 0u);                // record of the current group; the next one is fetched while this one runs
-        if (ng) rec = lds_u128(s0 + (uint32_t)sizeof(StreamSegHdr));
         for (uint32_t g = 0; g < ng; ++g) {
             const uint32_t mlo = uni_(rec.x), mhi = uni_(rec.y), w2 = uni_(rec.z), w3 = uni_(rec.w);
             if (g + 1u < ng) rec = lds_u128(s0 + (uint32_t)sizeof(StreamSegHdr) + (g + 1u) * (uint32_t)sizeof(StreamGroup));
