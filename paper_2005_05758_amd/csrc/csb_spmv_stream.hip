@@ -176,12 +176,11 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
     if constexpr (GATED) {
         float *xl = (float *)smem;
         const uint32_t na = min(A.n0, A.cols);
-        // (one copy of the cell arithmetic in the code, passed twice: see FORM)
-#pragma clang loop unroll(disable)
-        for (uint32_t k = 0; k < 2u; ++k) {
-            const GateSrc &gs = k ? A.g1 : A.g0;
-            stage_segment(xl + (k ? na : 0u), gs, k ? A.cols - na : na, tid, kStreamThreads, wg == 0u);
-        }
+        // (two inlined copies of the staging code on purpose: the compiler then has the loads of
+        // both segments in flight together, which is worth more than the 1.5 KiB of code: passing
+        // one copy twice makes an LSTM step 0.2-0.5 us slower, a Li-GRU step 0.8)
+        stage_segment(xl, A.g0, na, tid, kStreamThreads, wg == 0u);
+        stage_segment(xl + na, A.g1, A.cols - na, tid, kStreamThreads, wg == 0u);
     } else { if (NU >= (uint32_t)W) wait_outstanding<W>(); else wait_outstanding<0>(); }   // the wavefront's part of the vector has landed
     // (a plain barrier: the fence builtins would also wait for the segment, which is still on its way)
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
