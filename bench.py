@@ -683,7 +683,7 @@ def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, cases=(("cfg5", 128), 
         del M
     best = res.get("spmm_cfg5_b128")
     if best:
-        res["roofline"] = {"kernel": "csb::spmm_reg_kernel<false, 16, 2>", "bound": "mfma", "achieved": best["tflops_algorithmic"],
+        res["roofline"] = {"kernel": "csb::spmm_reg_kernel<false, 16, 2, 0>", "bound": "mfma", "achieved": best["tflops_algorithmic"],
                            "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": best["frac_fp32_mfma_peak"],
                            "traffic": TRAFFIC_BYTES.get("spmm_cfg5_b128"),
                            "us_per_launch": best["us"], "flops_per_launch": 2.0 * best["nnz"] * best["batch"],

@@ -468,8 +468,9 @@ __global__ __launch_bounds__(NW * 64) void spmm_bf16_kernel(const DevMat m, cons
 }
 
 // ---------------------------------------------------------------------------------------
-// The wide form for float32 kernel values and row tiles of 16 or 32 rows, with the results
-// kept in registers.  Counters of the general kernel above on the 8192 x 8192 matrix with 128
+// The wide form for row tiles of 16 or 32 rows, with the results kept in registers (VF: storage
+// format of the kernel values; 16-bit values come as one word per row and pair of columns and
+// are unpacked to binary32 on their way into the MFMA).  Counters of the general kernel above on the 8192 x 8192 matrix with 128
 // right-hand sides show what its launch time is made of: vector instructions other than MFMA
 // keep every SIMD busy for 38 % of the launch (about 480 instructions per pass of at most 16
 // MFMAs, among them the accumulate of every 16-row slice's 16 x 64 results into the wavefront's
@@ -499,7 +500,7 @@ struct RegPass {
     bool valid;
 };
 
-template <bool TWO, int NW, int NH>
+template <bool TWO, int NW, int NH, int VF>
 __device__ __forceinline__ void spmm_reg_body(const DevMat &m, const XSrc &X, float *__restrict__ Y, const int64_t ldy,
                                               const uint32_t batch, const uint32_t block_x, const uint32_t block_y) {
     extern __shared__ float4 smem4[];
@@ -573,7 +574,8 @@ __device__ __forceinline__ void spmm_reg_body(const DevMat &m, const XSrc &X, fl
             if (lane < 16u) ((uint32_t *)inv)[lane] = 0xffffffffu;
             if (lane < p.r) inv[slot] = (uint8_t)lane;
             parts = 0;
-            const uint32_t base4 = (p.val_off + p.lane0) * 4u;
+            // (16-bit formats: one 32-bit word per kernel row and PAIR of columns, the even column in the low half)
+            const uint32_t base4 = ((VF == CSB_VAL_F32 ? p.val_off : p.val_off >> 1) + p.lane0) * 4u;
 #pragma unroll
             for (int h = 0; h < NH; ++h) {
                 const uint32_t ir = inv[16u * h + mrow];
@@ -608,7 +610,11 @@ __device__ __forceinline__ void spmm_reg_body(const DevMat &m, const XSrc &X, fl
             for (int s4 = 0; s4 < 4; ++s4) {
 #pragma unroll
                 for (int h = 0; h < NH; ++h)
-                    o.av[h][s4] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(vrsrc, (int)(ja[s4] * 256u + irow4[h]), 0, 0));
+                    if constexpr (VF == CSB_VAL_F32) {
+                        o.av[h][s4] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(vrsrc, (int)(ja[s4] * 256u + irow4[h]), 0, 0));
+                    } else {                                        // (unpacked in multiply: the load's result is not waited for here)
+                        o.av[h][s4] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(vrsrc, (int)((ja[s4] >> 1) * 256u + irow4[h]), 0, 0));
+                    }
                 if constexpr (TWO) {
                     const bool first = cb[s4] < split4;
                     const uint8_t *src = first ? x0 + __umul24(cb[s4], X.sj0) : x1 + __umul24(cb[s4] - split4, X.sj1);
@@ -626,7 +632,12 @@ __device__ __forceinline__ void spmm_reg_body(const DevMat &m, const XSrc &X, fl
 #pragma unroll
                 for (int s4 = 0; s4 < 4; ++s4) {
                     if ((uint32_t)s4 >= nk) break;
-                    const float a = o.av[h][s4];
+                    float a = o.av[h][s4];
+                    if constexpr (VF != CSB_VAL_F32) {              // this lane's column of the pair: kc is even, so its parity is kq's
+                        const uint32_t w = __float_as_uint(a);
+                        if constexpr (VF == CSB_VAL_BF16) a = __uint_as_float((kq & 1u) ? w & 0xffff0000u : w << 16);
+                        else a = (float)__builtin_bit_cast(_Float16, (uint16_t)((kq & 1u) ? w >> 16 : w & 0xffffu));
+                    }
                     D[h][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, o.bv[s4].x, D[h][0], 0, 0, 0);
                     D[h][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, o.bv[s4].y, D[h][1], 0, 0, 0);
                     D[h][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, o.bv[s4].z, D[h][2], 0, 0, 0);
@@ -665,10 +676,10 @@ __device__ __forceinline__ void spmm_reg_body(const DevMat &m, const XSrc &X, fl
     }
 }
 
-template <bool TWO, int NW, int NH>
+template <bool TWO, int NW, int NH, int VF>
 __global__ __launch_bounds__(NW * 64) void spmm_reg_kernel(const DevMat m, const XSrc X, float *__restrict__ Y,
                                                            const int64_t ldy, const uint32_t batch) {
-    spmm_reg_body<TWO, NW, NH>(m, X, Y, ldy, batch, blockIdx.x, blockIdx.y);
+    spmm_reg_body<TWO, NW, NH, VF>(m, X, Y, ldy, batch, blockIdx.x, blockIdx.y);
 }
 
 // Several independent products in one launch (blockIdx.z picks the product): the per-step
@@ -686,20 +697,21 @@ __global__ __launch_bounds__(NW * 64) void spmm_multi_kernel(const SpmmJobs J, c
     spmm_body<NT, TWO, NW, WIDE>(J.m[j], J.X[j], J.Y[j], J.ldy[j], batch, blockIdx.x, blockIdx.y);
 }
 
-template <bool TWO, int NW, int NH>
+template <bool TWO, int NW, int NH, int VF>
 __global__ __launch_bounds__(NW * 64) void spmm_reg_multi_kernel(const SpmmJobs J, const uint32_t batch) {
     const uint32_t j = blockIdx.z;
     if (blockIdx.x >= J.m[j].n_nz_tiles + J.m[j].n_zero_tiles) return;      // the grid is as wide as the widest product
-    spmm_reg_body<TWO, NW, NH>(J.m[j], J.X[j], J.Y[j], J.ldy[j], batch, blockIdx.x, blockIdx.y);
+    spmm_reg_body<TWO, NW, NH, VF>(J.m[j], J.X[j], J.Y[j], J.ldy[j], batch, blockIdx.x, blockIdx.y);
 }
 
 // Launch shape of one product: batch columns per workgroup (16 nt), wavefronts per workgroup.
 struct SpmmShape {
     int nt, nw;
     bool two, wide;
-    int reg_parts;          // wide form, float32 kernel values, row tiles of 16 or 32 rows: the kernel that keeps the
-                            // results in registers, with this many 16-row parts (else 0; four parts do not fit the
+    int reg_parts;          // wide form, row tiles of 16 or 32 rows: the kernel that keeps the results in
+                            // registers, with this many 16-row parts (else 0; four parts do not fit the
                             // registers of a 16-wavefront workgroup)
+    int vf;                 // storage format of the kernel values
     size_t lds;
     unsigned tiles, batch_tiles;
 };
@@ -738,9 +750,9 @@ static int spmm_shape(const SpmmCall &c, int32_t batch, size_t launch_wgs_factor
     const bool fits16 = (size_t)h.seg_meta + 16 * acc_per_wave <= (size_t)kLdsBudget;
     const int nw = fits16 && (wide || wgs(nt) * launch_wgs_factor < 2 * 256) ? 16 : 8;
     // (its 32-bit byte offsets into the value stream must stay below the out-of-range marker)
-    const int reg_parts = (wide && h.val_fmt == CSB_VAL_F32 && (h.br == 16 || h.br == 32) && h.n_vals * 4 < 0x7fffff00ull &&
+    const int reg_parts = (wide && (h.br == 16 || h.br == 32) && h.n_vals * 4 < 0x7fffff00ull &&
                            (size_t)h.seg_meta + (size_t)nw * acc_per_wave + (size_t)nw * 64 <= (size_t)160 * 1024) ? (int)h.br / 16 : 0;
-    *out = SpmmShape{nt, nw, two, wide, reg_parts, (size_t)h.seg_meta + (size_t)nw * acc_per_wave + (reg_parts ? (size_t)nw * 64 : 0), (unsigned)tiles,
+    *out = SpmmShape{nt, nw, two, wide, reg_parts, (int)h.val_fmt, (size_t)h.seg_meta + (size_t)nw * acc_per_wave + (reg_parts ? (size_t)nw * 64 : 0), (unsigned)tiles,
                      (unsigned)((batch + 16 * nt - 1) / (16 * nt))};
     return CSB_OK;
 }
@@ -751,7 +763,8 @@ static const void *spmm_kernel_for(const SpmmShape &sh) {
 #define CSB_SPMM_K(NT, TWO, NW, WIDE) \
     (MULTI ? (const void *)spmm_multi_kernel<NT, TWO, NW, WIDE> : (const void *)spmm_kernel<NT, TWO, NW, WIDE>)
     if (sh.reg_parts) {
-#define CSB_SPMM_R(TWO, NW, NH) (MULTI ? (const void *)spmm_reg_multi_kernel<TWO, NW, NH> : (const void *)spmm_reg_kernel<TWO, NW, NH>)
+#define CSB_SPMM_RV(TWO, NW, NH, VF) (MULTI ? (const void *)spmm_reg_multi_kernel<TWO, NW, NH, VF> : (const void *)spmm_reg_kernel<TWO, NW, NH, VF>)
+#define CSB_SPMM_R(TWO, NW, NH) (sh.vf == CSB_VAL_F16 ? CSB_SPMM_RV(TWO, NW, NH, CSB_VAL_F16) : sh.vf == CSB_VAL_BF16 ? CSB_SPMM_RV(TWO, NW, NH, CSB_VAL_BF16) : CSB_SPMM_RV(TWO, NW, NH, CSB_VAL_F32))
 #define CSB_SPMM_RN(NH) \
         if (sh.nw == 16) return sh.two ? CSB_SPMM_R(true, 16, NH) : CSB_SPMM_R(false, 16, NH); \
         return sh.two ? CSB_SPMM_R(true, 8, NH) : CSB_SPMM_R(false, 8, NH);
@@ -759,6 +772,7 @@ static const void *spmm_kernel_for(const SpmmShape &sh) {
         CSB_SPMM_RN(2)
 #undef CSB_SPMM_RN
 #undef CSB_SPMM_R
+#undef CSB_SPMM_RV
     }
     if (sh.wide) {
         if (sh.nw == 16) return sh.two ? CSB_SPMM_K(4, true, 16, true) : CSB_SPMM_K(4, false, 16, true);
@@ -805,7 +819,7 @@ int spmm_strided_multi(const SpmmCall *calls, int n, int32_t batch, void *stream
         for (int i = 0; i < n; ++i) {
             int rc = spmm_shape(calls[i], batch, (size_t)n, &sh[i], &J.X[i]);
             if (rc != CSB_OK) return rc;
-            same = same && sh[i].nt == sh[0].nt && sh[i].nw == sh[0].nw && sh[i].two == sh[0].two && sh[i].wide == sh[0].wide && sh[i].reg_parts == sh[0].reg_parts;
+            same = same && sh[i].nt == sh[0].nt && sh[i].nw == sh[0].nw && sh[i].two == sh[0].two && sh[i].wide == sh[0].wide && sh[i].reg_parts == sh[0].reg_parts && sh[i].vf == sh[0].vf;
             lds = std::max(lds, sh[i].lds);
             tiles = std::max(tiles, sh[i].tiles);
             J.m[i] = dev_mat(calls[i].mat);

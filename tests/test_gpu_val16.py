@@ -87,7 +87,10 @@ def test_rounding_is_visible(fmt, name):
 
 @pytest.mark.parametrize("fmt,name", FORMATS)
 @pytest.mark.parametrize("R,C,br,bc,B", [(37, 53, 8, 8, 1), (200, 150, 16, 16, 5), (130, 257, 32, 32, 17), (300, 200, 64, 64, 40),
-                                         (1024, 700, 32, 32, 64)])
+                                         (1024, 700, 32, 32, 64),
+                                         # 256 row tiles and more, 64 right-hand sides per workgroup: the kernel that keeps
+                                         # its results in registers (one and two 16-row parts per tile), 16-bit values unpacked
+                                         (4200, 300, 16, 16, 64), (8300, 200, 32, 32, 128), (8300, 90, 32, 32, 52)])
 def test_spmm(fmt, name, R, C, br, bc, B):
     say(f"[val16] spmm {name} {R}x{C} block {br}x{bc} batch {B}")
     m = csb_inputs.small_matrix(R + C + B, R, C, br, bc, rate=4.0)
@@ -205,6 +208,25 @@ def test_spmm_bfloat_refusals():
         M.spmm_bfloat(torch.zeros((64, 10), dtype=torch.bfloat16, device="cuda")[:, :8])
     with pytest.raises(CsbError):                      # a bfloat16 matrix is not a binary16 one
         M.spmm_half(torch.zeros((64, 8), dtype=torch.float16, device="cuda"))
+
+
+@pytest.mark.parametrize("fmt,name", FORMATS)
+def test_spmm_16bit_values_full_size(fmt, name):
+    """csb_spmm with 16-bit kernel values and float32 right-hand sides on the 8192 x 8192
+    heavy-tailed matrix at batch 128, the launch bench.py times: sampled rows against the oracle."""
+    m = csb_inputs.make_mat(csb_inputs.CONFIGS["cfg5"])
+    B = 128
+    X = csb_inputs.make_vectors(9, m.cols, B).reshape(m.cols, B)
+    M = packed(m.A, m.br, m.bc, fmt)
+    Y = M.spmm(torch.from_numpy(X).cuda())
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([np.arange(0, 64), np.random.default_rng(1).integers(0, m.rows, 400), [m.rows - 1]]))
+    Aq = oracle.round_weights(m.A[rows], name)
+    ref = oracle.matmat(Aq, X)
+    got = Y.cpu().numpy()[rows].astype(np.float64)
+    absr = oracle.matmat(np.abs(Aq), np.abs(X))
+    k = np.count_nonzero(Aq, axis=1)[:, None]
+    assert np.all(np.abs(got - ref) <= 2.0 * np.maximum(k, 1) * 2.0 ** -24 * absr + 1e-30)
 
 
 @pytest.mark.parametrize("fmt,name", FORMATS)
