@@ -143,6 +143,35 @@ def test_rnn(fmt, name, cell, L, I, H, T, B, block):
 
 
 @pytest.mark.parametrize("fmt,name", FORMATS)
+@pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
+def test_rnn_batched_many_row_tiles(fmt, name, cell):
+    """Two layers of 1024 units in blocks of 16 at batch 64: 256 row tiles per matrix, so the
+    layers' products share launches of the kernel that keeps its results in registers, here
+    with 16-bit kernel values (one product per launch and two, one and two input sources)."""
+    cfg = csb_inputs.RnnConfig("t", cell, 2, 48, 1024, 16, 12.0, "binomial", 0.05, 64, 3, 33)
+    wl = csb_inputs.make_rnn(cfg)
+    Wq = [oracle.round_weights(m.A, name) for m in wl.W]
+    rseq, rhT, rcT = oracle.rnn_forward(cell, Wq, wl.bias, wl.x, cfg.input, cfg.hidden)
+    Ws = []
+    for m in wl.W:
+        M = CsbMatrix(m.A, m.br, m.bc)
+        M.set_value_format(fmt)
+        Ws.append(M)
+    rnn = CsbRnn(CELL_LSTM if cell == csb_inputs.LSTM else CELL_GRU, cfg.input, cfg.hidden, Ws,
+                 [torch.from_numpy(b).cuda() for b in wl.bias])
+    for M in Ws:
+        M.validate()
+        M.upload()
+    say(f"[val16] batched rnn {name} cell={cell} 2 x 1024, block 16, batch 64")
+    hseq, hT, cT = rnn.forward(torch.from_numpy(wl.x).cuda())
+    torch.cuda.synchronize()
+    e = max(float(np.max(np.abs(hseq.cpu().numpy() - rseq))), float(np.max(np.abs(hT.cpu().numpy() - rhT))))
+    if cell == csb_inputs.LSTM:
+        e = max(e, float(np.max(np.abs(cT.cpu().numpy() - rcT))))
+    assert e <= 1e-4, e
+
+
+@pytest.mark.parametrize("fmt,name", FORMATS)
 def test_spmv_full_size_stress(fmt, name):
     """The 8192 x 8192 heavy-tailed matrix bench.py times, in its launch configuration (default
     plan), every output row against the oracle."""
