@@ -173,8 +173,8 @@ int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *s
 /*
  * The row-owned layout of the mat-vec (Sec. 4.3.1 / the equal-work role of Sec. 5.2), which
  * csb_plan and csb_plan_ex(mode 0) build next to the tile-based sections whenever the matrix
- * fits it: at most 16383 columns, not planned for a GRU step (kernel values in any of the
- * three storage formats).  Every
+ * fits it: at most 16383 columns (kernel values in any of the three storage formats; a
+ * matrix planned for a GRU step is laid out with the row split of that step).  Every
  * workgroup owns a contiguous range of at most 256 output rows (ranges of nearly equal
  * stored bytes, cut at any row), so no sum crosses workgroups and nothing is merged.  The
  * kernel-matrix rows that land in a range are sorted by column count, packed 64 to a group

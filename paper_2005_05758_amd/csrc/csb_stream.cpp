@@ -29,10 +29,15 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 constexpr uint64_t kLanesPerWg = 256;
 
 // One virtual block of a workgroup: kernel-matrix rows [a0, a1) of CSB block b.
+// With a GRU row split (SplitSpec) a block below the split row comes as two: its columns in
+// front of the split column (summed into the row itself) and those from it on (summed into
+// row + shift); q0 is the first column position of the part inside the block's column list.
 struct SVb {
     uint32_t b;
     uint16_t a0, a1;
-    uint16_t c;
+    uint16_t c;       // columns of the part
+    uint16_t q0;
+    uint16_t hi;      // 1: the part that is summed into row + shift
 };
 
 struct Lane {
@@ -108,12 +113,23 @@ SegSize piece_size(const WgLayout &w, const Piece &p, size_t vbytes) {
 int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_stats *stats_out) {
     Plan &pl = m->plan;
     pl.stream = StreamPlan{};
-    if (pl.split.active()) return CSB_OK;
+    const SplitSpec split = pl.split;
+    // (a split whose shifted rows do not start where the matrix ends would interleave them with others: not laid out here)
+    if (split.active() && (split.split_row + split.shift != m->rows || split.split_row < 0 || split.split_row > m->rows)) return CSB_OK;
     const size_t vbytes = m->val_fmt == CSB_VAL_F32 ? 4 : 2;
-    if (m->cols > kMaxStageCols || m->rows > 0x7fffffff) return CSB_OK;
+    if (m->cols > kMaxStageCols || m->rows + (split.active() ? split.shift : 0) > 0x7fffffff) return CSB_OK;
     try {
         const int br = m->br;
-        const int64_t R = m->rows;
+        const int64_t R = m->rows + (split.active() ? split.shift : 0);    // output rows
+        // position of the split column in a block's column list (all of it without a split)
+        auto split_pos = [&](size_t b, int32_t bj) {
+            const int nc = m->ncols[b];
+            if (!split.active()) return nc;
+            const uint16_t *ci = m->colidx.data() + m->col_off[b];
+            int qs = 0;
+            while (qs < nc && (int64_t)bj * m->bc + ci[qs] < split.split_col) ++qs;
+            return qs;
+        };
 
         // ---- 1. bytes each output row brings along, lanes in all ---------------------------
         std::vector<uint32_t> roww((size_t)R, 0);
@@ -124,8 +140,17 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                 const int nr = m->nrows[b], nc = m->ncols[b];
                 if (nr == 0 || nc == 0) continue;
                 const uint16_t *ri = m->rowidx.data() + m->row_off[b];
-                for (int a = 0; a < nr; ++a) roww[(size_t)bi * br + ri[a]] += (uint32_t)nc + (uint32_t)kStreamGroupOverhead;
-                lanes_total += (uint64_t)nr;
+                const int qs = split_pos(b, bj);
+                for (int a = 0; a < nr; ++a) {
+                    const int64_t g = (int64_t)bi * br + ri[a];
+                    if (!split.active() || g < split.split_row) {
+                        roww[(size_t)g] += (uint32_t)nc + (uint32_t)kStreamGroupOverhead;
+                        ++lanes_total;
+                        continue;
+                    }
+                    if (qs > 0) { roww[(size_t)g] += (uint32_t)qs + (uint32_t)kStreamGroupOverhead; ++lanes_total; }
+                    if (nc > qs) { roww[(size_t)(g + split.shift)] += (uint32_t)(nc - qs) + (uint32_t)kStreamGroupOverhead; ++lanes_total; }
+                }
             }
         // Steps 2 to 4 run several times: first with the rows weighted by the work they bring
         // (column steps plus the per-piece overhead, per lane), then with corrected weights (below).
@@ -177,25 +202,45 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
             w.nrows = cut[k + 1] - cut[k];
             rows_max = std::max(rows_max, w.nrows);
             const int64_t r0 = w.row0, r1 = cut[k + 1];
-            for (int64_t bi = r0 / br; bi <= (r1 - 1) / br; ++bi)
-                for (int32_t bj = 0; bj < m->nbc; ++bj) {
-                    const size_t b = (size_t)bi * m->nbc + bj;
-                    const int nr = m->nrows[b], nc = m->ncols[b];
-                    if (nr == 0 || nc == 0) continue;
-                    const uint16_t *ri = m->rowidx.data() + m->row_off[b];
-                    int a0 = 0;
-                    while (a0 < nr && bi * br + ri[a0] < r0) ++a0;
-                    int a1 = a0;
-                    while (a1 < nr && bi * br + ri[a1] < r1) ++a1;
-                    if (a1 > a0) w.vbs.push_back(SVb{(uint32_t)b, (uint16_t)a0, (uint16_t)a1, (uint16_t)nc});
-                }
+            // the workgroup's output rows come from up to three zones of the matrix: rows in front
+            // of the split row (all columns), rows from it on (their columns in front of the split
+            // column), and the same rows once more, relabelled (their columns from it on)
+            struct Zone { int64_t o0, o1, back; int part; };      // output rows [o0, o1) = matrix rows - back; part 0 all, 1 low, 2 high
+            Zone zones[3];
+            int nz = 0;
+            if (!split.active()) zones[nz++] = Zone{r0, r1, 0, 0};
+            else {
+                const int64_t sr = split.split_row, mr = m->rows;
+                if (r0 < std::min(r1, sr)) zones[nz++] = Zone{r0, std::min(r1, sr), 0, 0};
+                if (std::max(r0, sr) < std::min(r1, mr)) zones[nz++] = Zone{std::max(r0, sr), std::min(r1, mr), 0, 1};
+                if (std::max(r0, mr) < r1) zones[nz++] = Zone{std::max(r0, mr), r1, split.shift, 2};
+            }
+            for (int zi = 0; zi < nz; ++zi) {
+                const Zone &z = zones[zi];
+                const int64_t g0 = z.o0 - z.back, g1 = z.o1 - z.back;          // matrix rows
+                for (int64_t bi = g0 / br; bi <= (g1 - 1) / br; ++bi)
+                    for (int32_t bj = 0; bj < m->nbc; ++bj) {
+                        const size_t b = (size_t)bi * m->nbc + bj;
+                        const int nr = m->nrows[b], nc = m->ncols[b];
+                        if (nr == 0 || nc == 0) continue;
+                        const int qs = z.part == 0 ? nc : split_pos(b, bj);
+                        const int q0 = z.part == 2 ? qs : 0, q1 = z.part == 1 ? qs : nc;
+                        if (q1 <= q0) continue;
+                        const uint16_t *ri = m->rowidx.data() + m->row_off[b];
+                        int a0 = 0;
+                        while (a0 < nr && bi * br + ri[a0] < g0) ++a0;
+                        int a1 = a0;
+                        while (a1 < nr && bi * br + ri[a1] < g1) ++a1;
+                        if (a1 > a0) w.vbs.push_back(SVb{(uint32_t)b, (uint16_t)a0, (uint16_t)a1, (uint16_t)(q1 - q0), (uint16_t)q0, (uint16_t)(z.part == 2 ? 1 : 0)});
+                    }
+            }
             std::stable_sort(w.vbs.begin(), w.vbs.end(), [](const SVb &x, const SVb &y) { return x.c > y.c; });
             for (uint32_t v = 0; v < w.vbs.size(); ++v) {
                 const SVb &vb = w.vbs[v];
                 const int64_t bi = vb.b / m->nbc;
                 const uint16_t *ri = m->rowidx.data() + m->row_off[vb.b];
                 for (int a = vb.a0; a < vb.a1; ++a)
-                    w.lanes.push_back(Lane{v, (uint16_t)a, (uint16_t)(bi * br + ri[a] - r0)});
+                    w.lanes.push_back(Lane{v, (uint16_t)a, (uint16_t)(bi * br + ri[a] + (vb.hi ? split.shift : 0) - r0)});
             }
             for (uint32_t l0 = 0; l0 < w.lanes.size(); l0 += kWave) w.g_cmax.push_back(w.vbs[w.lanes[l0].vb].c);
         }
@@ -466,14 +511,14 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                         // column indices; behind them, up to the piece's steps, the slice's first column again:
                         // an input every row of the block multiplies anyway (so a non-finite input
                         // reaches only rows that use it), here with values stored as zeros
-                        const uint16_t *ci = m->colidx.data() + m->col_off[vb.b] + p.j0;
+                        const uint16_t *ci = m->colidx.data() + m->col_off[vb.b] + vb.q0 + p.j0;
                         for (size_t j = 0; j < list_len; ++j) seg[list_pos + j] = (uint8_t)ci[j < (size_t)ck ? j : 0];
                         list_pos += list_len;
                         const float *kv = m->val.data() + m->val_off[vb.b];
                         for (uint32_t i = 0; i < rws; ++i) {
                             const Lane &ln = w.lanes[l0 + lane0 + i];
                             for (int j = 0; j < ck; ++j) {
-                                const float v = kv[(size_t)ln.a * vb.c + p.j0 + j];
+                                const float v = kv[(size_t)ln.a * m->ncols[vb.b] + vb.q0 + p.j0 + j];
                                 const size_t at = (size_t)j * kWave + lane0 + i;
                                 if (vbytes == 4) std::memcpy(dst + at * 4, &v, 4);
                                 else {
@@ -562,10 +607,19 @@ int validate_stream(const csb_matrix *m) {
         std::memcpy(&bits, &f, 4);
         return bits;
     };
-    const int64_t R = m->rows, Ccols = m->cols;
+    const SplitSpec &split = pl.split;
+    const int64_t R = m->rows + (split.active() ? split.shift : 0), Ccols = m->cols;     // output rows
     std::vector<float> expect((size_t)R * Ccols, 0.0f), got((size_t)R * Ccols, 0.0f);
     std::vector<uint8_t> seen((size_t)R * Ccols, 0);
     if (csb_unpack(m, expect.data(), Ccols) != CSB_OK) return CSB_EINVAL;
+    if (split.active()) {                                 // the relabelling: entries below the split row, from the split column on, move down by `shift` rows
+        if (split.split_row + split.shift != m->rows) return fail("row split");
+        for (int64_t g = split.split_row; g < m->rows; ++g)
+            for (int64_t c = split.split_col; c < Ccols; ++c) {
+                expect[(size_t)(g + split.shift) * Ccols + c] = expect[(size_t)g * Ccols + c];
+                expect[(size_t)g * Ccols + c] = 0.0f;
+            }
+    }
     std::vector<uint8_t> row_done((size_t)R, 0);
     size_t vals_used = 0;
     for (uint32_t k = 0; k < sp.n_wg; ++k) {

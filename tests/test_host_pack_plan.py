@@ -391,3 +391,21 @@ def test_plan_rows_sweep():
     Z = CsbMatrix(np.zeros((40, 48), np.float32), 16, 16)
     assert Z.plan_rows(0, 0)["row_owned"] == 1
     Z.validate()
+
+
+@pytest.mark.parametrize("I,H,block,layers", [(40, 100, 32, 1), (5, 7, 4, 2), (33, 50, 16, 2), (64, 96, 32, 1), (30, 300, 32, 2)])
+def test_gru_step_matrices_get_the_row_owned_layout(I, H, block, layers):
+    """A GRU handle plans its matrices with the row split of its step (the candidate's rows once
+    over the input columns and once, H rows further down, over the recurrent ones).  The
+    row-owned section holds that split as well -- also where the split column falls inside a
+    block column -- and decodes to the relabelled matrix (csb_plan_validate)."""
+    from paper_2005_05758_amd import CsbRnn
+    cfg = csb_inputs.RnnConfig("t", csb_inputs.GRU, layers, I, H, block, 3.0, "binomial", 0.3, 1, 2, 11)
+    wl = csb_inputs.make_rnn(cfg)
+    Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+    rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, None)
+    for w in Ws:
+        st = w.plan_stats()
+        assert st["row_owned"] == 1, st
+        w.validate()
+    del rnn
