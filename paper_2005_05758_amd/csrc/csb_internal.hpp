@@ -258,6 +258,8 @@ struct csb_matrix {
     std::vector<float> val;
     std::vector<int64_t> val_off, row_off, col_off;
     int32_t val_fmt = 0;          // CSB_VAL_*: how the device value stream is stored
+    int32_t stream_wg_limit = 256;   // most workgroups a default row-owned plan takes (an RNN handle with stacked layers,
+                                     // whose products share launches, leaves its matrices a share of the 256 CUs each)
     csb::Plan plan;
     void *d_buf = nullptr;        // caller-owned device image, set by csb_upload
     bool uploaded = false;

@@ -1167,6 +1167,7 @@ extern "C" int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int
             if (!W[l]->plan.valid || !(W[l]->plan.split == sp)) {
                 // (a plan the caller made keeps its workgroup count and mode)
                 const bool had = W[l]->plan.valid;
+                W[l]->stream_wg_limit = 256 / std::min(n_layers, kMaxJobsPerLaunch);   // the layers of a diagonal share a launch
                 int rc = plan_matrix(W[l], had ? W[l]->plan.req_chunks : 0, 16, sp, nullptr, had ? W[l]->plan.req_mode : 0);
                 if (rc != CSB_OK) { delete r; return rc; }
             }
@@ -1203,6 +1204,7 @@ extern "C" int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hid
         for (int l = 0; l < n_layers; ++l) {
             for (csb_matrix *m : {W[l], Wp[l]})
                 if (!m->plan.valid || m->plan.split.active()) {
+                    m->stream_wg_limit = 256 / std::min(n_layers, kMaxJobsPerLaunch);   // the layers of a diagonal share a launch
                     int rc = plan_matrix(m, 0, 16, SplitSpec{}, nullptr, 0);
                     if (rc != CSB_OK) { delete r; return rc; }
                 }
@@ -1256,6 +1258,7 @@ extern "C" int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hi
         for (int l = 0; l < n_layers; ++l) {
             for (csb_matrix *m : {Wa[l], Un[l]})
                 if (!m->plan.valid || m->plan.split.active()) {
+                    m->stream_wg_limit = 256 / std::min(n_layers, kMaxJobsPerLaunch);   // the layers of a diagonal share a launch
                     int rc = plan_matrix(m, 0, 16, SplitSpec{}, nullptr, 0);
                     if (rc != CSB_OK) { delete r; return rc; }
                 }

@@ -167,7 +167,7 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
         for (double v : rw) total_w += v;
 
         // ---- 2. row ranges of the workgroups: nearly equal weight, cut at any row ----------
-        int64_t n_wg = n_wg_req > 0 ? n_wg_req : (int64_t)std::min<uint64_t>(256, std::max<uint64_t>(1, (lanes_total + kLanesPerWg - 1) / kLanesPerWg));
+        int64_t n_wg = n_wg_req > 0 ? n_wg_req : (int64_t)std::min<uint64_t>((uint64_t)std::max(1, std::min(256, m->stream_wg_limit)), std::max<uint64_t>(1, (lanes_total + kLanesPerWg - 1) / kLanesPerWg));
         n_wg = std::max<int64_t>(n_wg, (R + kStreamMaxRows - 1) / kStreamMaxRows);
         n_wg = std::min<int64_t>(n_wg, R);
         cut.clear();
