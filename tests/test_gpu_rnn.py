@@ -102,6 +102,31 @@ def test_rnn_streaming_on_row_owned_plans_of_the_callers_choosing(L, n_wg, round
     assert float(np.max(np.abs(cT.cpu().numpy() - rcT))) <= TOL
 
 
+@pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
+@pytest.mark.parametrize("L", [1, 2])
+def test_rnn_streaming_on_tile_layout_plans(cell, L):
+    """The streaming path on matrices planned again in the tile layout (equal split, row tiles
+    shared between workgroups): its per-step launches then run the tile kernel, the GRU's with
+    the row split of its step, stacked layers two products to a launch."""
+    cfg = csb_inputs.RnnConfig("t", cell, L, 33, 100, 16, 3.0, "binomial", 0.3, 1, 6, 70 + L)
+    wl = csb_inputs.make_rnn(cfg)
+    W = [oracle.csb_decode(oracle.csb_encode(m.A, m.br, m.bc)) for m in wl.W]
+    rseq, rhT, rcT = oracle.rnn_forward(cfg.cell, W, wl.bias, wl.x, cfg.input, cfg.hidden)
+    Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+    rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, [torch.from_numpy(b).cuda() for b in wl.bias])
+    for w in Ws:
+        st = w.plan(5, 2)                                      # (a GRU's matrix keeps its row split)
+        assert st["row_owned"] == 0
+        w.validate()
+        w.upload()
+    hseq, hT, cT = rnn.forward(torch.from_numpy(wl.x).cuda())
+    torch.cuda.synchronize()
+    assert float(np.max(np.abs(hseq.cpu().numpy() - rseq))) <= TOL
+    assert float(np.max(np.abs(hT.cpu().numpy() - rhT))) <= TOL
+    if cell == csb_inputs.LSTM:
+        assert float(np.max(np.abs(cT.cpu().numpy() - rcT))) <= TOL
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3"])
 def test_rnn_workloads_full_size(name):
     cfg = csb_inputs.CONFIGS[name]
