@@ -331,7 +331,10 @@ int csb_sharing_model(const csb_matrix *m, int32_t P, int32_t Q, int32_t K, int3
  * d_bias[l] of G*hidden floats (d_bias NULL or d_bias[l] NULL = zero bias).
  * Each W[l] must be packed; it is planned by this call if it is not yet, in the layout
  * the step kernels need (the GRU keeps the input-side and recurrent-side sums of its n
- * rows apart).  Upload each W[l] afterwards with csb_upload.
+ * rows apart; in a model of several layers, whose products share launches, a matrix is laid
+ * out for its share of the compute units: at most 256 / min(n_layers, 4) workgroups in the
+ * row-owned layout; csb_plan* on the matrix afterwards plans for all of them again).  Upload
+ * each W[l] afterwards with csb_upload.
  */
 int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int32_t hidden,
                    csb_matrix *const *W, const float *const *d_bias, csb_rnn **out);
