@@ -107,6 +107,7 @@ def test_random_recurrent_models(group):
         h0 = rng.uniform(-0.5, 0.5, size=(L, B, hs)).astype(np.float32) if with_state else None
         c0 = (rng.uniform(-0.5, 0.5, size=(L, B, H)).astype(np.float32)
               if with_state and kind in ("lstm", "lstmp") else None)
+        fmt, fname = FORMATS[int(rng.integers(0, 3))] if kind in ("lstm", "gru", "ligru") else FORMATS[0]   # (drawn last)
         if kind == "lstmp":
             wl = csb_inputs.make_lstmp(tr, L, I, H, proj, block, rate, T, B, sigma=sigma)
             bias = [torch.from_numpy(b).cuda() for b in wl.bias]
@@ -126,12 +127,16 @@ def test_random_recurrent_models(group):
                 rnn, mats = CsbRnn(P.CELL_GRU_RB, I, H, Was, bias, Wp=Uns), Was + Uns
             else:
                 mats = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+                for m in mats:
+                    if fname:
+                        m.set_value_format(fmt)                  # before the handle is created over it
                 rnn = CsbRnn(cell, I, H, mats, bias)
-            rseq, rhT, rcT = oracle.rnn_forward(cell, [m.A for m in wl.W], wl.bias, wl.x, I, H, h0=h0, c0=c0)
+            Wref = [oracle.round_weights(m.A, fname) if fname else m.A for m in wl.W]
+            rseq, rhT, rcT = oracle.rnn_forward(cell, Wref, wl.bias, wl.x, I, H, h0=h0, c0=c0)
         # (a batch on the resident kernel in every second case that asks for the resident layout)
         resident = (B == 1 or tr % 2 == 0) and want_resident and rnn.stats()["resident"] == 1
         say(f"[random models] case {tr}: {kind} L={L} I={I} H={H} proj={proj if kind == 'lstmp' else 0} block={block} "
-            f"rate={rate} T={T} B={B} resident={resident} state={with_state}")
+            f"rate={rate} T={T} B={B} resident={resident} state={with_state} values={fname or 'f32'}")
         if resident:
             rnn.upload()
         else:
