@@ -643,10 +643,10 @@ def val16_leg(torch, np, csb_inputs, CsbMatrix, stream_gbps, formats=("f16", "bf
                 bf[f"batch{Bb}"] = {"us": round(us, 2), "tflops_algorithmic": round(tf, 3)}
             tf = bf["batch512"]["tflops_algorithmic"]
             entry["spmm_bfloat"] = dict(bf, roofline={
-                "kernel": "csb::spmm_bf16_kernel<16>", "bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
+                "kernel": "csb::spmm_reg16_kernel<16, 2, 2>", "bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
                 "frac": round(tf / 2500.0, 5), "traffic": None,
-                "note": "dense bf16 MFMA peak as the nominal roof; like the f32 kernel the launch is bound by the gather of X "
-                        "through L2 (half the bytes here), not by the matrix cores"})
+                "note": "dense bf16 MFMA peak as the nominal roof; one 16-column MFMA step per block, part and tile of 16 "
+                        "right-hand sides: the launch is bound by its loads and its instruction stream, not by the matrix cores"})
         res[f"spmv_cfg5_{name}"] = entry
         del copies, M
     return res

@@ -493,6 +493,15 @@ struct RegOps {
     float4 bv[4];
     uint32_t parts;              // bit h: the block has rows in part h (uniform)
 };
+// ... with 16-bit right-hand sides (X16): a pass is ONE 16-column MFMA step per part and tile; a
+// lane's four columns of its tile row are two words of the value stream, its four right-hand
+// sides of a column eight bytes of X.
+template <int NH>
+struct RegOps16 {
+    uint32_t aw[NH][2];
+    uint2 xv[4];
+    uint32_t parts;
+};
 struct RegPass {
     uint32_t k, kc;              // virtual block (inside the segment), first column of the pass
     uint32_t r, c, lane0;        // the block's rows, columns, first lane
@@ -500,7 +509,7 @@ struct RegPass {
     bool valid;
 };
 
-template <bool TWO, int NW, int NH, int VF>
+template <bool TWO, int NW, int NH, int VF, bool X16 = false>
 __device__ __forceinline__ void spmm_reg_body(const DevMat &m, const XSrc &X, float *__restrict__ Y, const int64_t ldy,
                                               const uint32_t batch, const uint32_t block_x, const uint32_t block_y) {
     extern __shared__ float4 smem4[];
@@ -523,7 +532,7 @@ __device__ __forceinline__ void spmm_reg_body(const DevMat &m, const XSrc &X, fl
     const uint32_t rank = block_x, tile = m.nz_tiles[rank];
     const uint32_t mrow = lane & 15u, kq = lane >> 4;              // A: tile row in its part, column-in-4; B: right-hand sides 4 mrow .. + 3, row-in-4
     const uint32_t ncol = bt0 + 4u * mrow;
-    const uint32_t nbyte = (ncol < batch ? ncol : 0u) * 4u;        // (batch is a multiple of 4: the four are in or out together)
+    const uint32_t nbyte = (ncol < batch ? ncol : 0u) * (X16 ? 2u : 4u);   // (batch is a multiple of 4: the four are in or out together)
     const uint8_t *const x0 = (const uint8_t *)X.p0 + nbyte, *const x1 = (const uint8_t *)X.p1 + nbyte;
     const uint32_t split4 = 4u * X.n0;
     floatx4 D[NH][4];
@@ -645,6 +654,58 @@ __device__ __forceinline__ void spmm_reg_body(const DevMat &m, const XSrc &X, fl
                 }
             }
         };
+        // The same two steps with 16-bit right-hand sides (X.p0: their rows, X.sj0: elements per row):
+        // 2 NH + 4 loads, always, and one 16-column MFMA per part and tile.
+        auto issue16 = [&](const RegPass &p, RegOps16<NH> &o) {
+            o.parts = parts;
+            const uint32_t j0 = p.kc + 4u * kq;                                  // this lane's four columns
+            const uint32_t w0 = j0 < p.c ? (j0 >> 1) * 256u : 0x3fffff00u;       // words of the pairs (j0, j0 + 1), (j0 + 2, j0 + 3);
+            const uint32_t w1 = j0 + 2u < p.c ? (j0 >> 1) * 256u + 256u : 0x3fffff00u;   // a pair the block lacks: past the stream
+            uint32_t cb[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) cb[i] = *(const uint16_t *)(meta + p.list + 2u * min(j0 + (uint32_t)i, p.c - 1u));   // 4 * column
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                o.aw[h][0] = __builtin_amdgcn_raw_buffer_load_b32(vrsrc, (int)(w0 + irow4[h]), 0, 0);
+                o.aw[h][1] = __builtin_amdgcn_raw_buffer_load_b32(vrsrc, (int)(w1 + irow4[h]), 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)      // (a column the block lacks reads its last one: finite, times a zero)
+                o.xv[i] = *(const uint2 *)((const uint8_t *)X.p0 + (size_t)((__umul24(cb[i], X.sj0) >> 1) + nbyte));
+        };
+        auto multiply16 = [&](const RegOps16<NH> &o) {
+            // xv[i] = right-hand sides 0..3 at column i; tile t wants columns 0..3 at right-hand side t
+            const uint2 b0 = make_uint2((o.xv[0].x & 0xffffu) | (o.xv[1].x << 16), (o.xv[2].x & 0xffffu) | (o.xv[3].x << 16));
+            const uint2 b1 = make_uint2((o.xv[0].x >> 16) | (o.xv[1].x & 0xffff0000u), (o.xv[2].x >> 16) | (o.xv[3].x & 0xffff0000u));
+            const uint2 b2 = make_uint2((o.xv[0].y & 0xffffu) | (o.xv[1].y << 16), (o.xv[2].y & 0xffffu) | (o.xv[3].y << 16));
+            const uint2 b3 = make_uint2((o.xv[0].y >> 16) | (o.xv[1].y & 0xffff0000u), (o.xv[2].y >> 16) | (o.xv[3].y & 0xffff0000u));
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                if (!((o.parts >> h) & 1u)) continue;              // (uniform) no row of the block in this part
+                const uint2 a = make_uint2(o.aw[h][0], o.aw[h][1]);
+                D[h][0] = mfma_16bit<VF == CSB_VAL_F16>(a, b0, D[h][0]);
+                D[h][1] = mfma_16bit<VF == CSB_VAL_F16>(a, b1, D[h][1]);
+                D[h][2] = mfma_16bit<VF == CSB_VAL_F16>(a, b2, D[h][2]);
+                D[h][3] = mfma_16bit<VF == CSB_VAL_F16>(a, b3, D[h][3]);
+            }
+        };
+        if constexpr (X16) {
+            RegOps16<NH> oa, ob;
+            RegPass pa, pb;
+            open_vb(wave, pa);
+            issue16(pa, oa);
+            while (true) {
+                pb = advance(pa);
+                issue16(pb, ob);
+                multiply16(oa);
+                if (!pb.valid) break;
+                pa = advance(pb);
+                issue16(pa, oa);
+                multiply16(ob);
+                if (!pa.valid) break;
+            }
+            continue;                                              // (the next segment)
+        }
         RegOps<NH> oa, ob;
         RegPass pa, pb;
         open_vb(wave, pa);
@@ -680,6 +741,14 @@ template <bool TWO, int NW, int NH, int VF>
 __global__ __launch_bounds__(NW * 64) void spmm_reg_kernel(const DevMat m, const XSrc X, float *__restrict__ Y,
                                                            const int64_t ldy, const uint32_t batch) {
     spmm_reg_body<TWO, NW, NH, VF>(m, X, Y, ldy, batch, blockIdx.x, blockIdx.y);
+}
+
+// 16-bit kernel values times 16-bit right-hand sides (X.p0: the rows of X, X.sj0: elements per row).
+template <int NW, int NH, int VF>
+__global__ __launch_bounds__(NW * 64) void spmm_reg16_kernel(const DevMat m, const XSrc X, float *__restrict__ Y,
+                                                             const int64_t ldy, const uint32_t batch) {
+    static_assert(VF == CSB_VAL_F16 || VF == CSB_VAL_BF16, "16-bit formats only");
+    spmm_reg_body<false, NW, NH, VF, true>(m, X, Y, ldy, batch, blockIdx.x, blockIdx.y);
 }
 
 // Several independent products in one launch (blockIdx.z picks the product): the per-step
@@ -874,12 +943,29 @@ static int spmm_16bit(const char *who, int fmt, const csb_matrix *m, const uint1
         return CSB_EUNSUPPORTED;
     }
     const int nw = fits16 ? 16 : 8;
-    const size_t lds = (size_t)h.seg_meta + (size_t)nw * acc_per_wave;
     DevMat dm = dev_mat(m);
     uint32_t b = (uint32_t)batch, ld = (uint32_t)ldx;
     int64_t ldy_ = ldy;
-    void *args[] = {&dm, &d_X, &ld, &d_Y, &ldy_, &b};
     const bool half = fmt == CSB_VAL_F16;
+    // row tiles of 16 or 32 rows: the kernel that keeps its results in registers
+    const size_t lds_reg = (size_t)h.seg_meta + (size_t)nw * acc_per_wave + (size_t)nw * 64;
+    if ((h.br == 16 || h.br == 32) && h.n_vals * 4 < 0x7fffff00ull && lds_reg <= (size_t)160 * 1024) {
+        XSrc X{(const float *)d_X, (uint32_t)h.cols, ld, 1u, (const float *)d_X, ld, 1u};
+        void *rargs[] = {&dm, &X, &d_Y, &ldy_, &b};
+        const void *kern;
+#define CSB_R16(NW, NH) (half ? (const void *)spmm_reg16_kernel<NW, NH, CSB_VAL_F16> : (const void *)spmm_reg16_kernel<NW, NH, CSB_VAL_BF16>)
+        if (nw == 16) kern = h.br == 16 ? CSB_R16(16, 1) : CSB_R16(16, 2);
+        else kern = h.br == 16 ? CSB_R16(8, 1) : CSB_R16(8, 2);
+#undef CSB_R16
+        hipError_t e = ensure_dynamic_lds(kern, lds_reg);
+        if (e == hipSuccess)
+            e = hipLaunchKernel(kern, dim3((unsigned)(h.n_nz_tiles + h.n_zero_tiles), (unsigned)((batch + 63) / 64)), dim3(nw * 64), rargs, lds_reg,
+                                (hipStream_t)stream);
+        if (e != hipSuccess) { set_error(w + ": " + hipGetErrorString(e)); return CSB_EDEVICE; }
+        return CSB_OK;
+    }
+    const size_t lds = (size_t)h.seg_meta + (size_t)nw * acc_per_wave;
+    void *args[] = {&dm, &d_X, &ld, &d_Y, &ldy_, &b};
     const void *kern = nw == 16 ? (half ? (const void *)spmm_bf16_kernel<16, true> : (const void *)spmm_bf16_kernel<16, false>)
                                 : (half ? (const void *)spmm_bf16_kernel<8, true> : (const void *)spmm_bf16_kernel<8, false>);
     hipError_t e = ensure_dynamic_lds(kern, lds);
