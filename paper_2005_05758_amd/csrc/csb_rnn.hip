@@ -921,6 +921,23 @@ __global__ void state_out_kernel(float *__restrict__ dst, const float *__restric
     }
 }
 
+// dst[l][k][b] = src[l][b][k] through a 32 x 32 tile in LDS, so that both sides move whole
+// rows of 128 bytes: block (32, 8), grid (ceil(K / 32), ceil(B / 32), L).
+__global__ __launch_bounds__(256) void frames_in_kernel(float *__restrict__ dst, const float *__restrict__ src, int B, int K) {
+    __shared__ float tile[32][33];
+    const size_t plane = (size_t)blockIdx.z * B * K;
+    const int k0 = blockIdx.x * 32, b0 = blockIdx.y * 32;
+    for (int i = threadIdx.y; i < 32; i += 8) {
+        const int b = b0 + i, k = k0 + threadIdx.x;
+        if (b < B && k < K) tile[i][threadIdx.x] = src[plane + (size_t)b * K + k];
+    }
+    __syncthreads();
+    for (int i = threadIdx.y; i < 32; i += 8) {
+        const int k = k0 + i, b = b0 + threadIdx.x;
+        if (b < B && k < K) dst[plane + (size_t)k * B + b] = tile[threadIdx.x][i];
+    }
+}
+
 __global__ void fill_kernel(float *p, size_t n, float v) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -943,6 +960,8 @@ static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 struct RnnWs {
     size_t off_a, off_a2, off_c, off_part, off_biasptr, off_seq, off_hint, off_cint, off_m, off_fa, off_fs, rows_out, part_stride, total;
+    size_t off_xt;                     // batched: the input frames of `xt_steps` steps as [input][batch]
+    int32_t xt_steps;
 };
 
 // XCDs one instance of the resident kernel occupies, and how many instances fit side by side
@@ -992,6 +1011,11 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
     if (batch > 1) {
         w.off_hint = off; off = align256(off + (size_t)r->n_layers * batch * HS * sizeof(float));
         w.off_cint = off; off = align256(off + (size_t)r->n_layers * batch * r->hidden * sizeof(float));
+        // the caller's frames are [batch][input]; the products read right-hand sides with the
+        // batch index contiguous, so the frames are turned over a few steps at a time (8 MB)
+        const size_t frame = (size_t)batch * r->input * sizeof(float);
+        w.xt_steps = (int32_t)std::max<size_t>(1, std::min<size_t>({(size_t)std::max(T, 1), (size_t)1024, ((size_t)8 << 20) / std::max<size_t>(frame, 1)}));
+        w.off_xt = off; off = align256(off + (size_t)w.xt_steps * frame);
     }
     w.off_m = off; off = align256(off + ((r->proj > 0 || two_products) ? (size_t)batch * r->hidden * sizeof(float) * per_layer : 0));
     // streaming at batch 1: per layer two buffers of gate sums (plus the second product's sums of
@@ -1431,6 +1455,7 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         // lives as [H][B] so that the batch index is the contiguous one
         float *hi = (float *)((uint8_t *)d_ws + wl.off_hint), *ci = (float *)((uint8_t *)d_ws + wl.off_cint);
         float *mb = (float *)((uint8_t *)d_ws + wl.off_m);
+        float *xt = (float *)((uint8_t *)d_ws + wl.off_xt);
         const int sblocks = (int)std::min<size_t>((std::max(nstate, ncstate) + 255) / 256, 2048);
         hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, hi, d_h0, L, batch, HS);
         if (lstm) hipLaunchKernelGGL(state_in_kernel, dim3(sblocks), dim3(256), 0, st, ci, d_c0, L, batch, H);
@@ -1472,13 +1497,18 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
                 });
             };
             // first (or only) product: W_l [input ; state]
+            if (d < T && d % wl.xt_steps == 0) {                // the first layer is at step d: its next frames
+                const int steps = std::min(wl.xt_steps, T - d);
+                hipLaunchKernelGGL(frames_in_kernel, dim3((I + 31) / 32, (batch + 31) / 32, steps), dim3(32, 8), 0, st, xt,
+                                   d_x + (size_t)d * batch * I, batch, I);
+            }
             int rc = for_groups([&](int l0, int n) {
                 SpmmCall calls[kMaxJobsPerLaunch];
                 for (int i = 0; i < n; ++i) {
                     const int l = l0 + i, t = d - l;
                     float *hl = hi + (size_t)l * HS * batch;
                     if (l == 0)
-                        calls[i] = SpmmCall{r->W[l], d_x + (size_t)t * batch * I, (uint32_t)I, 1, I, hl, batch, 1,
+                        calls[i] = SpmmCall{r->W[l], xt + (size_t)(t % wl.xt_steps) * batch * I, (uint32_t)I, batch, 1, hl, batch, 1,
                                             a + (size_t)l * a_stride, batch};
                     else
                         calls[i] = SpmmCall{r->W[l], hi + (size_t)(l - 1) * HS * batch, (uint32_t)HS, batch, 1, hl, batch, 1,
