@@ -404,8 +404,8 @@ def rnn_configs_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, stream_read, headl
                                 "us_warm": round(us_warm, 2), "us_cold": round(us_cold, 2),
                                 "gbps_cold": round(ab / us_cold / 1e3, 1)}
         res[name] = entry
-    res["note"] = ("at these sizes a mat-vec launch is a fixed chain of dependent phases (about 6.5 us of kernel time "
-                   "whatever the matrix holds): the resident kernel exists because of that")
+    res["note"] = ("at these sizes a mat-vec launch is a fixed chain of dependent phases (about 3 us warm and 6.4 us "
+                   "cold whatever the matrix holds; an empty launch takes 2.6): the resident kernel exists because of that")
     return res
 
 

@@ -69,6 +69,74 @@ __global__ __launch_bounds__(256) void row_segment_keys_kernel(const float *__re
     }
 }
 
+// The same for BC = 4 Q columns per segment (Q = 4, 8, 16), C a multiple of BC and rows that
+// start at multiples of 16 bytes.  A workgroup takes kRowKeyRows rows x 256 segments, a row at a
+// time: 16-byte loads, all of a row's in flight at once (and the next row's while this one is
+// added up, and the one after that); the row goes through LDS with the 16-byte words of segment s rotated by s, so
+// that the threads of the second phase -- thread s owns segment s, as above, and adds from
+// left to right -- read theirs without bank conflicts.  A thread's kRowKeyRows keys are
+// neighbours in keys[]: they leave as 32-byte words.
+constexpr int kRowKeyRows = 8;
+typedef float vec4f __attribute__((ext_vector_type(4)));
+template <int Q>
+__global__ __launch_bounds__(256) void row_segment_keys_vec_kernel(const float *__restrict__ W, const int64_t ld,
+                                                                     const uint32_t R, const uint32_t NBC,
+                                                                     uint32_t *__restrict__ keys) {
+    extern __shared__ vec4f tile4[];                // [256 segments][Q]
+    const uint32_t tid = threadIdx.x;
+    const uint32_t bj0 = blockIdx.x * 256u, i0 = blockIdx.y * kRowKeyRows;
+    const uint32_t nseg = min(256u, NBC - bj0), nf = nseg * Q;
+    const uint32_t nrows = min((uint32_t)kRowKeyRows, R - i0);
+    const vec4f zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    const float *const row0 = W + (size_t)i0 * ld + (size_t)bj0 * 4u * Q;
+    vec4f v[2][Q];                                   // two rows ahead of the one being added up
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int u = 0; u < Q; ++u) {
+            const uint32_t f = tid + 256u * u;
+            v[a][u] = (uint32_t)a < nrows && f < nf ? ((const vec4f *)(row0 + (size_t)a * ld))[f] : zero4;
+        }
+    uint32_t mine[kRowKeyRows];
+#pragma unroll
+    for (int r = 0; r < kRowKeyRows; ++r) {
+        mine[r] = 0u;
+        if ((uint32_t)r >= nrows) continue;          // uniform
+        if (r > 0) __syncthreads();                  // the previous row has been read
+#pragma unroll
+        for (int u = 0; u < Q; ++u) {
+            const uint32_t f = tid + 256u * u, sg = f / Q, m = f % Q;
+            tile4[sg * Q + ((m + sg) % Q)] = v[r & 1][u];
+        }
+        if ((uint32_t)r + 2 < nrows) {
+            const vec4f *p = (const vec4f *)(row0 + (size_t)(r + 2) * ld);
+#pragma unroll
+            for (int u = 0; u < Q; ++u) {
+                const uint32_t f = tid + 256u * u;
+                v[r & 1][u] = f < nf ? p[f] : zero4;
+            }
+        }
+        __syncthreads();
+        float acc = 0.0f;
+#pragma unroll
+        for (int m = 0; m < Q; ++m) {
+            const vec4f q = tile4[tid * Q + ((m + tid) % Q)];
+            acc = fmaf(q.x, q.x, acc); acc = fmaf(q.y, q.y, acc); acc = fmaf(q.z, q.z, acc); acc = fmaf(q.w, q.w, acc);
+        }
+        mine[r] = rank_key(acc);
+    }
+    if (tid >= nseg) return;
+    uint32_t *out = keys + (size_t)(bj0 + tid) * R + i0;
+    if (nrows == kRowKeyRows && (R & 3u) == 0) {
+#pragma unroll
+        for (int r = 0; r < kRowKeyRows; r += 4) *(uint4 *)(out + r) = make_uint4(mine[r], mine[r + 1], mine[r + 2], mine[r + 3]);
+    } else {
+#pragma unroll
+        for (int r = 0; r < kRowKeyRows; ++r)
+            if ((uint32_t)r < nrows) out[r] = mine[r];
+    }
+}
+
 // keys[bi * C + c] for column segment (bi, c) of the row-pruned matrix: thread per segment,
 // c fastest (every row of the segment is read coalesced).
 __global__ __launch_bounds__(256) void col_segment_keys_kernel(const float *__restrict__ W, const int64_t ld,
@@ -87,17 +155,46 @@ __global__ __launch_bounds__(256) void col_segment_keys_kernel(const float *__re
     keys[(size_t)bi * C + c] = rank_key(s);
 }
 
+// The same for R and BR multiples of 8: the keep flags of eight rows come as one 8-byte word
+// (the same word for all the lanes of a block-column), then the eight loads of the rows that
+// survive are in flight together.  Row segments that were pruned are not read at all.
+__global__ __launch_bounds__(256) void col_segment_keys_vec_kernel(const float *__restrict__ W, const int64_t ld,
+                                                                     const uint32_t R, const uint32_t C, const uint32_t BR,
+                                                                     const uint32_t BC, const uint8_t *__restrict__ keep_r,
+                                                                     uint32_t *__restrict__ keys) {
+    const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x, bi = blockIdx.y;
+    if (c >= C) return;
+    const uint32_t r0 = bi * BR, r1 = min(R, r0 + BR);
+    const uint8_t *kr = keep_r + (size_t)(c / BC) * R;
+    float s = 0.0f;
+    for (uint32_t i = r0; i < r1; i += 8) {
+        const uint2 f = *(const uint2 *)(kr + i);
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t byte = ((q < 4 ? f.x : f.y) >> (8 * (q & 3))) & 0xffu;
+            v[q] = byte ? W[(size_t)(i + q) * ld + c] : 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s = fmaf(v[q], v[q], s);
+    }
+    keys[(size_t)bi * C + c] = rank_key(s);
+}
+
 // One workgroup ranks the n <= 16384 segments of one block-column (block-row) and marks the k
 // weakest as pruned, "weaker" being the order of (key, position).  No sort: every thread keeps
-// 16 consecutive keys in registers; the key T of the k-th weakest is found bit by bit from the
-// top (per bit: how many of the still possible keys have a 0 there -- wavefront counts by
-// ballot, workgroup count through LDS); then a segment is pruned if its key is below T, or
-// equal to T and fewer than (k - #below) equal keys lie at earlier positions.
+// 16 consecutive keys in registers; the key T of the k-th weakest is found eight bits at a time
+// from the highest bit on which the keys differ at all (a histogram of the digit over the keys
+// that still match, by LDS atomics -- sums of squares of one block-column agree on their top
+// exponent bits, and counting those would put every key into one bin -- then the digit whose
+// bin holds the k-th); then a segment is pruned if its key is below T, or equal to T and fewer
+// than (k - #below) equal keys lie at earlier positions.
 constexpr int kSelPer = 16;          // keys per thread
 __global__ __launch_bounds__(1024) void select_kernel(const uint32_t *__restrict__ keys, uint8_t *__restrict__ keep,
                                                        const uint32_t n, const uint32_t k) {
     __shared__ uint32_t wsum[3][16];
-    __shared__ uint32_t cand[1024];              // the keys still possible once they are few (first: scratch)
+    __shared__ uint32_t hist[4][256];            // one histogram per digit
+    __shared__ uint32_t pick[2];                 // the digit that holds the k-th, and k inside its bin
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const size_t base = (size_t)blockIdx.x * n;
     const uint32_t i0 = tid * kSelPer;
@@ -127,15 +224,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const uint32_t *__restrict
 #pragma unroll
         for (int q = 0; q < kSelPer; ++q) key[q] = valid[q] ? keys[base + i0 + q] : 0u;
     }
-    // workgroup sum of a per-wavefront count (uniform in the wavefront)
-    auto wg_sum = [&](uint32_t wave_count, int buf) {
-        if (lane == 0) wsum[buf][wave] = wave_count;
-        __syncthreads();
-        uint32_t s = 0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) s += wsum[buf][w];
-        return s;
-    };
+    ((uint32_t *)hist)[tid] = 0u;                // 4 x 256 words, 1024 threads
     // bits on which every key agrees need no counting
     uint32_t all_and = 0xffffffffu, all_or = 0u;
 #pragma unroll
@@ -145,53 +234,41 @@ __global__ __launch_bounds__(1024) void select_kernel(const uint32_t *__restrict
         all_and &= (uint32_t)__shfl_xor((int)all_and, d, 64);
         all_or |= (uint32_t)__shfl_xor((int)all_or, d, 64);
     }
-    if (lane == 0) { cand[wave] = all_and; cand[16 + wave] = all_or; }
+    if (lane == 0) { wsum[1][wave] = all_and; wsum[2][wave] = all_or; }
     __syncthreads();
-    for (int w = 0; w < 16; ++w) { all_and &= cand[w]; all_or |= cand[16 + w]; }
-    __syncthreads();                             // cand is reused below
+    for (int w = 0; w < 16; ++w) { all_and &= wsum[1][w]; all_or |= wsum[2][w]; }
     const uint32_t varying = all_and ^ all_or;
-    uint32_t prefix = 0, mask = 0, kk = k;       // the kk-th weakest of the keys that match prefix on mask
-    uint32_t act = n;                            // keys still matching
-    bool compact = false;                        // the matching keys have been gathered, one per thread
-    uint32_t ckey = 0, ncand = 0;
-    int par = 0;
-    for (int b = 31; b >= 0; --b) {
-        const uint32_t bit = 1u << b;
-        if (!(varying & bit)) { prefix |= all_and & bit; mask |= bit; continue; }
-        if (!compact && act <= 1024u) {
-            // gather the matching keys into LDS, one per thread from here on (16 times fewer
-            // ballots per bit); their order does not matter for counting
-            uint32_t mine = 0;
+    const int top = varying ? 31 - __builtin_clz(varying) : -1;      // the highest bit on which keys differ
+    // the kk-th weakest of the keys that match prefix on mask
+    uint32_t mask = top < 0 ? 0xffffffffu : ~((2u << top) - 1u), prefix = all_and & mask, kk = k;
+    int round = 0;
+    for (int hi = top; hi >= 0; hi -= 8, ++round) {
+        const int lo = hi >= 7 ? hi - 7 : 0;
+        const uint32_t dmask = (2u << (hi - lo)) - 1u;
 #pragma unroll
-            for (int q = 0; q < kSelPer; ++q) mine += (valid[q] && (key[q] & mask) == prefix) ? 1u : 0u;
-            uint32_t incl = mine;                // inclusive scan over the wavefront's lanes
+        for (int q = 0; q < kSelPer; ++q)
+            if (valid[q] && (key[q] & mask) == prefix) atomicAdd(&hist[round][(key[q] >> lo) & dmask], 1u);
+        __syncthreads();
+        uint32_t h = 0, incl = 0;
+        if (tid < 256) {                         // inclusive scan of the 256 bins
+            h = hist[round][tid];
+            incl = h;
             for (int d = 1; d < 64; d <<= 1) {
                 const uint32_t up = (uint32_t)__shfl_up((int)incl, d, 64);
                 if (lane >= (uint32_t)d) incl += up;
             }
             if (lane == 63) wsum[0][wave] = incl;
-            __syncthreads();
-            uint32_t slot = incl - mine;
-            for (uint32_t w = 0; w < wave; ++w) slot += wsum[0][w];
-#pragma unroll
-            for (int q = 0; q < kSelPer; ++q)
-                if (valid[q] && (key[q] & mask) == prefix) cand[slot++] = key[q];
-            __syncthreads();
-            ncand = act;
-            ckey = tid < ncand ? cand[tid] : 0u;
-            compact = true;
         }
-        uint32_t c0 = 0;
-        if (compact) {
-            c0 = (uint32_t)__popcll(__ballot(tid < ncand && !(ckey & bit) && (ckey & mask) == prefix));
-        } else {
-#pragma unroll
-            for (int q = 0; q < kSelPer; ++q)
-                c0 += (uint32_t)__popcll(__ballot(valid[q] && (key[q] & mask) == prefix && !(key[q] & bit)));
+        __syncthreads();
+        if (tid < 256) {
+            for (uint32_t w = 0; w < wave; ++w) incl += wsum[0][w];
+            const uint32_t excl = incl - h;
+            if (excl < kk && kk <= incl) { pick[0] = tid; pick[1] = kk - excl; }
         }
-        const uint32_t zeros = wg_sum(c0, 1 + (par ^= 1));   // two buffers in turn: one barrier per counted bit
-        if (kk > zeros) { prefix |= bit; kk -= zeros; act -= zeros; } else act = zeros;
-        mask |= bit;
+        __syncthreads();                         // (pick and wsum[0] are next written behind two more barriers)
+        prefix |= pick[0] << lo;
+        mask |= dmask << lo;
+        kk = pick[1];
     }
     // prefix is T; kk of the keys equal to T are pruned: the first ones by position
     uint32_t eq_wave = 0, eq_lower = 0;          // equal keys in the wavefront / in its lower lanes
@@ -201,7 +278,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const uint32_t *__restrict
         eq_wave += (uint32_t)__popcll(m);
         eq_lower += __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
     }
-    __syncthreads();                             // the last wg_sum's readers are done with wsum[0]
+    __syncthreads();                             // (wsum[0] is free: the scans' readers are behind their rounds' last barrier)
     if (lane == 0) wsum[0][wave] = eq_wave;
     __syncthreads();
     uint32_t rank = eq_lower;
@@ -244,6 +321,38 @@ __global__ __launch_bounds__(256) void masked_copy_kernel(const float *W, const 
             const bool on = keep_r[(size_t)(cc / BC) * R + i] && kc[cc];
             Z[(size_t)i * ldz + cc] = on ? W[(size_t)i * ld + cc] : 0.0f;
         }
+    }
+}
+
+// The same for 16-byte aligned rows, C a multiple of 4 that BC divides into whole words (BC a
+// multiple of 4), R and BR multiples of 8: a thread takes four columns of eight rows.  Its
+// eight row flags are one 8-byte word, its four column flags one word; what does not survive
+// is not read.
+__global__ __launch_bounds__(256) void masked_copy_vec_kernel(const float *W, const int64_t ld, float *Z, const int64_t ldz,
+                                                                const uint32_t R, const uint32_t C, const uint32_t BR,
+                                                                const uint32_t BC, const uint8_t *__restrict__ keep_r,
+                                                                const uint8_t *__restrict__ keep_c) {
+    const uint32_t c = (blockIdx.x * 256u + threadIdx.x) * 4u;
+    const uint32_t i0 = blockIdx.y * 8u;
+    if (c >= C) return;
+    const uint2 fr = *(const uint2 *)(keep_r + (size_t)(c / BC) * R + i0);
+    const uint32_t kc4 = *(const uint32_t *)(keep_c + (size_t)(i0 / BR) * C + c);
+    float4 w[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const uint32_t byte = ((q < 4 ? fr.x : fr.y) >> (8 * (q & 3))) & 0xffu;
+        w[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (byte && kc4) w[q] = *(const float4 *)(W + (size_t)(i0 + q) * ld + c);
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const uint32_t byte = ((q < 4 ? fr.x : fr.y) >> (8 * (q & 3))) & 0xffu;
+        float4 z;
+        z.x = byte && (kc4 & 0xffu) ? w[q].x : 0.0f;
+        z.y = byte && (kc4 & 0xff00u) ? w[q].y : 0.0f;
+        z.z = byte && (kc4 & 0xff0000u) ? w[q].z : 0.0f;
+        z.w = byte && (kc4 & 0xff000000u) ? w[q].w : 0.0f;
+        *(float4 *)(Z + (size_t)(i0 + q) * ldz + c) = z;
     }
 }
 
@@ -310,21 +419,39 @@ extern "C" int csb_project(const float *d_W, int64_t rows, int64_t cols, int64_t
         const uint32_t TR = std::max(1u, std::min({256u / TS, 12288u / (TS * BCp), R}));
         const size_t lds_rows = (size_t)TR * TS * BCp * sizeof(float);
         const dim3 grid_r((NBC + TS - 1) / TS, (R + TR - 1) / TR);
+        // 16-byte accesses need 16-byte aligned rows on both sides (and flag words at multiples of 4)
+        const bool vec4 = C % 4 == 0 && ld % 4 == 0 && ldz % 4 == 0 && (uintptr_t)d_W % 16 == 0 && (uintptr_t)d_Z % 16 == 0;
+        const bool rows8 = R % 8 == 0 && BR % 8 == 0;
         int shift = -1;
         for (int b = 0; b < 9; ++b) if (BC == (1u << b)) shift = b;
-        switch (shift) {
-            case 4: hipLaunchKernelGGL(row_segment_keys_kernel<4>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
-            case 5: hipLaunchKernelGGL(row_segment_keys_kernel<5>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
-            case 6: hipLaunchKernelGGL(row_segment_keys_kernel<6>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
-            default: hipLaunchKernelGGL(row_segment_keys_kernel<-1>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
+        if (vec4 && C % BC == 0 && shift >= 4 && shift <= 6) {
+            const dim3 grid_v((NBC + 255) / 256, (R + kRowKeyRows - 1) / kRowKeyRows);
+            const size_t lds_v = (size_t)256 * BC * sizeof(float);
+            switch (shift) {
+                case 4: hipLaunchKernelGGL(row_segment_keys_vec_kernel<4>, grid_v, dim3(256), lds_v, st, d_W, ld, R, NBC, keys_r); break;
+                case 5: hipLaunchKernelGGL(row_segment_keys_vec_kernel<8>, grid_v, dim3(256), lds_v, st, d_W, ld, R, NBC, keys_r); break;
+                default: hipLaunchKernelGGL(row_segment_keys_vec_kernel<16>, grid_v, dim3(256), lds_v, st, d_W, ld, R, NBC, keys_r); break;
+            }
+        } else {
+            switch (shift) {
+                case 4: hipLaunchKernelGGL(row_segment_keys_kernel<4>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
+                case 5: hipLaunchKernelGGL(row_segment_keys_kernel<5>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
+                case 6: hipLaunchKernelGGL(row_segment_keys_kernel<6>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
+                default: hipLaunchKernelGGL(row_segment_keys_kernel<-1>, grid_r, dim3(256), lds_rows, st, d_W, ld, R, C, BC, NBC, TR, TS, keys_r); break;
+            }
         }
         hipLaunchKernelGGL(select_kernel, dim3(NBC), dim3(1024), 0, st, keys_r, keep_r, R, prune_count(rows, rate));
-        hipLaunchKernelGGL(col_segment_keys_kernel, dim3((C + 255) / 256, NBR), dim3(256), 0, st, d_W, ld, R, C, BR, BC, keep_r, keys_c);
+        if (rows8)
+            hipLaunchKernelGGL(col_segment_keys_vec_kernel, dim3((C + 255) / 256, NBR), dim3(256), 0, st, d_W, ld, R, C, BR, BC, keep_r, keys_c);
+        else
+            hipLaunchKernelGGL(col_segment_keys_kernel, dim3((C + 255) / 256, NBR), dim3(256), 0, st, d_W, ld, R, C, BR, BC, keep_r, keys_c);
         hipLaunchKernelGGL(select_kernel, dim3(NBR), dim3(1024), 0, st, keys_c, keep_c, C, prune_count(cols, rate));
-        // float4 accesses need 16-byte aligned rows on both sides (and flag words at multiples of 4)
-        const bool vec4 = C % 4 == 0 && ld % 4 == 0 && ldz % 4 == 0 && (uintptr_t)d_W % 16 == 0 && (uintptr_t)d_Z % 16 == 0;
-        hipLaunchKernelGGL(masked_copy_kernel, dim3((C + 255) / 256, (R + kMaskedCopyRows - 1) / kMaskedCopyRows), dim3(256), 0, st,
-                           d_W, ld, d_Z, ldz, R, C, BR, BC, keep_r, keep_c, vec4);
+        if (vec4 && rows8 && BC % 4 == 0)
+            hipLaunchKernelGGL(masked_copy_vec_kernel, dim3((C + 1023) / 1024, R / 8), dim3(256), 0, st,
+                               d_W, ld, d_Z, ldz, R, C, BR, BC, keep_r, keep_c);
+        else
+            hipLaunchKernelGGL(masked_copy_kernel, dim3((C + 255) / 256, (R + kMaskedCopyRows - 1) / kMaskedCopyRows), dim3(256), 0, st,
+                               d_W, ld, d_Z, ldz, R, C, BR, BC, keep_r, keep_c, vec4);
         e = hipGetLastError();
     }
     if (e != hipSuccess) { set_error(std::string("csb_project: ") + hipGetErrorString(e)); return CSB_EDEVICE; }

@@ -40,7 +40,11 @@ def check_project(W, br, bc, rate, tag="", f64_too=False):
 @pytest.mark.parametrize("R,C,br,bc,rate", [
     (4, 6, 2, 3, 4.0), (37, 53, 8, 8, 3.0), (200, 150, 16, 16, 6.0), (130, 257, 32, 32, 10.0),
     (96, 96, 32, 16, 1.0), (70, 300, 16, 64, 16.0), (300, 40, 128, 8, 2.0), (513, 100, 256, 256, 12.0),
-    (1, 1, 1, 1, 4.0), (1025, 3, 64, 2, 25.0)])
+    (1, 1, 1, 1, 4.0), (1025, 3, 64, 2, 25.0),
+    # the 16-byte forms of the kernels: whole blocks of 16 / 32 / 64 columns, with a ragged last
+    # group of rows, more than 256 blocks in a row, and row counts that are no multiple of 8
+    (100, 128, 16, 32, 5.0), (72, 320, 8, 64, 9.0), (40, 9600, 8, 32, 12.0), (24, 4800, 8, 16, 7.0),
+    (264, 544, 24, 32, 10.0)])
 def test_project_small_shapes(R, C, br, bc, rate):
     rng = np.random.default_rng(R * 7 + C)
     check_project(rng.normal(0, 0.05, (R, C)).astype(np.float32), br, bc, rate, tag="gauss", f64_too=True)
