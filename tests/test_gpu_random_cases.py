@@ -166,7 +166,11 @@ def test_random_projections():
         br, bc = int(rng.choice(BLOCKS)), int(rng.choice(BLOCKS))
         rate = float(rng.choice([1.0, 1.3, 2.0, 4.0, 10.0, 16.0, 100.0, 1e6]))
         style = str(rng.choice(["normal", "ties", "sparse", "strided"]))
-        say(f"[random projections] case {tr}: {rows}x{cols} block {br}x{bc} rate {rate} {style}")
+        whole = rng.random() < 0.4                        # whole blocks, rows in eights: the 16-byte forms of the kernels
+        if whole:
+            cols, rows = max(bc, cols // bc * bc), max(8, rows // 8 * 8)
+        pad = 8 if whole and rng.random() < 0.5 else 5    # (a row stride that keeps, or breaks, the alignment)
+        say(f"[random projections] case {tr}: {rows}x{cols} block {br}x{bc} rate {rate} {style} pad {pad}")
         W = rng.normal(size=(rows, cols)).astype(np.float32)
         if style == "ties":
             W = np.round(W).astype(np.float32)            # many equal segment sums
@@ -174,7 +178,7 @@ def test_random_projections():
             W[rng.random(W.shape) < 0.8] = 0.0
         ref = oracle.csb_project(W, br, bc, rate).astype(np.float32)
         if style == "strided":
-            buf = torch.zeros((rows, cols + 5), dtype=torch.float32, device="cuda")
+            buf = torch.zeros((rows, cols + pad), dtype=torch.float32, device="cuda")
             buf[:, :cols] = torch.from_numpy(W).cuda()
             got = project(buf[:, :cols], br, bc, rate)
         else:
