@@ -213,7 +213,8 @@ int csb_upload(csb_matrix *m, void *d_buf, size_t bytes, void *stream);
 
 /* Bytes of scratch csb_spmv / csb_spmm need for `batch` right-hand sides (partial sums of
  * row tiles that several workgroups share).  Contents need no initialisation.
- * Workspaces in general (this one, csb_rnn_forward's, csb_project's): a buffer may be handed to
+ * Workspaces in general (this one, csb_rnn_forward's, csb_project's): 256-byte aligned (else
+ * CSB_EINVAL); a buffer may be handed to
  * different handles and entry points in turn, never to two calls that overlap in time.  The
  * library identifies a workspace by its base address and clears the words that workgroups
  * exchange through it whenever another handle or entry point has used the buffer in between;

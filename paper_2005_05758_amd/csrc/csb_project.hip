@@ -395,6 +395,7 @@ extern "C" int csb_project(const float *d_W, int64_t rows, int64_t cols, int64_t
                            double rate, float *d_Z, int64_t ldz, void *d_ws, void *stream) {
     using namespace csb;
     if (!d_W || !d_Z || !d_ws) { set_error("csb_project: NULL pointer"); return CSB_EINVAL; }
+    if ((uintptr_t)d_ws % 256) { set_error("csb_project: workspace not 256-byte aligned"); return CSB_EINVAL; }
     if (rows <= 0 || cols <= 0 || ld < cols || ldz < cols) { set_error("csb_project: bad shape or leading dimension"); return CSB_EINVAL; }
     if (br < 1 || br > CSB_MAX_BLOCK || bc < 1 || bc > CSB_MAX_BLOCK) { set_error("csb_project: block size outside [1, 256]"); return CSB_EINVAL; }
     if (!(rate >= 1.0) || !std::isfinite(rate)) { set_error("csb_project: pruning rate must be a finite number >= 1"); return CSB_EINVAL; }

@@ -1388,6 +1388,7 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
                                void *d_ws, void *stream) {
     using namespace csb;
     if (!r || !d_hT || !d_ws) { set_error("csb_rnn_forward: NULL pointer"); return CSB_EINVAL; }
+    if ((uintptr_t)d_ws % 256) { set_error("csb_rnn_forward: workspace not 256-byte aligned"); return CSB_EINVAL; }
     if (batch <= 0 || T < 0) { set_error("csb_rnn_forward: batch <= 0 or T < 0"); return CSB_EINVAL; }
     if (T > 0 && !d_x) { set_error("csb_rnn_forward: NULL input sequence"); return CSB_EINVAL; }
     hipStream_t st = (hipStream_t)stream;

@@ -521,6 +521,7 @@ int spmv_segments(const csb_matrix *m, const float *d_x0, uint32_t n0, const flo
     if (!m->plan.valid || !m->uploaded || !m->d_buf) { set_error("csb_spmv: matrix not planned and uploaded"); return CSB_ESTATE; }
     if (m->plan.hdr.cols > (uint64_t)kMaxStageCols) { set_error("csb_spmv: more columns than the LDS staging covers"); return CSB_EUNSUPPORTED; }
     if (m->plan.hdr.n_partial_slots && !d_ws) { set_error("csb_spmv: workspace is NULL"); return CSB_EINVAL; }
+    if ((uintptr_t)d_ws % 256) { set_error("csb_spmv: workspace not 256-byte aligned"); return CSB_EINVAL; }
     hipError_t e = launch_spmv<false>(m, SpmvSrc<false>{d_x0}, n0, SpmvSrc<false>{d_x1}, d_y, (unsigned long long *)d_ws,
                                       (hipStream_t)stream, d_stamps);
     if (e != hipSuccess) { set_error(std::string("csb_spmv: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
@@ -537,6 +538,7 @@ int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSr
     }
     if (m->plan.stream.valid) return spmv_rows_gated(m, s0, n0, s1, d_y, stream);      // row-owned layout: no workspace
     if (m->plan.hdr.n_partial_slots && !d_ws) { set_error("csb_spmv: workspace is NULL"); return CSB_EINVAL; }
+    if ((uintptr_t)d_ws % 256) { set_error("csb_spmv: workspace not 256-byte aligned"); return CSB_EINVAL; }
     SpmvSrc<true> g0, g1;
     static_cast<GateSrc &>(g0) = s0;
     static_cast<GateSrc &>(g1) = s1;

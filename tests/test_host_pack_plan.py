@@ -128,6 +128,14 @@ def test_error_returns():
     assert L.csb_rnn_forward(r, 256, None, None, None, 256, None, -1, 1, 256, None) == -1
     assert L.csb_rnn_forward(r, 256, None, None, None, 256, None, 1, 0, 256, None) == -1
     assert L.csb_rnn_forward(r, 256, None, None, None, 256, None, 1, 1, 256, None) == -5   # not uploaded
+    assert L.csb_rnn_forward(r, 256, None, None, None, 256, None, 1, 1, 264, None) == -1   # misaligned workspace
+    assert b"aligned" in L.csb_last_error()
+    # the projection checks its arguments before anything touches a device
+    assert L.csb_project(256, 8, 8, 8, 2, 2, C.c_double(4.0), 256, 8, 264, None) == -1
+    assert b"aligned" in L.csb_last_error()
+    assert L.csb_project(256, 8, 8, 4, 2, 2, C.c_double(4.0), 256, 8, 256, None) == -1     # ld below cols
+    assert L.csb_project(256, 8, 8, 8, 2, 2, C.c_double(0.5), 256, 8, 256, None) == -1     # rate below 1
+    assert L.csb_project(256, 20000, 8, 8, 2, 2, C.c_double(4.0), 256, 8, 256, None) == -4 # more rows than one workgroup ranks
     L.csb_rnn_free(r)
     L.csb_free(h)
     L.csb_free(None)
