@@ -93,7 +93,10 @@ typedef struct {
     double chunk_max_over_mean;   /* largest / mean work per workgroup                   */
     int32_t whole_tiles;     /* 1: every workgroup owns whole output row tiles (no merge) */
     int32_t row_owned;       /* 1: csb_spmv runs the row-owned layout (below); the figures above
-                                then describe that layout                                */
+                                then describe that layout.  2: the same layout with every
+                                workgroup owning whole units of a recurrent cell (all their
+                                gate rows), which csb_rnn_create gives the matrices of stacked
+                                layers: the streaming step reads it, csb_spmv the tile sections */
     int32_t rounds;          /* row-owned layout: rounds per workgroup                   */
     int32_t reserved;
     int64_t matvec_bytes;    /* bytes of the device image one csb_spmv launch reads      */
@@ -334,7 +337,10 @@ int csb_sharing_model(const csb_matrix *m, int32_t P, int32_t Q, int32_t K, int3
  * the step kernels need (the GRU keeps the input-side and recurrent-side sums of its n
  * rows apart; in a model of several layers, whose products share launches, a matrix is laid
  * out for its share of the compute units: at most 256 / min(n_layers, 4) workgroups in the
- * row-owned layout; csb_plan* on the matrix afterwards plans for all of them again).  Upload
+ * row-owned layout, each of which then owns whole units with all their gate rows, so that a
+ * step of the streaming path is one launch that finishes its cells -- csb_plan_stats.row_owned
+ * = 2; the same for layers of 2048 units or more; csb_plan* on the matrix afterwards plans
+ * plain row ranges for all compute units again, which the step kernels run on as well).  Upload
  * each W[l] afterwards with csb_upload.
  */
 int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int32_t hidden,

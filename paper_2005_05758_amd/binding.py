@@ -321,7 +321,7 @@ class CsbMatrix:
         st = torch.zeros(n, dtype=torch.int64, device=x.device)
         ws = self._workspace(1, x.device)
         _check(lib().csb_debug_spmv_stamps(self._h, _dptr(x, _f32()), _dptr(y, _f32()), _dptr(ws), _dptr(st), _stream_ptr(stream)))
-        if getattr(self, "stats", None) and self.stats.get("row_owned"):
+        if getattr(self, "stats", None) and self.stats.get("row_owned") == 1:
             return y, st.view(-1, 16, 8)
         return y, st.view(-1, 8 + 3 * 16)
 

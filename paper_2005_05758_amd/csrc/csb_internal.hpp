@@ -222,6 +222,10 @@ struct StreamPlan {
     uint32_t lds_bytes = 0;
     uint32_t n_groups = 0;
     uint32_t val_fmt = 0;       // CSB_VAL_*: 32-bit values, or 16-bit ones (a column step is then a run of 64 half words)
+    uint32_t cell_gates = 0;    // 0: a workgroup owns output rows [row0, row0 + nrows).  G > 0: it owns the units
+                                // [row0, row0 + nrows / G) of a recurrent cell with all their G gate rows; its local row
+                                // g * (nrows / G) + j is output row g * cell_units + row0 + j
+    uint32_t cell_units = 0;    // units of the cell (output rows / G)
     uint64_t off = 0, bytes = 0;   // the section inside the image
 };
 
@@ -260,6 +264,9 @@ struct csb_matrix {
     int32_t val_fmt = 0;          // CSB_VAL_*: how the device value stream is stored
     int32_t stream_wg_limit = 256;   // most workgroups a default row-owned plan takes (an RNN handle with stacked layers,
                                      // whose products share launches, leaves its matrices a share of the 256 CUs each)
+    int32_t stream_cell_gates = 0;   // > 0: the rows are `gates` stacked groups of rows/gates units each, and a workgroup of
+                                     // the row-owned plan is to own all gate rows of its units (set by an RNN handle, whose
+                                     // mat-vec launches then finish their cells themselves; csb_plan* ask for plain ranges)
     csb::Plan plan;
     void *d_buf = nullptr;        // caller-owned device image, set by csb_upload
     bool uploaded = false;

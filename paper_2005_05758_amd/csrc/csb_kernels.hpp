@@ -116,6 +116,22 @@ int spmv_rows(const csb_matrix *m, const float *d_x, float *d_y, void *stream, u
 int spmv_rows_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *stream);
 struct SpmvGatedCall;
 int spmv_rows_gated_multi(const SpmvGatedCall *calls, int n, void *stream);
+// One step of a recurrent layer (LSTM, GRU, Li-GRU; Sec. 2.1) in one launch: the product
+// W [x0[0..n0) ; h_prev] from a row-owned plan whose workgroups own whole units
+// (StreamPlan::cell_gates), then the element-wise part, by the workgroup that has a unit's sums:
+// c_t (LSTM: c_in -> c_out) and h_t -> h_out (and hseq).  h_out is not h_prev.
+struct SpmvCellCall {
+    const csb_matrix *mat;
+    const float *x0;
+    uint32_t n0;
+    const float *h_prev;
+    int32_t cell;              // CSB_CELL_LSTM, CSB_CELL_GRU or CSB_CELL_LIGRU
+    const float *bias;         // as the cell stacks them, or null
+    const float *c_in;
+    float *c_out, *h_out, *hseq;
+};
+// ... for up to kMaxJobsPerLaunch layers at once (one value format for all).
+int spmv_rows_cell_multi(const SpmvCellCall *calls, int n, void *stream);
 // ... with either segment possibly a cell output still to be computed (see GateSrc).
 int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *d_ws, void *stream);
 // The element-wise part alone, one thread per unit: stores c_t, h_t (and hseq) of `s`.

@@ -866,13 +866,13 @@ int validate_plan(const csb_matrix *m) {
 // (A plan the caller asks for may take all 256 compute units again, whatever share of them an RNN
 // handle had left the matrix.)
 extern "C" int csb_plan(csb_matrix *m, int32_t n_chunks, csb_plan_stats *stats) {
-    if (m) m->stream_wg_limit = 256;
+    if (m) { m->stream_wg_limit = 256; m->stream_cell_gates = 0; }
     return csb::plan_matrix(m, n_chunks, 16, m ? m->plan.split : csb::SplitSpec{}, stats, 0);
 }
 
 extern "C" int csb_plan_ex(csb_matrix *m, int32_t n_chunks, int32_t mode, csb_plan_stats *stats) {
     if (mode == 3 || mode == 4) { csb::set_error("csb_plan: mode must be 0 (auto), 1 (whole tiles) or 2 (equal split)"); return CSB_EINVAL; }
-    if (m) m->stream_wg_limit = 256;
+    if (m) { m->stream_wg_limit = 256; m->stream_cell_gates = 0; }
     return csb::plan_matrix(m, n_chunks, 16, m ? m->plan.split : csb::SplitSpec{}, stats, mode);
 }
 
@@ -885,7 +885,7 @@ extern "C" int csb_plan_stats_get(const csb_matrix *m, csb_plan_stats *stats) {
 
 extern "C" int csb_plan_rows(csb_matrix *m, int32_t n_workgroups, int32_t min_rounds, csb_plan_stats *stats) {
     if (n_workgroups < 0 || min_rounds < 0) { csb::set_error("csb_plan_rows: negative parameter"); return CSB_EINVAL; }
-    if (m) m->stream_wg_limit = 256;
+    if (m) { m->stream_wg_limit = 256; m->stream_cell_gates = 0; }
     int rc = csb::plan_matrix(m, 0, 16, csb::SplitSpec{}, nullptr, 4);
     if (rc != CSB_OK) return rc;
     rc = csb::plan_stream(m, n_workgroups, min_rounds, stats);

@@ -1192,6 +1192,15 @@ extern "C" int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int
                 // (a plan the caller made keeps its workgroup count and mode)
                 const bool had = W[l]->plan.valid;
                 W[l]->stream_wg_limit = 256 / std::min(n_layers, kMaxJobsPerLaunch);   // the layers of a diagonal share a launch
+                // Stacked layers (and very wide ones): a workgroup of the row-owned plan owns units with
+                // all their gate rows (r, z and the two halves of n for the GRU), and the streaming
+                // step's launches finish their cells themselves.  Otherwise a cell is computed where
+                // its output is consumed, by every workgroup while its weights are on their way:
+                // measured, us per step, consumer-side / whole units: LSTM 153->512 x 1 5.06 / 5.68,
+                // x 2 6.66 / 5.77, x 3 6.68 / 5.89; 153->2048 x 1 6.73 / 6.29; GRU 256->1024 x 1
+                // 5.73 / 5.62, x 2 6.81 / 5.88; Li-GRU 256->1024 x 1 5.23 / 5.50 (with stacked layers
+                // a cell has two consumers, and both would compute it).
+                W[l]->stream_cell_gates = (n_layers >= 2 || hidden >= 2048) ? (cell == CSB_CELL_LIGRU ? 2 : 4) : 0;
                 int rc = plan_matrix(W[l], had ? W[l]->plan.req_chunks : 0, 16, sp, nullptr, had ? W[l]->plan.req_mode : 0);
                 if (rc != CSB_OK) { delete r; return rc; }
             }
@@ -1579,6 +1588,38 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
         g.kind = gru_rb ? kGateRbGate : 1u + (uint32_t)r->cell; g.H = (uint32_t)H;
         return g;
     };
+    // Row-owned plans whose workgroups own whole units (what csb_rnn_create lays out for these
+    // cells): a launch is the whole step of its layers -- product, then c_t and h_t by the workgroup
+    // that has the unit's sums -- and its input is two vectors that are already in memory.
+    bool whole_units = !lstmp && !gru_rb;
+    for (auto *m : r->W)
+        whole_units = whole_units && m->plan.stream.valid && m->plan.stream.cell_gates != 0 && m->plan.stream.val_fmt == r->W[0]->plan.stream.val_fmt &&
+                      m->plan.hdr.cols <= (uint64_t)kMaxStageCols;
+    if (whole_units) {
+        for (int d = 0; d < T + L - 1; ++d) {
+            const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
+            for (int l0 = lo; l0 <= hi_l; l0 += kMaxJobsPerLaunch) {
+                SpmvCellCall calls[kMaxJobsPerLaunch];
+                const int n = std::min(kMaxJobsPerLaunch, hi_l - l0 + 1);
+                for (int i = 0; i < n; ++i) {
+                    const int l = l0 + i, t = d - l;
+                    calls[i] = SpmvCellCall{r->W[l], l == 0 ? d_x + (size_t)t * I : h_buf(l - 1, t), l == 0 ? (uint32_t)I : (uint32_t)H,
+                                            h_buf(l, t - 1), (int32_t)r->cell, r->d_bias[l], lstm ? c_of(l, t - 1) : nullptr,
+                                            lstm ? c_of(l, t) : nullptr, h_buf(l, t),
+                                            (d_hseq && l == L - 1) ? d_hseq + (size_t)t * H : nullptr};
+                }
+                int rc = spmv_rows_cell_multi(calls, n, st);
+                if (rc != CSB_OK) return rc;
+            }
+        }
+        for (int l = 0; l < L; ++l) {
+            init_state(d_hT + (size_t)l * H, h_buf(l, T - 1), (size_t)H, st);
+            if (lstm && d_cT) init_state(d_cT + (size_t)l * H, c_of(l, T - 1), (size_t)H, st);
+        }
+        hipError_t ec = hipGetLastError();
+        if (ec != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(ec)); return CSB_EDEVICE; }
+        return CSB_OK;
+    }
     for (int d = 0; d < T + L - 1; ++d) {
         const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
         // first (or only) product of every pair on the diagonal: W_l [input ; state]

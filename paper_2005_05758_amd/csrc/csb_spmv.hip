@@ -536,7 +536,7 @@ int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSr
         set_error("csb_spmv: a computed input segment does not match the matrix's column split");
         return CSB_EINVAL;
     }
-    if (m->plan.stream.valid) return spmv_rows_gated(m, s0, n0, s1, d_y, stream);      // row-owned layout: no workspace
+    if (m->plan.stream.valid && !m->plan.stream.cell_gates) return spmv_rows_gated(m, s0, n0, s1, d_y, stream);      // row-owned layout: no workspace
     if (m->plan.hdr.n_partial_slots && !d_ws) { set_error("csb_spmv: workspace is NULL"); return CSB_EINVAL; }
     if ((uintptr_t)d_ws % 256) { set_error("csb_spmv: workspace not 256-byte aligned"); return CSB_EINVAL; }
     SpmvSrc<true> g0, g1;
@@ -553,7 +553,7 @@ int spmv_gated_multi(const SpmvGatedCall *calls, int n, void *stream) {
     bool rows = n > 1 && n <= kMaxJobsPerLaunch;            // every product in the row-owned layout: one launch of that kernel
     for (int i = 0; i < n && rows; ++i) {
         const csb_matrix *m = calls[i].mat;
-        rows = m->plan.valid && m->uploaded && m->d_buf && m->plan.stream.valid && m->plan.hdr.cols <= (uint64_t)kMaxStageCols &&
+        rows = m->plan.valid && m->uploaded && m->d_buf && m->plan.stream.valid && !m->plan.stream.cell_gates && m->plan.hdr.cols <= (uint64_t)kMaxStageCols &&
                m->plan.stream.val_fmt == calls[0].mat->plan.stream.val_fmt &&
                !(calls[i].s0.kind && calls[i].s0.H != calls[i].n0) &&
                !(calls[i].s1.kind && (uint64_t)calls[i].s1.H + calls[i].n0 != m->plan.hdr.cols);
@@ -630,7 +630,8 @@ extern "C" int csb_upload(csb_matrix *m, void *d_buf, size_t bytes, void *stream
 extern "C" int csb_spmv(const csb_matrix *m, const float *d_x, float *d_y, void *d_ws, void *stream) {
     if (!m || !d_x || !d_y) { csb::set_error("csb_spmv: NULL pointer"); return CSB_EINVAL; }
     if (m->plan.valid && m->plan.split.active()) { csb::set_error("csb_spmv: matrix is planned for a GRU step"); return CSB_ESTATE; }
-    if (m->plan.valid && m->plan.stream.valid) {            // the row-owned section: nothing is merged, no workspace
+    // (a section whose workgroups own the units of a recurrent cell is for that cell's steps: a plain product reads the tile sections)
+    if (m->plan.valid && m->plan.stream.valid && !m->plan.stream.cell_gates) {            // the row-owned section: nothing is merged, no workspace
         if (!m->uploaded || !m->d_buf) { csb::set_error("csb_spmv: matrix not planned and uploaded"); return CSB_ESTATE; }
         return csb::spmv_rows(m, d_x, d_y, stream);
     }
@@ -687,7 +688,7 @@ extern "C" int csb_spmv_static(const csb_matrix *m, const float *d_x, float *d_y
     if (!m || !d_x || !d_y) { csb::set_error("csb_spmv_static: NULL pointer"); return CSB_EINVAL; }
     if (m->plan.valid && m->plan.split.active()) { csb::set_error("csb_spmv_static: matrix is planned for a GRU step"); return CSB_ESTATE; }
     if (!m->plan.valid || !m->uploaded || !m->d_buf) { csb::set_error("csb_spmv_static: matrix not planned and uploaded"); return CSB_ESTATE; }
-    if (m->plan.stream.valid) return csb::spmv_rows(m, d_x, d_y, stream);      // row-owned layout: no partial sums in memory at all
+    if (m->plan.stream.valid && !m->plan.stream.cell_gates) return csb::spmv_rows(m, d_x, d_y, stream);      // row-owned layout: no partial sums in memory at all
     const size_t need = csb_workspace_bytes(m, 1);
     if (need > csb::kStaticScratchBytes) {
         csb::set_error("csb_spmv_static: the plan's shared row tiles need " + std::to_string(need) + " bytes of partial sums, the built-in buffer holds " +
@@ -747,7 +748,7 @@ extern "C" int csb_debug_stream_read(const void *d_buf, size_t bytes, float *d_o
 }
 
 extern "C" size_t csb_debug_stamp_count(const csb_matrix *m) {
-    if (m && m->plan.valid && m->plan.stream.valid) return (size_t)m->plan.stream.n_wg * csb::kStreamWaves * 8;
+    if (m && m->plan.valid && m->plan.stream.valid && !m->plan.stream.cell_gates) return (size_t)m->plan.stream.n_wg * csb::kStreamWaves * 8;
     return (m && m->plan.valid) ? (size_t)m->plan.hdr.n_chunks * csb::kStampsPerChunk : 0;
 }
 
@@ -755,7 +756,7 @@ extern "C" int csb_debug_spmv_stamps(const csb_matrix *m, const float *d_x, floa
                                      unsigned long long *d_stamps, void *stream) {
     if (!m || !d_x || !d_y || !d_stamps) { csb::set_error("csb_debug_spmv_stamps: NULL pointer"); return CSB_EINVAL; }
     if (m->plan.valid && m->plan.split.active()) { csb::set_error("csb_debug_spmv_stamps: matrix is planned for a GRU step"); return CSB_ESTATE; }
-    if (m->plan.valid && m->plan.stream.valid) {
+    if (m->plan.valid && m->plan.stream.valid && !m->plan.stream.cell_gates) {
         if (!m->uploaded || !m->d_buf) { csb::set_error("csb_debug_spmv_stamps: matrix not planned and uploaded"); return CSB_ESTATE; }
         return csb::spmv_rows(m, d_x, d_y, stream, d_stamps);
     }

@@ -122,7 +122,12 @@ enum : int {
     kRowsAny = 2,          // everything decided at run time
 };
 
-template <int W, bool GATED, int VF, int FORM>
+// CELL: the rows are the gate rows of a recurrent cell and the plan gives a workgroup all gate
+// rows of its units (StreamPlan::cell_gates): the input is two plain segments ([layer input ;
+// h_(t-1)]: A.g0.a, A.g1.a), and behind the row sums the workgroup applies the cell's element-wise
+// part (Sec. 2.1) to its units and stores c_t, h_t -- the whole step of a layer in this one
+// launch, the gates computed once, by the workgroup that has their sums.
+template <int W, bool GATED, int VF, int FORM, bool CELL = false>
 __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) {
     const bool stamps = FORM == kRowsAny && A.stamps != nullptr;
     const bool x_fast = A.x_fast != 0u;
@@ -142,7 +147,13 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
     if (stamps) t_start = wall_clock64();
 
     // ---- requests: the input vector and the header first, then the whole segment of round 0 --
-    if constexpr (GATED) {
+    if constexpr (CELL) {                                      // two plain segments, 4 bytes per lane (their joint lies anywhere)
+        const uint8_t *p0 = (const uint8_t *)A.g0.a, *p1 = (const uint8_t *)A.g1.a;
+        for (uint32_t u = wave; u * 64u < A.cols; u += kStreamWaves) {
+            const uint32_t e = u * 64u + lane;
+            if (e < A.cols) dma4(e < A.n0 ? p0 + 4u * e : p1 + 4u * (e - A.n0), lds0 + u * 256u);
+        }
+    } else if constexpr (GATED) {
         // (the segment's first units are requested below, before the cell arithmetic, whose loads
         // come back behind them)
     } else if (x_fast) {                                     // every wavefront's first requests: they arrive first
@@ -320,7 +331,46 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
         if (tpr >= 16u) s += dpp_f32<0x108>(s);                // eight further on
         if (tpr >= 32u) s += __shfl_down(s, 16);
         if (tpr >= 64u) s += __shfl_down(s, 32);
-        if (sub == 0u && rr < nrows) A.y[row0 + rr] = s;
+        if constexpr (!CELL) {
+            if (sub == 0u && rr < nrows) A.y[row0 + rr] = s;
+        } else {
+            // local row g * nu + j holds gate g of unit row0 + j: thread j finishes unit row0 + j
+            const GateSrc &c = A.g1;
+            const uint32_t G = A.g0.H, H = c.H, nu = nrows / G, u = row0 + tid;
+            const bool mine = tid < nu;
+            // (what the cell needs from memory is asked for before the sums change hands)
+            float b0 = 0.0f, b1 = 0.0f, b2 = 0.0f, b3 = 0.0f, prev = 0.0f;
+            if (mine) {
+                if (c.bias) {
+                    b0 = c.bias[u]; b1 = c.bias[H + u];
+                    if (c.kind != 1u + CSB_CELL_LIGRU) b2 = c.bias[2u * H + u];
+                    if (c.kind == 1u + CSB_CELL_LSTM) b3 = c.bias[3u * H + u];
+                }
+                prev = c.kind == 1u + CSB_CELL_LSTM ? c.c_in[u] : c.h_in[u];
+            }
+            float *rs = (float *)smem;                         // the staged vector is done with
+            if (sub == 0u && rr < nrows) rs[rr] = s;
+            lds_barrier();
+            if (mine) {
+                const float a0 = rs[tid] + b0, a1 = rs[nu + tid] + b1;
+                float hn;
+                if (c.kind == 1u + CSB_CELL_LSTM) {            // rows i, f, g, o
+                    const float a2 = rs[2u * nu + tid] + b2, a3 = rs[3u * nu + tid] + b3;
+                    const float cn = fast_sigmoid(a1) * prev + fast_sigmoid(a0) * fast_tanh(a2);
+                    hn = fast_sigmoid(a3) * fast_tanh(cn);
+                    c.c_out[u] = cn;
+                } else if (c.kind == 1u + CSB_CELL_GRU) {      // rows r, z, input side of n, recurrent side of n
+                    const float a2 = rs[2u * nu + tid] + b2, a3 = rs[3u * nu + tid];
+                    const float r = fast_sigmoid(a0), z = fast_sigmoid(a1);
+                    hn = (1.0f - z) * fast_tanh(a2 + r * a3) + z * prev;
+                } else {                                       // Li-GRU: rows z, candidate
+                    const float z = fast_sigmoid(a0);
+                    hn = z * prev + (1.0f - z) * fmaxf(a1, 0.0f);
+                }
+                c.h_out[u] = hn;
+                if (c.hseq) c.hseq[u] = hn;
+            }
+        }
     }
     if (stamps && lane == 0u) {
         unsigned long long *st = A.stamps + ((size_t)wg * kStreamWaves + wave) * 8;
@@ -346,6 +396,14 @@ __global__ __launch_bounds__(kStreamThreads) void spmv_rows_gated_multi_kernel(c
     rows_body<W, true, VF, FORM>(A, blockIdx.x);
 }
 
+// The step of a recurrent layer whose plan gives its workgroups whole units (blockIdx.y: the layer).
+template <int W, int VF, int FORM>
+__global__ __launch_bounds__(kStreamThreads) void spmv_rows_cell_multi_kernel(const RowsJobs J) {
+    const RowsArgs &A = J.a[blockIdx.y];
+    if (blockIdx.x >= A.n_wg) return;
+    rows_body<W, false, VF, FORM, true>(A, blockIdx.x);
+}
+
 // Kernel arguments of one product and the dynamic LDS it needs (0 with the error set if it does not fit).
 size_t rows_args(const csb_matrix *m, RowsArgs *out) {
     const StreamPlan &sp = m->plan.stream;
@@ -355,7 +413,8 @@ size_t rows_args(const csb_matrix *m, RowsArgs *out) {
     A.cols = (uint32_t)m->cols; A.kmax = sp.kmax; A.bc = (uint32_t)m->bc;
     A.tpr_log2 = (uint32_t)__builtin_ctz(sp.tpr);
     A.n_wg = sp.n_wg;
-    const uint32_t x_bytes = (uint32_t)(((size_t)m->cols * 4 + 15) / 16 * 16);
+    uint32_t x_bytes = (uint32_t)(((size_t)m->cols * 4 + 15) / 16 * 16);
+    if (sp.cell_gates) x_bytes = std::max<uint32_t>(x_bytes, 4u * (uint32_t)kStreamMaxRows);   // (the cell form keeps its row sums there)
     const uint32_t part_bytes = (uint32_t)(((size_t)sp.kmax * 4 + 15) / 16 * 16);
     A.off_hdr = x_bytes;
     A.off_part = A.off_hdr + sp.hdr_bytes;
@@ -426,6 +485,38 @@ int spmv_rows_gated_multi(const SpmvGatedCall *calls, int n, void *stream) {
     const dim3 grid(wgs, (unsigned)n);
     if (rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_gated_multi_kernel, vf, kRowsOneRound, grid, lds, stream, J);
     return CSB_ROWS_LAUNCH(spmv_rows_gated_multi_kernel, vf, kRowsRounds, grid, lds, stream, J);
+}
+
+int spmv_rows_cell_multi(const SpmvCellCall *calls, int n, void *stream) {
+    RowsJobs J{};
+    size_t lds = 0;
+    uint32_t wgs = 0, rounds = 1;
+    if (n < 1 || n > kMaxJobsPerLaunch) { set_error("csb_spmv: between one and four products share a launch"); return CSB_EINVAL; }
+    for (int i = 0; i < n; ++i) {
+        const SpmvCellCall &c = calls[i];
+        const StreamPlan &sp = c.mat->plan.stream;
+        const uint32_t G = c.cell == CSB_CELL_LIGRU ? 2u : 4u;
+        if (!c.mat->plan.valid || !c.mat->uploaded || !sp.valid || sp.cell_gates != G || sp.val_fmt != calls[0].mat->plan.stream.val_fmt ||
+            (uint64_t)c.n0 + sp.cell_units != (uint64_t)c.mat->cols) {
+            set_error("csb_spmv: matrix is not laid out for a cell of this kind");
+            return CSB_ESTATE;
+        }
+        const size_t l = rows_args(c.mat, &J.a[i]);
+        if (!l) return CSB_EUNSUPPORTED;
+        RowsArgs &A = J.a[i];
+        A.n0 = c.n0;
+        A.g0 = plain_src(c.x0); A.g0.H = G;
+        A.g1 = plain_src(c.h_prev);
+        A.g1.H = sp.cell_units; A.g1.kind = 1u + (uint32_t)c.cell; A.g1.bias = c.bias;
+        A.g1.c_in = c.c_in; A.g1.h_in = c.h_prev; A.g1.c_out = c.c_out; A.g1.h_out = c.h_out; A.g1.hseq = c.hseq;
+        lds = std::max(lds, l);
+        wgs = std::max(wgs, A.n_wg);
+        rounds = std::max(rounds, A.n_rounds);
+    }
+    const uint32_t vf = calls[0].mat->plan.stream.val_fmt;
+    const dim3 grid(wgs, (unsigned)n);
+    if (rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_cell_multi_kernel, vf, kRowsOneRound, grid, lds, stream, J);
+    return CSB_ROWS_LAUNCH(spmv_rows_cell_multi_kernel, vf, kRowsRounds, grid, lds, stream, J);
 }
 
 #undef CSB_ROWS_LAUNCH

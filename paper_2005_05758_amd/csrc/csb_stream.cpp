@@ -38,6 +38,7 @@ struct SVb {
     uint16_t c;       // columns of the part
     uint16_t q0;
     uint16_t hi;      // 1: the part that is summed into row + shift
+    int32_t radj;     // local row of the workgroup = output row + radj
 };
 
 struct Lane {
@@ -121,6 +122,10 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
     try {
         const int br = m->br;
         const int64_t R = m->rows + (split.active() ? split.shift : 0);    // output rows
+        // cell mode: workgroups own units (with all their gate rows) instead of row ranges
+        const int64_t G = m->stream_cell_gates > 0 && R % m->stream_cell_gates == 0 && kStreamMaxRows >= m->stream_cell_gates ? m->stream_cell_gates : 0;
+        const int64_t U = G ? R / G : 0;                                    // units
+        if (G && split.active() && (split.split_row % U != 0 || split.shift % U != 0)) return CSB_OK;   // (a gate's rows lie in one zone)
         // position of the split column in a block's column list (all of it without a split)
         auto split_pos = [&](size_t b, int32_t bj) {
             const int nc = m->ncols[b];
@@ -158,7 +163,8 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
         std::vector<uint32_t> cut;      // row boundaries: workgroup k owns [cut[k], cut[k+1])
         std::vector<WgLayout> W;
         uint32_t nwg = 0, rows_max = 0, hdr_bytes = 0, tpr = 0;
-        const uint32_t x_bytes = (uint32_t)align_up((size_t)m->cols * 4, 16);
+        // (the cell form of the kernel keeps its row sums where the input vector was)
+        const uint32_t x_bytes = std::max<uint32_t>((uint32_t)align_up((size_t)m->cols * 4, 16), G ? 4u * (uint32_t)kStreamMaxRows : 0u);
         StreamPlan sp{};
         bool found = false;
         uint32_t nr_start = 1;
@@ -167,28 +173,38 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
         for (double v : rw) total_w += v;
 
         // ---- 2. row ranges of the workgroups: nearly equal weight, cut at any row ----------
+        // (cell mode: the same over units, a unit weighing what its gate rows weigh)
+        const int64_t NI = G ? U : R;                                   // items that are cut: units or rows
+        const int64_t max_items = G ? kStreamMaxRows / G : kStreamMaxRows;
+        auto item_w = [&](int64_t i) {
+            if (!G) return rw[(size_t)i];
+            double v = 0;
+            for (int64_t g = 0; g < G; ++g) v += rw[(size_t)(g * U + i)];
+            return v;
+        };
         int64_t n_wg = n_wg_req > 0 ? n_wg_req : (int64_t)std::min<uint64_t>((uint64_t)std::max(1, std::min(256, m->stream_wg_limit)), std::max<uint64_t>(1, (lanes_total + kLanesPerWg - 1) / kLanesPerWg));
-        n_wg = std::max<int64_t>(n_wg, (R + kStreamMaxRows - 1) / kStreamMaxRows);
-        n_wg = std::min<int64_t>(n_wg, R);
+        n_wg = std::max<int64_t>(n_wg, (NI + max_items - 1) / max_items);
+        n_wg = std::min<int64_t>(n_wg, NI);
         cut.clear();
         cut.push_back(0);
         {
             double acc = 0;              // weight of the rows before `row`
             int64_t k = 0;               // workgroup being filled
-            for (int64_t row = 0; row < R; ++row) {
+            for (int64_t row = 0; row < NI; ++row) {
                 const int64_t rows_here = row - (int64_t)cut.back();
+                const double wrow = item_w(row);
                 if (rows_here > 0) {
-                    bool close = rows_here == kStreamMaxRows;
+                    bool close = rows_here == max_items;
                     if (!close && k + 1 < n_wg) {
                         // the boundary in front of this row is nearer to the k-th target than the one behind it
                         const double target = total_w * (double)(k + 1) / (double)n_wg;
-                        close = acc + rw[(size_t)row] / 2 >= target;
+                        close = acc + wrow / 2 >= target;
                     }
                     if (close) { cut.push_back((uint32_t)row); ++k; }
                 }
-                acc += rw[(size_t)row];
+                acc += wrow;
             }
-            cut.push_back((uint32_t)R);
+            cut.push_back((uint32_t)NI);
         }
         nwg = (uint32_t)cut.size() - 1;
 
@@ -199,23 +215,27 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
         for (uint32_t k = 0; k < nwg; ++k) {
             WgLayout &w = W[k];
             w.row0 = cut[k];
-            w.nrows = cut[k + 1] - cut[k];
+            w.nrows = (cut[k + 1] - cut[k]) * (uint32_t)(G ? G : 1);
             rows_max = std::max(rows_max, w.nrows);
-            const int64_t r0 = w.row0, r1 = cut[k + 1];
             // the workgroup's output rows come from up to three zones of the matrix: rows in front
             // of the split row (all columns), rows from it on (their columns in front of the split
-            // column), and the same rows once more, relabelled (their columns from it on)
-            struct Zone { int64_t o0, o1, back; int part; };      // output rows [o0, o1) = matrix rows - back; part 0 all, 1 low, 2 high
-            Zone zones[3];
-            int nz = 0;
-            if (!split.active()) zones[nz++] = Zone{r0, r1, 0, 0};
-            else {
+            // column), and the same rows once more, relabelled (their columns from it on); in cell
+            // mode from as many per gate (local rows: gate-major)
+            struct Zone { int64_t o0, o1, back; int part; int64_t loc; };      // output rows [o0, o1) = matrix rows - back; part 0 all, 1 low, 2 high; local row of o0
+            std::vector<Zone> zones;
+            auto add_range = [&](int64_t r0, int64_t r1, int64_t loc) {
+                if (!split.active()) { zones.push_back(Zone{r0, r1, 0, 0, loc}); return; }
                 const int64_t sr = split.split_row, mr = m->rows;
-                if (r0 < std::min(r1, sr)) zones[nz++] = Zone{r0, std::min(r1, sr), 0, 0};
-                if (std::max(r0, sr) < std::min(r1, mr)) zones[nz++] = Zone{std::max(r0, sr), std::min(r1, mr), 0, 1};
-                if (std::max(r0, mr) < r1) zones[nz++] = Zone{std::max(r0, mr), r1, split.shift, 2};
+                if (r0 < std::min(r1, sr)) zones.push_back(Zone{r0, std::min(r1, sr), 0, 0, loc});
+                if (std::max(r0, sr) < std::min(r1, mr)) zones.push_back(Zone{std::max(r0, sr), std::min(r1, mr), 0, 1, loc + std::max(r0, sr) - r0});
+                if (std::max(r0, mr) < r1) zones.push_back(Zone{std::max(r0, mr), r1, split.shift, 2, loc + std::max(r0, mr) - r0});
+            };
+            if (!G) add_range(cut[k], cut[k + 1], 0);
+            else {
+                const int64_t nu = (int64_t)cut[k + 1] - cut[k];
+                for (int64_t g = 0; g < G; ++g) add_range(g * U + cut[k], g * U + cut[k + 1], g * nu);
             }
-            for (int zi = 0; zi < nz; ++zi) {
+            for (size_t zi = 0; zi < zones.size(); ++zi) {
                 const Zone &z = zones[zi];
                 const int64_t g0 = z.o0 - z.back, g1 = z.o1 - z.back;          // matrix rows
                 for (int64_t bi = g0 / br; bi <= (g1 - 1) / br; ++bi)
@@ -231,7 +251,7 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                         while (a0 < nr && bi * br + ri[a0] < g0) ++a0;
                         int a1 = a0;
                         while (a1 < nr && bi * br + ri[a1] < g1) ++a1;
-                        if (a1 > a0) w.vbs.push_back(SVb{(uint32_t)b, (uint16_t)a0, (uint16_t)a1, (uint16_t)(q1 - q0), (uint16_t)q0, (uint16_t)(z.part == 2 ? 1 : 0)});
+                        if (a1 > a0) w.vbs.push_back(SVb{(uint32_t)b, (uint16_t)a0, (uint16_t)a1, (uint16_t)(q1 - q0), (uint16_t)q0, (uint16_t)(z.part == 2 ? 1 : 0), (int32_t)(z.loc - z.o0)});
                     }
             }
             std::stable_sort(w.vbs.begin(), w.vbs.end(), [](const SVb &x, const SVb &y) { return x.c > y.c; });
@@ -240,7 +260,7 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                 const int64_t bi = vb.b / m->nbc;
                 const uint16_t *ri = m->rowidx.data() + m->row_off[vb.b];
                 for (int a = vb.a0; a < vb.a1; ++a)
-                    w.lanes.push_back(Lane{v, (uint16_t)a, (uint16_t)(bi * br + ri[a] + (vb.hi ? split.shift : 0) - r0)});
+                    w.lanes.push_back(Lane{v, (uint16_t)a, (uint16_t)(bi * br + ri[a] + (vb.hi ? split.shift : 0) + vb.radj)});
             }
             for (uint32_t l0 = 0; l0 < w.lanes.size(); l0 += kWave) w.g_cmax.push_back(w.vbs[w.lanes[l0].vb].c);
         }
@@ -438,7 +458,8 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
                 const double target = sum / nwg;
                 for (uint32_t k = 0; k < nwg; ++k) {
                     const double f = 1.0 + 0.7 * (wg_max(W[k]) / target - 1.0);
-                    for (uint32_t r = cut[k]; r < cut[k + 1]; ++r) rw[r] *= f;
+                    for (uint32_t r = cut[k]; r < cut[k + 1]; ++r)
+                        for (int64_t g = 0; g < (G ? G : 1); ++g) rw[(size_t)(g * U + r)] *= f;
                 }
                 attempt();
                 last_is_best = false;
@@ -545,6 +566,7 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
         }
         sp.n_groups = n_groups;
         sp.val_fmt = (uint32_t)m->val_fmt;
+        sp.cell_gates = (uint32_t)G; sp.cell_units = (uint32_t)U;
         sp.valid = true;
         pl.stream = sp;
 
@@ -569,7 +591,7 @@ int plan_stream(csb_matrix *m, int32_t n_wg_req, int32_t rounds_min, csb_plan_st
         st.chunk_max_over_mean = csum_ > 0 ? cmax_ / (csum_ / sp.n_wg) : 0.0;
         st.lane_fill = fma_steps ? (double)m->val.size() / (64.0 * (double)fma_steps) : 0.0;
         st.whole_tiles = 1;
-        st.row_owned = 1;
+        st.row_owned = G ? 2 : 1;
         st.rounds = (int32_t)sp.n_rounds;
         st.matvec_bytes = (int64_t)traffic;          // segments are read up to their own length, not the stride
         pl.stats = st;
@@ -627,7 +649,10 @@ int validate_stream(const csb_matrix *m) {
         StreamRoundHdr rh;
         std::memcpy(&rh, wb, sizeof(rh));
         const uint32_t row0 = rh.row0, nrows = rh.nrows;
-        if (nrows > sp.rows_max || (int64_t)row0 + nrows > R) return fail("row range");
+        const uint32_t CG = sp.cell_gates, nu = CG ? nrows / CG : 0;
+        if (CG && (nrows % CG || (int64_t)sp.cell_units * CG != R || (int64_t)row0 + nu > sp.cell_units)) return fail("unit range");
+        if (nrows > sp.rows_max || (!CG && (int64_t)row0 + nrows > R)) return fail("row range");
+        auto out_row = [&](uint32_t rr) { return CG ? (size_t)(rr / nu) * sp.cell_units + row0 + rr % nu : (size_t)row0 + rr; };
         // (first slot, count) per row: consecutive, inside the table; every slot written exactly once
         std::vector<uint8_t> slot_used(sp.kmax, 0);
         std::vector<int32_t> slot_row(sp.kmax, -1);
@@ -694,7 +719,7 @@ int validate_stream(const csb_matrix *m) {
                             if (seg[lw + j] != seg[lw]) return fail("padding column is not the block's first");
                             continue;
                         }
-                        const size_t e = (size_t)(row0 + rr) * Ccols + col;
+                        const size_t e = out_row(rr) * Ccols + col;
                         if (seen[e]) return fail("entry stored twice");
                         seen[e] = 1;
                         std::memcpy(&got[e], &bits, 4);
@@ -706,8 +731,8 @@ int validate_stream(const csb_matrix *m) {
         for (uint32_t q = 0; q < sp.kmax; ++q)
             if (slot_row[q] >= 0 && !slot_used[q]) return fail("partial-sum slot never written");
         for (uint32_t i = 0; i < nrows; ++i) {
-            if (row_done[row0 + i]) return fail("row owned twice");
-            row_done[row0 + i] = 1;
+            if (row_done[out_row(i)]) return fail("row owned twice");
+            row_done[out_row(i)] = 1;
         }
     }
     for (int64_t i = 0; i < R; ++i) if (!row_done[i]) return fail("row without an owner");

@@ -102,6 +102,52 @@ def test_rnn_streaming_on_row_owned_plans_of_the_callers_choosing(L, n_wg, round
     assert float(np.max(np.abs(cT.cpu().numpy() - rcT))) <= TOL
 
 
+@pytest.mark.parametrize("cell,L,I,H,block,rate,T", [
+    (csb_inputs.LSTM, 2, 24, 96, 16, 3.0, 7), (csb_inputs.GRU, 3, 33, 100, 32, 3.0, 6), (csb_inputs.LIGRU, 2, 7, 40, 8, 2.0, 9),
+    (csb_inputs.LSTM, 5, 16, 64, 16, 4.0, 5),            # more layers on a diagonal than one launch takes
+    (csb_inputs.LSTM, 1, 5, 2048, 64, 2.0, 3)])         # a wide layer: wavefronts with several rounds
+def test_rnn_streaming_on_plans_whose_workgroups_own_whole_units(cell, L, I, H, block, rate, T):
+    """Stacked (and very wide) layers: csb_rnn_create lays the matrices out so that a workgroup owns
+    units with all their gate rows, and a step of the streaming path is one launch that finishes
+    its cells.  Without biases and without an output sequence as well; and csb_spmv on such a
+    matrix (it reads the tile sections) still gives the plain product."""
+    cfg = csb_inputs.RnnConfig("t", cell, L, I, H, block, rate, "binomial", 0.3, 1, T, 90 + L)
+    wl = csb_inputs.make_rnn(cfg)
+    W = [oracle.csb_decode(oracle.csb_encode(m.A, m.br, m.bc)) for m in wl.W]
+    rng = np.random.default_rng(3)
+    h0 = rng.uniform(-0.5, 0.5, (L, 1, H)).astype(np.float32).astype(np.float64)
+    c0 = rng.uniform(-0.5, 0.5, (L, 1, H)).astype(np.float32).astype(np.float64) if cell == csb_inputs.LSTM else None
+    for with_bias in (True, False):
+        bias = wl.bias if with_bias else [np.zeros_like(b) for b in wl.bias]
+        rseq, rhT, rcT = oracle.rnn_forward(cfg.cell, W, bias, wl.x, cfg.input, cfg.hidden, h0=h0, c0=c0)
+        Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+        rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, [torch.from_numpy(b).cuda() for b in wl.bias] if with_bias else None)
+        for w in Ws:
+            st = w.plan_stats()
+            say(f"[rnn] whole units: {st['n_chunks']} workgroups, {st['rounds']} rounds, bias {with_bias}")
+            assert st["row_owned"] == 2
+            w.upload()
+        xd = torch.from_numpy(wl.x).cuda()
+        h0d = torch.from_numpy(h0.astype(np.float32)).cuda()
+        c0d = None if c0 is None else torch.from_numpy(c0.astype(np.float32)).cuda()
+        hseq, hT, cT = rnn.forward(xd, h0d, c0d, want_hseq=with_bias)
+        torch.cuda.synchronize()
+        if with_bias:
+            assert float(np.max(np.abs(hseq.cpu().numpy() - rseq))) <= TOL
+        assert float(np.max(np.abs(hT.cpu().numpy() - rhT))) <= TOL
+        if cell == csb_inputs.LSTM:
+            assert float(np.max(np.abs(cT.cpu().numpy() - rcT))) <= TOL
+        if cell != csb_inputs.GRU:                          # (a GRU's matrix is laid out for its step: rows relabelled)
+            x = rng.uniform(-1, 1, W[0].shape[1]).astype(np.float32)
+            y = Ws[0].spmv(torch.from_numpy(x).cuda()).cpu().numpy()
+            ref = W[0].astype(np.float64) @ x.astype(np.float64)
+            # the float32 dot-product bound: k terms in any order, 2 k 2^-24 sum |a_ij x_j|
+            k = np.count_nonzero(W[0], axis=1)
+            bound = 2.0 * np.maximum(k, 1) * 2.0 ** -24 * (np.abs(W[0]).astype(np.float64) @ np.abs(x).astype(np.float64)) + 1e-30
+            assert np.all(np.abs(y - ref) <= bound)
+        del rnn
+
+
 @pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
 @pytest.mark.parametrize("L", [1, 2])
 def test_rnn_streaming_on_tile_layout_plans(cell, L):

@@ -414,6 +414,31 @@ def test_gru_step_matrices_get_the_row_owned_layout(I, H, block, layers):
     rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, None)
     for w in Ws:
         st = w.plan_stats()
-        assert st["row_owned"] == 1, st
+        assert st["row_owned"] == (2 if layers >= 2 else 1), st     # stacked layers: workgroups own whole units
         w.validate()
+    del rnn
+
+
+@pytest.mark.parametrize("cell,I,H,block,layers", [
+    (csb_inputs.LSTM, 20, 48, 16, 2), (csb_inputs.GRU, 33, 64, 32, 3), (csb_inputs.LIGRU, 7, 40, 8, 2),
+    (csb_inputs.LSTM, 5, 2048, 64, 1), (csb_inputs.LSTM, 64, 300, 16, 2), (csb_inputs.GRU, 12, 96, 32, 1)])
+def test_stacked_layers_get_plans_whose_workgroups_own_whole_units(cell, I, H, block, layers):
+    """csb_rnn_create lays the matrices of stacked (or very wide) layers out so that a workgroup
+    owns units with all their gate rows (the streaming step then finishes its cells in the
+    product's launch): the section decodes to the matrix (csb_plan_validate walks it with the
+    unit-to-row mapping), and a plan the caller makes afterwards owns plain row ranges again."""
+    from paper_2005_05758_amd import CsbRnn
+    cfg = csb_inputs.RnnConfig("t", cell, layers, I, H, block, 4.0, "binomial", 0.3, 1, 2, 5)
+    wl = csb_inputs.make_rnn(cfg)
+    Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+    rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, None)
+    want = 2 if (layers >= 2 or H >= 2048) else 1
+    for w in Ws:
+        st = w.plan_stats()
+        assert st["row_owned"] == want, st
+        w.validate()
+    if cell != csb_inputs.GRU:              # (a GRU's matrices keep their row split, and with it the handle's layout rules)
+        st = Ws[0].plan()
+        assert st["row_owned"] == 1
+        Ws[0].validate()
     del rnn
