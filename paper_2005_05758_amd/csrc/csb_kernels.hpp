@@ -119,7 +119,9 @@ int spmv_rows_gated_multi(const SpmvGatedCall *calls, int n, void *stream);
 // One step of a recurrent layer (LSTM, GRU, Li-GRU; Sec. 2.1) in one launch: the product
 // W [x0[0..n0) ; h_prev] from a row-owned plan whose workgroups own whole units
 // (StreamPlan::cell_gates), then the element-wise part, by the workgroup that has a unit's sums:
-// c_t (LSTM: c_in -> c_out) and h_t -> h_out (and hseq).  h_out is not h_prev.
+// c_t (LSTM: c_in -> c_out) and h_t -> h_out (and hseq).  h_out is not h_prev.  The second segment
+// has the matrix's other columns; for the LSTM it need not be the cell's own output (LSTMP: it is
+// the projected state, and h_out receives m_t).
 struct SpmvCellCall {
     const csb_matrix *mat;
     const float *x0;
@@ -132,6 +134,13 @@ struct SpmvCellCall {
 };
 // ... for up to kMaxJobsPerLaunch layers at once (one value format for all).
 int spmv_rows_cell_multi(const SpmvCellCall *calls, int n, void *stream);
+// Up to kMaxJobsPerLaunch independent plain products y = A x from row-owned plans in one launch.
+struct SpmvPlainCall {
+    const csb_matrix *mat;
+    const float *x;
+    float *y;
+};
+int spmv_rows_multi(const SpmvPlainCall *calls, int n, void *stream);
 // ... with either segment possibly a cell output still to be computed (see GateSrc).
 int spmv_gated(const csb_matrix *m, const GateSrc &s0, uint32_t n0, const GateSrc &s1, float *d_y, void *d_ws, void *stream);
 // The element-wise part alone, one thread per unit: stores c_t, h_t (and hseq) of `s`.

@@ -1017,7 +1017,8 @@ static RnnWs ws_layout(const csb_rnn *r, int32_t batch, int32_t T) {
         w.xt_steps = (int32_t)std::max<size_t>(1, std::min<size_t>({(size_t)std::max(T, 1), (size_t)1024, ((size_t)8 << 20) / std::max<size_t>(frame, 1)}));
         w.off_xt = off; off = align256(off + (size_t)w.xt_steps * frame);
     }
-    w.off_m = off; off = align256(off + ((r->proj > 0 || two_products) ? (size_t)batch * r->hidden * sizeof(float) * per_layer : 0));
+    // (LSTMP at batch 1 as well: every layer's m_t, between its gate launch and its projection launch)
+    w.off_m = off; off = align256(off + ((r->proj > 0 || two_products) ? (size_t)batch * r->hidden * sizeof(float) * (r->proj > 0 ? (size_t)r->n_layers : per_layer) : 0));
     // streaming at batch 1: per layer two buffers of gate sums (plus the second product's sums of
     // the reset-before GRU) and two of (c, h), used alternately by even and odd steps
     const bool fused = batch == 1;
@@ -1238,6 +1239,11 @@ extern "C" int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hid
             for (csb_matrix *m : {W[l], Wp[l]})
                 if (!m->plan.valid || m->plan.split.active()) {
                     m->stream_wg_limit = 256 / std::min(n_layers, kMaxJobsPerLaunch);   // the layers of a diagonal share a launch
+                    // (stacked layers, the gate matrix: workgroups own whole units, the launch of the gate product
+                    // leaves m_t = o tanh(c_t) behind and the projection is a plain product of it; measured on
+                    // the 153 -> 1024 -> 512 shape, us per frame, consumer-side / whole units: two layers 10.65 /
+                    // 10.28, one layer 8.96 / 9.98)
+                    m->stream_cell_gates = (m == W[l] && n_layers >= 2) ? 4 : 0;
                     int rc = plan_matrix(m, 0, 16, SplitSpec{}, nullptr, 0);
                     if (rc != CSB_OK) { delete r; return rc; }
                 }
@@ -1595,6 +1601,42 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
     for (auto *m : r->W)
         whole_units = whole_units && m->plan.stream.valid && m->plan.stream.cell_gates != 0 && m->plan.stream.val_fmt == r->W[0]->plan.stream.val_fmt &&
                       m->plan.hdr.cols <= (uint64_t)kMaxStageCols;
+    bool lstmp_units = lstmp;
+    for (auto *m : r->W)
+        lstmp_units = lstmp_units && m->plan.stream.valid && m->plan.stream.cell_gates == 4 && m->plan.stream.val_fmt == r->W[0]->plan.stream.val_fmt &&
+                      m->plan.hdr.cols <= (uint64_t)kMaxStageCols;
+    for (auto *m : r->Wp)
+        lstmp_units = lstmp_units && m->plan.stream.valid && m->plan.stream.cell_gates == 0 && m->plan.stream.val_fmt == r->Wp[0]->plan.stream.val_fmt;
+    if (lstmp_units) {
+        // LSTMP on such plans: the gate product's launch finishes the cell (c_t, m_t = o tanh(c_t)), the
+        // projection r_t = Wp m_t is a plain product (the last layer's straight into the output sequence)
+        float *mbuf = (float *)((uint8_t *)d_ws + wl.off_m);
+        for (int d = 0; d < T + L - 1; ++d) {
+            const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
+            for (int l0 = lo; l0 <= hi_l; l0 += kMaxJobsPerLaunch) {
+                SpmvCellCall calls[kMaxJobsPerLaunch];
+                SpmvPlainCall proj[kMaxJobsPerLaunch];
+                const int n = std::min(kMaxJobsPerLaunch, hi_l - l0 + 1);
+                for (int i = 0; i < n; ++i) {
+                    const int l = l0 + i, t = d - l;
+                    float *ml = mbuf + (size_t)l * H;
+                    calls[i] = SpmvCellCall{r->W[l], l == 0 ? d_x + (size_t)t * I : (const float *)r_of(l - 1, t), l == 0 ? (uint32_t)I : (uint32_t)HS,
+                                            r_of(l, t - 1), CSB_CELL_LSTM, r->d_bias[l], c_of(l, t - 1), c_of(l, t), ml, nullptr};
+                    proj[i] = SpmvPlainCall{r->Wp[l], ml, r_of(l, t)};
+                }
+                int rc = spmv_rows_cell_multi(calls, n, st);
+                if (rc == CSB_OK) rc = spmv_rows_multi(proj, n, st);
+                if (rc != CSB_OK) return rc;
+            }
+        }
+        for (int l = 0; l < L; ++l) {
+            init_state(d_hT + (size_t)l * HS, r_of(l, T - 1), (size_t)HS, st);
+            if (d_cT) init_state(d_cT + (size_t)l * H, c_of(l, T - 1), (size_t)H, st);
+        }
+        hipError_t ec = hipGetLastError();
+        if (ec != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(ec)); return CSB_EDEVICE; }
+        return CSB_OK;
+    }
     if (whole_units) {
         for (int d = 0; d < T + L - 1; ++d) {
             const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);

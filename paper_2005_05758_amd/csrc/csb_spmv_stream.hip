@@ -396,6 +396,14 @@ __global__ __launch_bounds__(kStreamThreads) void spmv_rows_gated_multi_kernel(c
     rows_body<W, true, VF, FORM>(A, blockIdx.x);
 }
 
+// Independent plain products in one launch (blockIdx.y).
+template <int W, int VF, int FORM>
+__global__ __launch_bounds__(kStreamThreads) void spmv_rows_multi_kernel(const RowsJobs J) {
+    const RowsArgs &A = J.a[blockIdx.y];
+    if (blockIdx.x >= A.n_wg) return;
+    rows_body<W, false, VF, FORM>(A, blockIdx.x);
+}
+
 // The step of a recurrent layer whose plan gives its workgroups whole units (blockIdx.y: the layer).
 template <int W, int VF, int FORM>
 __global__ __launch_bounds__(kStreamThreads) void spmv_rows_cell_multi_kernel(const RowsJobs J) {
@@ -487,6 +495,32 @@ int spmv_rows_gated_multi(const SpmvGatedCall *calls, int n, void *stream) {
     return CSB_ROWS_LAUNCH(spmv_rows_gated_multi_kernel, vf, kRowsRounds, grid, lds, stream, J);
 }
 
+int spmv_rows_multi(const SpmvPlainCall *calls, int n, void *stream) {
+    RowsJobs J{};
+    size_t lds = 0;
+    uint32_t wgs = 0, rounds = 1;
+    if (n < 1 || n > kMaxJobsPerLaunch) { set_error("csb_spmv: between one and four products share a launch"); return CSB_EINVAL; }
+    for (int i = 0; i < n; ++i) {
+        const csb_matrix *m = calls[i].mat;
+        if (!m->plan.valid || !m->uploaded || !m->plan.stream.valid || m->plan.stream.cell_gates ||
+            m->plan.stream.val_fmt != calls[0].mat->plan.stream.val_fmt) {
+            set_error("csb_spmv: matrix is not in the plain row-owned layout");
+            return CSB_ESTATE;
+        }
+        const size_t l = rows_args(m, &J.a[i]);
+        if (!l) return CSB_EUNSUPPORTED;
+        J.a[i].x = calls[i].x; J.a[i].y = calls[i].y;
+        J.a[i].x_fast = ((uintptr_t)calls[i].x % 16 == 0 && m->cols % 4 == 0) ? 1u : 0u;
+        lds = std::max(lds, l);
+        wgs = std::max(wgs, J.a[i].n_wg);
+        rounds = std::max(rounds, J.a[i].n_rounds);
+    }
+    const uint32_t vf = calls[0].mat->plan.stream.val_fmt;
+    const dim3 grid(wgs, (unsigned)n);
+    if (rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_multi_kernel, vf, kRowsOneRound, grid, lds, stream, J);
+    return CSB_ROWS_LAUNCH(spmv_rows_multi_kernel, vf, kRowsRounds, grid, lds, stream, J);
+}
+
 int spmv_rows_cell_multi(const SpmvCellCall *calls, int n, void *stream) {
     RowsJobs J{};
     size_t lds = 0;
@@ -497,7 +531,7 @@ int spmv_rows_cell_multi(const SpmvCellCall *calls, int n, void *stream) {
         const StreamPlan &sp = c.mat->plan.stream;
         const uint32_t G = c.cell == CSB_CELL_LIGRU ? 2u : 4u;
         if (!c.mat->plan.valid || !c.mat->uploaded || !sp.valid || sp.cell_gates != G || sp.val_fmt != calls[0].mat->plan.stream.val_fmt ||
-            (uint64_t)c.n0 + sp.cell_units != (uint64_t)c.mat->cols) {
+            (uint64_t)c.n0 >= (uint64_t)c.mat->cols || (c.cell != CSB_CELL_LSTM && (uint64_t)c.n0 + sp.cell_units != (uint64_t)c.mat->cols)) {
             set_error("csb_spmv: matrix is not laid out for a cell of this kind");
             return CSB_ESTATE;
         }
