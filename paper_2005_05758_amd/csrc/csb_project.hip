@@ -167,7 +167,18 @@ __global__ __launch_bounds__(256) void col_segment_keys_vec_kernel(const float *
     const uint32_t r0 = bi * BR, r1 = min(R, r0 + BR);
     const uint8_t *kr = keep_r + (size_t)(c / BC) * R;
     float s = 0.0f;
-    for (uint32_t i = r0; i < r1; i += 8) {
+    uint32_t i = r0;
+    for (; i + 32 <= r1; i += 32) {                          // 32 rows: their flags first, then all surviving loads at once
+        const uint2 fa = *(const uint2 *)(kr + i), fb = *(const uint2 *)(kr + i + 8), fc = *(const uint2 *)(kr + i + 16),
+                    fd = *(const uint2 *)(kr + i + 24);
+        const uint32_t fw[8] = {fa.x, fa.y, fb.x, fb.y, fc.x, fc.y, fd.x, fd.y};
+        float v[32];
+#pragma unroll
+        for (int q = 0; q < 32; ++q) v[q] = ((fw[q >> 2] >> (8 * (q & 3))) & 0xffu) ? W[(size_t)(i + q) * ld + c] : 0.0f;
+#pragma unroll
+        for (int q = 0; q < 32; ++q) s = fmaf(v[q], v[q], s);
+    }
+    for (; i < r1; i += 8) {
         const uint2 f = *(const uint2 *)(kr + i);
         float v[8];
 #pragma unroll
