@@ -295,6 +295,19 @@ def main():
     streaming = {"us_per_timestep": round(ms2 * 1000.0 / T, 3),
                  "gbps_algorithmic": round(bytes_step / (ms2 * 1e-3 / T) / 1e9, 2),
                  "note": "csb_rnn_forward without the resident layout: one csb spmv launch per step and layer, the gates computed while it stages its input"}
+    # the same call captured once into a HIP graph and replayed (the streaming path is kernel
+    # launches only: nothing in it depends on the host)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        rnn2.forward(xd, want_hseq=True)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        rnn2.forward(xd, want_hseq=True)
+    torch.cuda.synchronize()
+    graph.replay()
+    ms3 = time_region(graph.replay, 5, torch) / 5
+    streaming["graph_replay_us_per_timestep"] = round(ms3 * 1000.0 / T, 3)
 
     out = {
         "metric": "us_per_timestep_csb_lstm_batch1",
@@ -712,6 +725,18 @@ def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, cases=(("cfg5", 128), 
                        "sequences_per_s": round(cfg.batch / (ms * 1e-3), 1),
                        "note": "the matrix-core path (csb_spmm per diagonal); the same workload as instances of the resident "
                                "kernel laid out for this batch is timed in resident_batches.cfg4.batch64"}
+    # the same call captured into a HIP graph and replayed (kernel launches only)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        rnn.forward(xd, want_hseq=False)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        rnn.forward(xd, want_hseq=False)
+    torch.cuda.synchronize()
+    graph.replay()
+    msg = time_region(graph.replay, n, torch) / n
+    res["rnn_cfg4"]["graph_replay_us_per_timestep"] = round(msg * 1000.0 / cfg.T, 2)
     return res
 
 

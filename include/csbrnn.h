@@ -464,7 +464,11 @@ size_t csb_rnn_workspace_bytes(const csb_rnn *r, int32_t batch, int32_t T);
  * neither the resident layout nor every W[l] uploaded -> CSB_ESTATE.
  * Not for replay from a captured HIP graph: the resident kernel (and csb_spmv / csb_spmm on a
  * matrix planned with shared row tiles) tell this call's exchange words from stale ones by a
- * launch tag that the HOST draws per call; a replay would reuse the tag.  Calls on one handle
+ * launch tag that the HOST draws per call; a replay would reuse the tag.  Without a resident
+ * layout uploaded, the streaming path at batch 1 on row-owned plans (what csb_rnn_create lays
+ * out) and the batched path are kernel launches only and MAY be captured and replayed, with new
+ * contents in the captured buffers (call once before the capture: a kernel's first launch raises
+ * its LDS limit, which is not a stream operation).  Calls on one handle
  * must not overlap either (they share the workspace's exchange words).
  */
 int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0,

@@ -148,6 +148,54 @@ def test_rnn_streaming_on_plans_whose_workgroups_own_whole_units(cell, L, I, H, 
         del rnn
 
 
+@pytest.mark.parametrize("cell,L,B", [(csb_inputs.LSTM, 1, 1), (csb_inputs.LSTM, 2, 1), (csb_inputs.GRU, 1, 1), (csb_inputs.LIGRU, 3, 1),
+                                      (csb_inputs.LSTM, 2, 8), (csb_inputs.GRU, 1, 5)])
+def test_rnn_streaming_forward_replays_from_a_captured_graph(cell, L, B):
+    """The streaming path on row-owned plans (and the batched path) is kernel launches only, so a
+    caller may capture csb_rnn_forward into a HIP graph and replay it: three replays with new
+    inputs written into the captured buffers in between, eager work and synchronisation between
+    them, each compared with the oracle and with the eager call."""
+    cfg = csb_inputs.RnnConfig("t", cell, L, 20, 72, 16, 3.0, "binomial", 0.3, B, 9, 130 + L)
+    wl = csb_inputs.make_rnn(cfg)
+    W = [oracle.csb_decode(oracle.csb_encode(m.A, m.br, m.bc)) for m in wl.W]
+    Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+    rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, [torch.from_numpy(b).cuda() for b in wl.bias])
+    for w in Ws:
+        w.upload()
+    rng = np.random.default_rng(8)
+    xs = torch.from_numpy(wl.x).cuda()                       # the captured input buffer
+    h0s = torch.zeros((L, B, cfg.hidden), dtype=torch.float32, device="cuda")
+    c0s = torch.zeros_like(h0s) if cell == csb_inputs.LSTM else None
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        rnn.forward(xs, h0s, c0s)                            # (sizes the workspace outside the capture)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        out = rnn.forward(xs, h0s, c0s)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        x = rng.uniform(-1, 1, wl.x.shape).astype(np.float32)
+        h0 = rng.uniform(-0.5, 0.5, (L, B, cfg.hidden)).astype(np.float32)
+        c0 = rng.uniform(-0.5, 0.5, (L, B, cfg.hidden)).astype(np.float32)
+        xs.copy_(torch.from_numpy(x)); h0s.copy_(torch.from_numpy(h0))
+        if c0s is not None:
+            c0s.copy_(torch.from_numpy(c0))
+        rseq, rhT, rcT = oracle.rnn_forward(cfg.cell, W, wl.bias, x, cfg.input, cfg.hidden, h0=h0.astype(np.float64),
+                                            c0=c0.astype(np.float64) if c0s is not None else None)
+        graph.replay()
+        torch.cuda.synchronize()
+        hseq, hT, cT = (o.clone() if o is not None else None for o in out)
+        eager = rnn.forward(xs, h0s, c0s)                     # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        say(f"[rnn] graph replay {rep}: err {float(np.max(np.abs(hseq.cpu().numpy() - rseq))):.3g}")
+        assert float(np.max(np.abs(hseq.cpu().numpy() - rseq))) <= TOL
+        assert float(np.max(np.abs(hT.cpu().numpy() - rhT))) <= TOL
+        assert torch.equal(hseq, eager[0]) and torch.equal(hT, eager[1])
+        if c0s is not None:
+            assert float(np.max(np.abs(cT.cpu().numpy() - rcT))) <= TOL and torch.equal(cT, eager[2])
+
+
 @pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
 @pytest.mark.parametrize("L", [1, 2])
 def test_rnn_streaming_on_tile_layout_plans(cell, L):
