@@ -228,6 +228,8 @@ size_t csb_workspace_bytes(const csb_matrix *m, int32_t batch);
  * CSB-MVM, Sec. 4.3.1: y = A x.  d_x [cols], d_y [rows] device float32; d_ws device
  * scratch of csb_workspace_bytes(m, 1) (may be NULL if that is 0).  Every y entry is
  * written (rows without survivors get 0).  Results are bitwise reproducible run to run.
+ * On a row-owned plan (what csb_plan makes by default) the call is one kernel launch and
+ * nothing else, and may be captured into a HIP graph.
  * Errors: NULL -> CSB_EINVAL; not planned/uploaded -> CSB_ESTATE; launch failure ->
  * CSB_EDEVICE.
  */

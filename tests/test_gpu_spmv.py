@@ -206,3 +206,40 @@ def test_spmv_input_vector_at_any_four_byte_address(shift):
         torch.cuda.synchronize()
         assert torch.equal(ya, ys)
         assert rel_max_err(ys.cpu().numpy().astype(np.float64), ref) <= 1e-5
+
+
+def test_spmv_replays_from_a_captured_graph():
+    """csb_spmv on a row-owned plan is one kernel launch: captured into a HIP graph (two products
+    in a row, the second reading what the first wrote) and replayed three times with new inputs
+    in the captured buffer and eager launches in between."""
+    rng = np.random.default_rng(12)
+    m = csb_inputs.make_mat(csb_inputs.MatConfig("g", 320, 320, 16, 4.0, "binomial", 0.05, 3))
+    D = oracle.csb_decode(oracle.csb_encode(m.A, m.br, m.bc)).astype(np.float64)
+    M = CsbMatrix(m.A, m.br, m.bc)
+    assert M.plan()["row_owned"] == 1
+    M.upload()
+    xs = torch.zeros(320, dtype=torch.float32, device="cuda")
+    y1 = torch.empty(320, dtype=torch.float32, device="cuda")
+    y2 = torch.empty(320, dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        M.spmv(xs, y1)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        M.spmv(xs, y1)
+        M.spmv(y1, y2)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        x = rng.uniform(-1, 1, 320).astype(np.float32)
+        xs.copy_(torch.from_numpy(x))
+        graph.replay()
+        torch.cuda.synchronize()
+        g1, g2 = y1.clone(), y2.clone()
+        e1 = M.spmv(xs)
+        e2 = M.spmv(e1)
+        torch.cuda.synchronize()
+        assert torch.equal(g1, e1) and torch.equal(g2, e2)
+        ref = D @ x.astype(np.float64)
+        assert rel_max_err(g1.cpu().numpy().astype(np.float64), ref) <= 1e-5
+
