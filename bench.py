@@ -89,6 +89,21 @@ def time_region(fn, reps, torch):
     return start.elapsed_time(stop)
 
 
+def graph_replay_ms(fn, reps, torch):
+    """Milliseconds per replay of `fn` captured once into a HIP graph (fn must be launches only
+    and have run once before, so that nothing is set up inside the capture)."""
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        fn()
+    torch.cuda.synchronize()
+    graph.replay()
+    return time_region(graph.replay, reps, torch) / reps
+
+
 def time_each(fn, reps, torch):
     """One event pair per repetition: (median, min) in ms."""
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
@@ -297,16 +312,7 @@ def main():
                  "note": "csb_rnn_forward without the resident layout: one csb spmv launch per step and layer, the gates computed while it stages its input"}
     # the same call captured once into a HIP graph and replayed (the streaming path is kernel
     # launches only: nothing in it depends on the host)
-    side = torch.cuda.Stream()
-    with torch.cuda.stream(side):
-        rnn2.forward(xd, want_hseq=True)
-    torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=side):
-        rnn2.forward(xd, want_hseq=True)
-    torch.cuda.synchronize()
-    graph.replay()
-    ms3 = time_region(graph.replay, 5, torch) / 5
+    ms3 = graph_replay_ms(lambda: rnn2.forward(xd, want_hseq=True), 5, torch)
     streaming["graph_replay_us_per_timestep"] = round(ms3 * 1000.0 / T, 3)
 
     out = {
@@ -726,16 +732,7 @@ def batched_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, cases=(("cfg5", 128), 
                        "note": "the matrix-core path (csb_spmm per diagonal); the same workload as instances of the resident "
                                "kernel laid out for this batch is timed in resident_batches.cfg4.batch64"}
     # the same call captured into a HIP graph and replayed (kernel launches only)
-    side = torch.cuda.Stream()
-    with torch.cuda.stream(side):
-        rnn.forward(xd, want_hseq=False)
-    torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=side):
-        rnn.forward(xd, want_hseq=False)
-    torch.cuda.synchronize()
-    graph.replay()
-    msg = time_region(graph.replay, n, torch) / n
+    msg = graph_replay_ms(lambda: rnn.forward(xd, want_hseq=False), n, torch)
     res["rnn_cfg4"]["graph_replay_us_per_timestep"] = round(msg * 1000.0 / cfg.T, 2)
     return res
 
@@ -795,6 +792,8 @@ def lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
         key = f"batch{batch}" + ("_streaming" if batch == 1 else "")
         res[key] = {"us_per_frame": round(ms * 1000.0 / T, 2), "frames_per_s": round(batch * T / (ms * 1e-3), 1),
                     "nnz": nnz, "tflops_algorithmic": round(2.0 * nnz * batch / (ms * 1e-3 / T) / 1e12, 4)}
+        if batch == 1:          # the same call replayed from a HIP graph (launches only)
+            res[key]["graph_replay_us_per_frame"] = round(graph_replay_ms(lambda: rnn.forward(xd, want_hseq=True), n, torch) * 1000.0 / T, 2)
         if batch == 1:
             # the resident layout: one launch for the whole sequence
             rnn2 = CsbRnn(CELL_LSTMP, 153, 1024, [CsbMatrix(m.A, m.br, m.bc) for m in wl.W], bias, proj=512,
@@ -858,7 +857,9 @@ def cells_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
         m.upload()
     rr = CsbRnn(CELL_LIGRU, 39, 512, [CsbMatrix(m.A, m.br, m.bc) for m in wl.W], bias)
     rr.upload()
-    res["ligru_sr3"] = {"batch1_streaming_us_per_frame": timed(rs, xd, 3), "batch1_resident_us_per_frame": timed(rr, xd, 20),
+    res["ligru_sr3"] = {"batch1_streaming_us_per_frame": timed(rs, xd, 3),
+                        "batch1_streaming_graph_replay_us_per_frame": round(graph_replay_ms(lambda: rs.forward(xd, want_hseq=True), 3, torch) * 1000.0 / T, 3),
+                        "batch1_resident_us_per_frame": timed(rr, xd, 20),
                         "nnz": sum(int(m.view()["nnz"]) for m in Ws), "resident_plan": rr.stats()}
     if with_cpu:
         res["ligru_sr3"]["cpu_baseline"] = cpu(csb_inputs.LIGRU, wl, 39, 512)
@@ -887,7 +888,9 @@ def cells_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
     res["gru_sr2"] = {"reset_before_streaming_us_per_frame": timed(rb, xd, 3),
                       "reset_before_resident_us_per_frame": timed(rbr, xd, 20),
                       "reset_before_resident_plan": rbr.stats(),
+                      "reset_before_streaming_graph_replay_us_per_frame": round(graph_replay_ms(lambda: rb.forward(xd, want_hseq=True), 3, torch) * 1000.0 / T, 3),
                       "reset_after_streaming_us_per_frame": timed(ga, xd, 3),
+                      "reset_after_streaming_graph_replay_us_per_frame": round(graph_replay_ms(lambda: ga.forward(xd, want_hseq=True), 3, torch) * 1000.0 / T, 3),
                       "reset_after_resident_us_per_frame": timed(gr, xd, 20),
                       "nnz": sum(int(m.view()["nnz"]) for m in Wg), "resident_plan": gr.stats()}
     if with_cpu:
