@@ -785,7 +785,8 @@ def lstmp_leg(torch, np, csb_inputs, CsbMatrix, CsbRnn, with_cpu):
         for m in Ws + Ps:
             m.upload()
         xd = torch.from_numpy(wl.x).cuda()
-        rnn.forward(xd, want_hseq=True)
+        for _ in range(3):              # (steady state: a streaming call that repeats its arguments records its launches once)
+            rnn.forward(xd, want_hseq=True)
         n = 3
         ms = time_region(lambda: rnn.forward(xd, want_hseq=True), n, torch) / n
         nnz = sum(int(m.view()["nnz"]) for m in Ws + Ps)

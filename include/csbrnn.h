@@ -415,7 +415,7 @@ int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hidden,
  * csb_rnn_create*: CSB_RNN_S = slots per lane of the resident layout (multiple
  * of 4), CSB_RNN_XCDS = use at least this many XCDs, CSB_RNN_POLL_DELAY = sleeps before the
  * first poll of a step, CSB_RNN_BATCH_PATH = "resident" or "batched": the path of a batch when
- * both are uploaded.
+ * both are uploaded, CSB_RNN_GRAPH = 0: csb_rnn_forward never records its launches (below).
  */
 typedef struct {
     int32_t resident;          /* 1 if a resident layout exists                            */
@@ -470,7 +470,13 @@ size_t csb_rnn_workspace_bytes(const csb_rnn *r, int32_t batch, int32_t T);
  * layout uploaded, the streaming path at batch 1 on row-owned plans (what csb_rnn_create lays
  * out) and the batched path are kernel launches only and MAY be captured and replayed, with new
  * contents in the captured buffers (call once before the capture: a kernel's first launch raises
- * its LDS limit, which is not a stream operation).  Calls on one handle
+ * its LDS limit, which is not a stream operation).  The library does the same by itself for the
+ * streaming path at batch 1: a call whose arguments (pointers, T, the matrices' uploads) repeat
+ * those of the call before records its launches into a HIP graph that the handle keeps -- a
+ * few milliseconds once, about 17 us per launch -- and calls with the same arguments replay it
+ * from then on, on `stream` (a replayed launch costs less than an enqueued one); the buffers'
+ * contents may change between such calls, anything else makes the call enqueue its launches
+ * as before, and so does a `stream` that is being captured.  Calls on one handle
  * must not overlap either (they share the workspace's exchange words).
  */
 int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0,

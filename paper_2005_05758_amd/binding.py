@@ -467,6 +467,16 @@ class CsbRnn:
                                      T, B, _dptr(self._ws), _stream_ptr(stream)))
         return hseq, hT, cT
 
+    def forward_into(self, x, h0, c0, hseq, hT, cT, stream=None):
+        """csb_rnn_forward into the caller's output tensors (hseq, cT may be None)."""
+        import torch
+        T, B, I = x.shape
+        need = self.workspace_bytes(B, T)
+        if self._ws is None or self._ws.numel() * 4 < need:
+            self._ws = torch.empty((need + 3) // 4 + 64, dtype=torch.float32, device=x.device)
+        _check(lib().csb_rnn_forward(self._h, _dptr(x, _f32()), _dptr(h0, _f32()), _dptr(c0, _f32()), _dptr(hseq, _f32()), _dptr(hT, _f32()),
+                                     _dptr(cT, _f32()), T, B, _dptr(self._ws), _stream_ptr(stream)))
+
     def close(self):
         if self._h:
             lib().csb_rnn_free(self._h)

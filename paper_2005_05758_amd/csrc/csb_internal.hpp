@@ -270,6 +270,7 @@ struct csb_matrix {
     csb::Plan plan;
     void *d_buf = nullptr;        // caller-owned device image, set by csb_upload
     bool uploaded = false;
+    uint64_t upload_serial = 0;   // a number no other upload of any matrix has had (what a recorded launch sequence was made for)
     // launch bookkeeping for the cross-workgroup merge (mutable: csb_spmv takes a const handle)
     mutable uint32_t epoch = 0;          // tag generation in which ws_seen was cleared
     mutable const void *ws_seen = nullptr;  // workspace already cleared for this matrix

@@ -105,6 +105,13 @@ struct csb_rnn {
     mutable int64_t ws_use = -1;             // batch and path of the last forward call (they fix what lies where)
     // tuning knobs, read from the environment once, when the handle is created
     int32_t knob_xcds = 0;                   // CSB_RNN_XCDS: use at least this many XCDs (0: as few as hold the model)
+    // The launches of the last streaming call (batch 1, row-owned plans: kernel launches only) as a
+    // HIP graph: a call that repeats its predecessor's arguments records them, later ones replay.
+    mutable hipGraphExec_t fwd_exec = nullptr;
+    mutable hipStream_t fwd_cap = nullptr;                       // the stream the launches are recorded on
+    mutable std::vector<uint64_t> fwd_key, fwd_last;             // arguments the graph was made for / of the last call
+    mutable bool fwd_failed = false;                             // recording did not work here once: not tried again
+    bool knob_graph = true;                  // CSB_RNN_GRAPH=0: every call enqueues its launches itself
     int32_t knob_poll_delay = -1;            // CSB_RNN_POLL_DELAY: sleeps before the first poll of a step (-1: default)
     int32_t knob_batch_path = 0;             // CSB_RNN_BATCH_PATH: 1 resident, 2 batched, 0 by estimate
     uint32_t poll_limit = 1u << 24;          // polls of one exchange word before the resident kernel gives up
@@ -116,8 +123,15 @@ struct csb_rnn {
         (void)hipGetLastError();             // (no device: the default stands)
         if (const char *e = getenv("CSB_RNN_XCDS")) knob_xcds = std::min(8, std::max(1, atoi(e)));
         if (const char *e = getenv("CSB_RNN_POLL_DELAY")) knob_poll_delay = std::max(0, atoi(e));
+        if (const char *e = getenv("CSB_RNN_GRAPH")) knob_graph = atoi(e) != 0;
         if (const char *e = getenv("CSB_RNN_BATCH_PATH")) knob_batch_path = !strcmp(e, "resident") ? 1 : !strcmp(e, "batched") ? 2 : 0;
     }
+    ~csb_rnn() {
+        if (fwd_exec) (void)hipGraphExecDestroy(fwd_exec);
+        if (fwd_cap) (void)hipStreamDestroy(fwd_cap);
+    }
+    csb_rnn(const csb_rnn &) = delete;
+    csb_rnn &operator=(const csb_rnn &) = delete;
 };
 
 namespace csb {
@@ -1398,7 +1412,7 @@ extern "C" size_t csb_rnn_workspace_bytes(const csb_rnn *r, int32_t batch, int32
     return csb::ws_layout(r, batch, T).total;
 }
 
-extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0,
+static int rnn_forward_enqueue(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0,
                                float *d_hseq, float *d_hT, float *d_cT, int32_t T, int32_t batch,
                                void *d_ws, void *stream) {
     using namespace csb;
@@ -1717,6 +1731,72 @@ extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
     return CSB_OK;
+}
+
+extern "C" int csb_rnn_forward(const csb_rnn *r, const float *d_x, const float *d_h0, const float *d_c0,
+                               float *d_hseq, float *d_hT, float *d_cT, int32_t T, int32_t batch,
+                               void *d_ws, void *stream) {
+    using namespace csb;
+    // The streaming path at batch 1 on row-owned plans is launch-bound, and every launch of it
+    // follows from the arguments alone.  The second call in a row with the same arguments records
+    // its launches into a HIP graph (on a stream of the handle's own), the calls after it replay
+    // the graph on the caller's stream: a replayed launch costs less than an enqueued one.  The
+    // buffers' contents are free to change between the calls; other arguments, a new upload of
+    // a matrix, or a caller who is capturing `stream` himself, and the call enqueues as ever.
+    hipStream_t st = (hipStream_t)stream;
+    bool graphable = r && r->knob_graph && !r->fwd_failed && batch == 1 && T > 0 && d_x && d_hT && d_ws && (uintptr_t)d_ws % 256 == 0 &&
+                     !(r->plan.valid && r->uploaded);
+    if (graphable) {
+        for (auto *m : r->W) graphable = graphable && m->plan.valid && m->uploaded && m->plan.stream.valid;
+        for (auto *m : r->Wp) graphable = graphable && m->plan.valid && m->uploaded && m->plan.stream.valid;
+    }
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (graphable && (hipStreamIsCapturing(st, &capturing) != hipSuccess || capturing != hipStreamCaptureStatusNone)) {
+        (void)hipGetLastError();
+        graphable = false;
+    }
+    if (!graphable) return rnn_forward_enqueue(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, batch, d_ws, stream);
+    std::vector<uint64_t> key = {(uint64_t)(uintptr_t)d_x, (uint64_t)(uintptr_t)d_h0, (uint64_t)(uintptr_t)d_c0, (uint64_t)(uintptr_t)d_hseq,
+                                 (uint64_t)(uintptr_t)d_hT, (uint64_t)(uintptr_t)d_cT, (uint64_t)(uintptr_t)d_ws, (uint64_t)T};
+    for (auto *m : r->W) { key.push_back((uint64_t)(uintptr_t)m->d_buf); key.push_back(m->upload_serial); }
+    for (auto *m : r->Wp) { key.push_back((uint64_t)(uintptr_t)m->d_buf); key.push_back(m->upload_serial); }
+    if (r->fwd_exec && key == r->fwd_key) {
+        workspace_changed_hands(d_ws, r);                    // (this handle is the workspace's user again)
+        hipError_t e = hipGraphLaunch(r->fwd_exec, st);
+        if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+        return CSB_OK;
+    }
+    if (key != r->fwd_last) {                                // new arguments: an ordinary call, remembered
+        r->fwd_last = key;
+        return rnn_forward_enqueue(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, batch, d_ws, stream);
+    }
+    // the same arguments as the call before: record, then replay
+    if (r->fwd_exec) { (void)hipGraphExecDestroy(r->fwd_exec); r->fwd_exec = nullptr; r->fwd_key.clear(); }
+    if (!r->fwd_cap && hipStreamCreateWithFlags(&r->fwd_cap, hipStreamNonBlocking) != hipSuccess) {
+        (void)hipGetLastError();
+        r->fwd_cap = nullptr;
+        return rnn_forward_enqueue(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, batch, d_ws, stream);
+    }
+    hipGraph_t graph = nullptr;
+    int rc = CSB_EDEVICE;
+    if (hipStreamBeginCapture(r->fwd_cap, hipStreamCaptureModeRelaxed) == hipSuccess) {
+        rc = rnn_forward_enqueue(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, batch, d_ws, (void *)r->fwd_cap);
+        if (hipStreamEndCapture(r->fwd_cap, &graph) != hipSuccess) { graph = nullptr; if (rc == CSB_OK) rc = CSB_EDEVICE; }
+    }
+    if (rc == CSB_OK && graph && hipGraphInstantiate(&r->fwd_exec, graph, nullptr, nullptr, 0) == hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        r->fwd_key = key;
+        hipError_t e = hipGraphLaunch(r->fwd_exec, st);
+        if (e != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+        return CSB_OK;
+    }
+    // recording failed (or the call is in error, which the ordinary call below reports): nothing has run
+    // yet; enqueue as ever, and this handle does not try again
+    if (graph) (void)hipGraphDestroy(graph);
+    (void)hipGetLastError();
+    r->fwd_exec = nullptr;
+    r->fwd_failed = true;
+    return rnn_forward_enqueue(r, d_x, d_h0, d_c0, d_hseq, d_hT, d_cT, T, batch, d_ws, stream);
 }
 
 extern "C" void csb_rnn_free(csb_rnn *r) { delete r; }

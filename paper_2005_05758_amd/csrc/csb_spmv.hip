@@ -622,8 +622,10 @@ extern "C" int csb_upload(csb_matrix *m, void *d_buf, size_t bytes, void *stream
     hipError_t e = hipMemcpyAsync(d_buf, m->plan.image.data(), m->plan.image.size(), hipMemcpyHostToDevice,
                                   (hipStream_t)stream);
     if (e != hipSuccess) { csb::set_error(std::string("csb_upload: ") + hipGetErrorString(e)); return CSB_EDEVICE; }
+    static std::atomic<uint64_t> serial{0};
     m->d_buf = d_buf;
     m->uploaded = true;
+    m->upload_serial = ++serial;
     return CSB_OK;
 }
 

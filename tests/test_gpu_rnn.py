@@ -196,6 +196,47 @@ def test_rnn_streaming_forward_replays_from_a_captured_graph(cell, L, B):
             assert float(np.max(np.abs(cT.cpu().numpy() - rcT))) <= TOL and torch.equal(cT, eager[2])
 
 
+@pytest.mark.parametrize("cell,L", [(csb_inputs.LSTM, 1), (csb_inputs.GRU, 2), (csb_inputs.LIGRU, 2)])
+def test_rnn_streaming_calls_that_repeat_their_arguments(cell, L):
+    """A streaming call that repeats its predecessor's arguments records its launches, later ones
+    replay them (csb_rnn_forward keeps the graph): six calls on the same buffers with new contents
+    each time, a call with other arguments (a shorter sequence) in the middle, a fresh upload of a
+    matrix near the end -- every result against the oracle."""
+    cfg = csb_inputs.RnnConfig("t", cell, L, 20, 72, 16, 3.0, "binomial", 0.3, 1, 8, 140 + L)
+    wl = csb_inputs.make_rnn(cfg)
+    W = [oracle.csb_decode(oracle.csb_encode(m.A, m.br, m.bc)) for m in wl.W]
+    Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+    rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, [torch.from_numpy(b).cuda() for b in wl.bias])
+    for w in Ws:
+        w.upload()
+    rng = np.random.default_rng(9)
+    xs = torch.zeros((8, 1, 20), dtype=torch.float32, device="cuda")
+    h0s = torch.zeros((L, 1, 72), dtype=torch.float32, device="cuda")
+    c0s = torch.zeros_like(h0s) if cell == csb_inputs.LSTM else None
+    hseq = torch.empty((8, 1, 72), dtype=torch.float32, device="cuda")
+    hT = torch.empty((L, 1, 72), dtype=torch.float32, device="cuda")
+    cT = torch.empty((L, 1, 72), dtype=torch.float32, device="cuda") if cell == csb_inputs.LSTM else None
+    for call in range(7):
+        T = 5 if call == 3 else 8
+        if call == 5:
+            Ws[0].upload()                                      # the same plan into a new buffer
+        x = rng.uniform(-1, 1, (8, 1, 20)).astype(np.float32)
+        h0 = rng.uniform(-0.5, 0.5, (L, 1, 72)).astype(np.float32)
+        c0 = rng.uniform(-0.5, 0.5, (L, 1, 72)).astype(np.float32)
+        xs.copy_(torch.from_numpy(x)); h0s.copy_(torch.from_numpy(h0))
+        if c0s is not None:
+            c0s.copy_(torch.from_numpy(c0))
+        rseq, rhT, rcT = oracle.rnn_forward(cfg.cell, W, wl.bias, x[:T], cfg.input, cfg.hidden, h0=h0.astype(np.float64),
+                                            c0=c0.astype(np.float64) if c0s is not None else None)
+        rnn.forward_into(xs[:T], h0s, c0s, hseq[:T], hT, cT)
+        torch.cuda.synchronize()
+        say(f"[rnn] repeated call {call} (T={T}): err {float(np.max(np.abs(hseq[:T].cpu().numpy() - rseq))):.3g}")
+        assert float(np.max(np.abs(hseq[:T].cpu().numpy() - rseq))) <= TOL
+        assert float(np.max(np.abs(hT.cpu().numpy() - rhT))) <= TOL
+        if cT is not None:
+            assert float(np.max(np.abs(cT.cpu().numpy() - rcT))) <= TOL
+
+
 @pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
 @pytest.mark.parametrize("L", [1, 2])
 def test_rnn_streaming_on_tile_layout_plans(cell, L):
