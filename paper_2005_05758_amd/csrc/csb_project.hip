@@ -363,7 +363,10 @@ __global__ __launch_bounds__(256) void masked_copy_vec_kernel(const float *W, co
         z.y = byte && (kc4 & 0xff00u) ? w[q].y : 0.0f;
         z.z = byte && (kc4 & 0xff0000u) ? w[q].z : 0.0f;
         z.w = byte && (kc4 & 0xff000000u) ? w[q].w : 0.0f;
-        *(float4 *)(Z + (size_t)(i0 + q) * ldz + c) = z;
+        // (written once and not read again here: stores that do not stay behind in the caches -- with
+        // ordinary stores the 256 MB of an 8192 x 8192 result were still on their way to memory when
+        // the next call's first kernel read its input: 73 us for it instead of 45, and 56 instead of 43 here)
+        __builtin_nontemporal_store(__builtin_bit_cast(vec4f, z), (vec4f *)(Z + (size_t)(i0 + q) * ldz + c));
     }
 }
 
