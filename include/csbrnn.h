@@ -506,9 +506,9 @@ size_t csb_project_workspace_bytes(int64_t rows, int64_t cols, int32_t br, int32
 int csb_project(const float *d_W, int64_t rows, int64_t cols, int64_t ld, int32_t br, int32_t bc,
                 double rate, float *d_Z, int64_t ldz, void *d_ws, void *stream);
 
-/* Release a handle (NULL is allowed).  The work of every call on it must have completed on its
- * stream: kernels in flight still read the handle's device image (the caller's buffer) and, for
- * csb_rnn_forward, may be launches of a recorded sequence that the handle owns. */
+/* Release a handle (NULL is allowed).  The work of every call on it should have completed on its
+ * stream: kernels in flight still read the handle's device image (the caller's buffer).
+ * csb_rnn_free waits for the device first when the handle holds a recorded launch sequence. */
 void csb_free(csb_matrix *m);
 void csb_rnn_free(csb_rnn *r);
 

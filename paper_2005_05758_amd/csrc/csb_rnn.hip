@@ -127,7 +127,8 @@ struct csb_rnn {
         if (const char *e = getenv("CSB_RNN_BATCH_PATH")) knob_batch_path = !strcmp(e, "resident") ? 1 : !strcmp(e, "batched") ? 2 : 0;
     }
     ~csb_rnn() {
-        if (fwd_exec) (void)hipGraphExecDestroy(fwd_exec);
+        // (a recorded sequence may still be running for a caller who frees early: let it finish first)
+        if (fwd_exec) { (void)hipDeviceSynchronize(); (void)hipGraphExecDestroy(fwd_exec); }
         if (fwd_cap) (void)hipStreamDestroy(fwd_cap);
     }
     csb_rnn(const csb_rnn &) = delete;
