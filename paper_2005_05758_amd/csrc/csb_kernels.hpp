@@ -122,15 +122,23 @@ int spmv_rows_gated_multi(const SpmvGatedCall *calls, int n, void *stream);
 // c_t (LSTM: c_in -> c_out) and h_t -> h_out (and hseq).  h_out is not h_prev.  The second segment
 // has the matrix's other columns; for the LSTM it need not be the cell's own output (LSTMP: it is
 // the projected state, and h_out receives m_t).
+// The reset-before GRU takes two such launches per step: kCellRbReset on its first matrix (rows r, z,
+// n over [input ; h_(t-1)]) writes q = sigmoid(a_r) h_(t-1) to h_out, z = sigmoid(a_z) to c_out and
+// the n row's sum (with its bias) to hseq; kCellRbGate on the second (Un, one row per unit, input q:
+// n0 = all columns) reads z from c_in, that sum from aux and h_(t-1) from h_state, and writes
+// h_t = (1 - z) tanh(sum + Un q) + z h_(t-1) to h_out (and hseq).
+constexpr int32_t kCellRbReset = 100, kCellRbGate = 101;
 struct SpmvCellCall {
     const csb_matrix *mat;
     const float *x0;
     uint32_t n0;
-    const float *h_prev;
-    int32_t cell;              // CSB_CELL_LSTM, CSB_CELL_GRU or CSB_CELL_LIGRU
+    const float *h_prev;       // the second input segment (any valid pointer if there is none)
+    int32_t cell;              // CSB_CELL_LSTM, CSB_CELL_GRU, CSB_CELL_LIGRU, kCellRbReset or kCellRbGate
     const float *bias;         // as the cell stacks them, or null
     const float *c_in;
     float *c_out, *h_out, *hseq;
+    const float *h_state = nullptr;   // h_(t-1) where it is not the second input segment
+    const float *aux = nullptr;
 };
 // ... for up to kMaxJobsPerLaunch layers at once (one value format for all).
 int spmv_rows_cell_multi(const SpmvCellCall *calls, int n, void *stream);

@@ -1313,6 +1313,9 @@ extern "C" int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hi
             for (csb_matrix *m : {Wa[l], Un[l]})
                 if (!m->plan.valid || m->plan.split.active()) {
                     m->stream_wg_limit = 256 / std::min(n_layers, kMaxJobsPerLaunch);   // the layers of a diagonal share a launch
+                    // (stacked layers: workgroups own whole units -- r, z, n rows of the first matrix, the one row
+                    // of the second -- and both launches of a step finish their part of the cell themselves)
+                    m->stream_cell_gates = n_layers >= 2 ? (m == Wa[l] ? 3 : 1) : 0;
                     int rc = plan_matrix(m, 0, 16, SplitSpec{}, nullptr, 0);
                     if (rc != CSB_OK) { delete r; return rc; }
                 }
@@ -1622,6 +1625,38 @@ static int rnn_forward_enqueue(const csb_rnn *r, const float *d_x, const float *
                       m->plan.hdr.cols <= (uint64_t)kMaxStageCols;
     for (auto *m : r->Wp)
         lstmp_units = lstmp_units && m->plan.stream.valid && m->plan.stream.cell_gates == 0 && m->plan.stream.val_fmt == r->Wp[0]->plan.stream.val_fmt;
+    bool rb_units = gru_rb;
+    for (auto *m : r->W)
+        rb_units = rb_units && m->plan.stream.valid && m->plan.stream.cell_gates == 3 && m->plan.stream.val_fmt == r->W[0]->plan.stream.val_fmt &&
+                   m->plan.hdr.cols <= (uint64_t)kMaxStageCols;
+    for (auto *m : r->Wp)
+        rb_units = rb_units && m->plan.stream.valid && m->plan.stream.cell_gates == 1 && m->plan.stream.val_fmt == r->Wp[0]->plan.stream.val_fmt;
+    if (rb_units) {
+        // reset-before GRU on such plans: the first launch leaves q = r h_(t-1), z and the n row's sum (in the
+        // layer's sums buffer), the second adds Un q and writes h_t
+        for (int d = 0; d < T + L - 1; ++d) {
+            const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
+            for (int l0 = lo; l0 <= hi_l; l0 += kMaxJobsPerLaunch) {
+                SpmvCellCall first[kMaxJobsPerLaunch], second[kMaxJobsPerLaunch];
+                const int n = std::min(kMaxJobsPerLaunch, hi_l - l0 + 1);
+                for (int i = 0; i < n; ++i) {
+                    const int l = l0 + i, t = d - l;
+                    float *zs = sums(l, t), *ns = zs + H, *q = zs + 2 * (size_t)H;
+                    first[i] = SpmvCellCall{r->W[l], l == 0 ? d_x + (size_t)t * I : h_buf(l - 1, t), l == 0 ? (uint32_t)I : (uint32_t)H,
+                                            h_buf(l, t - 1), kCellRbReset, r->d_bias[l], nullptr, zs, q, ns};
+                    second[i] = SpmvCellCall{r->Wp[l], q, (uint32_t)H, q, kCellRbGate, nullptr, zs, nullptr, h_buf(l, t),
+                                             (d_hseq && l == L - 1) ? d_hseq + (size_t)t * H : nullptr, h_buf(l, t - 1), ns};
+                }
+                int rc = spmv_rows_cell_multi(first, n, st);
+                if (rc == CSB_OK) rc = spmv_rows_cell_multi(second, n, st);
+                if (rc != CSB_OK) return rc;
+            }
+        }
+        for (int l = 0; l < L; ++l) init_state(d_hT + (size_t)l * H, h_buf(l, T - 1), (size_t)H, st);
+        hipError_t ec = hipGetLastError();
+        if (ec != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(ec)); return CSB_EDEVICE; }
+        return CSB_OK;
+    }
     if (lstmp_units) {
         // LSTMP on such plans: the gate product's launch finishes the cell (c_t, m_t = o tanh(c_t)), the
         // projection r_t = Wp m_t is a plain product (the last layer's straight into the output sequence)

@@ -341,7 +341,9 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
             // (what the cell needs from memory is asked for before the sums change hands)
             float b0 = 0.0f, b1 = 0.0f, b2 = 0.0f, b3 = 0.0f, prev = 0.0f;
             if (mine) {
-                if (c.bias) {
+                if (c.kind == kGateRbGate) {                   // what the reset launch left: z, and the n row's sum with its bias
+                    b0 = c.c_in[u]; b1 = c.a2[u];
+                } else if (c.bias) {
                     b0 = c.bias[u]; b1 = c.bias[H + u];
                     if (c.kind != 1u + CSB_CELL_LIGRU) b2 = c.bias[2u * H + u];
                     if (c.kind == 1u + CSB_CELL_LSTM) b3 = c.bias[3u * H + u];
@@ -351,7 +353,15 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
             float *rs = (float *)smem;                         // the staged vector is done with
             if (sub == 0u && rr < nrows) rs[rr] = s;
             lds_barrier();
-            if (mine) {
+            if (mine && c.kind == kGateRbGate) {               // reset-before GRU, second product: its one row per unit is Un q
+                const float hn = (1.0f - b0) * fast_tanh(b1 + rs[tid]) + b0 * prev;
+                c.h_out[u] = hn;
+                if (c.hseq) c.hseq[u] = hn;
+            } else if (mine && c.kind == kGateRbReset) {       // ... first product, rows r, z, n (input side): q = r h_(t-1) for the second
+                c.h_out[u] = fast_sigmoid(rs[tid] + b0) * prev;
+                c.c_out[u] = fast_sigmoid(rs[nu + tid] + b1);  // z, kept for the second launch
+                c.hseq[u] = rs[2u * nu + tid] + b2;            // the n row's sum with its bias, likewise
+            } else if (mine) {
                 const float a0 = rs[tid] + b0, a1 = rs[nu + tid] + b1;
                 float hn;
                 if (c.kind == 1u + CSB_CELL_LSTM) {            // rows i, f, g, o
@@ -529,9 +539,11 @@ int spmv_rows_cell_multi(const SpmvCellCall *calls, int n, void *stream) {
     for (int i = 0; i < n; ++i) {
         const SpmvCellCall &c = calls[i];
         const StreamPlan &sp = c.mat->plan.stream;
-        const uint32_t G = c.cell == CSB_CELL_LIGRU ? 2u : 4u;
+        const uint32_t kind = c.cell == kCellRbReset ? kGateRbReset : c.cell == kCellRbGate ? kGateRbGate : 1u + (uint32_t)c.cell;
+        const uint32_t G = kind == kGateRbGate ? 1u : kind == kGateRbReset ? 3u : c.cell == CSB_CELL_LIGRU ? 2u : 4u;
+        const bool own_state = c.cell == CSB_CELL_GRU || c.cell == CSB_CELL_LIGRU || kind == kGateRbReset;   // the second segment is h_(t-1), H wide
         if (!c.mat->plan.valid || !c.mat->uploaded || !sp.valid || sp.cell_gates != G || sp.val_fmt != calls[0].mat->plan.stream.val_fmt ||
-            (uint64_t)c.n0 >= (uint64_t)c.mat->cols || (c.cell != CSB_CELL_LSTM && (uint64_t)c.n0 + sp.cell_units != (uint64_t)c.mat->cols)) {
+            (uint64_t)c.n0 > (uint64_t)c.mat->cols || (own_state && (uint64_t)c.n0 + sp.cell_units != (uint64_t)c.mat->cols)) {
             set_error("csb_spmv: matrix is not laid out for a cell of this kind");
             return CSB_ESTATE;
         }
@@ -541,8 +553,9 @@ int spmv_rows_cell_multi(const SpmvCellCall *calls, int n, void *stream) {
         A.n0 = c.n0;
         A.g0 = plain_src(c.x0); A.g0.H = G;
         A.g1 = plain_src(c.h_prev);
-        A.g1.H = sp.cell_units; A.g1.kind = 1u + (uint32_t)c.cell; A.g1.bias = c.bias;
-        A.g1.c_in = c.c_in; A.g1.h_in = c.h_prev; A.g1.c_out = c.c_out; A.g1.h_out = c.h_out; A.g1.hseq = c.hseq;
+        A.g1.H = sp.cell_units; A.g1.kind = kind; A.g1.bias = c.bias;
+        A.g1.c_in = c.c_in; A.g1.h_in = c.h_state ? c.h_state : c.h_prev; A.g1.c_out = c.c_out; A.g1.h_out = c.h_out; A.g1.hseq = c.hseq;
+        A.g1.a2 = c.aux;
         lds = std::max(lds, l);
         wgs = std::max(wgs, A.n_wg);
         rounds = std::max(rounds, A.n_rounds);
