@@ -382,8 +382,8 @@ int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hidden, int32_
  * (csb_rnn_upload): one kernel launch for the whole sequence, a layer being a reset stage
  * (row r, output r * h_(t-1)) and a gate stage (rows z and n, the latter over the layer input
  * and the reset stage's output of the same step); else the streaming paths: per step two
- * CSB product launches that do the element-wise parts themselves at batch 1 (stacked layers:
- * on plans whose workgroups own whole units, as for csb_rnn_create), two products and two
+ * CSB product launches that do the element-wise parts themselves at batch 1 (on plans whose
+ * workgroups own whole units, as csb_rnn_create makes them for stacked layers), two products and two
  * element-wise kernels on the matrix cores at batch > 1.
  * Errors as csb_rnn_create.
  */

@@ -1313,9 +1313,11 @@ extern "C" int csb_rnn_create_gru_rb(int32_t n_layers, int32_t input, int32_t hi
             for (csb_matrix *m : {Wa[l], Un[l]})
                 if (!m->plan.valid || m->plan.split.active()) {
                     m->stream_wg_limit = 256 / std::min(n_layers, kMaxJobsPerLaunch);   // the layers of a diagonal share a launch
-                    // (stacked layers: workgroups own whole units -- r, z, n rows of the first matrix, the one row
-                    // of the second -- and both launches of a step finish their part of the cell themselves)
-                    m->stream_cell_gates = n_layers >= 2 ? (m == Wa[l] ? 3 : 1) : 0;
+                    // (workgroups own whole units -- r, z, n rows of the first matrix, the one row of the second --
+                    // and both launches of a step finish their part of the cell themselves; for this cell
+                    // also with one layer: measured, us per step, consumer-side / whole units: 39 -> 1024
+                    // 8.43 / 7.52, 153 -> 512 7.91 / 7.11, 64 -> 256 7.39 / 7.12)
+                    m->stream_cell_gates = m == Wa[l] ? 3 : 1;
                     int rc = plan_matrix(m, 0, 16, SplitSpec{}, nullptr, 0);
                     if (rc != CSB_OK) { delete r; return rc; }
                 }
