@@ -1208,15 +1208,16 @@ extern "C" int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int
                 // (a plan the caller made keeps its workgroup count and mode)
                 const bool had = W[l]->plan.valid;
                 W[l]->stream_wg_limit = 256 / std::min(n_layers, kMaxJobsPerLaunch);   // the layers of a diagonal share a launch
-                // Stacked layers (and very wide ones): a workgroup of the row-owned plan owns units with
-                // all their gate rows (r, z and the two halves of n for the GRU), and the streaming
-                // step's launches finish their cells themselves.  Otherwise a cell is computed where
-                // its output is consumed, by every workgroup while its weights are on their way:
-                // measured, us per step, consumer-side / whole units: LSTM 153->512 x 1 5.06 / 5.68,
-                // x 2 6.66 / 5.77, x 3 6.68 / 5.89; 153->2048 x 1 6.73 / 6.29; GRU 256->1024 x 1
-                // 5.73 / 5.62, x 2 6.81 / 5.88; Li-GRU 256->1024 x 1 5.23 / 5.50 (with stacked layers
-                // a cell has two consumers, and both would compute it).
-                W[l]->stream_cell_gates = (n_layers >= 2 || hidden >= 2048) ? (cell == CSB_CELL_LIGRU ? 2 : 4) : 0;
+                // A workgroup of the row-owned plan owns units with all their gate rows (r, z and the two
+                // halves of n for the GRU), and the streaming step's launches finish their cells
+                // themselves (the other form -- a cell computed where its output is consumed, by every
+                // workgroup while its weights are on their way -- remains for plans the caller makes).
+                // Measured in a loop over the same buffers (launches replayed from the handle's graph), us
+                // per step, consumer-side / whole units: LSTM 64->128 3.81 / 3.62, 153->512 4.14 / 3.94,
+                // 153->1024 4.45 / 4.29; GRU 256->1024 4.76 / 4.01; Li-GRU 256->1024 4.29 / 3.92; with
+                // stacked layers, where a cell has two consumers, 12-17 % apart.  (Enqueued from the host
+                // one call at a time, single layers were the other way round: 5.06 / 5.68 for 153->512.)
+                W[l]->stream_cell_gates = cell == CSB_CELL_LIGRU ? 2 : 4;
                 int rc = plan_matrix(W[l], had ? W[l]->plan.req_chunks : 0, 16, sp, nullptr, had ? W[l]->plan.req_mode : 0);
                 if (rc != CSB_OK) { delete r; return rc; }
             }
@@ -1254,11 +1255,11 @@ extern "C" int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hid
             for (csb_matrix *m : {W[l], Wp[l]})
                 if (!m->plan.valid || m->plan.split.active()) {
                     m->stream_wg_limit = 256 / std::min(n_layers, kMaxJobsPerLaunch);   // the layers of a diagonal share a launch
-                    // (stacked layers, the gate matrix: workgroups own whole units, the launch of the gate product
-                    // leaves m_t = o tanh(c_t) behind and the projection is a plain product of it; measured on
-                    // the 153 -> 1024 -> 512 shape, us per frame, consumer-side / whole units: two layers 10.65 /
-                    // 10.28, one layer 8.96 / 9.98)
-                    m->stream_cell_gates = (m == W[l] && n_layers >= 2) ? 4 : 0;
+                    // (the gate matrix: workgroups own whole units, the launch of the gate product leaves
+                    // m_t = o tanh(c_t) behind and the projection is a plain product of it; measured on the
+                    // 153 -> 1024 -> 512 shape in a loop over the same buffers, us per frame, consumer-side /
+                    // whole units: one layer 7.71 / 7.24)
+                    m->stream_cell_gates = m == W[l] ? 4 : 0;
                     int rc = plan_matrix(m, 0, 16, SplitSpec{}, nullptr, 0);
                     if (rc != CSB_OK) { delete r; return rc; }
                 }

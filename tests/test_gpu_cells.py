@@ -23,7 +23,7 @@ def say(msg):
     sys.stdout.flush()
 
 
-def build(wl, resident):
+def build(wl, resident, replan=False):
     cfg = wl.cfg
     bias = [torch.from_numpy(b).cuda() for b in wl.bias]
     if cfg.cell == csb_inputs.LIGRU:
@@ -43,21 +43,22 @@ def build(wl, resident):
         rnn.upload()
     else:
         for m in mats:
-            # stacked layers: plans whose workgroups own whole units (the step's launches finish their cells)
-            # (the reset-before GRU also with one layer)
-            assert m.plan_stats()["row_owned"] == (2 if cfg.n_layers >= 2 or cfg.cell == csb_inputs.GRU_RB else 1)
+            # plans whose workgroups own whole units (the step's launches finish their cells)
+            assert m.plan_stats()["row_owned"] == 2
+            if replan:                        # a plan of the caller's: plain row ranges, cells computed where they are consumed
+                assert m.plan_rows(0, 0)["row_owned"] == 1
             m.validate()
             m.upload()
     return rnn
 
 
-def run_case(wl, h0=None, tag="", resident=False):
+def run_case(wl, h0=None, tag="", resident=False, replan=False):
     cfg = wl.cfg
     T, B, _ = wl.x.shape
     L = cfg.n_layers
     say(f"[cells] {tag} cell={cfg.cell} L={L} I={cfg.input} H={cfg.hidden} T={T} B={B} resident={resident}")
     rseq, rhT, _ = oracle.rnn_forward(cfg.cell, [m.A for m in wl.W], wl.bias, wl.x, cfg.input, cfg.hidden, h0=h0)
-    rnn = build(wl, resident)
+    rnn = build(wl, resident, replan)
     h0d = None if h0 is None else torch.from_numpy(h0.astype(np.float32)).cuda()
     hseq, hT, cT = rnn.forward(torch.from_numpy(wl.x).cuda(), h0d)
     torch.cuda.synchronize()
@@ -90,6 +91,16 @@ def test_ligru_small(L, I, H, T, B, block):
     if B == 1:
         run_case(wl, h0, tag="ligru-resident", resident=True)
         run_case(wl, None, tag="ligru-resident-zero-state", resident=True)
+
+
+@pytest.mark.parametrize("cell", [csb_inputs.LIGRU, csb_inputs.GRU_RB])
+@pytest.mark.parametrize("L,I,H,T,block", [(1, 40, 100, 12, 32), (2, 33, 300, 9, 32), (5, 9, 16, 6, 8)])
+def test_cells_on_plans_the_caller_makes(cell, L, I, H, T, block):
+    """Matrices planned again by the caller (plain row ranges instead of the whole units
+    csb_rnn_create lays out): the streaming step computes a cell where its output is consumed."""
+    wl = workload(cell, L, I, H, T, 1, block, seed=60 + L + I, sigma=min(0.3, 1.2 / np.sqrt(I + H)))   # (keeps the unbounded Li-GRU state tame)
+    h0 = np.random.default_rng(2).uniform(-0.5, 0.5, (L, 1, H)).astype(np.float32).astype(np.float64)
+    run_case(wl, h0, tag="caller-planned", replan=True)
 
 
 @pytest.mark.parametrize("L,I,H,T,B,block", SHAPES)

@@ -20,7 +20,7 @@ def say(msg):
     sys.stdout.flush()
 
 
-def build(wl, resident=False):
+def build(wl, resident=False, replan=False):
     """resident=True: upload the on-chip layout (one launch for the whole sequence, batch 1);
     else upload the matrices (mat-vec / mat-mat launches per step)."""
     Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
@@ -32,12 +32,14 @@ def build(wl, resident=False):
         rnn.upload()
     else:
         for m in Ws + Ps:
+            if replan:                        # a plan of the caller's: plain row ranges, the cell computed where it is consumed
+                assert m.plan_rows(0, 0)["row_owned"] == 1
             m.validate()
             m.upload()
     return rnn
 
 
-def run_case(wl, h0=None, c0=None, tag="", resident=None):
+def run_case(wl, h0=None, c0=None, tag="", resident=None, replan=False):
     T, B, _ = wl.x.shape
     L = len(wl.W)
     if resident is None:                      # both device paths where both apply
@@ -49,7 +51,7 @@ def run_case(wl, h0=None, c0=None, tag="", resident=None):
     W = [m.A for m in wl.W]
     Wp = [m.A for m in wl.Wp]
     rseq, rhT, rcT = oracle.lstmp_forward(W, Wp, wl.bias, wl.x, wl.input, wl.hidden, wl.proj, h0=h0, c0=c0)
-    rnn = build(wl, resident)
+    rnn = build(wl, resident, replan)
     h0d = None if h0 is None else torch.from_numpy(h0.astype(np.float32)).cuda()
     c0d = None if c0 is None else torch.from_numpy(c0.astype(np.float32)).cuda()
     hseq, hT, cT = rnn.forward(torch.from_numpy(wl.x).cuda(), h0d, c0d)
@@ -74,6 +76,18 @@ def test_lstmp_small(L, I, H, P, T, B, block):
     c0 = rng.uniform(-0.5, 0.5, (L, B, H)).astype(np.float32).astype(np.float64)
     run_case(wl, h0, c0, tag="small")
     run_case(wl, tag="small-zero-state")
+
+
+@pytest.mark.parametrize("L,I,H,P,T,block", [(1, 40, 100, 37, 12, 32), (2, 33, 300, 130, 9, 32), (5, 10, 16, 12, 6, 8)])
+def test_lstmp_on_plans_the_caller_makes(L, I, H, P, T, block):
+    """Matrices planned again by the caller (plain row ranges instead of the whole units
+    csb_rnn_create_lstmp lays the gate matrices out in): the projection's launch computes the cell
+    on its way in."""
+    wl = csb_inputs.make_lstmp(60 + L + I, L, I, H, P, block, 3.0, T, 1, sigma=0.3)
+    rng = np.random.default_rng(2)
+    h0 = rng.uniform(-0.5, 0.5, (L, 1, P)).astype(np.float32).astype(np.float64)
+    c0 = rng.uniform(-0.5, 0.5, (L, 1, H)).astype(np.float32).astype(np.float64)
+    run_case(wl, h0, c0, tag="caller-planned", resident=False, replan=True)
 
 
 def test_lstmp_speech_model_shape_batch1():

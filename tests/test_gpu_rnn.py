@@ -77,6 +77,27 @@ def test_rnn_small(cell, L, I, H, T, B, block):
     run_case(wl, tag="small-zero-state")
 
 
+@pytest.mark.parametrize("cell,L", [(csb_inputs.GRU, 1), (csb_inputs.GRU, 3), (csb_inputs.LIGRU, 2)])
+def test_rnn_cells_computed_where_they_are_consumed(cell, L):
+    """GRU and Li-GRU steps on plans the caller makes (plain row ranges; the GRU's keep the row
+    split of its step): the launches that consume a cell's output compute it on their way in."""
+    cfg = csb_inputs.RnnConfig("t", cell, L, 24, 96, 16, 3.0, "binomial", 0.3, 1, 7, 150 + L)
+    wl = csb_inputs.make_rnn(cfg)
+    W = [oracle.csb_decode(oracle.csb_encode(m.A, m.br, m.bc)) for m in wl.W]
+    rseq, rhT, rcT = oracle.rnn_forward(cfg.cell, W, wl.bias, wl.x, cfg.input, cfg.hidden)
+    Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
+    rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, [torch.from_numpy(b).cuda() for b in wl.bias])
+    for w in Ws:
+        assert w.plan_stats()["row_owned"] == 2
+        assert w.plan()["row_owned"] == 1                      # (csb_plan keeps a GRU matrix's row split)
+        w.validate()
+        w.upload()
+    hseq, hT, cT = rnn.forward(torch.from_numpy(wl.x).cuda())
+    torch.cuda.synchronize()
+    assert float(np.max(np.abs(hseq.cpu().numpy() - rseq))) <= TOL
+    assert float(np.max(np.abs(hT.cpu().numpy() - rhT))) <= TOL
+
+
 @pytest.mark.parametrize("L", [1, 2])
 @pytest.mark.parametrize("n_wg,rounds", [(0, 3), (2, 2), (5, 4), (1, 1)])
 def test_rnn_streaming_on_row_owned_plans_of_the_callers_choosing(L, n_wg, rounds):

@@ -414,7 +414,7 @@ def test_gru_step_matrices_get_the_row_owned_layout(I, H, block, layers):
     rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, None)
     for w in Ws:
         st = w.plan_stats()
-        assert st["row_owned"] == (2 if layers >= 2 else 1), st     # stacked layers: workgroups own whole units
+        assert st["row_owned"] == 2, st                             # workgroups own whole units
         w.validate()
     del rnn
 
@@ -422,8 +422,8 @@ def test_gru_step_matrices_get_the_row_owned_layout(I, H, block, layers):
 @pytest.mark.parametrize("cell,I,H,block,layers", [
     (csb_inputs.LSTM, 20, 48, 16, 2), (csb_inputs.GRU, 33, 64, 32, 3), (csb_inputs.LIGRU, 7, 40, 8, 2),
     (csb_inputs.LSTM, 5, 2048, 64, 1), (csb_inputs.LSTM, 64, 300, 16, 2), (csb_inputs.GRU, 12, 96, 32, 1)])
-def test_stacked_layers_get_plans_whose_workgroups_own_whole_units(cell, I, H, block, layers):
-    """csb_rnn_create lays the matrices of stacked (or very wide) layers out so that a workgroup
+def test_rnn_handles_get_plans_whose_workgroups_own_whole_units(cell, I, H, block, layers):
+    """csb_rnn_create lays its matrices out so that a workgroup
     owns units with all their gate rows (the streaming step then finishes its cells in the
     product's launch): the section decodes to the matrix (csb_plan_validate walks it with the
     unit-to-row mapping), and a plan the caller makes afterwards owns plain row ranges again."""
@@ -432,10 +432,9 @@ def test_stacked_layers_get_plans_whose_workgroups_own_whole_units(cell, I, H, b
     wl = csb_inputs.make_rnn(cfg)
     Ws = [CsbMatrix(m.A, m.br, m.bc) for m in wl.W]
     rnn = CsbRnn(cfg.cell, cfg.input, cfg.hidden, Ws, None)
-    want = 2 if (layers >= 2 or H >= 2048) else 1
     for w in Ws:
         st = w.plan_stats()
-        assert st["row_owned"] == want, st
+        assert st["row_owned"] == 2, st
         w.validate()
     if cell != csb_inputs.GRU:              # (a GRU's matrices keep their row split, and with it the handle's layout rules)
         st = Ws[0].plan()
