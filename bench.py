@@ -309,9 +309,9 @@ def main():
     ms2 = time_region(lambda: rnn2.forward(xd, want_hseq=True), 5, torch) / 5
     streaming = {"us_per_timestep": round(ms2 * 1000.0 / T, 3),
                  "gbps_algorithmic": round(bytes_step / (ms2 * 1e-3 / T) / 1e9, 2),
-                 "note": "csb_rnn_forward without the resident layout: one csb spmv launch per step and layer, the gates computed "
-                         "while it stages its input; timed in a loop over the same buffers, where the call replays the HIP "
-                         "graph of its launches that the handle keeps"}
+                 "note": "csb_rnn_forward without the resident layout: one csb spmv launch per step and layer, which also "
+                         "finishes the cells of its units; timed in a loop over the same buffers, where the call replays "
+                         "the HIP graph of its launches that the handle keeps"}
     # the same call captured once into a HIP graph and replayed (the streaming path is kernel
     # launches only: nothing in it depends on the host)
     ms3 = graph_replay_ms(lambda: rnn2.forward(xd, want_hseq=True), 5, torch)

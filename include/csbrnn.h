@@ -95,8 +95,8 @@ typedef struct {
     int32_t row_owned;       /* 1: csb_spmv runs the row-owned layout (below); the figures above
                                 then describe that layout.  2: the same layout with every
                                 workgroup owning whole units of a recurrent cell (all their
-                                gate rows), which csb_rnn_create gives the matrices of stacked
-                                layers: the streaming step reads it, csb_spmv the tile sections */
+                                gate rows), which csb_rnn_create* give their matrices: the
+                                streaming step reads it, csb_spmv the tile sections       */
     int32_t rounds;          /* row-owned layout: rounds per workgroup                   */
     int32_t reserved;
     int64_t matvec_bytes;    /* bytes of the device image one csb_spmv launch reads      */
@@ -337,13 +337,13 @@ int csb_sharing_model(const csb_matrix *m, int32_t P, int32_t Q, int32_t K, int3
  * d_bias[l] of G*hidden floats (d_bias NULL or d_bias[l] NULL = zero bias).
  * Each W[l] must be packed; it is planned by this call if it is not yet, in the layout
  * the step kernels need (the GRU keeps the input-side and recurrent-side sums of its n
- * rows apart; in a model of several layers, whose products share launches, a matrix is laid
- * out for its share of the compute units: at most 256 / min(n_layers, 4) workgroups in the
- * row-owned layout, each of which then owns whole units with all their gate rows, so that a
- * step of the streaming path is one launch that finishes its cells -- csb_plan_stats.row_owned
- * = 2; the same for layers of 2048 units or more; csb_plan* on the matrix afterwards plans
- * plain row ranges for all compute units again, which the step kernels run on as well).  Upload
- * each W[l] afterwards with csb_upload.
+ * rows apart; a workgroup of the row-owned layout owns whole units with all their gate rows,
+ * so that a step of the streaming path is one launch that finishes its cells --
+ * csb_plan_stats.row_owned = 2; in a model of several layers, whose products share launches, a
+ * matrix is laid out for its share of the compute units: at most 256 / min(n_layers, 4)
+ * workgroups; csb_plan* on the matrix afterwards plans plain row ranges for all compute units
+ * again, which the step kernels run on as well, computing a cell where its output is consumed).
+ * Upload each W[l] afterwards with csb_upload.
  */
 int csb_rnn_create(int32_t cell, int32_t n_layers, int32_t input, int32_t hidden,
                    csb_matrix *const *W, const float *const *d_bias, csb_rnn **out);
@@ -383,7 +383,7 @@ int csb_rnn_create_lstmp(int32_t n_layers, int32_t input, int32_t hidden, int32_
  * (row r, output r * h_(t-1)) and a gate stage (rows z and n, the latter over the layer input
  * and the reset stage's output of the same step); else the streaming paths: per step two
  * CSB product launches that do the element-wise parts themselves at batch 1 (on plans whose
- * workgroups own whole units, as csb_rnn_create makes them for stacked layers), two products and two
+ * workgroups own whole units, as csb_rnn_create makes them), two products and two
  * element-wise kernels on the matrix cores at batch > 1.
  * Errors as csb_rnn_create.
  */
