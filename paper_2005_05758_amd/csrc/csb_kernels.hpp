@@ -132,7 +132,8 @@ struct SpmvCellCall {
     const csb_matrix *mat;
     const float *x0;
     uint32_t n0;
-    const float *h_prev;       // the second input segment (any valid pointer if there is none)
+    const float *h_prev;       // the second input segment (any valid pointer if there is none); null: zeros
+                               // (LSTM, GRU, Li-GRU; c_in null likewise: the state of a sequence that starts at zero)
     int32_t cell;              // CSB_CELL_LSTM, CSB_CELL_GRU, CSB_CELL_LIGRU, kCellRbReset or kCellRbGate
     const float *bias;         // as the cell stacks them, or null
     const float *c_in;

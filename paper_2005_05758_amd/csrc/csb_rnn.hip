@@ -1598,10 +1598,23 @@ static int rnn_forward_enqueue(const csb_rnn *r, const float *d_x, const float *
     auto sums2 = [&](int l, int t) { return sums(l, t) + wl.rows_out; };       // reset-before GRU: Un q
     auto c_of = [&](int l, int t) { return fs + (((size_t)l * 2 + (size_t)(t & 1)) * 2) * SW; };
     auto h_buf = [&](int l, int t) { return c_of(l, t) + SW; };
-    for (int l = 0; l < L; ++l) {
-        init_state(h_buf(l, -1), d_h0 ? d_h0 + (size_t)l * HS : nullptr, (size_t)HS, st);
-        if (lstm) init_state(c_of(l, -1), d_c0 ? d_c0 + (size_t)l * H : nullptr, (size_t)H, st);
-    }
+    // Row-owned plans whose workgroups own whole units (what csb_rnn_create lays out for these
+    // cells): a launch is the whole step of its layers -- product, then c_t and h_t by the workgroup
+    // that has the unit's sums -- and its input is two vectors that are already in memory.
+    bool whole_units = !lstmp && !gru_rb;
+    for (auto *m : r->W)
+        whole_units = whole_units && m->plan.stream.valid && m->plan.stream.cell_gates != 0 && m->plan.stream.val_fmt == r->W[0]->plan.stream.val_fmt &&
+                      m->plan.hdr.cols <= (uint64_t)kMaxStageCols;
+    // ... and then the first step reads the caller's initial state where it lies (or none: zeros) and the
+    // last step writes the caller's final state: no launch besides the steps -- unless the caller's
+    // initial and final states share memory
+    auto overlap = [&](const float *a, const float *b) { const size_t n = (size_t)L * H; return a && b && a < b + n && b < a + n; };
+    const bool direct = whole_units && !overlap(d_h0, d_hT) && !overlap(d_c0, d_cT) && !overlap(d_h0, d_cT) && !overlap(d_c0, d_hT);
+    if (!direct)
+        for (int l = 0; l < L; ++l) {
+            init_state(h_buf(l, -1), d_h0 ? d_h0 + (size_t)l * HS : nullptr, (size_t)HS, st);
+            if (lstm) init_state(c_of(l, -1), d_c0 ? d_c0 + (size_t)l * H : nullptr, (size_t)H, st);
+        }
     // LSTMP: r_(l,t), the projected output, is a plain vector (the result of the layer's second
     // product); the last layer's goes straight into the output sequence when one is asked for
     auto r_of = [&](int l, int t) { return (t >= 0 && d_hseq && l == L - 1) ? d_hseq + (size_t)t * HS : h_buf(l, t); };
@@ -1615,13 +1628,6 @@ static int rnn_forward_enqueue(const csb_rnn *r, const float *d_x, const float *
         g.kind = gru_rb ? kGateRbGate : 1u + (uint32_t)r->cell; g.H = (uint32_t)H;
         return g;
     };
-    // Row-owned plans whose workgroups own whole units (what csb_rnn_create lays out for these
-    // cells): a launch is the whole step of its layers -- product, then c_t and h_t by the workgroup
-    // that has the unit's sums -- and its input is two vectors that are already in memory.
-    bool whole_units = !lstmp && !gru_rb;
-    for (auto *m : r->W)
-        whole_units = whole_units && m->plan.stream.valid && m->plan.stream.cell_gates != 0 && m->plan.stream.val_fmt == r->W[0]->plan.stream.val_fmt &&
-                      m->plan.hdr.cols <= (uint64_t)kMaxStageCols;
     bool lstmp_units = lstmp;
     for (auto *m : r->W)
         lstmp_units = lstmp_units && m->plan.stream.valid && m->plan.stream.cell_gates == 4 && m->plan.stream.val_fmt == r->W[0]->plan.stream.val_fmt &&
@@ -1691,6 +1697,14 @@ static int rnn_forward_enqueue(const csb_rnn *r, const float *d_x, const float *
         return CSB_OK;
     }
     if (whole_units) {
+        auto hs = [&](int l, int t) -> float * { return (direct && t == T - 1) ? d_hT + (size_t)l * H : h_buf(l, t); };
+        auto h_before = [&](int l, int t) -> const float * {
+            return (t > 0 || !direct) ? hs(l, t - 1) : d_h0 ? d_h0 + (size_t)l * H : nullptr;
+        };
+        auto c_before = [&](int l, int t) -> const float * {
+            return (t > 0 || !direct) ? c_of(l, t - 1) : d_c0 ? d_c0 + (size_t)l * H : nullptr;
+        };
+        auto c_after = [&](int l, int t) -> float * { return (direct && t == T - 1 && d_cT) ? d_cT + (size_t)l * H : c_of(l, t); };
         for (int d = 0; d < T + L - 1; ++d) {
             const int lo = std::max(0, d - (T - 1)), hi_l = std::min(L - 1, d);
             for (int l0 = lo; l0 <= hi_l; l0 += kMaxJobsPerLaunch) {
@@ -1698,19 +1712,20 @@ static int rnn_forward_enqueue(const csb_rnn *r, const float *d_x, const float *
                 const int n = std::min(kMaxJobsPerLaunch, hi_l - l0 + 1);
                 for (int i = 0; i < n; ++i) {
                     const int l = l0 + i, t = d - l;
-                    calls[i] = SpmvCellCall{r->W[l], l == 0 ? d_x + (size_t)t * I : h_buf(l - 1, t), l == 0 ? (uint32_t)I : (uint32_t)H,
-                                            h_buf(l, t - 1), (int32_t)r->cell, r->d_bias[l], lstm ? c_of(l, t - 1) : nullptr,
-                                            lstm ? c_of(l, t) : nullptr, h_buf(l, t),
+                    calls[i] = SpmvCellCall{r->W[l], l == 0 ? d_x + (size_t)t * I : hs(l - 1, t), l == 0 ? (uint32_t)I : (uint32_t)H,
+                                            h_before(l, t), (int32_t)r->cell, r->d_bias[l], lstm ? c_before(l, t) : nullptr,
+                                            lstm ? c_after(l, t) : nullptr, hs(l, t),
                                             (d_hseq && l == L - 1) ? d_hseq + (size_t)t * H : nullptr};
                 }
                 int rc = spmv_rows_cell_multi(calls, n, st);
                 if (rc != CSB_OK) return rc;
             }
         }
-        for (int l = 0; l < L; ++l) {
-            init_state(d_hT + (size_t)l * H, h_buf(l, T - 1), (size_t)H, st);
-            if (lstm && d_cT) init_state(d_cT + (size_t)l * H, c_of(l, T - 1), (size_t)H, st);
-        }
+        if (!direct)
+            for (int l = 0; l < L; ++l) {
+                init_state(d_hT + (size_t)l * H, h_buf(l, T - 1), (size_t)H, st);
+                if (lstm && d_cT) init_state(d_cT + (size_t)l * H, c_of(l, T - 1), (size_t)H, st);
+            }
         hipError_t ec = hipGetLastError();
         if (ec != hipSuccess) { set_error(std::string("csb_rnn_forward: ") + hipGetErrorString(ec)); return CSB_EDEVICE; }
         return CSB_OK;

@@ -151,7 +151,10 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
         const uint8_t *p0 = (const uint8_t *)A.g0.a, *p1 = (const uint8_t *)A.g1.a;
         for (uint32_t u = wave; u * 64u < A.cols; u += kStreamWaves) {
             const uint32_t e = u * 64u + lane;
-            if (e < A.cols) dma4(e < A.n0 ? p0 + 4u * e : p1 + 4u * (e - A.n0), lds0 + u * 256u);
+            if (e < A.cols) {
+                if (e < A.n0 || p1) dma4(e < A.n0 ? p0 + 4u * e : p1 + 4u * (e - A.n0), lds0 + u * 256u);
+                else ((float *)smem)[e] = 0.0f;                 // no second segment in memory: a state that starts at zero
+            }
         }
     } else if constexpr (GATED) {
         // (the segment's first units are requested below, before the cell arithmetic, whose loads
@@ -348,7 +351,8 @@ __device__ __forceinline__ void rows_body(const RowsArgs &A, const uint32_t wg) 
                     if (c.kind != 1u + CSB_CELL_LIGRU) b2 = c.bias[2u * H + u];
                     if (c.kind == 1u + CSB_CELL_LSTM) b3 = c.bias[3u * H + u];
                 }
-                prev = c.kind == 1u + CSB_CELL_LSTM ? c.c_in[u] : c.h_in[u];
+                const float *pv = c.kind == 1u + CSB_CELL_LSTM ? c.c_in : c.h_in;
+                if (pv) prev = pv[u];                          // (null: the state starts at zero)
             }
             float *rs = (float *)smem;                         // the staged vector is done with
             if (sub == 0u && rr < nrows) rs[rr] = s;

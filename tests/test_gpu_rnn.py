@@ -256,6 +256,22 @@ def test_rnn_streaming_calls_that_repeat_their_arguments(cell, L):
         assert float(np.max(np.abs(hT.cpu().numpy() - rhT))) <= TOL
         if cT is not None:
             assert float(np.max(np.abs(cT.cpu().numpy() - rcT))) <= TOL
+    # the final state written over the initial one (the same tensors for both), one step and several
+    for T in (1, 6):
+        x = rng.uniform(-1, 1, (8, 1, 20)).astype(np.float32)
+        h0 = rng.uniform(-0.5, 0.5, (L, 1, 72)).astype(np.float32)
+        c0 = rng.uniform(-0.5, 0.5, (L, 1, 72)).astype(np.float32)
+        xs.copy_(torch.from_numpy(x)); h0s.copy_(torch.from_numpy(h0))
+        if c0s is not None:
+            c0s.copy_(torch.from_numpy(c0))
+        rseq, rhT, rcT = oracle.rnn_forward(cfg.cell, W, wl.bias, x[:T], cfg.input, cfg.hidden, h0=h0.astype(np.float64),
+                                            c0=c0.astype(np.float64) if c0s is not None else None)
+        rnn.forward_into(xs[:T], h0s, c0s, hseq[:T], h0s, c0s)
+        torch.cuda.synchronize()
+        assert float(np.max(np.abs(hseq[:T].cpu().numpy() - rseq))) <= TOL
+        assert float(np.max(np.abs(h0s.cpu().numpy() - rhT))) <= TOL
+        if c0s is not None:
+            assert float(np.max(np.abs(c0s.cpu().numpy() - rcT))) <= TOL
 
 
 @pytest.mark.parametrize("cell", [csb_inputs.LSTM, csb_inputs.GRU])
