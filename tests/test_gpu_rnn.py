@@ -217,12 +217,15 @@ def test_rnn_streaming_forward_replays_from_a_captured_graph(cell, L, B):
             assert float(np.max(np.abs(cT.cpu().numpy() - rcT))) <= TOL and torch.equal(cT, eager[2])
 
 
-@pytest.mark.parametrize("cell,L", [(csb_inputs.LSTM, 1), (csb_inputs.GRU, 2), (csb_inputs.LIGRU, 2)])
-def test_rnn_streaming_calls_that_repeat_their_arguments(cell, L):
+@pytest.mark.parametrize("cell,L,record", [(csb_inputs.LSTM, 1, True), (csb_inputs.GRU, 2, True), (csb_inputs.LIGRU, 2, True),
+                                           (csb_inputs.LSTM, 2, False)])
+def test_rnn_streaming_calls_that_repeat_their_arguments(cell, L, record, monkeypatch):
     """A streaming call that repeats its predecessor's arguments records its launches, later ones
     replay them (csb_rnn_forward keeps the graph): six calls on the same buffers with new contents
     each time, a call with other arguments (a shorter sequence) in the middle, a fresh upload of a
     matrix near the end -- every result against the oracle."""
+    if not record:
+        monkeypatch.setenv("CSB_RNN_GRAPH", "0")               # (read when the handle is created: every call enqueues its launches)
     cfg = csb_inputs.RnnConfig("t", cell, L, 20, 72, 16, 3.0, "binomial", 0.3, 1, 8, 140 + L)
     wl = csb_inputs.make_rnn(cfg)
     W = [oracle.csb_decode(oracle.csb_encode(m.A, m.br, m.bc)) for m in wl.W]
