@@ -418,7 +418,14 @@ __global__ __launch_bounds__(kStreamThreads) void spmv_rows_multi_kernel(const R
     rows_body<W, false, VF, FORM>(A, blockIdx.x);
 }
 
-// The step of a recurrent layer whose plan gives its workgroups whole units (blockIdx.y: the layer).
+// The step of one recurrent layer whose plan gives its workgroups whole units (a launch of its own
+// for a single layer: the host then hands over one product's arguments instead of four).
+template <int W, int VF, int FORM>
+__global__ __launch_bounds__(kStreamThreads) void spmv_rows_cell_kernel(const RowsArgs A) {
+    rows_body<W, false, VF, FORM, true>(A, blockIdx.x);
+}
+
+// ... of up to kMaxJobsPerLaunch layers (blockIdx.y: the layer).
 template <int W, int VF, int FORM>
 __global__ __launch_bounds__(kStreamThreads) void spmv_rows_cell_multi_kernel(const RowsJobs J) {
     const RowsArgs &A = J.a[blockIdx.y];
@@ -530,6 +537,10 @@ int spmv_rows_multi(const SpmvPlainCall *calls, int n, void *stream) {
         rounds = std::max(rounds, J.a[i].n_rounds);
     }
     const uint32_t vf = calls[0].mat->plan.stream.val_fmt;
+    if (n == 1) {
+        if (rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_kernel, vf, kRowsOneRound, dim3(wgs), lds, stream, J.a[0]);
+        return CSB_ROWS_LAUNCH(spmv_rows_kernel, vf, kRowsRounds, dim3(wgs), lds, stream, J.a[0]);
+    }
     const dim3 grid(wgs, (unsigned)n);
     if (rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_multi_kernel, vf, kRowsOneRound, grid, lds, stream, J);
     return CSB_ROWS_LAUNCH(spmv_rows_multi_kernel, vf, kRowsRounds, grid, lds, stream, J);
@@ -565,6 +576,10 @@ int spmv_rows_cell_multi(const SpmvCellCall *calls, int n, void *stream) {
         rounds = std::max(rounds, A.n_rounds);
     }
     const uint32_t vf = calls[0].mat->plan.stream.val_fmt;
+    if (n == 1) {
+        if (rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_cell_kernel, vf, kRowsOneRound, dim3(wgs), lds, stream, J.a[0]);
+        return CSB_ROWS_LAUNCH(spmv_rows_cell_kernel, vf, kRowsRounds, dim3(wgs), lds, stream, J.a[0]);
+    }
     const dim3 grid(wgs, (unsigned)n);
     if (rounds == 1u) return CSB_ROWS_LAUNCH(spmv_rows_cell_multi_kernel, vf, kRowsOneRound, grid, lds, stream, J);
     return CSB_ROWS_LAUNCH(spmv_rows_cell_multi_kernel, vf, kRowsRounds, grid, lds, stream, J);
